@@ -1,0 +1,159 @@
+"""ctypes front end of the CPU oracle (oracle/lc_oracle.c).
+
+TEST INFRASTRUCTURE: only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this module.  It never touches the HIP library.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lc_oracle.c")
+_LIB = os.path.join(_HERE, "liblc_oracle.so")
+
+OK, BADARG, NONFINITE, OUT_TOO_SMALL, BAD_BLOB = 0, 1, 2, 3, 4
+
+
+def build(force=False):
+    """Compile the oracle with gcc (strict IEEE: no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-ffp-contract=off", "-fno-fast-math",
+             "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        u64, i64, i32, u32, vp = ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, ctypes.c_void_p
+        L.lco_bucket_stats.restype = i32
+        L.lco_bucket_stats.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.lco_promote.restype = i32
+        L.lco_promote.argtypes = [vp, i32, vp, vp]
+        L.lco_representative.restype = u32
+        L.lco_representative.argtypes = [u32, u32, u32]
+        L.lco_huffman_lengths.restype = None
+        L.lco_huffman_lengths.argtypes = [vp, i32, vp]
+        L.lco_canonical_codes.restype = None
+        L.lco_canonical_codes.argtypes = [vp, i32, vp]
+        L.lco_quantize.restype = i32
+        L.lco_quantize.argtypes = [vp, vp, u64, i32, vp, vp, vp]
+        L.lco_encode_bound.restype = u64
+        L.lco_encode_bound.argtypes = [u64, i32]
+        L.lco_encode.restype = i64
+        L.lco_encode.argtypes = [vp, vp, u64, i32, vp, u64]
+        L.lco_decode.restype = i64
+        L.lco_decode.argtypes = [vp, u64, vp, u64]
+        L.lco_accounting.restype = i32
+        L.lco_accounting.argtypes = [vp, vp]
+        L.lco_size_exponent_only.restype = u64
+        L.lco_size_exponent_only.argtypes = [u64, u32, u32]
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, status):
+        super().__init__("oracle status %d" % status)
+        self.status = status
+
+
+def bucket_stats(w, w_ref):
+    w, w_ref = _f32(w), _f32(w_ref)
+    count = np.zeros(512, np.uint64); mmin = np.zeros(512, np.uint32); mmax = np.zeros(512, np.uint32)
+    st = lib().lco_bucket_stats(_p(w), _p(w_ref), w.size, _p(count), _p(mmin), _p(mmax))
+    return st, count, mmin, mmax
+
+
+def promote(count, nbits):
+    count = np.ascontiguousarray(count, dtype=np.uint64)
+    kept = np.zeros(16, np.uint16); sym = np.zeros(512, np.uint8)
+    K = lib().lco_promote(_p(count), nbits, _p(kept), _p(sym))
+    return K, kept[:K].copy(), sym
+
+
+def representative(bucket, mmin, mmax):
+    return int(lib().lco_representative(int(bucket), int(mmin), int(mmax)))
+
+
+def huffman_lengths(cnt):
+    cnt = np.ascontiguousarray(cnt, dtype=np.uint64)
+    assert cnt.size <= 16
+    out = np.zeros(cnt.size, np.uint8)
+    lib().lco_huffman_lengths(_p(cnt), cnt.size, _p(out))
+    return out
+
+
+def canonical_codes(lens):
+    lens = np.ascontiguousarray(lens, dtype=np.uint8)
+    out = np.zeros(lens.size, np.uint16)
+    lib().lco_canonical_codes(_p(lens), lens.size, _p(out))
+    return out
+
+
+def quantize(w, w_ref, nbits):
+    """Symbols and dequantized deltas in memory order: (sym u8[n], dq f32[n], K, k_E)."""
+    w, w_ref = _f32(w), _f32(w_ref)
+    sym = np.zeros(w.size, np.uint8); dq = np.zeros(w.size, np.float32); info = np.zeros(2, np.uint32)
+    st = lib().lco_quantize(_p(w), _p(w_ref), w.size, nbits, _p(sym), _p(dq), _p(info))
+    if st != OK:
+        raise OracleError(st)
+    return sym, dq, int(info[0]), int(info[1])
+
+
+def encode_bound(n, nbits):
+    return int(lib().lco_encode_bound(n, nbits))
+
+
+def encode(w, w_ref, nbits, cap=None):
+    """Returns the blob as a uint8 array (exact size).  Raises OracleError."""
+    w, w_ref = _f32(w), _f32(w_ref)
+    assert w.size == w_ref.size
+    if cap is None:
+        cap = encode_bound(w.size, min(max(nbits, 1), 4))
+    out = np.zeros(max(cap, 1), np.uint8)
+    r = lib().lco_encode(_p(w), _p(w_ref), w.size, nbits, _p(out), cap)
+    if r < 0:
+        err = OracleError(-r)
+        err.header = out[:512].copy()
+        raise err
+    return out[:r].copy()
+
+
+def decode(blob, w_ref):
+    """Updates w_ref (float32 contiguous numpy array) in place; returns bytes consumed."""
+    assert w_ref.dtype == np.float32 and w_ref.flags.c_contiguous
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    r = lib().lco_decode(_p(blob), blob.size, _p(w_ref), w_ref.size)
+    if r < 0:
+        raise OracleError(-r)
+    return int(r)
+
+
+def accounting(blob):
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    acct = np.zeros(5, np.float64)
+    st = lib().lco_accounting(_p(blob), _p(acct))
+    if st != OK:
+        raise OracleError(st)
+    return dict(bits_E=acct[0], bits_EP=acct[1], bits_EPH=acct[2], entropy=acct[3], mean_len=acct[4])
+
+
+def size_exponent_only(n, k, b=32):
+    return int(lib().lco_size_exponent_only(n, k, b))
