@@ -1,0 +1,170 @@
+/*
+ * lc.h -- C ABI of the MI355X (gfx950) compress / restore path of LC-Checkpoint
+ * (arXiv 2009.13003, "On Efficient Constructions of Checkpoints").
+ *
+ * One checkpoint = one call:
+ *   lc_encode  takes the live fp32 parameters u_t and the last *recovered* state
+ *              u~_{t-1}, forms delta = u_t - u~_{t-1} (Algorithm 1 line 4), buckets
+ *              every delta by (sign, exponent) and keeps the 2^nbits - 1 non-empty
+ *              buckets of largest exponent, each represented by the mean of its
+ *              largest and smallest member, everything else becoming 0 (Section 3.1.1:
+ *              exponent-based quantization and x-bit priority promotion), then
+ *              Huffman-codes the bucket indices (Section 3.1.2; Algorithm 1 lines 5-6)
+ *              into an LCB1 blob in device memory.
+ *   lc_decode  is Algorithm 1 line 7 / the restore of Section 3 (C1): Huffman decode,
+ *              look up the representative, u~_t = u~_{t-1} + delta~_t in place.
+ *
+ * Every step runs in HIP kernels; nothing is computed on the host except argument
+ * checks.  All pointers are DEVICE pointers unless a parameter says "host".
+ * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls are
+ * serialised inside the library (one scratch area per device): they may be issued
+ * from several threads but do not overlap.
+ *
+ * ---------------------------------------------------------------------------
+ * LCB1 blob layout (little-endian).  The paper says only "save to disk"; this
+ * layout is this library's.
+ *
+ *   [0, 512)            header
+ *   [512, A)            u32 chunk_word_off[num_chunks + 1], zero-padded to 16 bytes;
+ *                       A = 512 + roundup16(4 * (num_chunks + 1))
+ *   [A, total_bytes)    chunk records, record c starting at A + 4*chunk_word_off[c];
+ *                       chunk_word_off[num_chunks] = size of the chunk area in words
+ *
+ *   Chunk c covers elements [c*C, min(n, (c+1)*C)), C = W*V*R = 64*4*64 = 16384.
+ *   Lane l (0..63) owns, in this order, the elements c*C + r*256 + 4*l + v
+ *   (r = 0..63, v = 0..3) that are < n.  A lane stream is the concatenation of the
+ *   codes of the lane's elements, each code most significant bit first.
+ *   Chunk record = u16 lane_bits[64] (bit length of each lane stream), then the
+ *   payload: the 64 lane streams concatenated in lane order without gaps, zero
+ *   padded to a whole 32-bit word.  Bit p of a payload is bit (31 - p%32) of
+ *   u32 word p/32.
+ *
+ *   Header:
+ *     0  char[4] "LCB1"        4  u16 version = 1       6  u16 header_bytes = 512
+ *     8  u64 n                16  u32 nbits            20  u32 K (kept buckets; zero symbol = K)
+ *    24  u32 W = 64           28  u32 V = 4            32  u32 R = 64
+ *    36  u32 num_chunks       40  u64 total_bytes      48  u32 status (0, or 2 = non-finite delta)
+ *    52  u32 k_E  non-empty buckets before promotion (the zero class counts once)
+ *    56  u32 max_len  longest code length              60  u32 0
+ *    64  16 symbol slots of 16 bytes: { u16 bucket_id, u8 len, u8 0, u32 rep_bits, u64 count }
+ *        slot j < K: bucket_id = (sign << 8) | biased exponent; rep_bits = the fp32
+ *        representative; slot K: bucket_id 0xFFFF, rep_bits 0 (the merged bucket,
+ *        "stored last", Section 4.4); slots > K are zero.  len = 0 iff count = 0.
+ *   320  192 zero bytes
+ *
+ *   Symbols: j < K is the j-th kept bucket in priority order (larger exponent first,
+ *   + before - at equal exponent).  Biased exponent 0 (zeros, subnormals: Figure 2
+ *   caption) always belongs to the merged bucket.  Code lengths are Huffman lengths
+ *   of the counts, built by repeatedly joining the two smallest nodes under the order
+ *   (weight, leaf before joined node, symbol index / creation order); one active
+ *   symbol gets length 1.  Codes are canonical: symbols sorted by (len, index), first
+ *   code 0, each next = (previous + 1) << (growth in length).
+ *   On a non-finite delta the blob is a header only (status 2, total_bytes 512).
+ * ---------------------------------------------------------------------------
+ */
+#ifndef LC_H
+#define LC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int64_t lc_ssize;        /* >= 0: byte count;  < 0: -(enum lc_status) */
+
+enum lc_status {
+    LC_OK = 0,
+    LC_ERR_BADARG = 1,           /* null/misaligned pointer, nbits outside [1,4], n too large, n mismatch */
+    LC_ERR_NONFINITE = 2,        /* some delta is Inf or NaN */
+    LC_ERR_OUT_TOO_SMALL = 3,    /* reserved (the encoder cannot exceed lc_encode_bound) */
+    LC_ERR_BAD_BLOB = 4,         /* blob fails validation */
+    LC_ERR_HIP = 5,              /* a HIP runtime call failed */
+    LC_ERR_WORKSPACE = 6         /* caller-supplied workspace too small or misaligned */
+};
+
+#define LC_MAX_N (1ull << 32)    /* largest n per call; larger vectors are sliced by the caller */
+#define LC_CHUNK 16384u
+
+/*
+ * Worst-case blob size in bytes for (n, nbits); host only, no GPU needed.  An optimal
+ * prefix code over at most 2^nbits symbols (Section 3.1.2) never averages more than
+ * nbits bits per symbol, so the bound is header + offsets + 132 bytes per chunk +
+ * ceil(n*nbits/8).  Returns 0 for invalid arguments.
+ */
+size_t lc_encode_bound(uint64_t n, int nbits);
+
+/*
+ * Device scratch the library needs for a call with (n, nbits): bucket histogram,
+ * code tables, decode look-up table, one 8-byte scan state per chunk.  Host only.
+ */
+size_t lc_workspace_bytes(uint64_t n, int nbits);
+
+/*
+ * Optional: hand the library a device scratch area for the current device instead of
+ * letting it allocate (lazily, once, grown on demand, freed by lc_shutdown).
+ * dev_ws must be 256-byte aligned and stay valid until replaced or lc_shutdown; the
+ * library never frees it.  dev_ws = NULL returns to library-owned scratch.  Calls
+ * whose lc_workspace_bytes exceeds `bytes` fail with LC_ERR_WORKSPACE.
+ * Returns an lc_status.
+ */
+int lc_set_workspace(void* dev_ws, size_t bytes);
+
+/*
+ * Algorithm 1 lines 4-6 for one checkpoint (Sections 3, 3.1.1, 3.1.2).
+ *   w      [n] fp32, device, read only: the live parameters u_t
+ *   w_ref  [n] fp32, device, read only: the last recovered state u~_{t-1}
+ *   n      0 <= n <= LC_MAX_N
+ *   nbits  promotion bits x in [1, 4]: 2^x - 1 buckets are kept
+ *   out    device, 16-byte aligned, at least lc_encode_bound(n, nbits) bytes, must not
+ *          overlap w / w_ref; receives the LCB1 blob
+ * w and w_ref need 4-byte alignment; 16-byte alignment of both takes the fast loads.
+ * Enqueues on `stream`, then waits for that stream and returns the blob size in
+ * bytes, or -(lc_status).  On LC_ERR_NONFINITE `out` holds a 512-byte header whose
+ * status field says so.  Caller owns all buffers; nothing is retained.
+ */
+lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
+                   void* out, void* stream);
+
+/*
+ * Algorithm 1 line 7 / Section 3 (C1): w_ref[i] += representative(symbol_i) in one
+ * fp32 add; elements whose symbol is the merged (zero) bucket keep their exact bit
+ * pattern.  `blob` is a device pointer to an LCB1 blob (16-byte aligned) whose header
+ * n must equal `n`.  The header, the offset table and all lane lengths are validated
+ * on the device before w_ref is touched (LC_ERR_BAD_BLOB leaves w_ref unchanged); a
+ * lane stream that does not decode to exactly its stated length is only found
+ * during the sweep and then also returns LC_ERR_BAD_BLOB, with w_ref partly updated.
+ * Reads never leave [blob, blob + header.total_bytes).  Waits for `stream`; returns
+ * the bytes consumed or -(lc_status).
+ */
+lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
+
+/*
+ * Parse a header that the caller copied to HOST memory (at least 64 bytes).  Any
+ * output pointer may be NULL.  Returns LC_OK, or LC_ERR_BAD_BLOB if magic/version
+ * are wrong; `status` receives the header's status field.
+ */
+int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status);
+
+/* Frees library-owned scratch on every device and the pinned result buffer. */
+void lc_shutdown(void);
+
+/* Static string for an lc_status (positive or negated). */
+const char* lc_strerror(int status);
+
+/*
+ * Per-kernel timing with HIP events on the caller's stream (for benchmarks).
+ * lc_profile(1) switches it on and clears the totals, lc_profile(0) switches it off.
+ * lc_profile_read copies up to `cap` accumulated kernel times (milliseconds) and
+ * launch counts; returns the number of kernel slots.  lc_profile_name(i) names slot i
+ * (NULL past the end).
+ */
+int lc_profile(int enable);
+int lc_profile_read(double* ms_total, uint64_t* launches, int cap);
+const char* lc_profile_name(int slot);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LC_H */

@@ -1,0 +1,237 @@
+// Host side of the C ABI declared in include/lc.h: argument checks, per-device scratch,
+// launch order, the small size/status read-back, optional per-kernel event timing.
+// No step of the method runs here.
+#include "../../include/lc.h"
+#include "lc_internal.h"
+
+#include <mutex>
+#include <string.h>
+
+namespace {
+
+using namespace lc;
+
+constexpr int kMaxDevices = 16;
+
+struct DeviceState {
+    void* owned = nullptr;       // library-owned scratch
+    size_t owned_bytes = 0;
+    void* user = nullptr;        // caller-supplied scratch (lc_set_workspace)
+    size_t user_bytes = 0;
+    int num_cu = 0;
+};
+
+std::mutex g_mu;
+DeviceState g_dev[kMaxDevices];
+Result* g_pinned = nullptr;      // pinned host landing area for the result read-back
+
+bool g_prof = false;
+double g_prof_ms[kNumSlots];
+uint64_t g_prof_n[kNumSlots];
+hipEvent_t g_ev[kNumSlots][2];
+bool g_ev_made = false;
+const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_finalize",
+                                           "k_dec_prepare", "k_dec_validate", "k_decode"};
+
+#define LC_HIP(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return -(lc_ssize)LC_ERR_HIP; } } while (0)
+
+struct Timed {                   // records a pair of events around a launch when profiling is on
+    int slot; hipStream_t s; bool on;
+    Timed(int slot_, hipStream_t s_) : slot(slot_), s(s_), on(g_prof) { if (on) (void)hipEventRecord(g_ev[slot][0], s); }
+    ~Timed() { if (on) (void)hipEventRecord(g_ev[slot][1], s); }
+};
+
+void collect(const int* slots, int count) {   // after the stream has been waited for
+    if (!g_prof) return;
+    for (int i = 0; i < count; ++i) {
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, g_ev[slots[i]][0], g_ev[slots[i]][1]) == hipSuccess) {
+            g_prof_ms[slots[i]] += ms; g_prof_n[slots[i]] += 1;
+        } else (void)hipGetLastError();
+    }
+}
+
+// Scratch for the current device, at least `need` bytes.  Returns nullptr with *err set.
+Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); *err = LC_ERR_HIP; return nullptr; }
+    DeviceState& ds = g_dev[dev];
+    if (ds.num_cu == 0) {
+        int cu = 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) { (void)hipGetLastError(); cu = 256; }
+        ds.num_cu = cu;
+    }
+    if (!g_pinned) {
+        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(Result) * 2, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError(); g_pinned = nullptr; *err = LC_ERR_HIP; return nullptr;
+        }
+    }
+    *ds_out = &ds;
+    if (ds.user) {
+        if (ds.user_bytes < need) { *err = LC_ERR_WORKSPACE; return nullptr; }
+        return static_cast<Workspace*>(ds.user);
+    }
+    if (ds.owned_bytes < need) {
+        if (ds.owned) { (void)hipDeviceSynchronize(); (void)hipFree(ds.owned); ds.owned = nullptr; ds.owned_bytes = 0; }
+        size_t want = need < (1u << 20) ? (1u << 20) : need;
+        if (hipMalloc(&ds.owned, want) != hipSuccess) { (void)hipGetLastError(); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        ds.owned_bytes = want;
+    }
+    return static_cast<Workspace*>(ds.owned);
+}
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+size_t lc_encode_bound(uint64_t n, int nbits) {
+    if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
+    const uint64_t nc = num_chunks_of(n);
+    return (size_t)(chunk_area_of(nc) + nc * (2 * kW + 4) + (n * (uint64_t)nbits + 7) / 8);
+}
+
+size_t lc_workspace_bytes(uint64_t n, int nbits) {
+    if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
+    return kWorkspaceFixed + (size_t)(8 * num_chunks_of(n) + 255) / 256 * 256;
+}
+
+int lc_set_workspace(void* dev_ws, size_t bytes) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceFixed)) return LC_ERR_WORKSPACE;
+    g_dev[dev].user = dev_ws;
+    g_dev[dev].user_bytes = dev_ws ? bytes : 0;
+    return LC_OK;
+}
+
+lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
+    if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
+    if (n && (!w || !w_ref || misaligned(w, 4) || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int err = 0; DeviceState* ds = nullptr;
+    Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
+    if (!ws) return -(lc_ssize)err;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned long long* state = reinterpret_cast<unsigned long long*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
+    uint8_t* o = static_cast<uint8_t*>(out);
+    { Timed t(kSlotReset, s);    launch_reset(ws, state, num_chunks_of(n), s); }
+    { Timed t(kSlotHist, s);     launch_hist(w, w_ref, n, ws, ds->num_cu, s); }
+    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, s); }
+    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, o, ws, state, ds->num_cu, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, n, nbits, s); }
+    LC_HIP(hipGetLastError());
+    LC_HIP(hipMemcpyAsync(g_pinned, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipStreamSynchronize(s));
+    const int slots[] = {kSlotReset, kSlotHist, kSlotTable, kSlotPack, kSlotFinalize};
+    collect(slots, 5);
+    if (g_pinned->status != LC_OK) return -(lc_ssize)g_pinned->status;
+    return (lc_ssize)g_pinned->bytes;
+}
+
+lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
+    if (!blob || misaligned(blob, 16) || n > LC_MAX_N) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int err = 0; DeviceState* ds = nullptr;
+    Workspace* ws = get_workspace(lc_workspace_bytes(n, 4), &err, &ds);
+    if (!ws) return -(lc_ssize)err;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint8_t* b = static_cast<const uint8_t*>(blob);
+    { Timed t(kSlotDecPrep, s);     launch_dec_prepare(b, n, lc_encode_bound(n, 4), ws, s); }
+    { Timed t(kSlotDecValidate, s); launch_dec_validate(b, n, ws, s); }
+    LC_HIP(hipGetLastError());
+    LC_HIP(hipMemcpyAsync(&g_pinned[0], &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipMemcpyAsync(&g_pinned[1].status, &ws->dec_status, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipStreamSynchronize(s));
+    const int slots0[] = {kSlotDecPrep, kSlotDecValidate};
+    collect(slots0, 2);
+    if (g_pinned[0].status != LC_OK) return -(lc_ssize)g_pinned[0].status;
+    if (g_pinned[1].status != LC_OK) return -(lc_ssize)g_pinned[1].status;
+    const uint64_t total = g_pinned[0].bytes;
+    const uint32_t max_len = g_pinned[0].pad;
+    if (n == 0) return (lc_ssize)total;
+    if (max_len < 1 || max_len > kMaxLutBits) return -LC_ERR_BAD_BLOB;
+    { Timed t(kSlotDecode, s); launch_decode(b, w_ref, n, ws, max_len, ds->num_cu, s); }
+    LC_HIP(hipGetLastError());
+    LC_HIP(hipMemcpyAsync(&g_pinned[1].status, &ws->dec_status, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipStreamSynchronize(s));
+    const int slots1[] = {kSlotDecode};
+    collect(slots1, 1);
+    if (g_pinned[1].status != LC_OK) return -(lc_ssize)g_pinned[1].status;
+    return (lc_ssize)total;
+}
+
+int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status) {
+    if (!host_header) return LC_ERR_BADARG;
+    const uint8_t* h = static_cast<const uint8_t*>(host_header);
+    uint16_t version; uint64_t hn, total; uint32_t hb, st;
+    memcpy(&version, h + 4, 2); memcpy(&hn, h + 8, 8); memcpy(&hb, h + 16, 4); memcpy(&total, h + 40, 8); memcpy(&st, h + 48, 4);
+    if (memcmp(h, "LCB1", 4) != 0 || version != 1) return LC_ERR_BAD_BLOB;
+    if (n) *n = hn;
+    if (nbits) *nbits = (int)hb;
+    if (total_bytes) *total_bytes = total;
+    if (status) *status = (int)st;
+    return LC_OK;
+}
+
+void lc_shutdown(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (g_dev[d].owned) {
+            if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_dev[d].owned); }
+            g_dev[d].owned = nullptr; g_dev[d].owned_bytes = 0;
+        }
+        g_dev[d].user = nullptr; g_dev[d].user_bytes = 0;
+    }
+    if (have_cur) (void)hipSetDevice(cur);
+    if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; }
+    if (g_ev_made) {
+        for (int i = 0; i < kNumSlots; ++i) { (void)hipEventDestroy(g_ev[i][0]); (void)hipEventDestroy(g_ev[i][1]); }
+        g_ev_made = false; g_prof = false;
+    }
+    (void)hipGetLastError();
+}
+
+const char* lc_strerror(int status) {
+    switch (status < 0 ? -status : status) {
+        case LC_OK: return "ok";
+        case LC_ERR_BADARG: return "bad argument";
+        case LC_ERR_NONFINITE: return "non-finite delta (Inf or NaN)";
+        case LC_ERR_OUT_TOO_SMALL: return "output buffer too small";
+        case LC_ERR_BAD_BLOB: return "blob failed validation";
+        case LC_ERR_HIP: return "HIP runtime error";
+        case LC_ERR_WORKSPACE: return "workspace too small or misaligned";
+        default: return "unknown status";
+    }
+}
+
+int lc_profile(int enable) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (enable && !g_ev_made) {
+        for (int i = 0; i < kNumSlots; ++i)
+            for (int k = 0; k < 2; ++k)
+                if (hipEventCreate(&g_ev[i][k]) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
+        g_ev_made = true;
+    }
+    g_prof = enable != 0;
+    for (int i = 0; i < kNumSlots; ++i) { g_prof_ms[i] = 0; g_prof_n[i] = 0; }
+    return LC_OK;
+}
+
+int lc_profile_read(double* ms_total, uint64_t* launches, int cap) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (int i = 0; i < kNumSlots && i < cap; ++i) {
+        if (ms_total) ms_total[i] = g_prof_ms[i];
+        if (launches) launches[i] = g_prof_n[i];
+    }
+    return kNumSlots;
+}
+
+const char* lc_profile_name(int slot) { return slot >= 0 && slot < kNumSlots ? kSlotNames[slot] : nullptr; }
+
+}  // extern "C"

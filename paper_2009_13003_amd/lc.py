@@ -1,0 +1,136 @@
+"""Thin ctypes binding of liblc.so: argument marshalling only, same names as include/lc.h.
+
+Device buffers are torch CUDA tensors (torch is used for device memory and streams,
+nothing else).  There is no CPU fallback: if the library is missing, importing fails.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_PATH = os.path.join(_HERE, "liblc.so")
+if not os.path.exists(_PATH):
+    raise ImportError("liblc.so is not built: run `python -m paper_2009_13003_amd.build` "
+                      "(or __graft_entry__.build()) first")
+_lib = ctypes.CDLL(_PATH)
+
+OK, ERR_BADARG, ERR_NONFINITE, ERR_OUT_TOO_SMALL, ERR_BAD_BLOB, ERR_HIP, ERR_WORKSPACE = range(7)
+MAX_N = 1 << 32
+CHUNK = 16384
+
+_u64, _i64, _int, _vp, _sz = ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+_lib.lc_encode_bound.restype = _sz
+_lib.lc_encode_bound.argtypes = [_u64, _int]
+_lib.lc_workspace_bytes.restype = _sz
+_lib.lc_workspace_bytes.argtypes = [_u64, _int]
+_lib.lc_set_workspace.restype = _int
+_lib.lc_set_workspace.argtypes = [_vp, _sz]
+_lib.lc_encode.restype = _i64
+_lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
+_lib.lc_decode.restype = _i64
+_lib.lc_decode.argtypes = [_vp, _vp, _u64, _vp]
+_lib.lc_blob_info.restype = _int
+_lib.lc_blob_info.argtypes = [_vp, ctypes.POINTER(_u64), ctypes.POINTER(_int), ctypes.POINTER(_u64), ctypes.POINTER(_int)]
+_lib.lc_shutdown.restype = None
+_lib.lc_shutdown.argtypes = []
+_lib.lc_strerror.restype = ctypes.c_char_p
+_lib.lc_strerror.argtypes = [_int]
+_lib.lc_profile.restype = _int
+_lib.lc_profile.argtypes = [_int]
+_lib.lc_profile_read.restype = _int
+_lib.lc_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64), _int]
+_lib.lc_profile_name.restype = ctypes.c_char_p
+_lib.lc_profile_name.argtypes = [_int]
+
+
+class LcError(RuntimeError):
+    def __init__(self, status):
+        super().__init__("lc status %d: %s" % (status, lc_strerror(status)))
+        self.status = status
+
+
+def lc_strerror(status):
+    return _lib.lc_strerror(int(status)).decode()
+
+
+def lc_encode_bound(n, nbits):
+    return int(_lib.lc_encode_bound(n, nbits))
+
+
+def lc_workspace_bytes(n, nbits):
+    return int(_lib.lc_workspace_bytes(n, nbits))
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dev_f32(t):
+    assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous(), "need a contiguous CUDA float32 tensor"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def lc_set_workspace(ws):
+    """ws: a CUDA uint8 tensor (kept alive by the caller) or None."""
+    if ws is None:
+        return int(_lib.lc_set_workspace(None, 0))
+    assert ws.is_cuda and ws.dtype == torch.uint8 and ws.is_contiguous()
+    return int(_lib.lc_set_workspace(ctypes.c_void_p(ws.data_ptr()), ws.numel()))
+
+
+def lc_encode(w, w_ref, nbits, out, stream=None, n=None):
+    """Returns the blob size in bytes (blob is out[:size]); raises LcError on a negative status."""
+    n = w.numel() if n is None else n
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    r = int(_lib.lc_encode(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_decode(blob, w_ref, stream=None, n=None):
+    """Updates w_ref in place; returns the bytes consumed; raises LcError on a negative status."""
+    n = w_ref.numel() if n is None else n
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    r = int(_lib.lc_decode(ctypes.c_void_p(blob.data_ptr()), _dev_f32(w_ref), n, _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_blob_info(host_header):
+    """host_header: bytes-like, at least 64 bytes, in host memory."""
+    buf = (ctypes.c_uint8 * 64).from_buffer_copy(bytes(host_header[:64]))
+    n, nbits, total, status = _u64(), _int(), _u64(), _int()
+    st = int(_lib.lc_blob_info(buf, ctypes.byref(n), ctypes.byref(nbits), ctypes.byref(total), ctypes.byref(status)))
+    if st != OK:
+        raise LcError(st)
+    return dict(n=n.value, nbits=nbits.value, total_bytes=total.value, status=status.value)
+
+
+def lc_shutdown():
+    _lib.lc_shutdown()
+
+
+def lc_profile(enable):
+    st = int(_lib.lc_profile(1 if enable else 0))
+    if st != OK:
+        raise LcError(st)
+
+
+def lc_profile_read():
+    """{kernel name: (total ms, launches)} since lc_profile(True)."""
+    k = int(_lib.lc_profile_read(None, None, 0))
+    ms = (ctypes.c_double * k)()
+    cnt = (_u64 * k)()
+    _lib.lc_profile_read(ms, cnt, k)
+    return {_lib.lc_profile_name(i).decode(): (ms[i], int(cnt[i])) for i in range(k)}
+
+
+def alloc_out(n, nbits, device="cuda"):
+    """A device buffer large enough for any blob of (n, nbits)."""
+    return torch.empty(lc_encode_bound(n, nbits), dtype=torch.uint8, device=device)

@@ -1,0 +1,73 @@
+"""The C-ABI library loads without a GPU and exports every function include/lc.h declares;
+the host-only entry points behave as documented.  No compute calls here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "lc.h")
+LIB = os.path.join(ROOT, "paper_2009_13003_amd", "liblc.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2009_13003_amd import build
+        build.build_library()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(lc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"lc_encode", "lc_decode", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
+            "lc_blob_info", "lc_shutdown", "lc_strerror", "lc_profile", "lc_profile_read",
+            "lc_profile_name"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_host_only_entry_points(lib):
+    lib.lc_encode_bound.restype = ctypes.c_size_t
+    lib.lc_encode_bound.argtypes = [ctypes.c_uint64, ctypes.c_int]
+    lib.lc_workspace_bytes.restype = ctypes.c_size_t
+    lib.lc_workspace_bytes.argtypes = [ctypes.c_uint64, ctypes.c_int]
+    lib.lc_strerror.restype = ctypes.c_char_p
+    # header + one offset entry padded to 16 bytes
+    assert lib.lc_encode_bound(0, 3) == 512 + 16
+    # one chunk: header, 2 offsets (16 bytes), 128 bytes of lane lengths + 4 bytes of padding, n*nbits/8
+    assert lib.lc_encode_bound(16384, 4) == 512 + 16 + 132 + 8192
+    assert lib.lc_encode_bound(16385, 1) == 512 + 16 + 2 * 132 + 2049
+    for bad in ((10, 0), (10, 5), ((1 << 32) + 1, 3)):
+        assert lib.lc_encode_bound(*bad) == 0 and lib.lc_workspace_bytes(*bad) == 0
+    assert lib.lc_workspace_bytes(1 << 28, 4) >= 8 * (1 << 14)
+    assert lib.lc_strerror(0) == b"ok" and lib.lc_strerror(-2) == lib.lc_strerror(2) != b"ok"
+    # blob info on a host header
+    import struct
+    hdr = bytearray(64)
+    hdr[0:4] = b"LCB1"
+    struct.pack_into("<HHQI", hdr, 4, 1, 512, 12345, 3)
+    struct.pack_into("<QI", hdr, 40, 999, 0)
+    n, nbits, total, status = ctypes.c_uint64(), ctypes.c_int(), ctypes.c_uint64(), ctypes.c_int()
+    buf = (ctypes.c_uint8 * 64).from_buffer(hdr)
+    assert lib.lc_blob_info(buf, ctypes.byref(n), ctypes.byref(nbits), ctypes.byref(total), ctypes.byref(status)) == 0
+    assert (n.value, nbits.value, total.value, status.value) == (12345, 3, 999, 0)
+    hdr[0] = ord("X")
+    assert lib.lc_blob_info(buf, None, None, None, None) == 4
+
+
+def test_workloads_have_the_stated_parameter_counts():
+    from paper_2009_13003_amd import workloads as W
+    for name, fn in W.SHAPES.items():
+        assert W.numel(fn()) == W.EXPECTED_NUMEL[name]
+    assert len(W.resnet50_shapes()) == 161 and len(W.vgg16_shapes()) == 32
+    assert len(W.gpt2_medium_shapes()) == 292 and len(W.llama7b_shapes()) == 291
+    w, w_ref, nbits = W.single_tensor(n=1000, seed=0, device="cpu")
+    w2, _, _ = W.single_tensor(n=1000, seed=0, device="cpu")
+    assert nbits == 3 and w.dtype == w_ref.dtype and (w == w2).all() and abs(float((w - w_ref).abs().mean()) - 1e-3) < 3e-4
