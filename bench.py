@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the compress / restore hot path on one MI355X.
+
+A step = one pass of the whole path over the workload: lc_encode(w, w_ref) followed by
+lc_decode(blob) accumulating into a recovered-state buffer.  Inputs are synthetic, seeded
+and resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vgg16|resnet50|single|gpt2_medium|llama7b]
+                  [--no-also] [--no-cpu]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+
+
+def make_workload(name, device):
+    from paper_2009_13003_amd import workloads as W
+    if name == "single":
+        w, r, nbits = W.single_tensor(device=device)
+    elif name == "resnet50":
+        w, r, nbits = W.resnet50(device=device)
+    elif name == "vgg16":
+        w, r, nbits = W.vgg16(device=device)
+    elif name == "llama7b":
+        w, r, nbits = W.llama7b(device=device)
+    elif name == "gpt2_medium":
+        chain = W.Gpt2Chain(device=device)
+        r = chain.w0
+        w = chain.step().clone()
+        nbits = chain.nbits
+    else:
+        raise SystemExit("unknown workload " + name)
+    return w, r, nbits
+
+
+def slices_of(n):
+    from paper_2009_13003_amd.workloads import SLICE
+    return [(lo, min(n, lo + SLICE)) for lo in range(0, n, SLICE)]
+
+
+class Job:
+    """Device buffers for one workload; every slice of 2^28 elements is an independent call."""
+
+    def __init__(self, name, device):
+        import torch
+        from paper_2009_13003_amd import lc
+        self.lc, self.torch, self.name = lc, torch, name
+        self.w, self.w_ref, self.nbits = make_workload(name, device)
+        self.n = self.w.numel()
+        self.rec = self.w_ref.clone()
+        self.sl = slices_of(self.n)
+        self.outs = [lc.alloc_out(hi - lo, self.nbits, device) for lo, hi in self.sl]
+        self.sizes = [0] * len(self.sl)
+        torch.cuda.synchronize()
+
+    def encode(self):
+        for k, (lo, hi) in enumerate(self.sl):
+            self.sizes[k] = self.lc.lc_encode(self.w[lo:hi], self.w_ref[lo:hi], self.nbits, self.outs[k])
+
+    def decode(self):
+        for k, (lo, hi) in enumerate(self.sl):
+            self.lc.lc_decode(self.outs[k], self.rec[lo:hi])
+
+    def step(self):
+        t0 = time.perf_counter(); self.encode()
+        t1 = time.perf_counter(); self.decode()
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1
+
+    def blob_bytes(self):
+        return sum(self.sizes)
+
+    def mean_code_bits(self):
+        """Payload + index bits per element as stored (everything after the headers)."""
+        return 8.0 * (self.blob_bytes() - 512 * len(self.sl)) / self.n
+
+
+def run(job, steps, warmup):
+    torch, lc = job.torch, job.lc
+    for _ in range(warmup):
+        job.step()
+    torch.cuda.synchronize()
+    lc.lc_profile(True)
+    enc = dec = 0.0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        e, d = job.step()
+        enc += e; dec += d
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t0
+    prof = lc.lc_profile_read()
+    lc.lc_profile(False)
+    gb = 4.0 * job.n / 1e9
+    bits = job.mean_code_bits()
+    alg = {"k_hist": 8.0, "k_pack": 8.0 + bits / 8.0, "k_decode": 8.0 + bits / 8.0}   # bytes per element
+    kernels = {}
+    for name, (ms, launches) in prof.items():
+        if launches == 0:
+            continue
+        per_step_ms = ms / steps
+        ent = {"ms_per_step": round(per_step_ms, 4), "launches_per_step": launches // steps}
+        if name in alg:
+            ach = alg[name] * job.n / 1e9 / (per_step_ms / 1e3)
+            ent.update(alg_bytes_per_elem=round(alg[name], 4), achieved_GBps=round(ach, 1), frac=round(ach / HBM_PEAK_GBPS, 4))
+        kernels[name] = ent
+    return dict(ms_per_step=1e3 * total / steps, value=gb / (total / steps),
+                encode_GBps=gb / (enc / steps), decode_GBps=gb / (dec / steps),
+                encode_ms=1e3 * enc / steps, decode_ms=1e3 * dec / steps,
+                encode_hbm_frac=(16.0 + bits / 8.0) * job.n / 1e9 / (enc / steps) / HBM_PEAK_GBPS,
+                decode_hbm_frac=(8.0 + bits / 8.0) * job.n / 1e9 / (dec / steps) / HBM_PEAK_GBPS,
+                ratio=4.0 * job.n / job.blob_bytes(), bits_per_elem=bits, blob_bytes=job.blob_bytes(), kernels=kernels)
+
+
+def traffic_from_profiles(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for this kernel/workload is committed."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(job):
+    """The oracle as it stands, single thread, on the first slice of the workload (<= 2^28 elements)."""
+    import numpy as np
+    from oracle import lc_oracle
+    lo, hi = job.sl[0]
+    w_h, r_h = job.w[lo:hi].cpu().numpy(), job.w_ref[lo:hi].cpu().numpy()
+    t0 = time.perf_counter()
+    blob = lc_oracle.encode(w_h, r_h, job.nbits)
+    t1 = time.perf_counter()
+    rec = r_h.copy()
+    t2 = time.perf_counter()
+    lc_oracle.decode(blob, rec)
+    t3 = time.perf_counter()
+    gpu_blob = job.outs[0][:job.sizes[0]].cpu().numpy()
+    same = bool(gpu_blob.size == blob.size and np.array_equal(gpu_blob, blob))
+    gb = 4.0 * (hi - lo) / 1e9
+    return dict(value=round(gb / ((t1 - t0) + (t3 - t2)), 4), unit="GB/s", cores=1, kind="oracle",
+                sample="%s elements [%d, %d): 1 encode + 1 decode, single thread" % (job.name, lo, hi),
+                encode_GBps=round(gb / (t1 - t0), 4), decode_GBps=round(gb / (t3 - t2), 4),
+                gpu_blob_identical=same)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by "
+                         "independent slices, see DESIGN.md")
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+
+    job = Job(args.workload, dev)
+    res = run(job, args.steps, args.warmup)
+    dom = max((k for k in res["kernels"] if "achieved_GBps" in res["kernels"][k]),
+              key=lambda k: res["kernels"][k]["ms_per_step"])
+    kd = res["kernels"][dom]
+    launches = kd["launches_per_step"]
+    roofline = {"bound": "hbm", "kernel": dom,
+                "achieved": kd["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kd["frac"],
+                "traffic": traffic_from_profiles(dom, args.workload),
+                "alg_bytes_per_launch": kd["alg_bytes_per_elem"] * job.n / launches,
+                "avg_launch_ms": round(kd["ms_per_step"] / launches, 4)}
+    cpu = None if args.no_cpu else cpu_baseline(job)
+    config = {"workload": args.workload, "n": job.n, "nbits": job.nbits, "calls_per_step": 2 * len(job.sl),
+              "slice_elems": min(job.n, 1 << 28)}
+
+    also = {}
+    if not args.no_also:
+        del job
+        torch.cuda.empty_cache()
+        for name in ("llama7b", "single"):
+            if name == args.workload:
+                continue
+            j = Job(name, dev)
+            r = run(j, max(2, args.steps // 4) if name == "llama7b" else args.steps, 1)
+            also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
+            also[name]["n"] = j.n
+            also[name]["nbits"] = j.nbits
+            del j
+            torch.cuda.empty_cache()
+
+    line = {
+        "metric": "encode+decode GB/s of fp32 params (one compress + one restore per step)",
+        "value": round(res["value"], 3), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": config,
+        "encode_GBps": round(res["encode_GBps"], 2), "decode_GBps": round(res["decode_GBps"], 2),
+        "encode_ms": round(res["encode_ms"], 4), "decode_ms": round(res["decode_ms"], 4),
+        "encode_hbm_frac": round(res["encode_hbm_frac"], 4), "decode_hbm_frac": round(res["decode_hbm_frac"], 4),
+        "compression_ratio": round(res["ratio"], 3), "bits_per_elem": round(res["bits_per_elem"], 4),
+        "roofline": roofline, "kernels": res["kernels"], "cpu_baseline": cpu, "also": also,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
