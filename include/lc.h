@@ -96,8 +96,10 @@ enum lc_status {
 size_t lc_encode_bound(uint64_t n, int nbits);
 
 /*
- * Device scratch the library needs for a call with (n, nbits): bucket histogram,
- * code tables, decode look-up table, one 8-byte scan state per chunk.  Host only.
+ * Device scratch lc_encode needs for (n, nbits): a few KB of tables plus, per chunk of
+ * 16384 elements, one slot that can hold the chunk's code bits at their longest
+ * (2^nbits - 1 bits per element): about 0.06 / 0.19 / 0.44 / 0.94 bytes per element for
+ * nbits = 1..4.  lc_decode needs only the fixed part (lc_workspace_bytes(0, 1)).  Host only.
  */
 size_t lc_workspace_bytes(uint64_t n, int nbits);
 

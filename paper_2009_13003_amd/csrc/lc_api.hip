@@ -5,6 +5,7 @@
 #include "lc_internal.h"
 
 #include <mutex>
+#include <stdlib.h>
 #include <string.h>
 
 namespace {
@@ -18,20 +19,30 @@ struct DeviceState {
     size_t owned_bytes = 0;
     void* user = nullptr;        // caller-supplied scratch (lc_set_workspace)
     size_t user_bytes = 0;
-    int num_cu = 0;
+    Tuning tune;
+    bool tuned = false;
 };
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
-Result* g_pinned = nullptr;      // pinned host landing area for the result read-back
+struct Landing { Result result; unsigned long long dec_status; unsigned long long pad; };
+Landing* g_pinned = nullptr;     // pinned host landing area for the result read-back
+uint64_t g_epoch = 0;            // tags the decode status word of each call
 
 bool g_prof = false;
 double g_prof_ms[kNumSlots];
 uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
-const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_finalize",
-                                           "k_dec_prepare", "k_dec_validate", "k_decode"};
+const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize",
+                                           "k_dec_check", "k_decode"};
+
+int env_int(const char* name, int dflt, int lo, int hi) {
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    const long x = strtol(v, nullptr, 10);
+    return x < lo ? lo : (x > hi ? hi : (int)x);
+}
 
 #define LC_HIP(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return -(lc_ssize)LC_ERR_HIP; } } while (0)
 
@@ -56,13 +67,18 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); *err = LC_ERR_HIP; return nullptr; }
     DeviceState& ds = g_dev[dev];
-    if (ds.num_cu == 0) {
+    if (!ds.tuned) {
         int cu = 0;
         if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) { (void)hipGetLastError(); cu = 256; }
-        ds.num_cu = cu;
+        ds.tune.num_cu = cu;
+        ds.tune.hist_blocks_per_cu = env_int("LC_TUNE_HIST_BLOCKS_PER_CU", ds.tune.hist_blocks_per_cu, 1, 64);
+        ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
+        ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
+        ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
+        ds.tuned = true;
     }
     if (!g_pinned) {
-        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(Result) * 2, hipHostMallocDefault) != hipSuccess) {
+        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(Landing), hipHostMallocDefault) != hipSuccess) {
             (void)hipGetLastError(); g_pinned = nullptr; *err = LC_ERR_HIP; return nullptr;
         }
     }
@@ -75,6 +91,7 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         if (ds.owned) { (void)hipDeviceSynchronize(); (void)hipFree(ds.owned); ds.owned = nullptr; ds.owned_bytes = 0; }
         size_t want = need < (1u << 20) ? (1u << 20) : need;
         if (hipMalloc(&ds.owned, want) != hipSuccess) { (void)hipGetLastError(); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        if (hipMemset(ds.owned, 0, kWorkspaceFixed) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(ds.owned); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
         ds.owned_bytes = want;
     }
     return static_cast<Workspace*>(ds.owned);
@@ -94,7 +111,9 @@ size_t lc_encode_bound(uint64_t n, int nbits) {
 
 size_t lc_workspace_bytes(uint64_t n, int nbits) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
-    return kWorkspaceFixed + (size_t)(8 * num_chunks_of(n) + 255) / 256 * 256;
+    const uint64_t nc = num_chunks_of(n);
+    return kWorkspaceFixed + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)((4 * ((nc + 63) / 64) + 255) / 256 * 256) +
+           (size_t)(nc * slot_words_of(nbits) * 4);
 }
 
 int lc_set_workspace(void* dev_ws, size_t bytes) {
@@ -102,6 +121,7 @@ int lc_set_workspace(void* dev_ws, size_t bytes) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
     if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceFixed)) return LC_ERR_WORKSPACE;
+    if (dev_ws && hipMemset(dev_ws, 0, kWorkspaceFixed) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
     g_dev[dev].user = dev_ws;
     g_dev[dev].user_bytes = dev_ws ? bytes : 0;
     return LC_OK;
@@ -115,20 +135,25 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, vo
     Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    unsigned long long* state = reinterpret_cast<unsigned long long*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
+    uint32_t* chunk_bits = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
+    const uint64_t nc = num_chunks_of(n);
+    uint32_t* group_words = chunk_bits + (nc + 63) / 64 * 64;
+    uint32_t* prov = group_words + ((nc + 63) / 64 + 63) / 64 * 64;
+    const uint32_t slot_words = slot_words_of(nbits);
     uint8_t* o = static_cast<uint8_t*>(out);
-    { Timed t(kSlotReset, s);    launch_reset(ws, state, num_chunks_of(n), s); }
-    { Timed t(kSlotHist, s);     launch_hist(w, w_ref, n, ws, ds->num_cu, s); }
+    { Timed t(kSlotReset, s);    launch_reset(ws, group_words, nc, s); }
+    { Timed t(kSlotHist, s);     launch_hist(w, w_ref, n, ws, ds->tune, s); }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, s); }
-    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, o, ws, state, ds->num_cu, s); }
+    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
     { Timed t(kSlotFinalize, s); launch_finalize(o, ws, n, nbits, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(g_pinned, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipMemcpyAsync(&g_pinned->result, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
-    const int slots[] = {kSlotReset, kSlotHist, kSlotTable, kSlotPack, kSlotFinalize};
-    collect(slots, 5);
-    if (g_pinned->status != LC_OK) return -(lc_ssize)g_pinned->status;
-    return (lc_ssize)g_pinned->bytes;
+    const int slots[] = {kSlotReset, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize};
+    collect(slots, 6);
+    if (g_pinned->result.status != LC_OK) return -(lc_ssize)g_pinned->result.status;
+    return (lc_ssize)g_pinned->result.bytes;
 }
 
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
@@ -136,32 +161,21 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     if (n && (!w_ref || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(lc_workspace_bytes(n, 4), &err, &ds);
+    Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
-    { Timed t(kSlotDecPrep, s);     launch_dec_prepare(b, n, lc_encode_bound(n, 4), ws, s); }
-    { Timed t(kSlotDecValidate, s); launch_dec_validate(b, n, ws, s); }
+    const uint64_t epoch = ++g_epoch;
+    { Timed t(kSlotDecCheck, s); launch_dec_check(b, n, lc_encode_bound(n, 4), ws, epoch, s); }
+    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, ds->tune, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(&g_pinned[0], &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
-    LC_HIP(hipMemcpyAsync(&g_pinned[1].status, &ws->dec_status, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipMemcpyAsync(&g_pinned->result, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
-    const int slots0[] = {kSlotDecPrep, kSlotDecValidate};
-    collect(slots0, 2);
-    if (g_pinned[0].status != LC_OK) return -(lc_ssize)g_pinned[0].status;
-    if (g_pinned[1].status != LC_OK) return -(lc_ssize)g_pinned[1].status;
-    const uint64_t total = g_pinned[0].bytes;
-    const uint32_t max_len = g_pinned[0].pad;
-    if (n == 0) return (lc_ssize)total;
-    if (max_len < 1 || max_len > kMaxLutBits) return -LC_ERR_BAD_BLOB;
-    { Timed t(kSlotDecode, s); launch_decode(b, w_ref, n, ws, max_len, ds->num_cu, s); }
-    LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(&g_pinned[1].status, &ws->dec_status, sizeof(uint32_t), hipMemcpyDeviceToHost, s));
-    LC_HIP(hipStreamSynchronize(s));
-    const int slots1[] = {kSlotDecode};
-    collect(slots1, 1);
-    if (g_pinned[1].status != LC_OK) return -(lc_ssize)g_pinned[1].status;
-    return (lc_ssize)total;
+    const int slots[] = {kSlotDecCheck, kSlotDecode};
+    collect(slots, 2);
+    if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
+    return (lc_ssize)g_pinned->result.bytes;
 }
 
 int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status) {

@@ -14,7 +14,7 @@ constexpr uint32_t kChunk = kRowElems * kR; // 16384 elements
 constexpr uint32_t kHeaderBytes = 512;
 constexpr uint32_t kLaneBitsWords = (2 * kW) / 4;   // 32 words of u16 lane lengths per chunk record
 constexpr uint32_t kMaxSym = 16;
-constexpr uint32_t kMaxLutBits = 15;
+constexpr uint32_t kDecLutBits = 11;        // decode look-up table covers codes up to this length
 
 // Written by the table kernel, read by pack / finalize.
 struct Table {
@@ -30,10 +30,11 @@ struct Table {
 
 // Written by the decode-prepare kernel.
 struct DecInfo {
-    uint32_t K, max_len, num_chunks, status;
+    uint32_t K, max_len, lut_bits, pad;
     uint64_t area;           // byte offset of the chunk area
     uint64_t total_words;    // chunk area size in 32-bit words
     uint32_t rep_bits[kMaxSym];
+    uint32_t len[kMaxSym], code[kMaxSym];
 };
 
 struct Result {              // copied to pinned host memory at the end of a call
@@ -42,38 +43,54 @@ struct Result {              // copied to pinned host memory at the end of a cal
     uint32_t pad;
 };
 
-// Fixed part of the per-device scratch; the per-chunk scan state follows it.
+// Fixed part of the per-device scratch.  It is followed by chunk_bits[num_chunks] and
+// group_words[ceil(num_chunks / 64)] (u32, each padded to 256 bytes) and by one slot of
+// slot_words_of(nbits) 32-bit words per chunk.
 struct Workspace {
     unsigned long long hist[512];
     uint32_t mmin[kMaxSym];
     uint32_t mmax[kMaxSym];
-    uint32_t ticket;
-    uint32_t dec_status;
+    uint32_t pad0[2];
+    unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
     DecInfo dec;
     Result result;
-    alignas(16) uint8_t dec_lut[1u << kMaxLutBits];
+    alignas(16) uint8_t dec_lut[1u << kDecLutBits];
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
 
 __host__ __device__ inline uint64_t num_chunks_of(uint64_t n) { return (n + kChunk - 1) / kChunk; }
+// Slot of one chunk in the scratch area: 64 lane lengths (u16), then up to 8 * max_len words
+// per lane (256 codes of at most max_len = 2^nbits - 1 bits), word k of lane l at [32 + 64 k + l].
+__host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u); }
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
-enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotFinalize,
-            kSlotDecPrep, kSlotDecValidate, kSlotDecode, kNumSlots };
+enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize,
+            kSlotDecCheck, kSlotDecode, kNumSlots };
 
-// Launchers (lc_kernels.hip).  `state` is the per-chunk scan state (num_chunks u64).
-void launch_reset(Workspace* ws, unsigned long long* state, uint64_t nchunks, hipStream_t s);
-void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, int num_cu, hipStream_t s);
+// Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
+// variables (read once) for sweeps.
+struct Tuning {
+    int num_cu = 256;
+    int hist_blocks_per_cu = 1;
+    int hist_threads = 256;
+    int pack_waves_per_cu = 6;
+    int decode_blocks_per_cu = 3;
+};
+
+// Launchers (lc_kernels.hip).
+void launch_reset(Workspace* ws, uint32_t* group_words, uint64_t nchunks, hipStream_t s);
+void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s);
-void launch_pack(const float* w, const float* w_ref, uint64_t n, uint8_t* out, Workspace* ws,
-                 unsigned long long* state, int num_cu, hipStream_t s);
+void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+                 uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
+void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStream_t s);
-void launch_dec_prepare(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, hipStream_t s);
-void launch_dec_validate(const uint8_t* blob, uint64_t n, Workspace* ws, hipStream_t s);
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint32_t max_len,
-                   int num_cu, hipStream_t s);
+void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, hipStream_t s);
+void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                   const Tuning& tune, hipStream_t s);
 
 }  // namespace lc

@@ -1,7 +1,7 @@
 // HIP kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64).
 //
-// encode:  k_reset -> k_hist -> k_table -> k_pack -> k_finalize
-// decode:  k_dec_prepare -> k_dec_validate -> (host checks status) -> k_decode
+// encode:  k_reset -> k_hist -> k_table -> k_pack -> k_place -> k_finalize
+// decode:  k_dec_check -> k_decode (gated on the check's verdict, no host round trip between)
 //
 // The paper (arXiv 2009.13003) defines what is computed: delta against the last
 // recovered state (Algorithm 1 line 4), (sign, exponent) buckets represented by the
@@ -55,14 +55,11 @@ __device__ __forceinline__ void load_row(const float* __restrict__ p, u64 idx, u
 }
 
 // ----------------------------------------------------------------------------- k_reset
-__global__ void k_reset(Workspace* ws, u64* state, u64 nchunks) {
-    const u64 tid = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    if (blockIdx.x == 0) {
-        for (u32 i = threadIdx.x; i < 512; i += blockDim.x) ws->hist[i] = 0;
-        if (threadIdx.x < kMaxSym) { ws->mmin[threadIdx.x] = 0x7FFFFFu; ws->mmax[threadIdx.x] = 0; }
-        if (threadIdx.x == 0) { ws->ticket = 0; ws->total_words = 0; ws->table.status = 0; }
-    }
-    for (u64 i = tid; i < nchunks; i += (u64)gridDim.x * blockDim.x) state[i] = 0;
+__global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups) {
+    for (u32 i = threadIdx.x; i < ngroups; i += blockDim.x) group_words[i] = 0;
+    for (u32 i = threadIdx.x; i < 512; i += blockDim.x) ws->hist[i] = 0;
+    if (threadIdx.x < kMaxSym) { ws->mmin[threadIdx.x] = 0x7FFFFFu; ws->mmax[threadIdx.x] = 0; }
+    if (threadIdx.x == 0) { ws->total_words = 0; ws->table.status = 0; }
 }
 
 // ----------------------------------------------------------------------------- k_hist
@@ -73,16 +70,16 @@ __global__ void k_reset(Workspace* ws, u64* state, u64 nchunks) {
 constexpr int kHistCopies = 8;
 
 template <bool ALIGNED>
-__global__ __launch_bounds__(256) void k_hist(const float* __restrict__ w, const float* __restrict__ w_ref,
-                                              u64 n, Workspace* ws) {
+__global__ __launch_bounds__(1024) void k_hist(const float* __restrict__ w, const float* __restrict__ w_ref,
+                                               u64 n, Workspace* ws) {
     __shared__ u32 h[512 * kHistCopies];
-    const u32 tid = threadIdx.x;
-    for (u32 i = tid; i < 512 * kHistCopies; i += 256) h[i] = 0;
+    const u32 tid = threadIdx.x, nthr = blockDim.x;
+    for (u32 i = tid; i < 512 * kHistCopies; i += nthr) h[i] = 0;
     __syncthreads();
     const u32 copy = tid & (kHistCopies - 1);
     const u64 n4 = n / 4;
-    const u64 stride = (u64)gridDim.x * 256;
-    u64 u = (u64)blockIdx.x * 256 + tid;
+    const u64 stride = (u64)gridDim.x * nthr;
+    u64 u = (u64)blockIdx.x * nthr + tid;
     for (; u + 3 * stride < n4; u += 4 * stride) {
         float a[4][4], b[4][4];
 #pragma unroll
@@ -103,7 +100,7 @@ __global__ __launch_bounds__(256) void k_hist(const float* __restrict__ w, const
         atomicAdd(&h[(delta_bits(w[i], w_ref[i]) >> 23) * kHistCopies + copy], 1u);
     }
     __syncthreads();
-    for (u32 b = tid; b < 512; b += 256) {
+    for (u32 b = tid; b < 512; b += nthr) {
         u32 s = 0;
 #pragma unroll
         for (int k = 0; k < kHistCopies; ++k) s += h[b * kHistCopies + k];
@@ -207,168 +204,250 @@ __global__ __launch_bounds__(512) void k_table(Workspace* ws, u64 n, int nbits) 
 }
 
 // ----------------------------------------------------------------------------- k_pack
-// Sweep 2: one wavefront per chunk.  Pass A re-derives each element's symbol, keeps it
-// (4 bits) in LDS, sums the lane's code lengths and tracks the mantissa extremes of the
-// kept buckets.  The chunk's size is then known; a decoupled look-back over a per-chunk
-// state word gives its word offset (chunks are handed out by an atomic ticket, so every
-// predecessor is already running).  Pass B emits the codes straight to their final place:
-// every payload word is stored exactly once by the lane whose stream holds its first bit;
-// partial words at lane boundaries travel through LDS.
-constexpr int kMmCopies = 8;
-constexpr u64 kFlagAgg = 1ull << 62, kFlagIncl = 2ull << 62, kValMask = (1ull << 62) - 1;
-
-__device__ __forceinline__ u64 lookback(u64* state, u32 c, u32 size_words) {
-    const u32 lane = lane_id();
-    if (c == 0) {
-        if (lane == 0) __hip_atomic_store(&state[0], kFlagIncl | size_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return 0;
-    }
-    if (lane == 0) __hip_atomic_store(&state[c], kFlagAgg | size_words, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    u64 excl = 0;
-    long long base = (long long)c - 1;
-    while (true) {
-        const long long idx = base - (long long)lane;
-        u64 v = kFlagIncl;                       // before chunk 0: an inclusive prefix of 0
-        if (idx >= 0) {
-            do {
-                v = __hip_atomic_load(&state[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((v >> 62) == 0) __builtin_amdgcn_s_sleep(2);
-            } while ((v >> 62) == 0);
-        }
-        const u64 incl = __ballot((v >> 62) == 2);
-        if (incl) {
-            const u32 p = __ffsll((long long)incl) - 1;      // nearest predecessor holding an inclusive prefix
-            excl += wave_sum64(lane <= p ? (v & kValMask) : 0);
-            break;
-        }
-        excl += wave_sum64(v & kValMask);
-        base -= 64;
-    }
-    if (lane == 0) __hip_atomic_store(&state[c], kFlagIncl | (excl + size_words), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return excl;
-}
+// Sweep 2: one wavefront per chunk, no communication between wavefronts.  Each lane codes its
+// 256 elements into a bit string of its own, written word by word to the chunk's slot in the
+// scratch area (lane-private, word k of lane l at slot[32 + 64 k + l]); the 64 bit lengths go
+// to the head of the slot, their sum to chunk_bits[c].  Where the strings end up in the blob is
+// decided afterwards by k_place, which knows all sizes.  A full, 16-byte aligned chunk takes
+// the fast path: rows are fetched eight at a time, one batch ahead (and the next chunk's first
+// batch before the current one ends), the table look-ups of 16 elements are issued together and
+// two symbols are coded per look-up.  Ragged or unaligned chunks take a plain path.  The
+// mantissa extremes of the kept buckets (Section 3.1.1: the representative is the mean of the
+// bucket's largest and smallest member) are tracked on the way.
+constexpr int kMmCopies = 32;       // LDS copies of the per-symbol extremes, one per lane of a half wave
 
 struct PackLds {
-    uint8_t symlen[512];
-    u32 codelen[kMaxSym];
-    u32 mn[kMaxSym * kMmCopies], mx[kMaxSym * kMmCopies];
-    u32 off[kW + 1];
-    u32 hw[kW];
-    uint16_t sym[kR * kW];       // 4 symbols (one row) per lane per entry
+    uint8_t sym8[512];               // bucket -> symbol << 3
+    u32 codelen[kMaxSym];            // (code << 5) | len
+    uint2 pair[256];                 // (symbol a, symbol b) -> {code of a followed by b, its length}
+    u32 mn[kMaxSym * kMmCopies], mx[kMaxSym * kMmCopies];   // extremes of the delta bit patterns per symbol
 };
 
-template <bool FAST>
-__device__ __forceinline__ void pack_chunk(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
-                                           uint8_t* out, u64 area, Workspace* ws, u64* state,
-                                           u32 c, u32 nchunks, u32 K, PackLds& L) {
+// chunk_bits[c] = payload bits of chunk c; group_words[g] = record words of chunks 64g .. 64g+63
+// (integer atomics: the sums do not depend on the order of arrival).
+__device__ __forceinline__ void finish_lane(u32* slot, u32* chunk_bits, u32* group_words, u32 c, u64 acc, u32 nb, u32 nw) {
+    const u32 lane = lane_id();
+    if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
+    const u32 bits = 32 * nw + nb;
+    reinterpret_cast<uint16_t*>(slot)[lane] = (uint16_t)bits;
+    const u32 total = wave_sum32(bits);
+    if (lane == 0) {
+        chunk_bits[c] = total;
+        atomicAdd(&group_words[c >> 6], kLaneBitsWords + ((total + 31) >> 5));
+    }
+}
+
+// Any size, any alignment: guarded scalar loads, one symbol per look-up.
+__device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+                                              u32* slot, u32* chunk_bits, u32* group_words, u32 c, PackLds& L) {
     const u32 lane = lane_id();
     const u64 base = (u64)c * kChunk;
-    // ---- pass A
-    u32 bits = 0;
-#pragma unroll 8
+    const u32 mm = lane & (kMmCopies - 1);
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;
     for (u32 r = 0; r < kR; ++r) {
         const u64 idx = base + (u64)r * kRowElems + lane * kV;
-        float a[4], b[4];
-        load_row<FAST>(w, idx, n, a); load_row<FAST>(w_ref, idx, n, b);
-        u32 packed = 0;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            if (!FAST && idx + v >= n) continue;
-            const u32 u = delta_bits(a[v], b[v]);
-            const u32 sl = L.symlen[u >> 23], s = sl & 15;
-            bits += sl >> 4;
-            packed |= s << (4 * v);
-            if (s < K) {
-                atomicMin(&L.mn[s * kMmCopies + (lane & (kMmCopies - 1))], u & 0x7FFFFFu);
-                atomicMax(&L.mx[s * kMmCopies + (lane & (kMmCopies - 1))], u & 0x7FFFFFu);
+            if (idx + v < n) {
+                const u32 u = delta_bits(w[idx + v], w_ref[idx + v]);
+                const u32 sy = L.sym8[u >> 23] >> 3;
+                const u32 cl = L.codelen[sy];
+                atomicMin(&L.mn[sy * kMmCopies + mm], u);
+                atomicMax(&L.mx[sy * kMmCopies + mm], u);
+                acc = (acc << (cl & 31)) | (cl >> 5);
+                nb += cl & 31;
+            }
+            if ((v & 1) && nb >= 32) {
+                slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
+                ++nw; nb -= 32;
             }
         }
-        L.sym[r * kW + lane] = (uint16_t)packed;
     }
-    // ---- size, offsets
-    const u32 incl = wave_incl_scan(bits);
-    const u32 o = incl - bits;                                  // first bit of this lane's stream
-    const u32 total_bits = __shfl(incl, 63, 64);
-    const u32 nwords = (total_bits + 31) >> 5;
-    const u32 size_words = kLaneBitsWords + nwords;
-    const u64 word_off = lookback(state, c, size_words);
-    u32* off_tab = reinterpret_cast<u32*>(out + kHeaderBytes);
-    if (lane == 0) {
-        off_tab[c] = (u32)word_off;
-        if (c + 1 == nchunks) ws->total_words = word_off + size_words;
-    }
-    uint8_t* rec = out + area + 4 * word_off;
-    reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
-    u32* payload = reinterpret_cast<u32*>(rec + 2 * kW);
-    L.off[lane] = o; L.hw[lane] = 0;
-    if (lane == 0) L.off[kW] = total_bits;
-    // ---- pass B
-    u64 acc = 0;
-    u32 nb = o & 31, widx = o >> 5;
-    auto flush = [&]() {
-        if (nb >= 32) {
-            const u32 word = (u32)(acc >> (nb - 32));
-            nb -= 32;
-            if (widx * 32 >= o) payload[widx] = word; else L.hw[lane] = word;
-            ++widx;
-        }
-    };
-    if (bits > 0) {
-#pragma unroll 4
-        for (u32 r = 0; r < kR; ++r) {
-            const u64 idx = base + (u64)r * kRowElems + lane * kV;
-            const u32 p = L.sym[r * kW + lane];
+    finish_lane(slot, chunk_bits, group_words, c, acc, nb, nw);
+}
+
+template <bool ROWCHK>
+__device__ __forceinline__ void pack_loop(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+                                          u32* prov, u32 slot_words, u32* chunk_bits, u32* group_words,
+                                          u32 nchunks, bool aligned, u32 K8, PackLds& L) {
+    constexpr int PF = 8;
+    const u32 lane = lane_id(), G = gridDim.x;
+    const u32 mm = lane & (kMmCopies - 1);
+    float4 A0[PF], B0[PF], A1[PF], B1[PF];
+    auto fast = [&](u32 c) { return aligned && c < nchunks && (u64)(c + 1) * kChunk <= n; };
+    auto rows_of = [&](const float* p, u32 c) { return reinterpret_cast<const float4*>(p + (u64)c * kChunk) + lane; };
+    u32 c = blockIdx.x;
+    if (fast(c)) {
+        const float4* pw = rows_of(w, c); const float4* pr = rows_of(w_ref, c);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (FAST || idx + v < n) {
-                    const u32 cl = L.codelen[(p >> (4 * v)) & 15];
-                    acc = (acc << (cl & 31)) | (cl >> 5);
-                    nb += cl & 31;
-                }
-                if (v & 1) flush();
+        for (int k = 0; k < PF; ++k) { A0[k] = pw[k * kW]; B0[k] = pr[k * kW]; }
+    }
+    for (; c < nchunks; c += G) {
+        u32* slot = prov + (u64)c * slot_words;
+        if (!fast(c)) {
+            pack_chunk_plain(w, w_ref, n, slot, chunk_bits, group_words, c, L);
+            if (fast(c + G)) {
+                const float4* pw = rows_of(w, c + G); const float4* pr = rows_of(w_ref, c + G);
+#pragma unroll
+                for (int k = 0; k < PF; ++k) { A0[k] = pw[k * kW]; B0[k] = pr[k * kW]; }
             }
+            continue;
         }
+        // ---- a full, aligned chunk whose first PF rows are already in A0/B0
+        const float4* pw = rows_of(w, c); const float4* pr = rows_of(w_ref, c);
+        const float4* qw = rows_of(w, c + G); const float4* qr = rows_of(w_ref, c + G);
+        const bool next_fast = fast(c + G);
+        u32* lane_words = slot + kLaneBitsWords + lane;
+        u64 acc = 0;
+        u32 nb = 0, nw = 0;                       // bits waiting in acc, words written
+        auto flush = [&]() {
+            if (nb >= 32) {
+                lane_words[nw * kW] = (u32)(acc >> (nb - 32));
+                ++nw; nb -= 32;
+            }
+        };
+        // Four rows at a time: all table look-ups of the 16 elements are issued together, so the
+        // LDS latency is paid twice per group instead of three times per row; only the shift/or
+        // chain that grows the lane's bit string is serial.
+        auto group = [&](const float4* a, const float4* b) {
+            u32 u[16], t[16];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                u[4 * k + 0] = delta_bits(a[k].x, b[k].x); u[4 * k + 1] = delta_bits(a[k].y, b[k].y);
+                u[4 * k + 2] = delta_bits(a[k].z, b[k].z); u[4 * k + 3] = delta_bits(a[k].w, b[k].w);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = L.sym8[u[i] >> 23];
+            uint2 p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                p[i] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(L.pair) + ((t[2 * i] << 4) | t[2 * i + 1]));
+            u32 tmin = t[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) tmin = min(tmin, t[i]);
+            if (__any(tmin < K8)) {
+                // some lane holds a kept element: everyone updates the extremes of its symbols
+                // (the merged symbol has a slot of its own that nobody reads)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    atomicMin(&L.mn[t[i] * (kMmCopies / 8) + mm], u[i]);
+                    atomicMax(&L.mx[t[i] * (kMmCopies / 8) + mm], u[i]);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                acc = (acc << p[i].y) | p[i].x; nb += p[i].y;
+                if (!ROWCHK || (i & 1)) flush();
+            }
+        };
+        for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) { A1[k] = pw[(r0 + PF + k) * kW]; B1[k] = pr[(r0 + PF + k) * kW]; }
+            group(A0, B0); group(A0 + 4, B0 + 4);
+            if (r0 + 2 * PF < kR) {
+#pragma unroll
+                for (int k = 0; k < PF; ++k) { A0[k] = pw[(r0 + 2 * PF + k) * kW]; B0[k] = pr[(r0 + 2 * PF + k) * kW]; }
+            } else if (next_fast) {
+#pragma unroll
+                for (int k = 0; k < PF; ++k) { A0[k] = qw[k * kW]; B0[k] = qr[k * kW]; }
+            }
+            group(A1, B1); group(A1 + 4, B1 + 4);
+        }
+        finish_lane(slot, chunk_bits, group_words, c, acc, nb, nw);
     }
-    u32 tail = 0; bool own_tail = false;
-    if (bits > 0 && nb > 0) {
-        tail = (u32)(acc << (32 - nb));
-        if (widx * 32 >= o) own_tail = true; else L.hw[lane] = tail;   // stream inside one foreign word
-    }
-    __syncthreads();
-    if (own_tail) {
-        for (u32 q = lane + 1; q < kW && (L.off[q] >> 5) == widx; ++q) tail |= L.hw[q];
-        payload[widx] = tail;
-    }
-    __syncthreads();
 }
 
 __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
-                                             uint8_t* out, Workspace* ws, u64* state, u32 nchunks, int aligned) {
+                                             Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                             u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds L;
     const u32 lane = threadIdx.x;
     const Table& T = ws->table;
     if (T.status != 0) return;
-    for (u32 i = lane; i < 512; i += 64) L.symlen[i] = T.symlen_of_bucket[i];
+    for (u32 i = lane; i < 512; i += 64) L.sym8[i] = (uint8_t)((T.symlen_of_bucket[i] & 15) << 3);
     if (lane < kMaxSym) L.codelen[lane] = T.codelen[lane];
-    for (u32 i = lane; i < kMaxSym * kMmCopies; i += 64) { L.mn[i] = 0x7FFFFFu; L.mx[i] = 0; }
-    const u32 K = T.K;
-    const u64 area = chunk_area_of(nchunks);
-    __syncthreads();
-    while (true) {
-        u32 c = 0;
-        if (lane == 0) c = atomicAdd(&ws->ticket, 1u);
-        c = __builtin_amdgcn_readfirstlane(c);
-        if (c >= nchunks) break;
-        const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) pack_chunk<true>(w, w_ref, n, out, area, ws, state, c, nchunks, K, L);
-        else pack_chunk<false>(w, w_ref, n, out, area, ws, state, c, nchunks, K, L);
+    for (u32 i = lane; i < 256; i += 64) {
+        const u32 ca = T.codelen[i >> 4], cb = T.codelen[i & 15];
+        L.pair[i] = make_uint2(((ca >> 5) << (cb & 31)) | (cb >> 5), (ca & 31) + (cb & 31));
     }
+    for (u32 i = lane; i < kMaxSym * kMmCopies; i += 64) { L.mn[i] = 0xFFFFFFFFu; L.mx[i] = 0; }
+    const u32 K = T.K;
+    __syncthreads();
+    // 31 waiting bits + 4 codes of <= 8 bits still fit the 64-bit accumulator: flush once per row
+    if (T.max_len <= 8) pack_loop<true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    else pack_loop<false>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
     __syncthreads();
     if (lane < K) {
-        u32 mn = 0x7FFFFFu, mx = 0;
+        u32 mn = 0xFFFFFFFFu, mx = 0;
 #pragma unroll
         for (int k = 0; k < kMmCopies; ++k) { mn = min(mn, L.mn[lane * kMmCopies + k]); mx = max(mx, L.mx[lane * kMmCopies + k]); }
-        if (mn <= mx) { atomicMin(&ws->mmin[lane], mn); atomicMax(&ws->mmax[lane], mx); }
+        if (mn <= mx) { atomicMin(&ws->mmin[lane], mn & 0x7FFFFFu); atomicMax(&ws->mmax[lane], mx & 0x7FFFFFu); }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_place
+// Builds the chunk area of the blob from the per-chunk slots, one wavefront per chunk.  The
+// chunk's word offset is the sum of the record sizes before it (whole groups of 64 chunks from
+// group_words, the rest from chunk_bits).  The 64 lane strings are joined without gaps: payload
+// word W0 + j of a lane takes the low bits of its word j-1 and the high bits of its word j.
+// Every payload word is stored exactly once, by the lane whose string holds its first bit;
+// partial words at lane boundaries travel through LDS.
+__global__ __launch_bounds__(64) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
+                                              const u32* __restrict__ group_words,
+                                              const u32* __restrict__ prov, u32 slot_words, u32 nchunks) {
+    __shared__ u32 s_off[kW + 1], s_hw[kW];
+    if (ws->table.status != 0) return;
+    const u32 lane = threadIdx.x, c = blockIdx.x;
+    const u32* slot = prov + (u64)c * slot_words;
+    const u32 bits = reinterpret_cast<const uint16_t*>(slot)[lane];
+    const u32 g = c >> 6;
+    u64 part = (64 * g + lane < c) ? kLaneBitsWords + ((chunk_bits[64 * g + lane] + 31) >> 5) : 0;
+#pragma unroll 4
+    for (u32 j = lane; j < g; j += kW) part += group_words[j];
+    const u64 word_off = wave_sum64(part);
+    const u32 incl = wave_incl_scan(bits);
+    const u32 o = incl - bits;                               // first bit of this lane's string
+    const u32 total_bits = __shfl(incl, 63, 64);
+    uint8_t* rec = out + chunk_area_of(nchunks) + 4 * word_off;
+    reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
+    u32* payload = reinterpret_cast<u32*>(rec + 2 * kW);
+    if (lane == 0) {
+        reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
+        s_off[kW] = total_bits;
+        if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + ((total_bits + 31) >> 5);
+    }
+    s_off[lane] = o; s_hw[lane] = 0;
+    const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
+    const u32 nt = bits ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
+    u32 nt_max = nt;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nt_max = max(nt_max, (u32)__shfl_xor(nt_max, d, 64));
+    const u32* lane_words = slot + kLaneBitsWords + lane;
+    u32 prev = 0, tail = 0;
+    bool own_tail = false;
+    for (u32 j0 = 0; j0 < nt_max; j0 += 8) {
+        u32 buf[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) buf[k] = (j0 + k < nloc) ? lane_words[(j0 + k) * kW] : 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const u32 j = j0 + k;
+            if (j < nt) {
+                const u32 val = __builtin_amdgcn_alignbit(prev, buf[k], sh);
+                prev = buf[k];
+                const bool owned = j > 0 || sh == 0;             // the word's first bit is this lane's
+                if (!owned) s_hw[lane] = val;
+                else if (j + 1 == nt) { tail = val; own_tail = true; }
+                else payload[W0 + j] = val;
+            }
+        }
+    }
+    __syncthreads();
+    if (own_tail) {                                              // following lanes may start inside this word
+        const u32 W = W0 + nt - 1;
+        for (u32 q = lane + 1; q < kW && (s_off[q] >> 5) == W; ++q) tail |= s_hw[q];
+        payload[W] = tail;
     }
 }
 
@@ -382,7 +461,8 @@ __global__ __launch_bounds__(128) void k_finalize(uint8_t* out, Workspace* ws, u
     const Table& T = ws->table;
     hdr[t] = 0;
     __syncthreads();
-    const bool ok = T.status == 0;
+    const u32 status = T.status;
+    const bool ok = status == 0;
     const u64 area = chunk_area_of(nchunks);
     const u64 total = ok ? area + 4 * ws->total_words : kHeaderBytes;
     if (t == 0) {
@@ -392,9 +472,9 @@ __global__ __launch_bounds__(128) void k_finalize(uint8_t* out, Workspace* ws, u
         hdr[4] = (u32)nbits;
         hdr[6] = kW; hdr[7] = kV; hdr[8] = kR;
         hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
-        hdr[12] = T.status;
+        hdr[12] = status;
         if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
-        ws->result.bytes = total; ws->result.status = T.status; ws->result.pad = 0;
+        ws->result.bytes = total; ws->result.status = status; ws->result.pad = 0;
     }
     if (ok && t <= T.K) {
         const u32 len = T.codelen[t] & 31;
@@ -422,40 +502,74 @@ __global__ __launch_bounds__(128) void k_finalize(uint8_t* out, Workspace* ws, u
     }
 }
 
-// ----------------------------------------------------------------------------- k_dec_prepare
-__global__ __launch_bounds__(256) void k_dec_prepare(const uint8_t* blob, u64 n, u64 max_total, Workspace* ws) {
+// ----------------------------------------------------------------------------- k_dec_check
+// Everything lc_decode verifies before w_ref is touched, in one launch.  Every workgroup
+// re-reads the header and does the cheap sanity checks that keep its own reads in bounds;
+// workgroup 0 additionally validates the symbol table, rebuilds the canonical codes and the
+// look-up table; each wavefront checks one chunk: the offset table must be the running sum
+// of the record sizes that the lane lengths imply, from 0 to the blob's stated size.
+// Errors are raised with atomicMax on a word tagged with the call's epoch, so the word
+// never needs clearing.
+__device__ __forceinline__ void raise_status(Workspace* ws, u64 epoch, u32 status) {
+    atomicMax(&ws->dec_status, (epoch << 8) | status);
+}
+
+__global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u64 max_total, Workspace* ws,
+                                                   u32 nchunks, u64 epoch) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     __shared__ u32 s_ok, s_K, s_max_len;
     __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
-    const u32 t = threadIdx.x;
+    const u32 t = threadIdx.x, lane = lane_id();
     if (t < kHeaderBytes / 4) hdr[t] = reinterpret_cast<const u32*>(blob)[t];
     __syncthreads();
+    const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
+    const u64 area = chunk_area_of(nchunks);
+    const bool head_ok = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 &&
+                         hn == n && hdr[9] == nchunks && total >= area && total <= max_total && ((total - area) & 3) == 0;
+    if (!head_ok) {
+        if (blockIdx.x == 0 && t == 0) {
+            const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 && hn != n;
+            raise_status(ws, epoch, n_mismatch ? 1u : 4u);
+            ws->result.bytes = 0;
+        }
+        return;
+    }
+    const u64 tw = (total - area) / 4;
+    // ---- one chunk per wavefront
+    const u32 c = blockIdx.x * 4 + (t >> 6);
+    if (c < nchunks) {
+        const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+        const u64 o0 = off_tab[c], o1 = off_tab[c + 1];
+        bool ok = o0 <= o1 && o1 <= tw && o1 - o0 >= kLaneBitsWords && (c > 0 || o0 == 0) && (c + 1 < nchunks || o1 == tw);
+        if (ok) {
+            const u32 lb = reinterpret_cast<const uint16_t*>(blob + area + 4 * o0)[lane];
+            const u32 sum = wave_sum32(lb);
+            ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
+        }
+        if (!ok && lane == 0) raise_status(ws, epoch, 4u);
+    }
+    if (blockIdx.x != 0) return;
+    // ---- workgroup 0: symbol table, codes, look-up table
     if (t == 0) {
-        const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
         const u32 nbits = hdr[4], K = hdr[5];
-        const u64 nchunks = (n + kChunk - 1) / kChunk, area = chunk_area_of(nchunks);
-        u32 status = 0;
-        bool ok = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0;
-        if (ok && hn != n) { ok = false; status = 1; }
-        ok = ok && nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1;
-        ok = ok && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR && hdr[9] == nchunks;
-        ok = ok && total >= area && total <= max_total && ((total - area) & 3) == 0;
+        bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
+        if (nchunks == 0 && tw != 0) ok = false;
         u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
         u32 per_len[17];
         for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+        for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; ws->dec.rep_bits[j] = 0; }
         if (ok) {
             for (u32 j = 0; j <= K; ++j) {
                 const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
-                const u64 c = hdr[18 + 4 * j] | ((u64)hdr[19 + 4 * j] << 32);
+                const u64 cn = hdr[18 + 4 * j] | ((u64)hdr[19 + 4 * j] << 32);
                 const u32 bucket = w0 & 0xFFFFu, len = (w0 >> 16) & 0xFFu;
-                cnt_sum += c;
-                if ((c > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) ok = false;
+                cnt_sum += cn;
+                if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
                 if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
                 if (j == K && rep != 0) ok = false;
                 s_len[j] = len; ws->dec.rep_bits[j] = rep;
-                if (len && len <= 15) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
+                if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
             }
-            for (u32 j = K + 1; j < kMaxSym; ++j) { s_len[j] = 0; ws->dec.rep_bits[j] = 0; }
             if (cnt_sum != n) ok = false;
             if (active >= 2 && kraft != (1u << 15)) ok = false;
             if (active == 1 && kraft != (1u << 14)) ok = false;
@@ -463,52 +577,57 @@ __global__ __launch_bounds__(256) void k_dec_prepare(const uint8_t* blob, u64 n,
         if (ok) {
             u32 next_code[17], code = 0;
             for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
-            for (u32 j = 0; j < kMaxSym; ++j) s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
-        }
-        if (!ok && status == 0) status = 4;
-        ws->dec.K = K; ws->dec.max_len = max_len; ws->dec.num_chunks = (u32)nchunks; ws->dec.status = status;
-        ws->dec.area = area; ws->dec.total_words = ok ? (total - area) / 4 : 0;
-        ws->dec_status = status;
-        ws->result.bytes = total; ws->result.status = status; ws->result.pad = max_len;
+            for (u32 j = 0; j < kMaxSym; ++j) {
+                s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
+                ws->dec.len[j] = s_len[j]; ws->dec.code[j] = s_code[j];
+            }
+        } else raise_status(ws, epoch, 4u);
+        ws->dec.K = K; ws->dec.max_len = max_len;
+        ws->dec.lut_bits = max_len < kDecLutBits ? max_len : kDecLutBits;
+        ws->dec.area = area; ws->dec.total_words = tw;
+        ws->result.bytes = total;
         s_ok = ok; s_K = K; s_max_len = max_len;
     }
     __syncthreads();
     if (!s_ok) return;
-    const u32 M = s_max_len, K = s_K;
-    for (u32 i = t; i < (1u << M); i += 256) {
-        u32 entry = K;                             // length 0: "no code starts like this"
-        for (u32 j = 0; j <= K; ++j)
-            if (s_len[j] && (i >> (M - s_len[j])) == s_code[j]) entry = j | (s_len[j] << 4);
+    const u32 M = s_max_len, K = s_K, P = M < kDecLutBits ? M : kDecLutBits;
+    for (u32 i = t; i < (1u << P); i += 256) {
+        // entry: symbol | len << 4; a prefix that starts no code: K with length 0; a prefix of a
+        // code longer than P bits: 0xFF
+        u32 entry = K;
+        for (u32 j = 0; j <= K; ++j) {
+            const u32 L = s_len[j];
+            if (L == 0) continue;
+            if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
+            else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+        }
         ws->dec_lut[i] = (uint8_t)entry;
     }
 }
 
-// ----------------------------------------------------------------------------- k_dec_validate
-// One wavefront per chunk: the offset table must be the running sum of the record sizes
-// that the lane lengths imply, starting at 0 and ending at the blob's stated size.
-__global__ __launch_bounds__(256) void k_dec_validate(const uint8_t* blob, Workspace* ws, u32 nchunks) {
-    if (ws->dec.status != 0) return;
-    const u32 c = blockIdx.x * 4 + (threadIdx.x >> 6), lane = lane_id();
-    if (c >= nchunks) return;
-    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
-    const u64 o0 = off_tab[c], o1 = off_tab[c + 1], tw = ws->dec.total_words;
-    bool ok = o0 <= o1 && o1 <= tw && o1 - o0 >= kLaneBitsWords && (c > 0 || o0 == 0) && (c + 1 < nchunks || o1 == tw);
-    if (ok) {
-        const u32 lb = reinterpret_cast<const uint16_t*>(blob + ws->dec.area + 4 * o0)[lane];
-        const u32 sum = wave_sum32(lb);
-        ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
-    }
-    if (!ok && lane == 0) atomicOr(&ws->dec_status, 4u);
-}
-
 // ----------------------------------------------------------------------------- k_decode
 // Algorithm 1 line 7: one wavefront per chunk, lane l decoding its own stream with a
-// 64-bit MSB-first window and a 2^max_len-entry look-up table in LDS, adding the
-// representative into w_ref with 16-byte read-modify-writes.
+// 64-bit MSB-first window and a look-up table in LDS over the next min(max_len, 11) bits
+// (longer codes take a short search), adding the representative into w_ref with 16-byte
+// read-modify-writes.
+struct DecLds {
+    uint8_t lut[1u << kDecLutBits];
+    float rep[kMaxSym];
+    u32 len[kMaxSym], code[kMaxSym];
+};
+
+__device__ __noinline__ u32 decode_long(const DecLds& L, u64 win, u32 P, u32 K) {
+    const u32 peek = (u32)(win >> (64 - 15));
+    for (u32 j = 0; j <= K; ++j) {
+        const u32 l = L.len[j];
+        if (l > P && (peek >> (15 - l)) == L.code[j]) return j | (l << 4);
+    }
+    return K;
+}
+
 template <bool FAST>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, u32 c, const uint8_t* lut, const float* s_rep,
-                                             u32 M, u32 K, u64 area) {
+                                             Workspace* ws, u32 c, const DecLds& L, u32 P, u32 K, u64 area, u64 epoch) {
     const u32 lane = lane_id();
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
     const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
@@ -526,7 +645,7 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, f
     wi += 2;
     u32 next = pw[min(wi, last)];
     const u64 base = (u64)c * kChunk;
-    const u32 shr = 64 - M;
+    const u32 shr = 64 - P;
 #pragma unroll 4
     for (u32 r = 0; r < kR; ++r) {
         const u64 idx = base + (u64)r * kRowElems + lane * kV;
@@ -536,10 +655,11 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, f
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (FAST || idx + v < n) {
-                const u32 e = lut[(u32)(win >> shr)];
+                u32 e = L.lut[(u32)(win >> shr)];
+                if (e == 0xFF) e = decode_long(L, win, P, K);
                 const u32 len = e >> 4, s = e & 15;
                 win <<= len; avail -= len; used += len;
-                const float rep = s_rep[s];
+                const float rep = L.rep[s];
                 x[v] = (s < K) ? __fadd_rn(x[v], rep) : x[v];
             }
             if ((v & 1) && avail <= 32) {
@@ -555,92 +675,93 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, f
             for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
         }
     }
-    if (__any(used != lane_bits) && lane == 0) atomicOr(&ws->dec_status, 4u);
+    if (__any(used != lane_bits) && lane == 0) raise_status(ws, epoch, 4u);
 }
 
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
-                                                Workspace* ws, u32 nchunks, int aligned) {
-    extern __shared__ __align__(16) uint8_t lut[];
-    __shared__ float s_rep[kMaxSym];
+                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch) {
+    __shared__ DecLds L;
+    if ((ws->dec_status >> 8) == epoch) return;          // the check kernel found something: touch nothing
     const u32 t = threadIdx.x;
-    const u32 M = ws->dec.max_len, K = ws->dec.K;
+    const u32 P = ws->dec.lut_bits, K = ws->dec.K;
     const u64 area = ws->dec.area;
-    {
-        const u32 nlut = 1u << M;
-        if (nlut >= 1024) {
-            const uint4* src = reinterpret_cast<const uint4*>(ws->dec_lut);
-            uint4* dst = reinterpret_cast<uint4*>(lut);
-            for (u32 i = t; i < nlut / 16; i += 256) dst[i] = src[i];
-        } else {
-            for (u32 i = t; i < nlut; i += 256) lut[i] = ws->dec_lut[i];
-        }
+    if ((1u << P) >= 1024) {
+        const uint4* src = reinterpret_cast<const uint4*>(ws->dec_lut);
+        uint4* dst = reinterpret_cast<uint4*>(L.lut);
+        for (u32 i = t; i < (1u << P) / 16; i += 256) dst[i] = src[i];
+    } else {
+        for (u32 i = t; i < (1u << P); i += 256) L.lut[i] = ws->dec_lut[i];
     }
-    if (t < kMaxSym) s_rep[t] = __uint_as_float(ws->dec.rep_bits[t]);
+    if (t < kMaxSym) { L.rep[t] = __uint_as_float(ws->dec.rep_bits[t]); L.len[t] = ws->dec.len[t]; L.code[t] = ws->dec.code[t]; }
     __syncthreads();
     const u32 wave = t >> 6;
     for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
         const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) decode_chunk<true>(blob, w_ref, n, ws, c, lut, s_rep, M, K, area);
-        else decode_chunk<false>(blob, w_ref, n, ws, c, lut, s_rep, M, K, area);
+        if (full && aligned) decode_chunk<true>(blob, w_ref, n, ws, c, L, P, K, area, epoch);
+        else decode_chunk<false>(blob, w_ref, n, ws, c, L, P, K, area, epoch);
     }
 }
 
 // ----------------------------------------------------------------------------- launchers
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-void launch_reset(Workspace* ws, u64* state, uint64_t nchunks, hipStream_t s) {
-    const u32 blocks = (u32)((nchunks + 255) / 256);
-    hipLaunchKernelGGL(k_reset, dim3(blocks < 1 ? 1 : (blocks > 1024 ? 1024 : blocks)), dim3(256), 0, s, ws, state, (u64)nchunks);
+void launch_reset(Workspace* ws, uint32_t* group_words, uint64_t nchunks, hipStream_t s) {
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)((nchunks + 63) / 64));
 }
 
-void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, int num_cu, hipStream_t s) {
+void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s) {
     if (n == 0) return;
-    u64 blocks = (n / 4 + 1023) / 1024;
-    const u64 cap = (u64)num_cu * 8;
+    const u32 threads = tune.hist_threads;
+    u64 blocks = (n / 4 + 4 * threads - 1) / (4 * threads);
+    const u64 cap = (u64)tune.num_cu * tune.hist_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist<true>, dim3((u32)blocks), dim3(256), 0, s, w, w_ref, (u64)n, ws);
-    else hipLaunchKernelGGL(k_hist<false>, dim3((u32)blocks), dim3(256), 0, s, w, w_ref, (u64)n, ws);
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist<true>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+    else hipLaunchKernelGGL(k_hist<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
 }
 
 void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s) {
     hipLaunchKernelGGL(k_table, dim3(1), dim3(512), 0, s, ws, (u64)n, nbits);
 }
 
-void launch_pack(const float* w, const float* w_ref, uint64_t n, uint8_t* out, Workspace* ws,
-                 u64* state, int num_cu, hipStream_t s) {
+void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+                 uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    u64 blocks = (u64)num_cu * 12;
+    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
     if (blocks > nchunks) blocks = nchunks;
     const int al = aligned16(w) && aligned16(w_ref);
-    hipLaunchKernelGGL(k_pack, dim3((u32)blocks), dim3(64), 0, s, w, w_ref, (u64)n, out, ws, state, (u32)nchunks, al);
+    hipLaunchKernelGGL(k_pack, dim3((u32)blocks), dim3(64), 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov,
+                       slot_words, (u32)nchunks, al);
+}
+
+void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    hipLaunchKernelGGL(k_place, dim3((u32)nchunks), dim3(64), 0, s, out, ws, chunk_bits, group_words, prov, slot_words,
+                       (u32)nchunks);
 }
 
 void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStream_t s) {
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(128), 0, s, out, ws, (u64)n, nbits, (u32)num_chunks_of(n));
 }
 
-void launch_dec_prepare(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, hipStream_t s) {
-    hipLaunchKernelGGL(k_dec_prepare, dim3(1), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws);
-}
-
-void launch_dec_validate(const uint8_t* blob, uint64_t n, Workspace* ws, hipStream_t s) {
+void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
-    if (nchunks == 0) return;
-    hipLaunchKernelGGL(k_dec_validate, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, blob, ws, (u32)nchunks);
+    const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
+    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws, (u32)nchunks, (u64)epoch);
 }
 
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint32_t max_len,
-                   int num_cu, hipStream_t s) {
+void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                   const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (nchunks + 3) / 4;
-    const u64 cap = (u64)num_cu * 4;
+    const u64 cap = (u64)tune.num_cu * tune.decode_blocks_per_cu;
     if (blocks > cap) blocks = cap;
-    const size_t lds = (size_t)1 << (max_len < 4 ? 4 : max_len);
-    hipLaunchKernelGGL(k_decode, dim3((u32)blocks), dim3(256), lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks,
-                       (int)aligned16(w_ref));
+    hipLaunchKernelGGL(k_decode, dim3((u32)blocks), dim3(256), 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks,
+                       (int)aligned16(w_ref), (u64)epoch);
 }
 
 }  // namespace lc
