@@ -84,19 +84,23 @@ class Job:
 
 
 def run(job, steps, warmup):
+    """Times `steps` steps with per-kernel events off (they cost ~60 us per step), then repeats the
+    same steps with the library's HIP-event timing on to get each kernel's average duration."""
     torch, lc = job.torch, job.lc
     for _ in range(warmup):
         job.step()
     torch.cuda.synchronize()
-    lc.lc_profile(True)
     enc = dec = 0.0
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         e, d = job.step()
         enc += e; dec += d
     torch.cuda.synchronize()
     total = time.perf_counter() - t0
+    lc.lc_profile(True)
+    for _ in range(steps):
+        job.step()
+    torch.cuda.synchronize()
     prof = lc.lc_profile_read()
     lc.lc_profile(False)
     gb = 4.0 * job.n / 1e9
@@ -162,6 +166,9 @@ def main():
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="run only a plain elementwise copy kernel of known size (553,430,176 bytes read and "
+                         "written per launch): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by "
@@ -170,6 +177,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
+
+    if args.calibrate:
+        src = torch.zeros(138_357_544, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "elementwise add, out-of-place", "bytes_read_per_launch": 4 * src.numel(),
+                          "bytes_written_per_launch": 4 * src.numel(), "launches": 5}))
+        return
 
     job = Job(args.workload, dev)
     res = run(job, args.steps, args.warmup)

@@ -80,14 +80,34 @@ __global__ __launch_bounds__(1024) void k_hist(const float* __restrict__ w, cons
     const u64 n4 = n / 4;
     const u64 stride = (u64)gridDim.x * nthr;
     u64 u = (u64)blockIdx.x * nthr + tid;
-    for (; u + 3 * stride < n4; u += 4 * stride) {
-        float a[4][4], b[4][4];
+    // Batches of PF 16-byte units per thread, one batch in flight while the previous one is counted.
+    constexpr int PF = 4;
+    float a0[PF][4], b0[PF][4], a1[PF][4], b1[PF][4];
+    auto fetch = [&](float (&a)[PF][4], float (&b)[PF][4], u64 at) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { load_row<ALIGNED>(w, 4 * (u + k * stride), n, a[k]); load_row<ALIGNED>(w_ref, 4 * (u + k * stride), n, b[k]); }
+        for (int k = 0; k < PF; ++k) { load_row<ALIGNED>(w, 4 * (at + k * stride), n, a[k]); load_row<ALIGNED>(w_ref, 4 * (at + k * stride), n, b[k]); }
+    };
+    auto count = [&](float (&a)[PF][4], float (&b)[PF][4]) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < PF; ++k)
 #pragma unroll
             for (int v = 0; v < 4; ++v) atomicAdd(&h[(delta_bits(a[k][v], b[k][v]) >> 23) * kHistCopies + copy], 1u);
+    };
+    const u64 step = PF * stride;
+    if (u + (PF - 1) * stride < n4) {
+        fetch(a0, b0, u);
+        while (true) {
+            const bool more1 = u + step + (PF - 1) * stride < n4;
+            if (more1) fetch(a1, b1, u + step);
+            count(a0, b0);
+            u += step;
+            if (!more1) break;
+            const bool more0 = u + step + (PF - 1) * stride < n4;
+            if (more0) fetch(a0, b0, u + step);
+            count(a1, b1);
+            u += step;
+            if (!more0) break;
+        }
     }
     for (; u < n4; u += stride) {
         float a[4], b[4];
@@ -393,29 +413,36 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
 // word W0 + j of a lane takes the low bits of its word j-1 and the high bits of its word j.
 // Every payload word is stored exactly once, by the lane whose string holds its first bit;
 // partial words at lane boundaries travel through LDS.
-__global__ __launch_bounds__(64) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
-                                              const u32* __restrict__ group_words,
-                                              const u32* __restrict__ prov, u32 slot_words, u32 nchunks) {
-    __shared__ u32 s_off[kW + 1], s_hw[kW];
+__global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
+                                               const u32* __restrict__ group_words,
+                                               const u32* __restrict__ prov, u32 slot_words, u32 nchunks) {
+    __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
     if (ws->table.status != 0) return;
-    const u32 lane = threadIdx.x, c = blockIdx.x;
-    const u32* slot = prov + (u64)c * slot_words;
-    const u32 bits = reinterpret_cast<const uint16_t*>(slot)[lane];
+    const u32 lane = lane_id(), wv = threadIdx.x >> 6;
+    u32* s_off = s_off_all[wv];
+    u32* s_hw = s_hw_all[wv];
+    const u32 c = blockIdx.x * 4 + wv;
+    const bool valid = c < nchunks;                          // the last workgroup may hold idle wavefronts
+    const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
+    const u32 bits = valid ? reinterpret_cast<const uint16_t*>(slot)[lane] : 0;
     const u32 g = c >> 6;
-    u64 part = (64 * g + lane < c) ? kLaneBitsWords + ((chunk_bits[64 * g + lane] + 31) >> 5) : 0;
+    u64 part = (valid && 64 * g + lane < c) ? kLaneBitsWords + ((chunk_bits[64 * g + lane] + 31) >> 5) : 0;
+    if (valid) {
 #pragma unroll 4
-    for (u32 j = lane; j < g; j += kW) part += group_words[j];
+        for (u32 j = lane; j < g; j += kW) part += group_words[j];
+    }
     const u64 word_off = wave_sum64(part);
     const u32 incl = wave_incl_scan(bits);
     const u32 o = incl - bits;                               // first bit of this lane's string
     const u32 total_bits = __shfl(incl, 63, 64);
     uint8_t* rec = out + chunk_area_of(nchunks) + 4 * word_off;
-    reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
     u32* payload = reinterpret_cast<u32*>(rec + 2 * kW);
-    if (lane == 0) {
-        reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
-        s_off[kW] = total_bits;
-        if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + ((total_bits + 31) >> 5);
+    if (valid) {
+        reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
+        if (lane == 0) {
+            reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
+            if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + ((total_bits + 31) >> 5);
+        }
     }
     s_off[lane] = o; s_hw[lane] = 0;
     const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
@@ -739,7 +766,7 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    hipLaunchKernelGGL(k_place, dim3((u32)nchunks), dim3(64), 0, s, out, ws, chunk_bits, group_words, prov, slot_words,
+    hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov, slot_words,
                        (u32)nchunks);
 }
 
