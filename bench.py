@@ -31,6 +31,8 @@ def make_workload(name, device):
         w, r, nbits = W.vgg16(device=device)
     elif name == "llama7b":
         w, r, nbits = W.llama7b(device=device)
+    elif name == "llama7b_slice0":
+        w, r, nbits = W.llama7b_head(device=device)
     elif name == "gpt2_medium":
         chain = W.Gpt2Chain(device=device)
         r = chain.w0

@@ -14,7 +14,8 @@ constexpr uint32_t kChunk = kRowElems * kR; // 16384 elements
 constexpr uint32_t kHeaderBytes = 512;
 constexpr uint32_t kLaneBitsWords = (2 * kW) / 4;   // 32 words of u16 lane lengths per chunk record
 constexpr uint32_t kMaxSym = 16;
-constexpr uint32_t kDecLutBits = 11;        // decode look-up table covers codes up to this length
+constexpr uint32_t kDecLut1Bits = 7;        // first decode table: conflict-free in LDS
+constexpr uint32_t kDecLut2Bits = 12;       // second decode table, for codes of 8..12 bits
 
 // Written by the table kernel, read by pack / finalize.
 struct Table {
@@ -30,7 +31,7 @@ struct Table {
 
 // Written by the decode-prepare kernel.
 struct DecInfo {
-    uint32_t K, max_len, lut_bits, pad;
+    uint32_t K, max_len, pad[2];
     uint64_t area;           // byte offset of the chunk area
     uint64_t total_words;    // chunk area size in 32-bit words
     uint32_t rep_bits[kMaxSym];
@@ -56,7 +57,8 @@ struct Workspace {
     Table table;
     DecInfo dec;
     Result result;
-    alignas(16) uint8_t dec_lut[1u << kDecLutBits];
+    alignas(16) uint8_t dec_lut1[1u << kDecLut1Bits];   // symbol | len << 4 over the next 7 bits
+    alignas(16) uint8_t dec_lut2[1u << kDecLut2Bits];   // ... over the next 12 bits
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
@@ -77,7 +79,7 @@ struct Tuning {
     int hist_blocks_per_cu = 1;
     int hist_threads = 256;
     int pack_waves_per_cu = 6;
-    int decode_blocks_per_cu = 3;
+    int decode_blocks_per_cu = 4;
 };
 
 // Launchers (lc_kernels.hip).

@@ -411,16 +411,22 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
 // chunk's word offset is the sum of the record sizes before it (whole groups of 64 chunks from
 // group_words, the rest from chunk_bits).  The 64 lane strings are joined without gaps: payload
 // word W0 + j of a lane takes the low bits of its word j-1 and the high bits of its word j.
-// Every payload word is stored exactly once, by the lane whose string holds its first bit;
-// partial words at lane boundaries travel through LDS.
+// A payload of up to kPlaceWords words is assembled in LDS (every lane ORs its shifted words
+// into a cleared buffer, so words shared by neighbouring lanes need no special care) and
+// written out with coalesced stores.  A larger payload is written directly: every word exactly
+// once, by the lane whose string holds its first bit, boundary words merged through LDS.
+constexpr u32 kPlaceWords = 2048;
+
 __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
                                                const u32* __restrict__ group_words,
                                                const u32* __restrict__ prov, u32 slot_words, u32 nchunks) {
     __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
+    __shared__ u32 s_buf_all[4][kPlaceWords];
     if (ws->table.status != 0) return;
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     u32* s_off = s_off_all[wv];
     u32* s_hw = s_hw_all[wv];
+    u32* s_buf = s_buf_all[wv];
     const u32 c = blockIdx.x * 4 + wv;
     const bool valid = c < nchunks;                          // the last workgroup may hold idle wavefronts
     const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
@@ -435,22 +441,29 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, cons
     const u32 incl = wave_incl_scan(bits);
     const u32 o = incl - bits;                               // first bit of this lane's string
     const u32 total_bits = __shfl(incl, 63, 64);
+    const u32 nwords = (total_bits + 31) >> 5;
     uint8_t* rec = out + chunk_area_of(nchunks) + 4 * word_off;
     u32* payload = reinterpret_cast<u32*>(rec + 2 * kW);
     if (valid) {
         reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
         if (lane == 0) {
             reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
-            if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + ((total_bits + 31) >> 5);
+            if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
         }
     }
-    s_off[lane] = o; s_hw[lane] = 0;
     const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
     const u32 nt = bits ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
     u32 nt_max = nt;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nt_max = max(nt_max, (u32)__shfl_xor(nt_max, d, 64));
     const u32* lane_words = slot + kLaneBitsWords + lane;
+    const bool staged = nwords <= kPlaceWords;               // wave-uniform
+    if (staged) {
+        for (u32 i = lane; i < nwords; i += kW) s_buf[i] = 0;
+    } else {
+        s_off[lane] = o; s_hw[lane] = 0;
+        if (lane == 0) s_off[kW] = total_bits;
+    }
     u32 prev = 0, tail = 0;
     bool own_tail = false;
     for (u32 j0 = 0; j0 < nt_max; j0 += 8) {
@@ -463,15 +476,21 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, cons
             if (j < nt) {
                 const u32 val = __builtin_amdgcn_alignbit(prev, buf[k], sh);
                 prev = buf[k];
-                const bool owned = j > 0 || sh == 0;             // the word's first bit is this lane's
-                if (!owned) s_hw[lane] = val;
-                else if (j + 1 == nt) { tail = val; own_tail = true; }
-                else payload[W0 + j] = val;
+                if (staged) {
+                    atomicOr(&s_buf[W0 + j], val);
+                } else {
+                    const bool owned = j > 0 || sh == 0;         // the word's first bit is this lane's
+                    if (!owned) s_hw[lane] = val;
+                    else if (j + 1 == nt) { tail = val; own_tail = true; }
+                    else payload[W0 + j] = val;
+                }
             }
         }
     }
     __syncthreads();
-    if (own_tail) {                                              // following lanes may start inside this word
+    if (staged) {
+        for (u32 i = lane; i < nwords; i += kW) payload[i] = s_buf[i];
+    } else if (own_tail) {                                       // following lanes may start inside this word
         const u32 W = W0 + nt - 1;
         for (u32 q = lane + 1; q < kW && (s_off[q] >> 5) == W; ++q) tail |= s_hw[q];
         payload[W] = tail;
@@ -610,99 +629,160 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
             }
         } else raise_status(ws, epoch, 4u);
         ws->dec.K = K; ws->dec.max_len = max_len;
-        ws->dec.lut_bits = max_len < kDecLutBits ? max_len : kDecLutBits;
         ws->dec.area = area; ws->dec.total_words = tw;
         ws->result.bytes = total;
         s_ok = ok; s_K = K; s_max_len = max_len;
     }
     __syncthreads();
     if (!s_ok) return;
-    const u32 M = s_max_len, K = s_K, P = M < kDecLutBits ? M : kDecLutBits;
-    for (u32 i = t; i < (1u << P); i += 256) {
-        // entry: symbol | len << 4; a prefix that starts no code: K with length 0; a prefix of a
-        // code longer than P bits: 0xFF
-        u32 entry = K;
-        for (u32 j = 0; j <= K; ++j) {
-            const u32 L = s_len[j];
-            if (L == 0) continue;
-            if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
-            else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+    // Two tables over the next P bits of a lane's string, entry = symbol | len << 4.  A prefix that
+    // starts no code: symbol K with length 0 (the lane then falls short of its stated length); a
+    // prefix of a code longer than P bits: 0xFF.  The first table (P = min(max_len, 7): 128 bytes,
+    // one 32-bit word per LDS bank) resolves the frequent short codes without bank conflicts.
+    const u32 M = s_max_len, K = s_K;
+    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+    for (u32 pass = 0; pass < 2; ++pass) {
+        const u32 P = pass ? P2 : P1;
+        uint8_t* lut = pass ? ws->dec_lut2 : ws->dec_lut1;
+        if (pass && M <= kDecLut1Bits) break;
+        for (u32 i = t; i < (1u << P); i += 256) {
+            u32 entry = K;
+            for (u32 j = 0; j <= K; ++j) {
+                const u32 L = s_len[j];
+                if (L == 0) continue;
+                if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
+                else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+            }
+            lut[i] = (uint8_t)entry;
         }
-        ws->dec_lut[i] = (uint8_t)entry;
     }
 }
 
 // ----------------------------------------------------------------------------- k_decode
-// Algorithm 1 line 7: one wavefront per chunk, lane l decoding its own stream with a
-// 64-bit MSB-first window and a look-up table in LDS over the next min(max_len, 11) bits
-// (longer codes take a short search), adding the representative into w_ref with 16-byte
-// read-modify-writes.
+// Algorithm 1 line 7: one wavefront per chunk, lane l decoding its own string with a 64-bit
+// MSB-first window.  The chunk's payload is first copied to LDS with coalesced 16-byte loads, so
+// the lanes' word-by-word refills never go to memory.  Symbols come from the two look-up tables
+// (codes longer than 12 bits take a short search); the merged symbol adds -0.0, which leaves
+// every fp32 pattern unchanged, and a row in which no lane decoded a kept symbol is not written
+// back at all.
+constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average)
+
 struct DecLds {
-    uint8_t lut[1u << kDecLutBits];
+    uint8_t lut1[1u << kDecLut1Bits];
+    uint8_t lut2[1u << kDecLut2Bits];
     float rep[kMaxSym];
     u32 len[kMaxSym], code[kMaxSym];
+    uint4 payload[4][kPayWords / 4 + 1];
 };
 
-__device__ __noinline__ u32 decode_long(const DecLds& L, u64 win, u32 P, u32 K) {
+__device__ __noinline__ u32 decode_long(const DecLds& L, u64 win, u32 K) {
     const u32 peek = (u32)(win >> (64 - 15));
     for (u32 j = 0; j <= K; ++j) {
         const u32 l = L.len[j];
-        if (l > P && (peek >> (15 - l)) == L.code[j]) return j | (l << 4);
+        if (l > kDecLut2Bits && (peek >> (15 - l)) == L.code[j]) return j | (l << 4);
     }
     return K;
 }
 
-template <bool FAST>
-__device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, u32 c, const DecLds& L, u32 P, u32 K, u64 area, u64 epoch) {
+// MSB-first bit window over payload words that live in LDS (STAGED) or in global memory.
+template <bool STAGED>
+struct BitReader {
+    const u32* pw;                   // payload words (index 0 = first word of the chunk's payload)
+    u32 last;                        // index of the last payload word (reads are clamped to it)
+    u64 win;                         // next bits, left aligned
+    u32 avail, wi, next;             // valid bits in win; index of `next`; the word after the window
+    __device__ __forceinline__ u32 word(u32 i) const { return pw[min(i, last)]; }
+    __device__ __forceinline__ void start(const u32* words, u32 nwords, u32 first_bit) {
+        pw = words; last = nwords - 1;
+        wi = first_bit >> 5;
+        const u32 sh = first_bit & 31;
+        win = (((u64)word(wi) << 32) | word(wi + 1)) << sh;
+        avail = 64 - sh;
+        wi += 2;
+        next = word(wi);
+    }
+    __device__ __forceinline__ void refill() {           // call when avail <= 32
+        win |= (u64)next << (32 - avail);
+        avail += 32; ++wi;
+        next = word(wi);
+    }
+};
+
+template <bool FAST, bool LV2, bool STAGED>
+__device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
+                                            float* __restrict__ w_ref, u64 n, Workspace* ws, u32 c,
+                                            const DecLds& L, u32 P1, u32 P2, u32 K, u64 epoch) {
     const u32 lane = lane_id();
-    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
-    const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
-    const uint8_t* rec = blob + area + 4 * (u64)o0;
-    const u32 nwords = o1 - o0 - kLaneBitsWords;        // >= 1 (validated)
-    const u32 lane_bits = reinterpret_cast<const uint16_t*>(rec)[lane];
-    const u32* __restrict__ pw = reinterpret_cast<const u32*>(rec + 2 * kW);
-    const u32 o = wave_incl_scan(lane_bits) - lane_bits;
-    const u32 last = nwords - 1;
-    u32 wi = o >> 5;
-    const u32 sh = o & 31;
-    const u32 w0 = pw[min(wi, last)], w1 = pw[min(wi + 1, last)];
-    u64 win = (((u64)w0 << 32) | w1) << sh;
-    u32 avail = 64 - sh, used = 0;
-    wi += 2;
-    u32 next = pw[min(wi, last)];
+    BitReader<STAGED> br;
+    br.start(words, nwords, first_bit);
+    const u32 wi0 = br.wi, avail0 = br.avail;
+    const u32 shr1 = 64 - P1, shr2 = 64 - P2;
     const u64 base = (u64)c * kChunk;
-    const u32 shr = 64 - P;
 #pragma unroll 4
     for (u32 r = 0; r < kR; ++r) {
         const u64 idx = base + (u64)r * kRowElems + lane * kV;
         if (!FAST && idx >= n) break;
         float x[4];
         load_row<FAST>(w_ref, idx, n, x);
+        u32 smin = K;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (FAST || idx + v < n) {
-                u32 e = L.lut[(u32)(win >> shr)];
-                if (e == 0xFF) e = decode_long(L, win, P, K);
-                const u32 len = e >> 4, s = e & 15;
-                win <<= len; avail -= len; used += len;
-                const float rep = L.rep[s];
-                x[v] = (s < K) ? __fadd_rn(x[v], rep) : x[v];
+                u32 e = L.lut1[(u32)(br.win >> shr1)];
+                if (LV2 && e == 0xFF) {
+                    e = L.lut2[(u32)(br.win >> shr2)];
+                    if (e == 0xFF) e = decode_long(L, br.win, K);
+                }
+                const u32 len = e >> 4, sy = e & 15;
+                br.win <<= len; br.avail -= len;
+                smin = min(smin, sy);
+                x[v] = __fadd_rn(x[v], L.rep[sy]);
             }
-            if ((v & 1) && avail <= 32) {
-                win |= (u64)next << (32 - avail);
-                avail += 32; ++wi;
-                next = pw[min(wi, last)];
-            }
+            if ((v & 1) && br.avail <= 32) br.refill();
         }
         if (FAST) {
-            *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+            if (__any(smin < K)) *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
         }
     }
+    const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
     if (__any(used != lane_bits) && lane == 0) raise_status(ws, epoch, 4u);
+}
+
+template <bool FAST, bool LV2>
+__device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
+                                             Workspace* ws, u32 c, DecLds& L, u32 P1, u32 P2, u32 K, u64 area, u64 epoch) {
+    const u32 lane = lane_id(), wv = threadIdx.x >> 6;
+    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+    const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
+    const uint8_t* rec = blob + area + 4 * (u64)o0;
+    const u32 nwords = o1 - o0 - kLaneBitsWords;        // >= 1 (validated)
+    const u32 lane_bits = reinterpret_cast<const uint16_t*>(rec)[lane];
+    const u32 o = wave_incl_scan(lane_bits) - lane_bits;
+    const u32* gw = reinterpret_cast<const u32*>(rec + 2 * kW);
+    const u32 k0 = (u32)((reinterpret_cast<uintptr_t>(gw) >> 2) & 3);     // words between the 16-byte boundary and the payload
+    if (nwords + k0 <= kPayWords) {
+        // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
+        // record's own lane lengths, and the last vector is read word by word so no read passes the end
+        const uint4* gv = reinterpret_cast<const uint4*>(gw - k0);
+        const u32 nvec = (nwords + k0 + 3) >> 2;
+        for (u32 i = lane; i < nvec; i += kW) {
+            uint4 q;
+            if (4 * i + 4 <= nwords + k0) q = gv[i];
+            else {
+                const u32* t = reinterpret_cast<const u32*>(gv + i);
+                const u32 left = nwords + k0 - 4 * i;
+                q.x = t[0]; q.y = left > 1 ? t[1] : 0; q.z = left > 2 ? t[2] : 0; q.w = 0;
+            }
+            L.payload[wv][i] = q;
+        }
+        decode_rows<FAST, LV2, true>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
+                                     w_ref, n, ws, c, L, P1, P2, K, epoch);
+    } else {
+        decode_rows<FAST, LV2, false>(gw, nwords, o, lane_bits, w_ref, n, ws, c, L, P1, P2, K, epoch);
+    }
 }
 
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
@@ -710,22 +790,33 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
     __shared__ DecLds L;
     if ((ws->dec_status >> 8) == epoch) return;          // the check kernel found something: touch nothing
     const u32 t = threadIdx.x;
-    const u32 P = ws->dec.lut_bits, K = ws->dec.K;
+    const u32 M = ws->dec.max_len, K = ws->dec.K;
+    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
     const u64 area = ws->dec.area;
-    if ((1u << P) >= 1024) {
-        const uint4* src = reinterpret_cast<const uint4*>(ws->dec_lut);
-        uint4* dst = reinterpret_cast<uint4*>(L.lut);
-        for (u32 i = t; i < (1u << P) / 16; i += 256) dst[i] = src[i];
-    } else {
-        for (u32 i = t; i < (1u << P); i += 256) L.lut[i] = ws->dec_lut[i];
+    if (t < (1u << P1)) L.lut1[t] = ws->dec_lut1[t];
+    if (M > kDecLut1Bits) {
+        if ((1u << P2) >= 4096) {
+            const uint4* src = reinterpret_cast<const uint4*>(ws->dec_lut2);
+            uint4* dst = reinterpret_cast<uint4*>(L.lut2);
+            for (u32 i = t; i < (1u << P2) / 16; i += 256) dst[i] = src[i];
+        } else {
+            for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = ws->dec_lut2[i];
+        }
     }
-    if (t < kMaxSym) { L.rep[t] = __uint_as_float(ws->dec.rep_bits[t]); L.len[t] = ws->dec.len[t]; L.code[t] = ws->dec.code[t]; }
+    if (t < kMaxSym) {
+        L.rep[t] = __uint_as_float(t < K ? ws->dec.rep_bits[t] : 0x80000000u);
+        L.len[t] = ws->dec.len[t]; L.code[t] = ws->dec.code[t];
+    }
     __syncthreads();
     const u32 wave = t >> 6;
     for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
         const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) decode_chunk<true>(blob, w_ref, n, ws, c, L, P, K, area, epoch);
-        else decode_chunk<false>(blob, w_ref, n, ws, c, L, P, K, area, epoch);
+        if (full && aligned) {
+            if (M > kDecLut1Bits) decode_chunk<true, true>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
+            else decode_chunk<true, false>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
+        } else {
+            decode_chunk<false, true>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
+        }
     }
 }
 

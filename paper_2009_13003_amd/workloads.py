@@ -144,6 +144,28 @@ def llama7b(seed=0, device="cpu", shrink_by=1):
     return per_tensor_laplace(shrink(llama7b_shapes(), shrink_by), -6, -3, 4, seed, device)
 
 
+def llama7b_head(nel=1 << 28, seed=0, device="cpu"):
+    """The first `nel` elements of config 5 (same values as llama7b()[:nel]): enough leading tensors, then cut."""
+    shapes, total = [], 0
+    for s in llama7b_shapes():
+        shapes.append(s)
+        total += math.prod(s)
+        if total >= nel:
+            break
+    nfull = len(llama7b_shapes())
+    scales = 10.0 ** np.random.RandomState(seed + 2).uniform(-6, -3, size=nfull)[:len(shapes)]
+    w_ref = reference_weights(total, seed, device)
+    g = _gen(seed + 1, device)
+    w = torch.empty_like(w_ref)
+    off = 0
+    for s, b in zip(shapes, scales):
+        m = math.prod(s)
+        _fill(w[off:off + m], lambda k, b=float(b): _laplace(k, b, g, device))
+        off += m
+    w += w_ref
+    return w[:nel].clone(), w_ref[:nel].clone(), 4
+
+
 def vgg16(seed=0, device="cpu", shrink_by=1):
     """Config 3: VGG-16 shapes, delta = 1e-4 * Student-t(3), 10 % of entries exactly unchanged, nbits = 3."""
     nel = numel(shrink(vgg16_shapes(), shrink_by))
