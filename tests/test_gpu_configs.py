@@ -118,3 +118,21 @@ def test_config5_llama7b_slices(lc):
         cnt = np.frombuffer(hdr[64:64 + 16 * 16].tobytes(), dtype=np.uint64)[1::2]
         assert int(cnt.sum()) == hi - lo and int(changed.sum()) <= int(cnt[:K].sum())
         del rec, d, dq, changed, err
+
+
+def test_single_call_past_4gib_offsets(lc):
+    """One call whose arrays are larger than 4 GiB (byte offsets and chunk indices beyond 32-bit
+    element arithmetic), ragged tail included, in full against the oracle."""
+    n = (1 << 30) + 100_000_007
+    g = torch.Generator(device=DEV); g.manual_seed(123)
+    w_ref = torch.empty(n, device=DEV)
+    w = torch.empty(n, device=DEV)
+    piece = 1 << 27
+    for lo in range(0, n, piece):
+        hi = min(n, lo + piece)
+        w_ref[lo:hi] = 0.05 * torch.randn(hi - lo, generator=g, device=DEV)
+        u = torch.rand(hi - lo, generator=g, device=DEV) - 0.5
+        scale = 1e-4 * (1 + 9 * (lo // piece % 3))               # three alternating scales
+        w[lo:hi] = w_ref[lo:hi] - scale * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
+        del u
+    full_check(lc, w, w_ref, 4, "n = 2^30 + 100,000,007")
