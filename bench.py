@@ -126,6 +126,47 @@ def run(job, steps, warmup):
                 ratio=4.0 * job.n / job.blob_bytes(), bits_per_elem=bits, blob_bytes=job.blob_bytes(), kernels=kernels)
 
 
+def chain_leg(device, steps):
+    """Config 4: `steps` successive checkpoints of the GPT-2-medium-shaped vector, each encoded against the
+    recovered state and decoded into it (Algorithm 1); then the restore from u_0 (Section 3, C1) timed two
+    ways: one lc_decode per blob, and lc_decode_many over all blobs."""
+    import torch
+    from paper_2009_13003_amd import lc, workloads
+    chain = workloads.Gpt2Chain(device=device)
+    n, nbits = chain.nel, chain.nbits
+    tracked = chain.w0.clone()
+    out = lc.alloc_out(n, nbits, device)
+    blobs, enc, dec = [], 0.0, 0.0
+    for _ in range(steps):
+        w = chain.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter(); size = lc.lc_encode(w, tracked, nbits, out)
+        t1 = time.perf_counter(); lc.lc_decode(out, tracked)
+        t2 = time.perf_counter()
+        enc += t1 - t0; dec += t2 - t1
+        blobs.append(out[:size].clone())
+    gb = 4.0 * n / 1e9
+    restored = chain.w0.clone()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for b in blobs:
+        lc.lc_decode(b, restored)
+    t_seq = time.perf_counter() - t0
+    same_seq = bool(torch.equal(restored.view(torch.int32), tracked.view(torch.int32)))
+    restored.copy_(chain.w0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lc.lc_decode_many(blobs, restored)
+    t_many = time.perf_counter() - t0
+    same_many = bool(torch.equal(restored.view(torch.int32), tracked.view(torch.int32)))
+    total_blob = sum(b.numel() for b in blobs)
+    return dict(n=n, nbits=nbits, steps=steps, encode_ms=round(1e3 * enc / steps, 4), decode_ms=round(1e3 * dec / steps, 4),
+                encode_GBps=round(gb / (enc / steps), 1), decode_GBps=round(gb / (dec / steps), 1),
+                ratio=round(4.0 * n * steps / total_blob, 3),
+                restore_ms_one_call_per_blob=round(1e3 * t_seq, 3), restore_ms_fused=round(1e3 * t_many, 3),
+                fused_speedup=round(t_seq / t_many, 3), restored_equals_tracked=same_seq and same_many)
+
+
 def traffic_from_profiles(kernel, workload):
     """HBM bytes per launch measured with rocprofv3 --pmc, if a summary for this kernel/workload is committed."""
     path = os.path.join(ROOT, "profiles", "%s_%s_pmc.txt" % (kernel, workload))
@@ -168,6 +209,7 @@ def main():
     ap.add_argument("--workload", default="vgg16")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--chain-steps", type=int, default=32, help="checkpoints in the config-4 chain leg (0 = skip)")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain elementwise copy kernel of known size (553,430,176 bytes read and "
                          "written per launch): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -218,6 +260,9 @@ def main():
             also[name]["n"] = j.n
             also[name]["nbits"] = j.nbits
             del j
+            torch.cuda.empty_cache()
+        if args.chain_steps > 0:
+            also["gpt2_medium_chain"] = chain_leg(dev, args.chain_steps)
             torch.cuda.empty_cache()
 
     line = {

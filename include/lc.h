@@ -86,6 +86,7 @@ enum lc_status {
 
 #define LC_MAX_N (1ull << 32)    /* largest n per call; larger vectors are sliced by the caller */
 #define LC_CHUNK 16384u
+#define LC_MAX_MANY 64           /* most blobs one lc_decode_many call accepts */
 
 /*
  * Worst-case blob size in bytes for (n, nbits); host only, no GPU needed.  An optimal
@@ -141,6 +142,19 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
  * the bytes consumed or -(lc_status).
  */
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
+
+/*
+ * Restore from several checkpoints at once (Section 3, C1: u_t = u_0 + the sum of the decoded
+ * deltas; Section 3.2, checkpoint merging): applies blobs[0], blobs[1], ... blobs[count-1] to
+ * w_ref in this order.  The result is bit for bit what `count` successive lc_decode calls
+ * give (one fp32 add per blob and element, in blob order), but w_ref is read and written
+ * once per 8 blobs instead of once per blob.
+ *   blobs  HOST array of `count` DEVICE pointers to LCB1 blobs (16-byte aligned), each with
+ *          header n equal to `n`; 1 <= count <= LC_MAX_MANY
+ * Every blob is validated as in lc_decode before w_ref is touched.  Waits for `stream`;
+ * returns the sum of the bytes consumed or -(lc_status).
+ */
+lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream);
 
 /*
  * Parse a header that the caller copied to HOST memory (at least 64 bytes).  Any

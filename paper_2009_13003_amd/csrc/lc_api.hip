@@ -25,7 +25,7 @@ struct DeviceState {
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
-struct Landing { Result result; unsigned long long dec_status; unsigned long long pad; };
+struct Landing { Result result; unsigned long long dec_status; unsigned long long pad; unsigned long long bytes[LC_MAX_MANY]; };
 Landing* g_pinned = nullptr;     // pinned host landing area for the result read-back
 uint64_t g_epoch = 0;            // tags the decode status word of each call
 
@@ -35,7 +35,7 @@ uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
 const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize",
-                                           "k_dec_check", "k_decode"};
+                                           "k_dec_check", "k_decode", "k_decode_many"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
     const char* v = getenv(name);
@@ -75,6 +75,7 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
         ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
         ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
+        ds.tune.many_blocks_per_cu = env_int("LC_TUNE_MANY_BLOCKS_PER_CU", ds.tune.many_blocks_per_cu, 1, 64);
         ds.tuned = true;
     }
     if (!g_pinned) {
@@ -166,16 +167,53 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     const uint64_t epoch = ++g_epoch;
-    { Timed t(kSlotDecCheck, s); launch_dec_check(b, n, lc_encode_bound(n, 4), ws, epoch, s); }
+    { Timed t(kSlotDecCheck, s); launch_dec_check(b, n, lc_encode_bound(n, 4), ws, epoch, 0, s); }
     { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, ds->tune, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(&g_pinned->result, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipMemcpyAsync(&g_pinned->bytes[0], &ws->dec_bytes[0], sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
     const int slots[] = {kSlotDecCheck, kSlotDecode};
     collect(slots, 2);
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
-    return (lc_ssize)g_pinned->result.bytes;
+    return (lc_ssize)g_pinned->bytes[0];
+}
+
+lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream) {
+    if (!blobs || count < 1 || count > LC_MAX_MANY || n > LC_MAX_N) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    for (int i = 0; i < count; ++i) if (!blobs[i] || misaligned(blobs[i], 16)) return -LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int err = 0; DeviceState* ds = nullptr;
+    Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
+    if (!ws) return -(lc_ssize)err;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t epoch = ++g_epoch, bound = lc_encode_bound(n, 4);
+    if (count > kMaxMany) {
+        // more than one sweep: validate every blob first, so that a bad one leaves w_ref untouched
+        for (int i = 0; i < count; ++i) launch_dec_check(static_cast<const uint8_t*>(blobs[i]), n, bound, ws, epoch, i % kMaxMany, s);
+        LC_HIP(hipGetLastError());
+        LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+        LC_HIP(hipStreamSynchronize(s));
+        if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
+    }
+    for (int g0 = 0; g0 < count; g0 += kMaxMany) {
+        const int T = count - g0 < kMaxMany ? count - g0 : kMaxMany;
+        BlobList list;
+        for (int t = 0; t < kMaxMany; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[g0 + (t < T ? t : 0)]);
+        for (int t = 0; t < T; ++t) { Timed tm(kSlotDecCheck, s); launch_dec_check(list.p[t], n, bound, ws, epoch, t, s); }
+        { Timed tm(kSlotDecodeMany, s); launch_decode_many(list, T, w_ref, n, ws, epoch, ds->tune, s); }
+        LC_HIP(hipGetLastError());
+        LC_HIP(hipMemcpyAsync(&g_pinned->bytes[g0], &ws->dec_bytes[0], T * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    }
+    LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    LC_HIP(hipStreamSynchronize(s));
+    const int slots[] = {kSlotDecCheck, kSlotDecodeMany};
+    collect(slots, 2);
+    if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
+    uint64_t total = 0;
+    for (int i = 0; i < count; ++i) total += g_pinned->bytes[i];
+    return (lc_ssize)total;
 }
 
 int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status) {

@@ -38,6 +38,15 @@ struct DecInfo {
     uint32_t len[kMaxSym], code[kMaxSym];
 };
 
+constexpr int kMaxMany = 8;  // blobs one fused restore sweep can apply
+
+// Everything the decode sweep needs to know about one blob, written by k_dec_check.
+struct DecSet {
+    DecInfo info;
+    alignas(16) uint8_t lut1[1u << kDecLut1Bits];   // symbol | len << 4 over the next 7 bits
+    alignas(16) uint8_t lut2[1u << kDecLut2Bits];   // ... over the next 12 bits
+};
+
 struct Result {              // copied to pinned host memory at the end of a call
     uint64_t bytes;
     uint32_t status;
@@ -55,10 +64,9 @@ struct Workspace {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
-    DecInfo dec;
     Result result;
-    alignas(16) uint8_t dec_lut1[1u << kDecLut1Bits];   // symbol | len << 4 over the next 7 bits
-    alignas(16) uint8_t dec_lut2[1u << kDecLut2Bits];   // ... over the next 12 bits
+    unsigned long long dec_bytes[kMaxMany];   // total_bytes of the blob checked into each set
+    DecSet dec_set[kMaxMany];
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
@@ -70,7 +78,7 @@ __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsW
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
 enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize,
-            kSlotDecCheck, kSlotDecode, kNumSlots };
+            kSlotDecCheck, kSlotDecode, kSlotDecodeMany, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
 // variables (read once) for sweeps.
@@ -80,6 +88,7 @@ struct Tuning {
     int hist_threads = 256;
     int pack_waves_per_cu = 6;
     int decode_blocks_per_cu = 4;
+    int many_blocks_per_cu = 2;
 };
 
 // Launchers (lc_kernels.hip).
@@ -91,8 +100,12 @@ void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, 
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStream_t s);
-void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, hipStream_t s);
+struct BlobList { const uint8_t* p[kMaxMany]; };
+void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
+                      hipStream_t s);
 void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
                    const Tuning& tune, hipStream_t s);
+void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                        const Tuning& tune, hipStream_t s);
 
 }  // namespace lc

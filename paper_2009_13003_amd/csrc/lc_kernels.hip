@@ -561,7 +561,7 @@ __device__ __forceinline__ void raise_status(Workspace* ws, u64 epoch, u32 statu
 }
 
 __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u64 max_total, Workspace* ws,
-                                                   u32 nchunks, u64 epoch) {
+                                                   u32 nchunks, u64 epoch, u32 set) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     __shared__ u32 s_ok, s_K, s_max_len;
     __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
         if (blockIdx.x == 0 && t == 0) {
             const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 && hn != n;
             raise_status(ws, epoch, n_mismatch ? 1u : 4u);
-            ws->result.bytes = 0;
+            ws->dec_bytes[set] = 0;
         }
         return;
     }
@@ -596,6 +596,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
     }
     if (blockIdx.x != 0) return;
     // ---- workgroup 0: symbol table, codes, look-up table
+    DecSet& D = ws->dec_set[set];
     if (t == 0) {
         const u32 nbits = hdr[4], K = hdr[5];
         bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
@@ -603,7 +604,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
         u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
         u32 per_len[17];
         for (int L = 0; L <= 16; ++L) per_len[L] = 0;
-        for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; ws->dec.rep_bits[j] = 0; }
+        for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; }
         if (ok) {
             for (u32 j = 0; j <= K; ++j) {
                 const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
                 if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
                 if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
                 if (j == K && rep != 0) ok = false;
-                s_len[j] = len; ws->dec.rep_bits[j] = rep;
+                s_len[j] = len; D.info.rep_bits[j] = rep;
                 if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
             }
             if (cnt_sum != n) ok = false;
@@ -625,12 +626,12 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
             for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
             for (u32 j = 0; j < kMaxSym; ++j) {
                 s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
-                ws->dec.len[j] = s_len[j]; ws->dec.code[j] = s_code[j];
+                D.info.len[j] = s_len[j]; D.info.code[j] = s_code[j];
             }
         } else raise_status(ws, epoch, 4u);
-        ws->dec.K = K; ws->dec.max_len = max_len;
-        ws->dec.area = area; ws->dec.total_words = tw;
-        ws->result.bytes = total;
+        D.info.K = K; D.info.max_len = max_len;
+        D.info.area = area; D.info.total_words = tw;
+        ws->dec_bytes[set] = total;
         s_ok = ok; s_K = K; s_max_len = max_len;
     }
     __syncthreads();
@@ -643,7 +644,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
     const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
     for (u32 pass = 0; pass < 2; ++pass) {
         const u32 P = pass ? P2 : P1;
-        uint8_t* lut = pass ? ws->dec_lut2 : ws->dec_lut1;
+        uint8_t* lut = pass ? D.lut2 : D.lut1;
         if (pass && M <= kDecLut1Bits) break;
         for (u32 i = t; i < (1u << P); i += 256) {
             u32 entry = K;
@@ -790,22 +791,23 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
     __shared__ DecLds L;
     if ((ws->dec_status >> 8) == epoch) return;          // the check kernel found something: touch nothing
     const u32 t = threadIdx.x;
-    const u32 M = ws->dec.max_len, K = ws->dec.K;
+    const DecSet& D = ws->dec_set[0];
+    const u32 M = D.info.max_len, K = D.info.K;
     const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-    const u64 area = ws->dec.area;
-    if (t < (1u << P1)) L.lut1[t] = ws->dec_lut1[t];
+    const u64 area = D.info.area;
+    if (t < (1u << P1)) L.lut1[t] = D.lut1[t];
     if (M > kDecLut1Bits) {
         if ((1u << P2) >= 4096) {
-            const uint4* src = reinterpret_cast<const uint4*>(ws->dec_lut2);
+            const uint4* src = reinterpret_cast<const uint4*>(D.lut2);
             uint4* dst = reinterpret_cast<uint4*>(L.lut2);
             for (u32 i = t; i < (1u << P2) / 16; i += 256) dst[i] = src[i];
         } else {
-            for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = ws->dec_lut2[i];
+            for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = D.lut2[i];
         }
     }
     if (t < kMaxSym) {
-        L.rep[t] = __uint_as_float(t < K ? ws->dec.rep_bits[t] : 0x80000000u);
-        L.len[t] = ws->dec.len[t]; L.code[t] = ws->dec.code[t];
+        L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
+        L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
     }
     __syncthreads();
     const u32 wave = t >> 6;
@@ -817,6 +819,118 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         } else {
             decode_chunk<false, true>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
         }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_decode_many
+// Restore from several checkpoints in one sweep (Section 3, C1: u_t = u_0 + sum of the decoded
+// deltas; Section 3.2, checkpoint merging): up to kMaxMany blobs of the same n are decoded side
+// by side and their values added to w_ref in blob order, one fp32 add per blob and element, so
+// the result equals that of applying the blobs one call after the other, with one read and
+// one write of w_ref instead of one per blob.  Lane strings are read straight from memory.
+struct ManyLds {
+    uint8_t lut1[kMaxMany][1u << kDecLut1Bits];
+    uint8_t lut2[kMaxMany][1u << kDecLut2Bits];
+    float rep[kMaxMany][kMaxSym];
+    u32 len[kMaxMany][kMaxSym], code[kMaxMany][kMaxSym];
+    u32 K[kMaxMany], P1[kMaxMany], P2[kMaxMany];
+    u64 area[kMaxMany];
+};
+
+__device__ __noinline__ u32 decode_long_many(const ManyLds& L, u32 t, u64 win) {
+    const u32 peek = (u32)(win >> (64 - 15)), K = L.K[t];
+    for (u32 j = 0; j <= K; ++j) {
+        const u32 l = L.len[t][j];
+        if (l > kDecLut2Bits && (peek >> (15 - l)) == L.code[t][j]) return j | (l << 4);
+    }
+    return K;
+}
+
+template <bool FAST>
+__device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, float* __restrict__ w_ref, u64 n,
+                                                  Workspace* ws, u32 c, const ManyLds& L, u64 epoch) {
+    const u32 lane = lane_id();
+    BitReader<false> br[kMaxMany];
+    u32 wi0[kMaxMany], avail0[kMaxMany], lane_bits[kMaxMany];
+#pragma unroll
+    for (int t = 0; t < kMaxMany; ++t) {
+        if ((u32)t < T) {
+            const uint8_t* blob = blobs.p[t];
+            const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+            const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
+            const uint8_t* rec = blob + L.area[t] + 4 * (u64)o0;
+            lane_bits[t] = reinterpret_cast<const uint16_t*>(rec)[lane];
+            const u32 o = wave_incl_scan(lane_bits[t]) - lane_bits[t];
+            br[t].start(reinterpret_cast<const u32*>(rec + 2 * kW), o1 - o0 - kLaneBitsWords, o);
+            wi0[t] = br[t].wi; avail0[t] = br[t].avail;
+        }
+    }
+    const u64 base = (u64)c * kChunk;
+#pragma unroll 2
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        if (!FAST && idx >= n) break;
+        float x[4];
+        load_row<FAST>(w_ref, idx, n, x);
+        u32 kept = 0;
+#pragma unroll
+        for (int t = 0; t < kMaxMany; ++t) {
+            if ((u32)t < T) {
+                const u32 shr1 = 64 - L.P1[t], shr2 = 64 - L.P2[t], K = L.K[t];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (FAST || idx + v < n) {
+                        u32 e = L.lut1[t][(u32)(br[t].win >> shr1)];
+                        if (e == 0xFF) {
+                            e = L.lut2[t][(u32)(br[t].win >> shr2)];
+                            if (e == 0xFF) e = decode_long_many(L, t, br[t].win);
+                        }
+                        const u32 len = e >> 4, sy = e & 15;
+                        br[t].win <<= len; br[t].avail -= len;
+                        kept |= K - sy;
+                        x[v] = __fadd_rn(x[v], L.rep[t][sy]);
+                    }
+                    if ((v & 1) && br[t].avail <= 32) br[t].refill();
+                }
+            }
+        }
+        if (FAST) {
+            if (__any(kept != 0)) *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
+        }
+    }
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < kMaxMany; ++t)
+        if ((u32)t < T) bad = bad || (avail0[t] + 32 * (br[t].wi - wi0[t]) - br[t].avail != lane_bits[t]);
+    if (__any(bad) && lane == 0) raise_status(ws, epoch, 4u);
+}
+
+__global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 T, float* __restrict__ w_ref, u64 n,
+                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch) {
+    __shared__ ManyLds L;
+    if ((ws->dec_status >> 8) == epoch) return;          // a check found something: touch nothing
+    const u32 tid = threadIdx.x;
+    for (u32 t = 0; t < T; ++t) {
+        const DecSet& D = ws->dec_set[t];
+        const u32 M = D.info.max_len, K = D.info.K;
+        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+        if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
+        if (M > kDecLut1Bits) for (u32 i = tid; i < (1u << P2); i += 256) L.lut2[t][i] = D.lut2[i];
+        if (tid < kMaxSym) {
+            L.rep[t][tid] = __uint_as_float(tid < K ? D.info.rep_bits[tid] : 0x80000000u);
+            L.len[t][tid] = D.info.len[tid]; L.code[t][tid] = D.info.code[tid];
+        }
+        if (tid == 0) { L.K[t] = K; L.P1[t] = P1; L.P2[t] = P2; L.area[t] = D.info.area; }
+    }
+    __syncthreads();
+    const u32 wave = tid >> 6;
+    for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+        const bool full = (u64)(c + 1) * kChunk <= n;
+        if (full && aligned) decode_many_chunk<true>(blobs, T, w_ref, n, ws, c, L, epoch);
+        else decode_many_chunk<false>(blobs, T, w_ref, n, ws, c, L, epoch);
     }
 }
 
@@ -865,10 +979,23 @@ void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStre
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(128), 0, s, out, ws, (u64)n, nbits, (u32)num_chunks_of(n));
 }
 
-void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, hipStream_t s) {
+void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
+                      hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
-    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws, (u32)nchunks, (u64)epoch);
+    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws, (u32)nchunks,
+                       (u64)epoch, (u32)set);
+}
+
+void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                        const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (nchunks + 3) / 4;
+    const u64 cap = (u64)tune.num_cu * tune.many_blocks_per_cu;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)count, w_ref, (u64)n, ws,
+                       (u32)nchunks, (int)aligned16(w_ref), (u64)epoch);
 }
 
 void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,

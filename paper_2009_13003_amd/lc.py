@@ -17,6 +17,7 @@ _lib = ctypes.CDLL(_PATH)
 
 OK, ERR_BADARG, ERR_NONFINITE, ERR_OUT_TOO_SMALL, ERR_BAD_BLOB, ERR_HIP, ERR_WORKSPACE = range(7)
 MAX_N = 1 << 32
+MAX_MANY = 64
 CHUNK = 16384
 
 _u64, _i64, _int, _vp, _sz = ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
@@ -30,6 +31,8 @@ _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
 _lib.lc_decode.restype = _i64
 _lib.lc_decode.argtypes = [_vp, _vp, _u64, _vp]
+_lib.lc_decode_many.restype = _i64
+_lib.lc_decode_many.argtypes = [ctypes.POINTER(_vp), _int, _vp, _u64, _vp]
 _lib.lc_blob_info.restype = _int
 _lib.lc_blob_info.argtypes = [_vp, ctypes.POINTER(_u64), ctypes.POINTER(_int), ctypes.POINTER(_u64), ctypes.POINTER(_int)]
 _lib.lc_shutdown.restype = None
@@ -97,6 +100,18 @@ def lc_decode(blob, w_ref, stream=None, n=None):
     n = w_ref.numel() if n is None else n
     assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
     r = int(_lib.lc_decode(ctypes.c_void_p(blob.data_ptr()), _dev_f32(w_ref), n, _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_decode_many(blobs, w_ref, stream=None, n=None):
+    """Applies the blobs (a list of CUDA uint8 tensors) to w_ref in order; returns the bytes consumed."""
+    n = w_ref.numel() if n is None else n
+    for b in blobs:
+        assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
+    ptrs = (_vp * len(blobs))(*[b.data_ptr() for b in blobs])
+    r = int(_lib.lc_decode_many(ptrs, len(blobs), _dev_f32(w_ref), n, _stream(stream)))
     if r < 0:
         raise LcError(-r)
     return r

@@ -268,3 +268,68 @@ def test_checkpoint_chain_small(lc):
     for b in blobs:
         lc.lc_decode(b, restored)
     assert torch.equal(restored.view(torch.int32), tracked.view(torch.int32))
+
+
+def make_chain(lc, n, steps, seed, nbits=3):
+    """`steps` checkpoints of a drifting vector, each encoded against the recovered state (Algorithm 1)."""
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    w = 0.05 * torch.randn(n, generator=g, device=DEV)
+    w0 = w.clone(); tracked = w.clone()
+    d = torch.zeros(n, device=DEV)
+    out = lc.alloc_out(n, nbits, DEV)
+    blobs = []
+    for t in range(steps):
+        u = torch.rand(n, generator=g, device=DEV) - 0.5
+        d = 0.9 * d - 5e-5 * (1 + t % 3) * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
+        w = w + d
+        size = lc.lc_encode(w, tracked, nbits, out)
+        blobs.append(out[:size].clone())
+        lc.lc_decode(blobs[-1], tracked)
+    return w0, tracked, blobs
+
+
+@pytest.mark.parametrize("steps", [1, 2, 3, 8, 9, 17])
+def test_fused_restore_equals_successive_restores(lc, steps):
+    """Section 3 (C1): restoring from u_0 and all the blobs at once gives, bit for bit, what the oracle gives
+    applying them one after the other."""
+    n = 7 * 16384 + 4321
+    w0, tracked, blobs = make_chain(lc, n, steps, seed=steps, nbits=3 + steps % 2)
+    restored = w0.clone()
+    consumed = lc.lc_decode_many(blobs, restored)
+    assert consumed == sum(b.numel() for b in blobs)
+    ref = w0.cpu().numpy()
+    for b in blobs:
+        orc.decode(b.cpu().numpy(), ref)
+    assert np.array_equal(bits(restored.cpu().numpy()), bits(ref))
+    assert torch.equal(restored.view(torch.int32), tracked.view(torch.int32))
+
+
+def test_fused_restore_edge_cases(lc):
+    # unaligned w_ref, tiny and empty vectors
+    for n in (0, 5, 300, 16384 + 1):
+        w0, tracked, blobs = make_chain(lc, n, 3, seed=n)
+        buf = torch.zeros(n + 4, device=DEV)
+        view = buf[1:1 + n]
+        view.copy_(w0)
+        lc.lc_decode_many(blobs, view)
+        assert torch.equal(view.view(torch.int32), tracked.view(torch.int32)), n
+    # a damaged blob anywhere in the list: error, w_ref untouched (also across more than one sweep)
+    n = 3 * 16384 + 77
+    w0, tracked, blobs = make_chain(lc, n, 11, seed=5)
+    for bad_at in (0, 4, 10):
+        damaged = [b.clone() for b in blobs]
+        damaged[bad_at][512 + 4] ^= 1
+        rec = w0.clone()
+        with pytest.raises(lc.LcError) as e:
+            lc.lc_decode_many(damaged, rec)
+        assert e.value.status == lc.ERR_BAD_BLOB
+        assert torch.equal(rec.view(torch.int32), w0.view(torch.int32))
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many(blobs, w0.clone()[:n - 1])
+    assert e.value.status == lc.ERR_BADARG
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many(blobs * 6, w0.clone())             # 66 > LC_MAX_MANY
+    assert e.value.status == lc.ERR_BADARG
+    rec = w0.clone()
+    lc.lc_decode_many(blobs, rec)
+    assert torch.equal(rec.view(torch.int32), tracked.view(torch.int32))
