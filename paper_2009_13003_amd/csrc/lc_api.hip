@@ -21,12 +21,14 @@ struct DeviceState {
     size_t user_bytes = 0;
     Tuning tune;
     bool tuned = false;
+    const void* clean = nullptr;  // scratch area whose encode state is known to be cleared
 };
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
-struct Landing { Result result; unsigned long long dec_status; unsigned long long pad; unsigned long long bytes[LC_MAX_MANY]; };
-Landing* g_pinned = nullptr;     // pinned host landing area for the result read-back
+static_assert(sizeof(((HostResult*)0)->bytes) / sizeof(unsigned long long) >= LC_MAX_MANY, "HostResult too small");
+HostResult* g_pinned = nullptr;  // mapped pinned host memory the kernels write their outcome to
+HostResult* g_pinned_dev = nullptr;   // the same memory as the device sees it
 uint64_t g_epoch = 0;            // tags the decode status word of each call
 
 bool g_prof = false;
@@ -79,9 +81,13 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         ds.tuned = true;
     }
     if (!g_pinned) {
-        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(Landing), hipHostMallocDefault) != hipSuccess) {
-            (void)hipGetLastError(); g_pinned = nullptr; *err = LC_ERR_HIP; return nullptr;
+        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(HostResult), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess ||
+            hipHostGetDevicePointer(reinterpret_cast<void**>(&g_pinned_dev), g_pinned, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            if (g_pinned) (void)hipHostFree(g_pinned);
+            g_pinned = nullptr; *err = LC_ERR_HIP; return nullptr;
         }
+        memset(g_pinned, 0, sizeof(HostResult));
     }
     *ds_out = &ds;
     if (ds.user) {
@@ -92,8 +98,9 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         if (ds.owned) { (void)hipDeviceSynchronize(); (void)hipFree(ds.owned); ds.owned = nullptr; ds.owned_bytes = 0; }
         size_t want = need < (1u << 20) ? (1u << 20) : need;
         if (hipMalloc(&ds.owned, want) != hipSuccess) { (void)hipGetLastError(); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
-        if (hipMemset(ds.owned, 0, kWorkspaceFixed) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(ds.owned); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        if (hipMemset(ds.owned, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(ds.owned); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
         ds.owned_bytes = want;
+        ds.clean = nullptr;      // new memory (possibly at the old address): its encode state is not set up yet
     }
     return static_cast<Workspace*>(ds.owned);
 }
@@ -113,18 +120,18 @@ size_t lc_encode_bound(uint64_t n, int nbits) {
 size_t lc_workspace_bytes(uint64_t n, int nbits) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
     const uint64_t nc = num_chunks_of(n);
-    return kWorkspaceFixed + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)((4 * ((nc + 63) / 64) + 255) / 256 * 256) +
-           (size_t)(nc * slot_words_of(nbits) * 4);
+    return kWorkspaceHead + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)(nc * slot_words_of(nbits) * 4);
 }
 
 int lc_set_workspace(void* dev_ws, size_t bytes) {
     std::lock_guard<std::mutex> lock(g_mu);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
-    if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceFixed)) return LC_ERR_WORKSPACE;
-    if (dev_ws && hipMemset(dev_ws, 0, kWorkspaceFixed) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceHead)) return LC_ERR_WORKSPACE;
+    if (dev_ws && hipMemset(dev_ws, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
     g_dev[dev].user = dev_ws;
     g_dev[dev].user_bytes = dev_ws ? bytes : 0;
+    g_dev[dev].clean = nullptr;
     return LC_OK;
 }
 
@@ -136,25 +143,28 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, vo
     Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint32_t* chunk_bits = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
+    uint32_t* group_words = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
+    uint32_t* chunk_bits = group_words + kMaxGroups;
     const uint64_t nc = num_chunks_of(n);
-    uint32_t* group_words = chunk_bits + (nc + 63) / 64 * 64;
-    uint32_t* prov = group_words + ((nc + 63) / 64 + 63) / 64 * 64;
+    uint32_t* prov = chunk_bits + (nc + 63) / 64 * 64;
     const uint32_t slot_words = slot_words_of(nbits);
     uint8_t* o = static_cast<uint8_t*>(out);
-    { Timed t(kSlotReset, s);    launch_reset(ws, group_words, nc, s); }
+    // Every call leaves the encode state cleared behind it; a fresh scratch area, or one whose last
+    // call did not run to its end, is cleared first.
+    if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, s); }
+    ds->clean = nullptr;
     { Timed t(kSlotHist, s);     launch_hist(w, w_ref, n, ws, ds->tune, s); }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, s); }
     { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, n, nbits, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, &g_pinned_dev->enc, group_words, n, nbits, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(&g_pinned->result, &ws->result, sizeof(Result), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
-    const int slots[] = {kSlotReset, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize};
-    collect(slots, 6);
-    if (g_pinned->result.status != LC_OK) return -(lc_ssize)g_pinned->result.status;
-    return (lc_ssize)g_pinned->result.bytes;
+    ds->clean = ws;
+    const int slots[] = {kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize};
+    collect(slots, 5);
+    if (g_pinned->enc.status != LC_OK) return -(lc_ssize)g_pinned->enc.status;
+    return (lc_ssize)g_pinned->enc.bytes;
 }
 
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
@@ -167,11 +177,9 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     const uint64_t epoch = ++g_epoch;
-    { Timed t(kSlotDecCheck, s); launch_dec_check(b, n, lc_encode_bound(n, 4), ws, epoch, 0, s); }
-    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, ds->tune, s); }
+    { Timed t(kSlotDecCheck, s); launch_dec_check(b, n, lc_encode_bound(n, 4), ws, epoch, 0, g_pinned_dev, 0, s); }
+    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, g_pinned_dev, ds->tune, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipMemcpyAsync(&g_pinned->bytes[0], &ws->dec_bytes[0], sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
-    LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
     const int slots[] = {kSlotDecCheck, kSlotDecode};
     collect(slots, 2);
@@ -191,9 +199,9 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     const uint64_t epoch = ++g_epoch, bound = lc_encode_bound(n, 4);
     if (count > kMaxMany) {
         // more than one sweep: validate every blob first, so that a bad one leaves w_ref untouched
-        for (int i = 0; i < count; ++i) launch_dec_check(static_cast<const uint8_t*>(blobs[i]), n, bound, ws, epoch, i % kMaxMany, s);
+        for (int i = 0; i < count; ++i)
+            launch_dec_check(static_cast<const uint8_t*>(blobs[i]), n, bound, ws, epoch, i % kMaxMany, g_pinned_dev, i, s);
         LC_HIP(hipGetLastError());
-        LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
         LC_HIP(hipStreamSynchronize(s));
         if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     }
@@ -201,12 +209,10 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
         const int T = count - g0 < kMaxMany ? count - g0 : kMaxMany;
         BlobList list;
         for (int t = 0; t < kMaxMany; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[g0 + (t < T ? t : 0)]);
-        for (int t = 0; t < T; ++t) { Timed tm(kSlotDecCheck, s); launch_dec_check(list.p[t], n, bound, ws, epoch, t, s); }
-        { Timed tm(kSlotDecodeMany, s); launch_decode_many(list, T, w_ref, n, ws, epoch, ds->tune, s); }
+        for (int t = 0; t < T; ++t) { Timed tm(kSlotDecCheck, s); launch_dec_check(list.p[t], n, bound, ws, epoch, t, g_pinned_dev, g0 + t, s); }
+        { Timed tm(kSlotDecodeMany, s); launch_decode_many(list, T, w_ref, n, ws, epoch, g_pinned_dev, ds->tune, s); }
         LC_HIP(hipGetLastError());
-        LC_HIP(hipMemcpyAsync(&g_pinned->bytes[g0], &ws->dec_bytes[0], T * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     }
-    LC_HIP(hipMemcpyAsync(&g_pinned->dec_status, &ws->dec_status, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     LC_HIP(hipStreamSynchronize(s));
     const int slots[] = {kSlotDecCheck, kSlotDecodeMany};
     collect(slots, 2);
@@ -241,7 +247,8 @@ void lc_shutdown(void) {
         g_dev[d].user = nullptr; g_dev[d].user_bytes = 0;
     }
     if (have_cur) (void)hipSetDevice(cur);
-    if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; }
+    if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; g_pinned_dev = nullptr; }
+    for (int d = 0; d < kMaxDevices; ++d) g_dev[d].clean = nullptr;
     if (g_ev_made) {
         for (int i = 0; i < kNumSlots; ++i) { (void)hipEventDestroy(g_ev[i][0]); (void)hipEventDestroy(g_ev[i][1]); }
         g_ev_made = false; g_prof = false;

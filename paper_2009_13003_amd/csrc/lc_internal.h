@@ -47,15 +47,23 @@ struct DecSet {
     alignas(16) uint8_t lut2[1u << kDecLut2Bits];   // ... over the next 12 bits
 };
 
-struct Result {              // copied to pinned host memory at the end of a call
+struct Result {
     uint64_t bytes;
     uint32_t status;
     uint32_t pad;
 };
 
-// Fixed part of the per-device scratch.  It is followed by chunk_bits[num_chunks] and
-// group_words[ceil(num_chunks / 64)] (u32, each padded to 256 bytes) and by one slot of
-// slot_words_of(nbits) 32-bit words per chunk.
+// Lives in mapped, pinned host memory: kernels write the outcome of a call here with plain
+// stores, and the host reads it after waiting for the stream.
+struct HostResult {
+    Result enc;                                  // lc_encode: blob bytes, lc_status
+    unsigned long long dec_status;               // lc_decode*: (epoch << 8) | lc_status of the worst finding
+    unsigned long long bytes[64];                // lc_decode*: total_bytes of each blob
+};
+
+// Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] (u32, at a
+// fixed place so that it can be left cleared from one call to the next), chunk_bits[num_chunks]
+// (u32, padded to 256 bytes) and one slot of slot_words_of(nbits) 32-bit words per chunk.
 struct Workspace {
     unsigned long long hist[512];
     uint32_t mmin[kMaxSym];
@@ -64,12 +72,13 @@ struct Workspace {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
-    Result result;
     unsigned long long dec_bytes[kMaxMany];   // total_bytes of the blob checked into each set
     DecSet dec_set[kMaxMany];
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
+constexpr uint32_t kMaxGroups = 4096;       // 2^32 elements / 16384 per chunk / 64 chunks per group
+constexpr size_t kWorkspaceHead = kWorkspaceFixed + 4 * kMaxGroups;   // fixed part + group_words
 
 __host__ __device__ inline uint64_t num_chunks_of(uint64_t n) { return (n + kChunk - 1) / kChunk; }
 // Slot of one chunk in the scratch area: 64 lane lengths (u16), then up to 8 * max_len words
@@ -92,20 +101,21 @@ struct Tuning {
 };
 
 // Launchers (lc_kernels.hip).
-void launch_reset(Workspace* ws, uint32_t* group_words, uint64_t nchunks, hipStream_t s);
+void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s);
 void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s);
 void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
                  uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
-void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStream_t s);
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint64_t n, int nbits,
+                     hipStream_t s);
 struct BlobList { const uint8_t* p[kMaxMany]; };
 void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
-                      hipStream_t s);
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                      HostResult* host, int host_slot, hipStream_t s);
+void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s);
-void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
-                        const Tuning& tune, hipStream_t s);
+void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws,
+                        uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s);
 
 }  // namespace lc

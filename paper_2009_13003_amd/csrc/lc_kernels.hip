@@ -1,6 +1,7 @@
 // HIP kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64).
 //
-// encode:  k_reset -> k_hist -> k_table -> k_pack -> k_place -> k_finalize
+// encode:  k_hist -> k_table -> k_pack -> k_place -> k_finalize (which also clears the scratch state
+//          for the next call); k_reset only for a fresh scratch area
 // decode:  k_dec_check -> k_decode (gated on the check's verdict, no host round trip between)
 //
 // The paper (arXiv 2009.13003) defines what is computed: delta against the last
@@ -63,11 +64,18 @@ __device__ __forceinline__ void load_row(const float* __restrict__ p, u64 idx, u
 }
 
 // ----------------------------------------------------------------------------- k_reset
+// Brings the scratch state to what every encode call expects to find (and leaves behind):
+// zero bucket counts, empty extremes, zero group sums and arrival counters.  Only launched
+// for a fresh scratch area or after a call that did not run to its end.
+__device__ __forceinline__ void clear_encode_state(Workspace* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
+    for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
+    for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
+    if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
+    if (tid == 0) ws->total_words = 0;
+}
+
 __global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups) {
-    for (u32 i = threadIdx.x; i < ngroups; i += blockDim.x) group_words[i] = 0;
-    for (u32 i = threadIdx.x; i < 512; i += blockDim.x) ws->hist[i] = 0;
-    if (threadIdx.x < kMaxSym) { ws->mmin[threadIdx.x] = 0x7FFFFFu; ws->mmax[threadIdx.x] = 0; }
-    if (threadIdx.x == 0) { ws->total_words = 0; ws->table.status = 0; }
+    clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
 }
 
 // ----------------------------------------------------------------------------- k_hist
@@ -137,57 +145,58 @@ __global__ __launch_bounds__(1024) void k_hist(const float* __restrict__ w, cons
 }
 
 // ----------------------------------------------------------------------------- k_table
-// Priority promotion (Section 3.1.1) and the Huffman table (Section 3.1.2), one
-// workgroup of 512 threads, thread t looking at the bucket of priority rank t
-// (exponent descending, + before -).
-__global__ __launch_bounds__(512) void k_table(Workspace* ws, u64 n, int nbits) {
-    __shared__ u32 wave_tot[8];
-    __shared__ u32 flag_nonfinite, flag_zero;
-    __shared__ uint8_t s_sym[512];
-    __shared__ u64 s_cnt[kMaxSym];
-    __shared__ u32 s_kept[kMaxSym], s_len[kMaxSym + 1], s_code[kMaxSym];
-    // Huffman scratch (thread 0 only)
-    __shared__ u32 leaf[kMaxSym], left[kMaxSym], right[kMaxSym], depth[kMaxSym];
-    __shared__ u64 node_w[kMaxSym];
+// Priority promotion (Section 3.1.1) and the Huffman table (Section 3.1.2), one wavefront.  Lane l looks at one exponent level (both signs) per step, from
+// the largest exponent down; a ballot/popcount scan ranks the non-empty buckets (+ before - at
+// equal exponent).  Lane 0 then builds the code lengths with two queues and the canonical codes
+// with per-length counters.
+struct TableLds {
+    uint8_t sym[512];
+    u64 cnt[kMaxSym + 1];
+    u32 kept[kMaxSym], len[kMaxSym + 1], code[kMaxSym + 1];
+    u32 leaf[kMaxSym], left[kMaxSym], right[kMaxSym], depth[kMaxSym];
+    u64 node_w[kMaxSym];
+};
 
-    const u32 t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    const u32 E = 255 - (t >> 1), sgn = t & 1, b = (sgn << 8) | E;
-    const u64 c = ws->hist[b];
-    const bool cand = c > 0 && E >= 1 && E <= 254;
-    const u64 m = __ballot(cand);
-    const u32 within = __popcll(m & ((1ull << lane) - 1));
-    if (lane == 0) wave_tot[wv] = __popcll(m);
-    if (t == 0) { flag_nonfinite = 0; flag_zero = 0; }
-    if (t < kMaxSym) { s_cnt[t] = 0; s_kept[t] = 0; s_len[t] = 0; s_code[t] = 0; }
-    __syncthreads();
-    if (E == 255 && c > 0) flag_nonfinite = 1;
-    if (E == 0 && c > 0) flag_zero = 1;
-    u32 before = 0, total = 0;
-    for (u32 i = 0; i < 8; ++i) { if (i < wv) before += wave_tot[i]; total += wave_tot[i]; }
-    const u32 rank = before + within;
+__global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits) {
+    __shared__ TableLds S;
+    const u32 lane = lane_id();
+    const bool active = threadIdx.x < kW;
     const u32 kmax = (1u << nbits) - 1;
+    if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; S.code[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
+    u32 total = 0;
+    bool nonfinite = false, zero_class = false;
+    for (u32 step = 0; active && step < 4; ++step) {
+        const u32 E = 255 - (step * kW + lane);
+        const u64 c0 = ws->hist[E], c1 = ws->hist[256 + E];
+        const bool normal = E >= 1 && E <= 254;
+        const bool cand0 = normal && c0 > 0, cand1 = normal && c1 > 0;
+        const u64 m0 = __ballot(cand0), m1 = __ballot(cand1), lt = (1ull << lane) - 1;
+        const u32 r0 = total + __popcll(m0 & lt) + __popcll(m1 & lt), r1 = r0 + (cand0 ? 1u : 0u);
+        S.sym[E] = 0xFF; S.sym[256 + E] = 0xFF;
+        if (cand0 && r0 < kmax) { S.kept[r0] = E; S.cnt[r0] = c0; S.sym[E] = (uint8_t)r0; }
+        if (cand1 && r1 < kmax) { S.kept[r1] = 256 + E; S.cnt[r1] = c1; S.sym[256 + E] = (uint8_t)r1; }
+        total += __popcll(m0) + __popcll(m1);
+        nonfinite = nonfinite || __any(E == 255 && (c0 | c1) != 0);
+        zero_class = zero_class || __any(E == 0 && (c0 | c1) != 0);
+    }
     const u32 K = total < kmax ? total : kmax;
-    const bool is_kept = cand && rank < K;
-    if (is_kept) { s_kept[rank] = b; s_cnt[rank] = c; }
-    s_sym[b] = (uint8_t)(is_kept ? rank : K);
     __syncthreads();
-
-    if (t == 0) {
+    if (threadIdx.x == 0) {
         Table& T = ws->table;
         u64 kept_total = 0;
-        for (u32 j = 0; j < K; ++j) kept_total += s_cnt[j];
-        s_cnt[K] = n - kept_total;
+        for (u32 j = 0; j < K; ++j) kept_total += S.cnt[j];
+        S.cnt[K] = n - kept_total;
         const u32 msym = K + 1;
         // leaves in ascending (count, symbol) order
         u32 nl = 0;
-        for (u32 s = 0; s < msym; ++s) {
-            if (s_cnt[s] == 0) continue;
+        for (u32 sy = 0; sy < msym; ++sy) {
+            if (S.cnt[sy] == 0) continue;
             u32 p = nl++;
-            while (p > 0 && s_cnt[leaf[p - 1]] > s_cnt[s]) { leaf[p] = leaf[p - 1]; --p; }
-            leaf[p] = s;
+            while (p > 0 && S.cnt[S.leaf[p - 1]] > S.cnt[sy]) { S.leaf[p] = S.leaf[p - 1]; --p; }
+            S.leaf[p] = sy;
         }
         u32 max_len = 0;
-        if (nl == 1) { s_len[leaf[0]] = 1; max_len = 1; }
+        if (nl == 1) { S.len[S.leaf[0]] = 1; max_len = 1; }
         else if (nl >= 2) {
             // two queues: sorted leaves and joined nodes in creation order (their weights never
             // decrease); on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
@@ -195,40 +204,42 @@ __global__ __launch_bounds__(512) void k_table(Workspace* ws, u64 n, int nbits) 
             for (u32 k = 0; k + 1 < nl; ++k) {
                 u32 pick[2]; u64 wsum = 0;
                 for (int q = 0; q < 2; ++q) {
-                    const bool take_leaf = li < nl && (qi >= ni || s_cnt[leaf[li]] <= node_w[qi]);
-                    if (take_leaf) { pick[q] = leaf[li]; wsum += s_cnt[leaf[li]]; ++li; }
-                    else { pick[q] = 16 + qi; wsum += node_w[qi]; ++qi; }
+                    const bool take_leaf = li < nl && (qi >= ni || S.cnt[S.leaf[li]] <= S.node_w[qi]);
+                    if (take_leaf) { pick[q] = S.leaf[li]; wsum += S.cnt[S.leaf[li]]; ++li; }
+                    else { pick[q] = 16 + qi; wsum += S.node_w[qi]; ++qi; }
                 }
-                node_w[ni] = wsum; left[ni] = pick[0]; right[ni] = pick[1]; ++ni;
+                S.node_w[ni] = wsum; S.left[ni] = pick[0]; S.right[ni] = pick[1]; ++ni;
             }
-            depth[ni - 1] = 0;
+            S.depth[ni - 1] = 0;
             for (int i = (int)ni - 1; i >= 0; --i) {
-                const u32 d = depth[i] + 1, ch[2] = {left[i], right[i]};
+                const u32 d = S.depth[i] + 1, ch[2] = {S.left[i], S.right[i]};
                 for (int q = 0; q < 2; ++q) {
-                    if (ch[q] >= 16) depth[ch[q] - 16] = d;
-                    else { s_len[ch[q]] = d; if (d > max_len) max_len = d; }
+                    if (ch[q] >= 16) S.depth[ch[q] - 16] = d;
+                    else { S.len[ch[q]] = d; if (d > max_len) max_len = d; }
                 }
             }
         }
         // canonical codes by counting codes per length
         u32 per_len[17], next_code[17];
         for (int L = 0; L <= 16; ++L) per_len[L] = 0;
-        for (u32 s = 0; s < msym; ++s) per_len[s_len[s]]++;
+        for (u32 sy = 0; sy < msym; ++sy) per_len[S.len[sy]]++;
         per_len[0] = 0;
         u32 code = 0;
         for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
-        for (u32 s = 0; s < msym; ++s) if (s_len[s]) s_code[s] = next_code[s_len[s]]++;
-        for (u32 s = 0; s < kMaxSym; ++s) {
-            T.codelen[s] = s < msym ? ((s_code[s] << 5) | s_len[s]) : 0;
-            T.kept[s] = s < K ? s_kept[s] : 0;
-            T.cnt[s] = s < msym ? s_cnt[s] : 0;
+        for (u32 sy = 0; sy < msym; ++sy) if (S.len[sy]) S.code[sy] = next_code[S.len[sy]]++;
+        for (u32 sy = 0; sy < kMaxSym; ++sy) {
+            T.codelen[sy] = sy < msym ? ((S.code[sy] << 5) | S.len[sy]) : 0;
+            T.kept[sy] = sy < K ? S.kept[sy] : 0;
+            T.cnt[sy] = sy < msym ? S.cnt[sy] : 0;
         }
-        T.K = K; T.max_len = max_len; T.k_E = total + flag_zero;
-        T.status = flag_nonfinite ? 2u : 0u;
+        T.K = K; T.max_len = max_len; T.k_E = total + (zero_class ? 1u : 0u);
+        T.status = nonfinite ? 2u : 0u;
     }
     __syncthreads();
-    const u32 s = s_sym[b];
-    ws->table.symlen_of_bucket[b] = (uint8_t)(s | (s_len[s] << 4));
+    if (active) for (u32 b = lane; b < 512; b += kW) {
+        const u32 sy = S.sym[b] == 0xFF ? K : S.sym[b];
+        ws->table.symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
+    }
 }
 
 // ----------------------------------------------------------------------------- k_pack
@@ -425,18 +436,72 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
 // once, by the lane whose string holds its first bit, boundary words merged through LDS.
 constexpr u32 kPlaceWords = 2048;
 
+// Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
+// to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
+// offset entry, the result for the host; then the scratch state is cleared for the next call.
+__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
+                                                  u64 n, int nbits, u32 nchunks) {
+    __shared__ u32 hdr[kHeaderBytes / 4];
+    const u32 t = threadIdx.x;
+    const Table& T = ws->table;
+    if (t < kHeaderBytes / 4) hdr[t] = 0;
+    __syncthreads();
+    const u32 status = T.status;
+    const bool ok = status == 0;
+    const u64 area = chunk_area_of(nchunks);
+    const u64 total_words = ws->total_words;
+    const u64 total = ok ? area + 4 * total_words : kHeaderBytes;
+    if (t == 0) {
+        hdr[0] = 0x3142434Cu;                     // "LCB1"
+        hdr[1] = 1u | (kHeaderBytes << 16);
+        hdr[2] = (u32)n; hdr[3] = (u32)(n >> 32);
+        hdr[4] = (u32)nbits;
+        hdr[6] = kW; hdr[7] = kV; hdr[8] = kR;
+        hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
+        hdr[12] = status;
+        if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
+        host_result->bytes = total; host_result->status = status; host_result->pad = 0;
+    }
+    if (ok && t <= T.K) {
+        const u32 len = T.codelen[t] & 31;
+        u32 bucket = 0xFFFFu, rep = 0;
+        if (t < T.K) {
+            bucket = T.kept[t];
+            const u32 sum = ws->mmin[t] + ws->mmax[t];
+            u32 mm = sum >> 1;
+            if ((sum & 1) && (mm & 1)) ++mm;
+            rep = (bucket << 23) | mm;
+        }
+        hdr[16 + 4 * t + 0] = bucket | (len << 16);
+        hdr[16 + 4 * t + 1] = rep;
+        hdr[16 + 4 * t + 2] = (u32)T.cnt[t];
+        hdr[16 + 4 * t + 3] = (u32)(T.cnt[t] >> 32);
+    }
+    __syncthreads();
+    if (t < kHeaderBytes / 4) reinterpret_cast<u32*>(out)[t] = hdr[t];
+    if (ok) {
+        // last offset entry and the zero padding of the offset table
+        u32* off_tab = reinterpret_cast<u32*>(out + kHeaderBytes);
+        const u32 entries = (u32)((area - kHeaderBytes) / 4);
+        if (t == 0) off_tab[nchunks] = (u32)total_words;
+        if (t >= 1 && t < 4 && nchunks + t < entries) off_tab[nchunks + t] = 0;
+    }
+    __syncthreads();
+    clear_encode_state(ws, group_words, (nchunks + 63) / 64, t, blockDim.x);
+    __threadfence_system();
+}
+
 __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
-                                               const u32* __restrict__ group_words,
-                                               const u32* __restrict__ prov, u32 slot_words, u32 nchunks) {
+                                               const u32* __restrict__ group_words, const u32* __restrict__ prov,
+                                               u32 slot_words, u32 nchunks) {
     __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
     __shared__ u32 s_buf_all[4][kPlaceWords];
-    if (ws->table.status != 0) return;
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     u32* s_off = s_off_all[wv];
     u32* s_hw = s_hw_all[wv];
     u32* s_buf = s_buf_all[wv];
     const u32 c = blockIdx.x * 4 + wv;
-    const bool valid = c < nchunks;                          // the last workgroup may hold idle wavefronts
+    const bool valid = c < nchunks && ws->table.status == 0;   // the last workgroup may hold idle wavefronts
     const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
     const u32 bits = valid ? reinterpret_cast<const uint16_t*>(slot)[lane] : 0;
     const u32 g = c >> 6;
@@ -505,57 +570,6 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, cons
     }
 }
 
-// ----------------------------------------------------------------------------- k_finalize
-// Representatives (Section 3.1.1: mean of the bucket's largest and smallest member,
-// rounded once to fp32, ties to even, done on the mantissas since both share a binade)
-// and the header.
-__global__ __launch_bounds__(128) void k_finalize(uint8_t* out, Workspace* ws, u64 n, int nbits, u32 nchunks) {
-    __shared__ u32 hdr[kHeaderBytes / 4];
-    const u32 t = threadIdx.x;
-    const Table& T = ws->table;
-    hdr[t] = 0;
-    __syncthreads();
-    const u32 status = T.status;
-    const bool ok = status == 0;
-    const u64 area = chunk_area_of(nchunks);
-    const u64 total = ok ? area + 4 * ws->total_words : kHeaderBytes;
-    if (t == 0) {
-        hdr[0] = 0x3142434Cu;                     // "LCB1"
-        hdr[1] = 1u | (kHeaderBytes << 16);
-        hdr[2] = (u32)n; hdr[3] = (u32)(n >> 32);
-        hdr[4] = (u32)nbits;
-        hdr[6] = kW; hdr[7] = kV; hdr[8] = kR;
-        hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
-        hdr[12] = status;
-        if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
-        ws->result.bytes = total; ws->result.status = status; ws->result.pad = 0;
-    }
-    if (ok && t <= T.K) {
-        const u32 len = T.codelen[t] & 31;
-        u32 bucket = 0xFFFFu, rep = 0;
-        if (t < T.K) {
-            bucket = T.kept[t];
-            const u32 sum = ws->mmin[t] + ws->mmax[t];
-            u32 mm = sum >> 1;
-            if ((sum & 1) && (mm & 1)) ++mm;
-            rep = (bucket << 23) | mm;
-        }
-        hdr[16 + 4 * t + 0] = bucket | (len << 16);
-        hdr[16 + 4 * t + 1] = rep;
-        hdr[16 + 4 * t + 2] = (u32)T.cnt[t];
-        hdr[16 + 4 * t + 3] = (u32)(T.cnt[t] >> 32);
-    }
-    __syncthreads();
-    reinterpret_cast<u32*>(out)[t] = hdr[t];
-    if (ok) {
-        // last offset entry and the zero padding of the offset table
-        u32* off_tab = reinterpret_cast<u32*>(out + kHeaderBytes);
-        const u32 entries = (u32)((area - kHeaderBytes) / 4);
-        if (t == 0) off_tab[nchunks] = (u32)ws->total_words;
-        if (t >= 1 && nchunks + t < entries) off_tab[nchunks + t] = 0;
-    }
-}
-
 // ----------------------------------------------------------------------------- k_dec_check
 // Everything lc_decode verifies before w_ref is touched, in one launch.  Every workgroup
 // re-reads the header and does the cheap sanity checks that keep its own reads in bounds;
@@ -564,12 +578,14 @@ __global__ __launch_bounds__(128) void k_finalize(uint8_t* out, Workspace* ws, u
 // of the record sizes that the lane lengths imply, from 0 to the blob's stated size.
 // Errors are raised with atomicMax on a word tagged with the call's epoch, so the word
 // never needs clearing.
-__device__ __forceinline__ void raise_status(Workspace* ws, u64 epoch, u32 status) {
-    atomicMax(&ws->dec_status, (epoch << 8) | status);
+__device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u64 epoch, u32 status) {
+    const u64 word = (epoch << 8) | status;
+    atomicMax(&ws->dec_status, word);     // gates the decode sweep on the device
+    host->dec_status = word;              // what the host reads after waiting for the stream (any finding will do)
 }
 
 __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u64 max_total, Workspace* ws,
-                                                   u32 nchunks, u64 epoch, u32 set) {
+                                                   u32 nchunks, u64 epoch, u32 set, HostResult* host, u32 host_slot) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     __shared__ u32 s_ok, s_K, s_max_len;
     __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
@@ -583,8 +599,8 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
     if (!head_ok) {
         if (blockIdx.x == 0 && t == 0) {
             const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 && hn != n;
-            raise_status(ws, epoch, n_mismatch ? 1u : 4u);
-            ws->dec_bytes[set] = 0;
+            raise_status(ws, host, epoch, n_mismatch ? 1u : 4u);
+            host->bytes[host_slot] = 0;
         }
         return;
     }
@@ -600,7 +616,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
             const u32 sum = wave_sum32(lb);
             ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
         }
-        if (!ok && lane == 0) raise_status(ws, epoch, 4u);
+        if (!ok && lane == 0) raise_status(ws, host, epoch, 4u);
     }
     if (blockIdx.x != 0) return;
     // ---- workgroup 0: symbol table, codes, look-up table
@@ -636,10 +652,10 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
                 s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
                 D.info.len[j] = s_len[j]; D.info.code[j] = s_code[j];
             }
-        } else raise_status(ws, epoch, 4u);
+        } else raise_status(ws, host, epoch, 4u);
         D.info.K = K; D.info.max_len = max_len;
         D.info.area = area; D.info.total_words = tw;
-        ws->dec_bytes[set] = total;
+        host->bytes[host_slot] = total;
         s_ok = ok; s_K = K; s_max_len = max_len;
     }
     __syncthreads();
@@ -719,7 +735,7 @@ struct BitReader {
 
 template <bool FAST, bool LV2, bool STAGED>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
-                                            float* __restrict__ w_ref, u64 n, Workspace* ws, u32 c,
+                                            float* __restrict__ w_ref, u64 n, Workspace* ws, HostResult* host, u32 c,
                                             const DecLds& L, u32 P1, u32 P2, u32 K, u64 epoch) {
     const u32 lane = lane_id();
     BitReader<STAGED> br;
@@ -757,12 +773,12 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
         }
     }
     const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
-    if (__any(used != lane_bits) && lane == 0) raise_status(ws, epoch, 4u);
+    if (__any(used != lane_bits) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
 template <bool FAST, bool LV2>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, u32 c, DecLds& L, u32 P1, u32 P2, u32 K, u64 area, u64 epoch) {
+                                             Workspace* ws, HostResult* host, u32 c, DecLds& L, u32 P1, u32 P2, u32 K, u64 area, u64 epoch) {
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
     const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
@@ -788,44 +804,46 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, f
             L.payload[wv][i] = q;
         }
         decode_rows<FAST, LV2, true>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
-                                     w_ref, n, ws, c, L, P1, P2, K, epoch);
+                                     w_ref, n, ws, host, c, L, P1, P2, K, epoch);
     } else {
-        decode_rows<FAST, LV2, false>(gw, nwords, o, lane_bits, w_ref, n, ws, c, L, P1, P2, K, epoch);
+        decode_rows<FAST, LV2, false>(gw, nwords, o, lane_bits, w_ref, n, ws, host, c, L, P1, P2, K, epoch);
     }
 }
 
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
-                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch) {
+                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
     __shared__ DecLds L;
-    if ((ws->dec_status >> 8) == epoch) return;          // the check kernel found something: touch nothing
-    const u32 t = threadIdx.x;
-    const DecSet& D = ws->dec_set[0];
-    const u32 M = D.info.max_len, K = D.info.K;
-    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-    const u64 area = D.info.area;
-    if (t < (1u << P1)) L.lut1[t] = D.lut1[t];
-    if (M > kDecLut1Bits) {
-        if ((1u << P2) >= 4096) {
-            const uint4* src = reinterpret_cast<const uint4*>(D.lut2);
-            uint4* dst = reinterpret_cast<uint4*>(L.lut2);
-            for (u32 i = t; i < (1u << P2) / 16; i += 256) dst[i] = src[i];
-        } else {
-            for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = D.lut2[i];
+    // if the check kernel found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
+        const u32 t = threadIdx.x;
+        const DecSet& D = ws->dec_set[0];
+        const u32 M = D.info.max_len, K = D.info.K;
+        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+        const u64 area = D.info.area;
+        if (t < (1u << P1)) L.lut1[t] = D.lut1[t];
+        if (M > kDecLut1Bits) {
+            if ((1u << P2) >= 4096) {
+                const uint4* src = reinterpret_cast<const uint4*>(D.lut2);
+                uint4* dst = reinterpret_cast<uint4*>(L.lut2);
+                for (u32 i = t; i < (1u << P2) / 16; i += 256) dst[i] = src[i];
+            } else {
+                for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = D.lut2[i];
+            }
         }
-    }
-    if (t < kMaxSym) {
-        L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
-        L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
-    }
-    __syncthreads();
-    const u32 wave = t >> 6;
-    for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
-        const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) {
-            if (M > kDecLut1Bits) decode_chunk<true, true>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
-            else decode_chunk<true, false>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
-        } else {
-            decode_chunk<false, true>(blob, w_ref, n, ws, c, L, P1, P2, K, area, epoch);
+        if (t < kMaxSym) {
+            L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
+            L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
+        }
+        __syncthreads();
+        const u32 wave = t >> 6;
+        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+            const bool full = (u64)(c + 1) * kChunk <= n;
+            if (full && aligned) {
+                if (M > kDecLut1Bits) decode_chunk<true, true>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                else decode_chunk<true, false>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+            } else {
+                decode_chunk<false, true>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+            }
         }
     }
 }
@@ -856,7 +874,7 @@ __device__ __noinline__ u32 decode_long_many(const ManyLds& L, u32 t, u64 win) {
 
 template <bool FAST>
 __device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, float* __restrict__ w_ref, u64 n,
-                                                  Workspace* ws, u32 c, const ManyLds& L, u64 epoch) {
+                                                  Workspace* ws, HostResult* host, u32 c, const ManyLds& L, u64 epoch) {
     const u32 lane = lane_id();
     BitReader<false> br[kMaxMany];
     u32 wi0[kMaxMany], avail0[kMaxMany], lane_bits[kMaxMany];
@@ -913,40 +931,42 @@ __device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, 
 #pragma unroll
     for (int t = 0; t < kMaxMany; ++t)
         if ((u32)t < T) bad = bad || (avail0[t] + 32 * (br[t].wi - wi0[t]) - br[t].avail != lane_bits[t]);
-    if (__any(bad) && lane == 0) raise_status(ws, epoch, 4u);
+    if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
 __global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 T, float* __restrict__ w_ref, u64 n,
-                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch) {
+                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
     __shared__ ManyLds L;
-    if ((ws->dec_status >> 8) == epoch) return;          // a check found something: touch nothing
-    const u32 tid = threadIdx.x;
-    for (u32 t = 0; t < T; ++t) {
-        const DecSet& D = ws->dec_set[t];
-        const u32 M = D.info.max_len, K = D.info.K;
-        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-        if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
-        if (M > kDecLut1Bits) for (u32 i = tid; i < (1u << P2); i += 256) L.lut2[t][i] = D.lut2[i];
-        if (tid < kMaxSym) {
-            L.rep[t][tid] = __uint_as_float(tid < K ? D.info.rep_bits[tid] : 0x80000000u);
-            L.len[t][tid] = D.info.len[tid]; L.code[t][tid] = D.info.code[tid];
+    // if a check found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
+        const u32 tid = threadIdx.x;
+        for (u32 t = 0; t < T; ++t) {
+            const DecSet& D = ws->dec_set[t];
+            const u32 M = D.info.max_len, K = D.info.K;
+            const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+            if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
+            if (M > kDecLut1Bits) for (u32 i = tid; i < (1u << P2); i += 256) L.lut2[t][i] = D.lut2[i];
+            if (tid < kMaxSym) {
+                L.rep[t][tid] = __uint_as_float(tid < K ? D.info.rep_bits[tid] : 0x80000000u);
+                L.len[t][tid] = D.info.len[tid]; L.code[t][tid] = D.info.code[tid];
+            }
+            if (tid == 0) { L.K[t] = K; L.P1[t] = P1; L.P2[t] = P2; L.area[t] = D.info.area; }
         }
-        if (tid == 0) { L.K[t] = K; L.P1[t] = P1; L.P2[t] = P2; L.area[t] = D.info.area; }
-    }
-    __syncthreads();
-    const u32 wave = tid >> 6;
-    for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
-        const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) decode_many_chunk<true>(blobs, T, w_ref, n, ws, c, L, epoch);
-        else decode_many_chunk<false>(blobs, T, w_ref, n, ws, c, L, epoch);
+        __syncthreads();
+        const u32 wave = tid >> 6;
+        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+            const bool full = (u64)(c + 1) * kChunk <= n;
+            if (full && aligned) decode_many_chunk<true>(blobs, T, w_ref, n, ws, host, c, L, epoch);
+            else decode_many_chunk<false>(blobs, T, w_ref, n, ws, host, c, L, epoch);
+        }
     }
 }
 
 // ----------------------------------------------------------------------------- launchers
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-void launch_reset(Workspace* ws, uint32_t* group_words, uint64_t nchunks, hipStream_t s) {
-    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)((nchunks + 63) / 64));
+void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)kMaxGroups);
 }
 
 void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s) {
@@ -961,7 +981,7 @@ void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, 
 }
 
 void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s) {
-    hipLaunchKernelGGL(k_table, dim3(1), dim3(512), 0, s, ws, (u64)n, nbits);
+    hipLaunchKernelGGL(k_table, dim3(1), dim3(64), 0, s, ws, (u64)n, nbits);
 }
 
 void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
@@ -979,34 +999,36 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov, slot_words,
-                       (u32)nchunks);
+    hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
+                       slot_words, (u32)nchunks);
 }
 
-void launch_finalize(uint8_t* out, Workspace* ws, uint64_t n, int nbits, hipStream_t s) {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(128), 0, s, out, ws, (u64)n, nbits, (u32)num_chunks_of(n));
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint64_t n, int nbits,
+                     hipStream_t s) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, (u64)n, nbits,
+                       (u32)num_chunks_of(n));
 }
 
 void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
-                      hipStream_t s) {
+                      HostResult* host, int host_slot, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
     hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws, (u32)nchunks,
-                       (u64)epoch, (u32)set);
+                       (u64)epoch, (u32)set, host, (u32)host_slot);
 }
 
-void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
-                        const Tuning& tune, hipStream_t s) {
+void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws,
+                        uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (nchunks + 3) / 4;
     const u64 cap = (u64)tune.num_cu * tune.many_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)count, w_ref, (u64)n, ws,
-                       (u32)nchunks, (int)aligned16(w_ref), (u64)epoch);
+                       (u32)nchunks, (int)aligned16(w_ref), (u64)epoch, host);
 }
 
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
@@ -1014,7 +1036,7 @@ void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws,
     const u64 cap = (u64)tune.num_cu * tune.decode_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     hipLaunchKernelGGL(k_decode, dim3((u32)blocks), dim3(256), 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks,
-                       (int)aligned16(w_ref), (u64)epoch);
+                       (int)aligned16(w_ref), (u64)epoch, host);
 }
 
 }  // namespace lc
