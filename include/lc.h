@@ -148,7 +148,8 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
  * deltas; Section 3.2, checkpoint merging): applies blobs[0], blobs[1], ... blobs[count-1] to
  * w_ref in this order.  The result is bit for bit what `count` successive lc_decode calls
  * give (one fp32 add per blob and element, in blob order), but w_ref is read and written
- * once per 8 blobs instead of once per blob.
+ * once per sweep of several blobs (up to 8; as many as the decoder's on-chip memory takes
+ * at full occupancy, typically 4 to 6) instead of once per blob.
  *   blobs  HOST array of `count` DEVICE pointers to LCB1 blobs (16-byte aligned), each with
  *          header n equal to `n`; 1 <= count <= LC_MAX_MANY
  * Every blob is validated as in lc_decode before w_ref is touched.  Waits for `stream`;

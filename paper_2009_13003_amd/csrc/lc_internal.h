@@ -39,6 +39,7 @@ struct DecInfo {
 };
 
 constexpr int kMaxMany = 8;  // blobs one fused restore sweep can apply
+constexpr int kMaxSets = 64; // blobs one lc_decode_many call accepts (= LC_MAX_MANY), each with a set of its own
 
 // Everything the decode sweep needs to know about one blob, written by k_dec_check.
 struct DecSet {
@@ -58,7 +59,8 @@ struct Result {
 struct HostResult {
     Result enc;                                  // lc_encode: blob bytes, lc_status
     unsigned long long dec_status;               // lc_decode*: (epoch << 8) | lc_status of the worst finding
-    unsigned long long bytes[64];                // lc_decode*: total_bytes of each blob
+    unsigned long long bytes[kMaxSets];          // lc_decode*: total_bytes of each blob
+    uint32_t max_len[kMaxSets];                  // lc_decode*: longest code of each blob
 };
 
 // Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] (u32, at a
@@ -72,8 +74,7 @@ struct Workspace {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
-    unsigned long long dec_bytes[kMaxMany];   // total_bytes of the blob checked into each set
-    DecSet dec_set[kMaxMany];
+    DecSet dec_set[kMaxSets];        // one per blob of the call
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
@@ -87,7 +88,7 @@ __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsW
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
 enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize,
-            kSlotDecCheck, kSlotDecode, kSlotDecodeMany, kNumSlots };
+            kSlotDecCheck, kSlotDecode, kSlotDecodeMany, kSlotDecodeFused, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
 // variables (read once) for sweeps.
@@ -98,6 +99,8 @@ struct Tuning {
     int pack_waves_per_cu = 6;
     int decode_blocks_per_cu = 4;
     int many_blocks_per_cu = 2;
+    int fused_waves_per_cu = 16;       // most wavefronts per compute unit
+    int fused_min_waves_per_cu = 8;    // a sweep takes as many blobs as still leave LDS for this many
 };
 
 // Launchers (lc_kernels.hip).
@@ -110,12 +113,23 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint64_t n, int nbits,
                      hipStream_t s);
-struct BlobList { const uint8_t* p[kMaxMany]; };
-void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
-                      HostResult* host, int host_slot, hipStream_t s);
+struct BlobList { const uint8_t* p[kMaxSets]; };
+// Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
+void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, uint64_t max_total, Workspace* ws,
+                      uint64_t epoch, HostResult* host, hipStream_t s);
 void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s);
-void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws,
+// Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused
+// kernel requires every code of these blobs to be at most kDecLut1Bits long.
+void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
                         uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s);
+// pay_words: LDS words each wavefront gets for the payloads of one chunk of all `count` blobs.
+void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+                         uint64_t epoch, HostResult* host, uint32_t pay_words, const Tuning& tune, hipStream_t s);
+
+constexpr uint32_t kLdsPerCu = 160 * 1024;        // gfx950
+constexpr uint32_t kFusedMinWords = 1024;
+// LDS bytes one wavefront (= workgroup) of the fused kernel takes for `count` blobs and pay_words payload words.
+size_t fused_lds_bytes(int count, uint32_t pay_words);
 
 }  // namespace lc

@@ -584,8 +584,10 @@ __device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u6
     host->dec_status = word;              // what the host reads after waiting for the stream (any finding will do)
 }
 
-__global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u64 max_total, Workspace* ws,
-                                                   u32 nchunks, u64 epoch, u32 set, HostResult* host, u32 host_slot) {
+__global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u64 n, u64 max_total, Workspace* ws,
+                                                   u32 nchunks, u64 epoch, HostResult* host) {
+    const u32 set = first + blockIdx.y, host_slot = set;     // one grid row per blob
+    const uint8_t* blob = blobs.p[set];
     __shared__ u32 hdr[kHeaderBytes / 4];
     __shared__ u32 s_ok, s_K, s_max_len;
     __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
@@ -600,7 +602,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
         if (blockIdx.x == 0 && t == 0) {
             const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 && hn != n;
             raise_status(ws, host, epoch, n_mismatch ? 1u : 4u);
-            host->bytes[host_slot] = 0;
+            host->bytes[host_slot] = 0; host->max_len[host_slot] = 0;
         }
         return;
     }
@@ -655,7 +657,7 @@ __global__ __launch_bounds__(256) void k_dec_check(const uint8_t* blob, u64 n, u
         } else raise_status(ws, host, epoch, 4u);
         D.info.K = K; D.info.max_len = max_len;
         D.info.area = area; D.info.total_words = tw;
-        host->bytes[host_slot] = total;
+        host->bytes[host_slot] = total; host->max_len[host_slot] = max_len;
         s_ok = ok; s_K = K; s_max_len = max_len;
     }
     __syncthreads();
@@ -873,7 +875,7 @@ __device__ __noinline__ u32 decode_long_many(const ManyLds& L, u32 t, u64 win) {
 }
 
 template <bool FAST>
-__device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, float* __restrict__ w_ref, u64 n,
+__device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
                                                   Workspace* ws, HostResult* host, u32 c, const ManyLds& L, u64 epoch) {
     const u32 lane = lane_id();
     BitReader<false> br[kMaxMany];
@@ -881,7 +883,7 @@ __device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, 
 #pragma unroll
     for (int t = 0; t < kMaxMany; ++t) {
         if ((u32)t < T) {
-            const uint8_t* blob = blobs.p[t];
+            const uint8_t* blob = blobs.p[first + t];
             const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
             const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
             const uint8_t* rec = blob + L.area[t] + 4 * (u64)o0;
@@ -934,14 +936,14 @@ __device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 T, 
     if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
-__global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 T, float* __restrict__ w_ref, u64 n,
+__global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
                                                      Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
     __shared__ ManyLds L;
     // if a check found something, touch nothing
     if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
         const u32 tid = threadIdx.x;
         for (u32 t = 0; t < T; ++t) {
-            const DecSet& D = ws->dec_set[t];
+            const DecSet& D = ws->dec_set[first + t];
             const u32 M = D.info.max_len, K = D.info.K;
             const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
             if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
@@ -956,9 +958,263 @@ __global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 T, floa
         const u32 wave = tid >> 6;
         for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
             const bool full = (u64)(c + 1) * kChunk <= n;
-            if (full && aligned) decode_many_chunk<true>(blobs, T, w_ref, n, ws, host, c, L, epoch);
-            else decode_many_chunk<false>(blobs, T, w_ref, n, ws, host, c, L, epoch);
+            if (full && aligned) decode_many_chunk<true>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
+            else decode_many_chunk<false>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
         }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_decode_fused
+// The same restore for blobs whose codes are all at most 7 bits long (always the case for
+// nbits <= 3), built for throughput.  T is a compile-time constant, so the T bit strings of a
+// lane are T independent dependency chains that the scheduler interleaves.  One wavefront per
+// workgroup; the payloads of a chunk (all T blobs) are staged in the workgroup's LDS area with
+// coalesced loads (the host sizes the area to the blobs, which also sets how many wavefronts
+// share a compute unit).  A row's 4 codes of one blob take at most 28 bits, so each blob's 32-bit
+// window is re-read once per row from the bit position alone, without a branch.  Both look-up
+// tables are free of LDS bank conflicts: 128 one-byte entries over the next 7 bits (code length
+// and symbol), then the symbol's representative.  A chunk whose payloads do not fit the LDS
+// area reads them from memory instead.
+template <int T>
+struct FusedHead {
+    uint16_t lut[T][1u << kDecLut1Bits];         // next 7 bits -> e = (len << 4 | symbol) << 2
+    u32 rep[T][128];                             // byte offset e -> representative bits (-0.0: merged symbol); a symbol
+                                                 // has one length, so distinct entries in use lie in distinct banks
+    const uint8_t* rec_base[T];                  // start of the chunk records
+    const u32* off_tab[T];
+    u32 pad[3];
+    u32 before_pay;                              // the word in front of the payload area (read, never used)
+};
+constexpr u32 kFusedSlack = 64;                  // words behind the payloads that a damaged lane string may run into:
+                                                 // 256 codes of at most 7 bits past a start that validation bounds
+
+// Bit positions are kept as p = 31 + bits from the start of the payload area (staged) or of the
+// blob's payload (from memory): the window is then the low 32 bits of {word[(p >> 5) - 1],
+// word[p >> 5]} >> (~p & 31), which is one v_alignbit.
+template <int T, bool FAST, bool STAGED>
+__device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
+                                          const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u64 idx,
+                                          float (&x)[4]) {
+    // Written step by step across the blobs (all windows, then the first code of every blob, ...), so
+    // that the T look-ups of a step are in flight together.
+    u32 win[T], rep[4][T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        u32 hi, lo;                                   // the two payload words around the lane's position
+        if (STAGED) {
+            const u32 wi = pos[t] >> 5;              // stays inside the area and its slack
+            hi = pay[(int)wi - 1]; lo = pay[wi];
+        } else {
+            const u32 wi = pos[t] >> 5, last = nw[t] - 1;
+            hi = wi ? gw[t][min(wi - 1, last)] : 0u; lo = gw[t][min(wi, last)];
+        }
+        win[t] = __builtin_amdgcn_alignbit(hi, lo, ~pos[t]);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        if (FAST || idx + v < n) {
+            u32 e[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                e[t] = H.lut[t][win[t] >> (32 - kDecLut1Bits)];
+                asm("" : "+v"(e[t]));                 // keep e a 32-bit value (no 16-bit shift plus re-extension)
+            }
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const u32 len = e[t] >> 6;
+                rep[v][t] = *reinterpret_cast<const u32*>(reinterpret_cast<const uint8_t*>(H.rep[t]) + e[t]);
+                win[t] <<= len; pos[t] += len;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < T; ++t) rep[v][t] = 0x80000000u;
+        }
+    }
+    u32 kept = 1;                                     // a single blob often leaves whole rows unchanged: skip their write
+    if (T == 1) kept = (rep[0][0] | rep[1][0] | rep[2][0] | rep[3][0]) & 0x7FFFFFFFu;
+    if (FAST) {
+        if (T > 1 || __any(kept != 0)) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));   // in blob order
+            *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (idx + v < n) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));
+                w_ref[idx + v] = x[v];
+            }
+        }
+    }
+}
+
+// All rows of a full, aligned chunk with staged payloads: w_ref is read PF rows ahead in two
+// alternating register batches, so the reads of the next rows are in flight while these decode.
+template <int T>
+__device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
+                                                const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u32 c) {
+    constexpr int PF = 4;
+    const u32 lane = lane_id();
+    float4* rows = reinterpret_cast<float4*>(w_ref + (u64)c * kChunk) + lane;
+    const u64 base = (u64)c * kChunk + lane * kV;
+    float4 A[PF], B[PF];
+#pragma unroll
+    for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + k * kW);
+    auto batch = [&](float4 (&X)[PF], u32 r0) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+            float x[4] = {X[k].x, X[k].y, X[k].z, X[k].w};
+            fused_row<T, true, true>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
+        }
+    };
+    for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) B[k] = load_stream(rows + (r0 + PF + k) * kW);
+        batch(A, r0);
+        if (r0 + 2 * PF < kR) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + (r0 + 2 * PF + k) * kW);
+        }
+        batch(B, r0 + PF);
+    }
+}
+
+// Any chunk (ragged, unaligned, or payloads read from memory), row by row.
+template <int T, bool FAST>
+__device__ __forceinline__ void fused_rows_plain(const FusedHead<T>& H, const u32* const (&gw)[T], const u32 (&nw)[T], u32 (&pos)[T],
+                                              float* __restrict__ w_ref, u64 n, u32 c) {
+    const u32 lane = lane_id();
+    const u64 base = (u64)c * kChunk;
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        if (!FAST && idx >= n) break;
+        float x[4];
+        load_row<FAST>(w_ref, idx, n, x);
+        fused_row<T, FAST, false>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
+    }
+}
+
+template <typename P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {        // a pointer every lane holds alike, moved to scalar registers
+    const u64 v = reinterpret_cast<u64>(p);
+    const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+    return reinterpret_cast<P*>(((u64)hi << 32) | lo);
+}
+
+template <int T, bool FAST>
+__device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32 pay_words, float* __restrict__ w_ref, u64 n,
+                                            Workspace* ws, HostResult* host, u32 c, u32 nchunks, u64 epoch) {
+    const u32 lane = lane_id();
+    const u32* gw[T];
+    u32 nw[T], k0[T], wbase[T], pos[T], start[T], lane_bits[T];
+    u32 total = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const u32* ot = uniform_ptr(H.off_tab[t]);
+        const u32 o0 = ot[c], o1 = ot[c + 1];
+        const uint8_t* rec = uniform_ptr(H.rec_base[t]) + 4 * (u64)o0;
+        nw[t] = o1 - o0 - kLaneBitsWords;                 // >= 1 (validated)
+        lane_bits[t] = reinterpret_cast<const uint16_t*>(rec)[lane];
+        gw[t] = reinterpret_cast<const u32*>(rec + 2 * kW);
+        k0[t] = (u32)((reinterpret_cast<uintptr_t>(gw[t]) >> 2) & 3);
+        wbase[t] = total;
+        total += (nw[t] + k0[t] + 3) & ~3u;
+    }
+    const bool staged = FAST && total <= pay_words;
+    if (staged) {
+        // Coalesced copies of [16-byte aligned start, payload end) into the LDS area; the words before a
+        // payload are its record's lane lengths.  A last partial vector may read up to 12 bytes past the
+        // payload: into the next record, except in the last chunk, which reads that vector word by word.
+        constexpr int CV = T > 4 ? 2 : 4;                 // vectors per lane and blob in flight
+        const bool guard = c + 1 == nchunks;
+        u32 most = 0;
+#pragma unroll
+        for (int t = 0; t < T; ++t) most = max(most, (nw[t] + k0[t] + 3) >> 2);
+        for (u32 i0 = 0; i0 < most; i0 += CV * kW) {
+            uint4 q[T][CV];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint4* gv = reinterpret_cast<const uint4*>(gw[t] - k0[t]);
+                const u32 have = nw[t] + k0[t], nvec = (have + 3) >> 2;
+#pragma unroll
+                for (int k = 0; k < CV; ++k) {
+                    const u32 i = i0 + k * kW + lane;
+                    if (i < nvec) {
+                        if (!guard || 4 * i + 4 <= have) q[t][k] = gv[i];
+                        else {
+                            const u32* tw = reinterpret_cast<const u32*>(gv + i);
+                            const u32 left = have - 4 * i;
+                            q[t][k].x = tw[0]; q[t][k].y = left > 1 ? tw[1] : 0; q[t][k].z = left > 2 ? tw[2] : 0; q[t][k].w = 0;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                uint4* dst = reinterpret_cast<uint4*>(pay + wbase[t]);
+                const u32 nvec = (nw[t] + k0[t] + 3) >> 2;
+#pragma unroll
+                for (int k = 0; k < CV; ++k) {
+                    const u32 i = i0 + k * kW + lane;
+                    if (i < nvec) dst[i] = q[t][k];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t) start[t] = 31 + wave_incl_scan(lane_bits[t]) - lane_bits[t];
+    if (staged) {
+#pragma unroll
+        for (int t = 0; t < T; ++t) { start[t] += 32 * (wbase[t] + k0[t]); pos[t] = start[t]; }
+        fused_rows_fast<T>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
+    } else {
+#pragma unroll
+        for (int t = 0; t < T; ++t) pos[t] = start[t];
+        fused_rows_plain<T, FAST>(H, gw, nw, pos, w_ref, n, c);
+    }
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < T; ++t) bad = bad || (pos[t] - start[t] != lane_bits[t]);
+    if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
+}
+
+template <int T>
+__global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, float* __restrict__ w_ref, u64 n,
+                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch,
+                                                     HostResult* host, u32 pay_words) {
+    __shared__ FusedHead<T> H;
+    static_assert(sizeof(FusedHead<T>) % 16 == 0, "payload area must stay 16-byte aligned");
+    extern __shared__ uint4 fused_pay[];                 // pay_words + kFusedSlack payload words, right behind H
+    u32* pay = reinterpret_cast<u32*>(fused_pay);
+    // if a check found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) == epoch) return;
+    const u32 tid = threadIdx.x;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const DecSet& D = ws->dec_set[first + t];
+        const u32 M = D.info.max_len, K = D.info.K;       // M <= 7: e < 128
+        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits;
+        for (u32 i = tid; i < (1u << kDecLut1Bits); i += kW) {
+            const u32 e = D.lut1[i >> (kDecLut1Bits - P1)];
+            H.lut[t][i] = (uint16_t)(e << 2);
+            H.rep[t][i] = (i & 15) < K ? D.info.rep_bits[i & 15] : 0x80000000u;
+        }
+        if (tid == 0) {
+            const uint8_t* blob = blobs.p[first + t];
+            H.rec_base[t] = blob + D.info.area;
+            H.off_tab[t] = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+        }
+    }
+    if (tid == 0) H.before_pay = 0;
+    __syncthreads();
+    for (u32 c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const bool full = (u64)(c + 1) * kChunk <= n;
+        if (full && aligned) fused_chunk<T, true>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        else fused_chunk<T, false>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
     }
 }
 
@@ -1009,23 +1265,60 @@ void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t*
                        (u32)num_chunks_of(n));
 }
 
-void launch_dec_check(const uint8_t* blob, uint64_t n, uint64_t max_total, Workspace* ws, uint64_t epoch, int set,
-                      HostResult* host, int host_slot, hipStream_t s) {
+void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, uint64_t max_total, Workspace* ws,
+                      uint64_t epoch, HostResult* host, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
-    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks), dim3(256), 0, s, blob, (u64)n, (u64)max_total, ws, (u32)nchunks,
-                       (u64)epoch, (u32)set, host, (u32)host_slot);
+    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
+                       ws, (u32)nchunks, (u64)epoch, host);
 }
 
-void launch_decode_many(const BlobList& blobs, int count, float* w_ref, uint64_t n, Workspace* ws,
+void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
                         uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (nchunks + 3) / 4;
     const u64 cap = (u64)tune.num_cu * tune.many_blocks_per_cu;
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)count, w_ref, (u64)n, ws,
+    hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)first, (u32)count, w_ref, (u64)n, ws,
                        (u32)nchunks, (int)aligned16(w_ref), (u64)epoch, host);
+}
+
+
+template <int T>
+static void launch_fused_t(const BlobList& blobs, int first, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                           HostResult* host, u32 blocks, u32 pay_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_decode_fused<T>, dim3(blocks), dim3(64), 4 * (size_t)(pay_words + kFusedSlack), s, blobs, (u32)first, w_ref,
+                       (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
+}
+
+size_t fused_lds_bytes(int count, uint32_t pay_words) {
+    static const size_t head[kMaxMany] = {sizeof(FusedHead<1>), sizeof(FusedHead<2>), sizeof(FusedHead<3>), sizeof(FusedHead<4>),
+                                          sizeof(FusedHead<5>), sizeof(FusedHead<6>), sizeof(FusedHead<7>), sizeof(FusedHead<8>)};
+    return head[count - 1] + 4 * (size_t)(pay_words + kFusedSlack);
+}
+
+void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+                         uint64_t epoch, HostResult* host, uint32_t pay_words, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    // one wavefront per workgroup; as many workgroups per compute unit as their LDS areas allow
+    u64 per_cu = kLdsPerCu / fused_lds_bytes(count, pay_words);
+    if (per_cu > (u64)tune.fused_waves_per_cu) per_cu = tune.fused_waves_per_cu;
+    if (per_cu < 1) per_cu = 1;
+    u64 blocks = (u64)tune.num_cu * per_cu;
+    if (blocks > nchunks) blocks = nchunks;
+    const u32 b = (u32)blocks;
+    switch (count) {
+        case 1: launch_fused_t<1>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 2: launch_fused_t<2>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 3: launch_fused_t<3>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 4: launch_fused_t<4>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 5: launch_fused_t<5>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 6: launch_fused_t<6>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 7: launch_fused_t<7>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        default: launch_fused_t<8>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+    }
 }
 
 void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,

@@ -333,3 +333,135 @@ def test_fused_restore_edge_cases(lc):
     rec = w0.clone()
     lc.lc_decode_many(blobs, rec)
     assert torch.equal(rec.view(torch.int32), tracked.view(torch.int32))
+
+
+def encode_chain(lc, w0, deltas, nbits_list):
+    """Blobs of successive checkpoints w0 + d_1, w0 + d_1 + d_2, ..., each against the recovered state."""
+    n = w0.numel()
+    tracked = w0.clone()
+    w = w0.clone()
+    out = lc.alloc_out(n, 4, DEV)
+    blobs = []
+    for d, nbits in zip(deltas, nbits_list):
+        w = w + d
+        size = lc.lc_encode(w, tracked, nbits, out)
+        blobs.append(out[:size].clone())
+        lc.lc_decode(blobs[-1], tracked)
+    return tracked, blobs
+
+
+def oracle_restore(w0, blobs):
+    ref = w0.cpu().numpy()
+    for b in blobs:
+        orc.decode(b.cpu().numpy(), ref)
+    return ref
+
+
+def test_fused_restore_mixed_code_lengths_and_whole_chunks(lc):
+    """Blobs with short codes (fused sweep) and long codes (general sweep) alternate in one call; n is a whole
+    number of chunks, so the last chunk is staged too."""
+    n = 6 * 16384
+    g = torch.Generator(device=DEV); g.manual_seed(77)
+    w0 = 0.05 * torch.randn(n, generator=g, device=DEV)
+    nbits_list = [3, 2, 4, 4, 1, 3, 3, 4, 2, 3, 3, 3]
+    # wide spread of magnitudes: with nbits = 4 the rare top buckets get codes longer than 7 bits
+    deltas = [torch.randn(n, generator=g, device=DEV) * torch.exp2(-6 - 12 * torch.rand(n, generator=g, device=DEV)) for _ in nbits_list]
+    tracked, blobs = encode_chain(lc, w0, deltas, nbits_list)
+    max_lens = [lcb1_reader.parse_header(b.cpu().numpy())["max_len"] for b in blobs]
+    assert max(max_lens) > 7 and min(max_lens) <= 7, max_lens      # both kernels take part
+    restored = w0.clone()
+    assert lc.lc_decode_many(blobs, restored) == sum(b.numel() for b in blobs)
+    assert np.array_equal(bits(restored.cpu().numpy()), bits(oracle_restore(w0, blobs)))
+    assert torch.equal(restored.view(torch.int32), tracked.view(torch.int32))
+
+
+def test_fused_restore_uneven_chunks(lc):
+    """Most chunks unchanged, one dense chunk per blob: where it lies, the payloads of the sweep's blobs
+    exceed the LDS area (sized to 1.1 x the sum of the blobs' average chunk payloads) and are read from
+    memory instead."""
+    nchunks = 24
+    n = nchunks * 16384 + 100
+    g = torch.Generator(device=DEV); g.manual_seed(78)
+    w0 = 0.05 * torch.randn(n, generator=g, device=DEV)
+    deltas = []
+    for t in range(5):
+        d = torch.zeros(n, device=DEV)
+        lo = (5 * t + 1) * 16384
+        d[lo - 50:lo + 16384 + 50] = 1e-3 * torch.randn(16384 + 100, generator=g, device=DEV)
+        deltas.append(d)
+    tracked, blobs = encode_chain(lc, w0, deltas, [3] * 5)
+    # payload words per chunk, from the offset tables
+    words = []
+    for b in blobs:
+        h = b.cpu().numpy()
+        off = h[512:512 + 4 * (nchunks + 2)].view(np.uint32).astype(np.int64)
+        words.append(np.diff(off) - 32)
+    words = np.array(words)                             # [blob, chunk]
+    area_words = 1.1 * (words.mean(axis=1) + 6).sum()
+    assert words[:, :nchunks].sum(axis=0).max() > area_words + 64, "no chunk overflows: the test misses its path"
+    restored = w0.clone()
+    lc.lc_decode_many(blobs, restored)
+    assert np.array_equal(bits(restored.cpu().numpy()), bits(oracle_restore(w0, blobs)))
+
+
+def test_fused_restore_stream_damage_matches_oracle(lc):
+    """A flipped payload bit is found, if at all, during the sweep: same verdict as the oracle's decoder, and
+    where both accept the blob, the same weights."""
+    n = 4 * 16384
+    w0, tracked, blobs = make_chain(lc, n, 4, seed=31, nbits=3)
+    for k, byte in enumerate((600, 1200, 2500, 4000)):
+        damaged = [b.clone() for b in blobs]
+        nchunks = lcb1_reader.parse_header(blobs[k].cpu().numpy())["num_chunks"]
+        at = 512 + (4 * (nchunks + 1) + 15) // 16 * 16 + 128 + byte    # inside the first chunk's payload
+        damaged[k][at] ^= 0x10
+        ref = w0.cpu().numpy()
+        ok = True
+        for b in damaged:
+            try:
+                orc.decode(b.cpu().numpy(), ref)
+            except orc.OracleError as e:
+                assert e.status == 4
+                ok = False
+                break
+        rec = w0.clone()
+        if ok:
+            lc.lc_decode_many(damaged, rec)
+            assert np.array_equal(bits(rec.cpu().numpy()), bits(ref))
+        else:
+            with pytest.raises(lc.LcError) as e:
+                lc.lc_decode_many(damaged, rec)
+            assert e.value.status == lc.ERR_BAD_BLOB
+
+
+FUSED_WIDE = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+from paper_2009_13003_amd import lc
+from oracle import lc_oracle as orc
+n = 5 * 16384 + 999
+g = torch.Generator(device="cuda:0"); g.manual_seed(5)
+w0 = 0.05 * torch.randn(n, generator=g, device="cuda:0")
+tracked, w, blobs = w0.clone(), w0.clone(), []
+out = lc.alloc_out(n, 3, "cuda:0")
+for t in range(15):
+    w = w + 1e-4 * torch.randn(n, generator=g, device="cuda:0") * (torch.rand(n, generator=g, device="cuda:0") < 0.3)
+    size = lc.lc_encode(w, tracked, 3, out); blobs.append(out[:size].clone()); lc.lc_decode(blobs[-1], tracked)
+for count in (5, 6, 7, 8, 15):
+    rec = w0.clone(); lc.lc_decode_many(blobs[:count], rec)
+    ref = w0.cpu().numpy()
+    for b in blobs[:count]: orc.decode(b.cpu().numpy(), ref)
+    assert np.array_equal(rec.cpu().numpy().view(np.uint32), ref.view(np.uint32)), count
+prof_on = lc.lc_profile(True); rec = w0.clone(); lc.lc_decode_many(blobs[:8], rec); p = lc.lc_profile_read(); lc.lc_profile(False)
+assert p["k_decode_fused"][1] == 1, p                  # all 8 blobs in one sweep
+print("ok")
+"""
+
+
+def test_fused_restore_eight_blobs_per_sweep():
+    """With the occupancy floor lowered (a launch-shape knob read once per process, hence the child process)
+    a sweep takes up to 8 blobs: every width of the fused kernel against the oracle."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, LC_TUNE_FUSED_MIN_WAVES_PER_CU="2")
+    r = subprocess.run([sys.executable, "-c", FUSED_WIDE % root], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
