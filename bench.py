@@ -117,6 +117,12 @@ def run(job, steps, warmup):
         if name in alg:
             ach = alg[name] * job.n / 1e9 / (per_step_ms / 1e3)
             ent.update(alg_bytes_per_elem=round(alg[name], 4), achieved_GBps=round(ach, 1), frac=round(ach / HBM_PEAK_GBPS, 4))
+            # k_decode does not write rows in which nothing changed, so on sparse updates it moves fewer bytes than
+            # the formula (frac can pass 1); the counter-based traffic, where a summary is committed, is what moved
+            tr = traffic_from_profiles(name, job.name)
+            if tr is not None:
+                per_launch_ms = per_step_ms / max(1, launches // steps)
+                ent.update(traffic_bytes_per_launch=tr, traffic_GBps=round(tr / 1e9 / (per_launch_ms / 1e3), 1))
         kernels[name] = ent
     return dict(ms_per_step=1e3 * total / steps, value=gb / (total / steps),
                 encode_GBps=gb / (enc / steps), decode_GBps=gb / (dec / steps),
@@ -210,6 +216,7 @@ def main():
     ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--chain-steps", type=int, default=32, help="checkpoints in the config-4 chain leg (0 = skip)")
+    ap.add_argument("--chain-only", action="store_true", help="run only the config-4 chain leg and print its result")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain elementwise copy kernel of known size (553,430,176 bytes read and "
                          "written per launch): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -230,6 +237,10 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate": "elementwise add, out-of-place", "bytes_read_per_launch": 4 * src.numel(),
                           "bytes_written_per_launch": 4 * src.numel(), "launches": 5}))
+        return
+
+    if args.chain_only:
+        print(json.dumps(chain_leg(dev, args.chain_steps)))
         return
 
     job = Job(args.workload, dev)
