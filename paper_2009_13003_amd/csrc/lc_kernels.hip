@@ -255,18 +255,20 @@ __global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits) {
 // bucket's largest and smallest member) are tracked on the way.
 constexpr int kMmCopies = 32;       // LDS copies of the per-symbol extremes, one per lane of a half wave
 
+constexpr u32 kStageRows = 32;      // code words per lane that a chunk gathers in LDS before they go to its slot
+
 struct PackLds {
     uint8_t sym8[512];               // bucket -> symbol << 3
     u32 codelen[kMaxSym];            // (code << 5) | len
     uint2 pair[256];                 // (symbol a, symbol b) -> {code of a followed by b, its length}
     u32 mn[kMaxSym * kMmCopies], mx[kMaxSym * kMmCopies];   // extremes of the delta bit patterns per symbol
+    alignas(16) u32 stage[kStageRows * kW];                 // word k of lane l at [64 k + l], as in the slot
 };
 
 // chunk_bits[c] = payload bits of chunk c; group_words[g] = record words of chunks 64g .. 64g+63
 // (integer atomics: the sums do not depend on the order of arrival).
-__device__ __forceinline__ void finish_lane(u32* slot, u32* chunk_bits, u32* group_words, u32 c, u64 acc, u32 nb, u32 nw) {
+__device__ __forceinline__ void finish_lane_sizes(u32* slot, u32* chunk_bits, u32* group_words, u32 c, u32 nb, u32 nw) {
     const u32 lane = lane_id();
-    if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
     const u32 bits = 32 * nw + nb;
     reinterpret_cast<uint16_t*>(slot)[lane] = (uint16_t)bits;
     const u32 total = wave_sum32(bits);
@@ -303,7 +305,8 @@ __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const
             }
         }
     }
-    finish_lane(slot, chunk_bits, group_words, c, acc, nb, nw);
+    if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
+    finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
 }
 
 template <bool ROWCHK>
@@ -340,9 +343,13 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
         u32* lane_words = slot + kLaneBitsWords + lane;
         u64 acc = 0;
         u32 nb = 0, nw = 0;                       // bits waiting in acc, words written
+        // Lanes fill their words at different times; gathering them in LDS and storing whole rows at
+        // the end of the chunk turns many partial-line stores into a few full ones.
         auto flush = [&]() {
             if (nb >= 32) {
-                lane_words[nw * kW] = (u32)(acc >> (nb - 32));
+                const u32 word = (u32)(acc >> (nb - 32));
+                if (nw < kStageRows) L.stage[nw * kW + lane] = word;
+                else lane_words[nw * kW] = word;
                 ++nw; nb -= 32;
             }
         };
@@ -393,7 +400,21 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
             }
             group(A1, B1); group(A1 + 4, B1 + 4);
         }
-        finish_lane(slot, chunk_bits, group_words, c, acc, nb, nw);
+        // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
+        if (nb > 0) {
+            const u32 word = (u32)(acc << (32 - nb));
+            if (nw < kStageRows) L.stage[nw * kW + lane] = word;
+            else lane_words[nw * kW] = word;
+        }
+        u32 rows = min(nw + (nb > 0 ? 1u : 0u), kStageRows);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) rows = max(rows, (u32)__shfl_xor(rows, d, 64));
+        {
+            const uint4* src = reinterpret_cast<const uint4*>(L.stage);
+            uint4* dst = reinterpret_cast<uint4*>(slot + kLaneBitsWords);
+            for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
+        }
+        finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
     }
 }
 
