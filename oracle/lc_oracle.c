@@ -301,9 +301,8 @@ static void write_header(uint8_t* out, uint64_t n, int nbits, const lco_model* M
 }
 
 /*
- * Algorithm 1 lines 4-6 for one checkpoint.  Returns the blob size in bytes, or
- * -(status).  On NONFINITE the first 512 bytes of out hold a header whose status
- * field says so (if cap allows).
+ * The blob of one checkpoint for a finished model M (kept set, representatives,
+ * counts, code lengths and codes).  Returns the blob size in bytes.
  *
  * Element order inside chunk c: lane l = 0..63 owns, in this order, elements
  * c*C + r*256 + l*4 + v for r = 0..63, v = 0..3 that are < n.  A lane's codes
@@ -311,12 +310,8 @@ static void write_header(uint8_t* out, uint64_t n, int nbits, const lco_model* M
  * gaps; the payload is zero-padded to a whole 32-bit word.  A chunk record is
  * the 64 lane bit-lengths (u16 each) followed by the payload.
  */
-int64_t lco_encode(const float* w, const float* wref, uint64_t n, int nbits,
-                   uint8_t* out, uint64_t cap) {
-    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || (n && (!w || !wref))) return -LCO_BADARG;
-    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
-    lco_model M; int st = build_model(w, wref, n, nbits, &M);
-    if (st == LCO_NONFINITE) { write_header(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+static int64_t write_blob(const float* w, const float* wref, uint64_t n, int nbits, const lco_model* M,
+                          uint8_t* out, uint64_t cap) {
     uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
     /* bits are OR-ed in below, so everything past the header starts at zero */
     memset(out + LCO_HEADER, 0, lco_encode_bound(n, nbits) - LCO_HEADER);
@@ -332,9 +327,9 @@ int64_t lco_encode(const float* w, const float* wref, uint64_t n, int nbits,
                 uint64_t i = c * LCO_C + (uint64_t)r * (LCO_W * LCO_V) + l * LCO_V + v;
                 if (i >= n) continue;
                 uint32_t b = f2u(delta_of(w[i], wref[i])) >> 23;
-                uint32_t s = M.sym_of_bucket[b];
-                if ((uint64_t)(payload - out) + 4 * ((p + M.len[s] + 31) / 32) > cap) return -LCO_OUT_TOO_SMALL;
-                for (int k = M.len[s] - 1; k >= 0; --k) put_bit(payload, p++, (M.code[s] >> k) & 1u);
+                uint32_t s = M->sym_of_bucket[b];
+                if ((uint64_t)(payload - out) + 4 * ((p + M->len[s] + 31) / 32) > cap) return -LCO_OUT_TOO_SMALL;
+                for (int k = M->len[s] - 1; k >= 0; --k) put_bit(payload, p++, (M->code[s] >> k) & 1u);
             }
             put16(rec + 2 * l, (uint32_t)(p - start));
         }
@@ -342,8 +337,76 @@ int64_t lco_encode(const float* w, const float* wref, uint64_t n, int nbits,
     }
     put32(out + LCO_HEADER + 4 * nchunks, (uint32_t)word_off);
     uint64_t total = area + 4 * word_off;
-    write_header(out, n, nbits, &M, nchunks, total, LCO_OK);
+    write_header(out, n, nbits, M, nchunks, total, LCO_OK);
     return (int64_t)total;
+}
+
+/*
+ * Algorithm 1 lines 4-6 for one checkpoint.  Returns the blob size in bytes, or
+ * -(status).  On NONFINITE the first 512 bytes of out hold a header whose status
+ * field says so (if cap allows).
+ */
+int64_t lco_encode(const float* w, const float* wref, uint64_t n, int nbits,
+                   uint8_t* out, uint64_t cap) {
+    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || (n && (!w || !wref))) return -LCO_BADARG;
+    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
+    lco_model M; int st = build_model(w, wref, n, nbits, &M);
+    if (st == LCO_NONFINITE) { write_header(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+    return write_blob(w, wref, n, nbits, &M, out, cap);
+}
+
+/*
+ * Section 3.2, "Huffman Code Table Caching": the code table of an earlier checkpoint
+ * is reused when the buckets stay the same.  Reading taken here (the paper re-sorts the
+ * buckets by population first, which needs this checkpoint's populations before any code
+ * is written; here the cached assignment of lengths to symbols is reused unchanged, so
+ * that codes can be written while the populations are still being counted):
+ *
+ *   The cache holds the kept set and the code lengths of the last blob encoded with it.
+ *   It is used for this checkpoint iff it is valid, was made with the same nbits, its
+ *   lengths are a complete prefix code (Kraft sum 1, or a single symbol of length 1),
+ *   this checkpoint's kept set (priority promotion on this delta's populations) is
+ *   the cached one, and exactly the symbols with a cached code occur.  Then the blob is
+ *   that of lco_encode with the cached lengths in place of this delta's Huffman lengths:
+ *   same quantized values, same counts and representatives, a valid but possibly longer
+ *   coding.  Otherwise the blob is exactly lco_encode's.  Either way the cache afterwards
+ *   holds this blob's kept set and lengths; on an error it is left alone.
+ *   *used (may be NULL) = 1 if the cached table was used.
+ */
+typedef struct { uint32_t valid, nbits, K, pad; uint32_t kept[LCO_SLOTS]; uint32_t len[LCO_SLOTS]; } lco_cache;
+
+int64_t lco_encode_cached(const float* w, const float* wref, uint64_t n, int nbits,
+                          uint8_t* out, uint64_t cap, lco_cache* cache, int* used) {
+    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || !cache || (n && (!w || !wref))) return -LCO_BADARG;
+    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
+    if (used) *used = 0;
+    lco_model M; int st = build_model(w, wref, n, nbits, &M);
+    if (st == LCO_NONFINITE) { write_header(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+    int ok = cache->valid == 1 && cache->nbits == (uint32_t)nbits && cache->K == (uint32_t)M.K;
+    if (ok) {
+        uint32_t kraft = 0; int active = 0;
+        for (int j = 0; j <= M.K; ++j) {
+            uint32_t l = cache->len[j];
+            if (l > 15) { ok = 0; break; }
+            if (l) { kraft += 1u << (15 - l); ++active; }
+            if (j < M.K && cache->kept[j] != M.kept[j]) ok = 0;
+            if ((l > 0) != (M.cnt[j] > 0)) ok = 0;
+        }
+        if (active >= 2 && kraft != (1u << 15)) ok = 0;
+        if (active == 1 && kraft != (1u << 14)) ok = 0;
+    }
+    if (ok) {
+        for (int j = 0; j <= M.K; ++j) M.len[j] = (uint8_t)cache->len[j];
+        lco_canonical_codes(M.len, M.K + 1, M.code);
+        if (used) *used = 1;
+    }
+    int64_t r = write_blob(w, wref, n, nbits, &M, out, cap);
+    if (r < 0) return r;
+    memset(cache, 0, sizeof *cache);
+    cache->valid = 1; cache->nbits = (uint32_t)nbits; cache->K = (uint32_t)M.K;
+    for (int j = 0; j < M.K; ++j) cache->kept[j] = M.kept[j];
+    for (int j = 0; j <= M.K; ++j) cache->len[j] = M.len[j];
+    return r;
 }
 
 /*

@@ -49,6 +49,8 @@ def lib():
         L.lco_encode_bound.argtypes = [u64, i32]
         L.lco_encode.restype = i64
         L.lco_encode.argtypes = [vp, vp, u64, i32, vp, u64]
+        L.lco_encode_cached.restype = i64
+        L.lco_encode_cached.argtypes = [vp, vp, u64, i32, vp, u64, vp, vp]
         L.lco_decode.restype = i64
         L.lco_decode.argtypes = [vp, u64, vp, u64]
         L.lco_accounting.restype = i32
@@ -134,6 +136,29 @@ def encode(w, w_ref, nbits, cap=None):
         err.header = out[:512].copy()
         raise err
     return out[:r].copy()
+
+
+CACHE_WORDS = 36    # valid, nbits, K, pad, kept[16], len[16]: uint32 each
+
+
+def new_cache():
+    """An empty table cache for encode_cached."""
+    return np.zeros(CACHE_WORDS, np.uint32)
+
+
+def encode_cached(w, w_ref, nbits, cache):
+    """Section 3.2 table caching: returns (blob, used_cache); `cache` (from new_cache) is updated in place."""
+    w, w_ref = _f32(w), _f32(w_ref)
+    assert w.size == w_ref.size and cache.dtype == np.uint32 and cache.size == CACHE_WORDS
+    cap = encode_bound(w.size, min(max(nbits, 1), 4))
+    out = np.zeros(max(cap, 1), np.uint8)
+    used = ctypes.c_int(0)
+    r = lib().lco_encode_cached(_p(w), _p(w_ref), w.size, nbits, _p(out), cap, _p(cache), ctypes.byref(used))
+    if r < 0:
+        err = OracleError(-r)
+        err.header = out[:512].copy()
+        raise err
+    return out[:r].copy(), bool(used.value)
 
 
 def decode(blob, w_ref):

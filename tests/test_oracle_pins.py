@@ -474,3 +474,136 @@ def test_bad_arguments():
         with pytest.raises(orc.OracleError) as e:
             orc.encode(w, w_ref, nb)
         assert e.value.status == orc.BADARG
+
+
+# ---------------------------------------------------------------- table caching (Section 3.2)
+def _drift_pair(n, seed, scale2=1.0, extra=None):
+    """Two successive deltas with the same spread of magnitudes (so the same kept set), and the states."""
+    rng = np.random.RandomState(seed)
+    w0 = (0.05 * rng.randn(n)).astype(np.float32)
+    d1 = (1e-3 * rng.laplace(size=n)).astype(np.float32)
+    d2 = (1e-3 * scale2 * rng.laplace(size=n)).astype(np.float32)
+    # pin the top of the range so both deltas have the same largest exponents, whatever the draw
+    for d in (d1, d2):
+        d[:4] = np.float32([0.02, -0.02, 0.011, -0.011])
+    if extra is not None:
+        d2[7] = extra
+    return w0, d1, d2
+
+
+def _chain_two(w0, d1, d2, nbits):
+    """Regular blobs and cached blobs of two successive checkpoints (each against the recovered state)."""
+    cache = orc.new_cache()
+    ref = w0.copy()
+    w1 = (ref + d1).astype(np.float32)
+    b1 = orc.encode(w1, ref, nbits)
+    c1, used1 = orc.encode_cached(w1, ref, nbits, cache)
+    cache_after_1 = cache.copy()
+    orc.decode(b1, ref)
+    w2 = (w1 + d2).astype(np.float32)
+    b2 = orc.encode(w2, ref, nbits)
+    c2, used2 = orc.encode_cached(w2, ref, nbits, cache)
+    return dict(b1=b1, c1=c1, used1=used1, cache1=cache_after_1, b2=b2, c2=c2, used2=used2, cache2=cache.copy(),
+                ref1=ref, w2=w2)
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_cached_encode_first_call_is_plain_encode_and_fills_the_cache(nbits):
+    w0, d1, d2 = _drift_pair(3 * lcb1_reader.C + 77, seed=nbits)
+    r = _chain_two(w0, d1, d2, nbits)
+    assert not r["used1"] and np.array_equal(r["b1"], r["c1"])
+    h = lcb1_reader.parse_header(r["b1"])
+    c = r["cache1"]
+    assert c[0] == 1 and c[1] == nbits and c[2] == h["K"]
+    assert [int(x) for x in c[4:4 + h["K"]]] == [s["bucket"] for s in h["slots"][:h["K"]]]
+    assert [int(x) for x in c[20:20 + h["K"] + 1]] == [s["len"] for s in h["slots"][:h["K"] + 1]]
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_cached_encode_hit_same_values_cached_lengths(nbits):
+    """Same kept set, same occurring symbols: the blob carries the cached lengths, and an independent reader
+    finds in it the very symbols, counts and representatives of the plain blob; its payload is
+    sum(count * cached length) bits; restoring from it gives the same weights bit for bit."""
+    w0, d1, d2 = _drift_pair(3 * lcb1_reader.C + 77, seed=10 + nbits, scale2=0.8)
+    r = _chain_two(w0, d1, d2, nbits)
+    assert r["used2"]
+    hp, sym_plain, _, _ = lcb1_reader.read(r["b2"])
+    hc, sym_cached, lane_bits_cached, _ = lcb1_reader.read(r["c2"])
+    K = hp["K"]
+    assert hc["K"] == K and hc["n"] == hp["n"] and hc["k_E"] == hp["k_E"]
+    for j in range(K + 1):
+        assert hc["slots"][j]["bucket"] == hp["slots"][j]["bucket"]
+        assert hc["slots"][j]["rep_bits"] == hp["slots"][j]["rep_bits"]
+        assert hc["slots"][j]["cnt"] == hp["slots"][j]["cnt"]
+        assert hc["slots"][j]["len"] == int(r["cache1"][20 + j])           # the lengths of checkpoint 1
+    assert np.array_equal(sym_plain, sym_cached)
+    bits_expected = sum(hc["slots"][j]["cnt"] * int(r["cache1"][20 + j]) for j in range(K + 1))
+    assert int(sum(lb.sum() for lb in lane_bits_cached)) == bits_expected
+    assert r["c2"].size >= r["b2"].size                                     # Huffman lengths are optimal for these counts
+    if nbits >= 3:      # here this delta's own Huffman lengths differ from the cached ones, so the test can tell them apart
+        assert [s["len"] for s in hc["slots"]] != [s["len"] for s in hp["slots"]] and r["c2"].size > r["b2"].size
+    a, b = r["ref1"].copy(), r["ref1"].copy()
+    orc.decode(r["b2"], a); orc.decode(r["c2"], b)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.array_equal(r["cache2"], r["cache1"])                          # same table stays cached
+
+
+def test_cached_encode_misses():
+    n, nbits = 2 * lcb1_reader.C + 5, 3
+    # a new, larger exponent appears: the kept set moves, the cache must not be used
+    w0, d1, d2 = _drift_pair(n, seed=3, extra=np.float32(0.3))
+    r = _chain_two(w0, d1, d2, nbits)
+    assert not r["used2"] and np.array_equal(r["b2"], r["c2"])
+    h = lcb1_reader.parse_header(r["c2"])
+    assert [int(x) for x in r["cache2"][4:4 + h["K"]]] == [s["bucket"] for s in h["slots"][:h["K"]]]   # refreshed
+    # the merged bucket stops occurring (every delta lands in a kept bucket): the cached code for it has no user
+    rng = np.random.RandomState(5)
+    w0 = (0.05 * rng.randn(n)).astype(np.float32)
+    mags = np.float32([0.02, 0.011, 0.006, 0.003])
+    d1 = (rng.choice(mags, n) * rng.choice(np.float32([1, -1]), n)).astype(np.float32)
+    d1[::3] = 0
+    d2 = (rng.choice(mags, n) * rng.choice(np.float32([1, -1]), n)).astype(np.float32)
+    # make the deltas exact in fp32 against the recovered state: work on a zero state
+    w0[:] = 0
+    cache = orc.new_cache()
+    b1, u1 = orc.encode_cached(d1, w0, 4, cache)
+    ref = w0.copy(); orc.decode(b1, ref)
+    w2 = (ref + d2).astype(np.float32)
+    b2, u2 = orc.encode_cached(w2, ref, 4, cache)
+    assert not u1 and not u2 and np.array_equal(b2, orc.encode(w2, ref, 4))
+    # another nbits: miss
+    w0, d1, d2 = _drift_pair(n, seed=4)
+    cache = orc.new_cache()
+    orc.encode_cached((w0 + d1).astype(np.float32), w0, 3, cache)
+    b, u = orc.encode_cached((w0 + d1).astype(np.float32), w0, 2, cache)
+    assert not u and np.array_equal(b, orc.encode((w0 + d1).astype(np.float32), w0, 2))
+    # the same checkpoint again with the right nbits: hit, and identical to the plain blob (same lengths)
+    b, u = orc.encode_cached((w0 + d1).astype(np.float32), w0, 2, cache)
+    assert u and np.array_equal(b, orc.encode((w0 + d1).astype(np.float32), w0, 2))
+
+
+def test_cached_encode_rejects_a_damaged_cache():
+    """A cache whose lengths are not a complete prefix code is not used, whatever else matches."""
+    n, nbits = lcb1_reader.C + 9, 3
+    w0, d1, d2 = _drift_pair(n, seed=6)
+    w1 = (w0 + d1).astype(np.float32)
+    cache = orc.new_cache()
+    plain, _ = orc.encode_cached(w1, w0, nbits, cache)
+    good = cache.copy()
+    for damage in ("len", "valid", "kept"):
+        c = good.copy()
+        if damage == "len":
+            j = int(np.argmax(c[20:36])); c[20 + j] += 1          # Kraft sum drops below 1
+        elif damage == "valid":
+            c[0] = 2
+        else:
+            c[4] ^= 1
+        b, u = orc.encode_cached(w1, w0, nbits, c)
+        assert not u and np.array_equal(b, plain), damage
+        assert np.array_equal(c, good), damage                      # and it is repaired
+    # non-finite delta: error, cache untouched
+    bad = w1.copy(); bad[3] = np.inf
+    c = good.copy()
+    with pytest.raises(orc.OracleError) as e:
+        orc.encode_cached(bad, w0, nbits, c)
+    assert e.value.status == 2 and np.array_equal(c, good)
