@@ -131,6 +131,30 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
                    void* out, void* stream);
 
 /*
+ * lc_encode with a code table cache (Section 3.2, "Huffman Code Table Caching": the table of an
+ * earlier checkpoint is reused while the buckets stay the same).  Here the reuse also saves the
+ * first of lc_encode's two sweeps over w and w_ref: the cached table is applied while this
+ * checkpoint's bucket populations are still being counted, and the coding is kept only if the
+ * counts confirm it.
+ *   cache  device memory, LC_CACHE_BYTES, 16-byte aligned, owned by the caller; all zero = empty.
+ *          Holds the kept buckets and the code lengths of the last blob encoded with it.
+ *   used   host pointer or NULL; receives 1 if the blob carries the cached table, else 0.
+ * The cached table is used iff it is valid and was made with the same nbits, this checkpoint's
+ * kept set (priority promotion on this delta's bucket populations) is the cached one, and
+ * exactly the symbols that have a cached code occur.  The blob is then lc_encode's blob with
+ * the cached code lengths in place of this delta's own Huffman lengths: the same kept buckets,
+ * counts and representatives, hence the same restored weights, in a valid and at most slightly
+ * longer coding.  (The paper re-sorts the buckets by population before reusing the table; that
+ * needs the populations before the first code is written, i.e. the sweep this call saves, so
+ * the cached assignment is reused as it is.)  Otherwise the blob is exactly lc_encode's.  Either
+ * way the cache afterwards describes this blob; on an error it is left as it was.
+ * Other arguments, return value and errors as lc_encode; cache NULL or misaligned: LC_ERR_BADARG.
+ */
+#define LC_CACHE_BYTES 256
+lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits,
+                          void* out, void* cache, int* used, void* stream);
+
+/*
  * Algorithm 1 line 7 / Section 3 (C1): w_ref[i] += representative(symbol_i) in one
  * fp32 add; elements whose symbol is the merged (zero) bucket keep their exact bit
  * pattern.  `blob` is a device pointer to an LCB1 blob (16-byte aligned) whose header

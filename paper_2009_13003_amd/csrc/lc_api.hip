@@ -26,6 +26,7 @@ struct DeviceState {
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
+static_assert(sizeof(TableCache) <= LC_CACHE_BYTES, "LC_CACHE_BYTES too small");
 static_assert(sizeof(((HostResult*)0)->bytes) / sizeof(unsigned long long) >= LC_MAX_MANY, "HostResult too small");
 HostResult* g_pinned = nullptr;  // mapped pinned host memory the kernels write their outcome to
 HostResult* g_pinned_dev = nullptr;   // the same memory as the device sees it
@@ -36,7 +37,7 @@ double g_prof_ms[kNumSlots];
 uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
-const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize",
+const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize", "k_spec_table", "k_spec_sweep",
                                            "k_dec_check", "k_decode", "k_decode_many", "k_decode_fused"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
@@ -137,7 +138,14 @@ int lc_set_workspace(void* dev_ws, size_t bytes) {
     return LC_OK;
 }
 
-lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
+}  // extern "C"
+
+namespace {
+// lc_encode (cache == nullptr: two sweeps) and lc_encode_cached (one sweep that counts and, when the
+// cache holds a usable table, codes with it; k_table confirms or voids that, and only then does the
+// second sweep have anything to do).
+lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, TableCache* cache, int* used,
+                     void* stream) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
     if (n && (!w || !w_ref || misaligned(w, 4) || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -155,18 +163,38 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, vo
     // call did not run to its end, is cleared first.
     if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, s); }
     ds->clean = nullptr;
-    { Timed t(kSlotHist, s);     launch_hist(w, w_ref, n, ws, ds->tune, s); }
-    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, s); }
+    if (cache) {
+        { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
+        { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    } else {
+        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, ws, ds->tune, s);
+    }
+    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, s); }
     { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, &g_pinned_dev->enc, group_words, n, nbits, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, &g_pinned_dev->enc, group_words, cache, n, nbits, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
     ds->clean = ws;
-    const int slots[] = {kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize};
-    collect(slots, 5);
+    const int slots[] = {cache ? kSlotSpecTable : kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecSweep};
+    collect(slots, cache ? 6 : 5);
+    if (used) *used = (int)g_pinned->enc.used_cache;
     if (g_pinned->enc.status != LC_OK) return -(lc_ssize)g_pinned->enc.status;
     return (lc_ssize)g_pinned->enc.bytes;
+}
+}  // namespace
+
+extern "C" {
+
+lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
+    return encode_impl(w, w_ref, n, nbits, out, nullptr, nullptr, stream);
+}
+
+lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, int* used,
+                          void* stream) {
+    if (used) *used = 0;
+    if (!cache || misaligned(cache, 16)) return -LC_ERR_BADARG;
+    return encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), used, stream);
 }
 
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {

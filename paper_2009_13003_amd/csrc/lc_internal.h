@@ -51,7 +51,15 @@ struct DecSet {
 struct Result {
     uint64_t bytes;
     uint32_t status;
-    uint32_t pad;
+    uint32_t used_cache;     // lc_encode_cached: 1 if the blob carries the cached code table
+};
+
+// Caller-owned device memory of lc_encode_cached (LC_CACHE_BYTES, all-zero = empty): the kept set and
+// the code lengths of the last blob encoded with it.
+struct TableCache {
+    uint32_t valid, nbits, K, pad;
+    uint32_t kept[kMaxSym];
+    uint32_t len[kMaxSym];
 };
 
 // Lives in mapped, pinned host memory: kernels write the outcome of a call here with plain
@@ -70,7 +78,8 @@ struct Workspace {
     unsigned long long hist[512];
     uint32_t mmin[kMaxSym];
     uint32_t mmax[kMaxSym];
-    uint32_t pad0[2];
+    uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
+    uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
@@ -87,7 +96,7 @@ __host__ __device__ inline uint64_t num_chunks_of(uint64_t n) { return (n + kChu
 __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u); }
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
-enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize,
+enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecTable, kSlotSpecSweep,
             kSlotDecCheck, kSlotDecode, kSlotDecodeMany, kSlotDecodeFused, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
@@ -106,13 +115,16 @@ struct Tuning {
 // Launchers (lc_kernels.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s);
 void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s);
-void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s);
+void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s);
+void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
+void launch_spec_sweep(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+                       uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
                  uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint64_t n, int nbits,
-                     hipStream_t s);
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
+                     uint64_t n, int nbits, hipStream_t s);
 struct BlobList { const uint8_t* p[kMaxSets]; };
 // Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, uint64_t max_total, Workspace* ws,

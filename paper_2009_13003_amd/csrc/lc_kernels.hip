@@ -71,7 +71,7 @@ __device__ __forceinline__ void clear_encode_state(Workspace* ws, u32* group_wor
     for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
     for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
     if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
-    if (tid == 0) ws->total_words = 0;
+    if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; }
 }
 
 __global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups) {
@@ -157,8 +157,13 @@ struct TableLds {
     u64 node_w[kMaxSym];
 };
 
-__global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits) {
+// When the sweep before it coded speculatively with a cached table (ws->spec), the kernel also decides
+// whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
+// cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
+// if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
+__global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
     __shared__ TableLds S;
+    __shared__ u32 s_reuse;
     const u32 lane = lane_id();
     const bool active = threadIdx.x < kW;
     const u32 kmax = (1u << nbits) - 1;
@@ -187,35 +192,46 @@ __global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits) {
         for (u32 j = 0; j < K; ++j) kept_total += S.cnt[j];
         S.cnt[K] = n - kept_total;
         const u32 msym = K + 1;
+        u32 max_len = 0;
+        bool reuse = false;
+        if (ws->spec) {
+            reuse = !nonfinite && T.K == K;
+            for (u32 j = 0; j < K && reuse; ++j) reuse = T.kept[j] == S.kept[j];
+            for (u32 j = 0; j < msym && reuse; ++j) reuse = ((T.codelen[j] & 31) != 0) == (S.cnt[j] != 0);
+            if (reuse) for (u32 j = 0; j < msym; ++j) { S.len[j] = T.codelen[j] & 31; if (S.len[j] > max_len) max_len = S.len[j]; }
+        }
+        s_reuse = reuse;
+        ws->spec_ok = reuse;
         // leaves in ascending (count, symbol) order
         u32 nl = 0;
-        for (u32 sy = 0; sy < msym; ++sy) {
-            if (S.cnt[sy] == 0) continue;
-            u32 p = nl++;
-            while (p > 0 && S.cnt[S.leaf[p - 1]] > S.cnt[sy]) { S.leaf[p] = S.leaf[p - 1]; --p; }
-            S.leaf[p] = sy;
-        }
-        u32 max_len = 0;
-        if (nl == 1) { S.len[S.leaf[0]] = 1; max_len = 1; }
-        else if (nl >= 2) {
-            // two queues: sorted leaves and joined nodes in creation order (their weights never
-            // decrease); on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
-            u32 li = 0, qi = 0, ni = 0;
-            for (u32 k = 0; k + 1 < nl; ++k) {
-                u32 pick[2]; u64 wsum = 0;
-                for (int q = 0; q < 2; ++q) {
-                    const bool take_leaf = li < nl && (qi >= ni || S.cnt[S.leaf[li]] <= S.node_w[qi]);
-                    if (take_leaf) { pick[q] = S.leaf[li]; wsum += S.cnt[S.leaf[li]]; ++li; }
-                    else { pick[q] = 16 + qi; wsum += S.node_w[qi]; ++qi; }
-                }
-                S.node_w[ni] = wsum; S.left[ni] = pick[0]; S.right[ni] = pick[1]; ++ni;
+        if (!reuse) {
+            for (u32 sy = 0; sy < msym; ++sy) {
+                if (S.cnt[sy] == 0) continue;
+                u32 p = nl++;
+                while (p > 0 && S.cnt[S.leaf[p - 1]] > S.cnt[sy]) { S.leaf[p] = S.leaf[p - 1]; --p; }
+                S.leaf[p] = sy;
             }
-            S.depth[ni - 1] = 0;
-            for (int i = (int)ni - 1; i >= 0; --i) {
-                const u32 d = S.depth[i] + 1, ch[2] = {S.left[i], S.right[i]};
-                for (int q = 0; q < 2; ++q) {
-                    if (ch[q] >= 16) S.depth[ch[q] - 16] = d;
-                    else { S.len[ch[q]] = d; if (d > max_len) max_len = d; }
+            if (nl == 1) { S.len[S.leaf[0]] = 1; max_len = 1; }
+            else if (nl >= 2) {
+                // two queues: sorted leaves and joined nodes in creation order (their weights never
+                // decrease); on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
+                u32 li = 0, qi = 0, ni = 0;
+                for (u32 k = 0; k + 1 < nl; ++k) {
+                    u32 pick[2]; u64 wsum = 0;
+                    for (int q = 0; q < 2; ++q) {
+                        const bool take_leaf = li < nl && (qi >= ni || S.cnt[S.leaf[li]] <= S.node_w[qi]);
+                        if (take_leaf) { pick[q] = S.leaf[li]; wsum += S.cnt[S.leaf[li]]; ++li; }
+                        else { pick[q] = 16 + qi; wsum += S.node_w[qi]; ++qi; }
+                    }
+                    S.node_w[ni] = wsum; S.left[ni] = pick[0]; S.right[ni] = pick[1]; ++ni;
+                }
+                S.depth[ni - 1] = 0;
+                for (int i = (int)ni - 1; i >= 0; --i) {
+                    const u32 d = S.depth[i] + 1, ch[2] = {S.left[i], S.right[i]};
+                    for (int q = 0; q < 2; ++q) {
+                        if (ch[q] >= 16) S.depth[ch[q] - 16] = d;
+                        else { S.len[ch[q]] = d; if (d > max_len) max_len = d; }
+                    }
                 }
             }
         }
@@ -240,6 +256,67 @@ __global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits) {
         const u32 sy = S.sym[b] == 0xFF ? K : S.sym[b];
         ws->table.symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
     }
+    if (active && ws->spec && !s_reuse) {          // the speculative coding is void: forget its extremes and sizes
+        for (u32 i = lane; i < ngroups; i += kW) group_words[i] = 0;
+        if (lane < kMaxSym) { ws->mmin[lane] = 0x7FFFFFu; ws->mmax[lane] = 0; }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_spec_table
+// lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
+// priority order, lengths forming a complete prefix code) into the table the sweep codes with.
+__global__ __launch_bounds__(64) void k_spec_table(Workspace* ws, const TableCache* cache, int nbits) {
+    __shared__ u32 s_ok, s_len[kMaxSym + 1], s_sym[512];
+    const u32 lane = threadIdx.x;
+    Table& T = ws->table;
+    for (u32 b = lane; b < 512; b += kW) s_sym[b] = 0xFF;
+    __syncthreads();
+    if (lane == 0) {
+        const u32 kmax = (1u << nbits) - 1, K = cache->K;
+        bool ok = cache->valid == 1 && cache->nbits == (u32)nbits && K <= kmax;
+        u32 kraft = 0, nact = 0, max_len = 0, per_len[17];
+        for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+        for (u32 j = 0; j <= kMaxSym; ++j) s_len[j] = 0;
+        if (ok) {
+            u32 prev_key = 0xFFFFFFFFu;
+            for (u32 j = 0; j < K; ++j) {
+                const u32 b = cache->kept[j], e = b & 255;
+                const u32 key = (e << 1) | (1u - ((b >> 8) & 1u));     // larger exponent first, + before -
+                if (b >= 512 || e == 0 || e == 255 || key >= prev_key) { ok = false; break; }
+                prev_key = key;
+            }
+            for (u32 j = 0; j <= K && ok; ++j) {
+                const u32 l = cache->len[j];
+                if (l > 15) { ok = false; break; }
+                s_len[j] = l;
+                if (l) { kraft += 1u << (15 - l); ++nact; per_len[l]++; if (l > max_len) max_len = l; }
+            }
+            if (nact >= 2 && kraft != (1u << 15)) ok = false;
+            if (nact == 1 && kraft != (1u << 14)) ok = false;
+        }
+        if (ok) {
+            u32 next_code[17], code = 0;
+            for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
+            for (u32 j = 0; j < kMaxSym; ++j) {
+                const u32 c = (j <= K && s_len[j]) ? next_code[s_len[j]]++ : 0;
+                T.codelen[j] = j <= K ? ((c << 5) | s_len[j]) : 0;
+                T.kept[j] = j < K ? cache->kept[j] : 0;
+                T.cnt[j] = 0;
+                if (j < K) s_sym[cache->kept[j]] = j;
+            }
+            T.K = K; T.max_len = max_len; T.k_E = 0; T.status = 0;
+        }
+        s_ok = ok;
+        ws->spec = ok; ws->spec_ok = 0;
+    }
+    __syncthreads();
+    if (s_ok) {
+        const u32 K = cache->K;
+        for (u32 b = lane; b < 512; b += kW) {
+            const u32 sy = s_sym[b] == 0xFF ? K : s_sym[b];
+            T.symlen_of_bucket[b] = (uint8_t)(sy | (s_len[sy] << 4));
+        }
+    }
 }
 
 // ----------------------------------------------------------------------------- k_pack
@@ -257,12 +334,16 @@ constexpr int kMmCopies = 32;       // LDS copies of the per-symbol extremes, on
 
 constexpr u32 kStageRows = 32;      // code words per lane that a chunk gathers in LDS before they go to its slot
 
+constexpr int kSpecCopies = 4;      // LDS copies of the bucket histogram in the speculative sweep
+
+template <bool HIST>
 struct PackLds {
     uint8_t sym8[512];               // bucket -> symbol << 3
     u32 codelen[kMaxSym];            // (code << 5) | len
     uint2 pair[256];                 // (symbol a, symbol b) -> {code of a followed by b, its length}
     u32 mn[kMaxSym * kMmCopies], mx[kMaxSym * kMmCopies];   // extremes of the delta bit patterns per symbol
     alignas(16) u32 stage[kStageRows * kW];                 // word k of lane l at [64 k + l], as in the slot
+    u32 hist[HIST ? 512 * kSpecCopies : 1];                 // bucket populations (speculative sweep only)
 };
 
 // chunk_bits[c] = payload bits of chunk c; group_words[g] = record words of chunks 64g .. 64g+63
@@ -279,8 +360,9 @@ __device__ __forceinline__ void finish_lane_sizes(u32* slot, u32* chunk_bits, u3
 }
 
 // Any size, any alignment: guarded scalar loads, one symbol per look-up.
+template <bool HIST, bool PACK>
 __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
-                                              u32* slot, u32* chunk_bits, u32* group_words, u32 c, PackLds& L) {
+                                              u32* slot, u32* chunk_bits, u32* group_words, u32 c, PackLds<HIST>& L) {
     const u32 lane = lane_id();
     const u64 base = (u64)c * kChunk;
     const u32 mm = lane & (kMmCopies - 1);
@@ -292,6 +374,8 @@ __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const
         for (int v = 0; v < 4; ++v) {
             if (idx + v < n) {
                 const u32 u = delta_bits(w[idx + v], w_ref[idx + v]);
+                if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+                if (!PACK) continue;
                 const u32 sy = L.sym8[u >> 23] >> 3;
                 const u32 cl = L.codelen[sy];
                 atomicMin(&L.mn[sy * kMmCopies + mm], u);
@@ -299,20 +383,21 @@ __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const
                 acc = (acc << (cl & 31)) | (cl >> 5);
                 nb += cl & 31;
             }
-            if ((v & 1) && nb >= 32) {
+            if (PACK && (v & 1) && nb >= 32) {
                 slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
                 ++nw; nb -= 32;
             }
         }
     }
+    if (!PACK) return;
     if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
     finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
 }
 
-template <bool ROWCHK>
+template <bool ROWCHK, bool HIST, bool PACK>
 __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
                                           u32* prov, u32 slot_words, u32* chunk_bits, u32* group_words,
-                                          u32 nchunks, bool aligned, u32 K8, PackLds& L) {
+                                          u32 nchunks, bool aligned, u32 K8, PackLds<HIST>& L) {
     constexpr int PF = 8;
     const u32 lane = lane_id(), G = gridDim.x;
     const u32 mm = lane & (kMmCopies - 1);
@@ -328,7 +413,7 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
     for (; c < nchunks; c += G) {
         u32* slot = prov + (u64)c * slot_words;
         if (!fast(c)) {
-            pack_chunk_plain(w, w_ref, n, slot, chunk_bits, group_words, c, L);
+            pack_chunk_plain<HIST, PACK>(w, w_ref, n, slot, chunk_bits, group_words, c, L);
             if (fast(c + G)) {
                 const float4* pw = rows_of(w, c + G); const float4* pr = rows_of(w_ref, c + G);
 #pragma unroll
@@ -363,6 +448,11 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
                 u[4 * k + 0] = delta_bits(a[k].x, b[k].x); u[4 * k + 1] = delta_bits(a[k].y, b[k].y);
                 u[4 * k + 2] = delta_bits(a[k].z, b[k].z); u[4 * k + 3] = delta_bits(a[k].w, b[k].w);
             }
+            if (HIST) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+            }
+            if (!PACK) return;
 #pragma unroll
             for (int i = 0; i < 16; ++i) t[i] = L.sym8[u[i] >> 23];
             uint2 p[8];
@@ -400,6 +490,7 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
             }
             group(A1, B1); group(A1 + 4, B1 + 4);
         }
+        if (!PACK) continue;
         // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
         if (nb > 0) {
             const u32 word = (u32)(acc << (32 - nb));
@@ -418,13 +509,8 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
     }
 }
 
-__global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
-                                             u32 slot_words, u32 nchunks, int aligned) {
-    __shared__ PackLds L;
-    const u32 lane = threadIdx.x;
-    const Table& T = ws->table;
-    if (T.status != 0) return;
+template <bool HIST>
+__device__ __forceinline__ void pack_setup(PackLds<HIST>& L, const Table& T, u32 lane) {
     for (u32 i = lane; i < 512; i += 64) L.sym8[i] = (uint8_t)((T.symlen_of_bucket[i] & 15) << 3);
     if (lane < kMaxSym) L.codelen[lane] = T.codelen[lane];
     for (u32 i = lane; i < 256; i += 64) {
@@ -432,18 +518,61 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
         L.pair[i] = make_uint2(((ca >> 5) << (cb & 31)) | (cb >> 5), (ca & 31) + (cb & 31));
     }
     for (u32 i = lane; i < kMaxSym * kMmCopies; i += 64) { L.mn[i] = 0xFFFFFFFFu; L.mx[i] = 0; }
-    const u32 K = T.K;
-    __syncthreads();
-    // 31 waiting bits + 4 codes of <= 8 bits still fit the 64-bit accumulator: flush once per row
-    if (T.max_len <= 8) pack_loop<true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    else pack_loop<false>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    __syncthreads();
+}
+
+template <bool HIST>
+__device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, Workspace* ws, u32 K, u32 lane) {
     if (lane < K) {
         u32 mn = 0xFFFFFFFFu, mx = 0;
 #pragma unroll
         for (int k = 0; k < kMmCopies; ++k) { mn = min(mn, L.mn[lane * kMmCopies + k]); mx = max(mx, L.mx[lane * kMmCopies + k]); }
         if (mn <= mx) { atomicMin(&ws->mmin[lane], mn & 0x7FFFFFu); atomicMax(&ws->mmax[lane], mx & 0x7FFFFFu); }
     }
+}
+
+__global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+                                             Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                             u32 slot_words, u32 nchunks, int aligned) {
+    __shared__ PackLds<false> L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    if (T.status != 0 || ws->spec_ok != 0) return;     // nothing to code, or the speculative sweep already did
+    pack_setup(L, T, lane);
+    const u32 K = T.K;
+    __syncthreads();
+    // 31 waiting bits + 4 codes of <= 8 bits still fit the 64-bit accumulator: flush once per row
+    if (T.max_len <= 8) pack_loop<true, false, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    else pack_loop<false, false, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    __syncthreads();
+    pack_merge_extremes(L, ws, K, lane);
+}
+
+// ----------------------------------------------------------------------------- k_spec_sweep
+// lc_encode_cached: the single sweep.  Counts the bucket populations like k_hist and, when a cached
+// table is in place (ws->spec), codes every chunk with it like k_pack in the same pass over w and
+// w_ref.  k_table then either confirms the coding or voids it.
+__global__ __launch_bounds__(64) void k_spec_sweep(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+                                                   Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                                   u32 slot_words, u32 nchunks, int aligned) {
+    __shared__ PackLds<true> L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    const bool spec = ws->spec != 0;
+    for (u32 i = lane; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
+    if (spec) pack_setup(L, T, lane);
+    const u32 K = spec ? T.K : 0;
+    __syncthreads();
+    if (!spec) pack_loop<true, true, false>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, 0, L);
+    else if (T.max_len <= 8) pack_loop<true, true, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    else pack_loop<false, true, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    __syncthreads();
+    for (u32 b = lane; b < 512; b += 64) {
+        u32 sum = 0;
+#pragma unroll
+        for (int k = 0; k < kSpecCopies; ++k) sum += L.hist[b * kSpecCopies + k];
+        if (sum) atomicAdd(&ws->hist[b], (u64)sum);
+    }
+    if (spec) pack_merge_extremes(L, ws, K, lane);
 }
 
 // ----------------------------------------------------------------------------- k_place
@@ -461,7 +590,7 @@ constexpr u32 kPlaceWords = 2048;
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
 __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
-                                                  u64 n, int nbits, u32 nchunks) {
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
@@ -481,7 +610,12 @@ __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, R
         hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
         hdr[12] = status;
         if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
-        host_result->bytes = total; host_result->status = status; host_result->pad = 0;
+        host_result->bytes = total; host_result->status = status; host_result->used_cache = ws->spec_ok;
+        if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = T.K; cache->pad = 0; }
+    }
+    if (cache && ok && t < kMaxSym) {              // what this blob was coded with, for the next call
+        cache->kept[t] = t < T.K ? T.kept[t] : 0;
+        cache->len[t] = t <= T.K ? (T.codelen[t] & 31) : 0;
     }
     if (ok && t <= T.K) {
         const u32 len = T.codelen[t] & 31;
@@ -1257,8 +1391,23 @@ void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, 
     else hipLaunchKernelGGL(k_hist<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
 }
 
-void launch_table(Workspace* ws, uint64_t n, int nbits, hipStream_t s) {
-    hipLaunchKernelGGL(k_table, dim3(1), dim3(64), 0, s, ws, (u64)n, nbits);
+void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_table, dim3(1), dim3(64), 0, s, ws, (u64)n, nbits, group_words, (u32)((num_chunks_of(n) + 63) / 64));
+}
+
+void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
+    hipLaunchKernelGGL(k_spec_table, dim3(1), dim3(64), 0, s, ws, cache, nbits);
+}
+
+void launch_spec_sweep(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+                       uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
+    if (blocks > nchunks) blocks = nchunks;
+    const int al = aligned16(w) && aligned16(w_ref);
+    hipLaunchKernelGGL(k_spec_sweep, dim3((u32)blocks), dim3(64), 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov,
+                       slot_words, (u32)nchunks, al);
 }
 
 void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
@@ -1280,9 +1429,9 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                        slot_words, (u32)nchunks);
 }
 
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint64_t n, int nbits,
-                     hipStream_t s) {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, (u64)n, nbits,
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
+                     uint64_t n, int nbits, hipStream_t s) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
                        (u32)num_chunks_of(n));
 }
 

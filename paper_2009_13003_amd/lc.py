@@ -29,6 +29,8 @@ _lib.lc_set_workspace.restype = _int
 _lib.lc_set_workspace.argtypes = [_vp, _sz]
 _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
+_lib.lc_encode_cached.restype = _i64
+_lib.lc_encode_cached.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, ctypes.POINTER(_int), _vp]
 _lib.lc_decode.restype = _i64
 _lib.lc_decode.argtypes = [_vp, _vp, _u64, _vp]
 _lib.lc_decode_many.restype = _i64
@@ -93,6 +95,28 @@ def lc_encode(w, w_ref, nbits, out, stream=None, n=None):
     if r < 0:
         raise LcError(-r)
     return r
+
+
+CACHE_BYTES = 256
+
+
+def new_cache(device="cuda"):
+    """An empty code table cache for lc_encode_cached."""
+    return torch.zeros(CACHE_BYTES, dtype=torch.uint8, device=device)
+
+
+def lc_encode_cached(w, w_ref, nbits, out, cache, stream=None, n=None):
+    """lc_encode with a code table cache (a tensor from new_cache). Returns (blob size, used_cache)."""
+    n = w.numel() if n is None else n
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    assert cache.is_cuda and cache.dtype == torch.uint8 and cache.is_contiguous() and cache.numel() >= CACHE_BYTES
+    used = _int(0)
+    r = int(_lib.lc_encode_cached(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()),
+                                  ctypes.c_void_p(cache.data_ptr()), ctypes.byref(used), _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r, bool(used.value)
 
 
 def lc_decode(blob, w_ref, stream=None, n=None):

@@ -465,3 +465,90 @@ def test_fused_restore_eight_blobs_per_sweep():
     env = dict(os.environ, LC_TUNE_FUSED_MIN_WAVES_PER_CU="2")
     r = subprocess.run([sys.executable, "-c", FUSED_WIDE % root], env=env, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+
+
+# ---------------------------------------------------------------- code table caching (Section 3.2)
+def cached_step(lc, w, ref, nbits, out, cache_gpu, cache_cpu):
+    """One lc_encode_cached on both sides with their own caches; compares blob, verdict and cache."""
+    size, used = lc.lc_encode_cached(w, ref, nbits, out, cache_gpu)
+    blob_cpu, used_cpu = orc.encode_cached(w.cpu().numpy(), ref.cpu().numpy(), nbits, cache_cpu)
+    blob_gpu = out[:size].cpu().numpy()
+    assert used == used_cpu
+    assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    assert np.array_equal(cache_gpu.cpu().numpy()[:4 * orc.CACHE_WORDS].view(np.uint32), cache_cpu)
+    return out[:size].clone(), used
+
+
+@pytest.mark.parametrize("nbits,n", [(3, 9 * 16384 + 1234), (4, 5 * 16384), (2, 16384 + 3), (3, 700)])
+def test_cached_encode_chain_matches_oracle(lc, nbits, n):
+    """A chain of checkpoints through lc_encode_cached: blob, hit/miss verdict and cache content equal the
+    oracle's at every step; hits and misses both occur; the restored state equals that of plain encodes."""
+    g = torch.Generator(device=DEV); g.manual_seed(100 + nbits)
+    w = 0.05 * torch.randn(n, generator=g, device=DEV)
+    tracked = w.clone()
+    plain_tracked = w.clone()
+    out = lc.alloc_out(n, nbits, DEV)
+    out2 = lc.alloc_out(n, nbits, DEV)
+    cache_gpu, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    verdicts = []
+    for t in range(8):
+        u = torch.rand(n, generator=g, device=DEV) - 0.5
+        d = -1e-3 * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
+        d[:4] = torch.tensor([0.02, -0.02, 0.011, -0.011], device=DEV)      # same top of the range every step
+        if t == 5:
+            d[9] = 0.4                                                        # a new largest exponent: miss
+        w = w + d
+        blob, used = cached_step(lc, w, tracked, nbits, out, cache_gpu, cache_cpu)
+        verdicts.append(used)
+        # the plain encode of the same checkpoint restores the same weights
+        size2 = lc.lc_encode(w, plain_tracked, nbits, out2)
+        lc.lc_decode(blob, tracked)
+        lc.lc_decode(out2[:size2], plain_tracked)
+        assert torch.equal(tracked.view(torch.int32), plain_tracked.view(torch.int32)), t
+    assert verdicts[0] is False and verdicts[5] is False and any(verdicts[1:5]), verdicts
+
+
+def test_cached_encode_edge_cases(lc):
+    nbits, n = 3, 2 * 16384 + 99
+    w, w_ref = laplace_case(n, seed=41)
+    out = lc.alloc_out(n, nbits, DEV)
+    cache_gpu, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    cached_step(lc, w, w_ref, nbits, out, cache_gpu, cache_cpu)
+    _, used = cached_step(lc, w, w_ref, nbits, out, cache_gpu, cache_cpu)          # same checkpoint again: hit
+    assert used
+    _, used = cached_step(lc, w, w_ref, 2, out, cache_gpu, cache_cpu)              # other nbits: miss
+    assert not used
+    # unaligned inputs take the plain path of the sweep
+    buf_w, buf_r = torch.zeros(n + 4, device=DEV), torch.zeros(n + 4, device=DEV)
+    buf_w[1:1 + n] = w; buf_r[1:1 + n] = w_ref
+    cached_step(lc, buf_w[1:1 + n], buf_r[1:1 + n], 2, out, cache_gpu, cache_cpu)
+    _, used = cached_step(lc, buf_w[1:1 + n], buf_r[1:1 + n], 2, out, cache_gpu, cache_cpu)
+    assert used
+    # a damaged cache is not used, and is repaired
+    good = cache_gpu.clone()
+    for word, value in ((0, 2), (4, int(good[16:20].view(torch.int32).item()) ^ 1), (20, 9)):
+        cache_gpu.copy_(good)
+        cache_gpu.view(torch.int32)[word] = value
+        cache_cpu[:] = cache_gpu.cpu().numpy()[:4 * orc.CACHE_WORDS].view(np.uint32)
+        _, used = cached_step(lc, buf_w[1:1 + n], buf_r[1:1 + n], 2, out, cache_gpu, cache_cpu)
+        assert not used
+        assert torch.equal(cache_gpu, good)
+    # non-finite delta: error, cache untouched
+    bad = w.clone(); bad[5] = float("nan")
+    cache_gpu.copy_(good)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_cached(bad, w_ref, 2, out, cache_gpu)
+    assert e.value.status == lc.ERR_NONFINITE and torch.equal(cache_gpu, good)
+    # the call after an error, and plain encodes in between, are unaffected
+    check_case(lc, w, w_ref, 3, "plain after cached")
+    cache_cpu[:] = good.cpu().numpy()[:4 * orc.CACHE_WORDS].view(np.uint32)
+    _, used = cached_step(lc, buf_w[1:1 + n], buf_r[1:1 + n], 2, out, cache_gpu, cache_cpu)
+    assert used
+    # empty vector, and bad arguments
+    z = torch.empty(0, device=DEV)
+    c0, c0_cpu = lc.new_cache(DEV), orc.new_cache()
+    cached_step(lc, z, z, 3, lc.alloc_out(0, 3, DEV), c0, c0_cpu)
+    cached_step(lc, z, z, 3, lc.alloc_out(0, 3, DEV), c0, c0_cpu)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_cached(w, w_ref, 3, out, torch.zeros(lc.CACHE_BYTES + 16, dtype=torch.uint8, device=DEV)[4:])   # misaligned cache
+    assert e.value.status == lc.ERR_BADARG
