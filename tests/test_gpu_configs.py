@@ -72,15 +72,23 @@ def test_config4_gpt2_chain_full_size_first_steps(lc):
     tracked = chain.w0.clone()
     tracked_h = tracked.cpu().numpy()
     out = lc.alloc_out(chain.nel, chain.nbits, DEV)
+    cache_gpu, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    used_any = False
     for t in range(3):
         print("chain step", t, flush=True)
         w = chain.step()
+        # with the code table cache (Section 3.2): blob and hit/miss verdict as the oracle's
+        size_c, used = lc.lc_encode_cached(w, tracked, chain.nbits, out, cache_gpu)
+        blob_c, used_cpu = orc.encode_cached(w.cpu().numpy(), tracked_h, chain.nbits, cache_cpu)
+        assert used == used_cpu and np.array_equal(out[:size_c].cpu().numpy(), blob_c), "cached, step %d" % t
+        used_any = used_any or used
         size = lc.lc_encode(w, tracked, chain.nbits, out)
         blob_cpu = orc.encode(w.cpu().numpy(), tracked_h, chain.nbits)
         assert np.array_equal(out[:size].cpu().numpy(), blob_cpu), "step %d" % t
         lc.lc_decode(out, tracked)
         orc.decode(blob_cpu, tracked_h)
         assert np.array_equal(bits(tracked.cpu().numpy()), bits(tracked_h)), "step %d" % t
+    assert used_any                                      # step 2 finds step 1's kept set again
 
 
 def test_config5_llama7b_slices(lc):
