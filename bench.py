@@ -85,7 +85,7 @@ class Job:
         return 8.0 * (self.blob_bytes() - 512 * len(self.sl)) / self.n
 
 
-def run(job, steps, warmup):
+def run(job, steps, warmup, with_cached=True):
     """Times `steps` steps with per-kernel events off (they cost ~60 us per step), then repeats the
     same steps with the library's HIP-event timing on to get each kernel's average duration."""
     torch, lc = job.torch, job.lc
@@ -107,32 +107,9 @@ def run(job, steps, warmup):
     lc.lc_profile(False)
     gb = 4.0 * job.n / 1e9
     bits = job.mean_code_bits()
-    # Section 3.2 table caching: the same checkpoint again through lc_encode_cached (every call after the first finds
-    # its kept set and symbols in the cache, so this times the single-sweep path; the blobs equal lc_encode's)
-    caches = [lc.new_cache(job.w.device) for _ in job.sl]
-    def encode_cached():
-        used = 0
-        for k, (lo, hi) in enumerate(job.sl):
-            size, u = lc.lc_encode_cached(job.w[lo:hi], job.w_ref[lo:hi], job.nbits, job.outs[k], caches[k])
-            assert size == job.sizes[k]
-            used += int(u)
-        return used
-    encode_cached()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    hits = sum(encode_cached() for _ in range(steps))
-    t_cached = (time.perf_counter() - tc) / steps
-    lc.lc_profile(True)
-    for _ in range(steps):
-        encode_cached()
-    prof_c = lc.lc_profile_read()
-    lc.lc_profile(False)
-    sweep_ms = prof_c["k_spec_sweep"][0] / max(1, prof_c["k_spec_sweep"][1])
-    sweep_alg = (8.0 + bits / 8.0) * job.n / len(job.sl)
-    cached = dict(encode_ms=round(1e3 * t_cached, 4), encode_GBps=round(gb / t_cached, 1), hits=hits, calls=steps * len(job.sl),
-                  hbm_frac=round((8.0 + bits / 8.0) * job.n / 1e9 / t_cached / HBM_PEAK_GBPS, 4),
-                  k_spec_sweep_ms=round(sweep_ms, 4), k_spec_sweep_GBps=round(sweep_alg / 1e9 / (sweep_ms / 1e3), 1),
-                  k_spec_sweep_frac=round(sweep_alg / 1e9 / (sweep_ms / 1e3) / HBM_PEAK_GBPS, 4))
+    cached = None
+    if with_cached:
+        cached = cached_leg(job, steps, bits)
     alg = {"k_hist": 8.0, "k_pack": 8.0 + bits / 8.0, "k_decode": 8.0 + bits / 8.0}   # bytes per element
     kernels = {}
     for name, (ms, launches) in prof.items():
@@ -157,6 +134,38 @@ def run(job, steps, warmup):
                 decode_hbm_frac=(8.0 + bits / 8.0) * job.n / 1e9 / (dec / steps) / HBM_PEAK_GBPS,
                 ratio=4.0 * job.n / job.blob_bytes(), bits_per_elem=bits, blob_bytes=job.blob_bytes(), kernels=kernels,
                 encode_cached=cached)
+
+
+def cached_leg(job, steps, bits):
+    """Section 3.2 table caching: the same checkpoint again through lc_encode_cached.  Every call after the first finds
+    its kept set and symbols in the cache, so this times the single-sweep path; the blobs equal lc_encode's."""
+    torch, lc = job.torch, job.lc
+    gb = 4.0 * job.n / 1e9
+    caches = [lc.new_cache(job.w.device) for _ in job.sl]
+    def encode_cached():
+        used = 0
+        for k, (lo, hi) in enumerate(job.sl):
+            size, u = lc.lc_encode_cached(job.w[lo:hi], job.w_ref[lo:hi], job.nbits, job.outs[k], caches[k])
+            assert size == job.sizes[k]
+            used += int(u)
+        return used
+    encode_cached()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    hits = sum(encode_cached() for _ in range(steps))
+    t_cached = (time.perf_counter() - tc) / steps
+    lc.lc_profile(True)
+    for _ in range(steps):
+        encode_cached()
+    prof_c = lc.lc_profile_read()
+    lc.lc_profile(False)
+    sweep_ms = prof_c["k_spec_sweep"][0] / max(1, prof_c["k_spec_sweep"][1])
+    sweep_alg = (8.0 + bits / 8.0) * job.n / len(job.sl)
+    cached = dict(encode_ms=round(1e3 * t_cached, 4), encode_GBps=round(gb / t_cached, 1), hits=hits, calls=steps * len(job.sl),
+                  hbm_frac=round((8.0 + bits / 8.0) * job.n / 1e9 / t_cached / HBM_PEAK_GBPS, 4),
+                  k_spec_sweep_ms=round(sweep_ms, 4), k_spec_sweep_GBps=round(sweep_alg / 1e9 / (sweep_ms / 1e3), 1),
+                  k_spec_sweep_frac=round(sweep_alg / 1e9 / (sweep_ms / 1e3) / HBM_PEAK_GBPS, 4))
+    return cached
 
 
 def chain_leg(device, steps):
@@ -249,6 +258,7 @@ def main():
     ap.add_argument("--no-also", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--chain-steps", type=int, default=32, help="checkpoints in the config-4 chain leg (0 = skip)")
+    ap.add_argument("--no-cached", action="store_true", help="skip the lc_encode_cached leg")
     ap.add_argument("--chain-only", action="store_true", help="run only the config-4 chain leg and print its result")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain elementwise copy kernel of known size (553,430,176 bytes read and "
@@ -277,7 +287,7 @@ def main():
         return
 
     job = Job(args.workload, dev)
-    res = run(job, args.steps, args.warmup)
+    res = run(job, args.steps, args.warmup, not args.no_cached)
     dom = max((k for k in res["kernels"] if "achieved_GBps" in res["kernels"][k]),
               key=lambda k: res["kernels"][k]["ms_per_step"])
     kd = res["kernels"][dom]
@@ -299,7 +309,7 @@ def main():
             if name == args.workload:
                 continue
             j = Job(name, dev)
-            r = run(j, max(2, args.steps // 4) if name == "llama7b" else args.steps, 1)
+            r = run(j, max(2, args.steps // 4) if name == "llama7b" else args.steps, 1, not args.no_cached)
             also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
             also[name]["n"] = j.n
             also[name]["nbits"] = j.nbits
