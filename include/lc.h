@@ -155,6 +155,25 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
                           void* out, void* cache, int* used, void* stream);
 
 /*
+ * Asynchronous form (Section 3.2, "Asynchronous Execution": only the first step depends on the model
+ * state, the rest can run beside the next iteration).  lc_encode_async enqueues the kernels of
+ * lc_encode (cache == NULL) or lc_encode_cached (cache != NULL) on `stream` and returns at once with
+ * a ticket >= 0, or -(lc_status).  At most LC_MAX_TICKETS calls may be in flight (one more:
+ * -LC_ERR_BADARG).  w and w_ref must stay unchanged until the call has read them for the last time:
+ * lc_encode_release_inputs(ticket, other_stream) makes work enqueued on other_stream afterwards
+ * (say the optimizer step that overwrites w) wait for exactly that point, without blocking the host;
+ * it returns an lc_status.  out, and cache, belong to the call until lc_encode_wait(ticket, used)
+ * returns: it blocks until the call has finished, returns what lc_encode / lc_encode_cached would
+ * have returned (`used` may be NULL) and frees the ticket.  All calls of this library on one device
+ * share one scratch area, so the library orders each call after the asynchronous calls issued
+ * before it, whatever their streams.
+ */
+#define LC_MAX_TICKETS 16
+int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream);
+int lc_encode_release_inputs(int ticket, void* other_stream);
+lc_ssize lc_encode_wait(int ticket, int* used);
+
+/*
  * Algorithm 1 line 7 / Section 3 (C1): w_ref[i] += representative(symbol_i) in one
  * fp32 add; elements whose symbol is the merged (zero) bucket keep their exact bit
  * pattern.  `blob` is a device pointer to an LCB1 blob (16-byte aligned) whose header

@@ -22,7 +22,19 @@ struct DeviceState {
     Tuning tune;
     bool tuned = false;
     const void* clean = nullptr;  // scratch area whose encode state is known to be cleared
+    hipEvent_t last = nullptr;    // end of the latest asynchronous call on this device
+    bool pending = false;         // ... which later calls must order themselves after (they share the scratch)
 };
+
+// lc_encode_async: a call in flight.
+constexpr int kMaxTickets = 16;
+struct Ticket {
+    bool busy = false;
+    hipEvent_t inputs = nullptr;  // after the last kernel that reads w / w_ref
+    hipEvent_t done = nullptr;    // after the last kernel
+};
+Ticket g_ticket[kMaxTickets];
+static_assert(sizeof(((HostResult*)0)->enc_async) / sizeof(Result) == kMaxTickets, "one result per ticket");
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
@@ -110,6 +122,14 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
 
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+// Every call uses the device's one scratch area: work enqueued on `s` must not start before the
+// latest asynchronous call has finished with it.
+bool order_after_async(DeviceState* ds, hipStream_t s) {
+    if (!ds->pending) return true;
+    if (hipStreamWaitEvent(s, ds->last, 0) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -145,7 +165,7 @@ namespace {
 // cache holds a usable table, codes with it; k_table confirms or voids that, and only then does the
 // second sweep have anything to do).
 lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, TableCache* cache, int* used,
-                     void* stream) {
+                     void* stream, bool async) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
     if (n && (!w || !w_ref || misaligned(w, 4) || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -159,6 +179,19 @@ lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, 
     uint32_t* prov = chunk_bits + (nc + 63) / 64 * 64;
     const uint32_t slot_words = slot_words_of(nbits);
     uint8_t* o = static_cast<uint8_t*>(out);
+    int ticket = -1;
+    if (async) {
+        for (int i = 0; i < kMaxTickets && ticket < 0; ++i) if (!g_ticket[i].busy) ticket = i;
+        if (ticket < 0) return -LC_ERR_BADARG;                       // too many calls in flight
+        Ticket& tk = g_ticket[ticket];
+        if (!tk.done) {
+            if (hipEventCreateWithFlags(&tk.inputs, hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&tk.done, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); tk.inputs = tk.done = nullptr; return -LC_ERR_HIP; }
+        }
+        if (!ds->last && hipEventCreateWithFlags(&ds->last, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); ds->last = nullptr; return -LC_ERR_HIP; }
+    }
+    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
+    Result* result = async ? &g_pinned_dev->enc_async[ticket] : &g_pinned_dev->enc;
     // Every call leaves the encode state cleared behind it; a fresh scratch area, or one whose last
     // call did not run to its end, is cleared first.
     if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, s); }
@@ -171,10 +204,20 @@ lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, 
     }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, s); }
     { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, &g_pinned_dev->enc, group_words, cache, n, nbits, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, s); }
     LC_HIP(hipGetLastError());
+    if (async) {
+        LC_HIP(hipEventRecord(g_ticket[ticket].done, s));
+        LC_HIP(hipEventRecord(ds->last, s));
+        ds->pending = true;
+        ds->clean = ws;              // later calls are ordered after this one
+        g_ticket[ticket].busy = true;
+        return ticket;
+    }
     LC_HIP(hipStreamSynchronize(s));
+    ds->pending = false;             // this call was ordered after every asynchronous one
     ds->clean = ws;
     const int slots[] = {cache ? kSlotSpecTable : kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecSweep};
     collect(slots, cache ? 6 : 5);
@@ -187,14 +230,43 @@ lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, 
 extern "C" {
 
 lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
-    return encode_impl(w, w_ref, n, nbits, out, nullptr, nullptr, stream);
+    return encode_impl(w, w_ref, n, nbits, out, nullptr, nullptr, stream, false);
+}
+
+int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream) {
+    if (cache && misaligned(cache, 16)) return -LC_ERR_BADARG;
+    return (int)encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), nullptr, stream, true);
+}
+
+int lc_encode_release_inputs(int ticket, void* other_stream) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (ticket < 0 || ticket >= kMaxTickets || !g_ticket[ticket].busy) return LC_ERR_BADARG;
+    if (hipStreamWaitEvent(static_cast<hipStream_t>(other_stream), g_ticket[ticket].inputs, 0) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    return LC_OK;
+}
+
+lc_ssize lc_encode_wait(int ticket, int* used) {
+    hipEvent_t done;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (ticket < 0 || ticket >= kMaxTickets || !g_ticket[ticket].busy) return -LC_ERR_BADARG;
+        done = g_ticket[ticket].done;
+    }
+    const hipError_t e = hipEventSynchronize(done);          // not under the lock: other threads may keep calling
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_ticket[ticket].busy = false;
+    if (e != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
+    const Result r = g_pinned->enc_async[ticket];
+    if (used) *used = (int)r.used_cache;
+    if (r.status != LC_OK) return -(lc_ssize)r.status;
+    return (lc_ssize)r.bytes;
 }
 
 lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, int* used,
                           void* stream) {
     if (used) *used = 0;
     if (!cache || misaligned(cache, 16)) return -LC_ERR_BADARG;
-    return encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), used, stream);
+    return encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), used, stream, false);
 }
 
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
@@ -207,12 +279,14 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     const uint64_t epoch = ++g_epoch;
+    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = b;
     { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, lc_encode_bound(n, 4), ws, epoch, g_pinned_dev, s); }
     { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, g_pinned_dev, ds->tune, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
+    ds->pending = false;
     const int slots[] = {kSlotDecCheck, kSlotDecode};
     collect(slots, 2);
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
@@ -229,12 +303,14 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t epoch = ++g_epoch, bound = lc_encode_bound(n, 4);
+    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[t < count ? t : 0]);
     // every blob is validated (one launch, one grid row per blob) before w_ref is touched
     { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, bound, ws, epoch, g_pinned_dev, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
+    ds->pending = false;
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     uint64_t total = 0;
     for (int i = 0; i < count; ++i) total += g_pinned->bytes[i];
@@ -306,6 +382,14 @@ void lc_shutdown(void) {
         g_dev[d].user = nullptr; g_dev[d].user_bytes = 0;
     }
     if (have_cur) (void)hipSetDevice(cur);
+    for (int i = 0; i < kMaxTickets; ++i) {
+        if (g_ticket[i].done) { (void)hipEventDestroy(g_ticket[i].inputs); (void)hipEventDestroy(g_ticket[i].done); }
+        g_ticket[i] = Ticket();
+    }
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (g_dev[d].last) { (void)hipEventDestroy(g_dev[d].last); g_dev[d].last = nullptr; }
+        g_dev[d].pending = false;
+    }
     if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; g_pinned_dev = nullptr; }
     for (int d = 0; d < kMaxDevices; ++d) g_dev[d].clean = nullptr;
     if (g_ev_made) {

@@ -66,6 +66,7 @@ struct TableCache {
 // stores, and the host reads it after waiting for the stream.
 struct HostResult {
     Result enc;                                  // lc_encode: blob bytes, lc_status
+    Result enc_async[16];                        // lc_encode_async: one per ticket
     unsigned long long dec_status;               // lc_decode*: (epoch << 8) | lc_status of the worst finding
     unsigned long long bytes[kMaxSets];          // lc_decode*: total_bytes of each blob
     uint32_t max_len[kMaxSets];                  // lc_decode*: longest code of each blob

@@ -31,6 +31,12 @@ _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
 _lib.lc_encode_cached.restype = _i64
 _lib.lc_encode_cached.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, ctypes.POINTER(_int), _vp]
+_lib.lc_encode_async.restype = _int
+_lib.lc_encode_async.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, _vp]
+_lib.lc_encode_release_inputs.restype = _int
+_lib.lc_encode_release_inputs.argtypes = [_int, _vp]
+_lib.lc_encode_wait.restype = _i64
+_lib.lc_encode_wait.argtypes = [_int, ctypes.POINTER(_int)]
 _lib.lc_decode.restype = _i64
 _lib.lc_decode.argtypes = [_vp, _vp, _u64, _vp]
 _lib.lc_decode_many.restype = _i64
@@ -114,6 +120,37 @@ def lc_encode_cached(w, w_ref, nbits, out, cache, stream=None, n=None):
     used = _int(0)
     r = int(_lib.lc_encode_cached(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()),
                                   ctypes.c_void_p(cache.data_ptr()), ctypes.byref(used), _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r, bool(used.value)
+
+
+def lc_encode_async(w, w_ref, nbits, out, cache=None, stream=None, n=None):
+    """Enqueues lc_encode (or lc_encode_cached if `cache` is given) and returns a ticket at once."""
+    n = w.numel() if n is None else n
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    c = None
+    if cache is not None:
+        assert cache.is_cuda and cache.dtype == torch.uint8 and cache.is_contiguous() and cache.numel() >= CACHE_BYTES
+        c = ctypes.c_void_p(cache.data_ptr())
+    r = int(_lib.lc_encode_async(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), c, _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_encode_release_inputs(ticket, stream=None):
+    """Work enqueued on `stream` after this waits until the call has read w and w_ref for the last time."""
+    r = int(_lib.lc_encode_release_inputs(ticket, _stream(stream)))
+    if r != 0:
+        raise LcError(r)
+
+
+def lc_encode_wait(ticket):
+    """Blocks until the call has finished. Returns (blob size, used_cache)."""
+    used = _int(0)
+    r = int(_lib.lc_encode_wait(ticket, ctypes.byref(used)))
     if r < 0:
         raise LcError(-r)
     return r, bool(used.value)

@@ -552,3 +552,73 @@ def test_cached_encode_edge_cases(lc):
     with pytest.raises(lc.LcError) as e:
         lc.lc_encode_cached(w, w_ref, 3, out, torch.zeros(lc.CACHE_BYTES + 16, dtype=torch.uint8, device=DEV)[4:])   # misaligned cache
     assert e.value.status == lc.ERR_BADARG
+
+
+# ---------------------------------------------------------------- asynchronous encode (Section 3.2)
+def test_async_encode_equals_sync_and_releases_inputs(lc):
+    """lc_encode_async + lc_encode_wait give lc_encode's blob; after lc_encode_release_inputs the caller may
+    overwrite w on another stream at once (the overwrite is enqueued while the encode is still running)."""
+    n, nbits = 4096 * 16384 + 321, 3                    # 67 M elements: the encode (~0.25 ms) outlasts the host's next enqueue
+    w, w_ref = laplace_case(n, seed=51)
+    out_sync = lc.alloc_out(n, nbits, DEV)
+    size_sync = lc.lc_encode(w, w_ref, nbits, out_sync)
+    expected = out_sync[:size_sync].clone()
+    enc_stream, other = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        w_live = w.clone()
+        out = lc.alloc_out(n, nbits, DEV)
+        torch.cuda.synchronize()
+        ticket = lc.lc_encode_async(w_live, w_ref, nbits, out, stream=enc_stream)
+        lc.lc_encode_release_inputs(ticket, other)
+        with torch.cuda.stream(other):
+            w_live.add_(1.0)                            # the "optimizer step"
+        size, used = lc.lc_encode_wait(ticket)
+        torch.cuda.synchronize()
+        assert size == size_sync and not used and torch.equal(out[:size], expected), rep
+        assert torch.equal(w_live, w + 1.0)
+
+
+def test_async_encode_many_in_flight_and_mixed_with_other_calls(lc):
+    nbits = 3
+    cases = [laplace_case(16384 * k + 7 * k, seed=60 + k) for k in range(1, 7)]
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w, _ in cases]
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    torch.cuda.synchronize()
+    tickets = [lc.lc_encode_async(w, r, nbits, o, stream=streams[i % 3]) for i, ((w, r), o) in enumerate(zip(cases, outs))]
+    assert len(set(tickets)) == len(tickets)
+    # a synchronous call on yet another stream while those are in flight: ordered after them, scratch intact
+    w0, r0 = cases[0]
+    blob0 = check_case(lc, w0, r0, nbits, "sync while async in flight")
+    for t, (w, r), o in reversed(list(zip(tickets, cases, outs))):
+        size, used = lc.lc_encode_wait(t)
+        ref = orc.encode(w.cpu().numpy(), r.cpu().numpy(), nbits)
+        assert size == ref.size and np.array_equal(o[:size].cpu().numpy(), ref)
+    # with a cache: first call fills, second hits; verdict comes back through the ticket
+    w, r = cases[3]
+    cache, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    for expect_used in (False, True):
+        t = lc.lc_encode_async(w, r, nbits, outs[3], cache=cache)
+        size, used = lc.lc_encode_wait(t)
+        ref, used_cpu = orc.encode_cached(w.cpu().numpy(), r.cpu().numpy(), nbits, cache_cpu)
+        assert used == used_cpu == expect_used and np.array_equal(outs[3][:size].cpu().numpy(), ref)
+    # errors: a finished ticket cannot be waited for twice; more calls in flight than tickets
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_wait(tickets[0])
+    assert e.value.status == lc.ERR_BADARG
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_release_inputs(99)
+    assert e.value.status == lc.ERR_BADARG
+    held = [lc.lc_encode_async(w, r, nbits, outs[3]) for _ in range(16)]
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_async(w, r, nbits, outs[3])
+    assert e.value.status == lc.ERR_BADARG
+    for t in held:
+        lc.lc_encode_wait(t)
+    # non-finite delta: the error arrives at the wait
+    bad = w.clone(); bad[11] = float("inf")
+    t = lc.lc_encode_async(bad, r, nbits, outs[3])
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_wait(t)
+    assert e.value.status == lc.ERR_NONFINITE
+    check_case(lc, w, r, nbits, "after async error")
