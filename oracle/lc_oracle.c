@@ -424,6 +424,7 @@ int64_t lco_decode(const uint8_t* blob, uint64_t blob_bytes, float* wref, uint64
     if (get32(blob + 48) != LCO_OK) return -LCO_BAD_BLOB;
     uint64_t hn = get64(blob + 8); uint32_t nbits = get32(blob + 16), K = get32(blob + 20);
     if (hn != n) return -LCO_BADARG;
+    if (get32(blob + 60) != 0) return -LCO_BADARG;      /* element type of the parameters: this routine restores fp32 */
     if (nbits < 1 || nbits > 4 || K > (1u << nbits) - 1) return -LCO_BAD_BLOB;
     if (get32(blob + 24) != LCO_W || get32(blob + 28) != LCO_V || get32(blob + 32) != LCO_R) return -LCO_BAD_BLOB;
     uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);

@@ -171,6 +171,54 @@ def decode(blob, w_ref):
     return int(r)
 
 
+# ---- 16-bit parameters.  The method works on the fp32 delta (Algorithm 1 line 4), so parameters stored as bf16 or
+# fp16 are widened exactly to fp32, coded as fp32, and the restored value fl32(w_ref + rep) is rounded once, to nearest
+# even, back to the storage type.  The blob says which type it restores (header offset 60: 0 fp32, 1 bf16, 2 fp16).
+DT_F32, DT_BF16, DT_F16 = 0, 1, 2
+
+
+def widen(a, dtype):
+    """Exact conversion to float32. bf16 arrays are uint16 bit patterns, fp16 arrays are numpy float16."""
+    if dtype == DT_F32:
+        return _f32(a)
+    if dtype == DT_F16:
+        assert a.dtype == np.float16
+        return np.ascontiguousarray(a).astype(np.float32)
+    assert dtype == DT_BF16 and a.dtype == np.uint16
+    return (np.ascontiguousarray(a).astype(np.uint32) << 16).view(np.float32)
+
+
+def narrow(x, dtype):
+    """Round finite float32 values to the storage type, to nearest, ties to even."""
+    x = _f32(x)
+    if dtype == DT_F32:
+        return x
+    if dtype == DT_F16:
+        return x.astype(np.float16)
+    bits = x.view(np.uint32).astype(np.uint64)
+    return ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def encode_t(w, w_ref, nbits, dtype):
+    blob = encode(widen(w, dtype), widen(w_ref, dtype), nbits)
+    blob[60:64] = np.frombuffer(np.uint32(dtype).tobytes(), np.uint8)
+    return blob
+
+
+def decode_t(blob, w_ref, dtype):
+    """Updates w_ref (storage type array) in place; returns bytes consumed."""
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    if blob.size >= 64 and int(np.frombuffer(blob[60:64].tobytes(), np.uint32)[0]) != dtype:
+        raise OracleError(1)
+    as_f32 = blob.copy()
+    if as_f32.size >= 64:
+        as_f32[60:64] = 0
+    tmp = widen(w_ref, dtype).copy()
+    r = decode(as_f32, tmp)
+    w_ref[...] = narrow(tmp, dtype)
+    return r
+
+
 def accounting(blob):
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
     acct = np.zeros(5, np.float64)

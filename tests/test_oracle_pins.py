@@ -607,3 +607,47 @@ def test_cached_encode_rejects_a_damaged_cache():
     with pytest.raises(orc.OracleError) as e:
         orc.encode_cached(bad, w0, nbits, c)
     assert e.value.status == 2 and np.array_equal(c, good)
+
+
+# ---------------------------------------------------------------- 16-bit parameters
+def test_narrow_to_bf16_is_round_to_nearest_even():
+    """Against torch's float32 -> bfloat16 conversion (a library routine), ties included."""
+    torch = pytest.importorskip("torch")
+    rng = np.random.RandomState(1)
+    x = np.concatenate([rng.randn(20000).astype(np.float32) * np.float32(10.0) ** rng.randint(-8, 8, 20000).astype(np.float32),
+                        np.float32([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.3895314e38, 1e-40])])
+    # exact ties: low 16 bits = 0x8000, with the kept mantissa bit even and odd
+    ties = (rng.randint(0, 1 << 15, 2000).astype(np.uint32) << 16 | 0x8000).view(np.float32)
+    x = np.concatenate([x, ties[np.isfinite(ties)]])
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(orc.narrow(x, orc.DT_BF16), want)
+    assert np.array_equal(orc.widen(want, orc.DT_BF16).view(np.uint32), want.astype(np.uint32) << 16)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_16_bit_parameters_round_trip_against_torch(dtype):
+    """Restore of bf16 / fp16 parameters = storage_type(float(w_ref) + dequantized delta), checked with torch's casts."""
+    torch = pytest.importorskip("torch")
+    tdt, code = (torch.bfloat16, orc.DT_BF16) if dtype == "bf16" else (torch.float16, orc.DT_F16)
+    g = torch.Generator().manual_seed(3)
+    n, nbits = 2 * lcb1_reader.C + 333, 3
+    ref_t = (0.05 * torch.randn(n, generator=g)).to(tdt)
+    w_t = (ref_t.float() + 1e-3 * torch.randn(n, generator=g)).to(tdt)
+    raw = (lambda t: t.view(torch.int16).numpy().view(np.uint16)) if dtype == "bf16" else (lambda t: t.numpy())
+    w, ref = raw(w_t).copy(), raw(ref_t).copy()
+    blob = orc.encode_t(w, ref, nbits, code)
+    assert int(np.frombuffer(blob[60:64].tobytes(), np.uint32)[0]) == code
+    sym, dq, K, _ = orc.quantize(w_t.float().numpy(), ref_t.float().numpy(), nbits)
+    want_t = (ref_t.float() + torch.from_numpy(dq)).to(tdt)
+    zero = torch.from_numpy(sym == K)
+    want_t[zero] = ref_t[zero]                                    # the merged symbol leaves the stored value alone
+    got = ref.copy()
+    assert orc.decode_t(blob, got, code) == blob.size
+    assert np.array_equal(got.view(np.uint16), raw(want_t).view(np.uint16))
+    # the blob names its element type: restoring another type is refused
+    with pytest.raises(orc.OracleError) as e:
+        orc.decode(blob, ref_t.float().numpy().copy())
+    assert e.value.status == 1
+    with pytest.raises(orc.OracleError) as e:
+        orc.decode_t(orc.encode(w_t.float().numpy(), ref_t.float().numpy(), nbits), got, code)
+    assert e.value.status == 1
