@@ -168,6 +168,35 @@ def cached_leg(job, steps, bits):
     return cached
 
 
+def bf16_leg(device, steps):
+    """Config 3's shapes and deltas with the parameters stored as bf16 (lc_encode_t / lc_decode_t)."""
+    import torch
+    from paper_2009_13003_amd import lc, workloads
+    w, r, nbits = workloads.vgg16(device=device)
+    rb = r.to(torch.bfloat16)
+    wb = (rb.float() + (w - r)).to(torch.bfloat16)
+    del w, r
+    n = wb.numel()
+    out = lc.alloc_out(n, nbits, device)
+    rec = rb.clone()
+    for _ in range(2):
+        size = lc.lc_encode_t(wb, rb, nbits, out); lc.lc_decode_t(out, rec)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        size = lc.lc_encode_t(wb, rb, nbits, out)
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        lc.lc_decode_t(out, rec)
+    t2 = time.perf_counter()
+    enc, dec, gb = (t1 - t0) / steps, (t2 - t1) / steps, 2.0 * n / 1e9
+    bits = 8.0 * (size - 512) / n
+    return dict(n=n, nbits=nbits, dtype="bf16", encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
+                encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(2.0 * n / size, 3),
+                encode_hbm_frac=round((8.0 + bits / 8.0) * n / 1e9 / enc / HBM_PEAK_GBPS, 4),
+                decode_hbm_frac=round((4.0 + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
+
+
 def chain_leg(device, steps):
     """Config 4: `steps` successive checkpoints of the GPT-2-medium-shaped vector, each encoded against the
     recovered state and decoded into it (Algorithm 1); then the restore from u_0 (Section 3, C1) timed two
@@ -315,6 +344,8 @@ def main():
             also[name]["nbits"] = j.nbits
             del j
             torch.cuda.empty_cache()
+        also["vgg16_bf16"] = bf16_leg(dev, args.steps)
+        torch.cuda.empty_cache()
         if args.chain_steps > 0:
             also["gpt2_medium_chain"] = chain_leg(dev, args.chain_steps)
             torch.cuda.empty_cache()

@@ -164,10 +164,12 @@ namespace {
 // lc_encode (cache == nullptr: two sweeps) and lc_encode_cached (one sweep that counts and, when the
 // cache holds a usable table, codes with it; k_table confirms or voids that, and only then does the
 // second sweep have anything to do).
-lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, TableCache* cache, int* used,
-                     void* stream, bool async) {
+lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, TableCache* cache,
+                     int* used, void* stream, bool async) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
-    if (n && (!w || !w_ref || misaligned(w, 4) || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
+    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
+    if (n && (!w || !w_ref || misaligned(w, esize) || misaligned(w_ref, esize))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
     Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
@@ -198,15 +200,15 @@ lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, 
     ds->clean = nullptr;
     if (cache) {
         { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
-        { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+        { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     } else {
-        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, ws, ds->tune, s);
+        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, ds->tune, s);
     }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, s); }
-    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, s); }
     LC_HIP(hipGetLastError());
     if (async) {
         LC_HIP(hipEventRecord(g_ticket[ticket].done, s));
@@ -230,12 +232,16 @@ lc_ssize encode_impl(const float* w, const float* w_ref, uint64_t n, int nbits, 
 extern "C" {
 
 lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
-    return encode_impl(w, w_ref, n, nbits, out, nullptr, nullptr, stream, false);
+    return encode_impl(w, w_ref, n, nbits, out, LC_F32, nullptr, nullptr, stream, false);
+}
+
+lc_ssize lc_encode_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* stream) {
+    return encode_impl(w, w_ref, n, nbits, out, dtype, nullptr, nullptr, stream, false);
 }
 
 int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream) {
     if (cache && misaligned(cache, 16)) return -LC_ERR_BADARG;
-    return (int)encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), nullptr, stream, true);
+    return (int)encode_impl(w, w_ref, n, nbits, out, LC_F32, static_cast<TableCache*>(cache), nullptr, stream, true);
 }
 
 int lc_encode_release_inputs(int ticket, void* other_stream) {
@@ -266,12 +272,13 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
                           void* stream) {
     if (used) *used = 0;
     if (!cache || misaligned(cache, 16)) return -LC_ERR_BADARG;
-    return encode_impl(w, w_ref, n, nbits, out, static_cast<TableCache*>(cache), used, stream, false);
+    return encode_impl(w, w_ref, n, nbits, out, LC_F32, static_cast<TableCache*>(cache), used, stream, false);
 }
 
-lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
+lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream) {
     if (!blob || misaligned(blob, 16) || n > LC_MAX_N) return -LC_ERR_BADARG;
-    if (n && (!w_ref || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : 2))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
     Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
@@ -282,8 +289,8 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = b;
-    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, lc_encode_bound(n, 4), ws, epoch, g_pinned_dev, s); }
-    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, ws, epoch, g_pinned_dev, ds->tune, s); }
+    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, lc_encode_bound(n, 4), ws, epoch, g_pinned_dev, s); }
+    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, dtype, ws, epoch, g_pinned_dev, ds->tune, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
     ds->pending = false;
@@ -291,6 +298,10 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
     collect(slots, 2);
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     return (lc_ssize)g_pinned->bytes[0];
+}
+
+lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
+    return lc_decode_t(blob, w_ref, n, LC_F32, stream);
 }
 
 lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream) {
@@ -307,7 +318,7 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[t < count ? t : 0]);
     // every blob is validated (one launch, one grid row per blob) before w_ref is touched
-    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, bound, ws, epoch, g_pinned_dev, s); }
+    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, LC_F32, bound, ws, epoch, g_pinned_dev, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
     ds->pending = false;

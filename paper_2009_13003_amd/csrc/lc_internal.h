@@ -14,6 +14,7 @@ constexpr uint32_t kChunk = kRowElems * kR; // 16384 elements
 constexpr uint32_t kHeaderBytes = 512;
 constexpr uint32_t kLaneBitsWords = (2 * kW) / 4;   // 32 words of u16 lane lengths per chunk record
 constexpr uint32_t kMaxSym = 16;
+enum ElemType { kF32 = 0, kBF16 = 1, kF16 = 2 };   // element type of the parameter arrays (= LC_F32 ...)
 constexpr uint32_t kDecLut1Bits = 7;        // first decode table: conflict-free in LDS
 constexpr uint32_t kDecLut2Bits = 12;       // second decode table, for codes of 8..12 bits
 
@@ -115,22 +116,22 @@ struct Tuning {
 
 // Launchers (lc_kernels.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s);
-void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s);
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s);
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
-void launch_spec_sweep(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
-void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                  uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, hipStream_t s);
+                     uint64_t n, int nbits, int dtype, hipStream_t s);
 struct BlobList { const uint8_t* p[kMaxSets]; };
 // Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
-void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, uint64_t max_total, Workspace* ws,
+void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
                       uint64_t epoch, HostResult* host, hipStream_t s);
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,
+void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s);
 // Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused
 // kernel requires every code of these blobs to be at most kDecLut1Bits long.

@@ -52,14 +52,73 @@ __device__ __forceinline__ float4 load_stream(const float4* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
-template <bool FAST>
-__device__ __forceinline__ void load_row(const float* __restrict__ p, u64 idx, u64 n, float (&x)[4]) {
+// ---- element types of the parameter arrays.  The method works on the fp32 delta (Algorithm 1 line 4):
+// bf16 / fp16 parameters are widened exactly on load, and the restored value fl32(w_ref + rep) is rounded
+// once, to nearest even, on store.  Raw<DT> is what one lane holds of one row: 4 consecutive elements.
+template <int DT> struct Raw { typedef uint2 type; };
+template <> struct Raw<kF32> { typedef float4 type; };
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int DT> __device__ __forceinline__ constexpr u32 elem_bytes() { return DT == kF32 ? 4u : 2u; }
+
+// 4 consecutive elements starting at element index i (a multiple of 4, base aligned to 4 elements), non-temporal
+template <int DT>
+__device__ __forceinline__ typename Raw<DT>::type load_raw(const void* base, u64 i) {
+    if constexpr (DT == kF32) {
+        return load_stream(reinterpret_cast<const float4*>(static_cast<const float*>(base) + i));
+    } else {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(base) + i));
+        return make_uint2(v.x, v.y);
+    }
+}
+
+__device__ __forceinline__ float widen16(u32 h, bool bf16) {
+    return bf16 ? __uint_as_float(h << 16) : (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+__device__ __forceinline__ u32 narrow16(float x, bool bf16) {      // finite x, round to nearest even
+    if (bf16) { const u32 u = __float_as_uint(x); return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; }
+    return (u32)__builtin_bit_cast(unsigned short, (_Float16)x);      // v_cvt_f16_f32, round to nearest even
+}
+
+template <int DT>
+__device__ __forceinline__ void unpack(const typename Raw<DT>::type& r, float (&x)[4]) {
+    if constexpr (DT == kF32) { x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w; }
+    else {
+        x[0] = widen16(r.x & 0xFFFFu, DT == kBF16); x[1] = widen16(r.x >> 16, DT == kBF16);
+        x[2] = widen16(r.y & 0xFFFFu, DT == kBF16); x[3] = widen16(r.y >> 16, DT == kBF16);
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ float load_one(const void* base, u64 i) {
+    if constexpr (DT == kF32) return static_cast<const float*>(base)[i];
+    else return widen16(static_cast<const uint16_t*>(base)[i], DT == kBF16);
+}
+
+template <int DT>
+__device__ __forceinline__ void store_one(void* base, u64 i, float x) {
+    if constexpr (DT == kF32) static_cast<float*>(base)[i] = x;
+    else static_cast<uint16_t*>(base)[i] = (uint16_t)narrow16(x, DT == kBF16);
+}
+
+template <int DT>
+__device__ __forceinline__ void store4(void* base, u64 i, const float (&x)[4]) {
+    if constexpr (DT == kF32) {
+        *reinterpret_cast<float4*>(static_cast<float*>(base) + i) = make_float4(x[0], x[1], x[2], x[3]);
+    } else {
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + i) =
+            make_uint2(narrow16(x[0], DT == kBF16) | (narrow16(x[1], DT == kBF16) << 16),
+                       narrow16(x[2], DT == kBF16) | (narrow16(x[3], DT == kBF16) << 16));
+    }
+}
+
+template <bool FAST, int DT = kF32>
+__device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u64 n, float (&x)[4]) {
     if (FAST) {
-        const float4 t = load_stream(reinterpret_cast<const float4*>(p + idx));
-        x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+        unpack<DT>(load_raw<DT>(p, idx), x);
     } else {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? p[idx + v] : 0.0f;
+        for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? load_one<DT>(p, idx + v) : 0.0f;
     }
 }
 
@@ -85,55 +144,81 @@ __global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups) {
 // collide; merged into 64-bit global counters once per workgroup.
 constexpr int kHistCopies = 8;
 
-template <bool ALIGNED>
-__global__ __launch_bounds__(1024) void k_hist(const float* __restrict__ w, const float* __restrict__ w_ref,
+// One 16-byte unit = EPU consecutive elements (4 fp32, 8 bf16 / fp16): counting does not care which lane
+// sees which element, so every type is read in 16-byte accesses and kept as loaded until it is counted.
+template <int DT, int EPU>
+__device__ __forceinline__ void unpack_unit(const float4& t, float (&x)[EPU]) {
+    if constexpr (DT == kF32) { x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; }
+    else {
+        const u32 q[4] = {__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w)};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { x[2 * k] = widen16(q[k] & 0xFFFFu, DT == kBF16); x[2 * k + 1] = widen16(q[k] >> 16, DT == kBF16); }
+    }
+}
+
+template <bool ALIGNED, int DT, int EPU>
+__device__ __forceinline__ float4 load_unit(const void* __restrict__ p, u64 unit) {
+    if (ALIGNED) return load_stream(reinterpret_cast<const float4*>(p) + unit);
+    // whole units only, so every element is in range; assemble the same 16 bytes from element loads
+    if constexpr (DT == kF32) {
+        const float* q = static_cast<const float*>(p) + unit * 4;
+        return make_float4(q[0], q[1], q[2], q[3]);
+    } else {
+        const uint16_t* q = static_cast<const uint16_t*>(p) + unit * 8;
+        return make_float4(__uint_as_float(q[0] | ((u32)q[1] << 16)), __uint_as_float(q[2] | ((u32)q[3] << 16)),
+                           __uint_as_float(q[4] | ((u32)q[5] << 16)), __uint_as_float(q[6] | ((u32)q[7] << 16)));
+    }
+}
+
+template <bool ALIGNED, int DT>
+__global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
                                                u64 n, Workspace* ws) {
     __shared__ u32 h[512 * kHistCopies];
+    constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
     for (u32 i = tid; i < 512 * kHistCopies; i += nthr) h[i] = 0;
     __syncthreads();
     const u32 copy = tid & (kHistCopies - 1);
-    const u64 n4 = n / 4;
+    const u64 nu = n / EPU;
     const u64 stride = (u64)gridDim.x * nthr;
     u64 u = (u64)blockIdx.x * nthr + tid;
     // Batches of PF 16-byte units per thread, one batch in flight while the previous one is counted.
     constexpr int PF = 4;
-    float a0[PF][4], b0[PF][4], a1[PF][4], b1[PF][4];
-    auto fetch = [&](float (&a)[PF][4], float (&b)[PF][4], u64 at) {
+    float4 a0[PF], b0[PF], a1[PF], b1[PF];
+    auto fetch = [&](float4 (&a)[PF], float4 (&b)[PF], u64 at) {
 #pragma unroll
-        for (int k = 0; k < PF; ++k) { load_row<ALIGNED>(w, 4 * (at + k * stride), n, a[k]); load_row<ALIGNED>(w_ref, 4 * (at + k * stride), n, b[k]); }
+        for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * stride); b[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * stride); }
     };
-    auto count = [&](float (&a)[PF][4], float (&b)[PF][4]) {
+    auto count_unit = [&](const float4& a, const float4& b) {
+        float x[EPU], y[EPU];
+        unpack_unit<DT, EPU>(a, x); unpack_unit<DT, EPU>(b, y);
 #pragma unroll
-        for (int k = 0; k < PF; ++k)
+        for (int v = 0; v < EPU; ++v) atomicAdd(&h[(delta_bits(x[v], y[v]) >> 23) * kHistCopies + copy], 1u);
+    };
+    auto count = [&](float4 (&a)[PF], float4 (&b)[PF]) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) atomicAdd(&h[(delta_bits(a[k][v], b[k][v]) >> 23) * kHistCopies + copy], 1u);
+        for (int k = 0; k < PF; ++k) count_unit(a[k], b[k]);
     };
     const u64 step = PF * stride;
-    if (u + (PF - 1) * stride < n4) {
+    if (u + (PF - 1) * stride < nu) {
         fetch(a0, b0, u);
         while (true) {
-            const bool more1 = u + step + (PF - 1) * stride < n4;
+            const bool more1 = u + step + (PF - 1) * stride < nu;
             if (more1) fetch(a1, b1, u + step);
             count(a0, b0);
             u += step;
             if (!more1) break;
-            const bool more0 = u + step + (PF - 1) * stride < n4;
+            const bool more0 = u + step + (PF - 1) * stride < nu;
             if (more0) fetch(a0, b0, u + step);
             count(a1, b1);
             u += step;
             if (!more0) break;
         }
     }
-    for (; u < n4; u += stride) {
-        float a[4], b[4];
-        load_row<ALIGNED>(w, 4 * u, n, a); load_row<ALIGNED>(w_ref, 4 * u, n, b);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) atomicAdd(&h[(delta_bits(a[v], b[v]) >> 23) * kHistCopies + copy], 1u);
-    }
-    if (blockIdx.x == 0 && tid < (u32)(n - 4 * n4)) {
-        const u64 i = 4 * n4 + tid;
-        atomicAdd(&h[(delta_bits(w[i], w_ref[i]) >> 23) * kHistCopies + copy], 1u);
+    for (; u < nu; u += stride) count_unit(load_unit<ALIGNED, DT, EPU>(w, u), load_unit<ALIGNED, DT, EPU>(w_ref, u));
+    if (blockIdx.x == 0 && tid < (u32)(n - EPU * nu)) {
+        const u64 i = EPU * nu + tid;
+        atomicAdd(&h[(delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i)) >> 23) * kHistCopies + copy], 1u);
     }
     __syncthreads();
     for (u32 b = tid; b < 512; b += nthr) {
@@ -360,8 +445,8 @@ __device__ __forceinline__ void finish_lane_sizes(u32* slot, u32* chunk_bits, u3
 }
 
 // Any size, any alignment: guarded scalar loads, one symbol per look-up.
-template <bool HIST, bool PACK>
-__device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+template <bool HIST, bool PACK, int DT>
+__device__ __noinline__ void pack_chunk_plain(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                               u32* slot, u32* chunk_bits, u32* group_words, u32 c, PackLds<HIST>& L) {
     const u32 lane = lane_id();
     const u64 base = (u64)c * kChunk;
@@ -373,7 +458,7 @@ __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (idx + v < n) {
-                const u32 u = delta_bits(w[idx + v], w_ref[idx + v]);
+                const u32 u = delta_bits(load_one<DT>(w, idx + v), load_one<DT>(w_ref, idx + v));
                 if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
                 if (!PACK) continue;
                 const u32 sy = L.sym8[u >> 23] >> 3;
@@ -394,36 +479,34 @@ __device__ __noinline__ void pack_chunk_plain(const float* __restrict__ w, const
     finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
 }
 
-template <bool ROWCHK, bool HIST, bool PACK>
-__device__ __forceinline__ void pack_loop(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+template <bool ROWCHK, bool HIST, bool PACK, int DT>
+__device__ __forceinline__ void pack_loop(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                           u32* prov, u32 slot_words, u32* chunk_bits, u32* group_words,
                                           u32 nchunks, bool aligned, u32 K8, PackLds<HIST>& L) {
     constexpr int PF = 8;
     const u32 lane = lane_id(), G = gridDim.x;
     const u32 mm = lane & (kMmCopies - 1);
-    float4 A0[PF], B0[PF], A1[PF], B1[PF];
+    typedef typename Raw<DT>::type raw_t;
+    raw_t A0[PF], B0[PF], A1[PF], B1[PF];
     auto fast = [&](u32 c) { return aligned && c < nchunks && (u64)(c + 1) * kChunk <= n; };
-    auto rows_of = [&](const float* p, u32 c) { return reinterpret_cast<const float4*>(p + (u64)c * kChunk) + lane; };
+    // element index of this lane's 4 elements in row r of chunk c
+    auto at = [&](u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane) * kV; };
     u32 c = blockIdx.x;
     if (fast(c)) {
-        const float4* pw = rows_of(w, c); const float4* pr = rows_of(w_ref, c);
 #pragma unroll
-        for (int k = 0; k < PF; ++k) { A0[k] = load_stream(pw + k * kW); B0[k] = load_stream(pr + k * kW); }
+        for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c, k)); B0[k] = load_raw<DT>(w_ref, at(c, k)); }
     }
     for (; c < nchunks; c += G) {
         u32* slot = prov + (u64)c * slot_words;
         if (!fast(c)) {
-            pack_chunk_plain<HIST, PACK>(w, w_ref, n, slot, chunk_bits, group_words, c, L);
+            pack_chunk_plain<HIST, PACK, DT>(w, w_ref, n, slot, chunk_bits, group_words, c, L);
             if (fast(c + G)) {
-                const float4* pw = rows_of(w, c + G); const float4* pr = rows_of(w_ref, c + G);
 #pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_stream(pw + k * kW); B0[k] = load_stream(pr + k * kW); }
+                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c + G, k)); B0[k] = load_raw<DT>(w_ref, at(c + G, k)); }
             }
             continue;
         }
         // ---- a full, aligned chunk whose first PF rows are already in A0/B0
-        const float4* pw = rows_of(w, c); const float4* pr = rows_of(w_ref, c);
-        const float4* qw = rows_of(w, c + G); const float4* qr = rows_of(w_ref, c + G);
         const bool next_fast = fast(c + G);
         u32* lane_words = slot + kLaneBitsWords + lane;
         u64 acc = 0;
@@ -441,12 +524,14 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
         // Four rows at a time: all table look-ups of the 16 elements are issued together, so the
         // LDS latency is paid twice per group instead of three times per row; only the shift/or
         // chain that grows the lane's bit string is serial.
-        auto group = [&](const float4* a, const float4* b) {
+        auto group = [&](const raw_t* a, const raw_t* b) {
             u32 u[16], t[16];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                u[4 * k + 0] = delta_bits(a[k].x, b[k].x); u[4 * k + 1] = delta_bits(a[k].y, b[k].y);
-                u[4 * k + 2] = delta_bits(a[k].z, b[k].z); u[4 * k + 3] = delta_bits(a[k].w, b[k].w);
+                float xa[4], xb[4];
+                unpack<DT>(a[k], xa); unpack<DT>(b[k], xb);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) u[4 * k + v] = delta_bits(xa[v], xb[v]);
             }
             if (HIST) {
 #pragma unroll
@@ -479,14 +564,14 @@ __device__ __forceinline__ void pack_loop(const float* __restrict__ w, const flo
         };
         for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
 #pragma unroll
-            for (int k = 0; k < PF; ++k) { A1[k] = load_stream(pw + (r0 + PF + k) * kW); B1[k] = load_stream(pr + (r0 + PF + k) * kW); }
+            for (int k = 0; k < PF; ++k) { A1[k] = load_raw<DT>(w, at(c, r0 + PF + k)); B1[k] = load_raw<DT>(w_ref, at(c, r0 + PF + k)); }
             group(A0, B0); group(A0 + 4, B0 + 4);
             if (r0 + 2 * PF < kR) {
 #pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_stream(pw + (r0 + 2 * PF + k) * kW); B0[k] = load_stream(pr + (r0 + 2 * PF + k) * kW); }
+                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c, r0 + 2 * PF + k)); B0[k] = load_raw<DT>(w_ref, at(c, r0 + 2 * PF + k)); }
             } else if (next_fast) {
 #pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_stream(qw + k * kW); B0[k] = load_stream(qr + k * kW); }
+                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c + G, k)); B0[k] = load_raw<DT>(w_ref, at(c + G, k)); }
             }
             group(A1, B1); group(A1 + 4, B1 + 4);
         }
@@ -530,7 +615,8 @@ __device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, Workspace*
     }
 }
 
-__global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+template <int DT>
+__global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                              Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
                                              u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<false> L;
@@ -541,8 +627,8 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
     const u32 K = T.K;
     __syncthreads();
     // 31 waiting bits + 4 codes of <= 8 bits still fit the 64-bit accumulator: flush once per row
-    if (T.max_len <= 8) pack_loop<true, false, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    else pack_loop<false, false, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    if (T.max_len <= 8) pack_loop<true, false, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    else pack_loop<false, false, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
     __syncthreads();
     pack_merge_extremes(L, ws, K, lane);
 }
@@ -551,7 +637,8 @@ __global__ __launch_bounds__(64) void k_pack(const float* __restrict__ w, const 
 // lc_encode_cached: the single sweep.  Counts the bucket populations like k_hist and, when a cached
 // table is in place (ws->spec), codes every chunk with it like k_pack in the same pass over w and
 // w_ref.  k_table then either confirms the coding or voids it.
-__global__ __launch_bounds__(64) void k_spec_sweep(const float* __restrict__ w, const float* __restrict__ w_ref, u64 n,
+template <int DT>
+__global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                                    Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
                                                    u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<true> L;
@@ -562,9 +649,9 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const float* __restrict__ w, 
     if (spec) pack_setup(L, T, lane);
     const u32 K = spec ? T.K : 0;
     __syncthreads();
-    if (!spec) pack_loop<true, true, false>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, 0, L);
-    else if (T.max_len <= 8) pack_loop<true, true, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    else pack_loop<false, true, true>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    if (!spec) pack_loop<true, true, false, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, 0, L);
+    else if (T.max_len <= 8) pack_loop<true, true, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    else pack_loop<false, true, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
     __syncthreads();
     for (u32 b = lane; b < 512; b += 64) {
         u32 sum = 0;
@@ -590,7 +677,7 @@ constexpr u32 kPlaceWords = 2048;
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
 __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
-                                                  TableCache* cache, u64 n, int nbits, u32 nchunks) {
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
@@ -609,6 +696,7 @@ __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, R
         hdr[6] = kW; hdr[7] = kV; hdr[8] = kR;
         hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
         hdr[12] = status;
+        hdr[15] = dtype;
         if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
         host_result->bytes = total; host_result->status = status; host_result->used_cache = ws->spec_ok;
         if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = T.K; cache->pad = 0; }
@@ -740,7 +828,7 @@ __device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u6
 }
 
 __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u64 n, u64 max_total, Workspace* ws,
-                                                   u32 nchunks, u64 epoch, HostResult* host) {
+                                                   u32 nchunks, u64 epoch, HostResult* host, u32 dtype) {
     const u32 set = first + blockIdx.y, host_slot = set;     // one grid row per blob
     const uint8_t* blob = blobs.p[set];
     __shared__ u32 hdr[kHeaderBytes / 4];
@@ -752,10 +840,12 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
     const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
     const u64 area = chunk_area_of(nchunks);
     const bool head_ok = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 &&
-                         hn == n && hdr[9] == nchunks && total >= area && total <= max_total && ((total - area) & 3) == 0;
+                         hn == n && hdr[15] == dtype && hdr[9] == nchunks && total >= area && total <= max_total &&
+                         ((total - area) & 3) == 0;
     if (!head_ok) {
         if (blockIdx.x == 0 && t == 0) {
-            const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 && hn != n;
+            const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 &&
+                                    (hn != n || hdr[15] != dtype);       // a sound blob for another vector or element type
             raise_status(ws, host, epoch, n_mismatch ? 1u : 4u);
             host->bytes[host_slot] = 0; host->max_len[host_slot] = 0;
         }
@@ -890,9 +980,9 @@ struct BitReader {
     }
 };
 
-template <bool FAST, bool LV2, bool STAGED>
+template <bool FAST, bool LV2, bool STAGED, int DT>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
-                                            float* __restrict__ w_ref, u64 n, Workspace* ws, HostResult* host, u32 c,
+                                            void* __restrict__ w_ref, u64 n, Workspace* ws, HostResult* host, u32 c,
                                             const DecLds& L, u32 P1, u32 P2, u32 K, u64 epoch) {
     const u32 lane = lane_id();
     BitReader<STAGED> br;
@@ -905,7 +995,7 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
         const u64 idx = base + (u64)r * kRowElems + lane * kV;
         if (!FAST && idx >= n) break;
         float x[4];
-        load_row<FAST>(w_ref, idx, n, x);
+        load_row<FAST, DT>(w_ref, idx, n, x);
         u32 smin = K;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -923,18 +1013,18 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
             if ((v & 1) && br.avail <= 32) br.refill();
         }
         if (FAST) {
-            if (__any(smin < K)) *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+            if (__any(smin < K)) store4<DT>(w_ref, idx, x);
         } else {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
+            for (int v = 0; v < 4; ++v) if (idx + v < n) store_one<DT>(w_ref, idx + v, x[v]);
         }
     }
     const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
     if (__any(used != lane_bits) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
-template <bool FAST, bool LV2>
-__device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
+template <bool FAST, bool LV2, int DT>
+__device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                              Workspace* ws, HostResult* host, u32 c, DecLds& L, u32 P1, u32 P2, u32 K, u64 area, u64 epoch) {
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
@@ -960,14 +1050,15 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, f
             }
             L.payload[wv][i] = q;
         }
-        decode_rows<FAST, LV2, true>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
+        decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
                                      w_ref, n, ws, host, c, L, P1, P2, K, epoch);
     } else {
-        decode_rows<FAST, LV2, false>(gw, nwords, o, lane_bits, w_ref, n, ws, host, c, L, P1, P2, K, epoch);
+        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, ws, host, c, L, P1, P2, K, epoch);
     }
 }
 
-__global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, float* __restrict__ w_ref, u64 n,
+template <int DT>
+__global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                                 Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
     __shared__ DecLds L;
     // if the check kernel found something, touch nothing
@@ -996,10 +1087,10 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
-                else decode_chunk<true, false>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
             } else {
-                decode_chunk<false, true>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                decode_chunk<false, true, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
             }
         }
     }
@@ -1380,15 +1471,27 @@ void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s) {
     hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)kMaxGroups);
 }
 
-void launch_hist(const float* w, const float* w_ref, uint64_t n, Workspace* ws, const Tuning& tune, hipStream_t s) {
+static inline bool aligned_rows(const void* p, int dtype) {     // 4 consecutive elements per access
+    return (reinterpret_cast<uintptr_t>(p) & (dtype == kF32 ? 15 : 7)) == 0;
+}
+
+template <int DT>
+static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32 blocks, u32 threads, hipStream_t s) {
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+}
+
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s) {
     if (n == 0) return;
     const u32 threads = tune.hist_threads;
-    u64 blocks = (n / 4 + 4 * threads - 1) / (4 * threads);
+    const u64 units = n / (dtype == kF32 ? 4 : 8);                 // 16-byte units
+    u64 blocks = (units + 4 * threads - 1) / (4 * threads);
     const u64 cap = (u64)tune.num_cu * tune.hist_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist<true>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
-    else hipLaunchKernelGGL(k_hist<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
+    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
+    else launch_hist_t<kF32>(w, w_ref, n, ws, (u32)blocks, threads, s);
 }
 
 void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s) {
@@ -1399,26 +1502,30 @@ void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStr
     hipLaunchKernelGGL(k_spec_table, dim3(1), dim3(64), 0, s, ws, cache, nbits);
 }
 
-void launch_spec_sweep(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
     if (blocks > nchunks) blocks = nchunks;
-    const int al = aligned16(w) && aligned16(w_ref);
-    hipLaunchKernelGGL(k_spec_sweep, dim3((u32)blocks), dim3(64), 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov,
-                       slot_words, (u32)nchunks, al);
+    const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
+    const dim3 grid((u32)blocks), wg(64);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_spec_sweep<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_spec_sweep<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_spec_sweep<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
 }
 
-void launch_pack(const float* w, const float* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits,
+void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                  uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
     if (blocks > nchunks) blocks = nchunks;
-    const int al = aligned16(w) && aligned16(w_ref);
-    hipLaunchKernelGGL(k_pack, dim3((u32)blocks), dim3(64), 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov,
-                       slot_words, (u32)nchunks, al);
+    const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
+    const dim3 grid((u32)blocks), wg(64);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
 }
 
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
@@ -1430,17 +1537,17 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
 }
 
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, hipStream_t s) {
+                     uint64_t n, int nbits, int dtype, hipStream_t s) {
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
-                       (u32)num_chunks_of(n));
+                       (u32)num_chunks_of(n), (u32)dtype);
 }
 
-void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, uint64_t max_total, Workspace* ws,
+void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
                       uint64_t epoch, HostResult* host, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
     hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
-                       ws, (u32)nchunks, (u64)epoch, host);
+                       ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
 }
 
 void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
@@ -1491,15 +1598,18 @@ void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_r
     }
 }
 
-void launch_decode(const uint8_t* blob, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch, HostResult* host,
+void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (nchunks + 3) / 4;
     const u64 cap = (u64)tune.num_cu * tune.decode_blocks_per_cu;
     if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_decode, dim3((u32)blocks), dim3(256), 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks,
-                       (int)aligned16(w_ref), (u64)epoch, host);
+    const dim3 grid((u32)blocks), wg(256);
+    const int al = aligned_rows(w_ref, dtype);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
 }
 
 }  // namespace lc

@@ -29,6 +29,10 @@ _lib.lc_set_workspace.restype = _int
 _lib.lc_set_workspace.argtypes = [_vp, _sz]
 _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
+_lib.lc_encode_t.restype = _i64
+_lib.lc_encode_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp]
+_lib.lc_decode_t.restype = _i64
+_lib.lc_decode_t.argtypes = [_vp, _vp, _u64, _int, _vp]
 _lib.lc_encode_cached.restype = _i64
 _lib.lc_encode_cached.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, ctypes.POINTER(_int), _vp]
 _lib.lc_encode_async.restype = _int
@@ -98,6 +102,36 @@ def lc_encode(w, w_ref, nbits, out, stream=None, n=None):
     assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
     assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
     r = int(_lib.lc_encode(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
+
+
+def _dev_any(t):
+    assert t.is_cuda and t.dtype in DTYPES and t.is_contiguous(), "need a contiguous CUDA float32 / bfloat16 / float16 tensor"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def lc_encode_t(w, w_ref, nbits, out, stream=None, n=None):
+    """lc_encode for float32, bfloat16 or float16 parameters (w and w_ref of the same dtype)."""
+    n = w.numel() if n is None else n
+    assert w.dtype == w_ref.dtype
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    r = int(_lib.lc_encode_t(_dev_any(w), _dev_any(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), DTYPES[w.dtype], _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_decode_t(blob, w_ref, stream=None, n=None):
+    """lc_decode for float32, bfloat16 or float16 parameters."""
+    n = w_ref.numel() if n is None else n
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    r = int(_lib.lc_decode_t(ctypes.c_void_p(blob.data_ptr()), _dev_any(w_ref), n, DTYPES[w_ref.dtype], _stream(stream)))
     if r < 0:
         raise LcError(-r)
     return r

@@ -622,3 +622,56 @@ def test_async_encode_many_in_flight_and_mixed_with_other_calls(lc):
         lc.lc_encode_wait(t)
     assert e.value.status == lc.ERR_NONFINITE
     check_case(lc, w, r, nbits, "after async error")
+
+
+# ---------------------------------------------------------------- bf16 / fp16 parameters
+def raw16(t):
+    """The oracle's view of a 16-bit tensor: uint16 bit patterns for bf16, numpy float16 for fp16."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+    return t.cpu().numpy().copy()
+
+
+@pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("n,nbits,offset", [(5 * 16384 + 777, 3, 0), (16384, 4, 0), (3 * 16384 + 5, 2, 1), (100, 3, 3), (0, 3, 0)])
+def test_16_bit_parameters_match_oracle(lc, tdt, n, nbits, offset):
+    """bf16 / fp16 parameters: blob byte-identical to the oracle's, restored 16-bit values bit-identical;
+    `offset` elements of misalignment take the guarded paths."""
+    code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+    g = torch.Generator(device=DEV); g.manual_seed(200 + n % 97 + nbits)
+    buf_r = (0.05 * torch.randn(n + 8, generator=g, device=DEV)).to(tdt)
+    buf_w = (buf_r.float() + 2e-3 * torch.randn(n + 8, generator=g, device=DEV)).to(tdt)
+    buf_w[::7] = buf_r[::7]                                              # some exactly unchanged
+    w, w_ref = buf_w[offset:offset + n], buf_r[offset:offset + n]
+    out = lc.alloc_out(n, nbits, DEV); out.fill_(0x5A)
+    size = lc.lc_encode_t(w, w_ref, nbits, out)
+    blob_cpu = orc.encode_t(raw16(w), raw16(w_ref), nbits, code)
+    blob_gpu = out[:size].cpu().numpy()
+    assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    rec = buf_r.clone()
+    assert lc.lc_decode_t(out, rec[offset:offset + n]) == size
+    ref_h = raw16(w_ref)
+    orc.decode_t(blob_cpu, ref_h, code)
+    assert np.array_equal(raw16(rec[offset:offset + n]).view(np.uint16), ref_h.view(np.uint16))
+    assert torch.equal(rec[:offset].view(torch.int16), buf_r[:offset].view(torch.int16))          # nothing outside the range
+    assert torch.equal(rec[offset + n:].view(torch.int16), buf_r[offset + n:].view(torch.int16))
+
+
+def test_element_type_mismatch_is_refused(lc):
+    n, nbits = 16384 + 9, 3
+    w, w_ref = laplace_case(n, seed=70)
+    out = lc.alloc_out(n, nbits, DEV)
+    lc.lc_encode(w, w_ref, nbits, out)
+    as_bf16 = w_ref.to(torch.bfloat16)
+    before = as_bf16.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_t(out, as_bf16)                        # an fp32 blob into bf16 parameters
+    assert e.value.status == lc.ERR_BADARG and torch.equal(as_bf16.view(torch.int16), before.view(torch.int16))
+    lc.lc_encode_t(w.to(torch.bfloat16), as_bf16, nbits, out)
+    rec = w_ref.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode(out, rec)                              # a bf16 blob into fp32 parameters
+    assert e.value.status == lc.ERR_BADARG and torch.equal(rec, w_ref)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many([out], rec)
+    assert e.value.status == lc.ERR_BADARG and torch.equal(rec, w_ref)
