@@ -73,18 +73,23 @@ struct HostResult {
     uint32_t max_len[kMaxSets];                  // lc_decode*: longest code of each blob
 };
 
-// Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] (u32, at a
-// fixed place so that it can be left cleared from one call to the next), chunk_bits[num_chunks]
-// (u32, padded to 256 bytes) and one slot of slot_words_of(nbits) 32-bit words per chunk.
-struct Workspace {
+// What the encode kernels of one vector share: bucket populations, extremes of the kept buckets, the
+// code table.  One per call; a batched call (one table per tensor) has one per tensor.
+struct EncState {
     unsigned long long hist[512];
     uint32_t mmin[kMaxSym];
     uint32_t mmax[kMaxSym];
     uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
     uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
-    unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     unsigned long long total_words;
     Table table;
+};
+
+// Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] (u32, at a
+// fixed place so that it can be left cleared from one call to the next), chunk_bits[num_chunks]
+// (u32, padded to 256 bytes) and one slot of slot_words_of(nbits) 32-bit words per chunk.
+struct Workspace : EncState {
+    unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     DecSet dec_set[kMaxSets];        // one per blob of the call
 };
 

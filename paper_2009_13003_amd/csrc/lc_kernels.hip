@@ -126,14 +126,14 @@ __device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u6
 // Brings the scratch state to what every encode call expects to find (and leaves behind):
 // zero bucket counts, empty extremes, zero group sums and arrival counters.  Only launched
 // for a fresh scratch area or after a call that did not run to its end.
-__device__ __forceinline__ void clear_encode_state(Workspace* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
+__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
     for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
     for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
     if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
     if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; }
 }
 
-__global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups) {
+__global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups) {
     clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
 }
 
@@ -172,7 +172,7 @@ __device__ __forceinline__ float4 load_unit(const void* __restrict__ p, u64 unit
 
 template <bool ALIGNED, int DT>
 __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
-                                               u64 n, Workspace* ws) {
+                                               u64 n, EncState* ws) {
     __shared__ u32 h[512 * kHistCopies];
     constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
@@ -246,7 +246,7 @@ struct TableLds {
 // whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
 // cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
 // if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
-__global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+__global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
     __shared__ TableLds S;
     __shared__ u32 s_reuse;
     const u32 lane = lane_id();
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(64) void k_table(Workspace* ws, u64 n, int nbits, u
 // ----------------------------------------------------------------------------- k_spec_table
 // lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
 // priority order, lengths forming a complete prefix code) into the table the sweep codes with.
-__global__ __launch_bounds__(64) void k_spec_table(Workspace* ws, const TableCache* cache, int nbits) {
+__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCache* cache, int nbits) {
     __shared__ u32 s_ok, s_len[kMaxSym + 1], s_sym[512];
     const u32 lane = threadIdx.x;
     Table& T = ws->table;
@@ -433,23 +433,34 @@ struct PackLds {
 
 // chunk_bits[c] = payload bits of chunk c; group_words[g] = record words of chunks 64g .. 64g+63
 // (integer atomics: the sums do not depend on the order of arrival).
-__device__ __forceinline__ void finish_lane_sizes(u32* slot, u32* chunk_bits, u32* group_words, u32 c, u32 nb, u32 nw) {
+// One chunk's work as the coding loop sees it: the vector it belongs to, its index there, and where its
+// code words, its bit count and its group's word sum go.
+struct ChunkRef {
+    const void* w; const void* w_ref;
+    u64 n;
+    u32 c;
+    u32* slot; u32* bits_at; u32* group_at;
+    bool valid, fast;            // fast: a full chunk of aligned arrays
+};
+
+__device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u32 nw) {
     const u32 lane = lane_id();
     const u32 bits = 32 * nw + nb;
-    reinterpret_cast<uint16_t*>(slot)[lane] = (uint16_t)bits;
+    reinterpret_cast<uint16_t*>(ch.slot)[lane] = (uint16_t)bits;
     const u32 total = wave_sum32(bits);
     if (lane == 0) {
-        chunk_bits[c] = total;
-        atomicAdd(&group_words[c >> 6], kLaneBitsWords + ((total + 31) >> 5));
+        *ch.bits_at = total;
+        atomicAdd(ch.group_at, kLaneBitsWords + ((total + 31) >> 5));
     }
 }
 
 // Any size, any alignment: guarded scalar loads, one symbol per look-up.
 template <bool HIST, bool PACK, int DT>
-__device__ __noinline__ void pack_chunk_plain(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
-                                              u32* slot, u32* chunk_bits, u32* group_words, u32 c, PackLds<HIST>& L) {
+__device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& L) {
     const u32 lane = lane_id();
-    const u64 base = (u64)c * kChunk;
+    const void* __restrict__ w = ch.w; const void* __restrict__ w_ref = ch.w_ref;
+    const u64 n = ch.n, base = (u64)ch.c * kChunk;
+    u32* slot = ch.slot;
     const u32 mm = lane & (kMmCopies - 1);
     u64 acc = 0;
     u32 nb = 0, nw = 0;
@@ -476,123 +487,168 @@ __device__ __noinline__ void pack_chunk_plain(const void* __restrict__ w, const 
     }
     if (!PACK) return;
     if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
-    finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
+    finish_lane_sizes(ch, nb, nw);
 }
 
+constexpr int kPackPF = 8;          // rows per prefetch batch of the coding loop
+
+// element index of this lane's 4 elements in row r of chunk c
+__device__ __forceinline__ u64 row_at(u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane_id()) * kV; }
+
+template <int DT>
+__device__ __forceinline__ void fetch_first_batch(const ChunkRef& ch, typename Raw<DT>::type (&A)[kPackPF],
+                                                  typename Raw<DT>::type (&B)[kPackPF]) {
+#pragma unroll
+    for (int k = 0; k < kPackPF; ++k) { A[k] = load_raw<DT>(ch.w, row_at(ch.c, k)); B[k] = load_raw<DT>(ch.w_ref, row_at(ch.c, k)); }
+}
+
+// A full, aligned chunk whose first batch of rows is already in A0/B0; leaves the first batch of `next`
+// there if that chunk takes this path too.
 template <bool ROWCHK, bool HIST, bool PACK, int DT>
-__device__ __forceinline__ void pack_loop(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
-                                          u32* prov, u32 slot_words, u32* chunk_bits, u32* group_words,
-                                          u32 nchunks, bool aligned, u32 K8, PackLds<HIST>& L) {
-    constexpr int PF = 8;
-    const u32 lane = lane_id(), G = gridDim.x;
-    const u32 mm = lane & (kMmCopies - 1);
+__device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const ChunkRef& next,
+                                                typename Raw<DT>::type (&A0)[kPackPF], typename Raw<DT>::type (&B0)[kPackPF],
+                                                u32 K8, PackLds<HIST>& L) {
+    constexpr int PF = kPackPF;
     typedef typename Raw<DT>::type raw_t;
-    raw_t A0[PF], B0[PF], A1[PF], B1[PF];
-    auto fast = [&](u32 c) { return aligned && c < nchunks && (u64)(c + 1) * kChunk <= n; };
-    // element index of this lane's 4 elements in row r of chunk c
-    auto at = [&](u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane) * kV; };
-    u32 c = blockIdx.x;
-    if (fast(c)) {
-#pragma unroll
-        for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c, k)); B0[k] = load_raw<DT>(w_ref, at(c, k)); }
-    }
-    for (; c < nchunks; c += G) {
-        u32* slot = prov + (u64)c * slot_words;
-        if (!fast(c)) {
-            pack_chunk_plain<HIST, PACK, DT>(w, w_ref, n, slot, chunk_bits, group_words, c, L);
-            if (fast(c + G)) {
-#pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c + G, k)); B0[k] = load_raw<DT>(w_ref, at(c + G, k)); }
-            }
-            continue;
-        }
-        // ---- a full, aligned chunk whose first PF rows are already in A0/B0
-        const bool next_fast = fast(c + G);
-        u32* lane_words = slot + kLaneBitsWords + lane;
-        u64 acc = 0;
-        u32 nb = 0, nw = 0;                       // bits waiting in acc, words written
-        // Lanes fill their words at different times; gathering them in LDS and storing whole rows at
-        // the end of the chunk turns many partial-line stores into a few full ones.
-        auto flush = [&]() {
-            if (nb >= 32) {
-                const u32 word = (u32)(acc >> (nb - 32));
-                if (nw < kStageRows) L.stage[nw * kW + lane] = word;
-                else lane_words[nw * kW] = word;
-                ++nw; nb -= 32;
-            }
-        };
-        // Four rows at a time: all table look-ups of the 16 elements are issued together, so the
-        // LDS latency is paid twice per group instead of three times per row; only the shift/or
-        // chain that grows the lane's bit string is serial.
-        auto group = [&](const raw_t* a, const raw_t* b) {
-            u32 u[16], t[16];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float xa[4], xb[4];
-                unpack<DT>(a[k], xa); unpack<DT>(b[k], xb);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) u[4 * k + v] = delta_bits(xa[v], xb[v]);
-            }
-            if (HIST) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
-            }
-            if (!PACK) return;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) t[i] = L.sym8[u[i] >> 23];
-            uint2 p[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                p[i] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(L.pair) + ((t[2 * i] << 4) | t[2 * i + 1]));
-            u32 tmin = t[0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) tmin = min(tmin, t[i]);
-            if (__any(tmin < K8)) {
-                // some lane holds a kept element: everyone updates the extremes of its symbols
-                // (the merged symbol has a slot of its own that nobody reads)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    atomicMin(&L.mn[t[i] * (kMmCopies / 8) + mm], u[i]);
-                    atomicMax(&L.mx[t[i] * (kMmCopies / 8) + mm], u[i]);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                acc = (acc << p[i].y) | p[i].x; nb += p[i].y;
-                if (!ROWCHK || (i & 1)) flush();
-            }
-        };
-        for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
-#pragma unroll
-            for (int k = 0; k < PF; ++k) { A1[k] = load_raw<DT>(w, at(c, r0 + PF + k)); B1[k] = load_raw<DT>(w_ref, at(c, r0 + PF + k)); }
-            group(A0, B0); group(A0 + 4, B0 + 4);
-            if (r0 + 2 * PF < kR) {
-#pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c, r0 + 2 * PF + k)); B0[k] = load_raw<DT>(w_ref, at(c, r0 + 2 * PF + k)); }
-            } else if (next_fast) {
-#pragma unroll
-                for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, at(c + G, k)); B0[k] = load_raw<DT>(w_ref, at(c + G, k)); }
-            }
-            group(A1, B1); group(A1 + 4, B1 + 4);
-        }
-        if (!PACK) continue;
-        // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
-        if (nb > 0) {
-            const u32 word = (u32)(acc << (32 - nb));
+    const u32 lane = lane_id();
+    const u32 mm = lane & (kMmCopies - 1);
+    const void* __restrict__ w = cur.w; const void* __restrict__ w_ref = cur.w_ref;
+    const u32 c = cur.c;
+    raw_t A1[PF], B1[PF];
+    const bool next_fast = next.valid && next.fast;
+    u32* lane_words = cur.slot + kLaneBitsWords + lane;
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;                       // bits waiting in acc, words written
+    // Lanes fill their words at different times; gathering them in LDS and storing whole rows at
+    // the end of the chunk turns many partial-line stores into a few full ones.
+    auto flush = [&]() {
+        if (nb >= 32) {
+            const u32 word = (u32)(acc >> (nb - 32));
             if (nw < kStageRows) L.stage[nw * kW + lane] = word;
             else lane_words[nw * kW] = word;
+            ++nw; nb -= 32;
         }
-        u32 rows = min(nw + (nb > 0 ? 1u : 0u), kStageRows);
+    };
+    // Four rows at a time: all table look-ups of the 16 elements are issued together, so the
+    // LDS latency is paid twice per group instead of three times per row; only the shift/or
+    // chain that grows the lane's bit string is serial.
+    auto group = [&](const raw_t* a, const raw_t* b) {
+        u32 u[16], t[16];
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) rows = max(rows, (u32)__shfl_xor(rows, d, 64));
-        {
-            const uint4* src = reinterpret_cast<const uint4*>(L.stage);
-            uint4* dst = reinterpret_cast<uint4*>(slot + kLaneBitsWords);
-            for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
+        for (int k = 0; k < 4; ++k) {
+            float xa[4], xb[4];
+            unpack<DT>(a[k], xa); unpack<DT>(b[k], xb);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) u[4 * k + v] = delta_bits(xa[v], xb[v]);
         }
-        finish_lane_sizes(slot, chunk_bits, group_words, c, nb, nw);
+        if (HIST) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+        }
+        if (!PACK) return;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] = L.sym8[u[i] >> 23];
+        uint2 p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            p[i] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(L.pair) + ((t[2 * i] << 4) | t[2 * i + 1]));
+        u32 tmin = t[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tmin = min(tmin, t[i]);
+        if (__any(tmin < K8)) {
+            // some lane holds a kept element: everyone updates the extremes of its symbols
+            // (the merged symbol has a slot of its own that nobody reads)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                atomicMin(&L.mn[t[i] * (kMmCopies / 8) + mm], u[i]);
+                atomicMax(&L.mx[t[i] * (kMmCopies / 8) + mm], u[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc = (acc << p[i].y) | p[i].x; nb += p[i].y;
+            if (!ROWCHK || (i & 1)) flush();
+        }
+    };
+    for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) { A1[k] = load_raw<DT>(w, row_at(c, r0 + PF + k)); B1[k] = load_raw<DT>(w_ref, row_at(c, r0 + PF + k)); }
+        group(A0, B0); group(A0 + 4, B0 + 4);
+        if (r0 + 2 * PF < kR) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, row_at(c, r0 + 2 * PF + k)); B0[k] = load_raw<DT>(w_ref, row_at(c, r0 + 2 * PF + k)); }
+        } else if (next_fast) {
+            fetch_first_batch<DT>(next, A0, B0);
+        }
+        group(A1, B1); group(A1 + 4, B1 + 4);
+    }
+    if (!PACK) return;
+    // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
+    if (nb > 0) {
+        const u32 word = (u32)(acc << (32 - nb));
+        if (nw < kStageRows) L.stage[nw * kW + lane] = word;
+        else lane_words[nw * kW] = word;
+    }
+    u32 rows = min(nw + (nb > 0 ? 1u : 0u), kStageRows);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) rows = max(rows, (u32)__shfl_xor(rows, d, 64));
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(L.stage);
+        uint4* dst = reinterpret_cast<uint4*>(cur.slot + kLaneBitsWords);
+        for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
+    }
+    finish_lane_sizes(cur, nb, nw);
+}
+
+// The coding loop of one wavefront over the chunks its source hands out.  Src::get(k) is the wavefront's
+// k-th chunk, Src::enter(chunk, L) runs before each (a batched call switches tables there), Src::K8() and
+// Src::rowchk() describe the table in force: symbol K << 3, and whether a lane's 64-bit accumulator can
+// take a whole row (31 waiting bits + 4 codes of <= 8 bits) between flushes.
+// ROWSEL: 1 / 0 = rowchk() is known to be true / false for every chunk (one vector, one table);
+// -1 = ask per chunk (a batched call, where tables change).
+template <bool HIST, bool PACK, int DT, int ROWSEL, typename Src>
+__device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
+    typedef typename Raw<DT>::type raw_t;
+    raw_t A0[kPackPF], B0[kPackPF];
+    ChunkRef cur = src.get(0);
+    if (cur.valid && cur.fast) fetch_first_batch<DT>(cur, A0, B0);
+    for (u32 k = 0; cur.valid; ++k) {
+        const ChunkRef next = src.get(k + 1);
+        src.enter(cur, L);
+        if (!cur.fast) {
+            pack_chunk_plain<HIST, PACK, DT>(cur, L);
+            if (next.valid && next.fast) fetch_first_batch<DT>(next, A0, B0);
+        } else if (ROWSEL == 1 || (ROWSEL < 0 && src.rowchk())) {
+            pack_chunk_fast<true, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L);
+        } else {
+            pack_chunk_fast<false, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L);
+        }
+        cur = next;
     }
 }
+
+// The chunks of one vector, dealt round-robin to the wavefronts of the grid.
+struct VectorChunks {
+    const void* w; const void* w_ref;
+    u64 n;
+    u32* prov; u32 slot_words; u32* chunk_bits; u32* group_words;
+    u32 nchunks; bool aligned;
+    u32 k8; bool row;
+    __device__ __forceinline__ ChunkRef get(u32 k) const {
+        ChunkRef ch;
+        ch.c = blockIdx.x + k * gridDim.x;
+        ch.valid = ch.c < nchunks;
+        ch.w = w; ch.w_ref = w_ref; ch.n = n;
+        ch.fast = aligned && (u64)(ch.c + 1) * kChunk <= n;
+        ch.slot = prov + (u64)ch.c * slot_words;
+        ch.bits_at = chunk_bits + ch.c;
+        ch.group_at = group_words + (ch.c >> 6);
+        return ch;
+    }
+    template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
+    __device__ __forceinline__ u32 K8() const { return k8; }
+    __device__ __forceinline__ bool rowchk() const { return row; }
+};
 
 template <bool HIST>
 __device__ __forceinline__ void pack_setup(PackLds<HIST>& L, const Table& T, u32 lane) {
@@ -606,7 +662,7 @@ __device__ __forceinline__ void pack_setup(PackLds<HIST>& L, const Table& T, u32
 }
 
 template <bool HIST>
-__device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, Workspace* ws, u32 K, u32 lane) {
+__device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, EncState* ws, u32 K, u32 lane) {
     if (lane < K) {
         u32 mn = 0xFFFFFFFFu, mx = 0;
 #pragma unroll
@@ -617,7 +673,7 @@ __device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, Workspace*
 
 template <int DT>
 __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                             EncState* ws, u32* chunk_bits, u32* group_words, u32* prov,
                                              u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<false> L;
     const u32 lane = threadIdx.x;
@@ -626,9 +682,9 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
     pack_setup(L, T, lane);
     const u32 K = T.K;
     __syncthreads();
-    // 31 waiting bits + 4 codes of <= 8 bits still fit the 64-bit accumulator: flush once per row
-    if (T.max_len <= 8) pack_loop<true, false, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    else pack_loop<false, false, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8};
+    if (src.row) pack_loop<false, true, DT, 1>(src, L);
+    else pack_loop<false, true, DT, 0>(src, L);
     __syncthreads();
     pack_merge_extremes(L, ws, K, lane);
 }
@@ -639,7 +695,7 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
 // w_ref.  k_table then either confirms the coding or voids it.
 template <int DT>
 __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
-                                                   Workspace* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                                   EncState* ws, u32* chunk_bits, u32* group_words, u32* prov,
                                                    u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<true> L;
     const u32 lane = threadIdx.x;
@@ -649,9 +705,10 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, c
     if (spec) pack_setup(L, T, lane);
     const u32 K = spec ? T.K : 0;
     __syncthreads();
-    if (!spec) pack_loop<true, true, false, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, 0, L);
-    else if (T.max_len <= 8) pack_loop<true, true, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
-    else pack_loop<false, true, true, DT>(w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, L);
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, !spec || T.max_len <= 8};
+    if (!spec) pack_loop<true, false, DT, 1>(src, L);
+    else if (src.row) pack_loop<true, true, DT, 1>(src, L);
+    else pack_loop<true, true, DT, 0>(src, L);
     __syncthreads();
     for (u32 b = lane; b < 512; b += 64) {
         u32 sum = 0;
@@ -676,7 +733,7 @@ constexpr u32 kPlaceWords = 2048;
 // Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
-__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
+__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
                                                   TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
@@ -734,7 +791,7 @@ __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, R
     __threadfence_system();
 }
 
-__global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
+__global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                                const u32* __restrict__ group_words, const u32* __restrict__ prov,
                                                u32 slot_words, u32 nchunks) {
     __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
