@@ -215,6 +215,33 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
 lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream);
 
 /*
+ * Many vectors in one call, each with a table of its own: tensor t is coded exactly as
+ * lc_encode(w[t], w_ref[t], n[t], nbits, out[t]) would (the paper quantizes layer by layer: Figure 2,
+ * Section 4.3; per-tensor tables keep small-scale tensors from being merged away by large-scale ones),
+ * but the whole list takes six kernel launches instead of five per tensor.
+ *   w, w_ref, out  HOST arrays of `count` DEVICE pointers (out[t]: 16-byte aligned, at least
+ *                  lc_encode_bound(n[t], nbits) bytes); n: HOST array of lengths; 1 <= count <= LC_MAX_BATCH
+ *   sizes          HOST array or NULL: blob size of each tensor, or -(lc_status) for a tensor whose delta
+ *                  is not finite (its blob is then the 512-byte header with status 2; the others are fine)
+ * Returns the sum of the blob sizes, or -(lc_status) of the first failing tensor.  Every blob is an
+ * ordinary LCB1 blob for lc_decode.  lc_batch_workspace_bytes: scratch the call needs (host only).
+ */
+#define LC_MAX_BATCH 1024
+size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits);
+lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const uint64_t* n, int count, int nbits,
+                         void* const* out, int64_t* sizes, void* stream);
+
+/*
+ * The restore of such a list: tensor t as lc_decode(blobs[t], w_ref[t], n[t]) (Algorithm 1 line 7), all tensors
+ * in five launches.  Every blob is validated like lc_decode's before the sweep; a tensor whose blob fails is
+ * left untouched (its size comes back as -(lc_status)) while the others are restored.  Arrays as in
+ * lc_encode_batch (blobs[t]: DEVICE pointer, 16-byte aligned; fp32 blobs only).  Returns the sum of the bytes
+ * consumed, or -(lc_status) of the first failing tensor.
+ */
+lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
+                         void* stream);
+
+/*
  * Parse a header that the caller copied to HOST memory (at least 64 bytes).  Any
  * output pointer may be NULL.  Returns LC_OK, or LC_ERR_BAD_BLOB if magic/version
  * are wrong; `status` receives the header's status field.

@@ -34,6 +34,15 @@ struct Ticket {
     hipEvent_t done = nullptr;    // after the last kernel
 };
 Ticket g_ticket[kMaxTickets];
+
+// lc_encode_batch: pinned host memory for the tensor list on its way to the device and for the
+// per-tensor outcomes the kernels write (mapped).
+struct BatchHost {
+    union { Seg segs[kMaxBatch]; SegD dsegs[kMaxBatch]; };
+    Result results[kMaxBatch];
+};
+BatchHost* g_batch = nullptr;
+BatchHost* g_batch_dev = nullptr;
 static_assert(sizeof(((HostResult*)0)->enc_async) / sizeof(Result) == kMaxTickets, "one result per ticket");
 
 std::mutex g_mu;
@@ -368,6 +377,148 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     return (lc_ssize)total;
 }
 
+}  // extern "C"
+
+namespace {
+bool batch_host() {
+    if (g_batch) return true;
+    if (hipHostMalloc(reinterpret_cast<void**>(&g_batch), sizeof(BatchHost), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess ||
+        hipHostGetDevicePointer(reinterpret_cast<void**>(&g_batch_dev), g_batch, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        if (g_batch) (void)hipHostFree(g_batch);
+        g_batch = nullptr;
+        return false;
+    }
+    return true;
+}
+
+size_t batch_decode_bytes(const uint64_t* n, int count, uint64_t* chunks_out) {
+    uint64_t chunks = 0;
+    for (int t = 0; t < count; ++t) chunks += num_chunks_of(n[t]);
+    if (chunks_out) *chunks_out = chunks;
+    auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
+    return (size_t)(kWorkspaceHead + up((uint64_t)count * sizeof(DecSet)) + up((uint64_t)count * sizeof(SegD)) + up(4 * chunks) + up(4ull * count));
+}
+}  // namespace
+
+extern "C" {
+
+lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
+                         void* stream) {
+    if (!blobs || !w_ref || !n || count < 1 || count > kMaxBatch) return -LC_ERR_BADARG;
+    for (int t = 0; t < count; ++t) {
+        if (n[t] > LC_MAX_N || !blobs[t] || misaligned(blobs[t], 16)) return -LC_ERR_BADARG;
+        if (n[t] && (!w_ref[t] || misaligned(w_ref[t], 4))) return -LC_ERR_BADARG;
+    }
+    uint64_t chunks64 = 0;
+    const size_t need = batch_decode_bytes(n, count, &chunks64);
+    if (chunks64 > 0xFFFFFFFFull) return -LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int err = 0; DeviceState* ds = nullptr;
+    Workspace* ws = get_workspace(need, &err, &ds);
+    if (!ws) return -(lc_ssize)err;
+    if (!batch_host()) return -LC_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
+    auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
+    uint8_t* base = reinterpret_cast<uint8_t*>(ws) + kWorkspaceHead;
+    BatchDecArgs a;
+    uint32_t chunks = 0;
+    for (int t = 0; t < count; ++t) {
+        SegD& sg = g_batch->dsegs[t];
+        sg.blob = static_cast<const uint8_t*>(blobs[t]); sg.w_ref = w_ref[t]; sg.n = n[t];
+        sg.nchunks = (uint32_t)num_chunks_of(n[t]); sg.chunk0 = chunks; sg.aligned = !misaligned(w_ref[t], 16); sg.pad = 0;
+        chunks += sg.nchunks;
+        g_batch->results[t].bytes = 0; g_batch->results[t].status = LC_ERR_HIP; g_batch->results[t].used_cache = 0;
+    }
+    a.sets = reinterpret_cast<DecSet*>(base);                base += up((uint64_t)count * sizeof(DecSet));
+    a.segs = reinterpret_cast<SegD*>(base);                  base += up((uint64_t)count * sizeof(SegD));
+    a.seg_of_chunk = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
+    a.seg_status = reinterpret_cast<uint32_t*>(base);
+    a.results = g_batch_dev->results;
+    a.count = (uint32_t)count; a.total_chunks = chunks;
+    LC_HIP(hipMemcpyAsync(a.segs, g_batch->dsegs, (size_t)count * sizeof(SegD), hipMemcpyHostToDevice, s));
+    launch_batch_decode(a, ds->tune, s);
+    LC_HIP(hipGetLastError());
+    LC_HIP(hipStreamSynchronize(s));
+    ds->pending = false;
+    lc_ssize total = 0; int first_err = 0;
+    for (int t = 0; t < count; ++t) {
+        const Result& r = g_batch->results[t];
+        if (r.status != LC_OK) { if (!first_err) first_err = (int)r.status; if (sizes) sizes[t] = -(int64_t)r.status; }
+        else { total += (lc_ssize)r.bytes; if (sizes) sizes[t] = (int64_t)r.bytes; }
+    }
+    return first_err ? -(lc_ssize)first_err : total;
+}
+
+size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits) {
+    if (!n || count < 1 || count > kMaxBatch || nbits < 1 || nbits > 4) return 0;
+    uint64_t chunks = 0, groups = 0;
+    for (int t = 0; t < count; ++t) {
+        if (n[t] > LC_MAX_N) return 0;
+        const uint64_t nc = num_chunks_of(n[t]);
+        chunks += nc; groups += (nc + 63) / 64;
+    }
+    if (chunks > 0xFFFFFFFFull) return 0;
+    auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
+    const size_t enc = (size_t)(kWorkspaceHead + up((uint64_t)count * sizeof(EncState)) + up((uint64_t)count * sizeof(Seg)) +
+                                up(4 * chunks) + up(4 * groups) + up(4 * chunks) + chunks * slot_words_of(nbits) * 4);
+    const size_t dec = batch_decode_bytes(n, count, nullptr);
+    return enc > dec ? enc : dec;
+}
+
+lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const uint64_t* n, int count, int nbits,
+                         void* const* out, int64_t* sizes, void* stream) {
+    if (!w || !w_ref || !n || !out || count < 1 || count > kMaxBatch || nbits < 1 || nbits > 4) return -LC_ERR_BADARG;
+    for (int t = 0; t < count; ++t) {
+        if (n[t] > LC_MAX_N || !out[t] || misaligned(out[t], 16)) return -LC_ERR_BADARG;
+        if (n[t] && (!w[t] || !w_ref[t] || misaligned(w[t], 4) || misaligned(w_ref[t], 4))) return -LC_ERR_BADARG;
+    }
+    const size_t need = lc_batch_workspace_bytes(n, count, nbits);
+    if (!need) return -LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int err = 0; DeviceState* ds = nullptr;
+    Workspace* ws = get_workspace(need, &err, &ds);
+    if (!ws) return -(lc_ssize)err;
+    if (!batch_host()) return -LC_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
+    // carve the scratch behind the single-vector head (which this call leaves alone)
+    auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
+    uint8_t* base = reinterpret_cast<uint8_t*>(ws) + kWorkspaceHead;
+    BatchArgs a;
+    uint32_t chunks = 0, groups = 0;
+    for (int t = 0; t < count; ++t) {
+        Seg& sg = g_batch->segs[t];
+        sg.w = w[t]; sg.w_ref = w_ref[t]; sg.out = static_cast<uint8_t*>(out[t]); sg.n = n[t];
+        sg.nchunks = (uint32_t)num_chunks_of(n[t]); sg.chunk0 = chunks; sg.group0 = groups;
+        sg.aligned = !misaligned(w[t], 16) && !misaligned(w_ref[t], 16);
+        chunks += sg.nchunks; groups += (sg.nchunks + 63) / 64;
+        g_batch->results[t].bytes = 0; g_batch->results[t].status = LC_ERR_HIP; g_batch->results[t].used_cache = 0;
+    }
+    a.states = reinterpret_cast<EncState*>(base);            base += up((uint64_t)count * sizeof(EncState));
+    a.segs = reinterpret_cast<Seg*>(base);                   base += up((uint64_t)count * sizeof(Seg));
+    a.seg_of_chunk = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
+    a.group_words = reinterpret_cast<uint32_t*>(base);       base += up(4ull * groups);
+    a.chunk_bits = reinterpret_cast<uint32_t*>(base);        base += up(4ull * chunks);
+    a.prov = reinterpret_cast<uint32_t*>(base);
+    a.results = g_batch_dev->results;
+    a.count = (uint32_t)count; a.total_chunks = chunks; a.total_groups = groups;
+    a.slot_words = slot_words_of(nbits); a.nbits = nbits;
+    LC_HIP(hipMemcpyAsync(a.segs, g_batch->segs, (size_t)count * sizeof(Seg), hipMemcpyHostToDevice, s));
+    launch_batch_encode(a, ds->tune, s);
+    LC_HIP(hipGetLastError());
+    LC_HIP(hipStreamSynchronize(s));
+    ds->pending = false;
+    lc_ssize total = 0; int first_err = 0;
+    for (int t = 0; t < count; ++t) {
+        const Result& r = g_batch->results[t];
+        if (r.status != LC_OK) { if (!first_err) first_err = (int)r.status; if (sizes) sizes[t] = -(int64_t)r.status; }
+        else { total += (lc_ssize)r.bytes; if (sizes) sizes[t] = (int64_t)r.bytes; }
+    }
+    return first_err ? -(lc_ssize)first_err : total;
+}
+
 int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status) {
     if (!host_header) return LC_ERR_BADARG;
     const uint8_t* h = static_cast<const uint8_t*>(host_header);
@@ -402,6 +553,7 @@ void lc_shutdown(void) {
         g_dev[d].pending = false;
     }
     if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; g_pinned_dev = nullptr; }
+    if (g_batch) { (void)hipHostFree(g_batch); g_batch = nullptr; g_batch_dev = nullptr; }
     for (int d = 0; d < kMaxDevices; ++d) g_dev[d].clean = nullptr;
     if (g_ev_made) {
         for (int i = 0; i < kNumSlots; ++i) { (void)hipEventDestroy(g_ev[i][0]); (void)hipEventDestroy(g_ev[i][1]); }

@@ -132,6 +132,35 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
                      uint64_t n, int nbits, int dtype, hipStream_t s);
+// One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
+// chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
+struct Seg {
+    const float* w; const float* w_ref; uint8_t* out;
+    uint64_t n;
+    uint32_t nchunks, chunk0, group0, aligned;
+};
+constexpr int kMaxBatch = 1024;
+struct BatchArgs {
+    Seg* segs; EncState* states; Result* results;     // device (results: mapped host memory)
+    uint32_t* seg_of_chunk; uint32_t* group_words; uint32_t* chunk_bits; uint32_t* prov;
+    uint32_t count, total_chunks, total_groups, slot_words;
+    int nbits;
+};
+void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s);
+
+// lc_decode_batch: one blob and one vector per tensor.
+struct SegD {
+    const uint8_t* blob; float* w_ref;
+    uint64_t n;
+    uint32_t nchunks, chunk0, aligned, pad;
+};
+struct BatchDecArgs {
+    SegD* segs; DecSet* sets; Result* results;         // device (results: mapped host memory)
+    uint32_t* seg_of_chunk; uint32_t* seg_status;      // seg_status: lc_status per tensor, raised with atomicMax
+    uint32_t count, total_chunks;
+};
+void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t s);
+
 struct BlobList { const uint8_t* p[kMaxSets]; };
 // Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,

@@ -246,7 +246,7 @@ struct TableLds {
 // whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
 // cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
 // if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
-__global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+__device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
     __shared__ TableLds S;
     __shared__ u32 s_reuse;
     const u32 lane = lane_id();
@@ -347,6 +347,10 @@ __global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u3
     }
 }
 
+__global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+    table_build(ws, n, nbits, group_words, ngroups);
+}
+
 // ----------------------------------------------------------------------------- k_spec_table
 // lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
 // priority order, lengths forming a complete prefix code) into the table the sweep codes with.
@@ -440,6 +444,7 @@ struct ChunkRef {
     u64 n;
     u32 c;
     u32* slot; u32* bits_at; u32* group_at;
+    u32 seg;                     // batched calls: which tensor
     bool valid, fast;            // fast: a full chunk of aligned arrays
 };
 
@@ -643,6 +648,7 @@ struct VectorChunks {
         ch.slot = prov + (u64)ch.c * slot_words;
         ch.bits_at = chunk_bits + ch.c;
         ch.group_at = group_words + (ch.c >> 6);
+        ch.seg = 0;
         return ch;
     }
     template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
@@ -733,8 +739,8 @@ constexpr u32 kPlaceWords = 2048;
 // Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
-__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
-                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
+__device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
+                                              u64 n, int nbits, u32 nchunks, u32 dtype) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
@@ -787,21 +793,26 @@ __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Re
         if (t >= 1 && t < 4 && nchunks + t < entries) off_tab[nchunks + t] = 0;
     }
     __syncthreads();
-    clear_encode_state(ws, group_words, (nchunks + 63) / 64, t, blockDim.x);
+}
+
+__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype);
+    clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
     __threadfence_system();
 }
 
-__global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
-                                               const u32* __restrict__ group_words, const u32* __restrict__ prov,
-                                               u32 slot_words, u32 nchunks) {
+// Chunk c of one vector, by one wavefront of a workgroup of four; `valid` false: an idle wavefront that only
+// keeps the workgroup's barrier company.
+__device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
+                                            const u32* __restrict__ group_words, const u32* __restrict__ prov,
+                                            u32 slot_words, u32 nchunks, u32 c, bool valid) {
     __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
     __shared__ u32 s_buf_all[4][kPlaceWords];
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     u32* s_off = s_off_all[wv];
     u32* s_hw = s_hw_all[wv];
     u32* s_buf = s_buf_all[wv];
-    const u32 c = blockIdx.x * 4 + wv;
-    const bool valid = c < nchunks && ws->table.status == 0;   // the last workgroup may hold idle wavefronts
     const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
     const u32 bits = valid ? reinterpret_cast<const uint16_t*>(slot)[lane] : 0;
     const u32 g = c >> 6;
@@ -870,6 +881,138 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const
     }
 }
 
+__global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
+                                               const u32* __restrict__ group_words, const u32* __restrict__ prov,
+                                               u32 slot_words, u32 nchunks) {
+    const u32 c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    // the last workgroup may hold idle wavefronts
+    place_chunk(out, ws, chunk_bits, group_words, prov, slot_words, nchunks, c, c < nchunks && ws->table.status == 0);
+}
+
+// ----------------------------------------------------------------------------- batched encode
+// lc_encode_batch: many vectors, one table each, in six launches.  The chunks of all tensors are numbered
+// through; the sweeps deal those dense chunks round-robin to their wavefronts exactly as for one vector,
+// and a wavefront that moves on to a chunk of another tensor first hands in what it gathered for the last
+// one (bucket counts, extremes) and loads the new tensor's table.
+__global__ __launch_bounds__(256) void kb_setup(BatchArgs a) {
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x, nthr = gridDim.x * blockDim.x;
+    for (u32 g = i; g < a.total_chunks; g += nthr) {          // tensor of dense chunk g: last one starting at or before it
+        u32 lo = 0, hi = a.count - 1;
+        while (lo < hi) {
+            const u32 mid = (lo + hi + 1) >> 1;
+            if (a.segs[mid].chunk0 <= g) lo = mid; else hi = mid - 1;
+        }
+        // tensors without chunks share their successor's chunk0: step to the one that owns g
+        while (lo > 0 && (a.segs[lo].nchunks == 0 || g >= a.segs[lo].chunk0 + a.segs[lo].nchunks)) --lo;
+        a.seg_of_chunk[g] = lo;
+    }
+    for (u32 g = i; g < a.total_groups; g += nthr) a.group_words[g] = 0;
+    constexpr u32 per = 512 + 2 * kMaxSym + 4;                // words of state to set per tensor
+    for (u64 k = i; k < (u64)a.count * per; k += nthr) {
+        EncState& st = a.states[k / per];
+        const u32 j = (u32)(k % per);
+        if (j < 512) st.hist[j] = 0;
+        else if (j < 512 + kMaxSym) st.mmin[j - 512] = 0x7FFFFFu;
+        else if (j < 512 + 2 * kMaxSym) st.mmax[j - 512 - kMaxSym] = 0;
+        else if (j == 512 + 2 * kMaxSym) st.spec = 0;
+        else if (j == 512 + 2 * kMaxSym + 1) st.spec_ok = 0;
+        else if (j == 512 + 2 * kMaxSym + 2) st.total_words = 0;
+        else st.table.status = 0;
+    }
+}
+
+// The dense chunks of a batched call as a chunk source for the coding loop.
+template <bool HIST, bool PACK>
+struct BatchChunks {
+    BatchArgs a;
+    u32 active;                  // tensor whose counts / extremes / table the LDS holds (0xFFFFFFFF: none yet)
+    u32 k8; bool row;
+    __device__ __forceinline__ ChunkRef get(u32 k) const {
+        ChunkRef ch;
+        const u32 g = blockIdx.x + k * gridDim.x;
+        ch.valid = g < a.total_chunks;
+        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false;
+        ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
+        if (ch.valid) {
+            ch.seg = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
+            const Seg& sg = a.segs[ch.seg];
+            ch.c = g - sg.chunk0;
+            ch.w = sg.w; ch.w_ref = sg.w_ref; ch.n = sg.n;
+            ch.fast = sg.aligned && (u64)(ch.c + 1) * kChunk <= sg.n;
+            ch.slot = a.prov + (u64)g * a.slot_words;
+            ch.bits_at = a.chunk_bits + g;
+            ch.group_at = a.group_words + sg.group0 + (ch.c >> 6);
+            // a tensor whose delta is not finite gets a header-only blob: nothing to code
+            if (PACK && a.states[ch.seg].table.status != 0) { ch.n = 0; ch.fast = false; }
+        }
+        return ch;
+    }
+    __device__ __forceinline__ void hand_in(PackLds<HIST>& L) {
+        if (active == 0xFFFFFFFFu) return;
+        const u32 lane = lane_id();
+        EncState* st = &a.states[active];
+        if (HIST) {
+            for (u32 b = lane; b < 512; b += kW) {
+                u32 sum = 0;
+#pragma unroll
+                for (int k = 0; k < kSpecCopies; ++k) { sum += L.hist[b * kSpecCopies + k]; L.hist[b * kSpecCopies + k] = 0; }
+                if (sum) atomicAdd(&st->hist[b], (u64)sum);
+            }
+        }
+        if (PACK) pack_merge_extremes(L, st, st->table.K, lane);
+    }
+    __device__ __forceinline__ void enter(const ChunkRef& ch, PackLds<HIST>& L) {
+        if (ch.seg == active) return;
+        hand_in(L);
+        active = ch.seg;
+        if (PACK) {
+            const Table& T = a.states[active].table;
+            __syncthreads();                  // one wavefront per workgroup: orders the LDS traffic around the switch
+            pack_setup(L, T, lane_id());
+            k8 = T.K << 3; row = T.max_len <= 8;
+            __syncthreads();
+        }
+    }
+    __device__ __forceinline__ u32 K8() const { return k8; }
+    __device__ __forceinline__ bool rowchk() const { return row; }
+};
+
+__global__ __launch_bounds__(64) void kb_hist(BatchArgs a) {
+    __shared__ PackLds<true> L;
+    for (u32 i = threadIdx.x; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
+    __syncthreads();
+    BatchChunks<true, false> src = {a, 0xFFFFFFFFu, 0, true};
+    pack_loop<true, false, kF32, 1>(src, L);
+    src.hand_in(L);
+}
+
+__global__ __launch_bounds__(64) void kb_table(BatchArgs a) {
+    table_build(&a.states[blockIdx.x], a.segs[blockIdx.x].n, a.nbits, nullptr, 0);
+}
+
+__global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
+    __shared__ PackLds<false> L;
+    BatchChunks<false, true> src = {a, 0xFFFFFFFFu, 0, true};
+    pack_loop<false, true, kF32, 0>(src, L);      // flush per pair of codes: right for every table of the batch
+    src.hand_in(L);
+}
+
+__global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
+    const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const bool in_range = g < a.total_chunks;
+    const u32 sidx = in_range ? a.seg_of_chunk[g] : 0;
+    const Seg& sg = a.segs[sidx];
+    EncState* st = &a.states[sidx];
+    place_chunk(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
+                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0);
+}
+
+__global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
+    const Seg& sg = a.segs[blockIdx.x];
+    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)kF32);
+    if (blockIdx.x == gridDim.x - 1) __threadfence_system();
+}
+
 // ----------------------------------------------------------------------------- k_dec_check
 // Everything lc_decode verifies before w_ref is touched, in one launch.  Every workgroup
 // re-reads the header and does the cheap sanity checks that keep its own reads in bounds;
@@ -878,6 +1021,83 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const
 // of the record sizes that the lane lengths imply, from 0 to the blob's stated size.
 // Errors are raised with atomicMax on a word tagged with the call's epoch, so the word
 // never needs clearing.
+// Thread 0 of a workgroup: validates the header's symbol table, builds the canonical codes and fills
+// D.info; s_len / s_code (LDS, kMaxSym entries) are left for dec_build_luts.  Returns whether the blob passes.
+__device__ __forceinline__ bool dec_symbol_table(const u32* hdr, u64 n, u32 nchunks, u64 area, u64 tw, DecSet& D,
+                                                 u32* s_len, u32* s_code) {
+    const u32 nbits = hdr[4], K = hdr[5];
+    bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
+    if (nchunks == 0 && tw != 0) ok = false;
+    u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
+    u32 per_len[17];
+    for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+    for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; }
+    if (ok) {
+        for (u32 j = 0; j <= K; ++j) {
+            const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
+            const u64 cn = hdr[18 + 4 * j] | ((u64)hdr[19 + 4 * j] << 32);
+            const u32 bucket = w0 & 0xFFFFu, len = (w0 >> 16) & 0xFFu;
+            cnt_sum += cn;
+            if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
+            if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
+            if (j == K && rep != 0) ok = false;
+            s_len[j] = len; D.info.rep_bits[j] = rep;
+            if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
+        }
+        if (cnt_sum != n) ok = false;
+        if (active >= 2 && kraft != (1u << 15)) ok = false;
+        if (active == 1 && kraft != (1u << 14)) ok = false;
+    }
+    if (ok) {
+        u32 next_code[17], code = 0;
+        for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
+        for (u32 j = 0; j < kMaxSym; ++j) {
+            s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
+            D.info.len[j] = s_len[j]; D.info.code[j] = s_code[j];
+        }
+    }
+    D.info.K = K; D.info.max_len = max_len;
+    D.info.area = area; D.info.total_words = tw;
+    return ok;
+}
+
+// Two tables over the next P bits of a lane's string, entry = symbol | len << 4.  A prefix that
+// starts no code: symbol K with length 0 (the lane then falls short of its stated length); a
+// prefix of a code longer than P bits: 0xFF.  The first table (P = min(max_len, 7): 128 bytes,
+// one 32-bit word per LDS bank) resolves the frequent short codes without bank conflicts.
+__device__ __forceinline__ void dec_build_luts(DecSet& D, const u32* s_len, const u32* s_code, u32 t, u32 nthr) {
+    const u32 M = D.info.max_len, K = D.info.K;
+    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+    for (u32 pass = 0; pass < 2; ++pass) {
+        const u32 P = pass ? P2 : P1;
+        uint8_t* lut = pass ? D.lut2 : D.lut1;
+        if (pass && M <= kDecLut1Bits) break;
+        for (u32 i = t; i < (1u << P); i += nthr) {
+            u32 entry = K;
+            for (u32 j = 0; j <= K; ++j) {
+                const u32 L = s_len[j];
+                if (L == 0) continue;
+                if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
+                else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+            }
+            lut[i] = (uint8_t)entry;
+        }
+    }
+}
+
+// One chunk's place in the offset table against the lane lengths of its record, by one wavefront.
+__device__ __forceinline__ bool dec_chunk_ok(const uint8_t* blob, u64 area, u64 tw, u32 nchunks, u32 c) {
+    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+    const u64 o0 = off_tab[c], o1 = off_tab[c + 1];
+    bool ok = o0 <= o1 && o1 <= tw && o1 - o0 >= kLaneBitsWords && (c > 0 || o0 == 0) && (c + 1 < nchunks || o1 == tw);
+    if (ok) {
+        const u32 lb = reinterpret_cast<const uint16_t*>(blob + area + 4 * o0)[lane_id()];
+        const u32 sum = wave_sum32(lb);
+        ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
+    }
+    return ok;
+}
+
 __device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u64 epoch, u32 status) {
     const u64 word = (epoch << 8) | status;
     atomicMax(&ws->dec_status, word);     // gates the decode sweep on the device
@@ -889,7 +1109,7 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
     const u32 set = first + blockIdx.y, host_slot = set;     // one grid row per blob
     const uint8_t* blob = blobs.p[set];
     __shared__ u32 hdr[kHeaderBytes / 4];
-    __shared__ u32 s_ok, s_K, s_max_len;
+    __shared__ u32 s_ok;
     __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
     const u32 t = threadIdx.x, lane = lane_id();
     if (t < kHeaderBytes / 4) hdr[t] = reinterpret_cast<const u32*>(blob)[t];
@@ -911,80 +1131,19 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
     const u64 tw = (total - area) / 4;
     // ---- one chunk per wavefront
     const u32 c = blockIdx.x * 4 + (t >> 6);
-    if (c < nchunks) {
-        const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
-        const u64 o0 = off_tab[c], o1 = off_tab[c + 1];
-        bool ok = o0 <= o1 && o1 <= tw && o1 - o0 >= kLaneBitsWords && (c > 0 || o0 == 0) && (c + 1 < nchunks || o1 == tw);
-        if (ok) {
-            const u32 lb = reinterpret_cast<const uint16_t*>(blob + area + 4 * o0)[lane];
-            const u32 sum = wave_sum32(lb);
-            ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
-        }
-        if (!ok && lane == 0) raise_status(ws, host, epoch, 4u);
-    }
+    if (c < nchunks && !dec_chunk_ok(blob, area, tw, nchunks, c) && lane == 0) raise_status(ws, host, epoch, 4u);
     if (blockIdx.x != 0) return;
     // ---- workgroup 0: symbol table, codes, look-up table
     DecSet& D = ws->dec_set[set];
     if (t == 0) {
-        const u32 nbits = hdr[4], K = hdr[5];
-        bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
-        if (nchunks == 0 && tw != 0) ok = false;
-        u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
-        u32 per_len[17];
-        for (int L = 0; L <= 16; ++L) per_len[L] = 0;
-        for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; }
-        if (ok) {
-            for (u32 j = 0; j <= K; ++j) {
-                const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
-                const u64 cn = hdr[18 + 4 * j] | ((u64)hdr[19 + 4 * j] << 32);
-                const u32 bucket = w0 & 0xFFFFu, len = (w0 >> 16) & 0xFFu;
-                cnt_sum += cn;
-                if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
-                if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
-                if (j == K && rep != 0) ok = false;
-                s_len[j] = len; D.info.rep_bits[j] = rep;
-                if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
-            }
-            if (cnt_sum != n) ok = false;
-            if (active >= 2 && kraft != (1u << 15)) ok = false;
-            if (active == 1 && kraft != (1u << 14)) ok = false;
-        }
-        if (ok) {
-            u32 next_code[17], code = 0;
-            for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
-            for (u32 j = 0; j < kMaxSym; ++j) {
-                s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
-                D.info.len[j] = s_len[j]; D.info.code[j] = s_code[j];
-            }
-        } else raise_status(ws, host, epoch, 4u);
-        D.info.K = K; D.info.max_len = max_len;
-        D.info.area = area; D.info.total_words = tw;
-        host->bytes[host_slot] = total; host->max_len[host_slot] = max_len;
-        s_ok = ok; s_K = K; s_max_len = max_len;
+        const bool ok = dec_symbol_table(hdr, n, nchunks, area, tw, D, s_len, s_code);
+        if (!ok) raise_status(ws, host, epoch, 4u);
+        host->bytes[host_slot] = total; host->max_len[host_slot] = D.info.max_len;
+        s_ok = ok;
     }
     __syncthreads();
     if (!s_ok) return;
-    // Two tables over the next P bits of a lane's string, entry = symbol | len << 4.  A prefix that
-    // starts no code: symbol K with length 0 (the lane then falls short of its stated length); a
-    // prefix of a code longer than P bits: 0xFF.  The first table (P = min(max_len, 7): 128 bytes,
-    // one 32-bit word per LDS bank) resolves the frequent short codes without bank conflicts.
-    const u32 M = s_max_len, K = s_K;
-    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-    for (u32 pass = 0; pass < 2; ++pass) {
-        const u32 P = pass ? P2 : P1;
-        uint8_t* lut = pass ? D.lut2 : D.lut1;
-        if (pass && M <= kDecLut1Bits) break;
-        for (u32 i = t; i < (1u << P); i += 256) {
-            u32 entry = K;
-            for (u32 j = 0; j <= K; ++j) {
-                const u32 L = s_len[j];
-                if (L == 0) continue;
-                if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
-                else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
-            }
-            lut[i] = (uint8_t)entry;
-        }
-    }
+    dec_build_luts(D, s_len, s_code, t, 256);
 }
 
 // ----------------------------------------------------------------------------- k_decode
@@ -996,15 +1155,18 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
 // back at all.
 constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average)
 
-struct DecLds {
+template <int WAVES>
+struct DecLdsT {
     uint8_t lut1[1u << kDecLut1Bits];
     uint8_t lut2[1u << kDecLut2Bits];
     float rep[kMaxSym];
     u32 len[kMaxSym], code[kMaxSym];
-    uint4 payload[4][kPayWords / 4 + 1];
+    uint4 payload[WAVES][kPayWords / 4 + 1];
 };
+typedef DecLdsT<4> DecLds;
 
-__device__ __noinline__ u32 decode_long(const DecLds& L, u64 win, u32 K) {
+template <typename LDS>
+__device__ __noinline__ u32 decode_long(const LDS& L, u64 win, u32 K) {
     const u32 peek = (u32)(win >> (64 - 15));
     for (u32 j = 0; j <= K; ++j) {
         const u32 l = L.len[j];
@@ -1037,10 +1199,11 @@ struct BitReader {
     }
 };
 
-template <bool FAST, bool LV2, bool STAGED, int DT>
+// `raise(code)` reports a lane string that does not decode to its stated length.
+template <bool FAST, bool LV2, bool STAGED, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
-                                            void* __restrict__ w_ref, u64 n, Workspace* ws, HostResult* host, u32 c,
-                                            const DecLds& L, u32 P1, u32 P2, u32 K, u64 epoch) {
+                                            void* __restrict__ w_ref, u64 n, u32 c,
+                                            const LDS& L, u32 P1, u32 P2, u32 K, Raise& raise) {
     const u32 lane = lane_id();
     BitReader<STAGED> br;
     br.start(words, nwords, first_bit);
@@ -1077,12 +1240,12 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
         }
     }
     const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
-    if (__any(used != lane_bits) && lane == 0) raise_status(ws, host, epoch, 4u);
+    if (__any(used != lane_bits) && lane == 0) raise(4u);
 }
 
-template <bool FAST, bool LV2, int DT>
+template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
-                                             Workspace* ws, HostResult* host, u32 c, DecLds& L, u32 P1, u32 P2, u32 K, u64 area, u64 epoch) {
+                                             u32 c, LDS& L, u32 P1, u32 P2, u32 K, u64 area, Raise& raise) {
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
     const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
@@ -1108,9 +1271,9 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
             L.payload[wv][i] = q;
         }
         decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
-                                     w_ref, n, ws, host, c, L, P1, P2, K, epoch);
+                                         w_ref, n, c, L, P1, P2, K, raise);
     } else {
-        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, ws, host, c, L, P1, P2, K, epoch);
+        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, raise);
     }
 }
 
@@ -1141,16 +1304,128 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         }
         __syncthreads();
         const u32 wave = t >> 6;
+        auto raise = [&](u32 code) { raise_status(ws, host, epoch, code); };
         for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
-                else decode_chunk<true, false, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
             } else {
-                decode_chunk<false, true, DT>(blob, w_ref, n, ws, host, c, L, P1, P2, K, area, epoch);
+                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
             }
         }
     }
+}
+
+// ----------------------------------------------------------------------------- batched decode
+// lc_decode_batch: the blobs of many tensors restored in five launches.  Every blob is validated as
+// lc_decode validates it (header and symbol table per tensor, then every chunk's place in its offset
+// table) before the sweep; a tensor whose blob fails is left untouched and reported, the others are
+// restored.  The sweep deals the chunks of all tensors round-robin to single-wavefront workgroups,
+// which reload their look-up tables when they move on to another tensor's chunk.
+__global__ __launch_bounds__(256) void kb_dec_setup(BatchDecArgs a) {
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x, nthr = gridDim.x * blockDim.x;
+    for (u32 g = i; g < a.total_chunks; g += nthr) {
+        u32 lo = 0, hi = a.count - 1;
+        while (lo < hi) {
+            const u32 mid = (lo + hi + 1) >> 1;
+            if (a.segs[mid].chunk0 <= g) lo = mid; else hi = mid - 1;
+        }
+        while (lo > 0 && (a.segs[lo].nchunks == 0 || g >= a.segs[lo].chunk0 + a.segs[lo].nchunks)) --lo;
+        a.seg_of_chunk[g] = lo;
+    }
+    for (u32 t = i; t < a.count; t += nthr) a.seg_status[t] = 0;
+}
+
+// One workgroup per tensor: header, symbol table, codes, look-up tables.
+__global__ __launch_bounds__(256) void kb_dec_tables(BatchDecArgs a) {
+    __shared__ u32 hdr[kHeaderBytes / 4];
+    __shared__ u32 s_ok;
+    __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
+    const u32 t = threadIdx.x, sidx = blockIdx.x;
+    const SegD& sg = a.segs[sidx];
+    DecSet& D = a.sets[sidx];
+    if (t < kHeaderBytes / 4) hdr[t] = reinterpret_cast<const u32*>(sg.blob)[t];
+    __syncthreads();
+    if (t == 0) {
+        const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
+        const u64 area = chunk_area_of(sg.nchunks);
+        // the largest blob lc_encode can produce for this n (nbits 4): header + offsets + 132 bytes per chunk + n/2
+        const u64 max_total = area + (u64)sg.nchunks * (2 * kW + 4) + (sg.n * 4 + 7) / 8;
+        const bool sound = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0;
+        const bool head_ok = sound && hn == sg.n && hdr[15] == (u32)kF32 && hdr[9] == sg.nchunks && total >= area &&
+                             total <= max_total && ((total - area) & 3) == 0;
+        bool ok = head_ok;
+        u32 status = 0;
+        if (!head_ok) status = (sound && (hn != sg.n || hdr[15] != (u32)kF32)) ? 1u : 4u;
+        else if (!dec_symbol_table(hdr, sg.n, sg.nchunks, area, (total - area) / 4, D, s_len, s_code)) { ok = false; status = 4u; }
+        if (!ok) { atomicMax(&a.seg_status[sidx], status); D.info.area = 0; D.info.total_words = 0; D.info.max_len = 0; D.info.K = 0; }
+        D.info.pad[0] = ok ? 1u : 0u;                        // the chunk checks and the sweep look here first
+        D.info.pad[1] = 0;
+        s_ok = ok;
+    }
+    __syncthreads();
+    if (s_ok) dec_build_luts(D, s_len, s_code, t, 256);
+}
+
+__global__ __launch_bounds__(256) void kb_dec_chunks(BatchDecArgs a) {
+    const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= a.total_chunks) return;
+    const u32 sidx = a.seg_of_chunk[g];
+    const SegD& sg = a.segs[sidx];
+    const DecInfo& I = a.sets[sidx].info;
+    if (!I.pad[0]) return;
+    if (!dec_chunk_ok(sg.blob, I.area, I.total_words, sg.nchunks, g - sg.chunk0) && lane_id() == 0) atomicMax(&a.seg_status[sidx], 4u);
+}
+
+__global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
+    __shared__ DecLdsT<1> L;
+    const u32 lane = threadIdx.x;
+    u32 active = 0xFFFFFFFFu, M = 0, K = 0, P1 = 0, P2 = 0;
+    u64 area = 0;
+    for (u32 g = blockIdx.x; g < a.total_chunks; g += gridDim.x) {
+        const u32 sidx = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
+        // a tensor whose blob failed a check is not touched
+        if (__hip_atomic_load(&a.seg_status[sidx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) continue;
+        const SegD& sg = a.segs[sidx];
+        if (sidx != active) {
+            active = sidx;
+            const DecSet& D = a.sets[sidx];
+            M = D.info.max_len; K = D.info.K; area = D.info.area;
+            P1 = M < kDecLut1Bits ? M : kDecLut1Bits; P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+            __syncthreads();
+            for (u32 i = lane; i < (1u << P1); i += kW) L.lut1[i] = D.lut1[i];
+            if (M > kDecLut1Bits) {
+                const u32* src = reinterpret_cast<const u32*>(D.lut2);
+                u32* dst = reinterpret_cast<u32*>(L.lut2);
+                for (u32 i = lane; i < ((1u << P2) + 3) / 4; i += kW) dst[i] = src[i];
+            }
+            if (lane < kMaxSym) {
+                L.rep[lane] = __uint_as_float(lane < K ? D.info.rep_bits[lane] : 0x80000000u);
+                L.len[lane] = D.info.len[lane]; L.code[lane] = D.info.code[lane];
+            }
+            __syncthreads();
+        }
+        auto raise = [&](u32 code) { atomicMax(&a.seg_status[sidx], code); };
+        const u32 c = g - sg.chunk0;
+        const bool full = (u64)(c + 1) * kChunk <= sg.n;
+        if (full && sg.aligned) {
+            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+        } else {
+            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void kb_dec_report(BatchDecArgs a) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.count) return;
+    const u32 st = a.seg_status[t];
+    const DecInfo& I = a.sets[t].info;
+    a.results[t].status = st;
+    a.results[t].bytes = st ? 0 : I.area + 4 * I.total_words;
+    a.results[t].used_cache = 0;
 }
 
 // ----------------------------------------------------------------------------- k_decode_many
@@ -1597,6 +1872,44 @@ void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t*
                      uint64_t n, int nbits, int dtype, hipStream_t s) {
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
                        (u32)num_chunks_of(n), (u32)dtype);
+}
+
+void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s) {
+    const u32 cap = (u32)tune.num_cu * 8;
+    u32 setup_blocks = (a.total_chunks + 255) / 256;
+    if (setup_blocks < a.count * 3) setup_blocks = a.count * 3;
+    if (setup_blocks > cap) setup_blocks = cap;
+    if (setup_blocks < 1) setup_blocks = 1;
+    hipLaunchKernelGGL(kb_setup, dim3(setup_blocks), dim3(256), 0, s, a);
+    if (a.total_chunks) {
+        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_hist, dim3(waves), dim3(64), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_table, dim3(a.count), dim3(64), 0, s, a);
+    if (a.total_chunks) {
+        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_pack, dim3(waves), dim3(64), 0, s, a);
+        hipLaunchKernelGGL(kb_place, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_finalize, dim3(a.count), dim3(256), 0, s, a);
+}
+
+void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t s) {
+    const u32 cap = (u32)tune.num_cu * 8;
+    u32 setup_blocks = (a.total_chunks + 255) / 256;
+    if (setup_blocks > cap) setup_blocks = cap;
+    if (setup_blocks < 1) setup_blocks = 1;
+    hipLaunchKernelGGL(kb_dec_setup, dim3(setup_blocks), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(kb_dec_tables, dim3(a.count), dim3(256), 0, s, a);
+    if (a.total_chunks) {
+        hipLaunchKernelGGL(kb_dec_chunks, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
+        u32 waves = (u32)tune.num_cu * (u32)tune.decode_blocks_per_cu * 4u;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_decode, dim3(waves), dim3(64), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_dec_report, dim3((a.count + 255) / 256), dim3(256), 0, s, a);
 }
 
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,

@@ -33,6 +33,13 @@ _lib.lc_encode_t.restype = _i64
 _lib.lc_encode_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp]
 _lib.lc_decode_t.restype = _i64
 _lib.lc_decode_t.argtypes = [_vp, _vp, _u64, _int, _vp]
+_lib.lc_batch_workspace_bytes.restype = _sz
+_lib.lc_batch_workspace_bytes.argtypes = [ctypes.POINTER(_u64), _int, _int]
+_lib.lc_encode_batch.restype = _i64
+_lib.lc_encode_batch.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, _int,
+                                 ctypes.POINTER(_vp), ctypes.POINTER(_i64), _vp]
+_lib.lc_decode_batch.restype = _i64
+_lib.lc_decode_batch.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, ctypes.POINTER(_i64), _vp]
 _lib.lc_encode_cached.restype = _i64
 _lib.lc_encode_cached.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, ctypes.POINTER(_int), _vp]
 _lib.lc_encode_async.restype = _int
@@ -135,6 +142,43 @@ def lc_decode_t(blob, w_ref, stream=None, n=None):
     if r < 0:
         raise LcError(-r)
     return r
+
+
+def lc_encode_batch(ws, w_refs, nbits, outs, stream=None):
+    """One table per tensor, all tensors in one call. Returns the list of blob sizes (negative: -(status) of that
+    tensor); raises LcError only for errors that concern the whole call."""
+    count = len(ws)
+    assert count == len(w_refs) == len(outs) and count >= 1
+    wp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in ws])
+    rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
+    op = (_vp * count)(*[t.data_ptr() for t in outs])
+    ns = (_u64 * count)(*[t.numel() for t in ws])
+    for w, r, o in zip(ws, w_refs, outs):
+        assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and r.is_cuda and r.dtype == torch.float32
+        assert r.is_contiguous() and r.numel() == w.numel() and o.is_cuda and o.dtype == torch.uint8 and o.is_contiguous()
+        assert o.numel() >= lc_encode_bound(w.numel(), nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    sizes = (_i64 * count)()
+    r = int(_lib.lc_encode_batch(wp, rp, ns, count, nbits, op, sizes, _stream(stream)))
+    if r < 0 and all(s >= 0 for s in sizes):
+        raise LcError(-r)
+    return [int(s) for s in sizes]
+
+
+def lc_decode_batch(blobs, w_refs, stream=None):
+    """Restores every tensor from its blob in one call. Returns the list of bytes consumed (negative: -(status))."""
+    count = len(blobs)
+    assert count == len(w_refs) and count >= 1
+    for b, r in zip(blobs, w_refs):
+        assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
+        assert r.is_cuda and r.dtype == torch.float32 and r.is_contiguous()
+    bp = (_vp * count)(*[t.data_ptr() for t in blobs])
+    rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
+    ns = (_u64 * count)(*[t.numel() for t in w_refs])
+    sizes = (_i64 * count)()
+    r = int(_lib.lc_decode_batch(bp, rp, ns, count, sizes, _stream(stream)))
+    if r < 0 and all(s >= 0 for s in sizes):
+        raise LcError(-r)
+    return [int(s) for s in sizes]
 
 
 CACHE_BYTES = 256

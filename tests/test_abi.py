@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"lc_encode", "lc_encode_t", "lc_decode_t", "lc_encode_cached", "lc_encode_async", "lc_encode_release_inputs", "lc_encode_wait", "lc_decode", "lc_decode_many", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
+    assert {"lc_encode", "lc_encode_batch", "lc_decode_batch", "lc_batch_workspace_bytes", "lc_encode_t", "lc_decode_t", "lc_encode_cached", "lc_encode_async", "lc_encode_release_inputs", "lc_encode_wait", "lc_decode", "lc_decode_many", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
             "lc_blob_info", "lc_shutdown", "lc_strerror", "lc_profile", "lc_profile_read",
             "lc_profile_name"} <= set(names)
     for name in names:

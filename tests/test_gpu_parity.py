@@ -675,3 +675,122 @@ def test_element_type_mismatch_is_refused(lc):
     with pytest.raises(lc.LcError) as e:
         lc.lc_decode_many([out], rec)
     assert e.value.status == lc.ERR_BADARG and torch.equal(rec, w_ref)
+
+
+# ---------------------------------------------------------------- batched per-tensor encode
+def batch_case(seed, sizes, scales, offsets=None):
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    ws, refs = [], []
+    for i, (n, sc) in enumerate(zip(sizes, scales)):
+        off = 0 if offsets is None else offsets[i]
+        buf_r = 0.05 * torch.randn(n + off, generator=g, device=DEV)
+        u = torch.rand(n + off, generator=g, device=DEV) - 0.5
+        buf_w = buf_r - sc * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
+        ws.append(buf_w[off:]); refs.append(buf_r[off:])
+    return ws, refs
+
+
+def check_batch(lc, ws, refs, nbits, expect_status=None):
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    for o in outs:
+        o.fill_(0x3C)
+    sizes = lc.lc_encode_batch(ws, refs, nbits, outs)
+    for t, (w, r, o, size) in enumerate(zip(ws, refs, outs, sizes)):
+        if expect_status and t in expect_status:
+            assert size == -expect_status[t], (t, size)
+            hdr = o[:512].cpu().numpy()
+            assert lc.lc_blob_info(hdr.tobytes())["status"] == expect_status[t]
+            continue
+        blob_cpu = orc.encode(w.cpu().numpy(), r.cpu().numpy(), nbits)
+        blob_gpu = o[:size].cpu().numpy()
+        assert size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), "tensor %d: %s" % (t, first_diff(blob_gpu, blob_cpu))
+        rec = r.clone()
+        assert lc.lc_decode(o, rec) == size
+        ref_h = r.cpu().numpy()
+        orc.decode(blob_cpu, ref_h)
+        assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h)), t
+    # the batched restore of the same list: every tensor as its own lc_decode would leave it
+    good = [t for t in range(len(ws)) if not (expect_status and t in expect_status)]
+    recs = [refs[t].clone() for t in good]
+    used = lc.lc_decode_batch([outs[t] for t in good], recs)
+    assert used == [sizes[t] for t in good]
+    for t, rec in zip(good, recs):
+        ref_h = refs[t].cpu().numpy()
+        orc.decode(outs[t][:sizes[t]].cpu().numpy(), ref_h)
+        assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h)), t
+    return sizes
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_batched_encode_one_table_per_tensor(lc, nbits):
+    """Every tensor of a batched call gets exactly the blob a call of its own would give (oracle, byte for byte):
+    sizes from empty to several groups of chunks, scales over four decades, so that every tensor keeps its own buckets."""
+    sizes = [5 * 16384 + 777, 0, 1, 100, 16384, 16385, 70 * 16384 + 5, 3 * 16384, 2 * 16384 + 1, 130 * 16384, 64, 16384 * 64]
+    scales = [10.0 ** (-6 + 4 * (i % 5) / 4) for i in range(len(sizes))]
+    ws, refs = batch_case(300 + nbits, sizes, scales)
+    check_batch(lc, ws, refs, nbits)
+    # a different table per tensor is really in play: the kept buckets of a small-scale and a large-scale tensor differ
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    lc.lc_encode_batch(ws, refs, nbits, outs)
+    k0 = lcb1_reader.parse_header(outs[0][:512].cpu().numpy())
+    k4 = lcb1_reader.parse_header(outs[4][:512].cpu().numpy())
+    assert k0["slots"][0]["bucket"] != k4["slots"][0]["bucket"]
+
+
+def test_batched_encode_edge_cases(lc):
+    nbits = 3
+    # unaligned tensors, a single tensor, many tiny tensors
+    ws, refs = batch_case(310, [3 * 16384 + 9, 16384, 5000], [1e-3, 1e-4, 1e-2], offsets=[1, 3, 2])
+    check_batch(lc, ws, refs, nbits)
+    ws, refs = batch_case(311, [9 * 16384 + 1], [1e-3])
+    check_batch(lc, ws, refs, nbits)
+    ws, refs = batch_case(312, [37 + 11 * i for i in range(200)], [1e-3] * 200)
+    check_batch(lc, ws, refs, nbits)
+    # a tensor with a non-finite delta: its blob is a header that says so, the others are untouched by it
+    ws, refs = batch_case(313, [2 * 16384 + 5, 4 * 16384, 999], [1e-3, 1e-4, 1e-2])
+    ws[1] = ws[1].clone(); ws[1][12345] = float("nan")
+    sizes = check_batch(lc, ws, refs, nbits, expect_status={1: 2})
+    assert sizes[0] > 512 and sizes[2] > 512
+    # calls of the other kinds afterwards find their scratch in order
+    w, r = laplace_case(3 * 16384 + 5, seed=314)
+    check_case(lc, w, r, 3, "single after batch")
+    # bad arguments
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_batch([w], [r], 5, [lc.alloc_out(w.numel(), 4, DEV)])
+    assert e.value.status == lc.ERR_BADARG
+
+
+def test_batched_decode_bad_blobs_leave_their_tensor_alone(lc):
+    nbits = 3
+    ws, refs = batch_case(320, [3 * 16384 + 9, 2 * 16384, 777, 5 * 16384], [1e-3, 1e-4, 1e-2, 1e-3])
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    sizes = lc.lc_encode_batch(ws, refs, nbits, outs)
+    blobs = [o[:s].clone() for o, s in zip(outs, sizes)]
+    blobs[1][512 + 4] ^= 1                               # offset table of tensor 1
+    blobs[2][20] ^= 3                                    # K in the header of tensor 2
+    recs = [r.clone() for r in refs]
+    used = lc.lc_decode_batch(blobs, recs)
+    assert used[1] == -lc.ERR_BAD_BLOB and used[2] == -lc.ERR_BAD_BLOB and used[0] == sizes[0] and used[3] == sizes[3]
+    assert torch.equal(recs[1], refs[1]) and torch.equal(recs[2], refs[2])
+    for t in (0, 3):
+        ref_h = refs[t].cpu().numpy()
+        orc.decode(blobs[t].cpu().numpy(), ref_h)
+        assert np.array_equal(bits(recs[t].cpu().numpy()), bits(ref_h))
+    # a blob for a vector of another length
+    recs = [refs[0].clone(), refs[1].clone()]
+    used = lc.lc_decode_batch([outs[1][:sizes[1]], outs[1][:sizes[1]]], recs)
+    assert used[0] == -lc.ERR_BADARG and used[1] == sizes[1] and torch.equal(recs[0], refs[0])
+    # a payload bit flipped: same verdict and, if accepted, same weights as the oracle
+    damaged = outs[3][:sizes[3]].clone()
+    damaged[512 + 16 * 2 + 128 + 700] ^= 0x20
+    ref_h = refs[3].cpu().numpy()
+    try:
+        orc.decode(damaged.cpu().numpy(), ref_h); ok = True
+    except orc.OracleError:
+        ok = False
+    recs = [refs[3].clone()]
+    used = lc.lc_decode_batch([damaged], recs)
+    if ok:
+        assert used[0] == sizes[3] and np.array_equal(bits(recs[0].cpu().numpy()), bits(ref_h))
+    else:
+        assert used[0] == -lc.ERR_BAD_BLOB
