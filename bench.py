@@ -197,6 +197,44 @@ def bf16_leg(device, steps):
                 decode_hbm_frac=round((4.0 + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
 
 
+def per_tensor_leg(device, steps):
+    """Config 2's tensors (ResNet-50: 161 tensors, 25.6 M parameters) with one table per tensor: lc_encode_batch /
+    lc_decode_batch against one lc_encode / lc_decode call per tensor."""
+    import math
+    import torch
+    from paper_2009_13003_amd import lc, workloads
+    shapes = workloads.resnet50_shapes()
+    w, r, nbits = workloads.resnet50(device=device)
+    offs = [0]
+    for sh in shapes:
+        offs.append(offs[-1] + math.prod(sh))
+    ws = [w[offs[i]:offs[i + 1]].clone() for i in range(len(shapes))]
+    rs = [r[offs[i]:offs[i + 1]].clone() for i in range(len(shapes))]
+    outs = [lc.alloc_out(t.numel(), nbits, device) for t in ws]
+    recs = [t.clone() for t in rs]
+    n = w.numel()
+    for _ in range(2):
+        sizes = lc.lc_encode_batch(ws, rs, nbits, outs); lc.lc_decode_batch(outs, recs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sizes = lc.lc_encode_batch(ws, rs, nbits, outs)
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        lc.lc_decode_batch(outs, recs)
+    t2 = time.perf_counter()
+    for a, b, o in zip(ws, rs, outs):
+        lc.lc_encode(a, b, nbits, o)
+    t3 = time.perf_counter()
+    for a, o in zip(recs, outs):
+        lc.lc_decode(o, a)
+    t4 = time.perf_counter()
+    enc, dec, gb = (t1 - t0) / steps, (t2 - t1) / steps, 4.0 * n / 1e9
+    return dict(n=n, tensors=len(ws), nbits=nbits, encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
+                encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(4.0 * n / sum(sizes), 3),
+                encode_ms_one_call_per_tensor=round(1e3 * (t3 - t2), 3), decode_ms_one_call_per_tensor=round(1e3 * (t4 - t3), 3))
+
+
 def chain_leg(device, steps):
     """Config 4: `steps` successive checkpoints of the GPT-2-medium-shaped vector, each encoded against the
     recovered state and decoded into it (Algorithm 1); then the restore from u_0 (Section 3, C1) timed two
@@ -345,6 +383,8 @@ def main():
             del j
             torch.cuda.empty_cache()
         also["vgg16_bf16"] = bf16_leg(dev, args.steps)
+        torch.cuda.empty_cache()
+        also["resnet50_per_tensor"] = per_tensor_leg(dev, args.steps)
         torch.cuda.empty_cache()
         if args.chain_steps > 0:
             also["gpt2_medium_chain"] = chain_leg(dev, args.chain_steps)
