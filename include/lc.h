@@ -248,6 +248,15 @@ lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const ui
  */
 int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* total_bytes, int* status);
 
+/*
+ * The size of a checkpoint after each stage of the method, in bits, from a header copied to HOST memory
+ * (at least 64 bytes): bits[0] exponent-based quantization alone, n * ceil(log2 k) + 32 k with k the number
+ * of non-empty buckets (Section 3.1.1); bits[1] after x-bit priority promotion, n * x + 32 * 2^x; bits[2]
+ * after Huffman coding, the blob as stored with all its indices (the E, E+P, E+P+H of Section 4.3).
+ * Returns LC_OK, LC_ERR_BADARG (NULL) or LC_ERR_BAD_BLOB (not an LCB1 header).
+ */
+int lc_blob_sizes(const void* host_header, uint64_t bits[3]);
+
 /* Frees library-owned scratch on every device and the pinned result buffer. */
 void lc_shutdown(void);
 

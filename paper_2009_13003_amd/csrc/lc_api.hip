@@ -532,6 +532,20 @@ int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* tot
     return LC_OK;
 }
 
+int lc_blob_sizes(const void* host_header, uint64_t bits[3]) {
+    if (!host_header || !bits) return LC_ERR_BADARG;
+    const uint8_t* h = static_cast<const uint8_t*>(host_header);
+    uint16_t version; uint64_t n, total; uint32_t x, k;
+    memcpy(&version, h + 4, 2); memcpy(&n, h + 8, 8); memcpy(&x, h + 16, 4); memcpy(&total, h + 40, 8); memcpy(&k, h + 52, 4);
+    if (memcmp(h, "LCB1", 4) != 0 || version != 1 || x < 1 || x > 4 || k > 512) return LC_ERR_BAD_BLOB;
+    uint32_t lg = 0;
+    while ((1u << lg) < k) ++lg;
+    bits[0] = n * lg + 32ull * k;               // index of one of k buckets per element + k representatives
+    bits[1] = n * x + 32ull * (1u << x);        // x bits per element + 2^x representatives
+    bits[2] = 8 * total;                        // the blob as stored
+    return LC_OK;
+}
+
 void lc_shutdown(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     int cur = 0;

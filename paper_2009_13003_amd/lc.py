@@ -54,6 +54,8 @@ _lib.lc_decode_many.restype = _i64
 _lib.lc_decode_many.argtypes = [ctypes.POINTER(_vp), _int, _vp, _u64, _vp]
 _lib.lc_blob_info.restype = _int
 _lib.lc_blob_info.argtypes = [_vp, ctypes.POINTER(_u64), ctypes.POINTER(_int), ctypes.POINTER(_u64), ctypes.POINTER(_int)]
+_lib.lc_blob_sizes.restype = _int
+_lib.lc_blob_sizes.argtypes = [_vp, ctypes.POINTER(_u64)]
 _lib.lc_shutdown.restype = None
 _lib.lc_shutdown.argtypes = []
 _lib.lc_strerror.restype = ctypes.c_char_p
@@ -162,6 +164,16 @@ def lc_encode_batch(ws, w_refs, nbits, outs, stream=None):
     if r < 0 and all(s >= 0 for s in sizes):
         raise LcError(-r)
     return [int(s) for s in sizes]
+
+
+def lc_blob_sizes(header_bytes):
+    """Checkpoint size in bits after each stage (Section 4.3): dict(E, EP, EPH), from the first 64+ bytes of a blob."""
+    buf = ctypes.create_string_buffer(bytes(header_bytes[:512]), 512)
+    bits = (_u64 * 3)()
+    st = int(_lib.lc_blob_sizes(buf, bits))
+    if st != 0:
+        raise LcError(st)
+    return dict(E=int(bits[0]), EP=int(bits[1]), EPH=int(bits[2]))
 
 
 def lc_decode_batch(blobs, w_refs, stream=None):

@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"lc_encode", "lc_encode_batch", "lc_decode_batch", "lc_batch_workspace_bytes", "lc_encode_t", "lc_decode_t", "lc_encode_cached", "lc_encode_async", "lc_encode_release_inputs", "lc_encode_wait", "lc_decode", "lc_decode_many", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
+    assert {"lc_encode", "lc_blob_sizes", "lc_encode_batch", "lc_decode_batch", "lc_batch_workspace_bytes", "lc_encode_t", "lc_decode_t", "lc_encode_cached", "lc_encode_async", "lc_encode_release_inputs", "lc_encode_wait", "lc_decode", "lc_decode_many", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
             "lc_blob_info", "lc_shutdown", "lc_strerror", "lc_profile", "lc_profile_read",
             "lc_profile_name"} <= set(names)
     for name in names:
@@ -60,6 +60,33 @@ def test_host_only_entry_points(lib):
     assert (n.value, nbits.value, total.value, status.value) == (12345, 3, 999, 0)
     hdr[0] = ord("X")
     assert lib.lc_blob_info(buf, None, None, None, None) == 4
+
+
+def test_blob_sizes_per_stage(lib):
+    """Section 3.1.1's worked example through the library's size breakdown (n = 10, k = 5: 190 bits), and the
+    three stages of a real blob against the oracle's accounting."""
+    import struct
+    import numpy as np
+    from oracle import lc_oracle as orc
+    bits = (ctypes.c_uint64 * 3)()
+    hdr = bytearray(64)
+    hdr[0:4] = b"LCB1"
+    struct.pack_into("<HHQI", hdr, 4, 1, 512, 10, 2)          # n = 10, x = 2
+    struct.pack_into("<QII", hdr, 40, 600, 0, 5)              # total bytes, status, k_E = 5
+    buf = (ctypes.c_uint8 * 64).from_buffer(hdr)
+    assert lib.lc_blob_sizes(buf, bits) == 0
+    assert (bits[0], bits[1], bits[2]) == (10 * 3 + 5 * 32, 10 * 2 + 4 * 32, 8 * 600)
+    rng = np.random.RandomState(0)
+    w_ref = (0.05 * rng.randn(40000)).astype(np.float32)
+    w = (w_ref + 1e-3 * rng.laplace(size=40000)).astype(np.float32)
+    for nbits in (2, 3, 4):
+        blob = orc.encode(w, w_ref, nbits)
+        acct = orc.accounting(blob)
+        head = (ctypes.c_uint8 * 512).from_buffer(bytearray(blob[:512].tobytes()))
+        assert lib.lc_blob_sizes(head, bits) == 0
+        assert (bits[0], bits[1], bits[2]) == (int(acct["bits_E"]), int(acct["bits_EP"]), int(acct["bits_EPH"]))
+    hdr[0] = ord("X")
+    assert lib.lc_blob_sizes(buf, bits) == 4 and lib.lc_blob_sizes(None, bits) == 1
 
 
 def test_workloads_have_the_stated_parameter_counts():
