@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblc.so")
-SOURCES = ["lc_kernels.hip", "lc_api.hip"]
+SOURCES = ["lc_encode.hip", "lc_decode.hip", "lc_api.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-ffp-contract=off",
          # packed fp32 instructions stay off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

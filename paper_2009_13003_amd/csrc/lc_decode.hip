@@ -1,0 +1,880 @@
+// Decode kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64): restore by
+// accumulation (Algorithm 1 line 7; Section 3, C1).
+//
+// lc_decode:        k_dec_check -> k_decode (gated on the check's verdict, no host round trip between)
+// lc_decode_many:   k_dec_check (all blobs) -> k_decode_fused<T> / k_decode_many per sweep
+// lc_decode_batch:  kb_dec_setup -> kb_dec_tables -> kb_dec_chunks -> kb_decode -> kb_dec_report
+#include "lc_device.h"
+
+namespace lc {
+
+// ----------------------------------------------------------------------------- k_dec_check
+// Everything lc_decode verifies before w_ref is touched, in one launch.  Every workgroup
+// re-reads the header and does the cheap sanity checks that keep its own reads in bounds;
+// workgroup 0 additionally validates the symbol table, rebuilds the canonical codes and the
+// look-up table; each wavefront checks one chunk: the offset table must be the running sum
+// of the record sizes that the lane lengths imply, from 0 to the blob's stated size.
+// Errors are raised with atomicMax on a word tagged with the call's epoch, so the word
+// never needs clearing.
+// Thread 0 of a workgroup: validates the header's symbol table, builds the canonical codes and fills
+// D.info; s_len / s_code (LDS, kMaxSym entries) are left for dec_build_luts.  Returns whether the blob passes.
+__device__ __forceinline__ bool dec_symbol_table(const u32* hdr, u64 n, u32 nchunks, u64 area, u64 tw, DecSet& D,
+                                                 u32* s_len, u32* s_code) {
+    const u32 nbits = hdr[4], K = hdr[5];
+    bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
+    if (nchunks == 0 && tw != 0) ok = false;
+    u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
+    u32 per_len[17];
+    for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+    for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; }
+    if (ok) {
+        for (u32 j = 0; j <= K; ++j) {
+            const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
+            const u64 cn = hdr[18 + 4 * j] | ((u64)hdr[19 + 4 * j] << 32);
+            const u32 bucket = w0 & 0xFFFFu, len = (w0 >> 16) & 0xFFu;
+            cnt_sum += cn;
+            if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
+            if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
+            if (j == K && rep != 0) ok = false;
+            s_len[j] = len; D.info.rep_bits[j] = rep;
+            if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
+        }
+        if (cnt_sum != n) ok = false;
+        if (active >= 2 && kraft != (1u << 15)) ok = false;
+        if (active == 1 && kraft != (1u << 14)) ok = false;
+    }
+    if (ok) {
+        u32 next_code[17], code = 0;
+        for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
+        for (u32 j = 0; j < kMaxSym; ++j) {
+            s_code[j] = s_len[j] ? next_code[s_len[j]]++ : 0;
+            D.info.len[j] = s_len[j]; D.info.code[j] = s_code[j];
+        }
+    }
+    D.info.K = K; D.info.max_len = max_len;
+    D.info.area = area; D.info.total_words = tw;
+    return ok;
+}
+
+// Two tables over the next P bits of a lane's string, entry = symbol | len << 4.  A prefix that
+// starts no code: symbol K with length 0 (the lane then falls short of its stated length); a
+// prefix of a code longer than P bits: 0xFF.  The first table (P = min(max_len, 7): 128 bytes,
+// one 32-bit word per LDS bank) resolves the frequent short codes without bank conflicts.
+__device__ __forceinline__ void dec_build_luts(DecSet& D, const u32* s_len, const u32* s_code, u32 t, u32 nthr) {
+    const u32 M = D.info.max_len, K = D.info.K;
+    const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+    for (u32 pass = 0; pass < 2; ++pass) {
+        const u32 P = pass ? P2 : P1;
+        uint8_t* lut = pass ? D.lut2 : D.lut1;
+        if (pass && M <= kDecLut1Bits) break;
+        for (u32 i = t; i < (1u << P); i += nthr) {
+            u32 entry = K;
+            for (u32 j = 0; j <= K; ++j) {
+                const u32 L = s_len[j];
+                if (L == 0) continue;
+                if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
+                else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+            }
+            lut[i] = (uint8_t)entry;
+        }
+    }
+}
+
+// One chunk's place in the offset table against the lane lengths of its record, by one wavefront.
+__device__ __forceinline__ bool dec_chunk_ok(const uint8_t* blob, u64 area, u64 tw, u32 nchunks, u32 c) {
+    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+    const u64 o0 = off_tab[c], o1 = off_tab[c + 1];
+    bool ok = o0 <= o1 && o1 <= tw && o1 - o0 >= kLaneBitsWords && (c > 0 || o0 == 0) && (c + 1 < nchunks || o1 == tw);
+    if (ok) {
+        const u32 lb = reinterpret_cast<const uint16_t*>(blob + area + 4 * o0)[lane_id()];
+        const u32 sum = wave_sum32(lb);
+        ok = (o1 - o0 == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb > kR * kV * 15);
+    }
+    return ok;
+}
+
+__device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u64 epoch, u32 status) {
+    const u64 word = (epoch << 8) | status;
+    atomicMax(&ws->dec_status, word);     // gates the decode sweep on the device
+    host->dec_status = word;              // what the host reads after waiting for the stream (any finding will do)
+}
+
+__global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u64 n, u64 max_total, Workspace* ws,
+                                                   u32 nchunks, u64 epoch, HostResult* host, u32 dtype) {
+    const u32 set = first + blockIdx.y, host_slot = set;     // one grid row per blob
+    const uint8_t* blob = blobs.p[set];
+    __shared__ u32 hdr[kHeaderBytes / 4];
+    __shared__ u32 s_ok;
+    __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
+    const u32 t = threadIdx.x, lane = lane_id();
+    if (t < kHeaderBytes / 4) hdr[t] = reinterpret_cast<const u32*>(blob)[t];
+    __syncthreads();
+    const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
+    const u64 area = chunk_area_of(nchunks);
+    const bool head_ok = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 &&
+                         hn == n && hdr[15] == dtype && hdr[9] == nchunks && total >= area && total <= max_total &&
+                         ((total - area) & 3) == 0;
+    if (!head_ok) {
+        if (blockIdx.x == 0 && t == 0) {
+            const bool n_mismatch = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0 &&
+                                    (hn != n || hdr[15] != dtype);       // a sound blob for another vector or element type
+            raise_status(ws, host, epoch, n_mismatch ? 1u : 4u);
+            host->bytes[host_slot] = 0; host->max_len[host_slot] = 0;
+        }
+        return;
+    }
+    const u64 tw = (total - area) / 4;
+    // ---- one chunk per wavefront
+    const u32 c = blockIdx.x * 4 + (t >> 6);
+    if (c < nchunks && !dec_chunk_ok(blob, area, tw, nchunks, c) && lane == 0) raise_status(ws, host, epoch, 4u);
+    if (blockIdx.x != 0) return;
+    // ---- workgroup 0: symbol table, codes, look-up table
+    DecSet& D = ws->dec_set[set];
+    if (t == 0) {
+        const bool ok = dec_symbol_table(hdr, n, nchunks, area, tw, D, s_len, s_code);
+        if (!ok) raise_status(ws, host, epoch, 4u);
+        host->bytes[host_slot] = total; host->max_len[host_slot] = D.info.max_len;
+        s_ok = ok;
+    }
+    __syncthreads();
+    if (!s_ok) return;
+    dec_build_luts(D, s_len, s_code, t, 256);
+}
+
+// ----------------------------------------------------------------------------- k_decode
+// Algorithm 1 line 7: one wavefront per chunk, lane l decoding its own string with a 64-bit
+// MSB-first window.  The chunk's payload is first copied to LDS with coalesced 16-byte loads, so
+// the lanes' word-by-word refills never go to memory.  Symbols come from the two look-up tables
+// (codes longer than 12 bits take a short search); the merged symbol adds -0.0, which leaves
+// every fp32 pattern unchanged, and a row in which no lane decoded a kept symbol is not written
+// back at all.
+constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average)
+
+template <int WAVES>
+struct DecLdsT {
+    uint8_t lut1[1u << kDecLut1Bits];
+    uint8_t lut2[1u << kDecLut2Bits];
+    float rep[kMaxSym];
+    u32 len[kMaxSym], code[kMaxSym];
+    uint4 payload[WAVES][kPayWords / 4 + 1];
+};
+typedef DecLdsT<4> DecLds;
+
+template <typename LDS>
+__device__ __noinline__ u32 decode_long(const LDS& L, u64 win, u32 K) {
+    const u32 peek = (u32)(win >> (64 - 15));
+    for (u32 j = 0; j <= K; ++j) {
+        const u32 l = L.len[j];
+        if (l > kDecLut2Bits && (peek >> (15 - l)) == L.code[j]) return j | (l << 4);
+    }
+    return K;
+}
+
+// MSB-first bit window over payload words that live in LDS (STAGED) or in global memory.
+template <bool STAGED>
+struct BitReader {
+    const u32* pw;                   // payload words (index 0 = first word of the chunk's payload)
+    u32 last;                        // index of the last payload word (reads are clamped to it)
+    u64 win;                         // next bits, left aligned
+    u32 avail, wi, next;             // valid bits in win; index of `next`; the word after the window
+    __device__ __forceinline__ u32 word(u32 i) const { return pw[min(i, last)]; }
+    __device__ __forceinline__ void start(const u32* words, u32 nwords, u32 first_bit) {
+        pw = words; last = nwords - 1;
+        wi = first_bit >> 5;
+        const u32 sh = first_bit & 31;
+        win = (((u64)word(wi) << 32) | word(wi + 1)) << sh;
+        avail = 64 - sh;
+        wi += 2;
+        next = word(wi);
+    }
+    __device__ __forceinline__ void refill() {           // call when avail <= 32
+        win |= (u64)next << (32 - avail);
+        avail += 32; ++wi;
+        next = word(wi);
+    }
+};
+
+// `raise(code)` reports a lane string that does not decode to its stated length.
+template <bool FAST, bool LV2, bool STAGED, int DT, typename LDS, typename Raise>
+__device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
+                                            void* __restrict__ w_ref, u64 n, u32 c,
+                                            const LDS& L, u32 P1, u32 P2, u32 K, Raise& raise) {
+    const u32 lane = lane_id();
+    BitReader<STAGED> br;
+    br.start(words, nwords, first_bit);
+    const u32 wi0 = br.wi, avail0 = br.avail;
+    const u32 shr1 = 64 - P1, shr2 = 64 - P2;
+    const u64 base = (u64)c * kChunk;
+#pragma unroll 4
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        if (!FAST && idx >= n) break;
+        float x[4];
+        load_row<FAST, DT>(w_ref, idx, n, x);
+        u32 smin = K;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (FAST || idx + v < n) {
+                u32 e = L.lut1[(u32)(br.win >> shr1)];
+                if (LV2 && e == 0xFF) {
+                    e = L.lut2[(u32)(br.win >> shr2)];
+                    if (e == 0xFF) e = decode_long(L, br.win, K);
+                }
+                const u32 len = e >> 4, sy = e & 15;
+                br.win <<= len; br.avail -= len;
+                smin = min(smin, sy);
+                x[v] = __fadd_rn(x[v], L.rep[sy]);
+            }
+            if ((v & 1) && br.avail <= 32) br.refill();
+        }
+        if (FAST) {
+            if (__any(smin < K)) store4<DT>(w_ref, idx, x);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) if (idx + v < n) store_one<DT>(w_ref, idx + v, x[v]);
+        }
+    }
+    const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
+    if (__any(used != lane_bits) && lane == 0) raise(4u);
+}
+
+template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
+__device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
+                                             u32 c, LDS& L, u32 P1, u32 P2, u32 K, u64 area, Raise& raise) {
+    const u32 lane = lane_id(), wv = threadIdx.x >> 6;
+    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+    const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
+    const uint8_t* rec = blob + area + 4 * (u64)o0;
+    const u32 nwords = o1 - o0 - kLaneBitsWords;        // >= 1 (validated)
+    const u32 lane_bits = reinterpret_cast<const uint16_t*>(rec)[lane];
+    const u32 o = wave_incl_scan(lane_bits) - lane_bits;
+    const u32* gw = reinterpret_cast<const u32*>(rec + 2 * kW);
+    const u32 k0 = (u32)((reinterpret_cast<uintptr_t>(gw) >> 2) & 3);     // words between the 16-byte boundary and the payload
+    if (nwords + k0 <= kPayWords) {
+        // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
+        // record's own lane lengths, and the last vector is read word by word so no read passes the end
+        const uint4* gv = reinterpret_cast<const uint4*>(gw - k0);
+        const u32 nvec = (nwords + k0 + 3) >> 2;
+        for (u32 i = lane; i < nvec; i += kW) {
+            uint4 q;
+            if (4 * i + 4 <= nwords + k0) q = gv[i];
+            else {
+                const u32* t = reinterpret_cast<const u32*>(gv + i);
+                const u32 left = nwords + k0 - 4 * i;
+                q.x = t[0]; q.y = left > 1 ? t[1] : 0; q.z = left > 2 ? t[2] : 0; q.w = 0;
+            }
+            L.payload[wv][i] = q;
+        }
+        decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
+                                         w_ref, n, c, L, P1, P2, K, raise);
+    } else {
+        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, raise);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
+                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
+    __shared__ DecLds L;
+    // if the check kernel found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
+        const u32 t = threadIdx.x;
+        const DecSet& D = ws->dec_set[0];
+        const u32 M = D.info.max_len, K = D.info.K;
+        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+        const u64 area = D.info.area;
+        if (t < (1u << P1)) L.lut1[t] = D.lut1[t];
+        if (M > kDecLut1Bits) {
+            if ((1u << P2) >= 4096) {
+                const uint4* src = reinterpret_cast<const uint4*>(D.lut2);
+                uint4* dst = reinterpret_cast<uint4*>(L.lut2);
+                for (u32 i = t; i < (1u << P2) / 16; i += 256) dst[i] = src[i];
+            } else {
+                for (u32 i = t; i < (1u << P2); i += 256) L.lut2[i] = D.lut2[i];
+            }
+        }
+        if (t < kMaxSym) {
+            L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
+            L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
+        }
+        __syncthreads();
+        const u32 wave = t >> 6;
+        auto raise = [&](u32 code) { raise_status(ws, host, epoch, code); };
+        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+            const bool full = (u64)(c + 1) * kChunk <= n;
+            if (full && aligned) {
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+            } else {
+                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- batched decode
+// lc_decode_batch: the blobs of many tensors restored in five launches.  Every blob is validated as
+// lc_decode validates it (header and symbol table per tensor, then every chunk's place in its offset
+// table) before the sweep; a tensor whose blob fails is left untouched and reported, the others are
+// restored.  The sweep deals the chunks of all tensors round-robin to single-wavefront workgroups,
+// which reload their look-up tables when they move on to another tensor's chunk.
+__global__ __launch_bounds__(256) void kb_dec_setup(BatchDecArgs a) {
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x, nthr = gridDim.x * blockDim.x;
+    for (u32 g = i; g < a.total_chunks; g += nthr) {
+        u32 lo = 0, hi = a.count - 1;
+        while (lo < hi) {
+            const u32 mid = (lo + hi + 1) >> 1;
+            if (a.segs[mid].chunk0 <= g) lo = mid; else hi = mid - 1;
+        }
+        while (lo > 0 && (a.segs[lo].nchunks == 0 || g >= a.segs[lo].chunk0 + a.segs[lo].nchunks)) --lo;
+        a.seg_of_chunk[g] = lo;
+    }
+    for (u32 t = i; t < a.count; t += nthr) a.seg_status[t] = 0;
+}
+
+// One workgroup per tensor: header, symbol table, codes, look-up tables.
+__global__ __launch_bounds__(256) void kb_dec_tables(BatchDecArgs a) {
+    __shared__ u32 hdr[kHeaderBytes / 4];
+    __shared__ u32 s_ok;
+    __shared__ u32 s_len[kMaxSym], s_code[kMaxSym];
+    const u32 t = threadIdx.x, sidx = blockIdx.x;
+    const SegD& sg = a.segs[sidx];
+    DecSet& D = a.sets[sidx];
+    if (t < kHeaderBytes / 4) hdr[t] = reinterpret_cast<const u32*>(sg.blob)[t];
+    __syncthreads();
+    if (t == 0) {
+        const u64 hn = hdr[2] | ((u64)hdr[3] << 32), total = hdr[10] | ((u64)hdr[11] << 32);
+        const u64 area = chunk_area_of(sg.nchunks);
+        // the largest blob lc_encode can produce for this n (nbits 4): header + offsets + 132 bytes per chunk + n/2
+        const u64 max_total = area + (u64)sg.nchunks * (2 * kW + 4) + (sg.n * 4 + 7) / 8;
+        const bool sound = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0;
+        const bool head_ok = sound && hn == sg.n && hdr[15] == (u32)kF32 && hdr[9] == sg.nchunks && total >= area &&
+                             total <= max_total && ((total - area) & 3) == 0;
+        bool ok = head_ok;
+        u32 status = 0;
+        if (!head_ok) status = (sound && (hn != sg.n || hdr[15] != (u32)kF32)) ? 1u : 4u;
+        else if (!dec_symbol_table(hdr, sg.n, sg.nchunks, area, (total - area) / 4, D, s_len, s_code)) { ok = false; status = 4u; }
+        if (!ok) { atomicMax(&a.seg_status[sidx], status); D.info.area = 0; D.info.total_words = 0; D.info.max_len = 0; D.info.K = 0; }
+        D.info.pad[0] = ok ? 1u : 0u;                        // the chunk checks and the sweep look here first
+        D.info.pad[1] = 0;
+        s_ok = ok;
+    }
+    __syncthreads();
+    if (s_ok) dec_build_luts(D, s_len, s_code, t, 256);
+}
+
+__global__ __launch_bounds__(256) void kb_dec_chunks(BatchDecArgs a) {
+    const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (g >= a.total_chunks) return;
+    const u32 sidx = a.seg_of_chunk[g];
+    const SegD& sg = a.segs[sidx];
+    const DecInfo& I = a.sets[sidx].info;
+    if (!I.pad[0]) return;
+    if (!dec_chunk_ok(sg.blob, I.area, I.total_words, sg.nchunks, g - sg.chunk0) && lane_id() == 0) atomicMax(&a.seg_status[sidx], 4u);
+}
+
+__global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
+    __shared__ DecLdsT<1> L;
+    const u32 lane = threadIdx.x;
+    u32 active = 0xFFFFFFFFu, M = 0, K = 0, P1 = 0, P2 = 0;
+    u64 area = 0;
+    for (u32 g = blockIdx.x; g < a.total_chunks; g += gridDim.x) {
+        const u32 sidx = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
+        // a tensor whose blob failed a check is not touched
+        if (__hip_atomic_load(&a.seg_status[sidx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) continue;
+        const SegD& sg = a.segs[sidx];
+        if (sidx != active) {
+            active = sidx;
+            const DecSet& D = a.sets[sidx];
+            M = D.info.max_len; K = D.info.K; area = D.info.area;
+            P1 = M < kDecLut1Bits ? M : kDecLut1Bits; P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+            __syncthreads();
+            for (u32 i = lane; i < (1u << P1); i += kW) L.lut1[i] = D.lut1[i];
+            if (M > kDecLut1Bits) {
+                const u32* src = reinterpret_cast<const u32*>(D.lut2);
+                u32* dst = reinterpret_cast<u32*>(L.lut2);
+                for (u32 i = lane; i < ((1u << P2) + 3) / 4; i += kW) dst[i] = src[i];
+            }
+            if (lane < kMaxSym) {
+                L.rep[lane] = __uint_as_float(lane < K ? D.info.rep_bits[lane] : 0x80000000u);
+                L.len[lane] = D.info.len[lane]; L.code[lane] = D.info.code[lane];
+            }
+            __syncthreads();
+        }
+        auto raise = [&](u32 code) { atomicMax(&a.seg_status[sidx], code); };
+        const u32 c = g - sg.chunk0;
+        const bool full = (u64)(c + 1) * kChunk <= sg.n;
+        if (full && sg.aligned) {
+            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+        } else {
+            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void kb_dec_report(BatchDecArgs a) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.count) return;
+    const u32 st = a.seg_status[t];
+    const DecInfo& I = a.sets[t].info;
+    a.results[t].status = st;
+    a.results[t].bytes = st ? 0 : I.area + 4 * I.total_words;
+    a.results[t].used_cache = 0;
+}
+
+// ----------------------------------------------------------------------------- k_decode_many
+// Restore from several checkpoints in one sweep (Section 3, C1: u_t = u_0 + sum of the decoded
+// deltas; Section 3.2, checkpoint merging): up to kMaxMany blobs of the same n are decoded side
+// by side and their values added to w_ref in blob order, one fp32 add per blob and element, so
+// the result equals that of applying the blobs one call after the other, with one read and
+// one write of w_ref instead of one per blob.  Lane strings are read straight from memory.
+struct ManyLds {
+    uint8_t lut1[kMaxMany][1u << kDecLut1Bits];
+    uint8_t lut2[kMaxMany][1u << kDecLut2Bits];
+    float rep[kMaxMany][kMaxSym];
+    u32 len[kMaxMany][kMaxSym], code[kMaxMany][kMaxSym];
+    u32 K[kMaxMany], P1[kMaxMany], P2[kMaxMany];
+    u64 area[kMaxMany];
+};
+
+__device__ __noinline__ u32 decode_long_many(const ManyLds& L, u32 t, u64 win) {
+    const u32 peek = (u32)(win >> (64 - 15)), K = L.K[t];
+    for (u32 j = 0; j <= K; ++j) {
+        const u32 l = L.len[t][j];
+        if (l > kDecLut2Bits && (peek >> (15 - l)) == L.code[t][j]) return j | (l << 4);
+    }
+    return K;
+}
+
+template <bool FAST>
+__device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
+                                                  Workspace* ws, HostResult* host, u32 c, const ManyLds& L, u64 epoch) {
+    const u32 lane = lane_id();
+    BitReader<false> br[kMaxMany];
+    u32 wi0[kMaxMany], avail0[kMaxMany], lane_bits[kMaxMany];
+#pragma unroll
+    for (int t = 0; t < kMaxMany; ++t) {
+        if ((u32)t < T) {
+            const uint8_t* blob = blobs.p[first + t];
+            const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+            const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
+            const uint8_t* rec = blob + L.area[t] + 4 * (u64)o0;
+            lane_bits[t] = reinterpret_cast<const uint16_t*>(rec)[lane];
+            const u32 o = wave_incl_scan(lane_bits[t]) - lane_bits[t];
+            br[t].start(reinterpret_cast<const u32*>(rec + 2 * kW), o1 - o0 - kLaneBitsWords, o);
+            wi0[t] = br[t].wi; avail0[t] = br[t].avail;
+        }
+    }
+    const u64 base = (u64)c * kChunk;
+#pragma unroll 2
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        if (!FAST && idx >= n) break;
+        float x[4];
+        load_row<FAST>(w_ref, idx, n, x);
+        u32 kept = 0;
+#pragma unroll
+        for (int t = 0; t < kMaxMany; ++t) {
+            if ((u32)t < T) {
+                const u32 shr1 = 64 - L.P1[t], shr2 = 64 - L.P2[t], K = L.K[t];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if (FAST || idx + v < n) {
+                        u32 e = L.lut1[t][(u32)(br[t].win >> shr1)];
+                        if (e == 0xFF) {
+                            e = L.lut2[t][(u32)(br[t].win >> shr2)];
+                            if (e == 0xFF) e = decode_long_many(L, t, br[t].win);
+                        }
+                        const u32 len = e >> 4, sy = e & 15;
+                        br[t].win <<= len; br[t].avail -= len;
+                        kept |= K - sy;
+                        x[v] = __fadd_rn(x[v], L.rep[t][sy]);
+                    }
+                    if ((v & 1) && br[t].avail <= 32) br[t].refill();
+                }
+            }
+        }
+        if (FAST) {
+            if (__any(kept != 0)) *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
+        }
+    }
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < kMaxMany; ++t)
+        if ((u32)t < T) bad = bad || (avail0[t] + 32 * (br[t].wi - wi0[t]) - br[t].avail != lane_bits[t]);
+    if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
+}
+
+__global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
+                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
+    __shared__ ManyLds L;
+    // if a check found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
+        const u32 tid = threadIdx.x;
+        for (u32 t = 0; t < T; ++t) {
+            const DecSet& D = ws->dec_set[first + t];
+            const u32 M = D.info.max_len, K = D.info.K;
+            const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
+            if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
+            if (M > kDecLut1Bits) for (u32 i = tid; i < (1u << P2); i += 256) L.lut2[t][i] = D.lut2[i];
+            if (tid < kMaxSym) {
+                L.rep[t][tid] = __uint_as_float(tid < K ? D.info.rep_bits[tid] : 0x80000000u);
+                L.len[t][tid] = D.info.len[tid]; L.code[t][tid] = D.info.code[tid];
+            }
+            if (tid == 0) { L.K[t] = K; L.P1[t] = P1; L.P2[t] = P2; L.area[t] = D.info.area; }
+        }
+        __syncthreads();
+        const u32 wave = tid >> 6;
+        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+            const bool full = (u64)(c + 1) * kChunk <= n;
+            if (full && aligned) decode_many_chunk<true>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
+            else decode_many_chunk<false>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_decode_fused
+// The same restore for blobs whose codes are all at most 7 bits long (always the case for
+// nbits <= 3), built for throughput.  T is a compile-time constant, so the T bit strings of a
+// lane are T independent dependency chains that the scheduler interleaves.  One wavefront per
+// workgroup; the payloads of a chunk (all T blobs) are staged in the workgroup's LDS area with
+// coalesced loads (the host sizes the area to the blobs, which also sets how many wavefronts
+// share a compute unit).  A row's 4 codes of one blob take at most 28 bits, so each blob's 32-bit
+// window is re-read once per row from the bit position alone, without a branch.  Both look-up
+// tables are free of LDS bank conflicts: 128 one-byte entries over the next 7 bits (code length
+// and symbol), then the symbol's representative.  A chunk whose payloads do not fit the LDS
+// area reads them from memory instead.
+template <int T>
+struct FusedHead {
+    uint16_t lut[T][1u << kDecLut1Bits];         // next 7 bits -> e = (len << 4 | symbol) << 2
+    u32 rep[T][128];                             // byte offset e -> representative bits (-0.0: merged symbol); a symbol
+                                                 // has one length, so distinct entries in use lie in distinct banks
+    const uint8_t* rec_base[T];                  // start of the chunk records
+    const u32* off_tab[T];
+    u32 pad[3];
+    u32 before_pay;                              // the word in front of the payload area (read, never used)
+};
+constexpr u32 kFusedSlack = 64;                  // words behind the payloads that a damaged lane string may run into:
+                                                 // 256 codes of at most 7 bits past a start that validation bounds
+
+// Bit positions are kept as p = 31 + bits from the start of the payload area (staged) or of the
+// blob's payload (from memory): the window is then the low 32 bits of {word[(p >> 5) - 1],
+// word[p >> 5]} >> (~p & 31), which is one v_alignbit.
+template <int T, bool FAST, bool STAGED>
+__device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
+                                          const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u64 idx,
+                                          float (&x)[4]) {
+    // Written step by step across the blobs (all windows, then the first code of every blob, ...), so
+    // that the T look-ups of a step are in flight together.
+    u32 win[T], rep[4][T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        u32 hi, lo;                                   // the two payload words around the lane's position
+        if (STAGED) {
+            const u32 wi = pos[t] >> 5;              // stays inside the area and its slack
+            hi = pay[(int)wi - 1]; lo = pay[wi];
+        } else {
+            const u32 wi = pos[t] >> 5, last = nw[t] - 1;
+            hi = wi ? gw[t][min(wi - 1, last)] : 0u; lo = gw[t][min(wi, last)];
+        }
+        win[t] = __builtin_amdgcn_alignbit(hi, lo, ~pos[t]);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        if (FAST || idx + v < n) {
+            u32 e[T];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                e[t] = H.lut[t][win[t] >> (32 - kDecLut1Bits)];
+                asm("" : "+v"(e[t]));                 // keep e a 32-bit value (no 16-bit shift plus re-extension)
+            }
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const u32 len = e[t] >> 6;
+                rep[v][t] = *reinterpret_cast<const u32*>(reinterpret_cast<const uint8_t*>(H.rep[t]) + e[t]);
+                win[t] <<= len; pos[t] += len;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < T; ++t) rep[v][t] = 0x80000000u;
+        }
+    }
+    u32 kept = 1;                                     // a single blob often leaves whole rows unchanged: skip their write
+    if (T == 1) kept = (rep[0][0] | rep[1][0] | rep[2][0] | rep[3][0]) & 0x7FFFFFFFu;
+    if (FAST) {
+        if (T > 1 || __any(kept != 0)) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));   // in blob order
+            *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (idx + v < n) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));
+                w_ref[idx + v] = x[v];
+            }
+        }
+    }
+}
+
+// All rows of a full, aligned chunk with staged payloads: w_ref is read PF rows ahead in two
+// alternating register batches, so the reads of the next rows are in flight while these decode.
+template <int T>
+__device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
+                                                const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u32 c) {
+    constexpr int PF = 4;
+    const u32 lane = lane_id();
+    float4* rows = reinterpret_cast<float4*>(w_ref + (u64)c * kChunk) + lane;
+    const u64 base = (u64)c * kChunk + lane * kV;
+    float4 A[PF], B[PF];
+#pragma unroll
+    for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + k * kW);
+    auto batch = [&](float4 (&X)[PF], u32 r0) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+            float x[4] = {X[k].x, X[k].y, X[k].z, X[k].w};
+            fused_row<T, true, true>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
+        }
+    };
+    for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) B[k] = load_stream(rows + (r0 + PF + k) * kW);
+        batch(A, r0);
+        if (r0 + 2 * PF < kR) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + (r0 + 2 * PF + k) * kW);
+        }
+        batch(B, r0 + PF);
+    }
+}
+
+// Any chunk (ragged, unaligned, or payloads read from memory), row by row.
+template <int T, bool FAST>
+__device__ __forceinline__ void fused_rows_plain(const FusedHead<T>& H, const u32* const (&gw)[T], const u32 (&nw)[T], u32 (&pos)[T],
+                                              float* __restrict__ w_ref, u64 n, u32 c) {
+    const u32 lane = lane_id();
+    const u64 base = (u64)c * kChunk;
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        if (!FAST && idx >= n) break;
+        float x[4];
+        load_row<FAST>(w_ref, idx, n, x);
+        fused_row<T, FAST, false>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
+    }
+}
+
+template <typename P>
+__device__ __forceinline__ P* uniform_ptr(P* p) {        // a pointer every lane holds alike, moved to scalar registers
+    const u64 v = reinterpret_cast<u64>(p);
+    const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+    return reinterpret_cast<P*>(((u64)hi << 32) | lo);
+}
+
+template <int T, bool FAST>
+__device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32 pay_words, float* __restrict__ w_ref, u64 n,
+                                            Workspace* ws, HostResult* host, u32 c, u32 nchunks, u64 epoch) {
+    const u32 lane = lane_id();
+    const u32* gw[T];
+    u32 nw[T], k0[T], wbase[T], pos[T], start[T], lane_bits[T];
+    u32 total = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const u32* ot = uniform_ptr(H.off_tab[t]);
+        const u32 o0 = ot[c], o1 = ot[c + 1];
+        const uint8_t* rec = uniform_ptr(H.rec_base[t]) + 4 * (u64)o0;
+        nw[t] = o1 - o0 - kLaneBitsWords;                 // >= 1 (validated)
+        lane_bits[t] = reinterpret_cast<const uint16_t*>(rec)[lane];
+        gw[t] = reinterpret_cast<const u32*>(rec + 2 * kW);
+        k0[t] = (u32)((reinterpret_cast<uintptr_t>(gw[t]) >> 2) & 3);
+        wbase[t] = total;
+        total += (nw[t] + k0[t] + 3) & ~3u;
+    }
+    const bool staged = FAST && total <= pay_words;
+    if (staged) {
+        // Coalesced copies of [16-byte aligned start, payload end) into the LDS area; the words before a
+        // payload are its record's lane lengths.  A last partial vector may read up to 12 bytes past the
+        // payload: into the next record, except in the last chunk, which reads that vector word by word.
+        constexpr int CV = T > 4 ? 2 : 4;                 // vectors per lane and blob in flight
+        const bool guard = c + 1 == nchunks;
+        u32 most = 0;
+#pragma unroll
+        for (int t = 0; t < T; ++t) most = max(most, (nw[t] + k0[t] + 3) >> 2);
+        for (u32 i0 = 0; i0 < most; i0 += CV * kW) {
+            uint4 q[T][CV];
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint4* gv = reinterpret_cast<const uint4*>(gw[t] - k0[t]);
+                const u32 have = nw[t] + k0[t], nvec = (have + 3) >> 2;
+#pragma unroll
+                for (int k = 0; k < CV; ++k) {
+                    const u32 i = i0 + k * kW + lane;
+                    if (i < nvec) {
+                        if (!guard || 4 * i + 4 <= have) q[t][k] = gv[i];
+                        else {
+                            const u32* tw = reinterpret_cast<const u32*>(gv + i);
+                            const u32 left = have - 4 * i;
+                            q[t][k].x = tw[0]; q[t][k].y = left > 1 ? tw[1] : 0; q[t][k].z = left > 2 ? tw[2] : 0; q[t][k].w = 0;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                uint4* dst = reinterpret_cast<uint4*>(pay + wbase[t]);
+                const u32 nvec = (nw[t] + k0[t] + 3) >> 2;
+#pragma unroll
+                for (int k = 0; k < CV; ++k) {
+                    const u32 i = i0 + k * kW + lane;
+                    if (i < nvec) dst[i] = q[t][k];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t) start[t] = 31 + wave_incl_scan(lane_bits[t]) - lane_bits[t];
+    if (staged) {
+#pragma unroll
+        for (int t = 0; t < T; ++t) { start[t] += 32 * (wbase[t] + k0[t]); pos[t] = start[t]; }
+        fused_rows_fast<T>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
+    } else {
+#pragma unroll
+        for (int t = 0; t < T; ++t) pos[t] = start[t];
+        fused_rows_plain<T, FAST>(H, gw, nw, pos, w_ref, n, c);
+    }
+    bool bad = false;
+#pragma unroll
+    for (int t = 0; t < T; ++t) bad = bad || (pos[t] - start[t] != lane_bits[t]);
+    if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
+}
+
+template <int T>
+__global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, float* __restrict__ w_ref, u64 n,
+                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch,
+                                                     HostResult* host, u32 pay_words) {
+    __shared__ FusedHead<T> H;
+    static_assert(sizeof(FusedHead<T>) % 16 == 0, "payload area must stay 16-byte aligned");
+    extern __shared__ uint4 fused_pay[];                 // pay_words + kFusedSlack payload words, right behind H
+    u32* pay = reinterpret_cast<u32*>(fused_pay);
+    // if a check found something, touch nothing
+    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) == epoch) return;
+    const u32 tid = threadIdx.x;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const DecSet& D = ws->dec_set[first + t];
+        const u32 M = D.info.max_len, K = D.info.K;       // M <= 7: e < 128
+        const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits;
+        for (u32 i = tid; i < (1u << kDecLut1Bits); i += kW) {
+            const u32 e = D.lut1[i >> (kDecLut1Bits - P1)];
+            H.lut[t][i] = (uint16_t)(e << 2);
+            H.rep[t][i] = (i & 15) < K ? D.info.rep_bits[i & 15] : 0x80000000u;
+        }
+        if (tid == 0) {
+            const uint8_t* blob = blobs.p[first + t];
+            H.rec_base[t] = blob + D.info.area;
+            H.off_tab[t] = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+        }
+    }
+    if (tid == 0) H.before_pay = 0;
+    __syncthreads();
+    for (u32 c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const bool full = (u64)(c + 1) * kChunk <= n;
+        if (full && aligned) fused_chunk<T, true>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        else fused_chunk<T, false>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+    }
+}
+// ----------------------------------------------------------------------------- launchers
+void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t s) {
+    const u32 cap = (u32)tune.num_cu * 8;
+    u32 setup_blocks = (a.total_chunks + 255) / 256;
+    if (setup_blocks > cap) setup_blocks = cap;
+    if (setup_blocks < 1) setup_blocks = 1;
+    hipLaunchKernelGGL(kb_dec_setup, dim3(setup_blocks), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(kb_dec_tables, dim3(a.count), dim3(256), 0, s, a);
+    if (a.total_chunks) {
+        hipLaunchKernelGGL(kb_dec_chunks, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
+        u32 waves = (u32)tune.num_cu * (u32)tune.decode_blocks_per_cu * 4u;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_decode, dim3(waves), dim3(64), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_dec_report, dim3((a.count + 255) / 256), dim3(256), 0, s, a);
+}
+
+void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
+                      uint64_t epoch, HostResult* host, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
+    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
+                       ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
+}
+
+void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+                        uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (nchunks + 3) / 4;
+    const u64 cap = (u64)tune.num_cu * tune.many_blocks_per_cu;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)first, (u32)count, w_ref, (u64)n, ws,
+                       (u32)nchunks, (int)aligned16(w_ref), (u64)epoch, host);
+}
+
+
+template <int T>
+static void launch_fused_t(const BlobList& blobs, int first, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                           HostResult* host, u32 blocks, u32 pay_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_decode_fused<T>, dim3(blocks), dim3(64), 4 * (size_t)(pay_words + kFusedSlack), s, blobs, (u32)first, w_ref,
+                       (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
+}
+
+size_t fused_lds_bytes(int count, uint32_t pay_words) {
+    static const size_t head[kMaxMany] = {sizeof(FusedHead<1>), sizeof(FusedHead<2>), sizeof(FusedHead<3>), sizeof(FusedHead<4>),
+                                          sizeof(FusedHead<5>), sizeof(FusedHead<6>), sizeof(FusedHead<7>), sizeof(FusedHead<8>)};
+    return head[count - 1] + 4 * (size_t)(pay_words + kFusedSlack);
+}
+
+void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+                         uint64_t epoch, HostResult* host, uint32_t pay_words, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    // one wavefront per workgroup; as many workgroups per compute unit as their LDS areas allow
+    u64 per_cu = kLdsPerCu / fused_lds_bytes(count, pay_words);
+    if (per_cu > (u64)tune.fused_waves_per_cu) per_cu = tune.fused_waves_per_cu;
+    if (per_cu < 1) per_cu = 1;
+    u64 blocks = (u64)tune.num_cu * per_cu;
+    if (blocks > nchunks) blocks = nchunks;
+    const u32 b = (u32)blocks;
+    switch (count) {
+        case 1: launch_fused_t<1>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 2: launch_fused_t<2>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 3: launch_fused_t<3>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 4: launch_fused_t<4>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 5: launch_fused_t<5>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 6: launch_fused_t<6>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 7: launch_fused_t<7>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        default: launch_fused_t<8>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+    }
+}
+
+void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch, HostResult* host,
+                   const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (nchunks + 3) / 4;
+    const u64 cap = (u64)tune.num_cu * tune.decode_blocks_per_cu;
+    if (blocks > cap) blocks = cap;
+    const dim3 grid((u32)blocks), wg(256);
+    const int al = aligned_rows(w_ref, dtype);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+}
+
+}  // namespace lc

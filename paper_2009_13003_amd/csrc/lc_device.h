@@ -1,0 +1,123 @@
+// Device-side helpers shared by the encode and the decode kernels (gfx950, wave64): wavefront
+// reductions and scans, the fp32 delta, streaming loads, and the element types of the parameter arrays.
+#pragma once
+#include "lc_internal.h"
+
+namespace lc {
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+// ----------------------------------------------------------------------------- small helpers
+__device__ __forceinline__ u32 lane_id() { return __lane_id(); }
+
+__device__ __forceinline__ u32 wave_incl_scan(u32 v) {
+    const u32 lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        u32 t = __shfl_up(v, d, 64);
+        if (lane >= (u32)d) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ u64 wave_sum64(u64 v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+__device__ __forceinline__ u32 wave_sum32(u32 v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+// delta of Algorithm 1 line 4: one IEEE binary32 subtraction (never fused or reassociated).
+__device__ __forceinline__ u32 delta_bits(float w, float w_ref) { return __float_as_uint(__fsub_rn(w, w_ref)); }
+
+// 16-byte load of data that is read once: marked non-temporal so that the stream does not push
+// other lines out of the caches (measured: +10 % read bandwidth on the sweeps).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_stream(const float4* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+// ---- element types of the parameter arrays.  The method works on the fp32 delta (Algorithm 1 line 4):
+// bf16 / fp16 parameters are widened exactly on load, and the restored value fl32(w_ref + rep) is rounded
+// once, to nearest even, on store.  Raw<DT> is what one lane holds of one row: 4 consecutive elements.
+template <int DT> struct Raw { typedef uint2 type; };
+template <> struct Raw<kF32> { typedef float4 type; };
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int DT> __device__ __forceinline__ constexpr u32 elem_bytes() { return DT == kF32 ? 4u : 2u; }
+
+// 4 consecutive elements starting at element index i (a multiple of 4, base aligned to 4 elements), non-temporal
+template <int DT>
+__device__ __forceinline__ typename Raw<DT>::type load_raw(const void* base, u64 i) {
+    if constexpr (DT == kF32) {
+        return load_stream(reinterpret_cast<const float4*>(static_cast<const float*>(base) + i));
+    } else {
+        const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(base) + i));
+        return make_uint2(v.x, v.y);
+    }
+}
+
+__device__ __forceinline__ float widen16(u32 h, bool bf16) {
+    return bf16 ? __uint_as_float(h << 16) : (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+}
+__device__ __forceinline__ u32 narrow16(float x, bool bf16) {      // finite x, round to nearest even
+    if (bf16) { const u32 u = __float_as_uint(x); return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; }
+    return (u32)__builtin_bit_cast(unsigned short, (_Float16)x);      // v_cvt_f16_f32, round to nearest even
+}
+
+template <int DT>
+__device__ __forceinline__ void unpack(const typename Raw<DT>::type& r, float (&x)[4]) {
+    if constexpr (DT == kF32) { x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w; }
+    else {
+        x[0] = widen16(r.x & 0xFFFFu, DT == kBF16); x[1] = widen16(r.x >> 16, DT == kBF16);
+        x[2] = widen16(r.y & 0xFFFFu, DT == kBF16); x[3] = widen16(r.y >> 16, DT == kBF16);
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ float load_one(const void* base, u64 i) {
+    if constexpr (DT == kF32) return static_cast<const float*>(base)[i];
+    else return widen16(static_cast<const uint16_t*>(base)[i], DT == kBF16);
+}
+
+template <int DT>
+__device__ __forceinline__ void store_one(void* base, u64 i, float x) {
+    if constexpr (DT == kF32) static_cast<float*>(base)[i] = x;
+    else static_cast<uint16_t*>(base)[i] = (uint16_t)narrow16(x, DT == kBF16);
+}
+
+template <int DT>
+__device__ __forceinline__ void store4(void* base, u64 i, const float (&x)[4]) {
+    if constexpr (DT == kF32) {
+        *reinterpret_cast<float4*>(static_cast<float*>(base) + i) = make_float4(x[0], x[1], x[2], x[3]);
+    } else {
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + i) =
+            make_uint2(narrow16(x[0], DT == kBF16) | (narrow16(x[1], DT == kBF16) << 16),
+                       narrow16(x[2], DT == kBF16) | (narrow16(x[3], DT == kBF16) << 16));
+    }
+}
+
+template <bool FAST, int DT = kF32>
+__device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u64 n, float (&x)[4]) {
+    if (FAST) {
+        unpack<DT>(load_raw<DT>(p, idx), x);
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? load_one<DT>(p, idx + v) : 0.0f;
+    }
+}
+
+// ---- host-side helpers of the launchers
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+static inline bool aligned_rows(const void* p, int dtype) {     // 4 consecutive elements per access
+    return (reinterpret_cast<uintptr_t>(p) & (dtype == kF32 ? 15 : 7)) == 0;
+}
+
+}  // namespace lc

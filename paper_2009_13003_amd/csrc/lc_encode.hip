@@ -1,0 +1,1000 @@
+// Encode kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64).
+//
+// lc_encode:         k_hist -> k_table -> k_pack -> k_place -> k_finalize (which also clears the scratch
+//                    state for the next call); k_reset only for a fresh scratch area
+// lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place -> k_finalize
+// lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_pack -> kb_place -> kb_finalize
+//
+// The paper (arXiv 2009.13003) defines what is computed: delta against the last
+// recovered state (Algorithm 1 line 4), (sign, exponent) buckets represented by the
+// mean of their extremes and x-bit priority promotion (Section 3.1.1), Huffman
+// coding of the bucket indices (Section 3.1.2).  How it is laid out on the GPU is this library's own.
+#include "lc_device.h"
+
+namespace lc {
+
+// ----------------------------------------------------------------------------- k_reset
+// Brings the scratch state to what every encode call expects to find (and leaves behind):
+// zero bucket counts, empty extremes, zero group sums and arrival counters.  Only launched
+// for a fresh scratch area or after a call that did not run to its end.
+__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
+    for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
+    for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
+    if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
+    if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; }
+}
+
+__global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups) {
+    clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
+}
+
+// ----------------------------------------------------------------------------- k_hist
+// Sweep 1 (Section 3.1.1, exponent-based quantization): population of each of the 2^9
+// (sign, exponent) buckets.  LDS histogram replicated 8 times (copy = lane & 7, copies
+// of one bin in different banks) so that lanes hitting the same popular bucket rarely
+// collide; merged into 64-bit global counters once per workgroup.
+constexpr int kHistCopies = 8;
+
+// One 16-byte unit = EPU consecutive elements (4 fp32, 8 bf16 / fp16): counting does not care which lane
+// sees which element, so every type is read in 16-byte accesses and kept as loaded until it is counted.
+template <int DT, int EPU>
+__device__ __forceinline__ void unpack_unit(const float4& t, float (&x)[EPU]) {
+    if constexpr (DT == kF32) { x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w; }
+    else {
+        const u32 q[4] = {__float_as_uint(t.x), __float_as_uint(t.y), __float_as_uint(t.z), __float_as_uint(t.w)};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { x[2 * k] = widen16(q[k] & 0xFFFFu, DT == kBF16); x[2 * k + 1] = widen16(q[k] >> 16, DT == kBF16); }
+    }
+}
+
+template <bool ALIGNED, int DT, int EPU>
+__device__ __forceinline__ float4 load_unit(const void* __restrict__ p, u64 unit) {
+    if (ALIGNED) return load_stream(reinterpret_cast<const float4*>(p) + unit);
+    // whole units only, so every element is in range; assemble the same 16 bytes from element loads
+    if constexpr (DT == kF32) {
+        const float* q = static_cast<const float*>(p) + unit * 4;
+        return make_float4(q[0], q[1], q[2], q[3]);
+    } else {
+        const uint16_t* q = static_cast<const uint16_t*>(p) + unit * 8;
+        return make_float4(__uint_as_float(q[0] | ((u32)q[1] << 16)), __uint_as_float(q[2] | ((u32)q[3] << 16)),
+                           __uint_as_float(q[4] | ((u32)q[5] << 16)), __uint_as_float(q[6] | ((u32)q[7] << 16)));
+    }
+}
+
+template <bool ALIGNED, int DT>
+__global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
+                                               u64 n, EncState* ws) {
+    __shared__ u32 h[512 * kHistCopies];
+    constexpr int EPU = 16 / (int)elem_bytes<DT>();
+    const u32 tid = threadIdx.x, nthr = blockDim.x;
+    for (u32 i = tid; i < 512 * kHistCopies; i += nthr) h[i] = 0;
+    __syncthreads();
+    const u32 copy = tid & (kHistCopies - 1);
+    const u64 nu = n / EPU;
+    const u64 stride = (u64)gridDim.x * nthr;
+    u64 u = (u64)blockIdx.x * nthr + tid;
+    // Batches of PF 16-byte units per thread, one batch in flight while the previous one is counted.
+    constexpr int PF = 4;
+    float4 a0[PF], b0[PF], a1[PF], b1[PF];
+    auto fetch = [&](float4 (&a)[PF], float4 (&b)[PF], u64 at) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * stride); b[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * stride); }
+    };
+    auto count_unit = [&](const float4& a, const float4& b) {
+        float x[EPU], y[EPU];
+        unpack_unit<DT, EPU>(a, x); unpack_unit<DT, EPU>(b, y);
+#pragma unroll
+        for (int v = 0; v < EPU; ++v) atomicAdd(&h[(delta_bits(x[v], y[v]) >> 23) * kHistCopies + copy], 1u);
+    };
+    auto count = [&](float4 (&a)[PF], float4 (&b)[PF]) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) count_unit(a[k], b[k]);
+    };
+    const u64 step = PF * stride;
+    if (u + (PF - 1) * stride < nu) {
+        fetch(a0, b0, u);
+        while (true) {
+            const bool more1 = u + step + (PF - 1) * stride < nu;
+            if (more1) fetch(a1, b1, u + step);
+            count(a0, b0);
+            u += step;
+            if (!more1) break;
+            const bool more0 = u + step + (PF - 1) * stride < nu;
+            if (more0) fetch(a0, b0, u + step);
+            count(a1, b1);
+            u += step;
+            if (!more0) break;
+        }
+    }
+    for (; u < nu; u += stride) count_unit(load_unit<ALIGNED, DT, EPU>(w, u), load_unit<ALIGNED, DT, EPU>(w_ref, u));
+    if (blockIdx.x == 0 && tid < (u32)(n - EPU * nu)) {
+        const u64 i = EPU * nu + tid;
+        atomicAdd(&h[(delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i)) >> 23) * kHistCopies + copy], 1u);
+    }
+    __syncthreads();
+    for (u32 b = tid; b < 512; b += nthr) {
+        u32 s = 0;
+#pragma unroll
+        for (int k = 0; k < kHistCopies; ++k) s += h[b * kHistCopies + k];
+        if (s) atomicAdd(&ws->hist[b], (u64)s);
+    }
+}
+
+// ----------------------------------------------------------------------------- k_table
+// Priority promotion (Section 3.1.1) and the Huffman table (Section 3.1.2), one wavefront.  Lane l looks at one exponent level (both signs) per step, from
+// the largest exponent down; a ballot/popcount scan ranks the non-empty buckets (+ before - at
+// equal exponent).  Lane 0 then builds the code lengths with two queues and the canonical codes
+// with per-length counters.
+struct TableLds {
+    uint8_t sym[512];
+    u64 cnt[kMaxSym + 1];
+    u32 kept[kMaxSym], len[kMaxSym + 1], code[kMaxSym + 1];
+    u32 leaf[kMaxSym], left[kMaxSym], right[kMaxSym], depth[kMaxSym];
+    u64 node_w[kMaxSym];
+};
+
+// When the sweep before it coded speculatively with a cached table (ws->spec), the kernel also decides
+// whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
+// cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
+// if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
+__device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+    __shared__ TableLds S;
+    __shared__ u32 s_reuse;
+    const u32 lane = lane_id();
+    const bool active = threadIdx.x < kW;
+    const u32 kmax = (1u << nbits) - 1;
+    if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; S.code[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
+    u32 total = 0;
+    bool nonfinite = false, zero_class = false;
+    for (u32 step = 0; active && step < 4; ++step) {
+        const u32 E = 255 - (step * kW + lane);
+        const u64 c0 = ws->hist[E], c1 = ws->hist[256 + E];
+        const bool normal = E >= 1 && E <= 254;
+        const bool cand0 = normal && c0 > 0, cand1 = normal && c1 > 0;
+        const u64 m0 = __ballot(cand0), m1 = __ballot(cand1), lt = (1ull << lane) - 1;
+        const u32 r0 = total + __popcll(m0 & lt) + __popcll(m1 & lt), r1 = r0 + (cand0 ? 1u : 0u);
+        S.sym[E] = 0xFF; S.sym[256 + E] = 0xFF;
+        if (cand0 && r0 < kmax) { S.kept[r0] = E; S.cnt[r0] = c0; S.sym[E] = (uint8_t)r0; }
+        if (cand1 && r1 < kmax) { S.kept[r1] = 256 + E; S.cnt[r1] = c1; S.sym[256 + E] = (uint8_t)r1; }
+        total += __popcll(m0) + __popcll(m1);
+        nonfinite = nonfinite || __any(E == 255 && (c0 | c1) != 0);
+        zero_class = zero_class || __any(E == 0 && (c0 | c1) != 0);
+    }
+    const u32 K = total < kmax ? total : kmax;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Table& T = ws->table;
+        u64 kept_total = 0;
+        for (u32 j = 0; j < K; ++j) kept_total += S.cnt[j];
+        S.cnt[K] = n - kept_total;
+        const u32 msym = K + 1;
+        u32 max_len = 0;
+        bool reuse = false;
+        if (ws->spec) {
+            reuse = !nonfinite && T.K == K;
+            for (u32 j = 0; j < K && reuse; ++j) reuse = T.kept[j] == S.kept[j];
+            for (u32 j = 0; j < msym && reuse; ++j) reuse = ((T.codelen[j] & 31) != 0) == (S.cnt[j] != 0);
+            if (reuse) for (u32 j = 0; j < msym; ++j) { S.len[j] = T.codelen[j] & 31; if (S.len[j] > max_len) max_len = S.len[j]; }
+        }
+        s_reuse = reuse;
+        ws->spec_ok = reuse;
+        // leaves in ascending (count, symbol) order
+        u32 nl = 0;
+        if (!reuse) {
+            for (u32 sy = 0; sy < msym; ++sy) {
+                if (S.cnt[sy] == 0) continue;
+                u32 p = nl++;
+                while (p > 0 && S.cnt[S.leaf[p - 1]] > S.cnt[sy]) { S.leaf[p] = S.leaf[p - 1]; --p; }
+                S.leaf[p] = sy;
+            }
+            if (nl == 1) { S.len[S.leaf[0]] = 1; max_len = 1; }
+            else if (nl >= 2) {
+                // two queues: sorted leaves and joined nodes in creation order (their weights never
+                // decrease); on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
+                u32 li = 0, qi = 0, ni = 0;
+                for (u32 k = 0; k + 1 < nl; ++k) {
+                    u32 pick[2]; u64 wsum = 0;
+                    for (int q = 0; q < 2; ++q) {
+                        const bool take_leaf = li < nl && (qi >= ni || S.cnt[S.leaf[li]] <= S.node_w[qi]);
+                        if (take_leaf) { pick[q] = S.leaf[li]; wsum += S.cnt[S.leaf[li]]; ++li; }
+                        else { pick[q] = 16 + qi; wsum += S.node_w[qi]; ++qi; }
+                    }
+                    S.node_w[ni] = wsum; S.left[ni] = pick[0]; S.right[ni] = pick[1]; ++ni;
+                }
+                S.depth[ni - 1] = 0;
+                for (int i = (int)ni - 1; i >= 0; --i) {
+                    const u32 d = S.depth[i] + 1, ch[2] = {S.left[i], S.right[i]};
+                    for (int q = 0; q < 2; ++q) {
+                        if (ch[q] >= 16) S.depth[ch[q] - 16] = d;
+                        else { S.len[ch[q]] = d; if (d > max_len) max_len = d; }
+                    }
+                }
+            }
+        }
+        // canonical codes by counting codes per length
+        u32 per_len[17], next_code[17];
+        for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+        for (u32 sy = 0; sy < msym; ++sy) per_len[S.len[sy]]++;
+        per_len[0] = 0;
+        u32 code = 0;
+        for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
+        for (u32 sy = 0; sy < msym; ++sy) if (S.len[sy]) S.code[sy] = next_code[S.len[sy]]++;
+        for (u32 sy = 0; sy < kMaxSym; ++sy) {
+            T.codelen[sy] = sy < msym ? ((S.code[sy] << 5) | S.len[sy]) : 0;
+            T.kept[sy] = sy < K ? S.kept[sy] : 0;
+            T.cnt[sy] = sy < msym ? S.cnt[sy] : 0;
+        }
+        T.K = K; T.max_len = max_len; T.k_E = total + (zero_class ? 1u : 0u);
+        T.status = nonfinite ? 2u : 0u;
+    }
+    __syncthreads();
+    if (active) for (u32 b = lane; b < 512; b += kW) {
+        const u32 sy = S.sym[b] == 0xFF ? K : S.sym[b];
+        ws->table.symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
+    }
+    if (active && ws->spec && !s_reuse) {          // the speculative coding is void: forget its extremes and sizes
+        for (u32 i = lane; i < ngroups; i += kW) group_words[i] = 0;
+        if (lane < kMaxSym) { ws->mmin[lane] = 0x7FFFFFu; ws->mmax[lane] = 0; }
+    }
+}
+
+__global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+    table_build(ws, n, nbits, group_words, ngroups);
+}
+
+// ----------------------------------------------------------------------------- k_spec_table
+// lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
+// priority order, lengths forming a complete prefix code) into the table the sweep codes with.
+__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCache* cache, int nbits) {
+    __shared__ u32 s_ok, s_len[kMaxSym + 1], s_sym[512];
+    const u32 lane = threadIdx.x;
+    Table& T = ws->table;
+    for (u32 b = lane; b < 512; b += kW) s_sym[b] = 0xFF;
+    __syncthreads();
+    if (lane == 0) {
+        const u32 kmax = (1u << nbits) - 1, K = cache->K;
+        bool ok = cache->valid == 1 && cache->nbits == (u32)nbits && K <= kmax;
+        u32 kraft = 0, nact = 0, max_len = 0, per_len[17];
+        for (int L = 0; L <= 16; ++L) per_len[L] = 0;
+        for (u32 j = 0; j <= kMaxSym; ++j) s_len[j] = 0;
+        if (ok) {
+            u32 prev_key = 0xFFFFFFFFu;
+            for (u32 j = 0; j < K; ++j) {
+                const u32 b = cache->kept[j], e = b & 255;
+                const u32 key = (e << 1) | (1u - ((b >> 8) & 1u));     // larger exponent first, + before -
+                if (b >= 512 || e == 0 || e == 255 || key >= prev_key) { ok = false; break; }
+                prev_key = key;
+            }
+            for (u32 j = 0; j <= K && ok; ++j) {
+                const u32 l = cache->len[j];
+                if (l > 15) { ok = false; break; }
+                s_len[j] = l;
+                if (l) { kraft += 1u << (15 - l); ++nact; per_len[l]++; if (l > max_len) max_len = l; }
+            }
+            if (nact >= 2 && kraft != (1u << 15)) ok = false;
+            if (nact == 1 && kraft != (1u << 14)) ok = false;
+        }
+        if (ok) {
+            u32 next_code[17], code = 0;
+            for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
+            for (u32 j = 0; j < kMaxSym; ++j) {
+                const u32 c = (j <= K && s_len[j]) ? next_code[s_len[j]]++ : 0;
+                T.codelen[j] = j <= K ? ((c << 5) | s_len[j]) : 0;
+                T.kept[j] = j < K ? cache->kept[j] : 0;
+                T.cnt[j] = 0;
+                if (j < K) s_sym[cache->kept[j]] = j;
+            }
+            T.K = K; T.max_len = max_len; T.k_E = 0; T.status = 0;
+        }
+        s_ok = ok;
+        ws->spec = ok; ws->spec_ok = 0;
+    }
+    __syncthreads();
+    if (s_ok) {
+        const u32 K = cache->K;
+        for (u32 b = lane; b < 512; b += kW) {
+            const u32 sy = s_sym[b] == 0xFF ? K : s_sym[b];
+            T.symlen_of_bucket[b] = (uint8_t)(sy | (s_len[sy] << 4));
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------- k_pack
+// Sweep 2: one wavefront per chunk, no communication between wavefronts.  Each lane codes its
+// 256 elements into a bit string of its own, written word by word to the chunk's slot in the
+// scratch area (lane-private, word k of lane l at slot[32 + 64 k + l]); the 64 bit lengths go
+// to the head of the slot, their sum to chunk_bits[c].  Where the strings end up in the blob is
+// decided afterwards by k_place, which knows all sizes.  A full, 16-byte aligned chunk takes
+// the fast path: rows are fetched eight at a time, one batch ahead (and the next chunk's first
+// batch before the current one ends), the table look-ups of 16 elements are issued together and
+// two symbols are coded per look-up.  Ragged or unaligned chunks take a plain path.  The
+// mantissa extremes of the kept buckets (Section 3.1.1: the representative is the mean of the
+// bucket's largest and smallest member) are tracked on the way.
+constexpr int kMmCopies = 32;       // LDS copies of the per-symbol extremes, one per lane of a half wave
+
+constexpr u32 kStageRows = 32;      // code words per lane that a chunk gathers in LDS before they go to its slot
+
+constexpr int kSpecCopies = 4;      // LDS copies of the bucket histogram in the speculative sweep
+
+template <bool HIST>
+struct PackLds {
+    uint8_t sym8[512];               // bucket -> symbol << 3
+    u32 codelen[kMaxSym];            // (code << 5) | len
+    uint2 pair[256];                 // (symbol a, symbol b) -> {code of a followed by b, its length}
+    u32 mn[kMaxSym * kMmCopies], mx[kMaxSym * kMmCopies];   // extremes of the delta bit patterns per symbol
+    alignas(16) u32 stage[kStageRows * kW];                 // word k of lane l at [64 k + l], as in the slot
+    u32 hist[HIST ? 512 * kSpecCopies : 1];                 // bucket populations (speculative sweep only)
+};
+
+// chunk_bits[c] = payload bits of chunk c; group_words[g] = record words of chunks 64g .. 64g+63
+// (integer atomics: the sums do not depend on the order of arrival).
+// One chunk's work as the coding loop sees it: the vector it belongs to, its index there, and where its
+// code words, its bit count and its group's word sum go.
+struct ChunkRef {
+    const void* w; const void* w_ref;
+    u64 n;
+    u32 c;
+    u32* slot; u32* bits_at; u32* group_at;
+    u32 seg;                     // batched calls: which tensor
+    bool valid, fast;            // fast: a full chunk of aligned arrays
+};
+
+__device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u32 nw) {
+    const u32 lane = lane_id();
+    const u32 bits = 32 * nw + nb;
+    reinterpret_cast<uint16_t*>(ch.slot)[lane] = (uint16_t)bits;
+    const u32 total = wave_sum32(bits);
+    if (lane == 0) {
+        *ch.bits_at = total;
+        atomicAdd(ch.group_at, kLaneBitsWords + ((total + 31) >> 5));
+    }
+}
+
+// Any size, any alignment: guarded scalar loads, one symbol per look-up.
+template <bool HIST, bool PACK, int DT>
+__device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& L) {
+    const u32 lane = lane_id();
+    const void* __restrict__ w = ch.w; const void* __restrict__ w_ref = ch.w_ref;
+    const u64 n = ch.n, base = (u64)ch.c * kChunk;
+    u32* slot = ch.slot;
+    const u32 mm = lane & (kMmCopies - 1);
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;
+    for (u32 r = 0; r < kR; ++r) {
+        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (idx + v < n) {
+                const u32 u = delta_bits(load_one<DT>(w, idx + v), load_one<DT>(w_ref, idx + v));
+                if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+                if (!PACK) continue;
+                const u32 sy = L.sym8[u >> 23] >> 3;
+                const u32 cl = L.codelen[sy];
+                atomicMin(&L.mn[sy * kMmCopies + mm], u);
+                atomicMax(&L.mx[sy * kMmCopies + mm], u);
+                acc = (acc << (cl & 31)) | (cl >> 5);
+                nb += cl & 31;
+            }
+            if (PACK && (v & 1) && nb >= 32) {
+                slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
+                ++nw; nb -= 32;
+            }
+        }
+    }
+    if (!PACK) return;
+    if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
+    finish_lane_sizes(ch, nb, nw);
+}
+
+constexpr int kPackPF = 8;          // rows per prefetch batch of the coding loop
+
+// element index of this lane's 4 elements in row r of chunk c
+__device__ __forceinline__ u64 row_at(u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane_id()) * kV; }
+
+template <int DT>
+__device__ __forceinline__ void fetch_first_batch(const ChunkRef& ch, typename Raw<DT>::type (&A)[kPackPF],
+                                                  typename Raw<DT>::type (&B)[kPackPF]) {
+#pragma unroll
+    for (int k = 0; k < kPackPF; ++k) { A[k] = load_raw<DT>(ch.w, row_at(ch.c, k)); B[k] = load_raw<DT>(ch.w_ref, row_at(ch.c, k)); }
+}
+
+// A full, aligned chunk whose first batch of rows is already in A0/B0; leaves the first batch of `next`
+// there if that chunk takes this path too.
+template <bool ROWCHK, bool HIST, bool PACK, int DT>
+__device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const ChunkRef& next,
+                                                typename Raw<DT>::type (&A0)[kPackPF], typename Raw<DT>::type (&B0)[kPackPF],
+                                                u32 K8, PackLds<HIST>& L) {
+    constexpr int PF = kPackPF;
+    typedef typename Raw<DT>::type raw_t;
+    const u32 lane = lane_id();
+    const u32 mm = lane & (kMmCopies - 1);
+    const void* __restrict__ w = cur.w; const void* __restrict__ w_ref = cur.w_ref;
+    const u32 c = cur.c;
+    raw_t A1[PF], B1[PF];
+    const bool next_fast = next.valid && next.fast;
+    u32* lane_words = cur.slot + kLaneBitsWords + lane;
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;                       // bits waiting in acc, words written
+    // Lanes fill their words at different times; gathering them in LDS and storing whole rows at
+    // the end of the chunk turns many partial-line stores into a few full ones.
+    auto flush = [&]() {
+        if (nb >= 32) {
+            const u32 word = (u32)(acc >> (nb - 32));
+            if (nw < kStageRows) L.stage[nw * kW + lane] = word;
+            else lane_words[nw * kW] = word;
+            ++nw; nb -= 32;
+        }
+    };
+    // Four rows at a time: all table look-ups of the 16 elements are issued together, so the
+    // LDS latency is paid twice per group instead of three times per row; only the shift/or
+    // chain that grows the lane's bit string is serial.
+    auto group = [&](const raw_t* a, const raw_t* b) {
+        u32 u[16], t[16];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float xa[4], xb[4];
+            unpack<DT>(a[k], xa); unpack<DT>(b[k], xb);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) u[4 * k + v] = delta_bits(xa[v], xb[v]);
+        }
+        if (HIST) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+        }
+        if (!PACK) return;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) t[i] = L.sym8[u[i] >> 23];
+        uint2 p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            p[i] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(L.pair) + ((t[2 * i] << 4) | t[2 * i + 1]));
+        u32 tmin = t[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tmin = min(tmin, t[i]);
+        if (__any(tmin < K8)) {
+            // some lane holds a kept element: everyone updates the extremes of its symbols
+            // (the merged symbol has a slot of its own that nobody reads)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                atomicMin(&L.mn[t[i] * (kMmCopies / 8) + mm], u[i]);
+                atomicMax(&L.mx[t[i] * (kMmCopies / 8) + mm], u[i]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc = (acc << p[i].y) | p[i].x; nb += p[i].y;
+            if (!ROWCHK || (i & 1)) flush();
+        }
+    };
+    for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
+#pragma unroll
+        for (int k = 0; k < PF; ++k) { A1[k] = load_raw<DT>(w, row_at(c, r0 + PF + k)); B1[k] = load_raw<DT>(w_ref, row_at(c, r0 + PF + k)); }
+        group(A0, B0); group(A0 + 4, B0 + 4);
+        if (r0 + 2 * PF < kR) {
+#pragma unroll
+            for (int k = 0; k < PF; ++k) { A0[k] = load_raw<DT>(w, row_at(c, r0 + 2 * PF + k)); B0[k] = load_raw<DT>(w_ref, row_at(c, r0 + 2 * PF + k)); }
+        } else if (next_fast) {
+            fetch_first_batch<DT>(next, A0, B0);
+        }
+        group(A1, B1); group(A1 + 4, B1 + 4);
+    }
+    if (!PACK) return;
+    // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
+    if (nb > 0) {
+        const u32 word = (u32)(acc << (32 - nb));
+        if (nw < kStageRows) L.stage[nw * kW + lane] = word;
+        else lane_words[nw * kW] = word;
+    }
+    u32 rows = min(nw + (nb > 0 ? 1u : 0u), kStageRows);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) rows = max(rows, (u32)__shfl_xor(rows, d, 64));
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(L.stage);
+        uint4* dst = reinterpret_cast<uint4*>(cur.slot + kLaneBitsWords);
+        for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
+    }
+    finish_lane_sizes(cur, nb, nw);
+}
+
+// The coding loop of one wavefront over the chunks its source hands out.  Src::get(k) is the wavefront's
+// k-th chunk, Src::enter(chunk, L) runs before each (a batched call switches tables there), Src::K8() and
+// Src::rowchk() describe the table in force: symbol K << 3, and whether a lane's 64-bit accumulator can
+// take a whole row (31 waiting bits + 4 codes of <= 8 bits) between flushes.
+// ROWSEL: 1 / 0 = rowchk() is known to be true / false for every chunk (one vector, one table);
+// -1 = ask per chunk (a batched call, where tables change).
+template <bool HIST, bool PACK, int DT, int ROWSEL, typename Src>
+__device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
+    typedef typename Raw<DT>::type raw_t;
+    raw_t A0[kPackPF], B0[kPackPF];
+    ChunkRef cur = src.get(0);
+    if (cur.valid && cur.fast) fetch_first_batch<DT>(cur, A0, B0);
+    for (u32 k = 0; cur.valid; ++k) {
+        const ChunkRef next = src.get(k + 1);
+        src.enter(cur, L);
+        if (!cur.fast) {
+            pack_chunk_plain<HIST, PACK, DT>(cur, L);
+            if (next.valid && next.fast) fetch_first_batch<DT>(next, A0, B0);
+        } else if (ROWSEL == 1 || (ROWSEL < 0 && src.rowchk())) {
+            pack_chunk_fast<true, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L);
+        } else {
+            pack_chunk_fast<false, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L);
+        }
+        cur = next;
+    }
+}
+
+// The chunks of one vector, dealt round-robin to the wavefronts of the grid.
+struct VectorChunks {
+    const void* w; const void* w_ref;
+    u64 n;
+    u32* prov; u32 slot_words; u32* chunk_bits; u32* group_words;
+    u32 nchunks; bool aligned;
+    u32 k8; bool row;
+    __device__ __forceinline__ ChunkRef get(u32 k) const {
+        ChunkRef ch;
+        ch.c = blockIdx.x + k * gridDim.x;
+        ch.valid = ch.c < nchunks;
+        ch.w = w; ch.w_ref = w_ref; ch.n = n;
+        ch.fast = aligned && (u64)(ch.c + 1) * kChunk <= n;
+        ch.slot = prov + (u64)ch.c * slot_words;
+        ch.bits_at = chunk_bits + ch.c;
+        ch.group_at = group_words + (ch.c >> 6);
+        ch.seg = 0;
+        return ch;
+    }
+    template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
+    __device__ __forceinline__ u32 K8() const { return k8; }
+    __device__ __forceinline__ bool rowchk() const { return row; }
+};
+
+template <bool HIST>
+__device__ __forceinline__ void pack_setup(PackLds<HIST>& L, const Table& T, u32 lane) {
+    for (u32 i = lane; i < 512; i += 64) L.sym8[i] = (uint8_t)((T.symlen_of_bucket[i] & 15) << 3);
+    if (lane < kMaxSym) L.codelen[lane] = T.codelen[lane];
+    for (u32 i = lane; i < 256; i += 64) {
+        const u32 ca = T.codelen[i >> 4], cb = T.codelen[i & 15];
+        L.pair[i] = make_uint2(((ca >> 5) << (cb & 31)) | (cb >> 5), (ca & 31) + (cb & 31));
+    }
+    for (u32 i = lane; i < kMaxSym * kMmCopies; i += 64) { L.mn[i] = 0xFFFFFFFFu; L.mx[i] = 0; }
+}
+
+template <bool HIST>
+__device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, EncState* ws, u32 K, u32 lane) {
+    if (lane < K) {
+        u32 mn = 0xFFFFFFFFu, mx = 0;
+#pragma unroll
+        for (int k = 0; k < kMmCopies; ++k) { mn = min(mn, L.mn[lane * kMmCopies + k]); mx = max(mx, L.mx[lane * kMmCopies + k]); }
+        if (mn <= mx) { atomicMin(&ws->mmin[lane], mn & 0x7FFFFFu); atomicMax(&ws->mmax[lane], mx & 0x7FFFFFu); }
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
+                                             EncState* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                             u32 slot_words, u32 nchunks, int aligned) {
+    __shared__ PackLds<false> L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    if (T.status != 0 || ws->spec_ok != 0) return;     // nothing to code, or the speculative sweep already did
+    pack_setup(L, T, lane);
+    const u32 K = T.K;
+    __syncthreads();
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8};
+    if (src.row) pack_loop<false, true, DT, 1>(src, L);
+    else pack_loop<false, true, DT, 0>(src, L);
+    __syncthreads();
+    pack_merge_extremes(L, ws, K, lane);
+}
+
+// ----------------------------------------------------------------------------- k_spec_sweep
+// lc_encode_cached: the single sweep.  Counts the bucket populations like k_hist and, when a cached
+// table is in place (ws->spec), codes every chunk with it like k_pack in the same pass over w and
+// w_ref.  k_table then either confirms the coding or voids it.
+template <int DT>
+__global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
+                                                   EncState* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                                   u32 slot_words, u32 nchunks, int aligned) {
+    __shared__ PackLds<true> L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    const bool spec = ws->spec != 0;
+    for (u32 i = lane; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
+    if (spec) pack_setup(L, T, lane);
+    const u32 K = spec ? T.K : 0;
+    __syncthreads();
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, !spec || T.max_len <= 8};
+    if (!spec) pack_loop<true, false, DT, 1>(src, L);
+    else if (src.row) pack_loop<true, true, DT, 1>(src, L);
+    else pack_loop<true, true, DT, 0>(src, L);
+    __syncthreads();
+    for (u32 b = lane; b < 512; b += 64) {
+        u32 sum = 0;
+#pragma unroll
+        for (int k = 0; k < kSpecCopies; ++k) sum += L.hist[b * kSpecCopies + k];
+        if (sum) atomicAdd(&ws->hist[b], (u64)sum);
+    }
+    if (spec) pack_merge_extremes(L, ws, K, lane);
+}
+
+// ----------------------------------------------------------------------------- k_place
+// Builds the chunk area of the blob from the per-chunk slots, one wavefront per chunk.  The
+// chunk's word offset is the sum of the record sizes before it (whole groups of 64 chunks from
+// group_words, the rest from chunk_bits).  The 64 lane strings are joined without gaps: payload
+// word W0 + j of a lane takes the low bits of its word j-1 and the high bits of its word j.
+// A payload of up to kPlaceWords words is assembled in LDS (every lane ORs its shifted words
+// into a cleared buffer, so words shared by neighbouring lanes need no special care) and
+// written out with coalesced stores.  A larger payload is written directly: every word exactly
+// once, by the lane whose string holds its first bit, boundary words merged through LDS.
+constexpr u32 kPlaceWords = 2048;
+
+// Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
+// to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
+// offset entry, the result for the host; then the scratch state is cleared for the next call.
+__device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
+                                              u64 n, int nbits, u32 nchunks, u32 dtype) {
+    __shared__ u32 hdr[kHeaderBytes / 4];
+    const u32 t = threadIdx.x;
+    const Table& T = ws->table;
+    if (t < kHeaderBytes / 4) hdr[t] = 0;
+    __syncthreads();
+    const u32 status = T.status;
+    const bool ok = status == 0;
+    const u64 area = chunk_area_of(nchunks);
+    const u64 total_words = ws->total_words;
+    const u64 total = ok ? area + 4 * total_words : kHeaderBytes;
+    if (t == 0) {
+        hdr[0] = 0x3142434Cu;                     // "LCB1"
+        hdr[1] = 1u | (kHeaderBytes << 16);
+        hdr[2] = (u32)n; hdr[3] = (u32)(n >> 32);
+        hdr[4] = (u32)nbits;
+        hdr[6] = kW; hdr[7] = kV; hdr[8] = kR;
+        hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
+        hdr[12] = status;
+        hdr[15] = dtype;
+        if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
+        host_result->bytes = total; host_result->status = status; host_result->used_cache = ws->spec_ok;
+        if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = T.K; cache->pad = 0; }
+    }
+    if (cache && ok && t < kMaxSym) {              // what this blob was coded with, for the next call
+        cache->kept[t] = t < T.K ? T.kept[t] : 0;
+        cache->len[t] = t <= T.K ? (T.codelen[t] & 31) : 0;
+    }
+    if (ok && t <= T.K) {
+        const u32 len = T.codelen[t] & 31;
+        u32 bucket = 0xFFFFu, rep = 0;
+        if (t < T.K) {
+            bucket = T.kept[t];
+            const u32 sum = ws->mmin[t] + ws->mmax[t];
+            u32 mm = sum >> 1;
+            if ((sum & 1) && (mm & 1)) ++mm;
+            rep = (bucket << 23) | mm;
+        }
+        hdr[16 + 4 * t + 0] = bucket | (len << 16);
+        hdr[16 + 4 * t + 1] = rep;
+        hdr[16 + 4 * t + 2] = (u32)T.cnt[t];
+        hdr[16 + 4 * t + 3] = (u32)(T.cnt[t] >> 32);
+    }
+    __syncthreads();
+    if (t < kHeaderBytes / 4) reinterpret_cast<u32*>(out)[t] = hdr[t];
+    if (ok) {
+        // last offset entry and the zero padding of the offset table
+        u32* off_tab = reinterpret_cast<u32*>(out + kHeaderBytes);
+        const u32 entries = (u32)((area - kHeaderBytes) / 4);
+        if (t == 0) off_tab[nchunks] = (u32)total_words;
+        if (t >= 1 && t < 4 && nchunks + t < entries) off_tab[nchunks + t] = 0;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype);
+    clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
+    __threadfence_system();
+}
+
+// Chunk c of one vector, by one wavefront of a workgroup of four; `valid` false: an idle wavefront that only
+// keeps the workgroup's barrier company.
+__device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
+                                            const u32* __restrict__ group_words, const u32* __restrict__ prov,
+                                            u32 slot_words, u32 nchunks, u32 c, bool valid) {
+    __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
+    __shared__ u32 s_buf_all[4][kPlaceWords];
+    const u32 lane = lane_id(), wv = threadIdx.x >> 6;
+    u32* s_off = s_off_all[wv];
+    u32* s_hw = s_hw_all[wv];
+    u32* s_buf = s_buf_all[wv];
+    const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
+    const u32 bits = valid ? reinterpret_cast<const uint16_t*>(slot)[lane] : 0;
+    const u32 g = c >> 6;
+    u64 part = (valid && 64 * g + lane < c) ? kLaneBitsWords + ((chunk_bits[64 * g + lane] + 31) >> 5) : 0;
+    if (valid) {
+#pragma unroll 4
+        for (u32 j = lane; j < g; j += kW) part += group_words[j];
+    }
+    const u64 word_off = wave_sum64(part);
+    const u32 incl = wave_incl_scan(bits);
+    const u32 o = incl - bits;                               // first bit of this lane's string
+    const u32 total_bits = __shfl(incl, 63, 64);
+    const u32 nwords = (total_bits + 31) >> 5;
+    uint8_t* rec = out + chunk_area_of(nchunks) + 4 * word_off;
+    u32* payload = reinterpret_cast<u32*>(rec + 2 * kW);
+    if (valid) {
+        reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
+        if (lane == 0) {
+            reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
+            if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
+        }
+    }
+    const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
+    const u32 nt = bits ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
+    u32 nt_max = nt;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nt_max = max(nt_max, (u32)__shfl_xor(nt_max, d, 64));
+    const u32* lane_words = slot + kLaneBitsWords + lane;
+    const bool staged = nwords <= kPlaceWords;               // wave-uniform
+    if (staged) {
+        for (u32 i = lane; i < nwords; i += kW) s_buf[i] = 0;
+    } else {
+        s_off[lane] = o; s_hw[lane] = 0;
+        if (lane == 0) s_off[kW] = total_bits;
+    }
+    u32 prev = 0, tail = 0;
+    bool own_tail = false;
+    for (u32 j0 = 0; j0 < nt_max; j0 += 8) {
+        u32 buf[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) buf[k] = (j0 + k < nloc) ? lane_words[(j0 + k) * kW] : 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const u32 j = j0 + k;
+            if (j < nt) {
+                const u32 val = __builtin_amdgcn_alignbit(prev, buf[k], sh);
+                prev = buf[k];
+                if (staged) {
+                    atomicOr(&s_buf[W0 + j], val);
+                } else {
+                    const bool owned = j > 0 || sh == 0;         // the word's first bit is this lane's
+                    if (!owned) s_hw[lane] = val;
+                    else if (j + 1 == nt) { tail = val; own_tail = true; }
+                    else payload[W0 + j] = val;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (staged) {
+        for (u32 i = lane; i < nwords; i += kW) payload[i] = s_buf[i];
+    } else if (own_tail) {                                       // following lanes may start inside this word
+        const u32 W = W0 + nt - 1;
+        for (u32 q = lane + 1; q < kW && (s_off[q] >> 5) == W; ++q) tail |= s_hw[q];
+        payload[W] = tail;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
+                                               const u32* __restrict__ group_words, const u32* __restrict__ prov,
+                                               u32 slot_words, u32 nchunks) {
+    const u32 c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    // the last workgroup may hold idle wavefronts
+    place_chunk(out, ws, chunk_bits, group_words, prov, slot_words, nchunks, c, c < nchunks && ws->table.status == 0);
+}
+
+// ----------------------------------------------------------------------------- batched encode
+// lc_encode_batch: many vectors, one table each, in six launches.  The chunks of all tensors are numbered
+// through; the sweeps deal those dense chunks round-robin to their wavefronts exactly as for one vector,
+// and a wavefront that moves on to a chunk of another tensor first hands in what it gathered for the last
+// one (bucket counts, extremes) and loads the new tensor's table.
+__global__ __launch_bounds__(256) void kb_setup(BatchArgs a) {
+    const u32 i = blockIdx.x * blockDim.x + threadIdx.x, nthr = gridDim.x * blockDim.x;
+    for (u32 g = i; g < a.total_chunks; g += nthr) {          // tensor of dense chunk g: last one starting at or before it
+        u32 lo = 0, hi = a.count - 1;
+        while (lo < hi) {
+            const u32 mid = (lo + hi + 1) >> 1;
+            if (a.segs[mid].chunk0 <= g) lo = mid; else hi = mid - 1;
+        }
+        // tensors without chunks share their successor's chunk0: step to the one that owns g
+        while (lo > 0 && (a.segs[lo].nchunks == 0 || g >= a.segs[lo].chunk0 + a.segs[lo].nchunks)) --lo;
+        a.seg_of_chunk[g] = lo;
+    }
+    for (u32 g = i; g < a.total_groups; g += nthr) a.group_words[g] = 0;
+    constexpr u32 per = 512 + 2 * kMaxSym + 4;                // words of state to set per tensor
+    for (u64 k = i; k < (u64)a.count * per; k += nthr) {
+        EncState& st = a.states[k / per];
+        const u32 j = (u32)(k % per);
+        if (j < 512) st.hist[j] = 0;
+        else if (j < 512 + kMaxSym) st.mmin[j - 512] = 0x7FFFFFu;
+        else if (j < 512 + 2 * kMaxSym) st.mmax[j - 512 - kMaxSym] = 0;
+        else if (j == 512 + 2 * kMaxSym) st.spec = 0;
+        else if (j == 512 + 2 * kMaxSym + 1) st.spec_ok = 0;
+        else if (j == 512 + 2 * kMaxSym + 2) st.total_words = 0;
+        else st.table.status = 0;
+    }
+}
+
+// The dense chunks of a batched call as a chunk source for the coding loop.
+template <bool HIST, bool PACK>
+struct BatchChunks {
+    BatchArgs a;
+    u32 active;                  // tensor whose counts / extremes / table the LDS holds (0xFFFFFFFF: none yet)
+    u32 k8; bool row;
+    __device__ __forceinline__ ChunkRef get(u32 k) const {
+        ChunkRef ch;
+        const u32 g = blockIdx.x + k * gridDim.x;
+        ch.valid = g < a.total_chunks;
+        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false;
+        ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
+        if (ch.valid) {
+            ch.seg = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
+            const Seg& sg = a.segs[ch.seg];
+            ch.c = g - sg.chunk0;
+            ch.w = sg.w; ch.w_ref = sg.w_ref; ch.n = sg.n;
+            ch.fast = sg.aligned && (u64)(ch.c + 1) * kChunk <= sg.n;
+            ch.slot = a.prov + (u64)g * a.slot_words;
+            ch.bits_at = a.chunk_bits + g;
+            ch.group_at = a.group_words + sg.group0 + (ch.c >> 6);
+            // a tensor whose delta is not finite gets a header-only blob: nothing to code
+            if (PACK && a.states[ch.seg].table.status != 0) { ch.n = 0; ch.fast = false; }
+        }
+        return ch;
+    }
+    __device__ __forceinline__ void hand_in(PackLds<HIST>& L) {
+        if (active == 0xFFFFFFFFu) return;
+        const u32 lane = lane_id();
+        EncState* st = &a.states[active];
+        if (HIST) {
+            for (u32 b = lane; b < 512; b += kW) {
+                u32 sum = 0;
+#pragma unroll
+                for (int k = 0; k < kSpecCopies; ++k) { sum += L.hist[b * kSpecCopies + k]; L.hist[b * kSpecCopies + k] = 0; }
+                if (sum) atomicAdd(&st->hist[b], (u64)sum);
+            }
+        }
+        if (PACK) pack_merge_extremes(L, st, st->table.K, lane);
+    }
+    __device__ __forceinline__ void enter(const ChunkRef& ch, PackLds<HIST>& L) {
+        if (ch.seg == active) return;
+        hand_in(L);
+        active = ch.seg;
+        if (PACK) {
+            const Table& T = a.states[active].table;
+            __syncthreads();                  // one wavefront per workgroup: orders the LDS traffic around the switch
+            pack_setup(L, T, lane_id());
+            k8 = T.K << 3; row = T.max_len <= 8;
+            __syncthreads();
+        }
+    }
+    __device__ __forceinline__ u32 K8() const { return k8; }
+    __device__ __forceinline__ bool rowchk() const { return row; }
+};
+
+__global__ __launch_bounds__(64) void kb_hist(BatchArgs a) {
+    __shared__ PackLds<true> L;
+    for (u32 i = threadIdx.x; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
+    __syncthreads();
+    BatchChunks<true, false> src = {a, 0xFFFFFFFFu, 0, true};
+    pack_loop<true, false, kF32, 1>(src, L);
+    src.hand_in(L);
+}
+
+__global__ __launch_bounds__(64) void kb_table(BatchArgs a) {
+    table_build(&a.states[blockIdx.x], a.segs[blockIdx.x].n, a.nbits, nullptr, 0);
+}
+
+__global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
+    __shared__ PackLds<false> L;
+    BatchChunks<false, true> src = {a, 0xFFFFFFFFu, 0, true};
+    pack_loop<false, true, kF32, 0>(src, L);      // flush per pair of codes: right for every table of the batch
+    src.hand_in(L);
+}
+
+__global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
+    const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const bool in_range = g < a.total_chunks;
+    const u32 sidx = in_range ? a.seg_of_chunk[g] : 0;
+    const Seg& sg = a.segs[sidx];
+    EncState* st = &a.states[sidx];
+    place_chunk(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
+                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0);
+}
+
+__global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
+    const Seg& sg = a.segs[blockIdx.x];
+    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)kF32);
+    if (blockIdx.x == gridDim.x - 1) __threadfence_system();
+}
+// ----------------------------------------------------------------------------- launchers
+void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)kMaxGroups);
+}
+
+template <int DT>
+static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32 blocks, u32 threads, hipStream_t s) {
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+}
+
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s) {
+    if (n == 0) return;
+    const u32 threads = tune.hist_threads;
+    const u64 units = n / (dtype == kF32 ? 4 : 8);                 // 16-byte units
+    u64 blocks = (units + 4 * threads - 1) / (4 * threads);
+    const u64 cap = (u64)tune.num_cu * tune.hist_blocks_per_cu;
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
+    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
+    else launch_hist_t<kF32>(w, w_ref, n, ws, (u32)blocks, threads, s);
+}
+
+void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s) {
+    hipLaunchKernelGGL(k_table, dim3(1), dim3(64), 0, s, ws, (u64)n, nbits, group_words, (u32)((num_chunks_of(n) + 63) / 64));
+}
+
+void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
+    hipLaunchKernelGGL(k_spec_table, dim3(1), dim3(64), 0, s, ws, cache, nbits);
+}
+
+void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
+                       uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
+    if (blocks > nchunks) blocks = nchunks;
+    const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
+    const dim3 grid((u32)blocks), wg(64);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_spec_sweep<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_spec_sweep<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_spec_sweep<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+}
+
+void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
+                 uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
+    if (blocks > nchunks) blocks = nchunks;
+    const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
+    const dim3 grid((u32)blocks), wg(64);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+}
+
+void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
+                       slot_words, (u32)nchunks);
+}
+
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
+                     uint64_t n, int nbits, int dtype, hipStream_t s) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
+                       (u32)num_chunks_of(n), (u32)dtype);
+}
+
+void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s) {
+    const u32 cap = (u32)tune.num_cu * 8;
+    u32 setup_blocks = (a.total_chunks + 255) / 256;
+    if (setup_blocks < a.count * 3) setup_blocks = a.count * 3;
+    if (setup_blocks > cap) setup_blocks = cap;
+    if (setup_blocks < 1) setup_blocks = 1;
+    hipLaunchKernelGGL(kb_setup, dim3(setup_blocks), dim3(256), 0, s, a);
+    if (a.total_chunks) {
+        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_hist, dim3(waves), dim3(64), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_table, dim3(a.count), dim3(64), 0, s, a);
+    if (a.total_chunks) {
+        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
+        if (waves > a.total_chunks) waves = a.total_chunks;
+        hipLaunchKernelGGL(kb_pack, dim3(waves), dim3(64), 0, s, a);
+        hipLaunchKernelGGL(kb_place, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
+    }
+    hipLaunchKernelGGL(kb_finalize, dim3(a.count), dim3(256), 0, s, a);
+}
+
+}  // namespace lc

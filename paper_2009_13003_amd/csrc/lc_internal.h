@@ -1,4 +1,4 @@
-// Shared between the kernels (lc_kernels.hip) and the host API (lc_api.hip):
+// Shared between the kernels (lc_encode.hip, lc_decode.hip) and the host API (lc_api.hip):
 // the device scratch layout and the launch entry points.  gfx950 only.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -119,7 +119,7 @@ struct Tuning {
     int fused_min_waves_per_cu = 8;    // a sweep takes as many blobs as still leave LDS for this many
 };
 
-// Launchers (lc_kernels.hip).
+// Launchers (lc_encode.hip, lc_decode.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s);
 void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s);
