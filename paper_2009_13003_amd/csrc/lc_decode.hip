@@ -867,9 +867,7 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
                    const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    u64 blocks = (nchunks + 3) / 4;
-    const u64 cap = (u64)tune.num_cu * tune.decode_blocks_per_cu;
-    if (blocks > cap) blocks = cap;
+    const u64 blocks = balanced_workers((nchunks + 3) / 4, (u64)tune.num_cu * tune.decode_blocks_per_cu);
     const dim3 grid((u32)blocks), wg(256);
     const int al = aligned_rows(w_ref, dtype);
     if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);

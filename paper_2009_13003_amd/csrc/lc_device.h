@@ -115,6 +115,13 @@ __device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u6
 }
 
 // ---- host-side helpers of the launchers
+// Work items dealt round-robin to at most `cap` workers: the smallest worker count that keeps the number of
+// rounds, so that every worker has the same load (+-1) and nobody idles through a last, half-empty round.
+static inline uint64_t balanced_workers(uint64_t items, uint64_t cap) {
+    if (items <= cap || cap == 0) return items;
+    const uint64_t rounds = (items + cap - 1) / cap;
+    return (items + rounds - 1) / rounds;
+}
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 static inline bool aligned_rows(const void* p, int dtype) {     // 4 consecutive elements per access
     return (reinterpret_cast<uintptr_t>(p) & (dtype == kF32 ? 15 : 7)) == 0;
