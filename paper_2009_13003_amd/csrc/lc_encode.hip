@@ -146,9 +146,14 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; S.code[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
     u32 total = 0;
     bool nonfinite = false, zero_class = false;
+    // all eight counts of this lane first: the four ranking steps below then run without waiting on memory
+    u64 cnt0[4], cnt1[4];
+#pragma unroll
+    for (u32 step = 0; step < 4; ++step) { cnt0[step] = ws->hist[255 - (step * kW + lane)]; cnt1[step] = ws->hist[511 - (step * kW + lane)]; }
+#pragma unroll
     for (u32 step = 0; active && step < 4; ++step) {
         const u32 E = 255 - (step * kW + lane);
-        const u64 c0 = ws->hist[E], c1 = ws->hist[256 + E];
+        const u64 c0 = cnt0[step], c1 = cnt1[step];
         const bool normal = E >= 1 && E <= 254;
         const bool cand0 = normal && c0 > 0, cand1 = normal && c1 > 0;
         const u64 m0 = __ballot(cand0), m1 = __ballot(cand1), lt = (1ull << lane) - 1;
