@@ -238,9 +238,16 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     if (__any(used != lane_bits) && lane == 0) raise(4u);
 }
 
+// zero_bits: what every lane length of a full chunk is when all its elements are the merged symbol and that
+// symbol's code is all zero bits (the canonical first code), else 0.  Such a chunk with an all-zero payload
+// decodes to the merged symbol throughout, exactly: it changes nothing and is left without reading w_ref.
+__device__ __forceinline__ u32 zero_chunk_bits(u32 len_merged, u32 code_merged) {
+    return (len_merged != 0 && code_merged == 0) ? kR * kV * len_merged : 0u;
+}
+
 template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
-                                             u32 c, LDS& L, u32 P1, u32 P2, u32 K, u64 area, Raise& raise) {
+                                             u32 c, LDS& L, u32 P1, u32 P2, u32 K, u64 area, u32 zero_bits, Raise& raise) {
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
     const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
@@ -255,6 +262,7 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
         // record's own lane lengths, and the last vector is read word by word so no read passes the end
         const uint4* gv = reinterpret_cast<const uint4*>(gw - k0);
         const u32 nvec = (nwords + k0 + 3) >> 2;
+        u32 nonzero = 0;
         for (u32 i = lane; i < nvec; i += kW) {
             uint4 q;
             if (4 * i + 4 <= nwords + k0) q = gv[i];
@@ -264,7 +272,10 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
                 q.x = t[0]; q.y = left > 1 ? t[1] : 0; q.z = left > 2 ? t[2] : 0; q.w = 0;
             }
             L.payload[wv][i] = q;
+            // payload words only: the first vector may start with up to 3 words of lane lengths
+            nonzero |= (i == 0) ? ((k0 < 1 ? q.x : 0u) | (k0 < 2 ? q.y : 0u) | (k0 < 3 ? q.z : 0u) | q.w) : (q.x | q.y | q.z | q.w);
         }
+        if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
         decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
                                          w_ref, n, c, L, P1, P2, K, raise);
     } else {
@@ -299,14 +310,15 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         }
         __syncthreads();
         const u32 wave = t >> 6;
+        const u32 zero_bits = zero_chunk_bits(L.len[K], L.code[K]);
         auto raise = [&](u32 code) { raise_status(ws, host, epoch, code); };
         for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
-                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, zero_bits, raise);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, P1, P2, K, area, zero_bits, raise);
             } else {
-                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, raise);
+                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, full ? zero_bits : 0u, raise);
             }
         }
     }
@@ -404,11 +416,12 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
         auto raise = [&](u32 code) { atomicMax(&a.seg_status[sidx], code); };
         const u32 c = g - sg.chunk0;
         const bool full = (u64)(c + 1) * kChunk <= sg.n;
+        const u32 zero_bits = full ? zero_chunk_bits(L.len[K], L.code[K]) : 0u;
         if (full && sg.aligned) {
-            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
-            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
+            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
         } else {
-            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, raise);
+            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
         }
     }
 }
@@ -555,6 +568,7 @@ struct FusedHead {
                                                  // has one length, so distinct entries in use lie in distinct banks
     const uint8_t* rec_base[T];                  // start of the chunk records
     const u32* off_tab[T];
+    u32 zero_bits[(T + 3) / 4 * 4];              // per blob: lane length of a chunk of merged symbols only (0: never skip)
     u32 pad[3];
     u32 before_pay;                              // the word in front of the payload area (read, never used)
 };
@@ -707,6 +721,7 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
         u32 most = 0;
 #pragma unroll
         for (int t = 0; t < T; ++t) most = max(most, (nw[t] + k0[t] + 3) >> 2);
+        u32 nonzero = 0;                                  // OR of this lane's share of the payload words
         for (u32 i0 = 0; i0 < most; i0 += CV * kW) {
             uint4 q[T][CV];
 #pragma unroll
@@ -729,14 +744,24 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 uint4* dst = reinterpret_cast<uint4*>(pay + wbase[t]);
-                const u32 nvec = (nw[t] + k0[t] + 3) >> 2;
+                const u32 have = nw[t] + k0[t], nvec = (have + 3) >> 2;
 #pragma unroll
                 for (int k = 0; k < CV; ++k) {
                     const u32 i = i0 + k * kW + lane;
-                    if (i < nvec) dst[i] = q[t][k];
+                    if (i < nvec) {
+                        dst[i] = q[t][k];
+                        const u32 j = 4 * i;              // words [k0, have) of the copied range are payload
+                        nonzero |= (j >= k0[t] && j < have ? q[t][k].x : 0u) | (j + 1 >= k0[t] && j + 1 < have ? q[t][k].y : 0u) |
+                                   (j + 2 >= k0[t] && j + 2 < have ? q[t][k].z : 0u) | (j + 3 >= k0[t] && j + 3 < have ? q[t][k].w : 0u);
+                    }
                 }
             }
         }
+        // every blob's chunk holds merged symbols only (see zero_chunk_bits): nothing changes, w_ref is not read
+        bool all_merged = true;
+#pragma unroll
+        for (int t = 0; t < T; ++t) all_merged = all_merged && H.zero_bits[t] != 0 && lane_bits[t] == H.zero_bits[t];
+        if (!__any(!all_merged || nonzero != 0)) return;
     }
 #pragma unroll
     for (int t = 0; t < T; ++t) start[t] = 31 + wave_incl_scan(lane_bits[t]) - lane_bits[t];
@@ -778,6 +803,7 @@ __global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, 
         }
         if (tid == 0) {
             const uint8_t* blob = blobs.p[first + t];
+            H.zero_bits[t] = zero_chunk_bits(D.info.len[K], D.info.code[K]);
             H.rec_base[t] = blob + D.info.area;
             H.off_tab[t] = reinterpret_cast<const u32*>(blob + kHeaderBytes);
         }

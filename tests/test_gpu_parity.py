@@ -794,3 +794,61 @@ def test_batched_decode_bad_blobs_leave_their_tensor_alone(lc):
         assert used[0] == sizes[3] and np.array_equal(bits(recs[0].cpu().numpy()), bits(ref_h))
     else:
         assert used[0] == -lc.ERR_BAD_BLOB
+
+
+def test_chunks_of_merged_symbols_only(lc):
+    """Deltas that touch a few chunks only: the other chunks hold the merged symbol throughout and are left
+    alone by the restore (plain, batched, several blobs at once).  Same weights as the oracle's, and a bit
+    flipped inside such a chunk's payload gives the oracle's verdict."""
+    nbits, nchunks = 3, 40
+    n = nchunks * 16384 + 77
+    g = torch.Generator(device=DEV); g.manual_seed(91)
+    w0 = 0.05 * torch.randn(n, generator=g, device=DEV)
+    deltas = []
+    for t in range(5):
+        d = torch.zeros(n, device=DEV)
+        lo = (7 * t + 3) * 16384 + 100
+        d[lo:lo + 20000] = 1e-3 * torch.randn(20000, generator=g, device=DEV)
+        deltas.append(d)
+    tracked, blobs = encode_chain(lc, w0, deltas, [nbits] * 5)
+    hdr = lcb1_reader.parse_header(blobs[0].cpu().numpy())
+    K = hdr["K"]
+    assert hdr["slots"][K]["len"] == 1 and all(s["len"] > 1 for s in hdr["slots"][:K])       # the merged symbol codes as "0"
+    ref = oracle_restore(w0, blobs)
+    rec = w0.clone()
+    for b in blobs:
+        lc.lc_decode(b, rec)
+    assert np.array_equal(bits(rec.cpu().numpy()), bits(ref))
+    rec = w0.clone()
+    lc.lc_decode_many(blobs, rec)
+    assert np.array_equal(bits(rec.cpu().numpy()), bits(ref))
+    rec = [w0.clone()]
+    lc.lc_decode_batch([blobs[0]], rec)
+    ref0 = w0.cpu().numpy(); orc.decode(blobs[0].cpu().numpy(), ref0)
+    assert np.array_equal(bits(rec[0].cpu().numpy()), bits(ref0))
+    # damage inside a chunk of merged symbols: chunk 0 of blob 0 (the delta starts in chunk 3)
+    area = 512 + (4 * (nchunks + 2) + 15) // 16 * 16
+    for byte in (128 + 5, 128 + 1000):
+        damaged = blobs[0].clone()
+        damaged[area + byte] ^= 0x40
+        ref_h = w0.cpu().numpy()
+        try:
+            orc.decode(damaged.cpu().numpy(), ref_h); ok = True
+        except orc.OracleError as e:
+            assert e.status == 4; ok = False
+        for call in ("one", "many", "batch"):
+            rec = w0.clone()
+            try:
+                if call == "one":
+                    lc.lc_decode(damaged, rec)
+                elif call == "many":
+                    lc.lc_decode_many([damaged], rec)
+                else:
+                    assert lc.lc_decode_batch([damaged], [rec])[0] == (damaged.numel() if ok else -lc.ERR_BAD_BLOB)
+                got_ok = True
+            except lc.LcError as e:
+                assert e.status == lc.ERR_BAD_BLOB; got_ok = False
+            if call != "batch":
+                assert got_ok == ok, call
+            if ok:
+                assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h)), call
