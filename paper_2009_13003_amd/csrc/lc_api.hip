@@ -120,7 +120,8 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
     }
     if (ds.owned_bytes < need) {
         if (ds.owned) { (void)hipDeviceSynchronize(); (void)hipFree(ds.owned); ds.owned = nullptr; ds.owned_bytes = 0; }
-        size_t want = need < (1u << 20) ? (1u << 20) : need;
+        size_t want = need < (4u << 20) ? (4u << 20) : need;     // never smaller than the head that is cleared below
+        static_assert(kWorkspaceHead <= (4u << 20), "the smallest scratch area must hold the fixed head");
         if (hipMalloc(&ds.owned, want) != hipSuccess) { (void)hipGetLastError(); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
         if (hipMemset(ds.owned, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(ds.owned); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
         ds.owned_bytes = want;
@@ -185,7 +186,9 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t* group_words = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
-    uint32_t* chunk_bits = group_words + kMaxGroups;
+    uint32_t* chunk_maxexp = group_words + kMaxGroups;
+    uint32_t* chunk_list = chunk_maxexp + kMaxChunks;
+    uint32_t* chunk_bits = chunk_list + kMaxChunks;
     const uint64_t nc = num_chunks_of(n);
     uint32_t* prov = chunk_bits + (nc + 63) / 64 * 64;
     const uint32_t slot_words = slot_words_of(nbits);
@@ -205,19 +208,19 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     Result* result = async ? &g_pinned_dev->enc_async[ticket] : &g_pinned_dev->enc;
     // Every call leaves the encode state cleared behind it; a fresh scratch area, or one whose last
     // call did not run to its end, is cleared first.
-    if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, s); }
+    if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, chunk_maxexp, s); }
     ds->clean = nullptr;
     if (cache) {
         { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
         { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     } else {
-        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, ds->tune, s);
+        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, ds->tune, s);
     }
-    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, s); }
-    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
+    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, chunk_maxexp, cache, n, nbits, dtype, s); }
     LC_HIP(hipGetLastError());
     if (async) {
         LC_HIP(hipEventRecord(g_ticket[ticket].done, s));

@@ -27,6 +27,18 @@ __device__ __forceinline__ u64 wave_sum64(u64 v) {
     return v;
 }
 
+// Largest value over the wavefront (all 64 lanes active), in every lane: row-wise running maxima with DPP
+// shifts, then the row results carried across rows (row_bcast), no LDS traffic.
+__device__ __forceinline__ u32 wave_max_u32(u32 v) {
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));     // row_shr:1
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));     // row_shr:2
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));     // row_shr:4
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));     // row_shr:8
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));     // row_bcast:15 into rows 1, 3
+    v = max(v, (u32)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));     // row_bcast:31 into rows 2, 3
+    return (u32)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 __device__ __forceinline__ u32 wave_sum32(u32 v) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);

@@ -15,17 +15,19 @@ namespace lc {
 
 // ----------------------------------------------------------------------------- k_reset
 // Brings the scratch state to what every encode call expects to find (and leaves behind):
-// zero bucket counts, empty extremes, zero group sums and arrival counters.  Only launched
+// zero bucket counts, empty extremes, zero group sums and per-chunk exponent maxima.  Only launched
 // for a fresh scratch area or after a call that did not run to its end.
-__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
+__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp,
+                                                   u32 nchunks, u32 tid, u32 nthr) {
     for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
+    for (u32 i = tid; i < nchunks; i += nthr) chunk_maxexp[i] = 0;
     for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
     if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
-    if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; }
+    if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; ws->list_count = 0; }
 }
 
-__global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups) {
-    clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
+__global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
+    clear_encode_state(ws, group_words, ngroups, chunk_maxexp, nchunks, threadIdx.x, blockDim.x);
 }
 
 // ----------------------------------------------------------------------------- k_hist
@@ -61,9 +63,21 @@ __device__ __forceinline__ float4 load_unit(const void* __restrict__ p, u64 unit
     }
 }
 
+// Largest magnitude among the EPU deltas of one unit and m (its exponent field is the largest biased exponent).
+// A NaN may drop out of a floating-point maximum: a vector with such a delta is not coded at all
+// (the table's status says so), and nobody looks at the chunk maxima then.
+template <int EPU>
+__device__ __forceinline__ float max_magnitude(const u32 (&u)[EPU], float m) {
+#pragma unroll
+    for (int v = 0; v < EPU; ++v) m = fmaxf(m, fabsf(__uint_as_float(u[v])));
+    return m;
+}
+
+// Every wavefront takes batches of PF consecutive rows of 64 units (PF KiB of each array), so a batch lies in
+// one chunk of the coding sweep and its largest exponent goes to chunk_maxexp with one atomic per batch.
 template <bool ALIGNED, int DT>
 __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
-                                               u64 n, EncState* ws) {
+                                               u64 n, EncState* ws, u32* chunk_maxexp) {
     __shared__ u32 h[512 * kHistCopies];
     constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
@@ -71,52 +85,68 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
     __syncthreads();
     const u32 copy = tid & (kHistCopies - 1);
     const u64 nu = n / EPU;
-    const u64 stride = (u64)gridDim.x * nthr;
-    u64 u = (u64)blockIdx.x * nthr + tid;
-    // Batches of PF 16-byte units per thread, one batch in flight while the previous one is counted.
+    // Batches of PF rows per wavefront, one batch in flight while the previous one is counted.
     constexpr int PF = 4;
+    constexpr u32 kBatchUnits = PF * kW;
+    static_assert(kChunk % (kBatchUnits * EPU) == 0, "a batch must not straddle two chunks");
+    const u64 nbatch = nu / kBatchUnits;
+    const u64 stride = (u64)gridDim.x * (nthr / kW);                    // wavefronts in the grid
+    u64 b = (u64)blockIdx.x * (nthr / kW) + tid / kW;
     float4 a0[PF], b0[PF], a1[PF], b1[PF];
-    auto fetch = [&](float4 (&a)[PF], float4 (&b)[PF], u64 at) {
+    auto fetch = [&](float4 (&a)[PF], float4 (&bb)[PF], u64 batch) {
+        const u64 at = batch * kBatchUnits + (tid & (kW - 1));
 #pragma unroll
-        for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * stride); b[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * stride); }
+        for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * kW); bb[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * kW); }
     };
-    auto count_unit = [&](const float4& a, const float4& b) {
+    auto count_unit = [&](const float4& a, const float4& bb, float m) {
         float x[EPU], y[EPU];
-        unpack_unit<DT, EPU>(a, x); unpack_unit<DT, EPU>(b, y);
+        u32 u[EPU];
+        unpack_unit<DT, EPU>(a, x); unpack_unit<DT, EPU>(bb, y);
 #pragma unroll
-        for (int v = 0; v < EPU; ++v) atomicAdd(&h[(delta_bits(x[v], y[v]) >> 23) * kHistCopies + copy], 1u);
+        for (int v = 0; v < EPU; ++v) { u[v] = delta_bits(x[v], y[v]); atomicAdd(&h[(u[v] >> 23) * kHistCopies + copy], 1u); }
+        return max_magnitude<EPU>(u, m);
     };
-    auto count = [&](float4 (&a)[PF], float4 (&b)[PF]) {
+    auto count = [&](float4 (&a)[PF], float4 (&bb)[PF], u64 batch) {
+        float mf = 0.f;
 #pragma unroll
-        for (int k = 0; k < PF; ++k) count_unit(a[k], b[k]);
+        for (int k = 0; k < PF; ++k) mf = count_unit(a[k], bb[k], mf);
+        const u32 m = wave_max_u32(__float_as_uint(mf));     // whole wavefronts only: b < nbatch is the same for all lanes
+        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[(batch * kBatchUnits * EPU) / kChunk], m >> 23);
     };
-    const u64 step = PF * stride;
-    if (u + (PF - 1) * stride < nu) {
-        fetch(a0, b0, u);
+    if (b < nbatch) {
+        fetch(a0, b0, b);
         while (true) {
-            const bool more1 = u + step + (PF - 1) * stride < nu;
-            if (more1) fetch(a1, b1, u + step);
-            count(a0, b0);
-            u += step;
+            const bool more1 = b + stride < nbatch;
+            if (more1) fetch(a1, b1, b + stride);
+            count(a0, b0, b);
+            b += stride;
             if (!more1) break;
-            const bool more0 = u + step + (PF - 1) * stride < nu;
-            if (more0) fetch(a0, b0, u + step);
-            count(a1, b1);
-            u += step;
+            const bool more0 = b + stride < nbatch;
+            if (more0) fetch(a0, b0, b + stride);
+            count(a1, b1, b);
+            b += stride;
             if (!more0) break;
         }
     }
-    for (; u < nu; u += stride) count_unit(load_unit<ALIGNED, DT, EPU>(w, u), load_unit<ALIGNED, DT, EPU>(w_ref, u));
-    if (blockIdx.x == 0 && tid < (u32)(n - EPU * nu)) {
-        const u64 i = EPU * nu + tid;
-        atomicAdd(&h[(delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i)) >> 23) * kHistCopies + copy], 1u);
+    // what is left of the vector: fewer than one batch of units, then fewer than one unit of elements
+    if (blockIdx.x == 0) {
+        for (u64 u = nbatch * kBatchUnits + tid; u < nu; u += nthr) {
+            const float mf = count_unit(load_unit<ALIGNED, DT, EPU>(w, u), load_unit<ALIGNED, DT, EPU>(w_ref, u), 0.f);
+            atomicMax(&chunk_maxexp[(u * EPU) / kChunk], __float_as_uint(mf) >> 23);
+        }
+        if (tid < (u32)(n - EPU * nu)) {
+            const u64 i = EPU * nu + tid;
+            const u32 u = delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i));
+            atomicAdd(&h[(u >> 23) * kHistCopies + copy], 1u);
+            atomicMax(&chunk_maxexp[i / kChunk], (u >> 23) & 255u);
+        }
     }
     __syncthreads();
-    for (u32 b = tid; b < 512; b += nthr) {
-        u32 s = 0;
+    for (u32 bk = tid; bk < 512; bk += nthr) {
+        u32 sum = 0;
 #pragma unroll
-        for (int k = 0; k < kHistCopies; ++k) s += h[b * kHistCopies + k];
-        if (s) atomicAdd(&ws->hist[b], (u64)s);
+        for (int k = 0; k < kHistCopies; ++k) sum += h[bk * kHistCopies + k];
+        if (sum) atomicAdd(&ws->hist[bk], (u64)sum);
     }
 }
 
@@ -137,9 +167,12 @@ struct TableLds {
 // whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
 // cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
 // if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
-__device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
+// With chunk_list (and a workgroup of more than one wavefront) the other wavefronts meanwhile list the chunks
+// that sweep 2 has to read: all but the full chunks whose largest exponent lies below every kept bucket.
+__device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups,
+                                            const u32* chunk_maxexp, u32* chunk_list) {
     __shared__ TableLds S;
-    __shared__ u32 s_reuse;
+    __shared__ u32 s_reuse, s_min_kept_exp, s_listed;
     const u32 lane = lane_id();
     const bool active = threadIdx.x < kW;
     const u32 kmax = (1u << nbits) - 1;
@@ -149,7 +182,7 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     // all eight counts of this lane first: the four ranking steps below then run without waiting on memory
     u64 cnt0[4], cnt1[4];
 #pragma unroll
-    for (u32 step = 0; step < 4; ++step) { cnt0[step] = ws->hist[255 - (step * kW + lane)]; cnt1[step] = ws->hist[511 - (step * kW + lane)]; }
+    for (u32 step = 0; active && step < 4; ++step) { cnt0[step] = ws->hist[255 - (step * kW + lane)]; cnt1[step] = ws->hist[511 - (step * kW + lane)]; }
 #pragma unroll
     for (u32 step = 0; active && step < 4; ++step) {
         const u32 E = 255 - (step * kW + lane);
@@ -165,8 +198,24 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
         nonfinite = nonfinite || __any(E == 255 && (c0 | c1) != 0);
         zero_class = zero_class || __any(E == 0 && (c0 | c1) != 0);
     }
-    const u32 K = total < kmax ? total : kmax;
+    const u32 K = total < kmax ? total : kmax;              // (meaningful in the first wavefront only)
     __syncthreads();
+    if (threadIdx.x == 0) { s_min_kept_exp = K ? (S.kept[K - 1] & 255u) : 256u; s_listed = 0; }   // kept buckets are in descending exponent order
+    __syncthreads();
+    if (chunk_list && threadIdx.x >= kW) {
+        const u32 min_kept_exp = s_min_kept_exp, workers = blockDim.x - kW;
+        const u32 nchunks = (u32)num_chunks_of(n), nfull = (u32)(n / kChunk);
+        for (u32 c0 = (threadIdx.x - kW) & ~(kW - 1); c0 < nchunks; c0 += workers) {
+            const u32 c = c0 + lane;
+            const bool read = c < nchunks && !(c < nfull && chunk_maxexp[c] < min_kept_exp);
+            const u64 m = __ballot(read);
+            if (m == 0) continue;
+            u32 base = 0;
+            if (lane == 0) base = atomicAdd(&s_listed, (u32)__popcll(m));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (read) chunk_list[base + __popcll(m & ((1ull << lane) - 1))] = c;
+        }
+    }
     if (threadIdx.x == 0) {
         Table& T = ws->table;
         u64 kept_total = 0;
@@ -230,9 +279,11 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
             T.cnt[sy] = sy < msym ? S.cnt[sy] : 0;
         }
         T.K = K; T.max_len = max_len; T.k_E = total + (zero_class ? 1u : 0u);
+        T.min_kept_exp = s_min_kept_exp;
         T.status = nonfinite ? 2u : 0u;
     }
     __syncthreads();
+    if (threadIdx.x == 0) ws->list_count = s_listed;
     if (active) for (u32 b = lane; b < 512; b += kW) {
         const u32 sy = S.sym[b] == 0xFF ? K : S.sym[b];
         ws->table.symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
@@ -243,8 +294,9 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     }
 }
 
-__global__ __launch_bounds__(64) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups) {
-    table_build(ws, n, nbits, group_words, ngroups);
+__global__ __launch_bounds__(1024) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups,
+                                                 const u32* chunk_maxexp, u32* chunk_list) {
+    table_build(ws, n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
 }
 
 // ----------------------------------------------------------------------------- k_spec_table
@@ -290,6 +342,7 @@ __global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCach
                 if (j < K) s_sym[cache->kept[j]] = j;
             }
             T.K = K; T.max_len = max_len; T.k_E = 0; T.status = 0;
+            T.min_kept_exp = K ? (cache->kept[K - 1] & 255u) : 256u;
         }
         s_ok = ok;
         ws->spec = ok; ws->spec_ok = 0;
@@ -390,6 +443,12 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
     if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
     finish_lane_sizes(ch, nb, nw);
 }
+
+// A full chunk whose largest exponent (sweep 1 recorded it) lies below every kept bucket: all 16384 symbols
+// are the merged one (Section 3.1.1, priority promotion) and each lane's string is 256 copies of its code.
+// Such a chunk gets no slot: sweep 2 only notes its size, with kMergedChunk set in chunk_bits, and k_place
+// writes the repeated code straight into the blob.
+constexpr u32 kMergedChunk = 0x80000000u;
 
 constexpr int kPackPF = 8;          // rows per prefetch batch of the coding loop
 
@@ -507,14 +566,15 @@ __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const Chunk
 // take a whole row (31 waiting bits + 4 codes of <= 8 bits) between flushes.
 // ROWSEL: 1 / 0 = rowchk() is known to be true / false for every chunk (one vector, one table);
 // -1 = ask per chunk (a batched call, where tables change).
+// Src::take() is the wavefront's next chunk.
 template <bool HIST, bool PACK, int DT, int ROWSEL, typename Src>
 __device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
     typedef typename Raw<DT>::type raw_t;
     raw_t A0[kPackPF], B0[kPackPF];
-    ChunkRef cur = src.get(0);
+    ChunkRef cur = src.take();
     if (cur.valid && cur.fast) fetch_first_batch<DT>(cur, A0, B0);
-    for (u32 k = 0; cur.valid; ++k) {
-        const ChunkRef next = src.get(k + 1);
+    while (cur.valid) {
+        const ChunkRef next = src.take();
         src.enter(cur, L);
         if (!cur.fast) {
             pack_chunk_plain<HIST, PACK, DT>(cur, L);
@@ -528,24 +588,32 @@ __device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
     }
 }
 
-// The chunks of one vector, dealt round-robin to the wavefronts of the grid.
+// The chunks of one vector that have to be read, dealt round-robin to the wavefronts of the grid: all of
+// them, or with chunk_list the `listed` ones named there.
 struct VectorChunks {
     const void* w; const void* w_ref;
     u64 n;
     u32* prov; u32 slot_words; u32* chunk_bits; u32* group_words;
     u32 nchunks; bool aligned;
     u32 k8; bool row;
-    __device__ __forceinline__ ChunkRef get(u32 k) const {
+    const u32* chunk_list; u32 listed;
+    u32 pos;
+    __device__ __forceinline__ ChunkRef ref(u32 c, bool valid) const {
         ChunkRef ch;
-        ch.c = blockIdx.x + k * gridDim.x;
-        ch.valid = ch.c < nchunks;
+        ch.c = c;
+        ch.valid = valid;
         ch.w = w; ch.w_ref = w_ref; ch.n = n;
-        ch.fast = aligned && (u64)(ch.c + 1) * kChunk <= n;
-        ch.slot = prov + (u64)ch.c * slot_words;
-        ch.bits_at = chunk_bits + ch.c;
-        ch.group_at = group_words + (ch.c >> 6);
+        ch.fast = aligned && (u64)(c + 1) * kChunk <= n;
+        ch.slot = prov + (u64)c * slot_words;
+        ch.bits_at = chunk_bits + c;
+        ch.group_at = group_words + (c >> 6);
         ch.seg = 0;
         return ch;
+    }
+    __device__ __forceinline__ ChunkRef take() {
+        const u32 i = blockIdx.x + (pos++) * gridDim.x;
+        if (!chunk_list) return ref(i, i < nchunks);
+        return i < listed ? ref(chunk_list[i], true) : ref(nchunks, false);
     }
     template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
     __device__ __forceinline__ u32 K8() const { return k8; }
@@ -575,7 +643,8 @@ __device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, EncState* 
 
 template <int DT>
 __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
-                                             EncState* ws, u32* chunk_bits, u32* group_words, u32* prov,
+                                             EncState* ws, u32* chunk_bits, u32* group_words,
+                                             const u32* chunk_maxexp, const u32* chunk_list, u32* prov,
                                              u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<false> L;
     const u32 lane = threadIdx.x;
@@ -584,7 +653,19 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
     pack_setup(L, T, lane);
     const u32 K = T.K;
     __syncthreads();
-    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8};
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8,
+                        chunk_list, chunk_list ? ws->list_count : 0, 0};
+    if (chunk_list) {
+        // the chunks k_table left off the list (full ones that hold merged elements only), a group of 64 per step
+        const u32 nfull = (u32)(n / kChunk), min_kept_exp = T.min_kept_exp, len_merged = T.codelen[K] & 31;
+        for (u32 c0 = blockIdx.x * kW; c0 < nfull; c0 += gridDim.x * kW) {
+            const u32 c = c0 + lane;
+            const bool merged = c < nfull && chunk_maxexp[c] < min_kept_exp;
+            if (merged) chunk_bits[c] = kMergedChunk | (kChunk * len_merged);
+            const u32 count = (u32)__popcll(__ballot(merged));
+            if (lane == 0 && count) atomicAdd(&group_words[c0 >> 6], count * (kLaneBitsWords + kChunk / 32 * len_merged));
+        }
+    }
     if (src.row) pack_loop<false, true, DT, 1>(src, L);
     else pack_loop<false, true, DT, 0>(src, L);
     __syncthreads();
@@ -607,7 +688,8 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, c
     if (spec) pack_setup(L, T, lane);
     const u32 K = spec ? T.K : 0;
     __syncthreads();
-    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, !spec || T.max_len <= 8};
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3,
+                        !spec || T.max_len <= 8, nullptr, 0, 0};
     if (!spec) pack_loop<true, false, DT, 1>(src, L);
     else if (src.row) pack_loop<true, true, DT, 1>(src, L);
     else pack_loop<true, true, DT, 0>(src, L);
@@ -692,9 +774,10 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
 }
 
 __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
-                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
+                                                  u32* chunk_maxexp, TableCache* cache, u64 n, int nbits, u32 nchunks,
+                                                  u32 dtype) {
     finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype);
-    clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
+    clear_encode_state(ws, group_words, (nchunks + 63) / 64, chunk_maxexp, nchunks, threadIdx.x, blockDim.x);
     __threadfence_system();
 }
 
@@ -710,9 +793,11 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
     u32* s_hw = s_hw_all[wv];
     u32* s_buf = s_buf_all[wv];
     const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
-    const u32 bits = valid ? reinterpret_cast<const uint16_t*>(slot)[lane] : 0;
+    const u32 own = valid ? __builtin_amdgcn_readfirstlane(chunk_bits[c]) : 0;
+    const bool merged = (own & kMergedChunk) != 0;               // wave-uniform: no slot, 256 copies of one code per lane
+    const u32 bits = !valid ? 0 : merged ? (own & ~kMergedChunk) / kW : reinterpret_cast<const uint16_t*>(slot)[lane];
     const u32 g = c >> 6;
-    u64 part = (valid && 64 * g + lane < c) ? kLaneBitsWords + ((chunk_bits[64 * g + lane] + 31) >> 5) : 0;
+    u64 part = (valid && 64 * g + lane < c) ? kLaneBitsWords + (((chunk_bits[64 * g + lane] & ~kMergedChunk) + 31) >> 5) : 0;
     if (valid) {
 #pragma unroll 4
         for (u32 j = lane; j < g; j += kW) part += group_words[j];
@@ -731,13 +816,28 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
             if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
         }
     }
+    if (merged) {
+        // every lane's string is a whole number of codes and of words, so the payload is the code repeated
+        // 16384 times: word i holds the 32 bits from bit 32 i of that endless repetition on
+        const u32 codelen = __builtin_amdgcn_readfirstlane(ws->table.codelen[ws->table.K]);
+        const u32 len = max(codelen & 31, 1u);                  // (a merged symbol that occurs has a code)
+        u64 rep = (u64)(codelen >> 5) << (64 - len);            // the code repeated from bit 63 downwards
+        for (u32 filled = len; filled < 64; filled <<= 1) rep |= rep >> filled;
+        u32 phase = (32 * lane) % len;                          // bit of the code that word i starts with
+        const u32 step = (32 * kW) % len;
+        for (u32 i = lane; i < nwords; i += kW) {
+            payload[i] = (u32)((rep << phase) >> 32);
+            phase += step;
+            if (phase >= len) phase -= len;
+        }
+    }
     const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
-    const u32 nt = bits ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
+    const u32 nt = (bits && !merged) ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
     u32 nt_max = nt;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nt_max = max(nt_max, (u32)__shfl_xor(nt_max, d, 64));
     const u32* lane_words = slot + kLaneBitsWords + lane;
-    const bool staged = nwords <= kPlaceWords;               // wave-uniform
+    const bool staged = nwords <= kPlaceWords && !merged;    // wave-uniform
     if (staged) {
         for (u32 i = lane; i < nwords; i += kW) s_buf[i] = 0;
     } else {
@@ -823,9 +923,10 @@ struct BatchChunks {
     BatchArgs a;
     u32 active;                  // tensor whose counts / extremes / table the LDS holds (0xFFFFFFFF: none yet)
     u32 k8; bool row;
-    __device__ __forceinline__ ChunkRef get(u32 k) const {
+    u32 pos;
+    __device__ __forceinline__ ChunkRef take() {
         ChunkRef ch;
-        const u32 g = blockIdx.x + k * gridDim.x;
+        const u32 g = blockIdx.x + (pos++) * gridDim.x;
         ch.valid = g < a.total_chunks;
         ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false;
         ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
@@ -877,18 +978,18 @@ __global__ __launch_bounds__(64) void kb_hist(BatchArgs a) {
     __shared__ PackLds<true> L;
     for (u32 i = threadIdx.x; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
     __syncthreads();
-    BatchChunks<true, false> src = {a, 0xFFFFFFFFu, 0, true};
+    BatchChunks<true, false> src = {a, 0xFFFFFFFFu, 0, true, 0};
     pack_loop<true, false, kF32, 1>(src, L);
     src.hand_in(L);
 }
 
 __global__ __launch_bounds__(64) void kb_table(BatchArgs a) {
-    table_build(&a.states[blockIdx.x], a.segs[blockIdx.x].n, a.nbits, nullptr, 0);
+    table_build(&a.states[blockIdx.x], a.segs[blockIdx.x].n, a.nbits, nullptr, 0, nullptr, nullptr);
 }
 
 __global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
     __shared__ PackLds<false> L;
-    BatchChunks<false, true> src = {a, 0xFFFFFFFFu, 0, true};
+    BatchChunks<false, true> src = {a, 0xFFFFFFFFu, 0, true, 0};
     pack_loop<false, true, kF32, 0>(src, L);      // flush per pair of codes: right for every table of the batch
     src.hand_in(L);
 }
@@ -909,17 +1010,19 @@ __global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
     if (blockIdx.x == gridDim.x - 1) __threadfence_system();
 }
 // ----------------------------------------------------------------------------- launchers
-void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s) {
-    hipLaunchKernelGGL(k_reset, dim3(1), dim3(256), 0, s, ws, group_words, (u32)kMaxGroups);
+void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s) {
+    hipLaunchKernelGGL(k_reset, dim3(1), dim3(1024), 0, s, ws, group_words, (u32)kMaxGroups, chunk_maxexp, (u32)kMaxChunks);
 }
 
 template <int DT>
-static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32 blocks, u32 threads, hipStream_t s) {
-    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
-    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws);
+static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32* chunk_maxexp, u32 blocks, u32 threads,
+                          hipStream_t s) {
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp);
+    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp);
 }
 
-void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s) {
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, const Tuning& tune,
+                 hipStream_t s) {
     if (n == 0) return;
     const u32 threads = tune.hist_threads;
     const u64 units = n / (dtype == kF32 ? 4 : 8);                 // 16-byte units
@@ -927,13 +1030,16 @@ void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     const u64 cap = (u64)tune.num_cu * tune.hist_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
-    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, (u32)blocks, threads, s);
-    else launch_hist_t<kF32>(w, w_ref, n, ws, (u32)blocks, threads, s);
+    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
+    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
+    else launch_hist_t<kF32>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
 }
 
-void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s) {
-    hipLaunchKernelGGL(k_table, dim3(1), dim3(64), 0, s, ws, (u64)n, nbits, group_words, (u32)((num_chunks_of(n) + 63) / 64));
+// chunk_list: where to list the chunks sweep 2 has to read (chunk_maxexp then holds what k_hist recorded), or null
+void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, const uint32_t* chunk_maxexp, uint32_t* chunk_list,
+                  hipStream_t s) {
+    hipLaunchKernelGGL(k_table, dim3(1), dim3(chunk_list ? 1024 : 64), 0, s, ws, (u64)n, nbits, group_words,
+                       (u32)((num_chunks_of(n) + 63) / 64), chunk_maxexp, chunk_list);
 }
 
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
@@ -953,17 +1059,19 @@ void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, 
     else hipLaunchKernelGGL(k_spec_sweep<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
 }
 
+// chunk_maxexp, chunk_list: what k_hist recorded and k_table listed for this vector, or both null
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
-                 uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
+                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, uint32_t* prov,
+                 uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
     if (blocks > nchunks) blocks = nchunks;
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
     const dim3 grid((u32)blocks), wg(64);
-    if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
-    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
-    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
+    if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
 }
 
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
@@ -974,9 +1082,9 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                        slot_words, (u32)nchunks);
 }
 
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, hipStream_t s) {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint32_t* chunk_maxexp,
+                     TableCache* cache, uint64_t n, int nbits, int dtype, hipStream_t s) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, chunk_maxexp, cache, (u64)n, nbits,
                        (u32)num_chunks_of(n), (u32)dtype);
 }
 

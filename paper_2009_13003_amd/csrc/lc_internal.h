@@ -28,6 +28,8 @@ struct Table {
     uint32_t kept[kMaxSym];      // bucket id of symbol j < K
     uint64_t cnt[kMaxSym];
     uint8_t  symlen_of_bucket[512];   // low nibble symbol, high nibble code length
+    uint32_t min_kept_exp;            // smallest biased exponent among the kept buckets (256: none kept)
+    uint32_t pad_t;
 };
 
 // Written by the decode-prepare kernel.
@@ -82,12 +84,15 @@ struct EncState {
     uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
     uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
     unsigned long long total_words;
+    uint32_t list_count;             // entries of chunk_list (the chunks sweep 2 has to read), written by k_table
+    uint32_t pad_e;
     Table table;
 };
 
-// Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] (u32, at a
-// fixed place so that it can be left cleared from one call to the next), chunk_bits[num_chunks]
-// (u32, padded to 256 bytes) and one slot of slot_words_of(nbits) 32-bit words per chunk.
+// Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] and
+// chunk_maxexp[kMaxChunks] (u32, at fixed places so that they can be left cleared from one call to the
+// next), chunk_list[kMaxChunks] (u32), chunk_bits[num_chunks] (u32, padded to 256 bytes) and one slot of
+// slot_words_of(nbits) 32-bit words per chunk.
 struct Workspace : EncState {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     DecSet dec_set[kMaxSets];        // one per blob of the call
@@ -95,7 +100,11 @@ struct Workspace : EncState {
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
 constexpr uint32_t kMaxGroups = 4096;       // 2^32 elements / 16384 per chunk / 64 chunks per group
-constexpr size_t kWorkspaceHead = kWorkspaceFixed + 4 * kMaxGroups;   // fixed part + group_words
+constexpr uint32_t kMaxChunks = 1u << 18;   // 2^32 elements / 16384 per chunk
+// fixed part + group_words[kMaxGroups] + chunk_maxexp[kMaxChunks] (largest biased exponent of |delta| per chunk,
+// written by sweep 1, kept cleared between calls like group_words) + chunk_list[kMaxChunks] (the chunks that
+// sweep 2 has to read, in no particular order)
+constexpr size_t kWorkspaceHead = kWorkspaceFixed + 4 * kMaxGroups + 8 * (size_t)kMaxChunks;
 
 __host__ __device__ inline uint64_t num_chunks_of(uint64_t n) { return (n + kChunk - 1) / kChunk; }
 // Slot of one chunk in the scratch area: 64 lane lengths (u16), then up to 8 * max_len words
@@ -120,18 +129,21 @@ struct Tuning {
 };
 
 // Launchers (lc_encode.hip, lc_decode.hip).
-void launch_reset(Workspace* ws, uint32_t* group_words, hipStream_t s);
-void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, const Tuning& tune, hipStream_t s);
-void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, hipStream_t s);
+void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s);
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, const Tuning& tune,
+                 hipStream_t s);
+void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, const uint32_t* chunk_maxexp, uint32_t* chunk_list,
+                  hipStream_t s);
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
-                 uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
+                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, uint32_t* prov,
+                 uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, hipStream_t s);
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint32_t* chunk_maxexp,
+                     TableCache* cache, uint64_t n, int nbits, int dtype, hipStream_t s);
 // One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
 // chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
 struct Seg {

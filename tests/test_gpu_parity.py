@@ -852,3 +852,70 @@ def test_chunks_of_merged_symbols_only(lc):
                 assert got_ok == ok, call
             if ok:
                 assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h)), call
+
+
+def quiet_chunk_case(n, seed, quiet, tiny=2.0 ** -30):
+    """Deltas of four binades (eight buckets) everywhere, except in the chunks listed in `quiet`, whose
+    deltas are far smaller (or zero): those chunks lie below every kept bucket."""
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    w_ref = 0.05 * torch.randn(n, generator=g, device=DEV)
+    e = torch.randint(10, 14, (n,), generator=g, device=DEV).float()
+    d = torch.exp2(-e) * (1 + torch.rand(n, generator=g, device=DEV))
+    d = d * (2 * torch.randint(0, 2, (n,), generator=g, device=DEV).float() - 1)
+    for k, c in enumerate(quiet):
+        lo, hi = c * 16384, min(n, (c + 1) * 16384)
+        if k % 3 == 2:
+            d[lo:hi] = 0
+        else:
+            d[lo:hi] = tiny * (1 + torch.rand(hi - lo, generator=g, device=DEV)) * (1 - 2 * (k % 2))
+    # w - w_ref must reproduce d's bucket: use a reference of zeros where d is tiny
+    w_ref = torch.where(d.abs() < 1e-6, torch.zeros_like(w_ref), w_ref)
+    return w_ref + d, w_ref
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_encode_of_chunks_below_every_kept_bucket(lc, nbits):
+    """Whole chunks whose deltas all fall into the merged bucket are coded without being read again, from the
+    per-chunk exponent maxima of the first sweep: at the start, at group borders (63, 64), in a run, as the
+    last full chunk and in the ragged tail (which is read as usual).  The merged symbol's code has one bit
+    (nbits = 2) or several (nbits = 3, 4), so the repeated code does not line up with 32-bit words."""
+    nchunks = 150
+    n = nchunks * 16384 + 1234
+    quiet = [0, 5, 63, 64] + list(range(100, 111)) + [149, 150]
+    w, w_ref = quiet_chunk_case(n, 300 + nbits, quiet)
+    blob = check_case(lc, w, w_ref, nbits, "quiet chunks")
+    hdr = lcb1_reader.parse_header(blob)
+    K = hdr["K"]
+    merged_len = hdr["slots"][K]["len"]
+    print("merged symbol's code length", merged_len, flush=True)
+    assert merged_len == 1 if nbits == 2 else merged_len >= 2
+    # unaligned arrays: the quiet chunks are still recognised, the others take the guarded path
+    check_case(lc, w[3:], w_ref[3:], nbits, "quiet chunks, unaligned")
+    # every full chunk quiet, and nothing but quiet chunks plus one loud element in the tail
+    w2, ref2 = quiet_chunk_case(n, 310 + nbits, list(range(nchunks + 1)))
+    check_case(lc, w2, ref2, nbits, "all quiet")
+    w2[-5] = ref2[-5] + 0.25
+    check_case(lc, w2, ref2, nbits, "all quiet but one")
+    # the caller's scratch area and a second call right after (the per-chunk maxima are left cleared)
+    check_case(lc, w, w_ref, nbits, "quiet chunks again")
+
+
+@pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
+def test_encode_of_quiet_chunks_16_bit(lc, tdt):
+    code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+    nbits, n = 3, 40 * 16384 + 99
+    g = torch.Generator(device=DEV); g.manual_seed(77)
+    w_ref = (0.05 * torch.randn(n, generator=g, device=DEV)).to(tdt)
+    w = (w_ref.float() + 2e-3 * torch.randn(n, generator=g, device=DEV)).to(tdt)
+    for c in (0, 7, 8, 9, 31, 39):
+        w[c * 16384:(c + 1) * 16384] = w_ref[c * 16384:(c + 1) * 16384]         # unchanged chunks
+    out = lc.alloc_out(n, nbits, DEV); out.fill_(0x5A)
+    size = lc.lc_encode_t(w, w_ref, nbits, out)
+    blob_cpu = orc.encode_t(raw16(w), raw16(w_ref), nbits, code)
+    blob_gpu = out[:size].cpu().numpy()
+    assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    rec = w_ref.clone()
+    assert lc.lc_decode_t(out, rec) == size
+    ref_h = raw16(w_ref)
+    orc.decode_t(blob_cpu, ref_h, code)
+    assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
