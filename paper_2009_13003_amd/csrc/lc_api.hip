@@ -219,8 +219,8 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
     { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
-    { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, chunk_maxexp, cache, n, nbits, dtype, s); }
+    { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, s); }
     LC_HIP(hipGetLastError());
     if (async) {
         LC_HIP(hipEventRecord(g_ticket[ticket].done, s));

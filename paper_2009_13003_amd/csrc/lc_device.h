@@ -27,6 +27,14 @@ __device__ __forceinline__ u64 wave_sum64(u64 v) {
     return v;
 }
 
+// Where chunk c's entry lies in chunk_maxexp[kMaxChunks]: sweep 1 works on a window of consecutive chunks at any
+// moment, and their atomics would all land in one or two cache lines (one memory channel); transposing the
+// 512 x 512 index puts neighbouring chunks 2 KiB apart.
+__device__ __forceinline__ u32 maxexp_slot(u32 c) {
+    static_assert(kMaxChunks == 512u * 512u, "the transposition assumes 2^18 entries");
+    return ((c & 511u) << 9) | (c >> 9);
+}
+
 // Largest value over the wavefront (all 64 lanes active), in every lane: row-wise running maxima with DPP
 // shifts, then the row results carried across rows (row_bcast), no LDS traffic.
 __device__ __forceinline__ u32 wave_max_u32(u32 v) {

@@ -1,7 +1,7 @@
 // Encode kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64).
 //
 // lc_encode:         k_hist -> k_table -> k_pack -> k_place -> k_finalize (which also clears the scratch
-//                    state for the next call); k_reset only for a fresh scratch area
+//                    state for the next call, k_place the per-chunk maxima); k_reset only for a fresh scratch area
 // lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place -> k_finalize
 // lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_pack -> kb_place -> kb_finalize
 //
@@ -17,17 +17,16 @@ namespace lc {
 // Brings the scratch state to what every encode call expects to find (and leaves behind):
 // zero bucket counts, empty extremes, zero group sums and per-chunk exponent maxima.  Only launched
 // for a fresh scratch area or after a call that did not run to its end.
-__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp,
-                                                   u32 nchunks, u32 tid, u32 nthr) {
+__device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_words, u32 ngroups, u32 tid, u32 nthr) {
     for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
-    for (u32 i = tid; i < nchunks; i += nthr) chunk_maxexp[i] = 0;
     for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
     if (tid < kMaxSym) { ws->mmin[tid] = 0x7FFFFFu; ws->mmax[tid] = 0; }
     if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; ws->list_count = 0; }
 }
 
 __global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
-    clear_encode_state(ws, group_words, ngroups, chunk_maxexp, nchunks, threadIdx.x, blockDim.x);
+    clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
+    for (u32 i = threadIdx.x; i < nchunks; i += blockDim.x) chunk_maxexp[i] = 0;
 }
 
 // ----------------------------------------------------------------------------- k_hist
@@ -111,34 +110,36 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
 #pragma unroll
         for (int k = 0; k < PF; ++k) mf = count_unit(a[k], bb[k], mf);
         const u32 m = wave_max_u32(__float_as_uint(mf));     // whole wavefronts only: b < nbatch is the same for all lanes
-        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[(batch * kBatchUnits * EPU) / kChunk], m >> 23);
+        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m >> 23);
     };
     if (b < nbatch) {
+        // The loads of the batch after next are issued without a branch around them (at the end the current
+        // batch is simply read again): only then does the compiler wait for the older batch alone.
         fetch(a0, b0, b);
         while (true) {
             const bool more1 = b + stride < nbatch;
-            if (more1) fetch(a1, b1, b + stride);
+            fetch(a1, b1, more1 ? b + stride : b);
             count(a0, b0, b);
-            b += stride;
             if (!more1) break;
-            const bool more0 = b + stride < nbatch;
-            if (more0) fetch(a0, b0, b + stride);
-            count(a1, b1, b);
             b += stride;
+            const bool more0 = b + stride < nbatch;
+            fetch(a0, b0, more0 ? b + stride : b);
+            count(a1, b1, b);
             if (!more0) break;
+            b += stride;
         }
     }
     // what is left of the vector: fewer than one batch of units, then fewer than one unit of elements
     if (blockIdx.x == 0) {
         for (u64 u = nbatch * kBatchUnits + tid; u < nu; u += nthr) {
             const float mf = count_unit(load_unit<ALIGNED, DT, EPU>(w, u), load_unit<ALIGNED, DT, EPU>(w_ref, u), 0.f);
-            atomicMax(&chunk_maxexp[(u * EPU) / kChunk], __float_as_uint(mf) >> 23);
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((u * EPU) / kChunk))], __float_as_uint(mf) >> 23);
         }
         if (tid < (u32)(n - EPU * nu)) {
             const u64 i = EPU * nu + tid;
             const u32 u = delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i));
             atomicAdd(&h[(u >> 23) * kHistCopies + copy], 1u);
-            atomicMax(&chunk_maxexp[i / kChunk], (u >> 23) & 255u);
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)(i / kChunk))], (u >> 23) & 255u);
         }
     }
     __syncthreads();
@@ -207,7 +208,7 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
         const u32 nchunks = (u32)num_chunks_of(n), nfull = (u32)(n / kChunk);
         for (u32 c0 = (threadIdx.x - kW) & ~(kW - 1); c0 < nchunks; c0 += workers) {
             const u32 c = c0 + lane;
-            const bool read = c < nchunks && !(c < nfull && chunk_maxexp[c] < min_kept_exp);
+            const bool read = c < nchunks && !(c < nfull && chunk_maxexp[maxexp_slot(c)] < min_kept_exp);
             const u64 m = __ballot(read);
             if (m == 0) continue;
             u32 base = 0;
@@ -660,7 +661,7 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
         const u32 nfull = (u32)(n / kChunk), min_kept_exp = T.min_kept_exp, len_merged = T.codelen[K] & 31;
         for (u32 c0 = blockIdx.x * kW; c0 < nfull; c0 += gridDim.x * kW) {
             const u32 c = c0 + lane;
-            const bool merged = c < nfull && chunk_maxexp[c] < min_kept_exp;
+            const bool merged = c < nfull && chunk_maxexp[maxexp_slot(c)] < min_kept_exp;
             if (merged) chunk_bits[c] = kMergedChunk | (kChunk * len_merged);
             const u32 count = (u32)__popcll(__ballot(merged));
             if (lane == 0 && count) atomicAdd(&group_words[c0 >> 6], count * (kLaneBitsWords + kChunk / 32 * len_merged));
@@ -774,10 +775,9 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
 }
 
 __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
-                                                  u32* chunk_maxexp, TableCache* cache, u64 n, int nbits, u32 nchunks,
-                                                  u32 dtype) {
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
     finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype);
-    clear_encode_state(ws, group_words, (nchunks + 63) / 64, chunk_maxexp, nchunks, threadIdx.x, blockDim.x);
+    clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
     __threadfence_system();
 }
 
@@ -879,8 +879,10 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
 
 __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                                const u32* __restrict__ group_words, const u32* __restrict__ prov,
-                                               u32 slot_words, u32 nchunks) {
+                                               u32 slot_words, u32 nchunks, u32* chunk_maxexp) {
     const u32 c = blockIdx.x * 4 + (threadIdx.x >> 6);
+    // sweep 2 was the last to look at the chunk maxima: leave them cleared for the next call, whatever this one's outcome
+    if (c < nchunks && lane_id() == 0) chunk_maxexp[maxexp_slot(c)] = 0;
     // the last workgroup may hold idle wavefronts
     place_chunk(out, ws, chunk_bits, group_words, prov, slot_words, nchunks, c, c < nchunks && ws->table.status == 0);
 }
@@ -1075,16 +1077,16 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
 }
 
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
-                  const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s) {
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
-                       slot_words, (u32)nchunks);
+                       slot_words, (u32)nchunks, chunk_maxexp);
 }
 
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint32_t* chunk_maxexp,
-                     TableCache* cache, uint64_t n, int nbits, int dtype, hipStream_t s) {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, chunk_maxexp, cache, (u64)n, nbits,
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
+                     uint64_t n, int nbits, int dtype, hipStream_t s) {
+    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
                        (u32)num_chunks_of(n), (u32)dtype);
 }
 

@@ -141,9 +141,9 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
                  uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, uint32_t* prov,
                  uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
-                  const uint32_t* prov, uint32_t slot_words, uint64_t n, hipStream_t s);
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, uint32_t* chunk_maxexp,
-                     TableCache* cache, uint64_t n, int nbits, int dtype, hipStream_t s);
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s);
+void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
+                     uint64_t n, int nbits, int dtype, hipStream_t s);
 // One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
 // chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
 struct Seg {
