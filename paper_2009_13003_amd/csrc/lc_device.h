@@ -27,6 +27,14 @@ __device__ __forceinline__ u64 wave_sum64(u64 v) {
     return v;
 }
 
+// A word of memory that no kernel now running writes (tables and lists a previous kernel left), at an address that
+// is the same in all lanes: read as constant memory it goes through the scalar cache, and waiting for it does not
+// mean waiting for every vector load and store the wavefront has in flight.
+__device__ __forceinline__ u32 load_uniform(const u32* p) {
+    typedef const __attribute__((address_space(4))) u32* const_ptr;
+    return *(const_ptr)(p);
+}
+
 // Where chunk c's entry lies in chunk_maxexp[kMaxChunks]: sweep 1 works on a window of consecutive chunks at any
 // moment, and their atomics would all land in one or two cache lines (one memory channel); transposing the
 // 512 x 512 index puts neighbouring chunks 2 KiB apart.

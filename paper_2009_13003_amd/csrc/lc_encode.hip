@@ -614,7 +614,7 @@ struct VectorChunks {
     __device__ __forceinline__ ChunkRef take() {
         const u32 i = blockIdx.x + (pos++) * gridDim.x;
         if (!chunk_list) return ref(i, i < nchunks);
-        return i < listed ? ref(chunk_list[i], true) : ref(nchunks, false);
+        return i < listed ? ref(load_uniform(chunk_list + i), true) : ref(nchunks, false);
     }
     template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
     __device__ __forceinline__ u32 K8() const { return k8; }
