@@ -120,8 +120,9 @@ def run(job, steps, warmup, with_cached=True):
         if name in alg:
             ach = alg[name] * job.n / 1e9 / (per_step_ms / 1e3)
             ent.update(alg_bytes_per_elem=round(alg[name], 4), achieved_GBps=round(ach, 1), frac=round(ach / HBM_PEAK_GBPS, 4))
-            # k_decode does not write rows in which nothing changed, so on sparse updates it moves fewer bytes than
-            # the formula (frac can pass 1); the counter-based traffic, where a summary is committed, is what moved
+            # k_pack and k_decode pass over chunks that hold the merged symbol only, so on sparse updates they move
+            # fewer bytes than the formula (frac can pass 1); the counter-based traffic, where a summary is committed,
+            # is what moved
             tr = traffic_from_profiles(name, job.name)
             if tr is not None:
                 per_launch_ms = per_step_ms / max(1, launches // steps)
