@@ -146,24 +146,38 @@ def lc_decode_t(blob, w_ref, stream=None, n=None):
     return r
 
 
+class EncodeBatch:
+    """The marshalled arguments of one lc_encode_batch call, kept for the next call on the same tensors: a
+    training loop checkpoints the same parameter tensors every time, and checking and converting a few hundred
+    tensors costs more host time than the call.  The tensors must stay alive and in place."""
+
+    def __init__(self, ws, w_refs, nbits, outs):
+        count = len(ws)
+        assert count == len(w_refs) == len(outs) and count >= 1
+        for w, r, o in zip(ws, w_refs, outs):
+            assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and r.is_cuda and r.dtype == torch.float32
+            assert r.is_contiguous() and r.numel() == w.numel() and o.is_cuda and o.dtype == torch.uint8 and o.is_contiguous()
+            assert o.numel() >= lc_encode_bound(w.numel(), nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+        self.keep = (list(ws), list(w_refs), list(outs))
+        self.count, self.nbits = count, nbits
+        self.wp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in ws])
+        self.rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
+        self.op = (_vp * count)(*[t.data_ptr() for t in outs])
+        self.ns = (_u64 * count)(*[t.numel() for t in ws])
+        self.sizes = (_i64 * count)()
+
+    def run(self, stream=None):
+        r = int(_lib.lc_encode_batch(self.wp, self.rp, self.ns, self.count, self.nbits, self.op, self.sizes, _stream(stream)))
+        sizes = list(self.sizes)
+        if r < 0 and all(s >= 0 for s in sizes):
+            raise LcError(-r)
+        return sizes
+
+
 def lc_encode_batch(ws, w_refs, nbits, outs, stream=None):
     """One table per tensor, all tensors in one call. Returns the list of blob sizes (negative: -(status) of that
     tensor); raises LcError only for errors that concern the whole call."""
-    count = len(ws)
-    assert count == len(w_refs) == len(outs) and count >= 1
-    wp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in ws])
-    rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
-    op = (_vp * count)(*[t.data_ptr() for t in outs])
-    ns = (_u64 * count)(*[t.numel() for t in ws])
-    for w, r, o in zip(ws, w_refs, outs):
-        assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and r.is_cuda and r.dtype == torch.float32
-        assert r.is_contiguous() and r.numel() == w.numel() and o.is_cuda and o.dtype == torch.uint8 and o.is_contiguous()
-        assert o.numel() >= lc_encode_bound(w.numel(), nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
-    sizes = (_i64 * count)()
-    r = int(_lib.lc_encode_batch(wp, rp, ns, count, nbits, op, sizes, _stream(stream)))
-    if r < 0 and all(s >= 0 for s in sizes):
-        raise LcError(-r)
-    return [int(s) for s in sizes]
+    return EncodeBatch(ws, w_refs, nbits, outs).run(stream)
 
 
 def lc_blob_sizes(header_bytes):
@@ -176,24 +190,34 @@ def lc_blob_sizes(header_bytes):
     return dict(E=int(bits[0]), EP=int(bits[1]), EPH=int(bits[2]))
 
 
+class DecodeBatch:
+    """The marshalled arguments of one lc_decode_batch call, kept for the next call on the same tensors (see EncodeBatch)."""
+
+    def __init__(self, blobs, w_refs):
+        count = len(blobs)
+        assert count == len(w_refs) and count >= 1
+        for b, r in zip(blobs, w_refs):
+            assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
+            assert r.is_cuda and r.dtype == torch.float32 and r.is_contiguous()
+        self.keep = (list(blobs), list(w_refs))
+        self.count = count
+        self.bp = (_vp * count)(*[t.data_ptr() for t in blobs])
+        self.rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
+        self.ns = (_u64 * count)(*[t.numel() for t in w_refs])
+        self.sizes = (_i64 * count)()
+
+    def run(self, stream=None):
+        r = int(_lib.lc_decode_batch(self.bp, self.rp, self.ns, self.count, self.sizes, _stream(stream)))
+        sizes = list(self.sizes)
+        if r < 0 and all(s >= 0 for s in sizes):
+            raise LcError(-r)
+        return sizes
+
+
 def lc_decode_batch(blobs, w_refs, stream=None):
     """Restores every tensor from its blob in one call. Returns the list of bytes consumed (negative: -(status))."""
-    count = len(blobs)
-    assert count == len(w_refs) and count >= 1
-    for b, r in zip(blobs, w_refs):
-        assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
-        assert r.is_cuda and r.dtype == torch.float32 and r.is_contiguous()
-    bp = (_vp * count)(*[t.data_ptr() for t in blobs])
-    rp = (_vp * count)(*[t.data_ptr() if t.numel() else None for t in w_refs])
-    ns = (_u64 * count)(*[t.numel() for t in w_refs])
-    sizes = (_i64 * count)()
-    r = int(_lib.lc_decode_batch(bp, rp, ns, count, sizes, _stream(stream)))
-    if r < 0 and all(s >= 0 for s in sizes):
-        raise LcError(-r)
-    return [int(s) for s in sizes]
+    return DecodeBatch(blobs, w_refs).run(stream)
 
-
-CACHE_BYTES = 256
 
 
 def new_cache(device="cuda"):
