@@ -5,6 +5,7 @@
 // lc_decode_many:   k_dec_check (all blobs) -> k_decode_fused<T> / k_decode_many per sweep
 // lc_decode_batch:  kb_dec_setup -> kb_dec_tables -> kb_dec_chunks -> kb_decode -> kb_dec_report
 #include "lc_device.h"
+#include <type_traits>
 
 namespace lc {
 
@@ -205,16 +206,13 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     const u32 wi0 = br.wi, avail0 = br.avail;
     const u32 shr1 = 64 - P1, shr2 = 64 - P2;
     const u64 base = (u64)c * kChunk;
-#pragma unroll 4
-    for (u32 r = 0; r < kR; ++r) {
-        const u64 idx = base + (u64)r * kRowElems + lane * kV;
-        if (!FAST && idx >= n) break;
-        float x[4];
-        load_row<FAST, DT>(w_ref, idx, n, x);
+    // one row of the chunk; WHOLE: all 4 elements of every lane exist and the row can be stored as vectors
+    auto row = [&](auto whole, u64 idx, float (&x)[4]) {
+        constexpr bool WHOLE = decltype(whole)::value;
         u32 smin = K;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            if (FAST || idx + v < n) {
+            if (WHOLE || idx + v < n) {
                 u32 e = L.lut1[(u32)(br.win >> shr1)];
                 if (LV2 && e == 0xFF) {
                     e = L.lut2[(u32)(br.win >> shr2)];
@@ -227,11 +225,44 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
             }
             if ((v & 1) && br.avail <= 32) br.refill();
         }
-        if (FAST) {
+        if (WHOLE) {
             if (__any(smin < K)) store4<DT>(w_ref, idx, x);
         } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v) if (idx + v < n) store_one<DT>(w_ref, idx + v, x[v]);
+        }
+    };
+    typedef std::integral_constant<bool, true> yes;
+    typedef std::integral_constant<bool, false> no;
+    if (FAST) {
+#pragma unroll 4
+        for (u32 r = 0; r < kR; ++r) {
+            const u64 idx = base + (u64)r * kRowElems + lane * kV;
+            float x[4];
+            load_row<true, DT>(w_ref, idx, n, x);
+            row(yes(), idx, x);
+        }
+    } else {
+        // A ragged or unaligned chunk (the vector's last chunk is one wavefront's work from start to end, so its
+        // memory round trips count): whole rows of an aligned array as in a full chunk, four fetched before the
+        // first is decoded; the rest with guarded element accesses.
+        const bool vec = (reinterpret_cast<uintptr_t>(w_ref) & (4 * elem_bytes<DT>() - 1)) == 0;
+        u32 r = 0;
+        if (vec) {
+            constexpr u32 RB = 4;
+            for (; r + RB <= kR && base + (u64)(r + RB) * kRowElems <= n; r += RB) {
+                float x[RB][4];
+#pragma unroll
+                for (u32 k = 0; k < RB; ++k) load_row<true, DT>(w_ref, base + (u64)(r + k) * kRowElems + lane * kV, n, x[k]);
+#pragma unroll
+                for (u32 k = 0; k < RB; ++k) row(yes(), base + (u64)(r + k) * kRowElems + lane * kV, x[k]);
+            }
+        }
+        for (; r < kR && base + (u64)r * kRowElems < n; ++r) {
+            const u64 idx = base + (u64)r * kRowElems + lane * kV;
+            float x[4];
+            load_row<false, DT>(w_ref, idx, n, x);
+            row(no(), idx, x);
         }
     }
     const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;

@@ -409,7 +409,10 @@ __device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u3
     }
 }
 
-// Any size, any alignment: guarded scalar loads, one symbol per look-up.
+// Any size, any alignment: guarded element loads, one symbol per look-up.  The rows are loaded four at a time,
+// so a ragged last chunk costs a quarter of the memory round trips (it is one wavefront's work from start to end).
+constexpr int kPlainRows = 4;
+
 template <bool HIST, bool PACK, int DT>
 __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& L) {
     const u32 lane = lane_id();
@@ -419,24 +422,33 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
     const u32 mm = lane & (kMmCopies - 1);
     u64 acc = 0;
     u32 nb = 0, nw = 0;
-    for (u32 r = 0; r < kR; ++r) {
-        const u64 idx = base + (u64)r * kRowElems + lane * kV;
+    for (u32 r0 = 0; r0 < kR && base + (u64)r0 * kRowElems < n; r0 += kPlainRows) {
+        float xa[kPlainRows][4], xb[kPlainRows][4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            if (idx + v < n) {
-                const u32 u = delta_bits(load_one<DT>(w, idx + v), load_one<DT>(w_ref, idx + v));
-                if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
-                if (!PACK) continue;
-                const u32 sy = L.sym8[u >> 23] >> 3;
-                const u32 cl = L.codelen[sy];
-                atomicMin(&L.mn[sy * kMmCopies + mm], u);
-                atomicMax(&L.mx[sy * kMmCopies + mm], u);
-                acc = (acc << (cl & 31)) | (cl >> 5);
-                nb += cl & 31;
-            }
-            if (PACK && (v & 1) && nb >= 32) {
-                slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
-                ++nw; nb -= 32;
+        for (int k = 0; k < kPlainRows; ++k) {
+            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
+            load_row<false, DT>(w, idx, n, xa[k]); load_row<false, DT>(w_ref, idx, n, xb[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < kPlainRows; ++k) {
+            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (idx + v < n) {
+                    const u32 u = delta_bits(xa[k][v], xb[k][v]);
+                    if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+                    if (!PACK) continue;
+                    const u32 sy = L.sym8[u >> 23] >> 3;
+                    const u32 cl = L.codelen[sy];
+                    atomicMin(&L.mn[sy * kMmCopies + mm], u);
+                    atomicMax(&L.mx[sy * kMmCopies + mm], u);
+                    acc = (acc << (cl & 31)) | (cl >> 5);
+                    nb += cl & 31;
+                }
+                if (PACK && (v & 1) && nb >= 32) {
+                    slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
+                    ++nw; nb -= 32;
+                }
             }
         }
     }

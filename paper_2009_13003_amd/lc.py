@@ -219,6 +219,8 @@ def lc_decode_batch(blobs, w_refs, stream=None):
     return DecodeBatch(blobs, w_refs).run(stream)
 
 
+CACHE_BYTES = 256
+
 
 def new_cache(device="cuda"):
     """An empty code table cache for lc_encode_cached."""

@@ -33,6 +33,22 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_binding_has_every_name_it_uses_and_every_entry_point():
+    """The Python binding imports without a GPU, carries a function for every call of the header (lc_batch_workspace_bytes
+    and lc_profile_name are used inside it), and refers to no module-level name that is not there."""
+    import ast
+    import builtins
+    from paper_2009_13003_amd import lc
+    for name in declared_functions():
+        assert hasattr(lc, name) or name in ("lc_batch_workspace_bytes", "lc_profile_name"), name
+    tree = ast.parse(open(lc.__file__).read())
+    used = {node.id for node in ast.walk(tree) if isinstance(node, ast.Name) and isinstance(node.ctx, ast.Load)}
+    local = {a.arg for node in ast.walk(tree) if isinstance(node, ast.arguments) for a in node.args + node.kwonlyargs}
+    local |= {node.id for node in ast.walk(tree) if isinstance(node, ast.Name) and isinstance(node.ctx, ast.Store)}
+    missing = [u for u in used if not hasattr(lc, u) and not hasattr(builtins, u) and u not in local]
+    assert not missing, missing
+
+
 def test_host_only_entry_points(lib):
     lib.lc_encode_bound.restype = ctypes.c_size_t
     lib.lc_encode_bound.argtypes = [ctypes.c_uint64, ctypes.c_int]
