@@ -9,7 +9,7 @@
  *
  * What follows the paper, and where:
  *   delta                 Algorithm 1 line 4; Section 3, component C1
- *   (sign, exponent) buckets, <= 2^9 of them for fp32
+ *   (sign, exponent) buckets, <= 2^9 of them for fp32, <= 2^12 for fp64 (second part of the file)
  *                         Section 3.1.1 "Exponent-based Quantization" + footnote
  *   bucket representative = average of the bucket's max and min
  *                         Section 3.1.1 "Exponent-based Quantization"
@@ -488,8 +488,8 @@ int64_t lco_decode(const uint8_t* blob, uint64_t blob_bytes, float* wref, uint64
 
 /*
  * Size accounting of Section 3.1.1 / Section 4.3, in bits:
- *   acct[0] = n*ceil(log2 k) + 32*k        exponent quantization alone (E), k = k_E
- *   acct[1] = n*x + 32*2^x                 after x-bit promotion (E+P)
+ *   acct[0] = n*ceil(log2 k) + b*k         exponent quantization alone (E), k = k_E, b = 32 (64 for binary64 blobs)
+ *   acct[1] = n*x + b*2^x                  after x-bit promotion (E+P)
  *   acct[2] = 8 * blob bytes               after Huffman, all overheads included (E+P+H)
  *   acct[3] = Shannon entropy of the symbol counts, bits per element
  *   acct[4] = mean code length, bits per element (sum cnt*len / n)
@@ -498,8 +498,9 @@ int lco_accounting(const uint8_t* blob, double acct[5]) {
     if (memcmp(blob, "LCB1", 4) != 0) return LCO_BAD_BLOB;
     uint64_t n = get64(blob + 8); uint32_t x = get32(blob + 16), K = get32(blob + 20), k = get32(blob + 52);
     uint32_t lg = 0; while ((1u << lg) < k) ++lg;
-    acct[0] = (double)n * lg + 32.0 * k;
-    acct[1] = (double)n * x + 32.0 * (double)(1u << x);
+    double b = get32(blob + 60) == 3 ? 64.0 : 32.0;     /* bits of a stored bucket value (Section 3.1.1, rate formula) */
+    acct[0] = (double)n * lg + b * k;
+    acct[1] = (double)n * x + b * (double)(1u << x);
     acct[2] = 8.0 * (double)get64(blob + 40);
     double H = 0, L = 0;
     for (uint32_t j = 0; j <= K; ++j) {
@@ -516,4 +517,247 @@ int lco_accounting(const uint8_t* blob, double acct[5]) {
 uint64_t lco_size_exponent_only(uint64_t n, uint32_t k, uint32_t b) {
     uint32_t lg = 0; while ((1u << lg) < k) ++lg;
     return n * lg + (uint64_t)k * b;
+}
+
+/* =====================================================================================
+ * Double-precision parameters.  Section 3.1.1 (footnote on the bucket count): the same
+ * method with the sign and the 11 exponent bits of binary64, at most 2^12 buckets.
+ * Everything is as above with 64-bit patterns: delta = fl64(w - wref), bucket = top 12
+ * bits, biased exponent 0 is the zero class, 2047 is an error, mantissas have 52 bits,
+ * the restore is one binary64 addition.  The blob says so at header offset 60 (3); a
+ * slot holds the low 32 bits of its representative, the high 32 bits are at 320 + 4 j.
+ * ===================================================================================== */
+#define LCO_NB64 4096
+
+static uint64_t d2u(double d) { uint64_t u; memcpy(&u, &d, 8); return u; }
+static double u2d(uint64_t u) { double d; memcpy(&d, &u, 8); return d; }
+
+static double delta_of64(double w, double wref) {
+    volatile double d = w - wref;
+    return d;
+}
+
+int lco_bucket_stats64(const double* w, const double* wref, uint64_t n,
+                       uint64_t count[LCO_NB64], uint64_t mmin[LCO_NB64], uint64_t mmax[LCO_NB64]) {
+    for (int b = 0; b < LCO_NB64; ++b) { count[b] = 0; mmin[b] = 0xFFFFFFFFFFFFFull; mmax[b] = 0; }
+    int bad = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t u = d2u(delta_of64(w[i], wref[i]));
+        uint32_t b = (uint32_t)(u >> 52), E = b & 2047u;
+        uint64_t m = u & 0xFFFFFFFFFFFFFull;
+        if (E == 2047u) bad = 1;
+        count[b] += 1;
+        if (E != 0u) {
+            if (m < mmin[b]) mmin[b] = m;
+            if (m > mmax[b]) mmax[b] = m;
+        }
+    }
+    return bad ? LCO_NONFINITE : LCO_OK;
+}
+
+/* Priority promotion over the 2 x 2046 normal buckets, as lco_promote. */
+int lco_promote64(const uint64_t count[LCO_NB64], int nbits, uint16_t kept[LCO_SLOTS],
+                  uint8_t sym_of_bucket[LCO_NB64]) {
+    int kmax = (1 << nbits) - 1, K = 0;
+    for (int i = 0; i < LCO_SLOTS; ++i) kept[i] = 0xFFFFu;
+    for (int E = 2046; E >= 1 && K < kmax; --E) {
+        for (int s = 0; s <= 1 && K < kmax; ++s) {
+            int b = (s << 11) | E;
+            if (count[b] > 0) kept[K++] = (uint16_t)b;
+        }
+    }
+    for (int b = 0; b < LCO_NB64; ++b) sym_of_bucket[b] = (uint8_t)K;
+    for (int j = 0; j < K; ++j) sym_of_bucket[kept[j]] = (uint8_t)j;
+    return K;
+}
+
+/*
+ * Average of the bucket's maximum and minimum.  Two binary64 values of one binade add
+ * up to at most 54 significant bits: exact in the x87 extended format (64 bits), as is
+ * the halving; the one rounding is the conversion back to binary64 (nearest even).
+ */
+uint64_t lco_representative64(uint32_t bucket, uint64_t mmin, uint64_t mmax) {
+    _Static_assert(sizeof(long double) >= 10 && __LDBL_MANT_DIG__ >= 64, "needs a 64-bit significand");
+    long double lo = (long double)u2d(((uint64_t)bucket << 52) | mmin);
+    long double hi = (long double)u2d(((uint64_t)bucket << 52) | mmax);
+    volatile double rep = (double)((lo + hi) * 0.5L);
+    return d2u(rep);
+}
+
+typedef struct {
+    int K;
+    uint16_t kept[LCO_SLOTS];
+    uint64_t rep_bits[LCO_SLOTS + 1];
+    uint64_t cnt[LCO_SLOTS + 1];
+    uint8_t  len[LCO_SLOTS + 1];
+    uint16_t code[LCO_SLOTS + 1];
+    uint8_t  sym_of_bucket[LCO_NB64];
+    uint32_t k_E;
+} lco_model64;
+
+static uint64_t s_count64[LCO_NB64], s_mmin64[LCO_NB64], s_mmax64[LCO_NB64];   /* (single-threaded by design) */
+
+static int build_model64(const double* w, const double* wref, uint64_t n, int nbits, lco_model64* M) {
+    memset(M, 0, sizeof *M);
+    int st = lco_bucket_stats64(w, wref, n, s_count64, s_mmin64, s_mmax64);
+    if (st != LCO_OK) return st;
+    M->K = lco_promote64(s_count64, nbits, M->kept, M->sym_of_bucket);
+    uint64_t kept_total = 0;
+    for (int j = 0; j < M->K; ++j) {
+        M->cnt[j] = s_count64[M->kept[j]];
+        kept_total += M->cnt[j];
+        M->rep_bits[j] = lco_representative64(M->kept[j], s_mmin64[M->kept[j]], s_mmax64[M->kept[j]]);
+    }
+    M->cnt[M->K] = n - kept_total;
+    M->rep_bits[M->K] = 0;
+    lco_huffman_lengths(M->cnt, M->K + 1, M->len);
+    lco_canonical_codes(M->len, M->K + 1, M->code);
+    uint32_t k = 0; uint64_t zero_class = 0;
+    for (int b = 0; b < LCO_NB64; ++b) {
+        if ((b & 2047) == 0) zero_class += s_count64[b];
+        else if (s_count64[b] > 0) ++k;
+    }
+    M->k_E = k + (zero_class > 0 ? 1u : 0u);
+    return LCO_OK;
+}
+
+/* Symbols and dequantized deltas, element by element (as lco_quantize). */
+int lco_quantize64(const double* w, const double* wref, uint64_t n, int nbits,
+                   uint8_t* sym, double* dq, uint32_t info[2]) {
+    if (nbits < 1 || nbits > 4) return LCO_BADARG;
+    lco_model64 M; int st = build_model64(w, wref, n, nbits, &M);
+    if (st != LCO_OK) return st;
+    for (uint64_t i = 0; i < n; ++i) {
+        uint32_t b = (uint32_t)(d2u(delta_of64(w[i], wref[i])) >> 52);
+        uint8_t s = M.sym_of_bucket[b];
+        sym[i] = s; dq[i] = u2d(M.rep_bits[s]);
+    }
+    info[0] = (uint32_t)M.K; info[1] = M.k_E;
+    return LCO_OK;
+}
+
+static void write_header64(uint8_t* out, uint64_t n, int nbits, const lco_model64* M,
+                           uint64_t nchunks, uint64_t total, uint32_t status) {
+    memset(out, 0, LCO_HEADER);
+    out[0] = 'L'; out[1] = 'C'; out[2] = 'B'; out[3] = '1';
+    put16(out + 4, 1); put16(out + 6, LCO_HEADER);
+    put64(out + 8, n); put32(out + 16, (uint32_t)nbits);
+    put32(out + 24, LCO_W); put32(out + 28, LCO_V); put32(out + 32, LCO_R);
+    put64(out + 40, total); put32(out + 48, status);
+    put32(out + 60, 3);                                  /* element type: binary64 */
+    if (!M) return;
+    put32(out + 20, (uint32_t)M->K); put32(out + 36, (uint32_t)nchunks);
+    put32(out + 52, M->k_E);
+    uint32_t maxlen = 0;
+    for (int j = 0; j <= M->K; ++j) {
+        uint8_t* s = out + 64 + 16 * j;
+        put16(s, j < M->K ? M->kept[j] : 0xFFFFu);
+        s[2] = M->len[j]; s[3] = 0;
+        put32(s + 4, (uint32_t)M->rep_bits[j]); put64(s + 8, M->cnt[j]);
+        put32(out + 320 + 4 * j, (uint32_t)(M->rep_bits[j] >> 32));
+        if (M->len[j] > maxlen) maxlen = M->len[j];
+    }
+    put32(out + 56, maxlen);
+}
+
+/* Algorithm 1 lines 4-6 for binary64 parameters; element order and records as in write_blob. */
+int64_t lco_encode64(const double* w, const double* wref, uint64_t n, int nbits,
+                     uint8_t* out, uint64_t cap) {
+    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || (n && (!w || !wref))) return -LCO_BADARG;
+    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
+    lco_model64 M; int st = build_model64(w, wref, n, nbits, &M);
+    if (st == LCO_NONFINITE) { write_header64(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+    uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
+    memset(out + LCO_HEADER, 0, lco_encode_bound(n, nbits) - LCO_HEADER);
+    uint64_t word_off = 0;
+    for (uint64_t c = 0; c < nchunks; ++c) {
+        put32(out + LCO_HEADER + 4 * c, (uint32_t)word_off);
+        uint8_t* rec = out + area + 4 * word_off;
+        uint8_t* payload = rec + 2 * LCO_W;
+        uint64_t p = 0;
+        for (uint32_t l = 0; l < LCO_W; ++l) {
+            uint64_t start = p;
+            for (uint32_t r = 0; r < LCO_R; ++r) for (uint32_t v = 0; v < LCO_V; ++v) {
+                uint64_t i = c * LCO_C + (uint64_t)r * (LCO_W * LCO_V) + l * LCO_V + v;
+                if (i >= n) continue;
+                uint32_t b = (uint32_t)(d2u(delta_of64(w[i], wref[i])) >> 52);
+                uint32_t s = M.sym_of_bucket[b];
+                if ((uint64_t)(payload - out) + 4 * ((p + M.len[s] + 31) / 32) > cap) return -LCO_OUT_TOO_SMALL;
+                for (int k = M.len[s] - 1; k >= 0; --k) put_bit(payload, p++, (M.code[s] >> k) & 1u);
+            }
+            put16(rec + 2 * l, (uint32_t)(p - start));
+        }
+        word_off += (2 * LCO_W) / 4 + (p + 31) / 32;
+    }
+    put32(out + LCO_HEADER + 4 * nchunks, (uint32_t)word_off);
+    uint64_t total = area + 4 * word_off;
+    write_header64(out, n, nbits, &M, nchunks, total, LCO_OK);
+    return (int64_t)total;
+}
+
+/* Algorithm 1 line 7 for binary64 parameters; checks as in lco_decode. */
+int64_t lco_decode64(const uint8_t* blob, uint64_t blob_bytes, double* wref, uint64_t n) {
+    if (!blob || blob_bytes < LCO_HEADER) return -LCO_BAD_BLOB;
+    if (memcmp(blob, "LCB1", 4) != 0 || get16(blob + 4) != 1 || get16(blob + 6) != LCO_HEADER) return -LCO_BAD_BLOB;
+    if (get32(blob + 48) != LCO_OK) return -LCO_BAD_BLOB;
+    uint64_t hn = get64(blob + 8); uint32_t nbits = get32(blob + 16), K = get32(blob + 20);
+    if (hn != n) return -LCO_BADARG;
+    if (get32(blob + 60) != 3) return -LCO_BADARG;
+    if (nbits < 1 || nbits > 4 || K > (1u << nbits) - 1) return -LCO_BAD_BLOB;
+    if (get32(blob + 24) != LCO_W || get32(blob + 28) != LCO_V || get32(blob + 32) != LCO_R) return -LCO_BAD_BLOB;
+    uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
+    if (get32(blob + 36) != nchunks) return -LCO_BAD_BLOB;
+    uint64_t total = get64(blob + 40);
+    if (total > blob_bytes || total < area) return -LCO_BAD_BLOB;
+    uint8_t len[LCO_SLOTS + 1]; uint16_t code[LCO_SLOTS + 1]; uint64_t rep[LCO_SLOTS + 1];
+    uint64_t cnt_sum = 0; uint32_t kraft = 0; int active = 0;
+    memset(len, 0, sizeof len);
+    for (uint32_t j = 0; j <= K; ++j) {
+        const uint8_t* s = blob + 64 + 16 * j;
+        len[j] = s[2]; rep[j] = (uint64_t)get32(s + 4) | ((uint64_t)get32(blob + 320 + 4 * j) << 32);
+        uint64_t c = get64(s + 8); cnt_sum += c;
+        if ((c > 0) != (len[j] > 0) || len[j] > 15) return -LCO_BAD_BLOB;
+        if (j < K && (get16(s) >= 4096u || (get16(s) & 2047u) == 0 || (get16(s) & 2047u) == 2047u)) return -LCO_BAD_BLOB;
+        if (j < K && (rep[j] >> 52) != get16(s)) return -LCO_BAD_BLOB;
+        if (len[j]) { kraft += 1u << (15 - len[j]); ++active; }
+    }
+    if (rep[K] != 0 || cnt_sum != n) return -LCO_BAD_BLOB;
+    if (active >= 2 && kraft != (1u << 15)) return -LCO_BAD_BLOB;
+    if (active == 1 && kraft != (1u << 14)) return -LCO_BAD_BLOB;
+    lco_canonical_codes(len, (int)K + 1, code);
+    uint64_t expect = 0;
+    for (uint64_t c = 0; c < nchunks; ++c) {
+        if (get32(blob + LCO_HEADER + 4 * c) != expect) return -LCO_BAD_BLOB;
+        if (area + 4 * expect + 2 * LCO_W > total) return -LCO_BAD_BLOB;
+        const uint8_t* rec = blob + area + 4 * expect;
+        uint64_t bits = 0;
+        for (uint32_t l = 0; l < LCO_W; ++l) bits += get16(rec + 2 * l);
+        expect += (2 * LCO_W) / 4 + (bits + 31) / 32;
+        if (area + 4 * expect > total) return -LCO_BAD_BLOB;
+    }
+    if (get32(blob + LCO_HEADER + 4 * nchunks) != expect || area + 4 * expect != total) return -LCO_BAD_BLOB;
+    for (uint64_t c = 0; c < nchunks; ++c) {
+        const uint8_t* rec = blob + area + 4 * (uint64_t)get32(blob + LCO_HEADER + 4 * c);
+        const uint8_t* payload = rec + 2 * LCO_W;
+        uint64_t p = 0;
+        for (uint32_t l = 0; l < LCO_W; ++l) {
+            uint64_t end = p + get16(rec + 2 * l);
+            for (uint32_t r = 0; r < LCO_R; ++r) for (uint32_t v = 0; v < LCO_V; ++v) {
+                uint64_t i = c * LCO_C + (uint64_t)r * (LCO_W * LCO_V) + l * LCO_V + v;
+                if (i >= n) continue;
+                uint32_t acc = 0; int L = 0, s = -1;
+                while (s < 0) {
+                    if (p >= end || L >= 15) return -LCO_BAD_BLOB;
+                    acc = (acc << 1) | get_bit(payload, p++); ++L;
+                    for (uint32_t j = 0; j <= K; ++j) if (len[j] == L && code[j] == acc) { s = (int)j; break; }
+                }
+                if ((uint32_t)s < K) {
+                    volatile double sum = wref[i] + u2d(rep[s]);   /* one binary64 add */
+                    wref[i] = sum;
+                }
+            }
+            if (p != end) return -LCO_BAD_BLOB;
+        }
+    }
+    return (int64_t)total;
 }

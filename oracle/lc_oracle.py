@@ -57,6 +57,18 @@ def lib():
         L.lco_accounting.argtypes = [vp, vp]
         L.lco_size_exponent_only.restype = u64
         L.lco_size_exponent_only.argtypes = [u64, u32, u32]
+        L.lco_bucket_stats64.restype = i32
+        L.lco_bucket_stats64.argtypes = [vp, vp, u64, vp, vp, vp]
+        L.lco_promote64.restype = i32
+        L.lco_promote64.argtypes = [vp, i32, vp, vp]
+        L.lco_representative64.restype = u64
+        L.lco_representative64.argtypes = [u32, u64, u64]
+        L.lco_quantize64.restype = i32
+        L.lco_quantize64.argtypes = [vp, vp, u64, i32, vp, vp, vp]
+        L.lco_encode64.restype = i64
+        L.lco_encode64.argtypes = [vp, vp, u64, i32, vp, u64]
+        L.lco_decode64.restype = i64
+        L.lco_decode64.argtypes = [vp, u64, vp, u64]
         _lib = L
     return _lib
 
@@ -171,10 +183,65 @@ def decode(blob, w_ref):
     return int(r)
 
 
+# ---- binary64 parameters (Section 3.1.1, footnote on the bucket count: sign and 11 exponent bits, at most 2^12 buckets)
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def bucket_stats64(w, w_ref):
+    w, w_ref = _f64(w), _f64(w_ref)
+    count = np.zeros(4096, np.uint64); mmin = np.zeros(4096, np.uint64); mmax = np.zeros(4096, np.uint64)
+    st = lib().lco_bucket_stats64(_p(w), _p(w_ref), w.size, _p(count), _p(mmin), _p(mmax))
+    return st, count, mmin, mmax
+
+
+def promote64(count, nbits):
+    count = np.ascontiguousarray(count, dtype=np.uint64)
+    kept = np.zeros(16, np.uint16); sym = np.zeros(4096, np.uint8)
+    K = lib().lco_promote64(_p(count), nbits, _p(kept), _p(sym))
+    return K, kept[:K].copy(), sym
+
+
+def representative64(bucket, mmin, mmax):
+    return int(lib().lco_representative64(int(bucket), int(mmin), int(mmax)))
+
+
+def quantize64(w, w_ref, nbits):
+    w, w_ref = _f64(w), _f64(w_ref)
+    sym = np.zeros(w.size, np.uint8); dq = np.zeros(w.size, np.float64); info = np.zeros(2, np.uint32)
+    st = lib().lco_quantize64(_p(w), _p(w_ref), w.size, nbits, _p(sym), _p(dq), _p(info))
+    if st != OK:
+        raise OracleError(st)
+    return sym, dq, int(info[0]), int(info[1])
+
+
+def encode64(w, w_ref, nbits):
+    w, w_ref = _f64(w), _f64(w_ref)
+    assert w.size == w_ref.size
+    cap = encode_bound(w.size, min(max(nbits, 1), 4))
+    out = np.zeros(max(cap, 1), np.uint8)
+    r = lib().lco_encode64(_p(w), _p(w_ref), w.size, nbits, _p(out), cap)
+    if r < 0:
+        err = OracleError(-r)
+        err.header = out[:512].copy()
+        raise err
+    return out[:r].copy()
+
+
+def decode64(blob, w_ref):
+    """Updates w_ref (float64 contiguous numpy array) in place; returns bytes consumed."""
+    assert w_ref.dtype == np.float64 and w_ref.flags.c_contiguous
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    r = lib().lco_decode64(_p(blob), blob.size, _p(w_ref), w_ref.size)
+    if r < 0:
+        raise OracleError(-r)
+    return int(r)
+
+
 # ---- 16-bit parameters.  The method works on the fp32 delta (Algorithm 1 line 4), so parameters stored as bf16 or
 # fp16 are widened exactly to fp32, coded as fp32, and the restored value fl32(w_ref + rep) is rounded once, to nearest
 # even, back to the storage type.  The blob says which type it restores (header offset 60: 0 fp32, 1 bf16, 2 fp16).
-DT_F32, DT_BF16, DT_F16 = 0, 1, 2
+DT_F32, DT_BF16, DT_F16, DT_F64 = 0, 1, 2, 3
 
 
 def widen(a, dtype):
@@ -200,6 +267,8 @@ def narrow(x, dtype):
 
 
 def encode_t(w, w_ref, nbits, dtype):
+    if dtype == DT_F64:
+        return encode64(w, w_ref, nbits)
     blob = encode(widen(w, dtype), widen(w_ref, dtype), nbits)
     blob[60:64] = np.frombuffer(np.uint32(dtype).tobytes(), np.uint8)
     return blob
@@ -208,6 +277,8 @@ def encode_t(w, w_ref, nbits, dtype):
 def decode_t(blob, w_ref, dtype):
     """Updates w_ref (storage type array) in place; returns bytes consumed."""
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    if dtype == DT_F64:
+        return decode64(blob, w_ref)
     if blob.size >= 64 and int(np.frombuffer(blob[60:64].tobytes(), np.uint32)[0]) != dtype:
         raise OracleError(1)
     as_f32 = blob.copy()

@@ -21,9 +21,17 @@ def parse_header(blob):
     for j in range(16):
         bucket, ln, pad, rep, cnt = struct.unpack_from("<HBBIQ", b, 64 + 16 * j)
         slots.append(dict(bucket=bucket, len=ln, pad=pad, rep_bits=rep, cnt=cnt))
+    dtype, = struct.unpack_from("<I", b, 60)
+    rep_hi = list(struct.unpack_from("<16I", b, 320))
+    if dtype == 3:                      # binary64 parameters: 64-bit representatives, high halves at 320 + 4 j
+        for j in range(16):
+            slots[j]["rep_bits"] |= rep_hi[j] << 32
+        reserved = b[384:512]
+    else:
+        reserved = b[320:512]
     return dict(magic=magic, version=version, header_bytes=hbytes, n=n, nbits=nbits, K=K, W=w, V=v, R=r,
                 num_chunks=nchunks, total_bytes=total, status=status, k_E=k_e, max_len=maxlen, slots=slots,
-                reserved=b[60:64] + b[320:512])
+                dtype=dtype, reserved=reserved)
 
 
 def canonical(lens):

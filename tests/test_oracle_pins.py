@@ -359,7 +359,7 @@ def test_blob_structure_and_round_trip(n):
     sym, dq, K, k_E = orc.quantize(w, w_ref, nbits)
     assert h["magic"] == b"LCB1" and h["version"] == 1 and h["header_bytes"] == 512
     assert (h["n"], h["nbits"], h["K"], h["W"], h["V"], h["R"]) == (n, nbits, K, 64, 4, 64)
-    assert h["status"] == 0 and h["k_E"] == k_E and set(h["reserved"]) <= {0}
+    assert h["status"] == 0 and h["k_E"] == k_E and set(h["reserved"]) <= {0} and h["dtype"] == 0
     assert np.array_equal(sym_r, sym)
     # symbol table: counts, representatives, bucket ids, unused slots zero, zero symbol last
     for j in range(16):
