@@ -45,12 +45,15 @@
  *    24  u32 W = 64           28  u32 V = 4            32  u32 R = 64
  *    36  u32 num_chunks       40  u64 total_bytes      48  u32 status (0, or 2 = non-finite delta)
  *    52  u32 k_E  non-empty buckets before promotion (the zero class counts once)
- *    56  u32 max_len  longest code length              60  u32 element type restored (0 fp32, 1 bf16, 2 fp16)
+ *    56  u32 max_len  longest code length              60  u32 element type restored (0 fp32, 1 bf16, 2 fp16, 3 fp64)
  *    64  16 symbol slots of 16 bytes: { u16 bucket_id, u8 len, u8 0, u32 rep_bits, u64 count }
  *        slot j < K: bucket_id = (sign << 8) | biased exponent; rep_bits = the fp32
  *        representative; slot K: bucket_id 0xFFFF, rep_bits 0 (the merged bucket,
  *        "stored last", Section 4.4); slots > K are zero.  len = 0 iff count = 0.
- *   320  192 zero bytes
+ *   320  192 zero bytes; in an fp64 blob (element type 3) the first 64 are u32 rep_hi[16]: the method then runs
+ *        on the binary64 delta (Section 3.1.1, footnote: sign and 11 exponent bits, at most 2^12 buckets),
+ *        bucket_id = (sign << 11) | biased exponent, and slot j's representative is the binary64 pattern
+ *        (rep_hi[j] << 32) | rep_bits
  *
  *   Symbols: j < K is the j-th kept bucket in priority order (larger exponent first,
  *   + before - at equal exponent).  Biased exponent 0 (zeros, subnormals: Figure 2
@@ -136,12 +139,14 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
  * 16-bit values are widened exactly to fp32, delta, buckets, representatives and codes are those of
  * lc_encode on the widened vectors, and the restore computes fl32(float(w_ref[i]) + representative) and
  * rounds it once, to nearest even, back to the storage type (elements of the merged bucket keep their
- * bits).  dtype: LC_F32 (then these are lc_encode / lc_decode), LC_BF16, LC_F16; w, w_ref: arrays of
+ * bits).  dtype: LC_F32 (then these are lc_encode / lc_decode), LC_BF16, LC_F16, LC_F64; w, w_ref: arrays of
  * that type, aligned to the element size (8-byte alignment of both takes the fast loads of 16-bit
- * types).  The blob records the element type at header offset 60 (0 for fp32 blobs) and restores only
+ * types, 16-byte alignment those of fp64).  LC_F64: the whole method in binary64 (Section 3.1.1, footnote on
+ * the bucket count): delta = fl64(w - w_ref), buckets by sign and the 11 exponent bits, representatives the
+ * exactly rounded binary64 midranges, restore by one binary64 addition.  The blob records the element type at header offset 60 (0 for fp32 blobs) and restores only
  * into that type (else LC_ERR_BADARG); otherwise arguments, results and errors as lc_encode / lc_decode.
  */
-enum lc_dtype { LC_F32 = 0, LC_BF16 = 1, LC_F16 = 2 };
+enum lc_dtype { LC_F32 = 0, LC_BF16 = 1, LC_F16 = 2, LC_F64 = 3 };
 lc_ssize lc_encode_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* stream);
 lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream);
 

@@ -177,8 +177,9 @@ namespace {
 lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, TableCache* cache,
                      int* used, void* stream, bool async) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
-    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
-    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
+    if (dtype == LC_F64 && (cache || async)) return -LC_ERR_BADARG;          // those entry points take fp32 only
+    const uintptr_t esize = dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2;
     if (n && (!w || !w_ref || misaligned(w, esize) || misaligned(w_ref, esize))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
@@ -216,7 +217,7 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     } else {
         Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, ds->tune, s);
     }
-    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
+    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, dtype, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
     { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
@@ -289,8 +290,8 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
 
 lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream) {
     if (!blob || misaligned(blob, 16) || n > LC_MAX_N) return -LC_ERR_BADARG;
-    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
-    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : 2))) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
     Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
@@ -538,13 +539,15 @@ int lc_blob_info(const void* host_header, uint64_t* n, int* nbits, uint64_t* tot
 int lc_blob_sizes(const void* host_header, uint64_t bits[3]) {
     if (!host_header || !bits) return LC_ERR_BADARG;
     const uint8_t* h = static_cast<const uint8_t*>(host_header);
-    uint16_t version; uint64_t n, total; uint32_t x, k;
+    uint16_t version; uint64_t n, total; uint32_t x, k, dtype;
     memcpy(&version, h + 4, 2); memcpy(&n, h + 8, 8); memcpy(&x, h + 16, 4); memcpy(&total, h + 40, 8); memcpy(&k, h + 52, 4);
-    if (memcmp(h, "LCB1", 4) != 0 || version != 1 || x < 1 || x > 4 || k > 512) return LC_ERR_BAD_BLOB;
+    memcpy(&dtype, h + 60, 4);
+    const uint64_t b = dtype == LC_F64 ? 64 : 32;             // bits of one stored bucket value (the delta's type)
+    if (memcmp(h, "LCB1", 4) != 0 || version != 1 || x < 1 || x > 4 || k > (dtype == LC_F64 ? 4096u : 512u)) return LC_ERR_BAD_BLOB;
     uint32_t lg = 0;
     while ((1u << lg) < k) ++lg;
-    bits[0] = n * lg + 32ull * k;               // index of one of k buckets per element + k representatives
-    bits[1] = n * x + 32ull * (1u << x);        // x bits per element + 2^x representatives
+    bits[0] = n * lg + b * k;                   // index of one of k buckets per element + k representatives
+    bits[1] = n * x + b * (1u << x);            // x bits per element + 2^x representatives
     bits[2] = 8 * total;                        // the blob as stored
     return LC_OK;
 }

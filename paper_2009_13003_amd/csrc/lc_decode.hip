@@ -22,12 +22,15 @@ namespace lc {
 __device__ __forceinline__ bool dec_symbol_table(const u32* hdr, u64 n, u32 nchunks, u64 area, u64 tw, DecSet& D,
                                                  u32* s_len, u32* s_code) {
     const u32 nbits = hdr[4], K = hdr[5];
+    // binary64 blobs (element type 3): 12-bit bucket ids, 64-bit representatives with the high halves at offset 320
+    const bool wide = hdr[15] == (u32)kF64;
+    const u32 emask = wide ? 2047u : 255u, nbuckets = 2 * (emask + 1);
     bool ok = nbits >= 1 && nbits <= 4 && K <= (1u << nbits) - 1 && hdr[6] == kW && hdr[7] == kV && hdr[8] == kR;
     if (nchunks == 0 && tw != 0) ok = false;
     u64 cnt_sum = 0; u32 kraft = 0, active = 0, max_len = 0;
     u32 per_len[17];
     for (int L = 0; L <= 16; ++L) per_len[L] = 0;
-    for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; }
+    for (u32 j = 0; j < kMaxSym; ++j) { s_len[j] = 0; s_code[j] = 0; D.info.rep_bits[j] = 0; D.info.rep_hi[j] = 0; }
     if (ok) {
         for (u32 j = 0; j <= K; ++j) {
             const u32 w0 = hdr[16 + 4 * j], rep = hdr[17 + 4 * j];
@@ -35,9 +38,11 @@ __device__ __forceinline__ bool dec_symbol_table(const u32* hdr, u64 n, u32 nchu
             const u32 bucket = w0 & 0xFFFFu, len = (w0 >> 16) & 0xFFu;
             cnt_sum += cn;
             if ((cn > 0) != (len > 0) || len > 15 || (w0 >> 24) != 0) { ok = false; continue; }
-            if (j < K && (bucket >= 512 || (bucket & 255) == 0 || (bucket & 255) == 255 || (rep >> 23) != bucket)) ok = false;
-            if (j == K && rep != 0) ok = false;
-            s_len[j] = len; D.info.rep_bits[j] = rep;
+            const u32 rep_hi = wide ? hdr[80 + j] : 0u;
+            if (j < K && (bucket >= nbuckets || (bucket & emask) == 0 || (bucket & emask) == emask)) ok = false;
+            if (j < K && (wide ? (rep_hi >> 20) : (rep >> 23)) != bucket) ok = false;
+            if (j == K && (rep | rep_hi) != 0) ok = false;
+            s_len[j] = len; D.info.rep_bits[j] = rep; D.info.rep_hi[j] = rep_hi;
             if (len) { kraft += 1u << (15 - len); ++active; per_len[len]++; if (len > max_len) max_len = len; }
         }
         if (cnt_sum != n) ok = false;
@@ -158,6 +163,11 @@ struct DecLdsT {
     float rep[kMaxSym];
     u32 len[kMaxSym], code[kMaxSym];
     uint4 payload[WAVES][kPayWords / 4 + 1];
+    double rep64[kMaxSym];            // binary64 blobs: the representatives (rep is not used then)
+    template <int DT> __device__ __forceinline__ typename Val<DT>::type rep_of(u32 sy) const {
+        if constexpr (DT == kF64) return rep64[sy];
+        else return rep[sy];
+    }
 };
 typedef DecLdsT<4> DecLds;
 
@@ -207,7 +217,8 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     const u32 shr1 = 64 - P1, shr2 = 64 - P2;
     const u64 base = (u64)c * kChunk;
     // one row of the chunk; WHOLE: all 4 elements of every lane exist and the row can be stored as vectors
-    auto row = [&](auto whole, u64 idx, float (&x)[4]) {
+    typedef typename Val<DT>::type val_t;
+    auto row = [&](auto whole, u64 idx, val_t (&x)[4]) {
         constexpr bool WHOLE = decltype(whole)::value;
         u32 smin = K;
 #pragma unroll
@@ -221,15 +232,15 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
                 const u32 len = e >> 4, sy = e & 15;
                 br.win <<= len; br.avail -= len;
                 smin = min(smin, sy);
-                x[v] = __fadd_rn(x[v], L.rep[sy]);
+                x[v] = add_rn(x[v], L.template rep_of<DT>(sy));
             }
             if ((v & 1) && br.avail <= 32) br.refill();
         }
         if (WHOLE) {
-            if (__any(smin < K)) store4<DT>(w_ref, idx, x);
+            if (__any(smin < K)) store4_v<DT>(w_ref, idx, x);
         } else {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) if (idx + v < n) store_one<DT>(w_ref, idx + v, x[v]);
+            for (int v = 0; v < 4; ++v) if (idx + v < n) store_one_v<DT>(w_ref, idx + v, x[v]);
         }
     };
     typedef std::integral_constant<bool, true> yes;
@@ -238,30 +249,30 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
 #pragma unroll 4
         for (u32 r = 0; r < kR; ++r) {
             const u64 idx = base + (u64)r * kRowElems + lane * kV;
-            float x[4];
-            load_row<true, DT>(w_ref, idx, n, x);
+            val_t x[4];
+            load_row_v<true, DT>(w_ref, idx, n, x);
             row(yes(), idx, x);
         }
     } else {
         // A ragged or unaligned chunk (the vector's last chunk is one wavefront's work from start to end, so its
         // memory round trips count): whole rows of an aligned array as in a full chunk, four fetched before the
         // first is decoded; the rest with guarded element accesses.
-        const bool vec = (reinterpret_cast<uintptr_t>(w_ref) & (4 * elem_bytes<DT>() - 1)) == 0;
+        const bool vec = (reinterpret_cast<uintptr_t>(w_ref) & (DT == kF64 ? 15 : 4 * elem_bytes<DT>() - 1)) == 0;
         u32 r = 0;
         if (vec) {
             constexpr u32 RB = 4;
             for (; r + RB <= kR && base + (u64)(r + RB) * kRowElems <= n; r += RB) {
-                float x[RB][4];
+                val_t x[RB][4];
 #pragma unroll
-                for (u32 k = 0; k < RB; ++k) load_row<true, DT>(w_ref, base + (u64)(r + k) * kRowElems + lane * kV, n, x[k]);
+                for (u32 k = 0; k < RB; ++k) load_row_v<true, DT>(w_ref, base + (u64)(r + k) * kRowElems + lane * kV, n, x[k]);
 #pragma unroll
                 for (u32 k = 0; k < RB; ++k) row(yes(), base + (u64)(r + k) * kRowElems + lane * kV, x[k]);
             }
         }
         for (; r < kR && base + (u64)r * kRowElems < n; ++r) {
             const u64 idx = base + (u64)r * kRowElems + lane * kV;
-            float x[4];
-            load_row<false, DT>(w_ref, idx, n, x);
+            val_t x[4];
+            load_row_v<false, DT>(w_ref, idx, n, x);
             row(no(), idx, x);
         }
     }
@@ -337,6 +348,7 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         }
         if (t < kMaxSym) {
             L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
+            L.rep64[t] = t < K ? __hiloint2double((int)D.info.rep_hi[t], (int)D.info.rep_bits[t]) : -0.0;
             L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
         }
         __syncthreads();
@@ -927,7 +939,8 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
     const u64 blocks = balanced_workers((nchunks + 3) / 4, (u64)tune.num_cu * tune.decode_blocks_per_cu);
     const dim3 grid((u32)blocks), wg(256);
     const int al = aligned_rows(w_ref, dtype);
-    if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
     else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
     else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
 }

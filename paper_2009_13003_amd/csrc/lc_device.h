@@ -63,6 +63,8 @@ __device__ __forceinline__ u32 wave_sum32(u32 v) {
 
 // delta of Algorithm 1 line 4: one IEEE binary32 subtraction (never fused or reassociated).
 __device__ __forceinline__ u32 delta_bits(float w, float w_ref) { return __float_as_uint(__fsub_rn(w, w_ref)); }
+// ... and for binary64 parameters one binary64 subtraction
+__device__ __forceinline__ u64 delta_bits(double w, double w_ref) { return (u64)__double_as_longlong(__dsub_rn(w, w_ref)); }
 
 // 16-byte load of data that is read once: marked non-temporal so that the stream does not push
 // other lines out of the caches (measured: +10 % read bandwidth on the sweeps).
@@ -75,17 +77,35 @@ __device__ __forceinline__ float4 load_stream(const float4* p) {
 // ---- element types of the parameter arrays.  The method works on the fp32 delta (Algorithm 1 line 4):
 // bf16 / fp16 parameters are widened exactly on load, and the restored value fl32(w_ref + rep) is rounded
 // once, to nearest even, on store.  Raw<DT> is what one lane holds of one row: 4 consecutive elements.
+// binary64 parameters are coded on the binary64 delta, with 2^12 buckets (Section 3.1.1, footnote on the bucket
+// count); Val<DT> is the type the arithmetic runs in, Bits<DT> its bit pattern.
+struct Row64 { double x[4]; };
 template <int DT> struct Raw { typedef uint2 type; };
 template <> struct Raw<kF32> { typedef float4 type; };
+template <> struct Raw<kF64> { typedef Row64 type; };
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <int DT> struct Val { typedef float type; typedef u32 bits; };
+template <> struct Val<kF64> { typedef double type; typedef u64 bits; };
 
-template <int DT> __device__ __forceinline__ constexpr u32 elem_bytes() { return DT == kF32 ? 4u : 2u; }
+template <int DT> __device__ __forceinline__ constexpr u32 elem_bytes() { return DT == kF32 ? 4u : DT == kF64 ? 8u : 2u; }
+template <int DT> __device__ __forceinline__ constexpr u32 exp_bits() { return DT == kF64 ? 11u : 8u; }
+template <int DT> __device__ __forceinline__ constexpr u32 num_buckets() { return 2u << exp_bits<DT>(); }
+// bucket id (sign and exponent bits) and biased exponent of a delta's bit pattern
+__device__ __forceinline__ u32 bucket_of(u32 u) { return u >> 23; }
+__device__ __forceinline__ u32 bucket_of(u64 u) { return (u32)(u >> 52); }
 
 // 4 consecutive elements starting at element index i (a multiple of 4, base aligned to 4 elements), non-temporal
 template <int DT>
 __device__ __forceinline__ typename Raw<DT>::type load_raw(const void* base, u64 i) {
     if constexpr (DT == kF32) {
         return load_stream(reinterpret_cast<const float4*>(static_cast<const float*>(base) + i));
+    } else if constexpr (DT == kF64) {
+        const float4* p = reinterpret_cast<const float4*>(static_cast<const double*>(base) + i);
+        const float4 a = load_stream(p), b = load_stream(p + 1);
+        Row64 r;
+        r.x[0] = __hiloint2double(__float_as_int(a.y), __float_as_int(a.x)); r.x[1] = __hiloint2double(__float_as_int(a.w), __float_as_int(a.z));
+        r.x[2] = __hiloint2double(__float_as_int(b.y), __float_as_int(b.x)); r.x[3] = __hiloint2double(__float_as_int(b.w), __float_as_int(b.z));
+        return r;
     } else {
         const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(base) + i));
         return make_uint2(v.x, v.y);
@@ -98,6 +118,11 @@ __device__ __forceinline__ float widen16(u32 h, bool bf16) {
 __device__ __forceinline__ u32 narrow16(float x, bool bf16) {      // finite x, round to nearest even
     if (bf16) { const u32 u = __float_as_uint(x); return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16; }
     return (u32)__builtin_bit_cast(unsigned short, (_Float16)x);      // v_cvt_f16_f32, round to nearest even
+}
+
+__device__ __forceinline__ void unpack64(const Row64& r, double (&x)[4]) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) x[v] = r.x[v];
 }
 
 template <int DT>
@@ -132,6 +157,21 @@ __device__ __forceinline__ void store4(void* base, u64 i, const float (&x)[4]) {
     }
 }
 
+// the same for binary64 parameters
+template <bool FAST>
+__device__ __forceinline__ void load_row64(const void* __restrict__ p, u64 idx, u64 n, double (&x)[4]) {
+    if (FAST) {
+        unpack64(load_raw<kF64>(p, idx), x);
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? static_cast<const double*>(p)[idx + v] : 0.0;
+    }
+}
+__device__ __forceinline__ void store4_64(void* base, u64 i, const double (&x)[4]) {
+    double2* q = reinterpret_cast<double2*>(static_cast<double*>(base) + i);
+    q[0] = make_double2(x[0], x[1]); q[1] = make_double2(x[2], x[3]);
+}
+
 template <bool FAST, int DT = kF32>
 __device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u64 n, float (&x)[4]) {
     if (FAST) {
@@ -141,6 +181,26 @@ __device__ __forceinline__ void load_row(const void* __restrict__ p, u64 idx, u6
         for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? load_one<DT>(p, idx + v) : 0.0f;
     }
 }
+
+// ---- the same three accesses and the restoring addition for any element type, on the type the arithmetic runs in
+template <bool FAST, int DT>
+__device__ __forceinline__ void load_row_v(const void* __restrict__ p, u64 idx, u64 n, typename Val<DT>::type (&x)[4]) {
+    if constexpr (DT == kF64) load_row64<FAST>(p, idx, n, x);
+    else load_row<FAST, DT>(p, idx, n, x);
+}
+template <int DT>
+__device__ __forceinline__ void store4_v(void* base, u64 i, const typename Val<DT>::type (&x)[4]) {
+    if constexpr (DT == kF64) store4_64(base, i, x);
+    else store4<DT>(base, i, x);
+}
+template <int DT>
+__device__ __forceinline__ void store_one_v(void* base, u64 i, typename Val<DT>::type x) {
+    if constexpr (DT == kF64) static_cast<double*>(base)[i] = x;
+    else store_one<DT>(base, i, x);
+}
+// Algorithm 1 line 7: one IEEE addition in the parameters' arithmetic type (never fused or reassociated)
+__device__ __forceinline__ float add_rn(float a, float b) { return __fadd_rn(a, b); }
+__device__ __forceinline__ double add_rn(double a, double b) { return __dadd_rn(a, b); }
 
 // ---- host-side helpers of the launchers
 // Work items dealt round-robin to at most `cap` workers: the smallest worker count that keeps the number of
@@ -152,7 +212,7 @@ static inline uint64_t balanced_workers(uint64_t items, uint64_t cap) {
 }
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 static inline bool aligned_rows(const void* p, int dtype) {     // 4 consecutive elements per access
-    return (reinterpret_cast<uintptr_t>(p) & (dtype == kF32 ? 15 : 7)) == 0;
+    return (reinterpret_cast<uintptr_t>(p) & (dtype == kF32 || dtype == kF64 ? 15 : 7)) == 0;
 }
 
 }  // namespace lc

@@ -24,8 +24,14 @@ __device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_word
     if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; ws->list_count = 0; }
 }
 
-__global__ void k_reset(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
+__device__ __forceinline__ void clear_ext64(Ext64* ext, u32 tid, u32 nthr) {
+    for (u32 i = tid; i < kBuckets64; i += nthr) ext->hist[i] = 0;
+    if (tid < kMaxSym) { ext->mmin[tid] = 0xFFFFFFFFFFFFFull; ext->mmax[tid] = 0; }
+}
+
+__global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
     clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
+    clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
     for (u32 i = threadIdx.x; i < nchunks; i += blockDim.x) chunk_maxexp[i] = 0;
 }
 
@@ -151,13 +157,101 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
     }
 }
 
+// ----------------------------------------------------------------------------- k_hist64
+// Sweep 1 for binary64 parameters: the same walk over the arrays (a 16-byte unit holds 2 elements, a batch of 4 rows
+// 512), 2^12 buckets (sign and 11 exponent bits; Section 3.1.1, footnote on the bucket count) in 2 LDS copies,
+// counts and chunk maxima of the binary64 delta.
+constexpr int kHistCopies64 = 2;
+
+template <bool ALIGNED>
+__device__ __forceinline__ float4 load_unit64(const void* __restrict__ p, u64 unit) {
+    if (ALIGNED) return load_stream(reinterpret_cast<const float4*>(p) + unit);
+    const double* q = static_cast<const double*>(p) + unit * 2;
+    const double a = q[0], b = q[1];
+    return make_float4(__int_as_float(__double2loint(a)), __int_as_float(__double2hiint(a)),
+                       __int_as_float(__double2loint(b)), __int_as_float(__double2hiint(b)));
+}
+
+template <bool ALIGNED>
+__global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, const void* __restrict__ w_ref,
+                                                 u64 n, Ext64* ext, u32* chunk_maxexp) {
+    __shared__ u32 h[kBuckets64 * kHistCopies64];
+    constexpr int EPU = 2;
+    const u32 tid = threadIdx.x, nthr = blockDim.x;
+    for (u32 i = tid; i < kBuckets64 * kHistCopies64; i += nthr) h[i] = 0;
+    __syncthreads();
+    const u32 copy = tid & (kHistCopies64 - 1);
+    const u64 nu = n / EPU;
+    constexpr int PF = 4;
+    constexpr u32 kBatchUnits = PF * kW;
+    static_assert(kChunk % (kBatchUnits * EPU) == 0, "a batch must not straddle two chunks");
+    const u64 nbatch = nu / kBatchUnits;
+    const u64 stride = (u64)gridDim.x * (nthr / kW);
+    u64 b = (u64)blockIdx.x * (nthr / kW) + tid / kW;
+    float4 a0[PF], b0[PF], a1[PF], b1[PF];
+    auto fetch = [&](float4 (&a)[PF], float4 (&bb)[PF], u64 batch) {
+        const u64 at = batch * kBatchUnits + (tid & (kW - 1));
+#pragma unroll
+        for (int k = 0; k < PF; ++k) { a[k] = load_unit64<ALIGNED>(w, at + k * kW); bb[k] = load_unit64<ALIGNED>(w_ref, at + k * kW); }
+    };
+    auto as_double = [](float lo, float hi) { return __hiloint2double(__float_as_int(hi), __float_as_int(lo)); };
+    auto count_one = [&](double x, double y, u32 m) {       // returns the larger of m and the delta's biased exponent
+        const u64 u = delta_bits(x, y);
+        atomicAdd(&h[bucket_of(u) * kHistCopies64 + copy], 1u);
+        return max(m, bucket_of(u) & 2047u);
+    };
+    auto count_unit = [&](const float4& a, const float4& bb, u32 m) {
+        m = count_one(as_double(a.x, a.y), as_double(bb.x, bb.y), m);
+        return count_one(as_double(a.z, a.w), as_double(bb.z, bb.w), m);
+    };
+    auto count = [&](float4 (&a)[PF], float4 (&bb)[PF], u64 batch) {
+        u32 m = 0;
+#pragma unroll
+        for (int k = 0; k < PF; ++k) m = count_unit(a[k], bb[k], m);
+        m = wave_max_u32(m);
+        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
+    };
+    if (b < nbatch) {
+        fetch(a0, b0, b);
+        while (true) {
+            const bool more1 = b + stride < nbatch;
+            fetch(a1, b1, more1 ? b + stride : b);
+            count(a0, b0, b);
+            if (!more1) break;
+            b += stride;
+            const bool more0 = b + stride < nbatch;
+            fetch(a0, b0, more0 ? b + stride : b);
+            count(a1, b1, b);
+            if (!more0) break;
+            b += stride;
+        }
+    }
+    if (blockIdx.x == 0) {
+        for (u64 u = nbatch * kBatchUnits + tid; u < nu; u += nthr) {
+            const u32 m = count_unit(load_unit64<ALIGNED>(w, u), load_unit64<ALIGNED>(w_ref, u), 0);
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((u * EPU) / kChunk))], m);
+        }
+        if (tid < (u32)(n - EPU * nu)) {
+            const u64 i = EPU * nu + tid;
+            const u32 m = count_one(static_cast<const double*>(w)[i], static_cast<const double*>(w_ref)[i], 0);
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)(i / kChunk))], m);
+        }
+    }
+    __syncthreads();
+    for (u32 bk = tid; bk < kBuckets64; bk += nthr) {
+        const u32 sum = h[bk * kHistCopies64] + h[bk * kHistCopies64 + 1];
+        if (sum) atomicAdd(&ext->hist[bk], (u64)sum);
+    }
+}
+
 // ----------------------------------------------------------------------------- k_table
 // Priority promotion (Section 3.1.1) and the Huffman table (Section 3.1.2), one wavefront.  Lane l looks at one exponent level (both signs) per step, from
 // the largest exponent down; a ballot/popcount scan ranks the non-empty buckets (+ before - at
 // equal exponent).  Lane 0 then builds the code lengths with two queues and the canonical codes
 // with per-length counters.
+template <int EB>                         // EB: exponent bits of the parameters' delta (8, or 11 for binary64)
 struct TableLds {
-    uint8_t sym[512];
+    uint8_t sym[2u << EB];
     u64 cnt[kMaxSym + 1];
     u32 kept[kMaxSym], len[kMaxSym + 1], code[kMaxSym + 1];
     u32 leaf[kMaxSym], left[kMaxSym], right[kMaxSym], depth[kMaxSym];
@@ -170,9 +264,12 @@ struct TableLds {
 // if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
 // With chunk_list (and a workgroup of more than one wavefront) the other wavefronts meanwhile list the chunks
 // that sweep 2 has to read: all but the full chunks whose largest exponent lies below every kept bucket.
-__device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups,
+template <int EB>
+__device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int nbits, u32* group_words, u32 ngroups,
                                             const u32* chunk_maxexp, u32* chunk_list) {
-    __shared__ TableLds S;
+    __shared__ TableLds<EB> S;
+    constexpr u32 kEmax = (1u << EB) - 1, kSteps = (1u << EB) / kW, kNeg = 1u << EB;
+    const unsigned long long* hist = EB == 8 ? ws->hist : ext->hist;
     __shared__ u32 s_reuse, s_min_kept_exp, s_listed;
     const u32 lane = lane_id();
     const bool active = threadIdx.x < kW;
@@ -180,28 +277,30 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; S.code[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
     u32 total = 0;
     bool nonfinite = false, zero_class = false;
-    // all eight counts of this lane first: the four ranking steps below then run without waiting on memory
+    // binary32: all eight counts of this lane first, the four ranking steps below then run without waiting on memory
     u64 cnt0[4], cnt1[4];
+    if (EB == 8) {
 #pragma unroll
-    for (u32 step = 0; active && step < 4; ++step) { cnt0[step] = ws->hist[255 - (step * kW + lane)]; cnt1[step] = ws->hist[511 - (step * kW + lane)]; }
-#pragma unroll
-    for (u32 step = 0; active && step < 4; ++step) {
-        const u32 E = 255 - (step * kW + lane);
-        const u64 c0 = cnt0[step], c1 = cnt1[step];
-        const bool normal = E >= 1 && E <= 254;
+        for (u32 step = 0; active && step < 4; ++step) { cnt0[step] = hist[kEmax - (step * kW + lane)]; cnt1[step] = hist[kNeg + kEmax - (step * kW + lane)]; }
+    }
+#pragma unroll 4
+    for (u32 step = 0; active && step < kSteps; ++step) {
+        const u32 E = kEmax - (step * kW + lane);
+        const u64 c0 = EB == 8 ? cnt0[step & 3] : hist[E], c1 = EB == 8 ? cnt1[step & 3] : hist[kNeg + E];
+        const bool normal = E >= 1 && E <= kEmax - 1;
         const bool cand0 = normal && c0 > 0, cand1 = normal && c1 > 0;
         const u64 m0 = __ballot(cand0), m1 = __ballot(cand1), lt = (1ull << lane) - 1;
         const u32 r0 = total + __popcll(m0 & lt) + __popcll(m1 & lt), r1 = r0 + (cand0 ? 1u : 0u);
-        S.sym[E] = 0xFF; S.sym[256 + E] = 0xFF;
+        S.sym[E] = 0xFF; S.sym[kNeg + E] = 0xFF;
         if (cand0 && r0 < kmax) { S.kept[r0] = E; S.cnt[r0] = c0; S.sym[E] = (uint8_t)r0; }
-        if (cand1 && r1 < kmax) { S.kept[r1] = 256 + E; S.cnt[r1] = c1; S.sym[256 + E] = (uint8_t)r1; }
+        if (cand1 && r1 < kmax) { S.kept[r1] = kNeg + E; S.cnt[r1] = c1; S.sym[kNeg + E] = (uint8_t)r1; }
         total += __popcll(m0) + __popcll(m1);
-        nonfinite = nonfinite || __any(E == 255 && (c0 | c1) != 0);
+        nonfinite = nonfinite || __any(E == kEmax && (c0 | c1) != 0);
         zero_class = zero_class || __any(E == 0 && (c0 | c1) != 0);
     }
     const u32 K = total < kmax ? total : kmax;              // (meaningful in the first wavefront only)
     __syncthreads();
-    if (threadIdx.x == 0) { s_min_kept_exp = K ? (S.kept[K - 1] & 255u) : 256u; s_listed = 0; }   // kept buckets are in descending exponent order
+    if (threadIdx.x == 0) { s_min_kept_exp = K ? (S.kept[K - 1] & kEmax) : kEmax + 1; s_listed = 0; }   // kept buckets are in descending exponent order
     __syncthreads();
     if (chunk_list && threadIdx.x >= kW) {
         const u32 min_kept_exp = s_min_kept_exp, workers = blockDim.x - kW;
@@ -285,9 +384,10 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     }
     __syncthreads();
     if (threadIdx.x == 0) ws->list_count = s_listed;
-    if (active) for (u32 b = lane; b < 512; b += kW) {
+    uint8_t* symlen_of_bucket = EB == 8 ? ws->table.symlen_of_bucket : ext->symlen_of_bucket;
+    if (active) for (u32 b = lane; b < (2u << EB); b += kW) {
         const u32 sy = S.sym[b] == 0xFF ? K : S.sym[b];
-        ws->table.symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
+        symlen_of_bucket[b] = (uint8_t)(sy | (S.len[sy] << 4));
     }
     if (active && ws->spec && !s_reuse) {          // the speculative coding is void: forget its extremes and sizes
         for (u32 i = lane; i < ngroups; i += kW) group_words[i] = 0;
@@ -295,9 +395,10 @@ __device__ __forceinline__ void table_build(EncState* ws, u64 n, int nbits, u32*
     }
 }
 
-__global__ __launch_bounds__(1024) void k_table(EncState* ws, u64 n, int nbits, u32* group_words, u32 ngroups,
+template <int EB>
+__global__ __launch_bounds__(1024) void k_table(EncState* ws, Ext64* ext, u64 n, int nbits, u32* group_words, u32 ngroups,
                                                  const u32* chunk_maxexp, u32* chunk_list) {
-    table_build(ws, n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
+    table_build<EB>(ws, ext, n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
 }
 
 // ----------------------------------------------------------------------------- k_spec_table
@@ -654,6 +755,20 @@ __device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, EncState* 
     }
 }
 
+// The chunks k_table left off the list (full ones that hold merged elements only): their sizes, a group of 64 per step.
+__device__ __forceinline__ void note_merged_chunks(const Table& T, u64 n, u32* chunk_bits, u32* group_words,
+                                                   const u32* chunk_maxexp) {
+    const u32 lane = lane_id();
+    const u32 nfull = (u32)(n / kChunk), min_kept_exp = T.min_kept_exp, len_merged = T.codelen[T.K] & 31;
+    for (u32 c0 = blockIdx.x * kW; c0 < nfull; c0 += gridDim.x * kW) {
+        const u32 c = c0 + lane;
+        const bool merged = c < nfull && chunk_maxexp[maxexp_slot(c)] < min_kept_exp;
+        if (merged) chunk_bits[c] = kMergedChunk | (kChunk * len_merged);
+        const u32 count = (u32)__popcll(__ballot(merged));
+        if (lane == 0 && count) atomicAdd(&group_words[c0 >> 6], count * (kLaneBitsWords + kChunk / 32 * len_merged));
+    }
+}
+
 template <int DT>
 __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                              EncState* ws, u32* chunk_bits, u32* group_words,
@@ -668,21 +783,92 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
     __syncthreads();
     VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8,
                         chunk_list, chunk_list ? ws->list_count : 0, 0};
-    if (chunk_list) {
-        // the chunks k_table left off the list (full ones that hold merged elements only), a group of 64 per step
-        const u32 nfull = (u32)(n / kChunk), min_kept_exp = T.min_kept_exp, len_merged = T.codelen[K] & 31;
-        for (u32 c0 = blockIdx.x * kW; c0 < nfull; c0 += gridDim.x * kW) {
-            const u32 c = c0 + lane;
-            const bool merged = c < nfull && chunk_maxexp[maxexp_slot(c)] < min_kept_exp;
-            if (merged) chunk_bits[c] = kMergedChunk | (kChunk * len_merged);
-            const u32 count = (u32)__popcll(__ballot(merged));
-            if (lane == 0 && count) atomicAdd(&group_words[c0 >> 6], count * (kLaneBitsWords + kChunk / 32 * len_merged));
-        }
-    }
+    if (chunk_list) note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
     if (src.row) pack_loop<false, true, DT, 1>(src, L);
     else pack_loop<false, true, DT, 0>(src, L);
     __syncthreads();
     pack_merge_extremes(L, ws, K, lane);
+}
+
+// ----------------------------------------------------------------------------- k_pack64
+// Sweep 2 for binary64 parameters: the same chunks, slots and lane strings; the symbol of an element comes from the
+// top 12 bits of its binary64 delta, the extremes are 64-bit patterns.  One symbol per look-up, rows fetched four
+// at a time (a row is 32 bytes per lane), code words stored as they fill.
+constexpr int kMmCopies64 = 16;
+
+struct PackLds64 {
+    uint8_t sym[kBuckets64];
+    u32 codelen[kMaxSym];
+    unsigned long long mn[kMaxSym * kMmCopies64], mx[kMaxSym * kMmCopies64];
+};
+
+template <bool WHOLE>            // WHOLE: a full chunk of 16-byte aligned arrays
+__device__ __forceinline__ void pack_chunk64(const ChunkRef& ch, PackLds64& L, u32 K) {
+    constexpr int RB = 4;
+    const u32 lane = lane_id();
+    const u64 n = ch.n, base = (u64)ch.c * kChunk;
+    u32* lane_words = ch.slot + kLaneBitsWords + lane;
+    const u32 mm = lane & (kMmCopies64 - 1);
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;
+    for (u32 r0 = 0; r0 < kR && (WHOLE || base + (u64)r0 * kRowElems < n); r0 += RB) {
+        double xa[RB][4], xb[RB][4];
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
+            load_row64<WHOLE>(ch.w, idx, n, xa[k]); load_row64<WHOLE>(ch.w_ref, idx, n, xb[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < RB; ++k) {
+            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (WHOLE || idx + v < n) {
+                    const u64 u = delta_bits(xa[k][v], xb[k][v]);
+                    const u32 sy = L.sym[bucket_of(u)];
+                    const u32 cl = L.codelen[sy];
+                    if (sy < K) { atomicMin(&L.mn[sy * kMmCopies64 + mm], u); atomicMax(&L.mx[sy * kMmCopies64 + mm], u); }
+                    acc = (acc << (cl & 31)) | (cl >> 5);
+                    nb += cl & 31;
+                }
+                if ((v & 1) && nb >= 32) {
+                    lane_words[nw * kW] = (u32)(acc >> (nb - 32));
+                    ++nw; nb -= 32;
+                }
+            }
+        }
+    }
+    if (nb > 0) lane_words[nw * kW] = (u32)(acc << (32 - nb));
+    finish_lane_sizes(ch, nb, nw);
+}
+
+__global__ __launch_bounds__(64) void k_pack64(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
+                                               EncState* ws, Ext64* ext, u32* chunk_bits, u32* group_words,
+                                               const u32* chunk_maxexp, const u32* chunk_list, u32* prov,
+                                               u32 slot_words, u32 nchunks, int aligned) {
+    __shared__ PackLds64 L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    if (T.status != 0) return;
+    const u32 K = T.K;
+    for (u32 i = lane; i < kBuckets64; i += kW) L.sym[i] = ext->symlen_of_bucket[i] & 15;
+    if (lane < kMaxSym) L.codelen[lane] = T.codelen[lane];
+    for (u32 i = lane; i < kMaxSym * kMmCopies64; i += kW) { L.mn[i] = ~0ull; L.mx[i] = 0; }
+    __syncthreads();
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, true,
+                        chunk_list, chunk_list ? ws->list_count : 0, 0};
+    if (chunk_list) note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
+    for (ChunkRef ch = src.take(); ch.valid; ch = src.take()) {
+        if (ch.fast) pack_chunk64<true>(ch, L, K);
+        else pack_chunk64<false>(ch, L, K);
+    }
+    __syncthreads();
+    if (lane < K) {
+        u64 mn = ~0ull, mx = 0;
+#pragma unroll
+        for (int k = 0; k < kMmCopies64; ++k) { mn = min(mn, (u64)L.mn[lane * kMmCopies64 + k]); mx = max(mx, (u64)L.mx[lane * kMmCopies64 + k]); }
+        if (mn <= mx) { atomicMin(&ext->mmin[lane], mn & 0xFFFFFFFFFFFFFull); atomicMax(&ext->mmax[lane], mx & 0xFFFFFFFFFFFFFull); }
+    }
 }
 
 // ----------------------------------------------------------------------------- k_spec_sweep
@@ -731,7 +917,7 @@ constexpr u32 kPlaceWords = 2048;
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
 __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
-                                              u64 n, int nbits, u32 nchunks, u32 dtype) {
+                                              u64 n, int nbits, u32 nchunks, u32 dtype, const Ext64* ext = nullptr) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
@@ -761,13 +947,23 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
     }
     if (ok && t <= T.K) {
         const u32 len = T.codelen[t] & 31;
+        // representative = midrange of the bucket's extremes, rounded once to nearest even (Section 3.1.1):
+        // halve the mantissa sum; an odd sum lies halfway between two mantissas and goes to the even one
         u32 bucket = 0xFFFFu, rep = 0;
-        if (t < T.K) {
+        if (t < T.K && dtype != kF64) {
             bucket = T.kept[t];
             const u32 sum = ws->mmin[t] + ws->mmax[t];
             u32 mm = sum >> 1;
             if ((sum & 1) && (mm & 1)) ++mm;
             rep = (bucket << 23) | mm;
+        } else if (t < T.K) {                          // binary64: 52-bit mantissas, high half at header offset 320 + 4 t
+            bucket = T.kept[t];
+            const u64 sum = ext->mmin[t] + ext->mmax[t];
+            u64 mm = sum >> 1;
+            if ((sum & 1) && (mm & 1)) ++mm;
+            const u64 rep64 = ((u64)bucket << 52) | mm;
+            rep = (u32)rep64;
+            hdr[80 + t] = (u32)(rep64 >> 32);
         }
         hdr[16 + 4 * t + 0] = bucket | (len << 16);
         hdr[16 + 4 * t + 1] = rep;
@@ -786,10 +982,11 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
     __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, EncState* ws, Result* host_result, u32* group_words,
+__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
                                                   TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
-    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype);
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, &ws->ext64);
     clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
+    if (dtype == kF64) clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
     __threadfence_system();
 }
 
@@ -998,7 +1195,7 @@ __global__ __launch_bounds__(64) void kb_hist(BatchArgs a) {
 }
 
 __global__ __launch_bounds__(64) void kb_table(BatchArgs a) {
-    table_build(&a.states[blockIdx.x], a.segs[blockIdx.x].n, a.nbits, nullptr, 0, nullptr, nullptr);
+    table_build<8>(&a.states[blockIdx.x], nullptr, a.segs[blockIdx.x].n, a.nbits, nullptr, 0, nullptr, nullptr);
 }
 
 __global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
@@ -1039,21 +1236,28 @@ void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
                  hipStream_t s) {
     if (n == 0) return;
     const u32 threads = tune.hist_threads;
-    const u64 units = n / (dtype == kF32 ? 4 : 8);                 // 16-byte units
+    const u64 units = n / (dtype == kF32 ? 4 : dtype == kF64 ? 2 : 8);   // 16-byte units
     u64 blocks = (units + 4 * threads - 1) / (4 * threads);
     const u64 cap = (u64)tune.num_cu * tune.hist_blocks_per_cu;
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
+    if (dtype == kF64) {
+        if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist64<true>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp);
+        else hipLaunchKernelGGL(k_hist64<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp);
+        return;
+    }
     if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
     else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
     else launch_hist_t<kF32>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
 }
 
 // chunk_list: where to list the chunks sweep 2 has to read (chunk_maxexp then holds what k_hist recorded), or null
-void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, const uint32_t* chunk_maxexp, uint32_t* chunk_list,
-                  hipStream_t s) {
-    hipLaunchKernelGGL(k_table, dim3(1), dim3(chunk_list ? 1024 : 64), 0, s, ws, (u64)n, nbits, group_words,
-                       (u32)((num_chunks_of(n) + 63) / 64), chunk_maxexp, chunk_list);
+void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
+                  uint32_t* chunk_list, hipStream_t s) {
+    const dim3 wg(chunk_list ? 1024 : 64);
+    const u32 ngroups = (u32)((num_chunks_of(n) + 63) / 64);
+    if (dtype == kF64) hipLaunchKernelGGL(k_table<11>, dim3(1), wg, 0, s, ws, &ws->ext64, (u64)n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
+    else hipLaunchKernelGGL(k_table<8>, dim3(1), wg, 0, s, ws, (Ext64*)nullptr, (u64)n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
 }
 
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
@@ -1083,7 +1287,8 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     if (blocks > nchunks) blocks = nchunks;
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
     const dim3 grid((u32)blocks), wg(64);
-    if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    if (dtype == kF64) hipLaunchKernelGGL(k_pack64, grid, wg, 0, s, w, w_ref, (u64)n, ws, &ws->ext64, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
     else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
 }

@@ -14,7 +14,7 @@ constexpr uint32_t kChunk = kRowElems * kR; // 16384 elements
 constexpr uint32_t kHeaderBytes = 512;
 constexpr uint32_t kLaneBitsWords = (2 * kW) / 4;   // 32 words of u16 lane lengths per chunk record
 constexpr uint32_t kMaxSym = 16;
-enum ElemType { kF32 = 0, kBF16 = 1, kF16 = 2 };   // element type of the parameter arrays (= LC_F32 ...)
+enum ElemType { kF32 = 0, kBF16 = 1, kF16 = 2, kF64 = 3 };   // element type of the parameter arrays (= LC_F32 ...)
 constexpr uint32_t kDecLut1Bits = 7;        // first decode table: conflict-free in LDS
 constexpr uint32_t kDecLut2Bits = 12;       // second decode table, for codes of 8..12 bits
 
@@ -39,6 +39,7 @@ struct DecInfo {
     uint64_t total_words;    // chunk area size in 32-bit words
     uint32_t rep_bits[kMaxSym];
     uint32_t len[kMaxSym], code[kMaxSym];
+    uint32_t rep_hi[kMaxSym];    // binary64 blobs: high halves of the representatives (rep_bits holds the low halves)
 };
 
 constexpr int kMaxMany = 8;  // blobs one fused restore sweep can apply
@@ -93,9 +94,19 @@ struct EncState {
 // chunk_maxexp[kMaxChunks] (u32, at fixed places so that they can be left cleared from one call to the
 // next), chunk_list[kMaxChunks] (u32), chunk_bits[num_chunks] (u32, padded to 256 bytes) and one slot of
 // slot_words_of(nbits) 32-bit words per chunk.
+// What an encode of binary64 parameters keeps instead of EncState's counts, extremes and bucket map: 2^12
+// (sign, exponent) buckets, 52-bit mantissas (Section 3.1.1, footnote on the bucket count).  Left cleared like them.
+constexpr uint32_t kBuckets64 = 4096;
+struct Ext64 {
+    unsigned long long hist[kBuckets64];
+    unsigned long long mmin[kMaxSym], mmax[kMaxSym];
+    uint8_t symlen_of_bucket[kBuckets64];
+};
+
 struct Workspace : EncState {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     DecSet dec_set[kMaxSets];        // one per blob of the call
+    Ext64 ext64;
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
@@ -132,8 +143,8 @@ struct Tuning {
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s);
 void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, const Tuning& tune,
                  hipStream_t s);
-void launch_table(Workspace* ws, uint64_t n, int nbits, uint32_t* group_words, const uint32_t* chunk_maxexp, uint32_t* chunk_list,
-                  hipStream_t s);
+void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
+                  uint32_t* chunk_list, hipStream_t s);
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);

@@ -116,16 +116,16 @@ def lc_encode(w, w_ref, nbits, out, stream=None, n=None):
     return r
 
 
-DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
+DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2, torch.float64: 3}
 
 
 def _dev_any(t):
-    assert t.is_cuda and t.dtype in DTYPES and t.is_contiguous(), "need a contiguous CUDA float32 / bfloat16 / float16 tensor"
+    assert t.is_cuda and t.dtype in DTYPES and t.is_contiguous(), "need a contiguous CUDA float32 / bfloat16 / float16 / float64 tensor"
     return ctypes.c_void_p(t.data_ptr())
 
 
 def lc_encode_t(w, w_ref, nbits, out, stream=None, n=None):
-    """lc_encode for float32, bfloat16 or float16 parameters (w and w_ref of the same dtype)."""
+    """lc_encode for float32, bfloat16, float16 or float64 parameters (w and w_ref of the same dtype)."""
     n = w.numel() if n is None else n
     assert w.dtype == w_ref.dtype
     assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
@@ -137,7 +137,7 @@ def lc_encode_t(w, w_ref, nbits, out, stream=None, n=None):
 
 
 def lc_decode_t(blob, w_ref, stream=None, n=None):
-    """lc_decode for float32, bfloat16 or float16 parameters."""
+    """lc_decode for float32, bfloat16, float16 or float64 parameters."""
     n = w_ref.numel() if n is None else n
     assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
     r = int(_lib.lc_decode_t(ctypes.c_void_p(blob.data_ptr()), _dev_any(w_ref), n, DTYPES[w_ref.dtype], _stream(stream)))

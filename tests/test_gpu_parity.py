@@ -919,3 +919,100 @@ def test_encode_of_quiet_chunks_16_bit(lc, tdt):
     ref_h = raw16(w_ref)
     orc.decode_t(blob_cpu, ref_h, code)
     assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
+
+
+# ---------------------------------------------------------------- binary64 parameters
+def bits64(a):
+    return np.ascontiguousarray(a, dtype=np.float64).view(np.uint64)
+
+
+def check_case64(lc, w, w_ref, nbits, label=""):
+    """fp64 parameters: blob byte-identical to the oracle's, restored values bit-identical."""
+    n = w.numel()
+    print("fp64 case", label, "n=%d nbits=%d" % (n, nbits), flush=True)
+    out = lc.alloc_out(n, nbits, DEV); out.fill_(0xA5)
+    size = lc.lc_encode_t(w, w_ref, nbits, out)
+    w_h, ref_h = w.cpu().numpy(), w_ref.cpu().numpy()
+    blob_cpu = orc.encode64(w_h, ref_h, nbits)
+    blob_gpu = out[:size].cpu().numpy()
+    assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    rec = w_ref.clone()
+    assert lc.lc_decode_t(out, rec) == size
+    orc.decode64(blob_cpu, ref_h)
+    bad = np.nonzero(bits64(rec.cpu().numpy()) != bits64(ref_h))[0]
+    assert bad.size == 0, "first differing element %d of %d" % (bad[0], bad.size)
+    return blob_cpu
+
+
+@pytest.mark.parametrize("n,nbits,offset", [(5 * 16384 + 777, 3, 0), (16384, 4, 0), (3 * 16384 + 5, 2, 1), (100, 3, 1),
+                                            (0, 3, 0), (1, 1, 0), (40 * 16384 + 99, 1, 0), (70 * 16384 + 4097, 4, 0)])
+def test_fp64_parameters_match_oracle(lc, n, nbits, offset):
+    """`offset` = 1 element leaves the arrays 8-byte aligned only: the guarded paths."""
+    g = torch.Generator(device=DEV); g.manual_seed(400 + n % 89 + nbits)
+    buf_r = 0.05 * torch.randn(n + 8, generator=g, device=DEV, dtype=torch.float64)
+    buf_w = buf_r + 2e-3 * torch.randn(n + 8, generator=g, device=DEV, dtype=torch.float64)
+    buf_w[::7] = buf_r[::7]                                              # some exactly unchanged
+    keep = buf_r.clone()
+    w, w_ref = buf_w[offset:offset + n], buf_r[offset:offset + n]
+    check_case64(lc, w, w_ref, nbits, "offset %d" % offset)
+    assert torch.equal(buf_r.view(torch.int64), keep.view(torch.int64))   # check_case64 restores into a clone
+
+
+def test_fp64_wide_exponent_range_and_quiet_chunks(lc):
+    """Exponents far outside binary32's range; whole chunks below every kept bucket (not read again by the second
+    sweep, written by the placement kernel); a merged code of several bits."""
+    nchunks = 70
+    n = nchunks * 16384 + 321
+    g = torch.Generator(device=DEV); g.manual_seed(41)
+    w_ref = torch.zeros(n, device=DEV, dtype=torch.float64)
+    e = torch.randint(0, 4, (n,), generator=g, device=DEV).double()
+    d = torch.exp2(600 - e) * (1 + torch.rand(n, generator=g, device=DEV, dtype=torch.float64))
+    d = d * (2 * torch.randint(0, 2, (n,), generator=g, device=DEV).double() - 1)
+    for k, c in enumerate([0, 5, 63, 64, 65, 69, 70]):
+        lo, hi = c * 16384, min(n, (c + 1) * 16384)
+        d[lo:hi] = 0 if k % 3 == 2 else 1e-250 * (1 + torch.rand(hi - lo, generator=g, device=DEV, dtype=torch.float64))
+    w = w_ref + d
+    for nbits in (2, 3, 4):
+        blob = check_case64(lc, w, w_ref, nbits, "wide range")
+        hdr = lcb1_reader.parse_header(blob)
+        assert hdr["dtype"] == 3 and (hdr["slots"][0]["bucket"] & 2047) == 1023 + 600
+    check_case64(lc, w, w_ref, 3, "again")                               # the scratch state was left clean
+    # and the fp32 path right after, on the same scratch area
+    w32, ref32 = laplace_case(3 * 16384 + 11, seed=5)
+    check_case(lc, w32, ref32, 3, "fp32 after fp64")
+
+
+def test_fp64_errors(lc):
+    n, nbits = 16384 + 9, 3
+    g = torch.Generator(device=DEV); g.manual_seed(43)
+    w_ref = 0.05 * torch.randn(n, generator=g, device=DEV, dtype=torch.float64)
+    w = w_ref + 1e-3 * torch.randn(n, generator=g, device=DEV, dtype=torch.float64)
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode_t(w, w_ref, nbits, out)
+    rec32 = w_ref.float()
+    before = rec32.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode(out, rec32)                                         # an fp64 blob into fp32 parameters
+    assert e.value.status == lc.ERR_BADARG and torch.equal(rec32, before)
+    out32 = lc.alloc_out(n, nbits, DEV)
+    lc.lc_encode(w.float(), w_ref.float(), nbits, out32)
+    rec = w_ref.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_t(out32, rec)                                       # an fp32 blob into fp64 parameters
+    assert e.value.status == lc.ERR_BADARG and torch.equal(rec, w_ref)
+    # damage in the high half of a representative: the oracle's verdict, parameters untouched
+    damaged = out[:size].clone(); damaged[320 + 3] ^= 0x10
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_t(damaged, rec)
+    assert e.value.status == lc.ERR_BAD_BLOB and torch.equal(rec, w_ref)
+    with pytest.raises(orc.OracleError) as eo:
+        orc.decode64(damaged.cpu().numpy(), w_ref.cpu().numpy())
+    assert eo.value.status == orc.BAD_BLOB
+    # a non-finite delta (the difference overflows)
+    w2 = w.clone(); ref2 = w_ref.clone(); w2[7] = 1.7e308; ref2[7] = -1.7e308
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_t(w2, ref2, nbits, out)
+    assert e.value.status == lc.ERR_NONFINITE
+    hdr = lcb1_reader.parse_header(out[:512].cpu().numpy())
+    assert hdr["status"] == 2 and hdr["dtype"] == 3 and hdr["total_bytes"] == 512
+    check_case64(lc, w, w_ref, nbits, "after a failed call")
