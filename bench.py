@@ -169,33 +169,37 @@ def cached_leg(job, steps, bits):
     return cached
 
 
-def bf16_leg(device, steps):
-    """Config 3's shapes and deltas with the parameters stored as bf16 (lc_encode_t / lc_decode_t)."""
+def typed_leg(device, steps, workload, tdt_name):
+    """A workload's shapes and deltas with the parameters stored as bf16 or fp64 (lc_encode_t / lc_decode_t)."""
     import torch
     from paper_2009_13003_amd import lc, workloads
-    w, r, nbits = workloads.vgg16(device=device)
-    rb = r.to(torch.bfloat16)
-    wb = (rb.float() + (w - r)).to(torch.bfloat16)
+    tdt = dict(bf16=torch.bfloat16, fp64=torch.float64)[tdt_name]
+    if workload == "vgg16":
+        w, r, nbits = workloads.vgg16(device=device)
+    else:
+        w, r, nbits = workloads.llama7b_head(device=device)
+    rt = r.to(tdt)
+    wt = (rt.float() + (w - r)).to(tdt) if tdt_name == "bf16" else rt + (w - r).double()
     del w, r
-    n = wb.numel()
+    n, esize = wt.numel(), wt.element_size()
     out = lc.alloc_out(n, nbits, device)
-    rec = rb.clone()
+    rec = rt.clone()
     for _ in range(2):
-        size = lc.lc_encode_t(wb, rb, nbits, out); lc.lc_decode_t(out, rec)
+        size = lc.lc_encode_t(wt, rt, nbits, out); lc.lc_decode_t(out, rec)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        size = lc.lc_encode_t(wb, rb, nbits, out)
+        size = lc.lc_encode_t(wt, rt, nbits, out)
     t1 = time.perf_counter()
     for _ in range(steps):
         lc.lc_decode_t(out, rec)
     t2 = time.perf_counter()
-    enc, dec, gb = (t1 - t0) / steps, (t2 - t1) / steps, 2.0 * n / 1e9
+    enc, dec, gb = (t1 - t0) / steps, (t2 - t1) / steps, esize * n / 1e9
     bits = 8.0 * (size - 512) / n
-    return dict(n=n, nbits=nbits, dtype="bf16", encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
-                encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(2.0 * n / size, 3),
-                encode_hbm_frac=round((8.0 + bits / 8.0) * n / 1e9 / enc / HBM_PEAK_GBPS, 4),
-                decode_hbm_frac=round((4.0 + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
+    return dict(n=n, nbits=nbits, dtype=tdt_name, encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
+                encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(esize * n / size, 3),
+                encode_hbm_frac=round((4.0 * esize + bits / 8.0) * n / 1e9 / enc / HBM_PEAK_GBPS, 4),
+                decode_hbm_frac=round((2.0 * esize + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
 
 
 def per_tensor_leg(device, steps):
@@ -386,7 +390,11 @@ def main():
             also[name]["nbits"] = j.nbits
             del j
             torch.cuda.empty_cache()
-        also["vgg16_bf16"] = bf16_leg(dev, args.steps)
+        also["vgg16_bf16"] = typed_leg(dev, args.steps, "vgg16", "bf16")
+        torch.cuda.empty_cache()
+        also["vgg16_fp64"] = typed_leg(dev, args.steps, "vgg16", "fp64")
+        torch.cuda.empty_cache()
+        also["llama7b_slice0_fp64"] = typed_leg(dev, max(2, args.steps // 2), "llama7b_slice0", "fp64")
         torch.cuda.empty_cache()
         also["resnet50_per_tensor"] = per_tensor_leg(dev, args.steps)
         torch.cuda.empty_cache()
