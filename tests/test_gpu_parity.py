@@ -1016,3 +1016,56 @@ def test_fp64_errors(lc):
     hdr = lcb1_reader.parse_header(out[:512].cpu().numpy())
     assert hdr["status"] == 2 and hdr["dtype"] == 3 and hdr["total_bytes"] == 512
     check_case64(lc, w, w_ref, nbits, "after a failed call")
+
+
+# ---------------------------------------------------------------- many small seeded cases
+def seeded_delta(kind, n, g, dtype):
+    """Deltas of different shapes: the paper's workloads have skewed exponent histograms, many near-zero
+    updates, sparse updates and heavy tails (Section 3.1.1, Section 4)."""
+    rnd = lambda: torch.rand(n, generator=g, device=DEV, dtype=dtype)
+    if kind == "laplace":
+        u = rnd() - 0.5
+        return -1e-3 * torch.sign(u) * torch.log1p(-2 * u.abs().clamp(max=0.4999999))
+    if kind == "sparse":                                     # most entries unchanged, the rest spread over many binades
+        d = torch.exp2(-20 * rnd()) * torch.sign(rnd() - 0.5)
+        return d * (rnd() < 0.02)
+    if kind == "heavy":                                      # a few huge outliers
+        d = 1e-5 * torch.randn(n, generator=g, device=DEV, dtype=dtype)
+        return torch.where(rnd() < 1e-3, 1e3 * d, d)
+    if kind == "blocks":                                     # scale changes every 5000 elements
+        scale = torch.exp2(-torch.floor(torch.arange(n, device=DEV, dtype=dtype) / 5000) % 12 - 6)
+        return scale * torch.randn(n, generator=g, device=DEV, dtype=dtype)
+    assert kind == "two_values"
+    return torch.where(rnd() < 0.5, 0.25, -0.125).to(dtype) * (rnd() < 0.7)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_cases_all_types(lc, seed):
+    kinds = ["laplace", "sparse", "heavy", "blocks", "two_values"]
+    rng = np.random.RandomState(1000 + seed)
+    kind = kinds[seed % len(kinds)]
+    n = int(rng.choice([1, 63, 4095, 16384, 16385, 50001, 5 * 16384 - 1, 9 * 16384 + 4097]))
+    nbits = int(rng.randint(1, 5))
+    offset = int(rng.choice([0, 0, 1, 2, 3]))
+    tdt = [torch.float32, torch.float64, torch.bfloat16, torch.float16][seed % 4]
+    print("seeded case", seed, kind, "n=%d nbits=%d offset=%d" % (n, nbits, offset), tdt, flush=True)
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    work = torch.float64 if tdt == torch.float64 else torch.float32
+    buf_r = (0.05 * torch.randn(n + 8, generator=g, device=DEV, dtype=work)).to(tdt)
+    buf_w = (buf_r.to(work) + seeded_delta(kind, n + 8, g, work)).to(tdt)
+    w, w_ref = buf_w[offset:offset + n], buf_r[offset:offset + n]
+    if tdt == torch.float32:
+        check_case(lc, w, w_ref, nbits, kind)
+    elif tdt == torch.float64:
+        check_case64(lc, w, w_ref, nbits, kind)
+    else:
+        code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+        out = lc.alloc_out(n, nbits, DEV)
+        size = lc.lc_encode_t(w, w_ref, nbits, out)
+        blob_cpu = orc.encode_t(raw16(w), raw16(w_ref), nbits, code)
+        assert np.array_equal(out[:size].cpu().numpy(), blob_cpu)
+        rec = w_ref.clone()
+        assert lc.lc_decode_t(out, rec) == size
+        ref_h = raw16(w_ref)
+        orc.decode_t(blob_cpu, ref_h, code)
+        assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
