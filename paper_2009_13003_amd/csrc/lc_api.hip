@@ -59,7 +59,7 @@ uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
 const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize", "k_spec_table", "k_spec_sweep",
-                                           "k_dec_check", "k_decode", "k_decode_many", "k_decode_fused"};
+                                           "k_dec_check", "k_decode", "k_decode_fused"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
     const char* v = getenv(name);
@@ -99,7 +99,6 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
         ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
         ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
-        ds.tune.many_blocks_per_cu = env_int("LC_TUNE_MANY_BLOCKS_PER_CU", ds.tune.many_blocks_per_cu, 1, 64);
         ds.tune.fused_waves_per_cu = env_int("LC_TUNE_FUSED_WAVES_PER_CU", ds.tune.fused_waves_per_cu, 1, 32);
         ds.tune.fused_min_waves_per_cu = env_int("LC_TUNE_FUSED_MIN_WAVES_PER_CU", ds.tune.fused_min_waves_per_cu, 1, 32);
         ds.tuned = true;
@@ -338,45 +337,39 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     uint64_t total = 0;
     for (int i = 0; i < count; ++i) total += g_pinned->bytes[i];
-    // Sweeps of up to kMaxMany blobs.  Blobs whose codes all fit the first decode table go through the
-    // fused kernel.  Its LDS payload area is sized to 1.1 x the blobs' average chunk payloads (a chunk
-    // above that still decodes, from memory), and a sweep takes only as many blobs as leave room for
-    // fused_min_waves_per_cu wavefronts per compute unit.  Anything else takes the general kernel.
+    // Sweeps of up to kMaxMany blobs through the fused kernel.  Its LDS payload area is sized to 1.1 x the blobs'
+    // average chunk payloads (a chunk above that still decodes, from memory), and a sweep takes only as many
+    // blobs as leave room for fused_min_waves_per_cu wavefronts per compute unit.  Blobs with codes longer than
+    // the first decode table (7 bits) are grouped apart from those without: they take the kernel's LONG form.
     const uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
     const size_t lds_budget = kLdsPerCu / (size_t)ds->tune.fused_min_waves_per_cu;
     auto pay_words_of = [](double words) {
         uint32_t w = ((uint32_t)(words * 1.1) + 63u) & ~63u;
         return w < kFusedMinWords ? kFusedMinWords : w;
     };
-    bool timed_many = false, timed_fused = false;
     for (int g0 = 0; g0 < count;) {
         const bool short_codes = g_pinned->max_len[g0] <= kDecLut1Bits;
         int T = 0;
         double words = 0;
         while (g0 + T < count && T < kMaxMany && (g_pinned->max_len[g0 + T] <= kDecLut1Bits) == short_codes) {
-            if (short_codes && nchunks) {
+            if (nchunks) {
                 const double avg = (double)(g_pinned->bytes[g0 + T] - area) / 4.0 / (double)nchunks - kLaneBitsWords + 6.0;
                 if (T > 0 && fused_lds_bytes(T + 1, pay_words_of(words + avg)) > lds_budget) break;
                 words += avg;
             }
             ++T;
         }
-        if (short_codes) {
+        {
             const uint32_t pay_words = pay_words_of(words);
-            Timed tm(kSlotDecodeFused, s); timed_fused = true;
-            launch_decode_fused(list, g0, T, w_ref, n, ws, epoch, g_pinned_dev, pay_words, ds->tune, s);
-        } else {
-            Timed tm(kSlotDecodeMany, s); timed_many = true;
-            launch_decode_many(list, g0, T, w_ref, n, ws, epoch, g_pinned_dev, ds->tune, s);
+            Timed tm(kSlotDecodeFused, s);
+            launch_decode_fused(list, g0, T, w_ref, n, ws, epoch, g_pinned_dev, pay_words, !short_codes, ds->tune, s);
         }
         LC_HIP(hipGetLastError());
         g0 += T;
     }
     LC_HIP(hipStreamSynchronize(s));
-    int slots[3] = {kSlotDecCheck, 0, 0}, ns = 1;
-    if (timed_many) slots[ns++] = kSlotDecodeMany;
-    if (timed_fused) slots[ns++] = kSlotDecodeFused;
-    collect(slots, ns);
+    int slots[2] = {kSlotDecCheck, kSlotDecodeFused};
+    collect(slots, 2);
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     return (lc_ssize)total;
 }

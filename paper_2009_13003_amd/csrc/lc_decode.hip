@@ -2,7 +2,7 @@
 // accumulation (Algorithm 1 line 7; Section 3, C1).
 //
 // lc_decode:        k_dec_check -> k_decode (gated on the check's verdict, no host round trip between)
-// lc_decode_many:   k_dec_check (all blobs) -> k_decode_fused<T> / k_decode_many per sweep
+// lc_decode_many:   k_dec_check (all blobs) -> k_decode_fused<T> per sweep
 // lc_decode_batch:  kb_dec_setup -> kb_dec_tables -> kb_dec_chunks -> kb_decode -> kb_dec_report
 #include "lc_device.h"
 #include <type_traits>
@@ -479,128 +479,19 @@ __global__ __launch_bounds__(256) void kb_dec_report(BatchDecArgs a) {
     a.results[t].used_cache = 0;
 }
 
-// ----------------------------------------------------------------------------- k_decode_many
+// ----------------------------------------------------------------------------- k_decode_fused
 // Restore from several checkpoints in one sweep (Section 3, C1: u_t = u_0 + sum of the decoded
 // deltas; Section 3.2, checkpoint merging): up to kMaxMany blobs of the same n are decoded side
 // by side and their values added to w_ref in blob order, one fp32 add per blob and element, so
 // the result equals that of applying the blobs one call after the other, with one read and
-// one write of w_ref instead of one per blob.  Lane strings are read straight from memory.
-struct ManyLds {
-    uint8_t lut1[kMaxMany][1u << kDecLut1Bits];
-    uint8_t lut2[kMaxMany][1u << kDecLut2Bits];
-    float rep[kMaxMany][kMaxSym];
-    u32 len[kMaxMany][kMaxSym], code[kMaxMany][kMaxSym];
-    u32 K[kMaxMany], P1[kMaxMany], P2[kMaxMany];
-    u64 area[kMaxMany];
-};
-
-__device__ __noinline__ u32 decode_long_many(const ManyLds& L, u32 t, u64 win) {
-    const u32 peek = (u32)(win >> (64 - 15)), K = L.K[t];
-    for (u32 j = 0; j <= K; ++j) {
-        const u32 l = L.len[t][j];
-        if (l > kDecLut2Bits && (peek >> (15 - l)) == L.code[t][j]) return j | (l << 4);
-    }
-    return K;
-}
-
-template <bool FAST>
-__device__ __forceinline__ void decode_many_chunk(const BlobList& blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
-                                                  Workspace* ws, HostResult* host, u32 c, const ManyLds& L, u64 epoch) {
-    const u32 lane = lane_id();
-    BitReader<false> br[kMaxMany];
-    u32 wi0[kMaxMany], avail0[kMaxMany], lane_bits[kMaxMany];
-#pragma unroll
-    for (int t = 0; t < kMaxMany; ++t) {
-        if ((u32)t < T) {
-            const uint8_t* blob = blobs.p[first + t];
-            const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
-            const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
-            const uint8_t* rec = blob + L.area[t] + 4 * (u64)o0;
-            lane_bits[t] = reinterpret_cast<const uint16_t*>(rec)[lane];
-            const u32 o = wave_incl_scan(lane_bits[t]) - lane_bits[t];
-            br[t].start(reinterpret_cast<const u32*>(rec + 2 * kW), o1 - o0 - kLaneBitsWords, o);
-            wi0[t] = br[t].wi; avail0[t] = br[t].avail;
-        }
-    }
-    const u64 base = (u64)c * kChunk;
-#pragma unroll 2
-    for (u32 r = 0; r < kR; ++r) {
-        const u64 idx = base + (u64)r * kRowElems + lane * kV;
-        if (!FAST && idx >= n) break;
-        float x[4];
-        load_row<FAST>(w_ref, idx, n, x);
-        u32 kept = 0;
-#pragma unroll
-        for (int t = 0; t < kMaxMany; ++t) {
-            if ((u32)t < T) {
-                const u32 shr1 = 64 - L.P1[t], shr2 = 64 - L.P2[t], K = L.K[t];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if (FAST || idx + v < n) {
-                        u32 e = L.lut1[t][(u32)(br[t].win >> shr1)];
-                        if (e == 0xFF) {
-                            e = L.lut2[t][(u32)(br[t].win >> shr2)];
-                            if (e == 0xFF) e = decode_long_many(L, t, br[t].win);
-                        }
-                        const u32 len = e >> 4, sy = e & 15;
-                        br[t].win <<= len; br[t].avail -= len;
-                        kept |= K - sy;
-                        x[v] = __fadd_rn(x[v], L.rep[t][sy]);
-                    }
-                    if ((v & 1) && br[t].avail <= 32) br[t].refill();
-                }
-            }
-        }
-        if (FAST) {
-            if (__any(kept != 0)) *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) if (idx + v < n) w_ref[idx + v] = x[v];
-        }
-    }
-    bool bad = false;
-#pragma unroll
-    for (int t = 0; t < kMaxMany; ++t)
-        if ((u32)t < T) bad = bad || (avail0[t] + 32 * (br[t].wi - wi0[t]) - br[t].avail != lane_bits[t]);
-    if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
-}
-
-__global__ __launch_bounds__(256) void k_decode_many(BlobList blobs, u32 first, u32 T, float* __restrict__ w_ref, u64 n,
-                                                     Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
-    __shared__ ManyLds L;
-    // if a check found something, touch nothing
-    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
-        const u32 tid = threadIdx.x;
-        for (u32 t = 0; t < T; ++t) {
-            const DecSet& D = ws->dec_set[first + t];
-            const u32 M = D.info.max_len, K = D.info.K;
-            const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-            if (tid < (1u << P1)) L.lut1[t][tid] = D.lut1[tid];
-            if (M > kDecLut1Bits) for (u32 i = tid; i < (1u << P2); i += 256) L.lut2[t][i] = D.lut2[i];
-            if (tid < kMaxSym) {
-                L.rep[t][tid] = __uint_as_float(tid < K ? D.info.rep_bits[tid] : 0x80000000u);
-                L.len[t][tid] = D.info.len[tid]; L.code[t][tid] = D.info.code[tid];
-            }
-            if (tid == 0) { L.K[t] = K; L.P1[t] = P1; L.P2[t] = P2; L.area[t] = D.info.area; }
-        }
-        __syncthreads();
-        const u32 wave = tid >> 6;
-        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
-            const bool full = (u64)(c + 1) * kChunk <= n;
-            if (full && aligned) decode_many_chunk<true>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
-            else decode_many_chunk<false>(blobs, first, T, w_ref, n, ws, host, c, L, epoch);
-        }
-    }
-}
-
-// ----------------------------------------------------------------------------- k_decode_fused
-// The same restore for blobs whose codes are all at most 7 bits long (always the case for
-// nbits <= 3), built for throughput.  T is a compile-time constant, so the T bit strings of a
+// one write of w_ref instead of one per blob.
+// T is a compile-time constant, so the T bit strings of a
 // lane are T independent dependency chains that the scheduler interleaves.  One wavefront per
 // workgroup; the payloads of a chunk (all T blobs) are staged in the workgroup's LDS area with
 // coalesced loads (the host sizes the area to the blobs, which also sets how many wavefronts
-// share a compute unit).  A row's 4 codes of one blob take at most 28 bits, so each blob's 32-bit
-// window is re-read once per row from the bit position alone, without a branch.  Both look-up
+// share a compute unit).  With codes of at most 7 bits (always the case for nbits <= 3) a row's 4 codes
+// of one blob take at most 28 bits, so each blob's 32-bit window is re-read once per row from the bit
+// position alone, without a branch; with longer codes (LONG) twice per row.  Both look-up
 // tables are free of LDS bank conflicts: 128 one-byte entries over the next 7 bits (code length
 // and symbol), then the symbol's representative.  A chunk whose payloads do not fit the LDS
 // area reads them from memory instead.
@@ -611,37 +502,53 @@ struct FusedHead {
                                                  // has one length, so distinct entries in use lie in distinct banks
     const uint8_t* rec_base[T];                  // start of the chunk records
     const u32* off_tab[T];
+    // Codes longer than the 7 bits of lut (its entry is then kFusedEscape): the symbols in canonical order
+    // (shorter codes first, then by index) have increasing left-justified codes, so the rank of the symbol a
+    // window starts with is the number of codes not above the window; only the long ones need comparing.
+    u32 lj[T][kMaxSym];                          // rank -> code, left-justified in 32 bits
+    uint16_t e_rank[T][kMaxSym];                 // rank -> (len << 4 | symbol) << 2
+    u32 rep_sym[T][kMaxSym];                     // symbol -> representative bits
+    u32 first_long[(T + 3) / 4 * 4];             // rank of the first code longer than 7 bits
+    u32 nranks[(T + 3) / 4 * 4];                 // symbols with a code
     u32 zero_bits[(T + 3) / 4 * 4];              // per blob: lane length of a chunk of merged symbols only (0: never skip)
     u32 pad[3];
     u32 before_pay;                              // the word in front of the payload area (read, never used)
 };
-constexpr u32 kFusedSlack = 64;                  // words behind the payloads that a damaged lane string may run into:
-                                                 // 256 codes of at most 7 bits past a start that validation bounds
+constexpr u32 kFusedEscape = 0xFFu << 2;         // what lut holds for a prefix of a longer code (no short entry has length 15)
+constexpr u32 kFusedSlack = 128;                 // words behind the payloads that a damaged lane string may run into:
+                                                 // 256 codes of at most 15 bits past a start that validation bounds
 
 // Bit positions are kept as p = 31 + bits from the start of the payload area (staged) or of the
 // blob's payload (from memory): the window is then the low 32 bits of {word[(p >> 5) - 1],
 // word[p >> 5]} >> (~p & 31), which is one v_alignbit.
-template <int T, bool FAST, bool STAGED>
+// LONG: some blob of the sweep has codes longer than 7 bits.  Two codes then take up to 30 bits, so the window is
+// re-read after the second code of a row, and a window that starts with a long code is ranked against the long
+// codes (a handful of compares; rare, since long codes belong to rare symbols).
+template <int T, bool FAST, bool STAGED, bool LONG>
 __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
                                           const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u64 idx,
                                           float (&x)[4]) {
     // Written step by step across the blobs (all windows, then the first code of every blob, ...), so
     // that the T look-ups of a step are in flight together.
     u32 win[T], rep[4][T];
+    auto windows = [&]() {
 #pragma unroll
-    for (int t = 0; t < T; ++t) {
-        u32 hi, lo;                                   // the two payload words around the lane's position
-        if (STAGED) {
-            const u32 wi = pos[t] >> 5;              // stays inside the area and its slack
-            hi = pay[(int)wi - 1]; lo = pay[wi];
-        } else {
-            const u32 wi = pos[t] >> 5, last = nw[t] - 1;
-            hi = wi ? gw[t][min(wi - 1, last)] : 0u; lo = gw[t][min(wi, last)];
+        for (int t = 0; t < T; ++t) {
+            u32 hi, lo;                                   // the two payload words around the lane's position
+            if (STAGED) {
+                const u32 wi = pos[t] >> 5;              // stays inside the area and its slack
+                hi = pay[(int)wi - 1]; lo = pay[wi];
+            } else {
+                const u32 wi = pos[t] >> 5, last = nw[t] - 1;
+                hi = wi ? gw[t][min(wi - 1, last)] : 0u; lo = gw[t][min(wi, last)];
+            }
+            win[t] = __builtin_amdgcn_alignbit(hi, lo, ~pos[t]);
         }
-        win[t] = __builtin_amdgcn_alignbit(hi, lo, ~pos[t]);
-    }
+    };
+    windows();
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
+        if (LONG && v == 2) windows();
         if (FAST || idx + v < n) {
             u32 e[T];
 #pragma unroll
@@ -649,10 +556,22 @@ __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay,
                 e[t] = H.lut[t][win[t] >> (32 - kDecLut1Bits)];
                 asm("" : "+v"(e[t]));                 // keep e a 32-bit value (no 16-bit shift plus re-extension)
             }
+            if (LONG) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    if (__any(e[t] == kFusedEscape)) {
+                        const u32 first = H.first_long[t], nr = H.nranks[t];
+                        u32 r = first;
+                        for (u32 j = first + 1; j < nr; ++j) r += win[t] >= H.lj[t][j] ? 1u : 0u;
+                        if (e[t] == kFusedEscape) e[t] = H.e_rank[t][r];
+                    }
+                }
+            }
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const u32 len = e[t] >> 6;
-                rep[v][t] = *reinterpret_cast<const u32*>(reinterpret_cast<const uint8_t*>(H.rep[t]) + e[t]);
+                if (LONG) rep[v][t] = H.rep_sym[t][(e[t] >> 2) & 15u];
+                else rep[v][t] = *reinterpret_cast<const u32*>(reinterpret_cast<const uint8_t*>(H.rep[t]) + e[t]);
                 win[t] <<= len; pos[t] += len;
             }
         } else {
@@ -684,7 +603,7 @@ __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay,
 
 // All rows of a full, aligned chunk with staged payloads: w_ref is read PF rows ahead in two
 // alternating register batches, so the reads of the next rows are in flight while these decode.
-template <int T>
+template <int T, bool LONG>
 __device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
                                                 const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u32 c) {
     constexpr int PF = 4;
@@ -698,7 +617,7 @@ __device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
             float x[4] = {X[k].x, X[k].y, X[k].z, X[k].w};
-            fused_row<T, true, true>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
+            fused_row<T, true, true, LONG>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
         }
     };
     for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
@@ -714,7 +633,7 @@ __device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32
 }
 
 // Any chunk (ragged, unaligned, or payloads read from memory), row by row.
-template <int T, bool FAST>
+template <int T, bool FAST, bool LONG>
 __device__ __forceinline__ void fused_rows_plain(const FusedHead<T>& H, const u32* const (&gw)[T], const u32 (&nw)[T], u32 (&pos)[T],
                                               float* __restrict__ w_ref, u64 n, u32 c) {
     const u32 lane = lane_id();
@@ -724,7 +643,7 @@ __device__ __forceinline__ void fused_rows_plain(const FusedHead<T>& H, const u3
         if (!FAST && idx >= n) break;
         float x[4];
         load_row<FAST>(w_ref, idx, n, x);
-        fused_row<T, FAST, false>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
+        fused_row<T, FAST, false, LONG>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
     }
 }
 
@@ -735,7 +654,7 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {        // a pointer every lane
     return reinterpret_cast<P*>(((u64)hi << 32) | lo);
 }
 
-template <int T, bool FAST>
+template <int T, bool FAST, bool LONG>
 __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32 pay_words, float* __restrict__ w_ref, u64 n,
                                             Workspace* ws, HostResult* host, u32 c, u32 nchunks, u64 epoch) {
     const u32 lane = lane_id();
@@ -811,11 +730,11 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
     if (staged) {
 #pragma unroll
         for (int t = 0; t < T; ++t) { start[t] += 32 * (wbase[t] + k0[t]); pos[t] = start[t]; }
-        fused_rows_fast<T>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
+        fused_rows_fast<T, LONG>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
     } else {
 #pragma unroll
         for (int t = 0; t < T; ++t) pos[t] = start[t];
-        fused_rows_plain<T, FAST>(H, gw, nw, pos, w_ref, n, c);
+        fused_rows_plain<T, FAST, LONG>(H, gw, nw, pos, w_ref, n, c);
     }
     bool bad = false;
 #pragma unroll
@@ -823,7 +742,7 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
     if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
-template <int T>
+template <int T, bool LONG>
 __global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, float* __restrict__ w_ref, u64 n,
                                                      Workspace* ws, u32 nchunks, int aligned, u64 epoch,
                                                      HostResult* host, u32 pay_words) {
@@ -837,12 +756,27 @@ __global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, 
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         const DecSet& D = ws->dec_set[first + t];
-        const u32 M = D.info.max_len, K = D.info.K;       // M <= 7: e < 128
+        const u32 M = D.info.max_len, K = D.info.K;       // entries of codes of at most 7 bits: e < 512
         const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits;
         for (u32 i = tid; i < (1u << kDecLut1Bits); i += kW) {
             const u32 e = D.lut1[i >> (kDecLut1Bits - P1)];
             H.lut[t][i] = (uint16_t)(e << 2);
             H.rep[t][i] = (i & 15) < K ? D.info.rep_bits[i & 15] : 0x80000000u;
+        }
+        if (LONG && tid < kMaxSym) {
+            // this symbol's rank in canonical order (shorter codes first, then by index)
+            const u32 j = tid, own = D.info.len[j];
+            u32 rank = 0, coded = 0, short_codes = 0;
+            for (u32 i = 0; i < kMaxSym; ++i) {
+                const u32 li = D.info.len[i];
+                if (li == 0) continue;
+                ++coded;
+                if (li <= kDecLut1Bits) ++short_codes;
+                if (own && (li < own || (li == own && i < j))) ++rank;
+            }
+            H.rep_sym[t][j] = j < K ? D.info.rep_bits[j] : 0x80000000u;
+            if (own) { H.lj[t][rank] = D.info.code[j] << (32 - own); H.e_rank[t][rank] = (uint16_t)(((own << 4) | j) << 2); }
+            if (tid == 0) { H.first_long[t] = short_codes; H.nranks[t] = coded; }
         }
         if (tid == 0) {
             const uint8_t* blob = blobs.p[first + t];
@@ -855,8 +789,8 @@ __global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, 
     __syncthreads();
     for (u32 c = blockIdx.x; c < nchunks; c += gridDim.x) {
         const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) fused_chunk<T, true>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
-        else fused_chunk<T, false>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        if (full && aligned) fused_chunk<T, true, LONG>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        else fused_chunk<T, false, LONG>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
     }
 }
 // ----------------------------------------------------------------------------- launchers
@@ -884,23 +818,16 @@ void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, i
                        ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
 }
 
-void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
-                        uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s) {
-    const u64 nchunks = num_chunks_of(n);
-    if (nchunks == 0) return;
-    u64 blocks = (nchunks + 3) / 4;
-    const u64 cap = (u64)tune.num_cu * tune.many_blocks_per_cu;
-    if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(k_decode_many, dim3((u32)blocks), dim3(256), 0, s, blobs, (u32)first, (u32)count, w_ref, (u64)n, ws,
-                       (u32)nchunks, (int)aligned16(w_ref), (u64)epoch, host);
-}
 
 
 template <int T>
 static void launch_fused_t(const BlobList& blobs, int first, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
-                           HostResult* host, u32 blocks, u32 pay_words, hipStream_t s) {
-    hipLaunchKernelGGL(k_decode_fused<T>, dim3(blocks), dim3(64), 4 * (size_t)(pay_words + kFusedSlack), s, blobs, (u32)first, w_ref,
-                       (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
+                           HostResult* host, u32 blocks, u32 pay_words, bool long_codes, hipStream_t s) {
+    const size_t lds = 4 * (size_t)(pay_words + kFusedSlack);
+    if (long_codes) hipLaunchKernelGGL((k_decode_fused<T, true>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
+                                       (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
+    else hipLaunchKernelGGL((k_decode_fused<T, false>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
+                            (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
 }
 
 size_t fused_lds_bytes(int count, uint32_t pay_words) {
@@ -910,7 +837,8 @@ size_t fused_lds_bytes(int count, uint32_t pay_words) {
 }
 
 void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
-                         uint64_t epoch, HostResult* host, uint32_t pay_words, const Tuning& tune, hipStream_t s) {
+                         uint64_t epoch, HostResult* host, uint32_t pay_words, bool long_codes, const Tuning& tune,
+                         hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     // one wavefront per workgroup; as many workgroups per compute unit as their LDS areas allow
@@ -921,14 +849,14 @@ void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_r
     if (blocks > nchunks) blocks = nchunks;
     const u32 b = (u32)blocks;
     switch (count) {
-        case 1: launch_fused_t<1>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 2: launch_fused_t<2>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 3: launch_fused_t<3>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 4: launch_fused_t<4>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 5: launch_fused_t<5>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 6: launch_fused_t<6>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        case 7: launch_fused_t<7>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
-        default: launch_fused_t<8>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, s); break;
+        case 1: launch_fused_t<1>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 2: launch_fused_t<2>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 3: launch_fused_t<3>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 4: launch_fused_t<4>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 5: launch_fused_t<5>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 6: launch_fused_t<6>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 7: launch_fused_t<7>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        default: launch_fused_t<8>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
     }
 }
 

@@ -124,7 +124,7 @@ __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsW
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
 enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecTable, kSlotSpecSweep,
-            kSlotDecCheck, kSlotDecode, kSlotDecodeMany, kSlotDecodeFused, kNumSlots };
+            kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
 // variables (read once) for sweeps.
@@ -134,7 +134,6 @@ struct Tuning {
     int hist_threads = 256;
     int pack_waves_per_cu = 6;
     int decode_blocks_per_cu = 4;
-    int many_blocks_per_cu = 2;
     int fused_waves_per_cu = 16;       // most wavefronts per compute unit
     int fused_min_waves_per_cu = 8;    // a sweep takes as many blobs as still leave LDS for this many
 };
@@ -192,11 +191,10 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
                    const Tuning& tune, hipStream_t s);
 // Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused
 // kernel requires every code of these blobs to be at most kDecLut1Bits long.
-void launch_decode_many(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
-                        uint64_t epoch, HostResult* host, const Tuning& tune, hipStream_t s);
 // pay_words: LDS words each wavefront gets for the payloads of one chunk of all `count` blobs.
 void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
-                         uint64_t epoch, HostResult* host, uint32_t pay_words, const Tuning& tune, hipStream_t s);
+                         uint64_t epoch, HostResult* host, uint32_t pay_words, bool long_codes, const Tuning& tune,
+                         hipStream_t s);
 
 constexpr uint32_t kLdsPerCu = 160 * 1024;        // gfx950
 constexpr uint32_t kFusedMinWords = 1024;

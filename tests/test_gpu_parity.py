@@ -358,8 +358,8 @@ def oracle_restore(w0, blobs):
 
 
 def test_fused_restore_mixed_code_lengths_and_whole_chunks(lc):
-    """Blobs with short codes (fused sweep) and long codes (general sweep) alternate in one call; n is a whole
-    number of chunks, so the last chunk is staged too."""
+    """Blobs with codes of at most 7 bits and blobs with longer codes alternate in one call (they go through
+    different forms of the fused sweep); n is a whole number of chunks, so the last chunk is staged too."""
     n = 6 * 16384
     g = torch.Generator(device=DEV); g.manual_seed(77)
     w0 = 0.05 * torch.randn(n, generator=g, device=DEV)
@@ -368,7 +368,7 @@ def test_fused_restore_mixed_code_lengths_and_whole_chunks(lc):
     deltas = [torch.randn(n, generator=g, device=DEV) * torch.exp2(-6 - 12 * torch.rand(n, generator=g, device=DEV)) for _ in nbits_list]
     tracked, blobs = encode_chain(lc, w0, deltas, nbits_list)
     max_lens = [lcb1_reader.parse_header(b.cpu().numpy())["max_len"] for b in blobs]
-    assert max(max_lens) > 7 and min(max_lens) <= 7, max_lens      # both kernels take part
+    assert max(max_lens) > 7 and min(max_lens) <= 7, max_lens      # both forms take part
     restored = w0.clone()
     assert lc.lc_decode_many(blobs, restored) == sum(b.numel() for b in blobs)
     assert np.array_equal(bits(restored.cpu().numpy()), bits(oracle_restore(w0, blobs)))
@@ -1069,3 +1069,47 @@ def test_seeded_cases_all_types(lc, seed):
         ref_h = raw16(w_ref)
         orc.decode_t(blob_cpu, ref_h, code)
         assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
+
+
+@pytest.mark.parametrize("steps,offset", [(2, 0), (5, 0), (8, 0), (3, 1)])
+def test_fused_restore_long_codes(lc, steps, offset):
+    """Every blob has codes of up to 15 bits (nbits = 4, magnitudes spread geometrically over many binades, so the
+    rare buckets get long codes): several blobs per sweep, ragged tail, an unaligned vector, and a damaged lane
+    string, each with the oracle's result."""
+    n = 9 * 16384 + 1234
+    g = torch.Generator(device=DEV); g.manual_seed(500 + steps)
+    buf = 0.05 * torch.randn(n + 4, generator=g, device=DEV)
+    w0 = buf[offset:offset + n]
+    # P(binade e) halves with every binade down: code lengths 1, 2, 3, ... up to 15
+    deltas = []
+    for _ in range(steps):
+        e = torch.floor(-torch.log2(torch.rand(n, generator=g, device=DEV).clamp_(min=2.0 ** -18)))
+        deltas.append(torch.exp2(-4 - e) * (1 + torch.rand(n, generator=g, device=DEV)))
+    tracked, blobs = encode_chain(lc, w0.clone(), deltas, [4] * steps)
+    max_lens = [lcb1_reader.parse_header(b.cpu().numpy())["max_len"] for b in blobs]
+    assert min(max_lens) > 7 and max(max_lens) >= 12, max_lens
+    restored = buf.clone()
+    assert lc.lc_decode_many(blobs, restored[offset:offset + n]) == sum(b.numel() for b in blobs)
+    assert np.array_equal(bits(restored[offset:offset + n].cpu().numpy()), bits(oracle_restore(w0, blobs)))
+    assert torch.equal(restored[:offset], buf[:offset]) and torch.equal(restored[offset + n:], buf[offset + n:])
+    # a flipped payload bit in the last blob: same verdict as the oracle's
+    nchunks = (n + 16383) // 16384
+    area = 512 + (4 * (nchunks + 1) + 15) // 16 * 16
+    damaged = [b.clone() for b in blobs]
+    damaged[-1][area + 128 + 777] ^= 0x08
+    ref_h = w0.cpu().numpy().copy()
+    try:
+        for b in damaged:
+            orc.decode(b.cpu().numpy(), ref_h)
+        oracle_ok = True
+    except orc.OracleError as e:
+        assert e.status == 4
+        oracle_ok = False
+    rec = w0.clone()
+    if oracle_ok:
+        lc.lc_decode_many(damaged, rec)
+        assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h))
+    else:
+        with pytest.raises(lc.LcError) as e:
+            lc.lc_decode_many(damaged, rec)
+        assert e.value.status == lc.ERR_BAD_BLOB
