@@ -2,6 +2,7 @@
 //
 // lc_encode:         k_hist -> k_table -> k_pack -> k_place -> k_finalize (which also clears the scratch
 //                    state for the next call, k_place the per-chunk maxima); k_reset only for a fresh scratch area
+//                    (fp64 parameters: k_hist64 -> k_table<11> -> k_pack64 -> k_place -> k_finalize)
 // lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place -> k_finalize
 // lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_pack -> kb_place -> kb_finalize
 //
