@@ -133,7 +133,7 @@ struct Tuning {
     int hist_blocks_per_cu = 1;
     int hist_threads = 256;
     int pack_waves_per_cu = 6;
-    int decode_blocks_per_cu = 4;
+    int decode_blocks_per_cu = 9;     // (LDS lets 4 run at once; more, smaller shares even out chunks that decode to nothing)
     int fused_waves_per_cu = 16;       // most wavefronts per compute unit
     int fused_min_waves_per_cu = 8;    // a sweep takes as many blobs as still leave LDS for this many
 };
