@@ -209,7 +209,7 @@ struct BitReader {
 template <bool FAST, bool LV2, bool STAGED, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
                                             void* __restrict__ w_ref, u64 n, u32 c,
-                                            const LDS& L, u32 P1, u32 P2, u32 K, Raise& raise) {
+                                            const LDS& L, u32 P1, u32 P2, u32 K, u32 row_zero_bits, Raise& raise) {
     const u32 lane = lane_id();
     BitReader<STAGED> br;
     br.start(words, nwords, first_bit);
@@ -220,6 +220,13 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     typedef typename Val<DT>::type val_t;
     auto row = [&](auto whole, u64 idx, val_t (&x)[4]) {
         constexpr bool WHOLE = decltype(whole)::value;
+        // row_zero_bits = 4 x the merged symbol's code length when that code is all zero bits (at most 32): so many
+        // zero bits at the head of every lane's window are 4 merged symbols each, and the row stays as it is
+        if (WHOLE && row_zero_bits != 0 && !__any((u32)(br.win >> (64 - row_zero_bits)) != 0)) {
+            br.win <<= row_zero_bits; br.avail -= row_zero_bits;
+            if (br.avail <= 32) br.refill();
+            return;
+        }
         u32 smin = K;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -299,6 +306,7 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
     const u32 o = wave_incl_scan(lane_bits) - lane_bits;
     const u32* gw = reinterpret_cast<const u32*>(rec + 2 * kW);
     const u32 k0 = (u32)((reinterpret_cast<uintptr_t>(gw) >> 2) & 3);     // words between the 16-byte boundary and the payload
+    const u32 row_zero_bits = zero_bits / (kR * kV) * kV <= 32 ? zero_bits / (kR * kV) * kV : 0u;
     if (nwords + k0 <= kPayWords) {
         // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
         // record's own lane lengths, and the last vector is read word by word so no read passes the end
@@ -319,9 +327,9 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
         }
         if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
         decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
-                                         w_ref, n, c, L, P1, P2, K, raise);
+                                         w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
     } else {
-        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, raise);
+        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
     }
 }
 

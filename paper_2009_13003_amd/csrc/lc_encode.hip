@@ -11,6 +11,7 @@
 // mean of their extremes and x-bit priority promotion (Section 3.1.1), Huffman
 // coding of the bucket indices (Section 3.1.2).  How it is laid out on the GPU is this library's own.
 #include "lc_device.h"
+#include <type_traits>
 
 namespace lc {
 
@@ -498,6 +499,7 @@ struct ChunkRef {
     u32* slot; u32* bits_at; u32* group_at;
     u32 seg;                     // batched calls: which tensor
     bool valid, fast;            // fast: a full chunk of aligned arrays
+    bool vec;                    // the arrays are aligned for 4-element accesses (whole rows of a ragged chunk too)
 };
 
 __device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u32 nw) {
@@ -511,8 +513,9 @@ __device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u3
     }
 }
 
-// Any size, any alignment: guarded element loads, one symbol per look-up.  The rows are loaded four at a time,
-// so a ragged last chunk costs a quarter of the memory round trips (it is one wavefront's work from start to end).
+// Any size, any alignment, one symbol per look-up.  The vector's ragged last chunk is one wavefront's work from
+// start to end, so its memory round trips count: the rows that lie wholly inside an aligned vector are fetched as
+// in a full chunk, four at a time and one batch ahead; what is left takes guarded element loads.
 constexpr int kPlainRows = 4;
 
 template <bool HIST, bool PACK, int DT>
@@ -524,35 +527,60 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
     const u32 mm = lane & (kMmCopies - 1);
     u64 acc = 0;
     u32 nb = 0, nw = 0;
-    for (u32 r0 = 0; r0 < kR && base + (u64)r0 * kRowElems < n; r0 += kPlainRows) {
-        float xa[kPlainRows][4], xb[kPlainRows][4];
+    auto code_row = [&](auto whole, u64 idx, const float (&xa)[4], const float (&xb)[4]) {
+        constexpr bool WHOLE = decltype(whole)::value;
 #pragma unroll
-        for (int k = 0; k < kPlainRows; ++k) {
-            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
-            load_row<false, DT>(w, idx, n, xa[k]); load_row<false, DT>(w_ref, idx, n, xb[k]);
-        }
-#pragma unroll
-        for (int k = 0; k < kPlainRows; ++k) {
-            const u64 idx = base + (u64)(r0 + k) * kRowElems + lane * kV;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                if (idx + v < n) {
-                    const u32 u = delta_bits(xa[k][v], xb[k][v]);
-                    if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
-                    if (!PACK) continue;
-                    const u32 sy = L.sym8[u >> 23] >> 3;
-                    const u32 cl = L.codelen[sy];
-                    atomicMin(&L.mn[sy * kMmCopies + mm], u);
-                    atomicMax(&L.mx[sy * kMmCopies + mm], u);
-                    acc = (acc << (cl & 31)) | (cl >> 5);
-                    nb += cl & 31;
-                }
-                if (PACK && (v & 1) && nb >= 32) {
-                    slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
-                    ++nw; nb -= 32;
-                }
+        for (int v = 0; v < 4; ++v) {
+            if (WHOLE || idx + v < n) {
+                const u32 u = delta_bits(xa[v], xb[v]);
+                if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+                if (!PACK) continue;
+                const u32 sy = L.sym8[u >> 23] >> 3;
+                const u32 cl = L.codelen[sy];
+                atomicMin(&L.mn[sy * kMmCopies + mm], u);
+                atomicMax(&L.mx[sy * kMmCopies + mm], u);
+                acc = (acc << (cl & 31)) | (cl >> 5);
+                nb += cl & 31;
+            }
+            if (PACK && (v & 1) && nb >= 32) {
+                slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32));
+                ++nw; nb -= 32;
             }
         }
+    };
+    typedef std::integral_constant<bool, true> yes;
+    typedef std::integral_constant<bool, false> no;
+    auto row_at_ = [&](u32 r) { return base + (u64)r * kRowElems + lane * kV; };
+    // whole rows of an aligned vector, in batches of kPlainRows
+    u32 r = 0;
+    const u64 inside = n > base ? n - base : 0;
+    const u32 whole_rows = ch.vec ? (u32)min((u64)kR, inside / kRowElems) / kPlainRows * kPlainRows : 0u;
+    if (whole_rows) {
+        float xa[kPlainRows][4], xb[kPlainRows][4], ya[kPlainRows][4], yb[kPlainRows][4];
+        auto fetch = [&](float (&a)[kPlainRows][4], float (&b)[kPlainRows][4], u32 r0) {
+#pragma unroll
+            for (int k = 0; k < kPlainRows; ++k) { load_row<true, DT>(w, row_at_(r0 + k), n, a[k]); load_row<true, DT>(w_ref, row_at_(r0 + k), n, b[k]); }
+        };
+        auto code = [&](const float (&a)[kPlainRows][4], const float (&b)[kPlainRows][4], u32 r0) {
+#pragma unroll
+            for (int k = 0; k < kPlainRows; ++k) code_row(yes(), row_at_(r0 + k), a[k], b[k]);
+        };
+        fetch(xa, xb, 0);
+        for (; r < whole_rows; r += 2 * kPlainRows) {
+            // the batch after this one, or (none left) this one again: loads on every path, see k_hist
+            fetch(ya, yb, r + kPlainRows < whole_rows ? r + kPlainRows : r);
+            code(xa, xb, r);
+            if (r + kPlainRows >= whole_rows) { r += kPlainRows; break; }
+            fetch(xa, xb, r + 2 * kPlainRows < whole_rows ? r + 2 * kPlainRows : r);
+            code(ya, yb, r + kPlainRows);
+        }
+    }
+    for (; r < kR && base + (u64)r * kRowElems < n; r += kPlainRows) {
+        float xa[kPlainRows][4], xb[kPlainRows][4];
+#pragma unroll
+        for (int k = 0; k < kPlainRows; ++k) { load_row<false, DT>(w, row_at_(r + k), n, xa[k]); load_row<false, DT>(w_ref, row_at_(r + k), n, xb[k]); }
+#pragma unroll
+        for (int k = 0; k < kPlainRows; ++k) code_row(no(), row_at_(r + k), xa[k], xb[k]);
     }
     if (!PACK) return;
     if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
@@ -719,6 +747,7 @@ struct VectorChunks {
         ch.valid = valid;
         ch.w = w; ch.w_ref = w_ref; ch.n = n;
         ch.fast = aligned && (u64)(c + 1) * kChunk <= n;
+        ch.vec = aligned;
         ch.slot = prov + (u64)c * slot_words;
         ch.bits_at = chunk_bits + c;
         ch.group_at = group_words + (c >> 6);
@@ -1140,7 +1169,7 @@ struct BatchChunks {
         ChunkRef ch;
         const u32 g = blockIdx.x + (pos++) * gridDim.x;
         ch.valid = g < a.total_chunks;
-        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false;
+        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false; ch.vec = false;
         ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
         if (ch.valid) {
             ch.seg = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
@@ -1148,6 +1177,7 @@ struct BatchChunks {
             ch.c = g - sg.chunk0;
             ch.w = sg.w; ch.w_ref = sg.w_ref; ch.n = sg.n;
             ch.fast = sg.aligned && (u64)(ch.c + 1) * kChunk <= sg.n;
+            ch.vec = sg.aligned != 0;
             ch.slot = a.prov + (u64)g * a.slot_words;
             ch.bits_at = a.chunk_bits + g;
             ch.group_at = a.group_words + sg.group0 + (ch.c >> 6);
