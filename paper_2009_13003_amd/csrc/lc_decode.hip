@@ -306,7 +306,9 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
     const u32 o = wave_incl_scan(lane_bits) - lane_bits;
     const u32* gw = reinterpret_cast<const u32*>(rec + 2 * kW);
     const u32 k0 = (u32)((reinterpret_cast<uintptr_t>(gw) >> 2) & 3);     // words between the 16-byte boundary and the payload
-    const u32 row_zero_bits = zero_bits / (kR * kV) * kV <= 32 ? zero_bits / (kR * kV) * kV : 0u;
+    // 4 merged symbols in a row are this many zero bits (when the merged code is zeros, and short enough to test)
+    const u32 whole_zero = zero_chunk_bits(L.len[K], L.code[K]);
+    const u32 row_zero_bits = whole_zero / (kR * kV) * kV <= 32 ? whole_zero / (kR * kV) * kV : 0u;
     if (nwords + k0 <= kPayWords) {
         // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
         // record's own lane lengths, and the last vector is read word by word so no read passes the end
