@@ -144,3 +144,29 @@ def test_single_call_past_4gib_offsets(lc):
         w[lo:hi] = w_ref[lo:hi] - scale * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
         del u
     full_check(lc, w, w_ref, 4, "n = 2^30 + 100,000,007")
+
+
+def test_largest_n_one_call_takes(lc):
+    """n = LC_MAX_N = 2^32 elements in one call (2^18 chunks, 4096 groups: every per-chunk and per-group array of the
+    scratch area at its full size), in full against the oracle; one element more is refused."""
+    n = 1 << 32
+    g = torch.Generator(device=DEV); g.manual_seed(321)
+    w_ref = torch.empty(n, device=DEV)
+    w = torch.empty(n, device=DEV)
+    piece = 1 << 28
+    for lo in range(0, n, piece):
+        hi = lo + piece
+        w_ref[lo:hi] = 0.05 * torch.randn(piece, generator=g, device=DEV)
+        u = torch.rand(piece, generator=g, device=DEV) - 0.5
+        k = lo // piece
+        scale = 1e-3 * 10.0 ** -(k % 4)                                   # four alternating scales
+        w[lo:hi] = w_ref[lo:hi] - scale * torch.sign(u) * torch.log1p(-2 * u.abs().clamp_(max=0.49999997))
+        if k % 5 == 4:
+            w[lo + piece // 2:hi] = w_ref[lo + piece // 2:hi]                  # long unchanged stretches
+        del u
+    full_check(lc, w, w_ref, 3, "n = 2^32")
+    import ctypes
+    assert lc.lc_encode_bound(n + 1, 3) == 0 and lc.lc_workspace_bytes(n + 1, 3) == 0
+    out = lc.alloc_out(1 << 20, 3, DEV)
+    vp = lambda t: ctypes.c_void_p(t.data_ptr())
+    assert lc._lib.lc_encode(vp(w), vp(w_ref), n + 1, 3, vp(out), None) == -lc.ERR_BADARG
