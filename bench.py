@@ -380,7 +380,7 @@ def main():
     if not args.no_also:
         del job
         torch.cuda.empty_cache()
-        for name in ("llama7b", "single"):
+        for name in ("llama7b", "resnet50", "single"):
             if name == args.workload:
                 continue
             j = Job(name, dev)

@@ -154,22 +154,21 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
 // (codes longer than 12 bits take a short search); the merged symbol adds -0.0, which leaves
 // every fp32 pattern unchanged, and a row in which no lane decoded a kept symbol is not written
 // back at all.
-constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average)
+constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average) when the
+                                     // compute unit is shared by as many workgroups as fit; more when fewer are needed
+constexpr u32 kPayWordsMax = 3808;   // what keeps a workgroup's LDS within 64 KB (7.4 bits per element on average)
 
-template <int WAVES>
-struct DecLdsT {
+struct DecLds {
     uint8_t lut1[1u << kDecLut1Bits];
     uint8_t lut2[1u << kDecLut2Bits];
     float rep[kMaxSym];
     u32 len[kMaxSym], code[kMaxSym];
-    uint4 payload[WAVES][kPayWords / 4 + 1];
     double rep64[kMaxSym];            // binary64 blobs: the representatives (rep is not used then)
     template <int DT> __device__ __forceinline__ typename Val<DT>::type rep_of(u32 sy) const {
         if constexpr (DT == kF64) return rep64[sy];
         else return rep[sy];
     }
 };
-typedef DecLdsT<4> DecLds;
 
 template <typename LDS>
 __device__ __noinline__ u32 decode_long(const LDS& L, u64 win, u32 K) {
@@ -294,10 +293,12 @@ __device__ __forceinline__ u32 zero_chunk_bits(u32 len_merged, u32 code_merged) 
     return (len_merged != 0 && code_merged == 0) ? kR * kV * len_merged : 0u;
 }
 
+// pay: this wavefront's LDS area of pay_words + 4 words for the chunk's payload
 template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
-                                             u32 c, LDS& L, u32 P1, u32 P2, u32 K, u64 area, u32 zero_bits, Raise& raise) {
-    const u32 lane = lane_id(), wv = threadIdx.x >> 6;
+                                             u32 c, LDS& L, uint4* pay, u32 pay_words, u32 P1, u32 P2, u32 K, u64 area,
+                                             u32 zero_bits, Raise& raise) {
+    const u32 lane = lane_id();
     const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
     const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
     const uint8_t* rec = blob + area + 4 * (u64)o0;
@@ -309,7 +310,7 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
     // 4 merged symbols in a row are this many zero bits (when the merged code is zeros, and short enough to test)
     const u32 whole_zero = zero_chunk_bits(L.len[K], L.code[K]);
     const u32 row_zero_bits = whole_zero / (kR * kV) * kV <= 32 ? whole_zero / (kR * kV) * kV : 0u;
-    if (nwords + k0 <= kPayWords) {
+    if (nwords + k0 <= pay_words) {
         // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
         // record's own lane lengths, and the last vector is read word by word so no read passes the end
         const uint4* gv = reinterpret_cast<const uint4*>(gw - k0);
@@ -323,12 +324,12 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
                 const u32 left = nwords + k0 - 4 * i;
                 q.x = t[0]; q.y = left > 1 ? t[1] : 0; q.z = left > 2 ? t[2] : 0; q.w = 0;
             }
-            L.payload[wv][i] = q;
+            pay[i] = q;
             // payload words only: the first vector may start with up to 3 words of lane lengths
             nonzero |= (i == 0) ? ((k0 < 1 ? q.x : 0u) | (k0 < 2 ? q.y : 0u) | (k0 < 3 ? q.z : 0u) | q.w) : (q.x | q.y | q.z | q.w);
         }
         if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
-        decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(L.payload[wv]) + k0, nwords, o, lane_bits,
+        decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
                                          w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
     } else {
         decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
@@ -337,8 +338,10 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
 
 template <int DT>
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
-                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host) {
+                                                Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host,
+                                                u32 pay_words) {
     __shared__ DecLds L;
+    extern __shared__ uint4 dec_pay[];                   // 4 areas of pay_words + 4 payload words, one per wavefront
     // if the check kernel found something, touch nothing
     if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
         const u32 t = threadIdx.x;
@@ -363,15 +366,16 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
         }
         __syncthreads();
         const u32 wave = t >> 6;
+        uint4* pay = dec_pay + wave * (pay_words / 4 + 1);
         const u32 zero_bits = zero_chunk_bits(L.len[K], L.code[K]);
         auto raise = [&](u32 code) { raise_status(ws, host, epoch, code); };
         for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, zero_bits, raise);
-                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, P1, P2, K, area, zero_bits, raise);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
             } else {
-                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, P1, P2, K, area, full ? zero_bits : 0u, raise);
+                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
             }
         }
     }
@@ -439,7 +443,8 @@ __global__ __launch_bounds__(256) void kb_dec_chunks(BatchDecArgs a) {
 }
 
 __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
-    __shared__ DecLdsT<1> L;
+    __shared__ DecLds L;
+    __shared__ uint4 pay[kPayWords / 4 + 1];
     const u32 lane = threadIdx.x;
     u32 active = 0xFFFFFFFFu, M = 0, K = 0, P1 = 0, P2 = 0;
     u64 area = 0;
@@ -471,10 +476,10 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
         const bool full = (u64)(c + 1) * kChunk <= sg.n;
         const u32 zero_bits = full ? zero_chunk_bits(L.len[K], L.code[K]) : 0u;
         if (full && sg.aligned) {
-            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
-            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
+            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         } else {
-            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, P1, P2, K, area, zero_bits, raise);
+            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         }
     }
 }
@@ -877,10 +882,23 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
     const u64 blocks = balanced_workers((nchunks + 3) / 4, (u64)tune.num_cu * tune.decode_blocks_per_cu);
     const dim3 grid((u32)blocks), wg(256);
     const int al = aligned_rows(w_ref, dtype);
-    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
-    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
-    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
-    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, 0, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host);
+    // LDS payload areas: the usual size when every compute unit gets as many workgroups as fit beside each other
+    // (4); with fewer workgroups than that, what the unit's LDS leaves each, so that chunks with long payloads
+    // (codes of 5 and more bits on average) need not read their lane strings from memory
+    const u64 per_cu = (blocks + tune.num_cu - 1) / tune.num_cu;
+    u32 pay_words = kPayWords;
+    if (per_cu < 4) {
+        static_assert(sizeof(DecLds) + 4 * (kPayWordsMax / 4 + 1) * sizeof(uint4) <= 64 * 1024, "one workgroup's LDS");
+        const size_t room = kLdsPerCu / (size_t)per_cu - sizeof(DecLds) - 1024;
+        const u64 fit = room / 16 / 4 * 4 - 4;                      // words per wavefront, a multiple of 4
+        pay_words = (u32)(fit > kPayWordsMax ? kPayWordsMax : fit);
+        if (pay_words < kPayWords) pay_words = kPayWords;
+    }
+    const size_t lds = 4 * (size_t)(pay_words / 4 + 1) * sizeof(uint4);
+    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
+    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
+    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
 }
 
 }  // namespace lc
