@@ -73,16 +73,21 @@ __device__ __forceinline__ void dec_build_luts(DecSet& D, const u32* s_len, cons
         const u32 P = pass ? P2 : P1;
         uint8_t* lut = pass ? D.lut2 : D.lut1;
         if (pass && M <= kDecLut1Bits) break;
-        for (u32 i = t; i < (1u << P); i += nthr) {
-            u32 entry = K;
-            for (u32 j = 0; j <= K; ++j) {
-                const u32 L = s_len[j];
-                if (L == 0) continue;
-                if (L <= P) { if ((i >> (P - L)) == s_code[j]) entry = j | (L << 4); }
-                else if ((s_code[j] >> (L - P)) == i) entry = 0xFF;
+        // every thread of the workgroup takes part: first "starts no code" everywhere, then each code's own range
+        // of prefixes (the ranges of a prefix code do not overlap), all threads sharing the entries of a range
+        for (u32 i = t; i < (1u << P); i += nthr) lut[i] = (uint8_t)K;
+        __syncthreads();
+        for (u32 j = 0; j <= K; ++j) {
+            const u32 L = s_len[j];
+            if (L == 0) continue;
+            if (L <= P) {
+                const u32 first = s_code[j] << (P - L), count = 1u << (P - L);
+                for (u32 i = t; i < count; i += nthr) lut[first + i] = (uint8_t)(j | (L << 4));
+            } else if (t == 0) {
+                lut[s_code[j] >> (L - P)] = 0xFF;
             }
-            lut[i] = (uint8_t)entry;
         }
+        __syncthreads();
     }
 }
 
