@@ -55,6 +55,10 @@ __device__ __forceinline__ u32 wave_max_u32(u32 v) {
     return (u32)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Value of one lane (the same index in every lane), in every lane.
+__device__ __forceinline__ u32 read_lane(u32 v, u32 l) { return (u32)__builtin_amdgcn_readlane((int)v, (int)l); }
+__device__ __forceinline__ u64 read_lane64(u64 v, u32 l) { return ((u64)read_lane((u32)(v >> 32), l) << 32) | read_lane((u32)v, l); }
+
 __device__ __forceinline__ u32 wave_sum32(u32 v) {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);

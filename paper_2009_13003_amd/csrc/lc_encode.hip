@@ -255,9 +255,7 @@ template <int EB>                         // EB: exponent bits of the parameters
 struct TableLds {
     uint8_t sym[2u << EB];
     u64 cnt[kMaxSym + 1];
-    u32 kept[kMaxSym], len[kMaxSym + 1], code[kMaxSym + 1];
-    u32 leaf[kMaxSym], left[kMaxSym], right[kMaxSym], depth[kMaxSym];
-    u64 node_w[kMaxSym];
+    u32 kept[kMaxSym], len[kMaxSym + 1];
 };
 
 // When the sweep before it coded speculatively with a cached table (ws->spec), the kernel also decides
@@ -276,7 +274,7 @@ __device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int
     const u32 lane = lane_id();
     const bool active = threadIdx.x < kW;
     const u32 kmax = (1u << nbits) - 1;
-    if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; S.code[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
+    if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
     u32 total = 0;
     bool nonfinite = false, zero_class = false;
     // binary32: all eight counts of this lane first, the four ranking steps below then run without waiting on memory
@@ -300,89 +298,139 @@ __device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int
         nonfinite = nonfinite || __any(E == kEmax && (c0 | c1) != 0);
         zero_class = zero_class || __any(E == 0 && (c0 | c1) != 0);
     }
+    // The other wavefronts list chunks; the maxima of their first batch are already on their way while the
+    // first wavefront ranks the buckets (a chunk with a ragged end is always read).  Work item t stands for
+    // slot (hi << 9) | lo of the transposed maxima, hi = t / per_row, so that a wavefront's loads fall on a few
+    // cache lines; its chunk is (lo << 9) | hi.  One batch covers the 16384 chunks of a 2^28-element call.
+    constexpr u32 kListBatch = 18;
+    const bool lister = chunk_list && threadIdx.x >= kW;
+    const u32 workers = blockDim.x - kW, list_first = (threadIdx.x - kW) & ~(kW - 1);
+    const u32 nchunks = (u32)num_chunks_of(n), nfull = (u32)(n / kChunk);
+    const u32 per_row = nchunks > 512 ? (nchunks + 511) >> 9 : 1, items = 512 * per_row;
+    const float inv_per_row = 1.0f / (float)per_row;
+    u32 maxima[kListBatch], chunk_of[kListBatch];
+    auto fetch_maxima = [&](u32 t0) {
+#pragma unroll
+        for (u32 u = 0; u < kListBatch; ++u) {
+            const u32 t = t0 + u * workers + lane;
+            u32 hi = (u32)((float)t * inv_per_row);                    // t < 2^18: off by one at most
+            if (hi * per_row > t) --hi; else if ((hi + 1) * per_row <= t) ++hi;
+            const u32 lo = t - hi * per_row, c = (lo << 9) | hi;
+            chunk_of[u] = t < items ? c : 0xFFFFFFFFu;
+            maxima[u] = (t < items && c < nfull) ? chunk_maxexp[(hi << 9) | lo] : 0xFFFFFFFFu;
+        }
+    };
+    if (lister) fetch_maxima(list_first);
     const u32 K = total < kmax ? total : kmax;              // (meaningful in the first wavefront only)
     __syncthreads();
     if (threadIdx.x == 0) { s_min_kept_exp = K ? (S.kept[K - 1] & kEmax) : kEmax + 1; s_listed = 0; }   // kept buckets are in descending exponent order
     __syncthreads();
-    if (chunk_list && threadIdx.x >= kW) {
-        const u32 min_kept_exp = s_min_kept_exp, workers = blockDim.x - kW;
-        const u32 nchunks = (u32)num_chunks_of(n), nfull = (u32)(n / kChunk);
-        for (u32 c0 = (threadIdx.x - kW) & ~(kW - 1); c0 < nchunks; c0 += workers) {
-            const u32 c = c0 + lane;
-            const bool read = c < nchunks && !(c < nfull && chunk_maxexp[maxexp_slot(c)] < min_kept_exp);
-            const u64 m = __ballot(read);
-            if (m == 0) continue;
-            u32 base = 0;
-            if (lane == 0) base = atomicAdd(&s_listed, (u32)__popcll(m));
+    if (lister) {
+        const u32 min_kept_exp = s_min_kept_exp;
+        for (u32 t0 = list_first; t0 < items; t0 += kListBatch * workers) {
+            if (t0 != list_first) fetch_maxima(t0);
+            u64 m[kListBatch];
+            u32 found = 0;
+#pragma unroll
+            for (u32 u = 0; u < kListBatch; ++u) {
+                m[u] = __ballot(chunk_of[u] < nchunks && maxima[u] >= min_kept_exp);
+                found += (u32)__popcll(m[u]);
+            }
+            if (found == 0) continue;
+            u32 base = 0;                                  // one claim on the list per batch
+            if (lane == 0) base = atomicAdd(&s_listed, found);
             base = __builtin_amdgcn_readfirstlane(base);
-            if (read) chunk_list[base + __popcll(m & ((1ull << lane) - 1))] = c;
+#pragma unroll
+            for (u32 u = 0; u < kListBatch; ++u) {
+                if ((m[u] >> lane) & 1) chunk_list[base + __popcll(m[u] & ((1ull << lane) - 1))] = chunk_of[u];
+                base += (u32)__popcll(m[u]);
+            }
         }
     }
-    if (threadIdx.x == 0) {
+    if (active) {
+        // The first wavefront builds the code.  Lane j holds what belongs to symbol j (count, length, code),
+        // to the j-th lightest leaf and to the j-th joined node; single values travel between lanes by
+        // readlane, so that no step waits on memory.
         Table& T = ws->table;
+        u64 c = lane < K ? S.cnt[lane] : 0;
         u64 kept_total = 0;
-        for (u32 j = 0; j < K; ++j) kept_total += S.cnt[j];
-        S.cnt[K] = n - kept_total;
+        for (u32 j = 0; j < K; ++j) kept_total += read_lane64(c, j);
+        if (lane == K) c = n - kept_total;
         const u32 msym = K + 1;
-        u32 max_len = 0;
+        const bool have = lane < msym && c != 0;
+        const u32 nl = (u32)__popcll(__ballot(have));
+        u32 len = 0;
         bool reuse = false;
         if (ws->spec) {
-            reuse = !nonfinite && T.K == K;
-            for (u32 j = 0; j < K && reuse; ++j) reuse = T.kept[j] == S.kept[j];
-            for (u32 j = 0; j < msym && reuse; ++j) reuse = ((T.codelen[j] & 31) != 0) == (S.cnt[j] != 0);
-            if (reuse) for (u32 j = 0; j < msym; ++j) { S.len[j] = T.codelen[j] & 31; if (S.len[j] > max_len) max_len = S.len[j]; }
+            bool differs = false;
+            u32 cached_len = 0;
+            if (lane < K) differs = T.kept[lane] != S.kept[lane];
+            if (lane < msym) { cached_len = T.codelen[lane] & 31; differs = differs || ((cached_len != 0) != (c != 0)); }
+            reuse = !nonfinite && T.K == K && !__any(differs);
+            if (reuse) len = cached_len;
         }
-        s_reuse = reuse;
-        ws->spec_ok = reuse;
-        // leaves in ascending (count, symbol) order
-        u32 nl = 0;
-        if (!reuse) {
-            for (u32 sy = 0; sy < msym; ++sy) {
-                if (S.cnt[sy] == 0) continue;
-                u32 p = nl++;
-                while (p > 0 && S.cnt[S.leaf[p - 1]] > S.cnt[sy]) { S.leaf[p] = S.leaf[p - 1]; --p; }
-                S.leaf[p] = sy;
+        if (!reuse && nl == 1) len = have ? 1u : 0u;
+        if (!reuse && nl >= 2) {
+            // place of every occurring symbol in ascending (count, symbol) order, then the leaves in that order
+            u32 place = 0;
+            for (u32 i = 0; i < msym; ++i) {
+                const u64 ci = read_lane64(c, i);
+                place += (ci != 0 && (ci < c || (ci == c && i < lane))) ? 1u : 0u;
             }
-            if (nl == 1) { S.len[S.leaf[0]] = 1; max_len = 1; }
-            else if (nl >= 2) {
-                // two queues: sorted leaves and joined nodes in creation order (their weights never
-                // decrease); on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
-                u32 li = 0, qi = 0, ni = 0;
-                for (u32 k = 0; k + 1 < nl; ++k) {
-                    u32 pick[2]; u64 wsum = 0;
-                    for (int q = 0; q < 2; ++q) {
-                        const bool take_leaf = li < nl && (qi >= ni || S.cnt[S.leaf[li]] <= S.node_w[qi]);
-                        if (take_leaf) { pick[q] = S.leaf[li]; wsum += S.cnt[S.leaf[li]]; ++li; }
-                        else { pick[q] = 16 + qi; wsum += S.node_w[qi]; ++qi; }
-                    }
-                    S.node_w[ni] = wsum; S.left[ni] = pick[0]; S.right[ni] = pick[1]; ++ni;
+            u64 leaf_w = 0; u32 leaf_sym = 0;
+            for (u32 i = 0; i < msym; ++i) {
+                const u64 ci = read_lane64(c, i);
+                const u32 pi = read_lane(place, i);
+                if (ci != 0 && pi == lane) { leaf_w = ci; leaf_sym = i; }
+            }
+            // two queues: sorted leaves and joined nodes in creation order (their weights never decrease);
+            // on equal weight the leaf is taken first.  Ids >= 16 are joined nodes.
+            u64 node_w = 0; u32 left = 0, right = 0;
+            u32 li = 0, qi = 0, ni = 0;
+            for (u32 k = 0; k + 1 < nl; ++k) {
+                u32 pick[2]; u64 wsum = 0;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const u64 lw = read_lane64(leaf_w, li < nl ? li : 0), nw = read_lane64(node_w, qi < ni ? qi : 0);
+                    const bool take_leaf = li < nl && (qi >= ni || lw <= nw);
+                    if (take_leaf) { pick[q] = read_lane(leaf_sym, li); wsum += lw; ++li; }
+                    else { pick[q] = 16 + qi; wsum += nw; ++qi; }
                 }
-                S.depth[ni - 1] = 0;
-                for (int i = (int)ni - 1; i >= 0; --i) {
-                    const u32 d = S.depth[i] + 1, ch[2] = {S.left[i], S.right[i]};
-                    for (int q = 0; q < 2; ++q) {
-                        if (ch[q] >= 16) S.depth[ch[q] - 16] = d;
-                        else { S.len[ch[q]] = d; if (d > max_len) max_len = d; }
-                    }
+                if (lane == ni) { node_w = wsum; left = pick[0]; right = pick[1]; }
+                ++ni;
+            }
+            u32 depth = 0;                                   // of node `lane`; the root (the last node) has depth 0
+            for (int i = (int)ni - 1; i >= 0; --i) {
+                const u32 d = read_lane(depth, (u32)i) + 1, ch[2] = {read_lane(left, (u32)i), read_lane(right, (u32)i)};
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    if (ch[q] >= 16) { if (lane == ch[q] - 16) depth = d; }
+                    else if (lane == ch[q]) len = d;
                 }
             }
         }
-        // canonical codes by counting codes per length
-        u32 per_len[17], next_code[17];
-        for (int L = 0; L <= 16; ++L) per_len[L] = 0;
-        for (u32 sy = 0; sy < msym; ++sy) per_len[S.len[sy]]++;
-        per_len[0] = 0;
-        u32 code = 0;
-        for (int L = 1; L <= 16; ++L) { code = (code + per_len[L - 1]) << 1; next_code[L] = code; }
-        for (u32 sy = 0; sy < msym; ++sy) if (S.len[sy]) S.code[sy] = next_code[S.len[sy]]++;
-        for (u32 sy = 0; sy < kMaxSym; ++sy) {
-            T.codelen[sy] = sy < msym ? ((S.code[sy] << 5) | S.len[sy]) : 0;
-            T.kept[sy] = sy < K ? S.kept[sy] : 0;
-            T.cnt[sy] = sy < msym ? S.cnt[sy] : 0;
+        // canonical codes: within a length in symbol order, the first code of a length from the counts below it
+        u32 code = 0, first = 0, shorter = 0;
+        for (u32 L = 1; L < kMaxSym; ++L) {
+            const u64 m = __ballot(len == L);
+            first = (first + shorter) << 1;
+            shorter = (u32)__popcll(m);
+            if (len == L) code = first + (u32)__popcll(m & ((1ull << lane) - 1));
         }
-        T.K = K; T.max_len = max_len; T.k_E = total + (zero_class ? 1u : 0u);
-        T.min_kept_exp = s_min_kept_exp;
-        T.status = nonfinite ? 2u : 0u;
+        const u32 max_len = wave_max_u32(len);
+        if (lane < kMaxSym) {
+            T.codelen[lane] = lane < msym ? ((code << 5) | len) : 0;
+            T.kept[lane] = lane < K ? S.kept[lane] : 0;
+            T.cnt[lane] = lane < msym ? c : 0;
+        }
+        if (lane <= kMaxSym) S.len[lane] = len;
+        if (lane == 0) {
+            s_reuse = reuse;
+            ws->spec_ok = reuse;
+            T.K = K; T.max_len = max_len; T.k_E = total + (zero_class ? 1u : 0u);
+            T.min_kept_exp = s_min_kept_exp;
+            T.status = nonfinite ? 2u : 0u;
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) ws->list_count = s_listed;
