@@ -98,6 +98,8 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
         ds.tune.hist_blocks_per_cu = env_int("LC_TUNE_HIST_BLOCKS_PER_CU", ds.tune.hist_blocks_per_cu, 1, 64);
         ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
         ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
+        ds.tune.spec_waves_per_cu = env_int("LC_TUNE_SPEC_WAVES_PER_CU", ds.tune.spec_waves_per_cu, 1, 64);
+        ds.tune.batch_waves_per_cu = env_int("LC_TUNE_BATCH_WAVES_PER_CU", ds.tune.batch_waves_per_cu, 1, 64);
         ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
         ds.tune.fused_waves_per_cu = env_int("LC_TUNE_FUSED_WAVES_PER_CU", ds.tune.fused_waves_per_cu, 1, 32);
         ds.tune.fused_min_waves_per_cu = env_int("LC_TUNE_FUSED_MIN_WAVES_PER_CU", ds.tune.fused_min_waves_per_cu, 1, 32);

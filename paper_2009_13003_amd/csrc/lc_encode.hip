@@ -1339,6 +1339,14 @@ void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* gro
     else hipLaunchKernelGGL(k_table<8>, dim3(1), wg, 0, s, ws, (Ext64*)nullptr, (u64)n, nbits, group_words, ngroups, chunk_maxexp, chunk_list);
 }
 
+// Single-wave workgroups for a sweep over `nchunks` chunks dealt round-robin, at most `cap`: the largest count that
+// gives every wavefront the same number of chunks (to within one), so that none is left with a turn of its own.
+static u32 even_waves(u64 nchunks, u64 cap) {
+    if (nchunks <= cap) return (u32)nchunks;
+    const u64 turns = (nchunks + cap - 1) / cap;
+    return (u32)((nchunks + turns - 1) / turns);
+}
+
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
     hipLaunchKernelGGL(k_spec_table, dim3(1), dim3(64), 0, s, ws, cache, nbits);
 }
@@ -1347,10 +1355,9 @@ void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, 
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
-    if (blocks > nchunks) blocks = nchunks;
+    const u32 blocks = even_waves(nchunks, (u64)tune.num_cu * tune.spec_waves_per_cu);
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
-    const dim3 grid((u32)blocks), wg(64);
+    const dim3 grid(blocks), wg(64);
     if (dtype == kBF16) hipLaunchKernelGGL(k_spec_sweep<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kF16) hipLaunchKernelGGL(k_spec_sweep<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
     else hipLaunchKernelGGL(k_spec_sweep<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, prov, slot_words, (u32)nchunks, al);
@@ -1362,10 +1369,9 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
                  uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    u64 blocks = (u64)tune.num_cu * tune.pack_waves_per_cu;
-    if (blocks > nchunks) blocks = nchunks;
+    const u32 blocks = even_waves(nchunks, (u64)tune.num_cu * tune.pack_waves_per_cu);
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
-    const dim3 grid((u32)blocks), wg(64);
+    const dim3 grid(blocks), wg(64);
     if (dtype == kF64) hipLaunchKernelGGL(k_pack64, grid, wg, 0, s, w, w_ref, (u64)n, ws, &ws->ext64, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
@@ -1394,14 +1400,12 @@ void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s) 
     if (setup_blocks < 1) setup_blocks = 1;
     hipLaunchKernelGGL(kb_setup, dim3(setup_blocks), dim3(256), 0, s, a);
     if (a.total_chunks) {
-        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
-        if (waves > a.total_chunks) waves = a.total_chunks;
+        const u32 waves = even_waves(a.total_chunks, (u64)tune.num_cu * tune.batch_waves_per_cu);
         hipLaunchKernelGGL(kb_hist, dim3(waves), dim3(64), 0, s, a);
     }
     hipLaunchKernelGGL(kb_table, dim3(a.count), dim3(64), 0, s, a);
     if (a.total_chunks) {
-        u32 waves = (u32)tune.num_cu * (u32)tune.pack_waves_per_cu;
-        if (waves > a.total_chunks) waves = a.total_chunks;
+        const u32 waves = even_waves(a.total_chunks, (u64)tune.num_cu * tune.batch_waves_per_cu);
         hipLaunchKernelGGL(kb_pack, dim3(waves), dim3(64), 0, s, a);
         hipLaunchKernelGGL(kb_place, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
     }

@@ -132,7 +132,9 @@ struct Tuning {
     int num_cu = 256;
     int hist_blocks_per_cu = 1;
     int hist_threads = 256;
-    int pack_waves_per_cu = 6;
+    int pack_waves_per_cu = 8;         // single-wave workgroups of k_pack per compute unit
+    int spec_waves_per_cu = 6;         // of the single sweep of the cached encode
+    int batch_waves_per_cu = 8;        // of the batch kernels
     int decode_blocks_per_cu = 9;     // (LDS lets 4 run at once; more, smaller shares even out chunks that decode to nothing)
     int fused_waves_per_cu = 16;       // most wavefronts per compute unit
     int fused_min_waves_per_cu = 8;    // a sweep takes as many blobs as still leave LDS for this many
