@@ -124,6 +124,15 @@ __device__ __forceinline__ u32 narrow16(float x, bool bf16) {      // finite x, 
     return (u32)__builtin_bit_cast(unsigned short, (_Float16)x);      // v_cvt_f16_f32, round to nearest even
 }
 
+// Two values at once, a in the low half.  bf16: v_cvt_pk_bf16_f32, which rounds every finite binary32 value as the
+// integer formula above does (compared over all 2^32 patterns); infinities stay infinities.
+typedef __bf16 lc_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float lc_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32 narrow16_pair(float a, float b, bool bf16) {
+    if (bf16) { const lc_f32x2 f = {a, b}; return __builtin_bit_cast(u32, __builtin_convertvector(f, lc_bf16x2)); }
+    return narrow16(a, false) | (narrow16(b, false) << 16);
+}
+
 __device__ __forceinline__ void unpack64(const Row64& r, double (&x)[4]) {
 #pragma unroll
     for (int v = 0; v < 4; ++v) x[v] = r.x[v];
@@ -156,8 +165,7 @@ __device__ __forceinline__ void store4(void* base, u64 i, const float (&x)[4]) {
         *reinterpret_cast<float4*>(static_cast<float*>(base) + i) = make_float4(x[0], x[1], x[2], x[3]);
     } else {
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(base) + i) =
-            make_uint2(narrow16(x[0], DT == kBF16) | (narrow16(x[1], DT == kBF16) << 16),
-                       narrow16(x[2], DT == kBF16) | (narrow16(x[3], DT == kBF16) << 16));
+            make_uint2(narrow16_pair(x[0], x[1], DT == kBF16), narrow16_pair(x[2], x[3], DT == kBF16));
     }
 }
 
