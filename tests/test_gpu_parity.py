@@ -657,6 +657,51 @@ def test_16_bit_parameters_match_oracle(lc, tdt, n, nbits, offset):
     assert torch.equal(rec[offset + n:].view(torch.int16), buf_r[offset + n:].view(torch.int16))
 
 
+@pytest.mark.parametrize("offset", [0, 1])
+def test_bf16_restore_rounds_ties_subnormals_and_overflow_like_the_oracle(lc, offset):
+    """Restored bf16 values that land exactly between two neighbours (both parities), on half the smallest
+    subnormal (either sign) and above the largest finite value: the vector path narrows with the hardware
+    conversion, the guarded path (offset 1) with integers, the oracle with integers."""
+    def bf(bits):
+        return torch.tensor(bits, dtype=torch.int16).view(torch.bfloat16)
+    # (w_ref, [w choices]) as bf16 bit patterns
+    one, one1 = 0x3F80, 0x3F81                    # 1, 1 + 2^-7
+    groups = [
+        (one, [0x3F82, 0x3F83]),                  # delta 2^-6, 3*2^-7 -> rep 5*2^-8: 1 + 5*2^-8 is a tie, even neighbour below
+        (one1, [0x3F83, 0x3F84]),                 # same deltas from an odd mantissa: tie, even neighbour above
+        (0x8080, [0x0000, 0x0001]),               # w_ref = -2^-126, w in {0, 2^-133}: rep 2^-126 (1 + 2^-8) -> +2^-134
+        (0x8081, [0x8001, 0x0000]),               # w_ref = -2^-126 (1 + 2^-7): restored -2^-134
+        (0x7F7D, [0x7F7F]),                       # largest finite minus 2 ulp, delta 2 ulp
+        (0x0000, [0x7C60]),                       # delta 1.75 * 2^121 in the same bucket: rep 2.75 ulp -> above the largest finite
+    ]
+    reps = 2600
+    r_bits, w_bits = [], []
+    for k in range(reps):
+        for ref, ws in groups:
+            r_bits.append(ref); w_bits.append(ws[k % len(ws)])
+    n = len(r_bits)
+    to_i16 = lambda v: [x - 65536 if x >= 32768 else x for x in v]
+    buf_r = torch.zeros(n + 8, dtype=torch.bfloat16); buf_w = torch.zeros(n + 8, dtype=torch.bfloat16)
+    buf_r[offset:offset + n] = bf(to_i16(r_bits)); buf_w[offset:offset + n] = bf(to_i16(w_bits))
+    buf_r, buf_w = buf_r.to(DEV), buf_w.to(DEV)
+    w, w_ref = buf_w[offset:offset + n], buf_r[offset:offset + n]
+    nbits = 3
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode_t(w, w_ref, nbits, out)
+    blob_cpu = orc.encode_t(raw16(w), raw16(w_ref), nbits, orc.DT_BF16)
+    assert np.array_equal(out[:size].cpu().numpy(), blob_cpu)
+    rec = buf_r.clone()
+    assert lc.lc_decode_t(out, rec[offset:offset + n]) == size
+    ref_h = raw16(w_ref)
+    orc.decode_t(blob_cpu, ref_h, orc.DT_BF16)
+    got = raw16(rec[offset:offset + n])
+    assert np.array_equal(got, ref_h)
+    per_group = got[:len(groups) * 2].reshape(2, len(groups))
+    assert per_group[0].tolist() == [0x3F82, 0x3F84, 0x0000, 0x8000, 0x7F80, 0x7C30]      # the cases the groups aim at do occur
+    assert torch.equal(rec[:offset].view(torch.int16), buf_r[:offset].view(torch.int16))
+    assert torch.equal(rec[offset + n:].view(torch.int16), buf_r[offset + n:].view(torch.int16))
+
+
 def test_element_type_mismatch_is_refused(lc):
     n, nbits = 16384 + 9, 3
     w, w_ref = laplace_case(n, seed=70)
