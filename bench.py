@@ -340,8 +340,8 @@ def main():
                          "written per launch): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
-        raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by "
-                         "independent slices, see DESIGN.md")
+        raise SystemExit("bench.py: this build runs on one GPU only (--gpus 1); more GPUs would each take "
+                         "independent slices of the parameter vector, with no exchange between them")
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)

@@ -173,6 +173,10 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
 #define LC_CACHE_BYTES 256
 lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits,
                           void* out, void* cache, int* used, void* stream);
+/* The same for parameters stored as bf16 or fp16 (dtype as for lc_encode_t; a cache serves any of LC_F32, LC_BF16,
+ * LC_F16, since all three code the fp32 delta; LC_F64: LC_ERR_BADARG). */
+lc_ssize lc_encode_cached_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype,
+                            void* cache, int* used, void* stream);
 
 /*
  * Asynchronous form (Section 3.2, "Asynchronous Execution": only the first step depends on the model
@@ -190,6 +194,9 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
  */
 #define LC_MAX_TICKETS 16
 int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream);
+/* lc_encode_async for parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: -LC_ERR_BADARG). */
+int lc_encode_async_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* cache,
+                      void* stream);
 int lc_encode_release_inputs(int ticket, void* other_stream);
 lc_ssize lc_encode_wait(int ticket, int* used);
 

@@ -274,6 +274,15 @@ def encode_t(w, w_ref, nbits, dtype):
     return blob
 
 
+def encode_cached_t(w, w_ref, nbits, dtype, cache):
+    """encode_cached on the exactly widened vectors (16-bit storage types code the fp32 delta, as in encode_t);
+    the blob names the storage type.  Returns (blob, used_cache)."""
+    assert dtype in (DT_F32, DT_BF16, DT_F16)
+    blob, used = encode_cached(widen(w, dtype), widen(w_ref, dtype), nbits, cache)
+    blob[60:64] = np.frombuffer(np.uint32(dtype).tobytes(), np.uint8)
+    return blob, used
+
+
 def decode_t(blob, w_ref, dtype):
     """Updates w_ref (storage type array) in place; returns bytes consumed."""
     blob = np.ascontiguousarray(blob, dtype=np.uint8)

@@ -179,7 +179,7 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
                      int* used, void* stream, bool async) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
     if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
-    if (dtype == LC_F64 && (cache || async)) return -LC_ERR_BADARG;          // those entry points take fp32 only
+    if (dtype == LC_F64 && (cache || async)) return -LC_ERR_BADARG;          // those forms code the fp32 delta only
     const uintptr_t esize = dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2;
     if (n && (!w || !w_ref || misaligned(w, esize) || misaligned(w_ref, esize))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -253,9 +253,14 @@ lc_ssize lc_encode_t(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     return encode_impl(w, w_ref, n, nbits, out, dtype, nullptr, nullptr, stream, false);
 }
 
-int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream) {
+int lc_encode_async_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* cache,
+                      void* stream) {
     if (cache && misaligned(cache, 16)) return -LC_ERR_BADARG;
-    return (int)encode_impl(w, w_ref, n, nbits, out, LC_F32, static_cast<TableCache*>(cache), nullptr, stream, true);
+    return (int)encode_impl(w, w_ref, n, nbits, out, dtype, static_cast<TableCache*>(cache), nullptr, stream, true);
+}
+
+int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream) {
+    return lc_encode_async_t(w, w_ref, n, nbits, out, LC_F32, cache, stream);
 }
 
 int lc_encode_release_inputs(int ticket, void* other_stream) {
@@ -282,11 +287,16 @@ lc_ssize lc_encode_wait(int ticket, int* used) {
     return (lc_ssize)r.bytes;
 }
 
-lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, int* used,
-                          void* stream) {
+lc_ssize lc_encode_cached_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* cache,
+                            int* used, void* stream) {
     if (used) *used = 0;
     if (!cache || misaligned(cache, 16)) return -LC_ERR_BADARG;
-    return encode_impl(w, w_ref, n, nbits, out, LC_F32, static_cast<TableCache*>(cache), used, stream, false);
+    return encode_impl(w, w_ref, n, nbits, out, dtype, static_cast<TableCache*>(cache), used, stream, false);
+}
+
+lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, int* used,
+                          void* stream) {
+    return lc_encode_cached_t(w, w_ref, n, nbits, out, LC_F32, cache, used, stream);
 }
 
 lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream) {

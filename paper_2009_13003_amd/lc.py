@@ -42,6 +42,10 @@ _lib.lc_decode_batch.restype = _i64
 _lib.lc_decode_batch.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, ctypes.POINTER(_i64), _vp]
 _lib.lc_encode_cached.restype = _i64
 _lib.lc_encode_cached.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, ctypes.POINTER(_int), _vp]
+_lib.lc_encode_cached_t.restype = _i64
+_lib.lc_encode_cached_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp, ctypes.POINTER(_int), _vp]
+_lib.lc_encode_async_t.restype = _int
+_lib.lc_encode_async_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp, _vp]
 _lib.lc_encode_async.restype = _int
 _lib.lc_encode_async.argtypes = [_vp, _vp, _u64, _int, _vp, _vp, _vp]
 _lib.lc_encode_release_inputs.restype = _int
@@ -239,6 +243,38 @@ def lc_encode_cached(w, w_ref, nbits, out, cache, stream=None, n=None):
     if r < 0:
         raise LcError(-r)
     return r, bool(used.value)
+
+
+def lc_encode_cached_t(w, w_ref, nbits, out, cache, stream=None, n=None):
+    """lc_encode_cached for float32, bfloat16 or float16 parameters (w and w_ref of the same dtype)."""
+    n = w.numel() if n is None else n
+    assert w.dtype == w_ref.dtype
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    assert cache.is_cuda and cache.dtype == torch.uint8 and cache.is_contiguous() and cache.numel() >= CACHE_BYTES
+    used = _int(0)
+    r = int(_lib.lc_encode_cached_t(_dev_any(w), _dev_any(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), DTYPES[w.dtype],
+                                    ctypes.c_void_p(cache.data_ptr()), ctypes.byref(used), _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r, bool(used.value)
+
+
+def lc_encode_async_t(w, w_ref, nbits, out, cache=None, stream=None, n=None):
+    """lc_encode_async for float32, bfloat16 or float16 parameters."""
+    n = w.numel() if n is None else n
+    assert w.dtype == w_ref.dtype
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    c = None
+    if cache is not None:
+        assert cache.is_cuda and cache.dtype == torch.uint8 and cache.is_contiguous() and cache.numel() >= CACHE_BYTES
+        c = ctypes.c_void_p(cache.data_ptr())
+    r = int(_lib.lc_encode_async_t(_dev_any(w), _dev_any(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), DTYPES[w.dtype], c,
+                                   _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
 
 
 def lc_encode_async(w, w_ref, nbits, out, cache=None, stream=None, n=None):

@@ -508,6 +508,51 @@ def test_cached_encode_chain_matches_oracle(lc, nbits, n):
     assert verdicts[0] is False and verdicts[5] is False and any(verdicts[1:5]), verdicts
 
 
+@pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
+def test_cached_and_async_encode_of_16_bit_parameters(lc, tdt):
+    """lc_encode_cached_t / lc_encode_async_t: a chain of bf16 / fp16 checkpoints, blob, verdict and cache as the
+    oracle's at every step, hits and a miss both occur; the asynchronous form gives the same blobs; fp64 is refused."""
+    code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+    nbits, n = 3, 7 * 16384 + 321
+    g = torch.Generator(device=DEV); g.manual_seed(321)
+    w = (0.05 * torch.randn(n, generator=g, device=DEV)).to(tdt)
+    tracked = w.clone()
+    out, out2 = lc.alloc_out(n, nbits, DEV), lc.alloc_out(n, nbits, DEV)
+    cache_gpu, cache_cpu, cache_async = lc.new_cache(DEV), orc.new_cache(), lc.new_cache(DEV)
+    verdicts = []
+    for t in range(6):
+        d = 2e-3 * torch.randn(n, generator=g, device=DEV)
+        d[:4] = torch.tensor([0.02, -0.02, 0.011, -0.011], device=DEV)
+        if t == 4:
+            d[9] = 0.4                                                        # a new largest exponent: miss
+        w = (w.float() + d).to(tdt)
+        size, used = lc.lc_encode_cached_t(w, tracked, nbits, out, cache_gpu)
+        blob_cpu, used_cpu = orc.encode_cached_t(raw16(w), raw16(tracked), nbits, code, cache_cpu)
+        blob_gpu = out[:size].cpu().numpy()
+        assert used == used_cpu, t
+        assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+        assert np.array_equal(cache_gpu.cpu().numpy()[:4 * orc.CACHE_WORDS].view(np.uint32), cache_cpu)
+        verdicts.append(used)
+        ticket = lc.lc_encode_async_t(w, tracked, nbits, out2, cache_async)
+        size2, used2 = lc.lc_encode_wait(ticket)
+        assert size2 == size and used2 == used and torch.equal(out2[:size2], out[:size])
+        ref_h = raw16(tracked)
+        orc.decode_t(blob_cpu, ref_h, code)
+        assert lc.lc_decode_t(out, tracked) == size
+        assert np.array_equal(raw16(tracked).view(np.uint16), ref_h.view(np.uint16))
+    assert verdicts[0] is False and verdicts[4] is False and any(verdicts[1:4]), verdicts
+    ticket = lc.lc_encode_async_t(w, tracked, nbits, out2)                    # without a cache: lc_encode_t's blob
+    size2, used2 = lc.lc_encode_wait(ticket)
+    assert not used2 and size2 == lc.lc_encode_t(w, tracked, nbits, out) and torch.equal(out2[:size2], out[:size2])
+    w64 = w.double()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_cached_t(w64, w64.clone(), nbits, out, cache_gpu)
+    assert e.value.status == lc.ERR_BADARG
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_async_t(w64, w64.clone(), nbits, out)
+    assert e.value.status == lc.ERR_BADARG
+
+
 def test_cached_encode_edge_cases(lc):
     nbits, n = 3, 2 * 16384 + 99
     w, w_ref = laplace_case(n, seed=41)

@@ -651,3 +651,35 @@ def test_16_bit_parameters_round_trip_against_torch(dtype):
     with pytest.raises(orc.OracleError) as e:
         orc.decode_t(orc.encode(w_t.float().numpy(), ref_t.float().numpy(), nbits), got, code)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_cached_encode_of_16_bit_parameters_is_the_fp32_method_on_the_widened_vectors(dtype):
+    """encode_cached_t: with an empty cache the blob is encode_t's; a hit keeps kept buckets, counts and
+    representatives (bytes 64.. of every slot but the length), names the storage type, and restores the same
+    values as encode_t's blob (torch's casts give the 16-bit inputs)."""
+    torch = pytest.importorskip("torch")
+    tdt, code = (torch.bfloat16, orc.DT_BF16) if dtype == "bf16" else (torch.float16, orc.DT_F16)
+    g = torch.Generator().manual_seed(11)
+    n, nbits = lcb1_reader.C + 77, 3
+    ref_t = (0.05 * torch.randn(n, generator=g)).to(tdt)
+    raw = (lambda t: t.view(torch.int16).numpy().view(np.uint16).copy()) if dtype == "bf16" else (lambda t: t.numpy().copy())
+    cache = orc.new_cache()
+    blobs = []
+    for step in range(2):
+        w_t = (ref_t.float() + 2e-3 * torch.randn(n, generator=g)).to(tdt)
+        # the seven largest buckets occupied at every step, so that the kept set repeats
+        w_t[:7] = (ref_t[:7].float() + torch.tensor([0.02, -0.02, 0.011, -0.011, 0.005, -0.005, 0.0025])).to(tdt)
+        plain = orc.encode_t(raw(w_t), raw(ref_t), nbits, code)
+        blob, used = orc.encode_cached_t(raw(w_t), raw(ref_t), nbits, code, cache)
+        assert used == (step == 1)
+        assert int(np.frombuffer(blob[60:64].tobytes(), np.uint32)[0]) == code
+        if step == 0:
+            assert np.array_equal(blob, plain)
+        hp, hc = lcb1_reader.parse_header(plain), lcb1_reader.parse_header(blob)
+        for a, b in zip(hp["slots"], hc["slots"]):
+            assert (a["bucket"], a["rep_bits"], a["cnt"]) == (b["bucket"], b["rep_bits"], b["cnt"])
+        r1, r2 = raw(ref_t), raw(ref_t)
+        orc.decode_t(plain, r1, code); orc.decode_t(blob, r2, code)
+        assert np.array_equal(r1.view(np.uint16), r2.view(np.uint16))
+        blobs.append(blob)
