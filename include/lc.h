@@ -226,6 +226,10 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
  * returns the sum of the bytes consumed or -(lc_status).
  */
 lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream);
+/* The same for parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: LC_ERR_BADARG), every blob of that
+ * type: bit for bit what `count` successive lc_decode_t calls give, i.e. the running value is rounded to the
+ * storage type after every blob's addition. */
+lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint64_t n, int dtype, void* stream);
 
 /*
  * Many vectors in one call, each with a table of its own: tensor t is coded exactly as

@@ -329,8 +329,13 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {
 }
 
 lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream) {
+    return lc_decode_many_t(blobs, count, w_ref, n, LC_F32, stream);
+}
+
+lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint64_t n, int dtype, void* stream) {
     if (!blobs || count < 1 || count > LC_MAX_MANY || n > LC_MAX_N) return -LC_ERR_BADARG;
-    if (n && (!w_ref || misaligned(w_ref, 4))) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : 2))) return -LC_ERR_BADARG;
     for (int i = 0; i < count; ++i) if (!blobs[i] || misaligned(blobs[i], 16)) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     int err = 0; DeviceState* ds = nullptr;
@@ -342,7 +347,7 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[t < count ? t : 0]);
     // every blob is validated (one launch, one grid row per blob) before w_ref is touched
-    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, LC_F32, bound, ws, epoch, g_pinned_dev, s); }
+    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, dtype, bound, ws, epoch, g_pinned_dev, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
     ds->pending = false;
@@ -374,7 +379,7 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
         {
             const uint32_t pay_words = pay_words_of(words);
             Timed tm(kSlotDecodeFused, s);
-            launch_decode_fused(list, g0, T, w_ref, n, ws, epoch, g_pinned_dev, pay_words, !short_codes, ds->tune, s);
+            launch_decode_fused(list, g0, T, w_ref, n, dtype, ws, epoch, g_pinned_dev, pay_words, !short_codes, ds->tune, s);
         }
         LC_HIP(hipGetLastError());
         g0 += T;

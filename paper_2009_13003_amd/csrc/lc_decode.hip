@@ -544,9 +544,9 @@ constexpr u32 kFusedSlack = 128;                 // words behind the payloads th
 // LONG: some blob of the sweep has codes longer than 7 bits.  Two codes then take up to 30 bits, so the window is
 // re-read after the second code of a row, and a window that starts with a long code is ranked against the long
 // codes (a handful of compares; rare, since long codes belong to rare symbols).
-template <int T, bool FAST, bool STAGED, bool LONG>
+template <int T, bool FAST, bool STAGED, bool LONG, int DT>
 __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
-                                          const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u64 idx,
+                                          const u32 (&nw)[T], u32 (&pos)[T], void* __restrict__ w_ref, u64 n, u64 idx,
                                           float (&x)[4]) {
     // Written step by step across the blobs (all windows, then the first code of every blob, ...), so
     // that the T look-ups of a step are in flight together.
@@ -606,16 +606,16 @@ __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay,
 #pragma unroll
             for (int v = 0; v < 4; ++v)
 #pragma unroll
-                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));   // in blob order
-            *reinterpret_cast<float4*>(w_ref + idx) = make_float4(x[0], x[1], x[2], x[3]);
+                for (int t = 0; t < T; ++t) x[v] = stored<DT>(__fadd_rn(x[v], __uint_as_float(rep[v][t])));   // in blob order
+            store4<DT>(w_ref, idx, x);
         }
     } else {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             if (idx + v < n) {
 #pragma unroll
-                for (int t = 0; t < T; ++t) x[v] = __fadd_rn(x[v], __uint_as_float(rep[v][t]));
-                w_ref[idx + v] = x[v];
+                for (int t = 0; t < T; ++t) x[v] = stored<DT>(__fadd_rn(x[v], __uint_as_float(rep[v][t])));
+                store_one<DT>(w_ref, idx + v, x[v]);
             }
         }
     }
@@ -623,47 +623,48 @@ __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay,
 
 // All rows of a full, aligned chunk with staged payloads: w_ref is read PF rows ahead in two
 // alternating register batches, so the reads of the next rows are in flight while these decode.
-template <int T, bool LONG>
+template <int T, bool LONG, int DT>
 __device__ __forceinline__ void fused_rows_fast(const FusedHead<T>& H, const u32* pay, u32 pay_words, const u32* const (&gw)[T],
-                                                const u32 (&nw)[T], u32 (&pos)[T], float* __restrict__ w_ref, u64 n, u32 c) {
+                                                const u32 (&nw)[T], u32 (&pos)[T], void* __restrict__ w_ref, u64 n, u32 c) {
     constexpr int PF = 4;
+    typedef typename Raw<DT>::type RowT;
     const u32 lane = lane_id();
-    float4* rows = reinterpret_cast<float4*>(w_ref + (u64)c * kChunk) + lane;
     const u64 base = (u64)c * kChunk + lane * kV;
-    float4 A[PF], B[PF];
+    RowT A[PF], B[PF];
 #pragma unroll
-    for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + k * kW);
-    auto batch = [&](float4 (&X)[PF], u32 r0) {
+    for (int k = 0; k < PF; ++k) A[k] = load_raw<DT>(w_ref, base + (u64)k * kRowElems);
+    auto batch = [&](RowT (&X)[PF], u32 r0) {
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
-            float x[4] = {X[k].x, X[k].y, X[k].z, X[k].w};
-            fused_row<T, true, true, LONG>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
+            float x[4];
+            unpack<DT>(X[k], x);
+            fused_row<T, true, true, LONG, DT>(H, pay, pay_words, gw, nw, pos, w_ref, n, base + (u64)(r0 + k) * kRowElems, x);
         }
     };
     for (u32 r0 = 0; r0 < kR; r0 += 2 * PF) {
 #pragma unroll
-        for (int k = 0; k < PF; ++k) B[k] = load_stream(rows + (r0 + PF + k) * kW);
+        for (int k = 0; k < PF; ++k) B[k] = load_raw<DT>(w_ref, base + (u64)(r0 + PF + k) * kRowElems);
         batch(A, r0);
         if (r0 + 2 * PF < kR) {
 #pragma unroll
-            for (int k = 0; k < PF; ++k) A[k] = load_stream(rows + (r0 + 2 * PF + k) * kW);
+            for (int k = 0; k < PF; ++k) A[k] = load_raw<DT>(w_ref, base + (u64)(r0 + 2 * PF + k) * kRowElems);
         }
         batch(B, r0 + PF);
     }
 }
 
 // Any chunk (ragged, unaligned, or payloads read from memory), row by row.
-template <int T, bool FAST, bool LONG>
+template <int T, bool FAST, bool LONG, int DT>
 __device__ __forceinline__ void fused_rows_plain(const FusedHead<T>& H, const u32* const (&gw)[T], const u32 (&nw)[T], u32 (&pos)[T],
-                                              float* __restrict__ w_ref, u64 n, u32 c) {
+                                              void* __restrict__ w_ref, u64 n, u32 c) {
     const u32 lane = lane_id();
     const u64 base = (u64)c * kChunk;
     for (u32 r = 0; r < kR; ++r) {
         const u64 idx = base + (u64)r * kRowElems + lane * kV;
         if (!FAST && idx >= n) break;
         float x[4];
-        load_row<FAST>(w_ref, idx, n, x);
-        fused_row<T, FAST, false, LONG>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
+        load_row<FAST, DT>(w_ref, idx, n, x);
+        fused_row<T, FAST, false, LONG, DT>(H, nullptr, 0, gw, nw, pos, w_ref, n, idx, x);
     }
 }
 
@@ -674,8 +675,8 @@ __device__ __forceinline__ P* uniform_ptr(P* p) {        // a pointer every lane
     return reinterpret_cast<P*>(((u64)hi << 32) | lo);
 }
 
-template <int T, bool FAST, bool LONG>
-__device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32 pay_words, float* __restrict__ w_ref, u64 n,
+template <int T, bool FAST, bool LONG, int DT>
+__device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32 pay_words, void* __restrict__ w_ref, u64 n,
                                             Workspace* ws, HostResult* host, u32 c, u32 nchunks, u64 epoch) {
     const u32 lane = lane_id();
     const u32* gw[T];
@@ -750,11 +751,11 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
     if (staged) {
 #pragma unroll
         for (int t = 0; t < T; ++t) { start[t] += 32 * (wbase[t] + k0[t]); pos[t] = start[t]; }
-        fused_rows_fast<T, LONG>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
+        fused_rows_fast<T, LONG, DT>(H, pay, pay_words, gw, nw, pos, w_ref, n, c);
     } else {
 #pragma unroll
         for (int t = 0; t < T; ++t) pos[t] = start[t];
-        fused_rows_plain<T, FAST, LONG>(H, gw, nw, pos, w_ref, n, c);
+        fused_rows_plain<T, FAST, LONG, DT>(H, gw, nw, pos, w_ref, n, c);
     }
     bool bad = false;
 #pragma unroll
@@ -762,8 +763,8 @@ __device__ __forceinline__ void fused_chunk(const FusedHead<T>& H, u32* pay, u32
     if (__any(bad) && lane == 0) raise_status(ws, host, epoch, 4u);
 }
 
-template <int T, bool LONG>
-__global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, float* __restrict__ w_ref, u64 n,
+template <int T, bool LONG, int DT>
+__global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, void* __restrict__ w_ref, u64 n,
                                                      Workspace* ws, u32 nchunks, int aligned, u64 epoch,
                                                      HostResult* host, u32 pay_words) {
     __shared__ FusedHead<T> H;
@@ -809,8 +810,8 @@ __global__ __launch_bounds__(64) void k_decode_fused(BlobList blobs, u32 first, 
     __syncthreads();
     for (u32 c = blockIdx.x; c < nchunks; c += gridDim.x) {
         const bool full = (u64)(c + 1) * kChunk <= n;
-        if (full && aligned) fused_chunk<T, true, LONG>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
-        else fused_chunk<T, false, LONG>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        if (full && aligned) fused_chunk<T, true, LONG, DT>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
+        else fused_chunk<T, false, LONG, DT>(H, pay, pay_words, w_ref, n, ws, host, c, nchunks, epoch);
     }
 }
 // ----------------------------------------------------------------------------- launchers
@@ -840,14 +841,23 @@ void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, i
 
 
 
-template <int T>
-static void launch_fused_t(const BlobList& blobs, int first, float* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
-                           HostResult* host, u32 blocks, u32 pay_words, bool long_codes, hipStream_t s) {
+template <int T, int DT>
+static void launch_fused_td(const BlobList& blobs, int first, void* w_ref, uint64_t n, Workspace* ws, uint64_t epoch,
+                            HostResult* host, u32 blocks, u32 pay_words, bool long_codes, hipStream_t s) {
     const size_t lds = 4 * (size_t)(pay_words + kFusedSlack);
-    if (long_codes) hipLaunchKernelGGL((k_decode_fused<T, true>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
-                                       (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
-    else hipLaunchKernelGGL((k_decode_fused<T, false>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
-                            (u64)n, ws, (u32)num_chunks_of(n), (int)aligned16(w_ref), (u64)epoch, host, pay_words);
+    const int al = aligned_rows(w_ref, DT);
+    if (long_codes) hipLaunchKernelGGL((k_decode_fused<T, true, DT>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
+                                       (u64)n, ws, (u32)num_chunks_of(n), al, (u64)epoch, host, pay_words);
+    else hipLaunchKernelGGL((k_decode_fused<T, false, DT>), dim3(blocks), dim3(64), lds, s, blobs, (u32)first, w_ref,
+                            (u64)n, ws, (u32)num_chunks_of(n), al, (u64)epoch, host, pay_words);
+}
+
+template <int T>
+static void launch_fused_t(const BlobList& blobs, int first, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch,
+                           HostResult* host, u32 blocks, u32 pay_words, bool long_codes, hipStream_t s) {
+    if (dtype == kBF16) launch_fused_td<T, kBF16>(blobs, first, w_ref, n, ws, epoch, host, blocks, pay_words, long_codes, s);
+    else if (dtype == kF16) launch_fused_td<T, kF16>(blobs, first, w_ref, n, ws, epoch, host, blocks, pay_words, long_codes, s);
+    else launch_fused_td<T, kF32>(blobs, first, w_ref, n, ws, epoch, host, blocks, pay_words, long_codes, s);
 }
 
 size_t fused_lds_bytes(int count, uint32_t pay_words) {
@@ -856,7 +866,7 @@ size_t fused_lds_bytes(int count, uint32_t pay_words) {
     return head[count - 1] + 4 * (size_t)(pay_words + kFusedSlack);
 }
 
-void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+void launch_decode_fused(const BlobList& blobs, int first, int count, void* w_ref, uint64_t n, int dtype, Workspace* ws,
                          uint64_t epoch, HostResult* host, uint32_t pay_words, bool long_codes, const Tuning& tune,
                          hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
@@ -869,14 +879,14 @@ void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_r
     if (blocks > nchunks) blocks = nchunks;
     const u32 b = (u32)blocks;
     switch (count) {
-        case 1: launch_fused_t<1>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 2: launch_fused_t<2>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 3: launch_fused_t<3>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 4: launch_fused_t<4>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 5: launch_fused_t<5>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 6: launch_fused_t<6>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        case 7: launch_fused_t<7>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
-        default: launch_fused_t<8>(blobs, first, w_ref, n, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 1: launch_fused_t<1>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 2: launch_fused_t<2>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 3: launch_fused_t<3>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 4: launch_fused_t<4>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 5: launch_fused_t<5>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 6: launch_fused_t<6>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        case 7: launch_fused_t<7>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
+        default: launch_fused_t<8>(blobs, first, w_ref, n, dtype, ws, epoch, host, b, pay_words, long_codes, s); break;
     }
 }
 

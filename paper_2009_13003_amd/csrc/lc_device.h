@@ -147,6 +147,13 @@ __device__ __forceinline__ void unpack(const typename Raw<DT>::type& r, float (&
     }
 }
 
+// x as it reads back after a store in the storage type (rounded to nearest even; binary32: x itself)
+template <int DT>
+__device__ __forceinline__ float stored(float x) {
+    if constexpr (DT == kF32) return x;
+    else return widen16(narrow16(x, DT == kBF16), DT == kBF16);
+}
+
 template <int DT>
 __device__ __forceinline__ float load_one(const void* base, u64 i) {
     if constexpr (DT == kF32) return static_cast<const float*>(base)[i];

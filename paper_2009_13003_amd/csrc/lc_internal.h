@@ -194,7 +194,7 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
 // Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused
 // kernel requires every code of these blobs to be at most kDecLut1Bits long.
 // pay_words: LDS words each wavefront gets for the payloads of one chunk of all `count` blobs.
-void launch_decode_fused(const BlobList& blobs, int first, int count, float* w_ref, uint64_t n, Workspace* ws,
+void launch_decode_fused(const BlobList& blobs, int first, int count, void* w_ref, uint64_t n, int dtype, Workspace* ws,
                          uint64_t epoch, HostResult* host, uint32_t pay_words, bool long_codes, const Tuning& tune,
                          hipStream_t s);
 

@@ -55,6 +55,8 @@ _lib.lc_encode_wait.argtypes = [_int, ctypes.POINTER(_int)]
 _lib.lc_decode.restype = _i64
 _lib.lc_decode.argtypes = [_vp, _vp, _u64, _vp]
 _lib.lc_decode_many.restype = _i64
+_lib.lc_decode_many_t.restype = _i64
+_lib.lc_decode_many_t.argtypes = [ctypes.POINTER(_vp), _int, _vp, _u64, _int, _vp]
 _lib.lc_decode_many.argtypes = [ctypes.POINTER(_vp), _int, _vp, _u64, _vp]
 _lib.lc_blob_info.restype = _int
 _lib.lc_blob_info.argtypes = [_vp, ctypes.POINTER(_u64), ctypes.POINTER(_int), ctypes.POINTER(_u64), ctypes.POINTER(_int)]
@@ -325,6 +327,18 @@ def lc_decode_many(blobs, w_ref, stream=None, n=None):
         assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
     ptrs = (_vp * len(blobs))(*[b.data_ptr() for b in blobs])
     r = int(_lib.lc_decode_many(ptrs, len(blobs), _dev_f32(w_ref), n, _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_decode_many_t(blobs, w_ref, stream=None, n=None):
+    """lc_decode_many for float32, bfloat16 or float16 parameters."""
+    n = w_ref.numel() if n is None else n
+    for b in blobs:
+        assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
+    ptrs = (_vp * len(blobs))(*[b.data_ptr() for b in blobs])
+    r = int(_lib.lc_decode_many_t(ptrs, len(blobs), _dev_any(w_ref), n, DTYPES[w_ref.dtype], _stream(stream)))
     if r < 0:
         raise LcError(-r)
     return r

@@ -1203,3 +1203,48 @@ def test_fused_restore_long_codes(lc, steps, offset):
         with pytest.raises(lc.LcError) as e:
             lc.lc_decode_many(damaged, rec)
         assert e.value.status == lc.ERR_BAD_BLOB
+
+
+@pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("steps,nbits,offset", [(1, 3, 0), (5, 3, 0), (11, 2, 1), (6, 4, 0)])
+def test_fused_restore_of_16_bit_parameters(lc, tdt, steps, nbits, offset):
+    """lc_decode_many_t on bf16 / fp16 parameters: bit for bit the oracle's successive restores (the running value
+    is rounded to the storage type after every blob), ragged tail, an offset that takes the guarded path, more
+    blobs than one sweep takes; nbits 4 spreads the magnitudes so that long codes occur; fp64 is refused."""
+    code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+    n = 7 * 16384 + 4321
+    g = torch.Generator(device=DEV); g.manual_seed(900 + steps)
+    buf0 = (0.05 * torch.randn(n + 8, generator=g, device=DEV)).to(tdt)
+    w0 = buf0[offset:offset + n]
+    tracked, w, blobs = w0.clone(), w0.clone(), []
+    out = lc.alloc_out(n, nbits, DEV)
+    ref_h = raw16(w0)
+    for t in range(steps):
+        if nbits == 4:
+            e = torch.floor(-torch.log2(torch.rand(n, generator=g, device=DEV).clamp_(min=2.0 ** -18)))
+            d = torch.exp2(-4 - e) * (1 + torch.rand(n, generator=g, device=DEV)) * torch.sign(torch.randn(n, generator=g, device=DEV))
+        else:
+            d = 2e-3 * torch.randn(n, generator=g, device=DEV)
+            d[::5] = 0
+        w = (w.float() + d).to(tdt)
+        size = lc.lc_encode_t(w, tracked, nbits, out)
+        blobs.append(out[:size].clone())
+        assert lc.lc_decode_t(blobs[-1], tracked) == size
+        orc.decode_t(blobs[-1].cpu().numpy(), ref_h, code)
+    assert np.array_equal(raw16(tracked).view(np.uint16), ref_h.view(np.uint16))
+    restored = buf0.clone()
+    assert lc.lc_decode_many_t(blobs, restored[offset:offset + n]) == sum(b.numel() for b in blobs)
+    assert np.array_equal(raw16(restored[offset:offset + n]).view(np.uint16), ref_h.view(np.uint16))
+    assert torch.equal(restored[:offset].view(torch.int16), buf0[:offset].view(torch.int16))
+    assert torch.equal(restored[offset + n:].view(torch.int16), buf0[offset + n:].view(torch.int16))
+    # a blob of another element type in the list: refused, parameters untouched
+    other = torch.bfloat16 if tdt == torch.float16 else torch.float16
+    wo = w.float().to(other)
+    so = lc.lc_encode_t(wo, wo.clone(), nbits, out)
+    rec = w0.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many_t(blobs + [out[:so].clone()], rec)
+    assert e.value.status == lc.ERR_BADARG and torch.equal(rec.view(torch.int16), w0.view(torch.int16))
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many_t(blobs, w0.double())
+    assert e.value.status == lc.ERR_BADARG
