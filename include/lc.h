@@ -247,6 +247,10 @@ lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint
 size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits);
 lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const uint64_t* n, int count, int nbits,
                          void* const* out, int64_t* sizes, void* stream);
+/* The same for tensors that all hold parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: LC_ERR_BADARG):
+ * tensor t is coded as lc_encode_t(w[t], w_ref[t], n[t], nbits, out[t], dtype) would. */
+lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const uint64_t* n, int count, int nbits,
+                           void* const* out, int64_t* sizes, int dtype, void* stream);
 
 /*
  * The restore of such a list: tensor t as lc_decode(blobs[t], w_ref[t], n[t]) (Algorithm 1 line 7), all tensors
@@ -257,6 +261,10 @@ lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const
  */
 lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
                          void* stream);
+/* The same for tensors and blobs of element type dtype (LC_F32, LC_BF16 or LC_F16): tensor t as
+ * lc_decode_t(blobs[t], w_ref[t], n[t], dtype); a blob of another element type fails with LC_ERR_BADARG. */
+lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
+                           int dtype, void* stream);
 
 /*
  * Parse a header that the caller copied to HOST memory (at least 64 bytes).  Any

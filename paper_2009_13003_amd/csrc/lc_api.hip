@@ -419,10 +419,17 @@ extern "C" {
 
 lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
                          void* stream) {
+    return lc_decode_batch_t(blobs, reinterpret_cast<void* const*>(w_ref), n, count, sizes, LC_F32, stream);
+}
+
+lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
+                           int dtype, void* stream) {
     if (!blobs || !w_ref || !n || count < 1 || count > kMaxBatch) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
+    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
     for (int t = 0; t < count; ++t) {
         if (n[t] > LC_MAX_N || !blobs[t] || misaligned(blobs[t], 16)) return -LC_ERR_BADARG;
-        if (n[t] && (!w_ref[t] || misaligned(w_ref[t], 4))) return -LC_ERR_BADARG;
+        if (n[t] && (!w_ref[t] || misaligned(w_ref[t], esize))) return -LC_ERR_BADARG;
     }
     uint64_t chunks64 = 0;
     const size_t need = batch_decode_bytes(n, count, &chunks64);
@@ -441,7 +448,7 @@ lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const ui
     for (int t = 0; t < count; ++t) {
         SegD& sg = g_batch->dsegs[t];
         sg.blob = static_cast<const uint8_t*>(blobs[t]); sg.w_ref = w_ref[t]; sg.n = n[t];
-        sg.nchunks = (uint32_t)num_chunks_of(n[t]); sg.chunk0 = chunks; sg.aligned = !misaligned(w_ref[t], 16); sg.pad = 0;
+        sg.nchunks = (uint32_t)num_chunks_of(n[t]); sg.chunk0 = chunks; sg.aligned = !misaligned(w_ref[t], 4 * esize); sg.pad = 0;
         chunks += sg.nchunks;
         g_batch->results[t].bytes = 0; g_batch->results[t].status = LC_ERR_HIP; g_batch->results[t].used_cache = 0;
     }
@@ -450,7 +457,7 @@ lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const ui
     a.seg_of_chunk = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
     a.seg_status = reinterpret_cast<uint32_t*>(base);
     a.results = g_batch_dev->results;
-    a.count = (uint32_t)count; a.total_chunks = chunks;
+    a.count = (uint32_t)count; a.total_chunks = chunks; a.dtype = dtype; a.pad = 0;
     LC_HIP(hipMemcpyAsync(a.segs, g_batch->dsegs, (size_t)count * sizeof(SegD), hipMemcpyHostToDevice, s));
     launch_batch_decode(a, ds->tune, s);
     LC_HIP(hipGetLastError());
@@ -483,10 +490,18 @@ size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits) {
 
 lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const uint64_t* n, int count, int nbits,
                          void* const* out, int64_t* sizes, void* stream) {
+    return lc_encode_batch_t(reinterpret_cast<const void* const*>(w), reinterpret_cast<const void* const*>(w_ref), n, count,
+                             nbits, out, sizes, LC_F32, stream);
+}
+
+lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const uint64_t* n, int count, int nbits,
+                           void* const* out, int64_t* sizes, int dtype, void* stream) {
     if (!w || !w_ref || !n || !out || count < 1 || count > kMaxBatch || nbits < 1 || nbits > 4) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
+    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
     for (int t = 0; t < count; ++t) {
         if (n[t] > LC_MAX_N || !out[t] || misaligned(out[t], 16)) return -LC_ERR_BADARG;
-        if (n[t] && (!w[t] || !w_ref[t] || misaligned(w[t], 4) || misaligned(w_ref[t], 4))) return -LC_ERR_BADARG;
+        if (n[t] && (!w[t] || !w_ref[t] || misaligned(w[t], esize) || misaligned(w_ref[t], esize))) return -LC_ERR_BADARG;
     }
     const size_t need = lc_batch_workspace_bytes(n, count, nbits);
     if (!need) return -LC_ERR_BADARG;
@@ -506,7 +521,7 @@ lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const
         Seg& sg = g_batch->segs[t];
         sg.w = w[t]; sg.w_ref = w_ref[t]; sg.out = static_cast<uint8_t*>(out[t]); sg.n = n[t];
         sg.nchunks = (uint32_t)num_chunks_of(n[t]); sg.chunk0 = chunks; sg.group0 = groups;
-        sg.aligned = !misaligned(w[t], 16) && !misaligned(w_ref[t], 16);
+        sg.aligned = !misaligned(w[t], 4 * esize) && !misaligned(w_ref[t], 4 * esize);
         chunks += sg.nchunks; groups += (sg.nchunks + 63) / 64;
         g_batch->results[t].bytes = 0; g_batch->results[t].status = LC_ERR_HIP; g_batch->results[t].used_cache = 0;
     }
@@ -518,7 +533,7 @@ lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const
     a.prov = reinterpret_cast<uint32_t*>(base);
     a.results = g_batch_dev->results;
     a.count = (uint32_t)count; a.total_chunks = chunks; a.total_groups = groups;
-    a.slot_words = slot_words_of(nbits); a.nbits = nbits;
+    a.slot_words = slot_words_of(nbits); a.nbits = nbits; a.dtype = dtype;
     LC_HIP(hipMemcpyAsync(a.segs, g_batch->segs, (size_t)count * sizeof(Seg), hipMemcpyHostToDevice, s));
     launch_batch_encode(a, ds->tune, s);
     LC_HIP(hipGetLastError());

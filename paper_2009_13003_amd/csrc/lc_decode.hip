@@ -422,11 +422,11 @@ __global__ __launch_bounds__(256) void kb_dec_tables(BatchDecArgs a) {
         // the largest blob lc_encode can produce for this n (nbits 4): header + offsets + 132 bytes per chunk + n/2
         const u64 max_total = area + (u64)sg.nchunks * (2 * kW + 4) + (sg.n * 4 + 7) / 8;
         const bool sound = hdr[0] == 0x3142434Cu && hdr[1] == (1u | (kHeaderBytes << 16)) && hdr[12] == 0;
-        const bool head_ok = sound && hn == sg.n && hdr[15] == (u32)kF32 && hdr[9] == sg.nchunks && total >= area &&
+        const bool head_ok = sound && hn == sg.n && hdr[15] == (u32)a.dtype && hdr[9] == sg.nchunks && total >= area &&
                              total <= max_total && ((total - area) & 3) == 0;
         bool ok = head_ok;
         u32 status = 0;
-        if (!head_ok) status = (sound && (hn != sg.n || hdr[15] != (u32)kF32)) ? 1u : 4u;
+        if (!head_ok) status = (sound && (hn != sg.n || hdr[15] != (u32)a.dtype)) ? 1u : 4u;
         else if (!dec_symbol_table(hdr, sg.n, sg.nchunks, area, (total - area) / 4, D, s_len, s_code)) { ok = false; status = 4u; }
         if (!ok) { atomicMax(&a.seg_status[sidx], status); D.info.area = 0; D.info.total_words = 0; D.info.max_len = 0; D.info.K = 0; }
         D.info.pad[0] = ok ? 1u : 0u;                        // the chunk checks and the sweep look here first
@@ -447,6 +447,7 @@ __global__ __launch_bounds__(256) void kb_dec_chunks(BatchDecArgs a) {
     if (!dec_chunk_ok(sg.blob, I.area, I.total_words, sg.nchunks, g - sg.chunk0) && lane_id() == 0) atomicMax(&a.seg_status[sidx], 4u);
 }
 
+template <int DT>
 __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
     __shared__ DecLds L;
     __shared__ uint4 pay[kPayWords / 4 + 1];
@@ -481,10 +482,10 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
         const bool full = (u64)(c + 1) * kChunk <= sg.n;
         const u32 zero_bits = full ? zero_chunk_bits(L.len[K], L.code[K]) : 0u;
         if (full && sg.aligned) {
-            if (M > kDecLut1Bits) decode_chunk<true, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
-            else decode_chunk<true, false, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            if (M > kDecLut1Bits) decode_chunk<true, true, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            else decode_chunk<true, false, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         } else {
-            decode_chunk<false, true, kF32>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            decode_chunk<false, true, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         }
     }
 }
@@ -826,7 +827,9 @@ void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t 
         hipLaunchKernelGGL(kb_dec_chunks, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
         u32 waves = (u32)tune.num_cu * (u32)tune.decode_blocks_per_cu * 4u;
         if (waves > a.total_chunks) waves = a.total_chunks;
-        hipLaunchKernelGGL(kb_decode, dim3(waves), dim3(64), 0, s, a);
+        if (a.dtype == kBF16) hipLaunchKernelGGL(kb_decode<kBF16>, dim3(waves), dim3(64), 0, s, a);
+        else if (a.dtype == kF16) hipLaunchKernelGGL(kb_decode<kF16>, dim3(waves), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL(kb_decode<kF32>, dim3(waves), dim3(64), 0, s, a);
     }
     hipLaunchKernelGGL(kb_dec_report, dim3((a.count + 255) / 256), dim3(256), 0, s, a);
 }

@@ -1264,12 +1264,13 @@ struct BatchChunks {
     __device__ __forceinline__ bool rowchk() const { return row; }
 };
 
+template <int DT>
 __global__ __launch_bounds__(64) void kb_hist(BatchArgs a) {
     __shared__ PackLds<true> L;
     for (u32 i = threadIdx.x; i < 512 * kSpecCopies; i += 64) L.hist[i] = 0;
     __syncthreads();
     BatchChunks<true, false> src = {a, 0xFFFFFFFFu, 0, true, 0};
-    pack_loop<true, false, kF32, 1>(src, L);
+    pack_loop<true, false, DT, 1>(src, L);
     src.hand_in(L);
 }
 
@@ -1277,10 +1278,11 @@ __global__ __launch_bounds__(64) void kb_table(BatchArgs a) {
     table_build<8>(&a.states[blockIdx.x], nullptr, a.segs[blockIdx.x].n, a.nbits, nullptr, 0, nullptr, nullptr);
 }
 
+template <int DT>
 __global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
     __shared__ PackLds<false> L;
     BatchChunks<false, true> src = {a, 0xFFFFFFFFu, 0, true, 0};
-    pack_loop<false, true, kF32, 0>(src, L);      // flush per pair of codes: right for every table of the batch
+    pack_loop<false, true, DT, 0>(src, L);      // flush per pair of codes: right for every table of the batch
     src.hand_in(L);
 }
 
@@ -1296,7 +1298,7 @@ __global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
 
 __global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
     const Seg& sg = a.segs[blockIdx.x];
-    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)kF32);
+    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)a.dtype);
     if (blockIdx.x == gridDim.x - 1) __threadfence_system();
 }
 // ----------------------------------------------------------------------------- launchers
@@ -1401,12 +1403,16 @@ void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s) 
     hipLaunchKernelGGL(kb_setup, dim3(setup_blocks), dim3(256), 0, s, a);
     if (a.total_chunks) {
         const u32 waves = even_waves(a.total_chunks, (u64)tune.num_cu * tune.batch_waves_per_cu);
-        hipLaunchKernelGGL(kb_hist, dim3(waves), dim3(64), 0, s, a);
+        if (a.dtype == kBF16) hipLaunchKernelGGL(kb_hist<kBF16>, dim3(waves), dim3(64), 0, s, a);
+        else if (a.dtype == kF16) hipLaunchKernelGGL(kb_hist<kF16>, dim3(waves), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL(kb_hist<kF32>, dim3(waves), dim3(64), 0, s, a);
     }
     hipLaunchKernelGGL(kb_table, dim3(a.count), dim3(64), 0, s, a);
     if (a.total_chunks) {
         const u32 waves = even_waves(a.total_chunks, (u64)tune.num_cu * tune.batch_waves_per_cu);
-        hipLaunchKernelGGL(kb_pack, dim3(waves), dim3(64), 0, s, a);
+        if (a.dtype == kBF16) hipLaunchKernelGGL(kb_pack<kBF16>, dim3(waves), dim3(64), 0, s, a);
+        else if (a.dtype == kF16) hipLaunchKernelGGL(kb_pack<kF16>, dim3(waves), dim3(64), 0, s, a);
+        else hipLaunchKernelGGL(kb_pack<kF32>, dim3(waves), dim3(64), 0, s, a);
         hipLaunchKernelGGL(kb_place, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
     }
     hipLaunchKernelGGL(kb_finalize, dim3(a.count), dim3(256), 0, s, a);

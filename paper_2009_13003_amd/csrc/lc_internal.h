@@ -159,7 +159,7 @@ void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t*
 // One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
 // chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
 struct Seg {
-    const float* w; const float* w_ref; uint8_t* out;
+    const void* w; const void* w_ref; uint8_t* out;
     uint64_t n;
     uint32_t nchunks, chunk0, group0, aligned;
 };
@@ -168,13 +168,13 @@ struct BatchArgs {
     Seg* segs; EncState* states; Result* results;     // device (results: mapped host memory)
     uint32_t* seg_of_chunk; uint32_t* group_words; uint32_t* chunk_bits; uint32_t* prov;
     uint32_t count, total_chunks, total_groups, slot_words;
-    int nbits;
+    int nbits, dtype;                                  // dtype: element type of every tensor of the call
 };
 void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s);
 
 // lc_decode_batch: one blob and one vector per tensor.
 struct SegD {
-    const uint8_t* blob; float* w_ref;
+    const uint8_t* blob; void* w_ref;
     uint64_t n;
     uint32_t nchunks, chunk0, aligned, pad;
 };
@@ -182,6 +182,7 @@ struct BatchDecArgs {
     SegD* segs; DecSet* sets; Result* results;         // device (results: mapped host memory)
     uint32_t* seg_of_chunk; uint32_t* seg_status;      // seg_status: lc_status per tensor, raised with atomicMax
     uint32_t count, total_chunks;
+    int dtype, pad;
 };
 void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t s);
 

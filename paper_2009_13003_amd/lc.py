@@ -38,6 +38,11 @@ _lib.lc_batch_workspace_bytes.argtypes = [ctypes.POINTER(_u64), _int, _int]
 _lib.lc_encode_batch.restype = _i64
 _lib.lc_encode_batch.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, _int,
                                  ctypes.POINTER(_vp), ctypes.POINTER(_i64), _vp]
+_lib.lc_encode_batch_t.restype = _i64
+_lib.lc_encode_batch_t.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, _int,
+                                   ctypes.POINTER(_vp), ctypes.POINTER(_i64), _int, _vp]
+_lib.lc_decode_batch_t.restype = _i64
+_lib.lc_decode_batch_t.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, ctypes.POINTER(_i64), _int, _vp]
 _lib.lc_decode_batch.restype = _i64
 _lib.lc_decode_batch.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_u64), _int, ctypes.POINTER(_i64), _vp]
 _lib.lc_encode_cached.restype = _i64
@@ -160,8 +165,9 @@ class EncodeBatch:
     def __init__(self, ws, w_refs, nbits, outs):
         count = len(ws)
         assert count == len(w_refs) == len(outs) and count >= 1
+        self.dtype = ws[0].dtype                             # float32, bfloat16 or float16, the same for every tensor
         for w, r, o in zip(ws, w_refs, outs):
-            assert w.is_cuda and w.dtype == torch.float32 and w.is_contiguous() and r.is_cuda and r.dtype == torch.float32
+            assert w.is_cuda and w.dtype == self.dtype and w.is_contiguous() and r.is_cuda and r.dtype == self.dtype
             assert r.is_contiguous() and r.numel() == w.numel() and o.is_cuda and o.dtype == torch.uint8 and o.is_contiguous()
             assert o.numel() >= lc_encode_bound(w.numel(), nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
         self.keep = (list(ws), list(w_refs), list(outs))
@@ -173,7 +179,11 @@ class EncodeBatch:
         self.sizes = (_i64 * count)()
 
     def run(self, stream=None):
-        r = int(_lib.lc_encode_batch(self.wp, self.rp, self.ns, self.count, self.nbits, self.op, self.sizes, _stream(stream)))
+        if self.dtype == torch.float32:
+            r = int(_lib.lc_encode_batch(self.wp, self.rp, self.ns, self.count, self.nbits, self.op, self.sizes, _stream(stream)))
+        else:
+            r = int(_lib.lc_encode_batch_t(self.wp, self.rp, self.ns, self.count, self.nbits, self.op, self.sizes,
+                                           DTYPES[self.dtype], _stream(stream)))
         sizes = list(self.sizes)
         if r < 0 and all(s >= 0 for s in sizes):
             raise LcError(-r)
@@ -183,6 +193,11 @@ class EncodeBatch:
 def lc_encode_batch(ws, w_refs, nbits, outs, stream=None):
     """One table per tensor, all tensors in one call. Returns the list of blob sizes (negative: -(status) of that
     tensor); raises LcError only for errors that concern the whole call."""
+    return EncodeBatch(ws, w_refs, nbits, outs).run(stream)
+
+
+def lc_encode_batch_t(ws, w_refs, nbits, outs, stream=None):
+    """lc_encode_batch for float32, bfloat16 or float16 tensors (all of one dtype)."""
     return EncodeBatch(ws, w_refs, nbits, outs).run(stream)
 
 
@@ -202,9 +217,10 @@ class DecodeBatch:
     def __init__(self, blobs, w_refs):
         count = len(blobs)
         assert count == len(w_refs) and count >= 1
+        self.dtype = w_refs[0].dtype
         for b, r in zip(blobs, w_refs):
             assert b.is_cuda and b.dtype == torch.uint8 and b.is_contiguous()
-            assert r.is_cuda and r.dtype == torch.float32 and r.is_contiguous()
+            assert r.is_cuda and r.dtype == self.dtype and r.is_contiguous()
         self.keep = (list(blobs), list(w_refs))
         self.count = count
         self.bp = (_vp * count)(*[t.data_ptr() for t in blobs])
@@ -213,7 +229,10 @@ class DecodeBatch:
         self.sizes = (_i64 * count)()
 
     def run(self, stream=None):
-        r = int(_lib.lc_decode_batch(self.bp, self.rp, self.ns, self.count, self.sizes, _stream(stream)))
+        if self.dtype == torch.float32:
+            r = int(_lib.lc_decode_batch(self.bp, self.rp, self.ns, self.count, self.sizes, _stream(stream)))
+        else:
+            r = int(_lib.lc_decode_batch_t(self.bp, self.rp, self.ns, self.count, self.sizes, DTYPES[self.dtype], _stream(stream)))
         sizes = list(self.sizes)
         if r < 0 and all(s >= 0 for s in sizes):
             raise LcError(-r)
@@ -222,6 +241,11 @@ class DecodeBatch:
 
 def lc_decode_batch(blobs, w_refs, stream=None):
     """Restores every tensor from its blob in one call. Returns the list of bytes consumed (negative: -(status))."""
+    return DecodeBatch(blobs, w_refs).run(stream)
+
+
+def lc_decode_batch_t(blobs, w_refs, stream=None):
+    """lc_decode_batch for float32, bfloat16 or float16 tensors (all of one dtype)."""
     return DecodeBatch(blobs, w_refs).run(stream)
 
 

@@ -1248,3 +1248,61 @@ def test_fused_restore_of_16_bit_parameters(lc, tdt, steps, nbits, offset):
     with pytest.raises(lc.LcError) as e:
         lc.lc_decode_many_t(blobs, w0.double())
     assert e.value.status == lc.ERR_BADARG
+
+
+@pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
+def test_batched_encode_and_restore_of_16_bit_tensors(lc, tdt):
+    """lc_encode_batch_t / lc_decode_batch_t: every bf16 / fp16 tensor gets the blob lc_encode_t gives it alone (the
+    oracle's, byte for byte) and is restored as lc_decode_t restores it; aligned and unaligned tensors, empty and
+    ragged ones, a non-finite delta in one tensor, a blob of another element type in the restore list."""
+    code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+    nbits = 3
+    sizes_n = [5 * 16384 + 777, 0, 1, 100, 16384, 16385, 20 * 16384 + 5, 3 * 16384, 64]
+    scales = [10.0 ** (-4 + 2 * (i % 5) / 4) for i in range(len(sizes_n))]
+    offsets = [0, 0, 1, 3, 0, 2, 0, 1, 0]
+    ws32, refs32 = batch_case(700, sizes_n, scales, offsets)
+    refs = [r.to(tdt) for r in refs32]                                   # (.to makes fresh, aligned tensors)
+    ws = [(r.float() + (w - r0)).to(tdt) for w, r0, r in zip(ws32, refs32, refs)]
+    # bring the misalignment back: element offsets into 16-bit buffers
+    def shifted(t, off):
+        buf = torch.zeros(t.numel() + off, dtype=tdt, device=DEV)
+        buf[off:] = t
+        return buf[off:]
+    ws = [shifted(w, o) for w, o in zip(ws, offsets)]
+    refs = [shifted(r, o) for r, o in zip(refs, offsets)]
+    ws[7] = ws[7].clone(); ws[7][4321] = float("inf")
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    sizes = lc.lc_encode_batch_t(ws, refs, nbits, outs)
+    good = []
+    for t, (w, r, o, size) in enumerate(zip(ws, refs, outs, sizes)):
+        if t == 7:
+            assert size == -lc.ERR_NONFINITE
+            assert lc.lc_blob_info(o[:512].cpu().numpy().tobytes())["status"] == lc.ERR_NONFINITE
+            continue
+        blob_cpu = orc.encode_t(raw16(w), raw16(r), nbits, code)
+        blob_gpu = o[:size].cpu().numpy()
+        assert size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), "tensor %d: %s" % (t, first_diff(blob_gpu, blob_cpu))
+        good.append(t)
+    recs = [refs[t].clone() if offsets[t] == 0 else shifted(refs[t], offsets[t]) for t in good]
+    used = lc.lc_decode_batch_t([outs[t] for t in good], recs)
+    assert used == [sizes[t] for t in good]
+    for t, rec in zip(good, recs):
+        ref_h = raw16(refs[t])
+        orc.decode_t(outs[t][:sizes[t]].cpu().numpy(), ref_h, code)
+        assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16)), t
+    # a blob of the other 16-bit type in the list: that tensor fails and stays as it was, the others are restored
+    other = torch.bfloat16 if tdt == torch.float16 else torch.float16
+    wo, ro = ws[0].float().to(other), refs[0].float().to(other)
+    oo = lc.alloc_out(wo.numel(), nbits, DEV)
+    lc.lc_encode_t(wo, ro, nbits, oo)
+    recs = [refs[0].clone(), refs[4].clone()]
+    used = lc.lc_decode_batch_t([oo, outs[4]], recs)
+    assert used[0] == -lc.ERR_BADARG and used[1] == sizes[4]
+    assert torch.equal(recs[0].view(torch.int16), refs[0].view(torch.int16))
+    ref_h = raw16(refs[4]); orc.decode_t(outs[4][:sizes[4]].cpu().numpy(), ref_h, code)
+    assert np.array_equal(raw16(recs[1]).view(np.uint16), ref_h.view(np.uint16))
+    # binary64 tensors are refused
+    w64 = ws[0].double()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_batch_t([w64], [w64.clone()], nbits, [outs[0]])
+    assert e.value.status == lc.ERR_BADARG
