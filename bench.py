@@ -392,6 +392,8 @@ def main():
             torch.cuda.empty_cache()
         also["vgg16_bf16"] = typed_leg(dev, args.steps, "vgg16", "bf16")
         torch.cuda.empty_cache()
+        also["llama7b_slice0_bf16"] = typed_leg(dev, max(2, args.steps // 2), "llama7b_slice0", "bf16")
+        torch.cuda.empty_cache()
         also["vgg16_fp64"] = typed_leg(dev, args.steps, "vgg16", "fp64")
         torch.cuda.empty_cache()
         also["llama7b_slice0_fp64"] = typed_leg(dev, max(2, args.steps // 2), "llama7b_slice0", "fp64")
