@@ -161,6 +161,7 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
 // back at all.
 constexpr u32 kPayWords = 2048;      // LDS room for one chunk's payload (4 bits per element on average) when the
                                      // compute unit is shared by as many workgroups as fit; more when fewer are needed
+constexpr u32 kSparseSlack = 512;    // bits above an all-merged chunk up to which a chunk is decoded symbols first
 constexpr u32 kPayWordsMax = 3808;   // what keeps a workgroup's LDS within 64 KB (7.4 bits per element on average)
 
 struct DecLds {
@@ -213,7 +214,7 @@ struct BitReader {
 template <bool FAST, bool LV2, bool STAGED, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
                                             void* __restrict__ w_ref, u64 n, u32 c,
-                                            const LDS& L, u32 P1, u32 P2, u32 K, u32 row_zero_bits, Raise& raise) {
+                                            const LDS& L, u32 P1, u32 P2, u32 K, u32 row_zero_bits, bool sparse, Raise& raise) {
     const u32 lane = lane_id();
     BitReader<STAGED> br;
     br.start(words, nwords, first_bit);
@@ -256,7 +257,73 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     };
     typedef std::integral_constant<bool, true> yes;
     typedef std::integral_constant<bool, false> no;
-    if (FAST) {
+    const bool vec = FAST || (reinterpret_cast<uintptr_t>(w_ref) & (DT == kF64 ? 15 : 4 * elem_bytes<DT>() - 1)) == 0;
+    if (sparse && vec) {
+        // A chunk that holds few kept symbols (its caller has seen that from its size): a row of merged symbols
+        // needs no look at w_ref at all, so the symbols come first, a group of rows at a time, and only the rows
+        // in which some lane decoded a kept symbol are then fetched (together), added to and stored.  The one
+        // wavefront that owns such a chunk no longer waits for 64 rows of memory, only for the few it changes.
+        constexpr u32 G = DT == kF64 ? 4 : 8;
+        // the symbols of one whole row: 4 representatives per lane; true if any lane holds a kept symbol
+        auto row_reps = [&](val_t (&rp)[4]) -> bool {
+            if (row_zero_bits != 0 && !__any((u32)(br.win >> (64 - row_zero_bits)) != 0)) {
+                br.win <<= row_zero_bits; br.avail -= row_zero_bits;
+                if (br.avail <= 32) br.refill();
+                return false;
+            }
+            u32 smin = K;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                u32 e = L.lut1[(u32)(br.win >> shr1)];
+                if (LV2 && e == 0xFF) {
+                    e = L.lut2[(u32)(br.win >> shr2)];
+                    if (e == 0xFF) e = decode_long(L, br.win, K);
+                }
+                const u32 len = e >> 4, sy = e & 15;
+                br.win <<= len; br.avail -= len;
+                smin = min(smin, sy);
+                rp[v] = L.template rep_of<DT>(sy);
+                if ((v & 1) && br.avail <= 32) br.refill();
+            }
+            return __any(smin < K);
+        };
+        const u64 left = n - base;
+        const u32 whole_rows = FAST ? kR : (u32)(left / kRowElems < kR ? left / kRowElems : kR);
+        u32 r = 0;
+        for (; r + G <= whole_rows; r += G) {
+            val_t rp[G][4], x[G][4];
+            bool kept[G];
+#pragma unroll
+            for (u32 k = 0; k < G; ++k) kept[k] = row_reps(rp[k]);
+#pragma unroll
+            for (u32 k = 0; k < G; ++k)
+                if (kept[k]) load_row_v<true, DT>(w_ref, base + (u64)(r + k) * kRowElems + lane * kV, n, x[k]);
+#pragma unroll
+            for (u32 k = 0; k < G; ++k) {
+                if (kept[k]) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) x[k][v] = add_rn(x[k][v], rp[k][v]);
+                    store4_v<DT>(w_ref, base + (u64)(r + k) * kRowElems + lane * kV, x[k]);
+                }
+            }
+        }
+        for (; r < whole_rows; ++r) {
+            val_t rp[4], x[4];
+            if (row_reps(rp)) {
+                const u64 idx = base + (u64)r * kRowElems + lane * kV;
+                load_row_v<true, DT>(w_ref, idx, n, x);
+#pragma unroll
+                for (int v = 0; v < 4; ++v) x[v] = add_rn(x[v], rp[v]);
+                store4_v<DT>(w_ref, idx, x);
+            }
+        }
+        for (; r < kR && base + (u64)r * kRowElems < n; ++r) {
+            const u64 idx = base + (u64)r * kRowElems + lane * kV;
+            val_t x[4];
+            load_row_v<false, DT>(w_ref, idx, n, x);
+            row(no(), idx, x);
+        }
+    } else if (FAST) {
 #pragma unroll 4
         for (u32 r = 0; r < kR; ++r) {
             const u64 idx = base + (u64)r * kRowElems + lane * kV;
@@ -268,7 +335,6 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
         // A ragged or unaligned chunk (the vector's last chunk is one wavefront's work from start to end, so its
         // memory round trips count): whole rows of an aligned array as in a full chunk, four fetched before the
         // first is decoded; the rest with guarded element accesses.
-        const bool vec = (reinterpret_cast<uintptr_t>(w_ref) & (DT == kF64 ? 15 : 4 * elem_bytes<DT>() - 1)) == 0;
         u32 r = 0;
         if (vec) {
             constexpr u32 RB = 4;
@@ -301,11 +367,10 @@ __device__ __forceinline__ u32 zero_chunk_bits(u32 len_merged, u32 code_merged) 
 // pay: this wavefront's LDS area of pay_words + 4 words for the chunk's payload
 template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
-                                             u32 c, LDS& L, uint4* pay, u32 pay_words, u32 P1, u32 P2, u32 K, u64 area,
-                                             u32 zero_bits, Raise& raise) {
+                                             u32 c, u32 o0, u32 o1, LDS& L, uint4* pay, u32 pay_words, u32 P1, u32 P2, u32 K,
+                                             u64 area, u32 zero_bits, Raise& raise) {
+    // o0, o1: the chunk's entries c and c + 1 of the offset table (fetched by the caller, ahead of time)
     const u32 lane = lane_id();
-    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
-    const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
     const uint8_t* rec = blob + area + 4 * (u64)o0;
     const u32 nwords = o1 - o0 - kLaneBitsWords;        // >= 1 (validated)
     const u32 lane_bits = reinterpret_cast<const uint16_t*>(rec)[lane];
@@ -315,6 +380,14 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
     // 4 merged symbols in a row are this many zero bits (when the merged code is zeros, and short enough to test)
     const u32 whole_zero = zero_chunk_bits(L.len[K], L.code[K]);
     const u32 row_zero_bits = whole_zero / (kR * kV) * kV <= 32 ? whole_zero / (kR * kV) * kV : 0u;
+    // Few kept symbols?  When the merged symbol's code is shorter than every other, each kept symbol costs at least
+    // one bit more, so a chunk of at most kSparseSlack bits above (elements x merged length) holds at most that many.
+    u32 len_merged = L.len[K];
+    for (u32 j = 0; j < K; ++j) if (L.len[j] != 0 && L.len[j] <= L.len[K]) len_merged = 0;
+    const u64 left = n - (u64)c * kChunk;
+    const u32 elems = left < kChunk ? (u32)left : kChunk;
+    const u32 chunk_bits = read_lane(o + lane_bits, kW - 1);
+    const bool sparse = len_merged != 0 && chunk_bits <= elems * len_merged + kSparseSlack;
     if (nwords + k0 <= pay_words) {
         // coalesced copy of [aligned start, payload end) to LDS; the bytes before the payload are the
         // record's own lane lengths, and the last vector is read word by word so no read passes the end
@@ -335,9 +408,9 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
         }
         if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
         decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
-                                         w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
+                                         w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     } else {
-        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, raise);
+        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     }
 }
 
@@ -347,14 +420,28 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
                                                 u32 pay_words) {
     __shared__ DecLds L;
     extern __shared__ uint4 dec_pay[];                   // 4 areas of pay_words + 4 payload words, one per wavefront
-    // if the check kernel found something, touch nothing
-    if ((__hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 8) != epoch) {
-        const u32 t = threadIdx.x;
-        const DecSet& D = ws->dec_set[0];
-        const u32 M = D.info.max_len, K = D.info.K;
+    // What the check kernel left (the verdict and the blob's tables) is fetched in one go: a failed check leaves
+    // tables that mean nothing, but reading them is harmless.  If it found something, nothing else is touched.
+    const u32 t = threadIdx.x;
+    const DecSet& D = ws->dec_set[0];
+    const u64 verdict = __hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u32 M = D.info.max_len, K = D.info.K;
+    u64 area = D.info.area;
+    u32 lut1_entry = t < (1u << kDecLut1Bits) ? D.lut1[t] : 0u;
+    u32 sym_rep = 0, sym_rep_hi = 0, sym_len = 0, sym_code = 0;
+    if (t < kMaxSym) { sym_rep = D.info.rep_bits[t]; sym_rep_hi = D.info.rep_hi[t]; sym_len = D.info.len[t]; sym_code = D.info.code[t]; }
+    // (the empty statement keeps these loads ahead of the branch; the values every lane holds alike go back to scalars)
+    asm volatile("" : "+v"(M), "+v"(K), "+v"(area), "+v"(lut1_entry), "+v"(sym_rep), "+v"(sym_rep_hi), "+v"(sym_len), "+v"(sym_code));
+    M = __builtin_amdgcn_readfirstlane(M); K = __builtin_amdgcn_readfirstlane(K);
+    area = ((u64)__builtin_amdgcn_readfirstlane((u32)(area >> 32)) << 32) | __builtin_amdgcn_readfirstlane((u32)area);
+    if ((verdict >> 8) != epoch) {
         const u32 P1 = M < kDecLut1Bits ? M : kDecLut1Bits, P2 = M < kDecLut2Bits ? M : kDecLut2Bits;
-        const u64 area = D.info.area;
-        if (t < (1u << P1)) L.lut1[t] = D.lut1[t];
+        const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+        const u32 wave = t >> 6, stride = gridDim.x * 4;
+        u32 c = blockIdx.x * 4 + wave;
+        u32 o0 = 0, o1 = 0;
+        if (c < nchunks) { o0 = off_tab[c]; o1 = off_tab[c + 1]; }
+        if (t < (1u << P1)) L.lut1[t] = (uint8_t)lut1_entry;
         if (M > kDecLut1Bits) {
             if ((1u << P2) >= 4096) {
                 const uint4* src = reinterpret_cast<const uint4*>(D.lut2);
@@ -365,23 +452,27 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
             }
         }
         if (t < kMaxSym) {
-            L.rep[t] = __uint_as_float(t < K ? D.info.rep_bits[t] : 0x80000000u);
-            L.rep64[t] = t < K ? __hiloint2double((int)D.info.rep_hi[t], (int)D.info.rep_bits[t]) : -0.0;
-            L.len[t] = D.info.len[t]; L.code[t] = D.info.code[t];
+            L.rep[t] = __uint_as_float(t < K ? sym_rep : 0x80000000u);
+            L.rep64[t] = t < K ? __hiloint2double((int)sym_rep_hi, (int)sym_rep) : -0.0;
+            L.len[t] = sym_len; L.code[t] = sym_code;
         }
         __syncthreads();
-        const u32 wave = t >> 6;
         uint4* pay = dec_pay + wave * (pay_words / 4 + 1);
         const u32 zero_bits = zero_chunk_bits(L.len[K], L.code[K]);
         auto raise = [&](u32 code) { raise_status(ws, host, epoch, code); };
-        for (u32 c = blockIdx.x * 4 + wave; c < nchunks; c += gridDim.x * 4) {
+        while (c < nchunks) {
+            // the next chunk's place in the offset table is on its way while this one is decoded
+            const u32 cn = c + stride;
+            u32 n0 = 0, n1 = 0;
+            if (cn < nchunks) { n0 = off_tab[cn]; n1 = off_tab[cn + 1]; }
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
-                else decode_chunk<true, false, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                else decode_chunk<true, false, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
             } else {
-                decode_chunk<false, true, DT>(blob, w_ref, n, c, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
+                decode_chunk<false, true, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
             }
+            c = cn; o0 = n0; o1 = n1;
         }
     }
 }
@@ -479,13 +570,15 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
         }
         auto raise = [&](u32 code) { atomicMax(&a.seg_status[sidx], code); };
         const u32 c = g - sg.chunk0;
+        const u32* off_tab = reinterpret_cast<const u32*>(sg.blob + kHeaderBytes);
+        const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
         const bool full = (u64)(c + 1) * kChunk <= sg.n;
         const u32 zero_bits = full ? zero_chunk_bits(L.len[K], L.code[K]) : 0u;
         if (full && sg.aligned) {
-            if (M > kDecLut1Bits) decode_chunk<true, true, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
-            else decode_chunk<true, false, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            if (M > kDecLut1Bits) decode_chunk<true, true, DT>(sg.blob, sg.w_ref, sg.n, c, o0, o1, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            else decode_chunk<true, false, DT>(sg.blob, sg.w_ref, sg.n, c, o0, o1, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         } else {
-            decode_chunk<false, true, DT>(sg.blob, sg.w_ref, sg.n, c, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
+            decode_chunk<false, true, DT>(sg.blob, sg.w_ref, sg.n, c, o0, o1, L, pay, kPayWords, P1, P2, K, area, zero_bits, raise);
         }
     }
 }
