@@ -154,7 +154,8 @@ size_t lc_encode_bound(uint64_t n, int nbits) {
 size_t lc_workspace_bytes(uint64_t n, int nbits) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
     const uint64_t nc = num_chunks_of(n);
-    return kWorkspaceHead + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)(nc * slot_words_of(nbits) * 4);
+    return kWorkspaceHead + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)(nc * slot_words_of(nbits) * 4) +
+           256 + (size_t)((16 * nc + 255) / 256 * 256);      // + the per-batch maxima of sweep 1
 }
 
 int lc_set_workspace(void* dev_ws, size_t bytes) {
@@ -194,6 +195,8 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     const uint64_t nc = num_chunks_of(n);
     uint32_t* prov = chunk_bits + (nc + 63) / 64 * 64;
     const uint32_t slot_words = slot_words_of(nbits);
+    // one byte per 4 KiB batch of sweep 1 (16 per chunk at most), behind the slots
+    uint8_t* batch_max = reinterpret_cast<uint8_t*>((reinterpret_cast<uintptr_t>(prov + nc * slot_words) + 255) & ~(uintptr_t)255);
     uint8_t* o = static_cast<uint8_t*>(out);
     int ticket = -1;
     if (async) {
@@ -216,10 +219,10 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
         { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
         { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     } else {
-        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, ds->tune, s);
+        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, batch_max, ds->tune, s);
     }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, dtype, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
-    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, prov, slot_words, ds->tune, s); }
+    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, batch_max, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
     { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, s); }

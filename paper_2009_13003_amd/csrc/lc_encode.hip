@@ -82,9 +82,11 @@ __device__ __forceinline__ float max_magnitude(const u32 (&u)[EPU], float m) {
 
 // Every wavefront takes batches of PF consecutive rows of 64 units (PF KiB of each array), so a batch lies in
 // one chunk of the coding sweep and its largest exponent goes to chunk_maxexp with one atomic per batch.
+// batch_max (or null) receives every whole batch's largest exponent as a byte of its own: the coding sweep then
+// knows which parts of a chunk it has to read.
 template <bool ALIGNED, int DT>
 __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
-                                               u64 n, EncState* ws, u32* chunk_maxexp) {
+                                               u64 n, EncState* ws, u32* chunk_maxexp, uint8_t* batch_max) {
     __shared__ u32 h[512 * kHistCopies];
     constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
@@ -118,7 +120,10 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
 #pragma unroll
         for (int k = 0; k < PF; ++k) mf = count_unit(a[k], bb[k], mf);
         const u32 m = wave_max_u32(__float_as_uint(mf));     // whole wavefronts only: b < nbatch is the same for all lanes
-        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m >> 23);
+        if ((tid & (kW - 1)) == 0) {
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m >> 23);
+            if (batch_max) batch_max[batch] = (uint8_t)(m >> 23);
+        }
     };
     if (b < nbatch) {
         // The loads of the batch after next are issued without a branch around them (at the end the current
@@ -548,6 +553,8 @@ struct ChunkRef {
     u32 seg;                     // batched calls: which tensor
     bool valid, fast;            // fast: a full chunk of aligned arrays
     bool vec;                    // the arrays are aligned for 4-element accesses (whole rows of a ragged chunk too)
+    bool by_parts;               // a chunk of aligned arrays that is mostly merged: coded part by part, and
+    u32 parts;                   // which of its whole parts have to be read
 };
 
 __device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u32 nw) {
@@ -635,6 +642,90 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
     finish_lane_sizes(ch, nb, nw);
 }
 
+// element index of this lane's 4 elements in row r of chunk c
+__device__ __forceinline__ u64 row_at(u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane_id()) * kV; }
+
+// A chunk of aligned arrays of which sweep 1 has seen that only a few parts hold anything but merged elements
+// (a part = one batch of that sweep: 4 KiB of each array; bit p of `parts` set = part p has to be read).  The lone
+// wavefront that codes such a chunk would otherwise wait for all 64 rows of both arrays; here it fetches the
+// marked parts only and writes the merged code for every element of the others; the rows of a ragged chunk
+// behind its last whole part are read as they are.  Same lane strings as any path.
+template <int DT>
+__device__ __noinline__ void pack_chunk_parts(const ChunkRef ch, u32 cl_merged, PackLds<false>& L) {
+    constexpr u32 kRowsPerPart = 4096 / (kRowElems * elem_bytes<DT>());      // 4 (4-byte elements) or 8 (2-byte)
+    constexpr u32 kParts = kR / kRowsPerPart;
+    const u32 lane = lane_id();
+    u32* slot = ch.slot;
+    const u32 mm = lane & (kMmCopies - 1);
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;
+    auto flush = [&]() {
+        if (nb >= 32) { slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32)); ++nw; nb -= 32; }
+    };
+    const u32 len_merged = cl_merged & 31, per_step = 32 / len_merged;       // (the merged symbol occurs here: length >= 1)
+    u32 run = 0;                                                             // per_step copies of the merged code
+    for (u32 i = 0; i < per_step; ++i) run = (run << len_merged) | (cl_merged >> 5);
+    auto code_element = [&](float a, float b) {
+        const u32 u = delta_bits(a, b);
+        const u32 sy = L.sym8[u >> 23] >> 3;
+        const u32 cl = L.codelen[sy];
+        atomicMin(&L.mn[sy * kMmCopies + mm], u);
+        atomicMax(&L.mx[sy * kMmCopies + mm], u);
+        acc = (acc << (cl & 31)) | (cl >> 5);
+        nb += cl & 31;
+    };
+    const u64 n = ch.n, inside = n - (u64)ch.c * kChunk;
+    const u32 whole = inside >= kChunk ? kParts : (u32)(inside / (kRowsPerPart * kRowElems));
+    for (u32 p = 0; p < whole; ++p) {
+        if ((ch.parts >> p) & 1u) {
+            float xa[kRowsPerPart][4], xb[kRowsPerPart][4];
+#pragma unroll
+            for (u32 k = 0; k < kRowsPerPart; ++k) {
+                load_row<true, DT>(ch.w, row_at(ch.c, p * kRowsPerPart + k), ch.n, xa[k]);
+                load_row<true, DT>(ch.w_ref, row_at(ch.c, p * kRowsPerPart + k), ch.n, xb[k]);
+            }
+#pragma unroll
+            for (u32 k = 0; k < kRowsPerPart; ++k) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    code_element(xa[k][v], xb[k][v]);
+                    if (v & 1) flush();
+                }
+            }
+        } else {
+            // the merged code kRowsPerPart * 4 times, as many copies per step as fit 32 bits
+            for (u32 left = kRowsPerPart * kV; left != 0;) {
+                const u32 k = left < per_step ? left : per_step;
+                acc = (acc << (k * len_merged)) | (u64)(run >> ((per_step - k) * len_merged));
+                nb += k * len_merged;
+                flush();
+                left -= k;
+            }
+        }
+    }
+    if (whole < kParts) {
+        // a ragged chunk's last rows (fewer than one part), fetched together, elements past the end left out
+        float xa[kRowsPerPart][4], xb[kRowsPerPart][4];
+#pragma unroll
+        for (u32 k = 0; k < kRowsPerPart; ++k) {
+            const u64 idx = row_at(ch.c, whole * kRowsPerPart + k);
+            load_row<false, DT>(ch.w, idx, n, xa[k]);
+            load_row<false, DT>(ch.w_ref, idx, n, xb[k]);
+        }
+#pragma unroll
+        for (u32 k = 0; k < kRowsPerPart; ++k) {
+            const u64 idx = row_at(ch.c, whole * kRowsPerPart + k);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (idx + v < n) code_element(xa[k][v], xb[k][v]);
+                if (v & 1) flush();
+            }
+        }
+    }
+    if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
+    finish_lane_sizes(ch, nb, nw);
+}
+
 // A full chunk whose largest exponent (sweep 1 recorded it) lies below every kept bucket: all 16384 symbols
 // are the merged one (Section 3.1.1, priority promotion) and each lane's string is 256 copies of its code.
 // Such a chunk gets no slot: sweep 2 only notes its size, with kMergedChunk set in chunk_bits, and k_place
@@ -643,8 +734,6 @@ constexpr u32 kMergedChunk = 0x80000000u;
 
 constexpr int kPackPF = 8;          // rows per prefetch batch of the coding loop
 
-// element index of this lane's 4 elements in row r of chunk c
-__device__ __forceinline__ u64 row_at(u32 c, u32 r) { return (u64)c * kChunk + (u64)(r * kW + lane_id()) * kV; }
 
 template <int DT>
 __device__ __forceinline__ void fetch_first_batch(const ChunkRef& ch, typename Raw<DT>::type (&A)[kPackPF],
@@ -768,7 +857,12 @@ __device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
         const ChunkRef next = src.take();
         src.enter(cur, L);
         if (!cur.fast) {
-            pack_chunk_plain<HIST, PACK, DT>(cur, L);
+            if constexpr (!HIST && PACK) {
+                if (cur.by_parts) pack_chunk_parts<DT>(cur, src.merged_codelen(), L);
+                else pack_chunk_plain<HIST, PACK, DT>(cur, L);
+            } else {
+                pack_chunk_plain<HIST, PACK, DT>(cur, L);
+            }
             if (next.valid && next.fast) fetch_first_batch<DT>(next, A0, B0);
         } else if (ROWSEL == 1 || (ROWSEL < 0 && src.rowchk())) {
             pack_chunk_fast<true, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L);
@@ -789,6 +883,22 @@ struct VectorChunks {
     u32 k8; bool row;
     const u32* chunk_list; u32 listed;
     u32 pos;
+    const uint8_t* batch_max; u32 parts_per_chunk, min_kept_exp, cl_merged;     // what sweep 1 recorded per 4 KiB batch, or null
+    __device__ __forceinline__ u32 merged_codelen() const { return cl_merged; }
+    // Which of the first `whole` parts of chunk c hold an exponent of a kept bucket; false if those are more than a
+    // quarter of a chunk's parts (the chunk then takes the usual paths).
+    __device__ __forceinline__ bool parts_to_read(u32 c, u32 whole, u32* parts) const {
+        const u32* p = reinterpret_cast<const u32*>(batch_max + (u64)c * parts_per_chunk);
+        u32 mask = 0;
+        for (u32 i = 0; i < parts_per_chunk / 4; ++i) {
+            const u32 word = load_uniform(p + i);
+#pragma unroll
+            for (u32 b = 0; b < 4; ++b) mask |= (((word >> (8 * b)) & 255u) >= min_kept_exp ? 1u : 0u) << (4 * i + b);
+        }
+        mask &= (1u << whole) - 1u;                   // (a ragged chunk: the bytes of its missing parts mean nothing)
+        *parts = mask;
+        return (u32)__popc(mask) <= parts_per_chunk / 4;
+    }
     __device__ __forceinline__ ChunkRef ref(u32 c, bool valid) const {
         ChunkRef ch;
         ch.c = c;
@@ -800,6 +910,13 @@ struct VectorChunks {
         ch.bits_at = chunk_bits + c;
         ch.group_at = group_words + (c >> 6);
         ch.seg = 0;
+        ch.parts = 0; ch.by_parts = false;
+        if (valid && aligned && batch_max) {
+            const u64 inside = n - (u64)c * kChunk, part_elems = kChunk / parts_per_chunk;
+            const u32 whole = inside >= kChunk ? parts_per_chunk : (u32)(inside / part_elems);
+            ch.by_parts = parts_to_read(c, whole, &ch.parts);
+            if (ch.by_parts) ch.fast = false;        // off the pipelined path: see pack_chunk_parts
+        }
         return ch;
     }
     __device__ __forceinline__ ChunkRef take() {
@@ -850,8 +967,8 @@ __device__ __forceinline__ void note_merged_chunks(const Table& T, u64 n, u32* c
 template <int DT>
 __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                              EncState* ws, u32* chunk_bits, u32* group_words,
-                                             const u32* chunk_maxexp, const u32* chunk_list, u32* prov,
-                                             u32 slot_words, u32 nchunks, int aligned) {
+                                             const u32* chunk_maxexp, const u32* chunk_list, const uint8_t* batch_max,
+                                             u32* prov, u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds<false> L;
     const u32 lane = threadIdx.x;
     const Table& T = ws->table;
@@ -860,7 +977,9 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
     const u32 K = T.K;
     __syncthreads();
     VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, T.max_len <= 8,
-                        chunk_list, chunk_list ? ws->list_count : 0, 0};
+                        chunk_list, chunk_list ? ws->list_count : 0, 0,
+                        chunk_list ? batch_max : nullptr, 4096u / (kRowElems * elem_bytes<DT>()) == 4 ? 16u : 8u, T.min_kept_exp,
+                        T.codelen[K]};
     if (chunk_list) note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
     if (src.row) pack_loop<false, true, DT, 1>(src, L);
     else pack_loop<false, true, DT, 0>(src, L);
@@ -934,7 +1053,7 @@ __global__ __launch_bounds__(64) void k_pack64(const void* __restrict__ w, const
     for (u32 i = lane; i < kMaxSym * kMmCopies64; i += kW) { L.mn[i] = ~0ull; L.mx[i] = 0; }
     __syncthreads();
     VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, true,
-                        chunk_list, chunk_list ? ws->list_count : 0, 0};
+                        chunk_list, chunk_list ? ws->list_count : 0, 0, nullptr, 16u, 0u, 0u};
     if (chunk_list) note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
     for (ChunkRef ch = src.take(); ch.valid; ch = src.take()) {
         if (ch.fast) pack_chunk64<true>(ch, L, K);
@@ -966,7 +1085,7 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, c
     const u32 K = spec ? T.K : 0;
     __syncthreads();
     VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3,
-                        !spec || T.max_len <= 8, nullptr, 0, 0};
+                        !spec || T.max_len <= 8, nullptr, 0, 0, nullptr, 16u, 0u, 0u};
     if (!spec) pack_loop<true, false, DT, 1>(src, L);
     else if (src.row) pack_loop<true, true, DT, 1>(src, L);
     else pack_loop<true, true, DT, 0>(src, L);
@@ -1217,7 +1336,7 @@ struct BatchChunks {
         ChunkRef ch;
         const u32 g = blockIdx.x + (pos++) * gridDim.x;
         ch.valid = g < a.total_chunks;
-        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false; ch.vec = false;
+        ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false; ch.vec = false; ch.by_parts = false; ch.parts = 0;
         ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
         if (ch.valid) {
             ch.seg = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
@@ -1262,6 +1381,7 @@ struct BatchChunks {
     }
     __device__ __forceinline__ u32 K8() const { return k8; }
     __device__ __forceinline__ bool rowchk() const { return row; }
+    __device__ __forceinline__ u32 merged_codelen() const { return 0; }      // (no chunk of a batched call has parts)
 };
 
 template <int DT>
@@ -1307,14 +1427,14 @@ void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, 
 }
 
 template <int DT>
-static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32* chunk_maxexp, u32 blocks, u32 threads,
-                          hipStream_t s) {
-    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp);
-    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp);
+static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32* chunk_maxexp, uint8_t* batch_max,
+                          u32 blocks, u32 threads, hipStream_t s) {
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max);
+    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max);
 }
 
-void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, const Tuning& tune,
-                 hipStream_t s) {
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, uint8_t* batch_max,
+                 const Tuning& tune, hipStream_t s) {
     if (n == 0) return;
     const u32 threads = tune.hist_threads;
     const u64 units = n / (dtype == kF32 ? 4 : dtype == kF64 ? 2 : 8);   // 16-byte units
@@ -1327,9 +1447,9 @@ void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
         else hipLaunchKernelGGL(k_hist64<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp);
         return;
     }
-    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
-    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
-    else launch_hist_t<kF32>(w, w_ref, n, ws, chunk_maxexp, (u32)blocks, threads, s);
+    if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
+    else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
+    else launch_hist_t<kF32>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
 }
 
 // chunk_list: where to list the chunks sweep 2 has to read (chunk_maxexp then holds what k_hist recorded), or null
@@ -1367,17 +1487,17 @@ void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, 
 
 // chunk_maxexp, chunk_list: what k_hist recorded and k_table listed for this vector, or both null
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
-                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, uint32_t* prov,
-                 uint32_t slot_words, const Tuning& tune, hipStream_t s) {
+                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, const uint8_t* batch_max,
+                 uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
     const u32 blocks = even_waves(nchunks, (u64)tune.num_cu * tune.pack_waves_per_cu);
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
     const dim3 grid(blocks), wg(64);
     if (dtype == kF64) hipLaunchKernelGGL(k_pack64, grid, wg, 0, s, w, w_ref, (u64)n, ws, &ws->ext64, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
-    else if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
-    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
-    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
+    else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
 }
 
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,

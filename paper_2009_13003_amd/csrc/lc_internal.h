@@ -142,16 +142,16 @@ struct Tuning {
 
 // Launchers (lc_encode.hip, lc_decode.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s);
-void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, const Tuning& tune,
-                 hipStream_t s);
+void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, uint8_t* batch_max,
+                 const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
                   uint32_t* chunk_list, hipStream_t s);
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
-                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, uint32_t* prov,
-                 uint32_t slot_words, const Tuning& tune, hipStream_t s);
+                 uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, const uint8_t* batch_max,
+                 uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s);
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,

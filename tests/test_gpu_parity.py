@@ -990,6 +990,47 @@ def test_encode_of_chunks_below_every_kept_bucket(lc, nbits):
     check_case(lc, w, w_ref, nbits, "quiet chunks again")
 
 
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+@pytest.mark.parametrize("tdt", [torch.float32, torch.bfloat16])
+def test_mostly_quiet_chunks_are_coded_part_by_part(lc, nbits, tdt):
+    """Chunks that lie below every kept bucket except for a few elements: the second sweep reads only the 4 KiB
+    parts that the first one marked (first, middle and last part; two elements in one part; exactly a quarter of
+    the parts, and one more, which takes the usual path; a ragged last chunk with a loud element in a whole part,
+    in its last rows, or nowhere).  Blob and restored values as the oracle's; the decoder meets chunks with few
+    kept symbols in every one of these shapes."""
+    nchunks = 24
+    n = nchunks * 16384 + 9 * 1024 + 300
+    w, w_ref = quiet_chunk_case(n, 400 + nbits, list(range(4, nchunks + 1)), tiny=2.0 ** -22)
+    part = 1024 if tdt == torch.float32 else 2048
+    loud = {4: [0], 5: [7 * part + 5], 6: [16384 - 1], 7: [3 * part + 1, 3 * part + 900],
+            8: [p * (16384 // 4) + 17 for p in range(4)],                        # a quarter of the parts (fp32) or more
+            9: [p * part + 3 for p in range(16384 // part // 4)],                 # exactly a quarter
+            10: [p * part + 3 for p in range(16384 // part // 4 + 1)],            # one more: the usual path
+            11: list(range(0, 16384, 64)), 12: [8191, 8192],
+            nchunks: [2 * part + 77, 9 * 1024 + 299, 8 * 1024 + 1]}            # the ragged chunk
+    for c, offs in loud.items():
+        for k, o in enumerate(offs):
+            i = c * 16384 + o
+            w[i] = w_ref[i] + (2.0 ** -10) * (1.25 + 0.5 * (k % 2)) * (1 - 2 * (k % 3 == 1))
+    if tdt == torch.float32:
+        check_case(lc, w, w_ref, nbits, "part by part")
+        w[nchunks * 16384:] = w_ref[nchunks * 16384:]                            # a ragged chunk without a loud element
+        check_case(lc, w, w_ref, nbits, "part by part, quiet tail")
+        return
+    rt = w_ref.to(tdt)
+    wt = (rt.float() + (w - w_ref)).to(tdt)
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode_t(wt, rt, nbits, out)
+    blob_cpu = orc.encode_t(raw16(wt), raw16(rt), nbits, orc.DT_BF16)
+    blob_gpu = out[:size].cpu().numpy()
+    assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    rec = rt.clone()
+    assert lc.lc_decode_t(out, rec) == size
+    ref_h = raw16(rt)
+    orc.decode_t(blob_cpu, ref_h, orc.DT_BF16)
+    assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
+
+
 @pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
 def test_encode_of_quiet_chunks_16_bit(lc, tdt):
     code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
