@@ -97,8 +97,17 @@ def lc_workspace_bytes(n, nbits):
     return int(_lib.lc_workspace_bytes(n, nbits))
 
 
+try:                                    # torch's current stream as a raw handle, without building a Stream object
+    _raw_current_stream = torch._C._cuda_getCurrentRawStream
+    _current_device = torch._C._cuda_getDevice
+except AttributeError:                  # (other torch builds: the public, slower way)
+    _raw_current_stream = None
+
+
 def _stream(stream):
     if stream is None:
+        if _raw_current_stream is not None:
+            return ctypes.c_void_p(_raw_current_stream(_current_device()))
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
 
