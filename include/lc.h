@@ -103,8 +103,8 @@ size_t lc_encode_bound(uint64_t n, int nbits);
  * Device scratch lc_encode needs for (n, nbits): a fixed part of about 2.1 MB (tables,
  * and per-chunk notes sized for LC_MAX_N) plus, per chunk of 16384 elements, one slot that
  * can hold the chunk's code bits at their longest (2^nbits - 1 bits per element): about
- * 0.06 / 0.19 / 0.44 / 0.94 bytes per element for nbits = 1..4.  lc_decode needs only the
- * fixed part (lc_workspace_bytes(0, 1)).  Host only.
+ * 0.06 / 0.19 / 0.44 / 0.94 bytes per element for nbits = 1..4, and 16 bytes of notes per chunk.
+ * lc_decode needs only the fixed part (lc_workspace_bytes(0, 1)).  Host only.
  */
 size_t lc_workspace_bytes(uint64_t n, int nbits);
 

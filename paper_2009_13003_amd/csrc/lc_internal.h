@@ -92,8 +92,9 @@ struct EncState {
 
 // Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] and
 // chunk_maxexp[kMaxChunks] (u32, at fixed places so that they can be left cleared from one call to the
-// next), chunk_list[kMaxChunks] (u32), chunk_bits[num_chunks] (u32, padded to 256 bytes) and one slot of
-// slot_words_of(nbits) 32-bit words per chunk.
+// next), chunk_list[kMaxChunks] (u32), chunk_bits[num_chunks] (u32, padded to 256 bytes), one slot of
+// slot_words_of(nbits) 32-bit words per chunk and, 256-byte aligned behind the slots, 16 bytes per chunk for the
+// largest exponent of every 4 KiB batch of sweep 1.
 // What an encode of binary64 parameters keeps instead of EncState's counts, extremes and bucket map: 2^12
 // (sign, exponent) buckets, 52-bit mantissas (Section 3.1.1, footnote on the bucket count).  Left cleared like them.
 constexpr uint32_t kBuckets64 = 4096;
