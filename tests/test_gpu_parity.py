@@ -1347,3 +1347,54 @@ def test_batched_encode_and_restore_of_16_bit_tensors(lc, tdt):
     with pytest.raises(lc.LcError) as e:
         lc.lc_encode_batch_t([w64], [w64.clone()], nbits, [outs[0]])
     assert e.value.status == lc.ERR_BADARG
+
+
+def test_seeded_mixtures_of_loud_and_quiet_chunks_all_types(lc):
+    """Sixty seeded vectors (1 to 13 chunks, sometimes 60 to 140, ragged ends, offsets, nbits 1 to 4, all four element
+    types): deltas over one to six binades, a random set of chunks quiet (tiny or zero deltas), some of those with 1 to
+    40 loud elements put back.  Every mixture of the sweeps' paths (whole-chunk skips, part-by-part coding, symbols-first
+    decode, the pipelined and the guarded paths) in one vector; blob and restored values as the oracle's."""
+    for seed in range(60):
+        rng = np.random.RandomState(5000 + seed)
+        g = torch.Generator(device=DEV); g.manual_seed(5000 + seed)
+        nchunks = int(rng.randint(1, 14)) if seed % 7 else int(rng.randint(60, 140))
+        n = nchunks * 16384 + int(rng.choice([0, 1, 255, 256, 1023, 1024, 4097, 9000, 16383]))
+        nbits = int(rng.randint(1, 5))
+        tdt = [torch.float32, torch.float32, torch.bfloat16, torch.float16, torch.float64][seed % 5]
+        off = int(rng.choice([0, 0, 0, 1, 2]))
+        work = torch.float64 if tdt == torch.float64 else torch.float32
+        binades = int(rng.randint(1, 7))
+        e = torch.randint(8, 8 + binades, (n + 8,), generator=g, device=DEV).to(work)
+        d = torch.exp2(-e) * (1 + torch.rand(n + 8, generator=g, device=DEV, dtype=work))
+        d = d * (2 * torch.randint(0, 2, (n + 8,), generator=g, device=DEV).to(work) - 1)
+        nq = int(rng.randint(0, nchunks + 2))
+        for c in rng.choice(nchunks + 1, size=min(nq, nchunks + 1), replace=False):
+            lo, hi = int(c) * 16384, min(n + 8, (int(c) + 1) * 16384)
+            if lo >= hi:
+                continue
+            loud = d[lo:hi].clone()
+            d[lo:hi] = (2.0 ** -20) * (1 + torch.rand(hi - lo, generator=g, device=DEV, dtype=work)) if rng.rand() < 0.7 else 0
+            k = int(rng.choice([0, 1, 2, 5, 40]))
+            if k:
+                idx = torch.from_numpy(rng.randint(0, hi - lo, size=k)).to(DEV)
+                d[lo:hi][idx] = loud[idx]
+        rt = torch.zeros(n + 8, device=DEV, dtype=tdt)
+        wt = d.to(tdt)                                                   # (w_ref = 0: every delta is its own value, exactly)
+        w, r = wt[off:off + n], rt[off:off + n]
+        tag = "seed %d n=%d nbits=%d %s off=%d" % (seed, n, nbits, str(tdt), off)
+        if tdt == torch.float32:
+            check_case(lc, w, r, nbits, tag)
+        elif tdt == torch.float64:
+            check_case64(lc, w, r, nbits, tag)
+        else:
+            print("case", tag, flush=True)
+            code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
+            out = lc.alloc_out(n, nbits, DEV)
+            size = lc.lc_encode_t(w, r, nbits, out)
+            blob_cpu = orc.encode_t(raw16(w), raw16(r), nbits, code)
+            assert np.array_equal(out[:size].cpu().numpy(), blob_cpu), tag
+            rec = rt.clone()
+            assert lc.lc_decode_t(out, rec[off:off + n]) == size
+            ref_h = raw16(r)
+            orc.decode_t(blob_cpu, ref_h, code)
+            assert np.array_equal(raw16(rec[off:off + n]).view(np.uint16), ref_h.view(np.uint16)), tag
