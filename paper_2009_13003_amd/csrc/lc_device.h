@@ -196,11 +196,10 @@ __device__ __forceinline__ void load_row64(const void* __restrict__ p, u64 idx, 
         for (int v = 0; v < 4; ++v) x[v] = (idx + v < n) ? static_cast<const double*>(p)[idx + v] : 0.0;
     }
 }
-typedef double f64x2 __attribute__((ext_vector_type(2)));
+// (plain stores: marked non-temporal, the two 16-byte halves of a lane's 32 bytes made this sweep 15 % slower)
 __device__ __forceinline__ void store4_64(void* base, u64 i, const double (&x)[4]) {
-    f64x2* q = reinterpret_cast<f64x2*>(static_cast<double*>(base) + i);
-    const f64x2 lo = {x[0], x[1]}, hi = {x[2], x[3]};
-    __builtin_nontemporal_store(lo, q); __builtin_nontemporal_store(hi, q + 1);
+    double2* q = reinterpret_cast<double2*>(static_cast<double*>(base) + i);
+    q[0] = make_double2(x[0], x[1]); q[1] = make_double2(x[2], x[3]);
 }
 
 template <bool FAST, int DT = kF32>
