@@ -268,12 +268,16 @@ def chain_leg(device, steps):
         blobs.append(out[:size].clone())
     gb = 4.0 * n / 1e9
     restored = chain.w0.clone()
+    lc.lc_decode(blobs[0], restored)                      # untimed, as for the fused restore below
+    restored.copy_(chain.w0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for b in blobs:
         lc.lc_decode(b, restored)
     t_seq = time.perf_counter() - t0
     same_seq = bool(torch.equal(restored.view(torch.int32), tracked.view(torch.int32)))
+    restored.copy_(chain.w0)
+    lc.lc_decode_many(blobs, restored)                    # untimed: the first launch of these kernels in the process
     restored.copy_(chain.w0)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -78,13 +78,6 @@ __device__ __forceinline__ float4 load_stream(const float4* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
-// 16-byte store of data this kernel does not read again (the slots of sweep 2: 4 % off that sweep on dense data)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void store_stream(uint4* p, const uint4& v) {
-    const u32x4 x = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(p));
-}
-
 // ---- element types of the parameter arrays.  The method works on the fp32 delta (Algorithm 1 line 4):
 // bf16 / fp16 parameters are widened exactly on load, and the restored value fl32(w_ref + rep) is rounded
 // once, to nearest even, on store.  Raw<DT> is what one lane holds of one row: 4 consecutive elements.

@@ -835,7 +835,7 @@ __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const Chunk
     {
         const uint4* src = reinterpret_cast<const uint4*>(L.stage);
         uint4* dst = reinterpret_cast<uint4*>(cur.slot + kLaneBitsWords);
-        for (u32 i = lane; i < rows * (kW / 4); i += kW) store_stream(dst + i, src[i]);
+        for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
     }
     finish_lane_sizes(cur, nb, nw);
 }
