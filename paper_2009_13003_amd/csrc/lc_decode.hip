@@ -701,7 +701,11 @@ __device__ __forceinline__ void fused_row(const FusedHead<T>& H, const u32* pay,
             for (int v = 0; v < 4; ++v)
 #pragma unroll
                 for (int t = 0; t < T; ++t) x[v] = stored<DT>(__fadd_rn(x[v], __uint_as_float(rep[v][t])));   // in blob order
-            store4<DT>(w_ref, idx, x);
+            // (binary32 rows as a plain float4 store: with non-temporal stores, or with the same 16 bytes stored through
+            // a compiler vector type, the first sweep over parameters that a device copy had just written took 830-880 us
+            // instead of 600-650)
+            if constexpr (DT == kF32) *reinterpret_cast<float4*>(static_cast<float*>(w_ref) + idx) = make_float4(x[0], x[1], x[2], x[3]);
+            else store4<DT, false>(w_ref, idx, x);
         }
     } else {
 #pragma unroll

@@ -168,14 +168,17 @@ __device__ __forceinline__ void store_one(void* base, u64 i, float x) {
 
 // Restored rows are written once and not read again by the sweep: non-temporal stores, like the loads (a bare
 // read-modify-write sweep in this access pattern runs 4-5 % faster with both marked than with the loads alone).
-template <int DT>
+// (STREAM false: plain stores, which the sweep over several blobs keeps.)
+template <int DT, bool STREAM = true>
 __device__ __forceinline__ void store4(void* base, u64 i, const float (&x)[4]) {
     if constexpr (DT == kF32) {
         const f32x4 v = {x[0], x[1], x[2], x[3]};
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(static_cast<float*>(base) + i));
+        if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(static_cast<float*>(base) + i));
+        else *reinterpret_cast<f32x4*>(static_cast<float*>(base) + i) = v;
     } else {
         const u32x2 v = {narrow16_pair(x[0], x[1], DT == kBF16), narrow16_pair(x[2], x[3], DT == kBF16)};
-        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(base) + i));
+        if constexpr (STREAM) __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(static_cast<uint16_t*>(base) + i));
+        else *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(base) + i) = v;
     }
 }
 
