@@ -104,12 +104,40 @@ __device__ __forceinline__ bool dec_chunk_ok(const uint8_t* blob, u64 area, u64 
     return ok;
 }
 
+// The same for chunks c0 .. c0 + 3 at once (their loads in flight together); false if any of those below nchunks fails.
+__device__ __forceinline__ bool dec_chunks_ok4(const uint8_t* blob, u64 area, u64 tw, u32 nchunks, u32 c0) {
+    const u32* off_tab = reinterpret_cast<const u32*>(blob + kHeaderBytes);
+    const u32 lane = lane_id();
+    u64 o[5];
+#pragma unroll
+    for (u32 k = 0; k < 5; ++k) o[k] = c0 + k <= nchunks ? off_tab[c0 + k] : 0;
+    bool ok[4];
+    u32 lb[4];
+#pragma unroll
+    for (u32 k = 0; k < 4; ++k) {
+        const u32 c = c0 + k;
+        ok[k] = c < nchunks && o[k] <= o[k + 1] && o[k + 1] <= tw && o[k + 1] - o[k] >= kLaneBitsWords && (c > 0 || o[k] == 0) &&
+                (c + 1 < nchunks || o[k + 1] == tw);
+        lb[k] = ok[k] ? reinterpret_cast<const uint16_t*>(blob + area + 4 * o[k])[lane] : 0u;
+    }
+    bool all = true;
+#pragma unroll
+    for (u32 k = 0; k < 4; ++k) {
+        if (c0 + k >= nchunks) continue;
+        const u32 sum = wave_sum32(lb[k]);
+        all = all && ok[k] && (o[k + 1] - o[k] == kLaneBitsWords + ((sum + 31) >> 5)) && sum > 0 && !__any(lb[k] > kR * kV * 15);
+    }
+    return all;
+}
+
 __device__ __forceinline__ void raise_status(Workspace* ws, HostResult* host, u64 epoch, u32 status) {
     const u64 word = (epoch << 8) | status;
     atomicMax(&ws->dec_status, word);     // gates the decode sweep on the device
     host->dec_status = word;              // what the host reads after waiting for the stream (any finding will do)
 }
 
+// PER: chunks per wavefront, 1 or 4 (4 when one chunk each would take many rounds of workgroups: several blobs, or a long one)
+template <int PER>
 __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u64 n, u64 max_total, Workspace* ws,
                                                    u32 nchunks, u64 epoch, HostResult* host, u32 dtype) {
     const u32 set = first + blockIdx.y, host_slot = set;     // one grid row per blob
@@ -135,9 +163,12 @@ __global__ __launch_bounds__(256) void k_dec_check(BlobList blobs, u32 first, u6
         return;
     }
     const u64 tw = (total - area) / 4;
-    // ---- one chunk per wavefront
-    const u32 c = blockIdx.x * 4 + (t >> 6);
-    if (c < nchunks && !dec_chunk_ok(blob, area, tw, nchunks, c) && lane == 0) raise_status(ws, host, epoch, 4u);
+    // ---- one chunk, or four, per wavefront
+    const u32 c0 = (blockIdx.x * 4 + (t >> 6)) * PER;
+    if (c0 < nchunks) {
+        const bool ok = PER == 4 ? dec_chunks_ok4(blob, area, tw, nchunks, c0) : dec_chunk_ok(blob, area, tw, nchunks, c0);
+        if (!ok && lane == 0) raise_status(ws, host, epoch, 4u);
+    }
     if (blockIdx.x != 0) return;
     // ---- workgroup 0: symbol table, codes, look-up table
     DecSet& D = ws->dec_set[set];
@@ -960,9 +991,14 @@ void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t 
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
                       uint64_t epoch, HostResult* host, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
-    const u64 blocks = nchunks ? (nchunks + 3) / 4 : 1;
-    hipLaunchKernelGGL(k_dec_check, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
-                       ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
+    // one chunk per wavefront while that is at most a few rounds of workgroups on the chip, else four
+    const bool four = (u64)count * ((nchunks + 3) / 4) > 8192;
+    const u64 per_block = four ? 16 : 4;
+    const u64 blocks = nchunks ? (nchunks + per_block - 1) / per_block : 1;
+    if (four) hipLaunchKernelGGL(k_dec_check<4>, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
+                                 ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
+    else hipLaunchKernelGGL(k_dec_check<1>, dim3((u32)blocks, (u32)count), dim3(256), 0, s, blobs, (u32)first, (u64)n, (u64)max_total,
+                            ws, (u32)nchunks, (u64)epoch, host, (u32)dtype);
 }
 
 
