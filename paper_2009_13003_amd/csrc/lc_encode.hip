@@ -662,7 +662,8 @@ __device__ __noinline__ void pack_chunk_parts(const ChunkRef ch, u32 cl_merged, 
     auto flush = [&]() {
         if (nb >= 32) { slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc >> (nb - 32)); ++nw; nb -= 32; }
     };
-    const u32 len_merged = cl_merged & 31, per_step = 32 / len_merged;       // (the merged symbol occurs here: length >= 1)
+    // (a chunk with an unmarked part holds merged elements, so their symbol has a code; without one nothing is skipped)
+    const u32 len_merged = cl_merged & 31, per_step = len_merged ? 32 / len_merged : 1;
     u32 run = 0;                                                             // per_step copies of the merged code
     for (u32 i = 0; i < per_step; ++i) run = (run << len_merged) | (cl_merged >> 5);
     auto code_element = [&](float a, float b) {
@@ -914,7 +915,7 @@ struct VectorChunks {
         if (valid && aligned && batch_max) {
             const u64 inside = n - (u64)c * kChunk, part_elems = kChunk / parts_per_chunk;
             const u32 whole = inside >= kChunk ? parts_per_chunk : (u32)(inside / part_elems);
-            ch.by_parts = parts_to_read(c, whole, &ch.parts);
+            ch.by_parts = whole != 0 && parts_to_read(c, whole, &ch.parts);   // (less than one whole part: the guarded path)
             if (ch.by_parts) ch.fast = false;        // off the pipelined path: see pack_chunk_parts
         }
         return ch;

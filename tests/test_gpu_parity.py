@@ -1398,3 +1398,21 @@ def test_seeded_mixtures_of_loud_and_quiet_chunks_all_types(lc):
             ref_h = raw16(r)
             orc.decode_t(blob_cpu, ref_h, code)
             assert np.array_equal(raw16(rec[off:off + n]).view(np.uint16), ref_h.view(np.uint16)), tag
+
+
+@pytest.mark.parametrize("n", [1, 100, 1023, 1024, 1025, 4096, 5000, 16384, 16384 + 1024, 3 * 16384 + 2048 + 7])
+def test_vectors_in_which_no_element_is_merged(lc, n):
+    """Every delta lies in a kept bucket (three buckets, nbits 2), so the merged symbol has no code at all: short
+    vectors, vectors of exactly one or a few 4 KiB parts, whole chunks and ragged ends, fp32 and bf16."""
+    g = torch.Generator(device=DEV); g.manual_seed(n)
+    w_ref = torch.zeros(n, device=DEV)
+    pick = torch.randint(0, 3, (n,), generator=g, device=DEV)
+    mag = torch.where(pick == 2, 0.25, 0.5) * (1 + 0.5 * torch.rand(n, generator=g, device=DEV))
+    w = torch.where(pick == 1, -mag, mag)                       # buckets (+, -1), (-, -1), (+, -2) once n is large enough
+    blob = check_case(lc, w, w_ref, 2, "no merged element")
+    hdr = lcb1_reader.parse_header(blob)
+    assert hdr["slots"][hdr["K"]]["len"] == 0 and hdr["slots"][hdr["K"]]["cnt"] == 0
+    wt, rt = w.to(torch.bfloat16), w_ref.to(torch.bfloat16)
+    out = lc.alloc_out(n, 2, DEV)
+    size = lc.lc_encode_t(wt, rt, 2, out)
+    assert np.array_equal(out[:size].cpu().numpy(), orc.encode_t(raw16(wt), raw16(rt), 2, orc.DT_BF16))
