@@ -63,6 +63,20 @@ def test_host_only_entry_points(lib):
     for bad in ((10, 0), (10, 5), ((1 << 32) + 1, 3)):
         assert lib.lc_encode_bound(*bad) == 0 and lib.lc_workspace_bytes(*bad) == 0
     assert lib.lc_workspace_bytes(1 << 28, 4) >= 8 * (1 << 14)
+    # the scratch grows with n and with nbits, by at least a slot (the chunk's longest code bits) and 16 bytes of notes
+    # per chunk
+    fixed = lib.lc_workspace_bytes(0, 1)
+    assert fixed == lib.lc_workspace_bytes(0, 4)
+    for nbits in (1, 2, 3, 4):
+        prev = fixed
+        for nchunks in (1, 2, 63, 64, 65, 1000):
+            size = lib.lc_workspace_bytes(nchunks * 16384, nbits)
+            assert size > prev
+            assert size - fixed >= nchunks * (16 + 4 + 16384 * ((1 << nbits) - 1) // 8)
+            assert lib.lc_workspace_bytes(nchunks * 16384 - 1, nbits) == size          # a ragged chunk counts as a chunk
+            if nbits > 1:
+                assert size > lib.lc_workspace_bytes(nchunks * 16384, nbits - 1)
+            prev = size
     assert lib.lc_strerror(0) == b"ok" and lib.lc_strerror(-2) == lib.lc_strerror(2) != b"ok"
     # blob info on a host header
     import struct
