@@ -1416,3 +1416,42 @@ def test_vectors_in_which_no_element_is_merged(lc, n):
     out = lc.alloc_out(n, 2, DEV)
     size = lc.lc_encode_t(wt, rt, 2, out)
     assert np.array_equal(out[:size].cpu().numpy(), orc.encode_t(raw16(wt), raw16(rt), 2, orc.DT_BF16))
+
+
+def test_calls_from_two_host_threads(lc):
+    """Two host threads, each with its own stream, vectors and outputs, calling lc_encode / lc_decode at the same time
+    (ctypes drops the interpreter lock during a call): every call returns its own vector's blob and restore, the ones
+    a single thread gets."""
+    import threading
+    cases = []
+    for k, (n, nbits) in enumerate([(5 * 16384 + 99, 3), (11 * 16384 + 4097, 4)]):
+        w, w_ref = laplace_case(n, seed=900 + k)
+        out = lc.alloc_out(n, nbits, DEV)
+        size = lc.lc_encode(w, w_ref, nbits, out)
+        rec = w_ref.clone()
+        lc.lc_decode(out, rec)
+        cases.append((w, w_ref, nbits, out[:size].clone(), rec))
+    errors = []
+
+    def work(k):
+        try:
+            w, w_ref, nbits, want_blob, want_rec = cases[k]
+            stream = torch.cuda.Stream()
+            out = lc.alloc_out(w.numel(), nbits, DEV)
+            torch.cuda.synchronize()
+            for _ in range(40):
+                size = lc.lc_encode(w, w_ref, nbits, out, stream=stream)
+                assert size == want_blob.numel() and torch.equal(out[:size], want_blob)
+                rec = w_ref.clone()
+                torch.cuda.synchronize()
+                assert lc.lc_decode(out, rec, stream=stream) == size
+                assert torch.equal(rec.view(torch.int32), want_rec.view(torch.int32))
+        except Exception as e:                                      # noqa: BLE001  (reported by the main thread)
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads) and not errors, errors
