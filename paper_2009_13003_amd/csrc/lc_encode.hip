@@ -1105,11 +1105,12 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, c
 // chunk's word offset is the sum of the record sizes before it (whole groups of 64 chunks from
 // group_words, the rest from chunk_bits).  The 64 lane strings are joined without gaps: payload
 // word W0 + j of a lane takes the low bits of its word j-1 and the high bits of its word j.
-// A payload of up to kPlaceWords words is assembled in LDS (every lane ORs its shifted words
-// into a cleared buffer, so words shared by neighbouring lanes need no special care) and
-// written out with coalesced stores.  A larger payload is written directly: every word exactly
-// once, by the lane whose string holds its first bit, boundary words merged through LDS.
-constexpr u32 kPlaceWords = 2048;
+// The payload is assembled in LDS, kPlaceWords words at a time: every lane ORs the words of its shifted string
+// that fall into the window into a cleared buffer (so words shared by neighbouring lanes need no special care),
+// then the window is written out with coalesced stores.  Most chunks fit one window.  PW words per window: 1024
+// lets twice as many workgroups share a compute unit as 2048, which a call with few chunks (all of its workgroups
+// resident anyway, one chunk's latency what counts) takes instead.
+constexpr u32 kPlaceWords = 1024, kPlaceWordsFew = 2048;
 
 // Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
@@ -1188,16 +1189,13 @@ __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, R
     __threadfence_system();
 }
 
-// Chunk c of one vector, by one wavefront of a workgroup of four; `valid` false: an idle wavefront that only
-// keeps the workgroup's barrier company.
+// Chunk c of one vector, by one wavefront of a workgroup of four; `valid` false: an idle wavefront.
+template <u32 PW>
 __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                             const u32* __restrict__ group_words, const u32* __restrict__ prov,
                                             u32 slot_words, u32 nchunks, u32 c, bool valid) {
-    __shared__ u32 s_off_all[4][kW + 1], s_hw_all[4][kW];
-    __shared__ u32 s_buf_all[4][kPlaceWords];
+    __shared__ u32 s_buf_all[4][PW];
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
-    u32* s_off = s_off_all[wv];
-    u32* s_hw = s_hw_all[wv];
     u32* s_buf = s_buf_all[wv];
     const u32* slot = prov + (u64)(valid ? c : 0) * slot_words;
     const u32 own = valid ? __builtin_amdgcn_readfirstlane(chunk_bits[c]) : 0;
@@ -1240,50 +1238,41 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
     }
     const u32 sh = o & 31, W0 = o >> 5, nloc = (bits + 31) >> 5;
     const u32 nt = (bits && !merged) ? ((o + bits - 1) >> 5) - W0 + 1 : 0;   // payload words this lane touches
-    u32 nt_max = nt;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) nt_max = max(nt_max, (u32)__shfl_xor(nt_max, d, 64));
     const u32* lane_words = slot + kLaneBitsWords + lane;
-    const bool staged = nwords <= kPlaceWords && !merged;    // wave-uniform
-    if (staged) {
-        for (u32 i = lane; i < nwords; i += kW) s_buf[i] = 0;
-    } else {
-        s_off[lane] = o; s_hw[lane] = 0;
-        if (lane == 0) s_off[kW] = total_bits;
-    }
-    u32 prev = 0, tail = 0;
-    bool own_tail = false;
-    for (u32 j0 = 0; j0 < nt_max; j0 += 8) {
-        u32 buf[8];
+    if (merged) return;
+    // Only this wavefront touches its buffer, and a wavefront's LDS operations take effect in program order: no
+    // barrier between clearing, ORing and reading a window.
+    for (u32 win = 0; win < nwords; win += PW) {
+        const u32 wlen = min(PW, nwords - win);
+        for (u32 i = lane; i < wlen; i += kW) s_buf[i] = 0;
+        // the touched words j of this lane (payload word W0 + j) that lie inside the window
+        const u32 jlo = win > W0 ? win - W0 : 0;
+        const u32 jend = win + wlen > W0 ? win + wlen - W0 : 0;
+        const u32 jhi = jend < nt ? jend : nt;
+        const u32 cnt = jhi > jlo ? jhi - jlo : 0;
+        const u32 cnt_max = wave_max_u32(cnt);
+        u32 prev = (cnt != 0 && jlo != 0) ? lane_words[(jlo - 1) * kW] : 0;   // (jlo - 1 < nloc whenever jlo < nt)
+        for (u32 i0 = 0; i0 < cnt_max; i0 += 8) {
+            u32 buf[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) buf[k] = (j0 + k < nloc) ? lane_words[(j0 + k) * kW] : 0;
+            for (int k = 0; k < 8; ++k) {
+                const u32 j = jlo + i0 + k;
+                buf[k] = (i0 + k < cnt && j < nloc) ? lane_words[j * kW] : 0;
+            }
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const u32 j = j0 + k;
-            if (j < nt) {
-                const u32 val = __builtin_amdgcn_alignbit(prev, buf[k], sh);
-                prev = buf[k];
-                if (staged) {
-                    atomicOr(&s_buf[W0 + j], val);
-                } else {
-                    const bool owned = j > 0 || sh == 0;         // the word's first bit is this lane's
-                    if (!owned) s_hw[lane] = val;
-                    else if (j + 1 == nt) { tail = val; own_tail = true; }
-                    else payload[W0 + j] = val;
+            for (int k = 0; k < 8; ++k) {
+                if (i0 + k < cnt) {
+                    const u32 val = __builtin_amdgcn_alignbit(prev, buf[k], sh);
+                    prev = buf[k];
+                    atomicOr(&s_buf[W0 + jlo + i0 + k - win], val);
                 }
             }
         }
-    }
-    __syncthreads();
-    if (staged) {
-        for (u32 i = lane; i < nwords; i += kW) payload[i] = s_buf[i];
-    } else if (own_tail) {                                       // following lanes may start inside this word
-        const u32 W = W0 + nt - 1;
-        for (u32 q = lane + 1; q < kW && (s_off[q] >> 5) == W; ++q) tail |= s_hw[q];
-        payload[W] = tail;
+        for (u32 i = lane; i < wlen; i += kW) payload[win + i] = s_buf[i];
     }
 }
 
+template <u32 PW>
 __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                                const u32* __restrict__ group_words, const u32* __restrict__ prov,
                                                u32 slot_words, u32 nchunks, u32* chunk_maxexp) {
@@ -1291,7 +1280,7 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const
     // sweep 2 was the last to look at the chunk maxima: leave them cleared for the next call, whatever this one's outcome
     if (c < nchunks && lane_id() == 0) chunk_maxexp[maxexp_slot(c)] = 0;
     // the last workgroup may hold idle wavefronts
-    place_chunk(out, ws, chunk_bits, group_words, prov, slot_words, nchunks, c, c < nchunks && ws->table.status == 0);
+    place_chunk<PW>(out, ws, chunk_bits, group_words, prov, slot_words, nchunks, c, c < nchunks && ws->table.status == 0);
 }
 
 // ----------------------------------------------------------------------------- batched encode
@@ -1413,7 +1402,7 @@ __global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
     const u32 sidx = in_range ? a.seg_of_chunk[g] : 0;
     const Seg& sg = a.segs[sidx];
     EncState* st = &a.states[sidx];
-    place_chunk(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
+    place_chunk<kPlaceWords>(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
                 a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0);
 }
 
@@ -1505,8 +1494,12 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
-    hipLaunchKernelGGL(k_place, dim3((u32)((nchunks + 3) / 4)), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
-                       slot_words, (u32)nchunks, chunk_maxexp);
+    const u32 blocks = (u32)((nchunks + 3) / 4);
+    // (up to 1024 workgroups are resident together on this chip even with the larger windows)
+    if (blocks <= 1024u) hipLaunchKernelGGL(k_place<kPlaceWordsFew>, dim3(blocks), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
+                                                slot_words, (u32)nchunks, chunk_maxexp);
+    else hipLaunchKernelGGL(k_place<kPlaceWords>, dim3(blocks), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
+                            slot_words, (u32)nchunks, chunk_maxexp);
 }
 
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
