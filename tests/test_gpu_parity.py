@@ -1455,3 +1455,26 @@ def test_calls_from_two_host_threads(lc):
     for t in threads:
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads) and not errors, errors
+
+
+def test_chunks_with_very_long_payloads(lc):
+    """A chunk made of the vector's rarest symbols only: its payload (about 7 bits per element, 3,400 words) is more than
+    the placement kernel assembles in one go, in the single-vector call and in the batched call (which use different
+    window sizes); the chunks around it are ordinary.  Blob and restore as the oracle's."""
+    nbits, nchunks = 4, 40
+    n = nchunks * 16384 + 777
+    g = torch.Generator(device=DEV); g.manual_seed(4242)
+    # binade e with probability ~ 2^-(e+1): code lengths 1, 2, 3, ... for the 15 kept buckets
+    e = torch.floor(-torch.log2(torch.rand(n, generator=g, device=DEV).clamp_(min=2.0 ** -13)))
+    for c in (3, 17, 39):                                          # chunks of rare binades only
+        lo, hi = c * 16384, (c + 1) * 16384
+        e[lo:hi] = torch.randint(7, 13, (hi - lo,), generator=g, device=DEV).float()
+    d = torch.exp2(-4 - e) * (1 + torch.rand(n, generator=g, device=DEV))
+    w_ref = torch.zeros(n, device=DEV)
+    w = w_ref + d
+    blob = check_case(lc, w, w_ref, nbits, "very long payloads")
+    hdr = lcb1_reader.parse_header(blob)
+    offs = np.frombuffer(bytes(blob[512:512 + 4 * (nchunks + 2)]), dtype="<u4")
+    words = [int(offs[c + 1]) - int(offs[c]) - 32 for c in (3, 17, 39)]
+    assert min(words) > 3000 and hdr["max_len"] >= 7, (words, hdr["max_len"])
+    check_batch(lc, [w, w[:5 * 16384].clone()], [w_ref, w_ref[:5 * 16384].clone()], nbits)
