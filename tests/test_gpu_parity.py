@@ -1478,3 +1478,18 @@ def test_chunks_with_very_long_payloads(lc):
     words = [int(offs[c + 1]) - int(offs[c]) - 32 for c in (3, 17, 39)]
     assert min(words) > 3000 and hdr["max_len"] >= 7, (words, hdr["max_len"])
     check_batch(lc, [w, w[:5 * 16384].clone()], [w_ref, w_ref[:5 * 16384].clone()], nbits)
+
+
+def test_many_chunks_with_long_payloads(lc):
+    """More than 4096 chunks in one vector (the placement kernel then works with its smaller windows) with payloads
+    of 1,000 to 3,500 words per chunk: blob and restore as the oracle's, in full."""
+    nbits, nchunks = 4, 4200
+    n = nchunks * 16384 + 5
+    g = torch.Generator(device=DEV); g.manual_seed(nbits)
+    e = torch.floor(-torch.log2(torch.rand(n, generator=g, device=DEV).clamp_(min=2.0 ** -13)))
+    for c in (3, 1700, nchunks - 1):
+        lo, hi = c * 16384, (c + 1) * 16384
+        e[lo:hi] = torch.randint(5, 12, (hi - lo,), generator=g, device=DEV).float()
+    d = torch.exp2(-4 - e) * (1 + torch.rand(n, generator=g, device=DEV))
+    w_ref = torch.zeros(n, device=DEV)
+    check_case(lc, w_ref + d, w_ref, nbits, "many chunks, long payloads")
