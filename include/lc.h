@@ -160,14 +160,17 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
  *          Holds the kept buckets and the code lengths of the last blob encoded with it.
  *   used   host pointer or NULL; receives 1 if the blob carries the cached table, else 0.
  * The cached table is used iff it is valid and was made with the same nbits, this checkpoint's
- * kept set (priority promotion on this delta's bucket populations) is the cached one, and
- * exactly the symbols that have a cached code occur.  The blob is then lc_encode's blob with
- * the cached code lengths in place of this delta's own Huffman lengths: the same kept buckets,
- * counts and representatives, hence the same restored weights, in a valid and at most slightly
- * longer coding.  (The paper re-sorts the buckets by population before reusing the table; that
- * needs the populations before the first code is written, i.e. the sweep this call saves, so
- * the cached assignment is reused as it is.)  Otherwise the blob is exactly lc_encode's.  Either
- * way the cache afterwards describes this blob; on an error it is left as it was.
+ * kept set (priority promotion on this delta's bucket populations) is the cached one, exactly
+ * the symbols that have a cached code occur, and the payload under the cached lengths (the sum
+ * of count x cached length) is at most n * nbits bits, so that the blob fits lc_encode_bound
+ * like any other (a stale table on shifted populations could need more; this checkpoint's own
+ * Huffman code never does).  The blob is then lc_encode's blob with the cached code lengths in
+ * place of this delta's own Huffman lengths: the same kept buckets, counts and representatives,
+ * hence the same restored weights, in a valid, possibly longer coding.  (Section 3.2 sorts the
+ * buckets by population before a table is reused; that needs the populations before the first
+ * code is written, i.e. the sweep this call saves, so the cached assignment is reused as it
+ * is.)  Otherwise the blob is exactly lc_encode's.  Either way the cache afterwards describes
+ * this blob; on an error it is left as it was.
  * Other arguments, return value and errors as lc_encode; cache NULL or misaligned: LC_ERR_BADARG.
  */
 #define LC_CACHE_BYTES 256

@@ -366,11 +366,14 @@ int64_t lco_encode(const float* w, const float* wref, uint64_t n, int nbits,
  *   It is used for this checkpoint iff it is valid, was made with the same nbits, its
  *   lengths are a complete prefix code (Kraft sum 1, or a single symbol of length 1),
  *   this checkpoint's kept set (priority promotion on this delta's populations) is
- *   the cached one, and exactly the symbols with a cached code occur.  Then the blob is
- *   that of lco_encode with the cached lengths in place of this delta's Huffman lengths:
- *   same quantized values, same counts and representatives, a valid but possibly longer
- *   coding.  Otherwise the blob is exactly lco_encode's.  Either way the cache afterwards
- *   holds this blob's kept set and lengths; on an error it is left alone.
+ *   the cached one, exactly the symbols with a cached code occur, and the coding fits the
+ *   size every blob of (n, nbits) is promised to fit: sum of count x cached length at most
+ *   n * nbits bits (a stale table on shifted populations can need more than that; this
+ *   checkpoint's own Huffman code never does).  Then the blob is that of lco_encode with
+ *   the cached lengths in place of this delta's Huffman lengths: same quantized values,
+ *   same counts and representatives, a valid but possibly longer coding.  Otherwise the
+ *   blob is exactly lco_encode's.  Either way the cache afterwards holds this blob's kept
+ *   set and lengths; on an error it is left alone.
  *   *used (may be NULL) = 1 if the cached table was used.
  */
 typedef struct { uint32_t valid, nbits, K, pad; uint32_t kept[LCO_SLOTS]; uint32_t len[LCO_SLOTS]; } lco_cache;
@@ -394,6 +397,12 @@ int64_t lco_encode_cached(const float* w, const float* wref, uint64_t n, int nbi
         }
         if (active >= 2 && kraft != (1u << 15)) ok = 0;
         if (active == 1 && kraft != (1u << 14)) ok = 0;
+    }
+    if (ok) {
+        /* the payload under the cached lengths, against what lco_encode_bound allows for it */
+        uint64_t payload_bits = 0;
+        for (int j = 0; j <= M.K; ++j) payload_bits += M.cnt[j] * (uint64_t)cache->len[j];
+        if (payload_bits > n * (uint64_t)nbits) ok = 0;
     }
     if (ok) {
         for (int j = 0; j <= M.K; ++j) M.len[j] = (uint8_t)cache->len[j];

@@ -86,25 +86,29 @@ void collect(const int* slots, int count) {   // after the stream has been waite
     }
 }
 
+// Launch shapes of a device: the compute unit count and the LC_TUNE_* overrides, read once.  Allocates nothing.
+void read_tuning(DeviceState& ds, int dev) {
+    if (ds.tuned) return;
+    int cu = 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) { (void)hipGetLastError(); cu = 256; }
+    ds.tune.num_cu = cu;
+    ds.tune.hist_blocks_per_cu = env_int("LC_TUNE_HIST_BLOCKS_PER_CU", ds.tune.hist_blocks_per_cu, 1, 64);
+    ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
+    ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
+    ds.tune.spec_waves_per_cu = env_int("LC_TUNE_SPEC_WAVES_PER_CU", ds.tune.spec_waves_per_cu, 1, 64);
+    ds.tune.batch_waves_per_cu = env_int("LC_TUNE_BATCH_WAVES_PER_CU", ds.tune.batch_waves_per_cu, 1, 64);
+    ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
+    ds.tune.fused_waves_per_cu = env_int("LC_TUNE_FUSED_WAVES_PER_CU", ds.tune.fused_waves_per_cu, 1, 32);
+    ds.tune.fused_min_waves_per_cu = env_int("LC_TUNE_FUSED_MIN_WAVES_PER_CU", ds.tune.fused_min_waves_per_cu, 1, 32);
+    ds.tuned = true;
+}
+
 // Scratch for the current device, at least `need` bytes.  Returns nullptr with *err set.
 Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); *err = LC_ERR_HIP; return nullptr; }
     DeviceState& ds = g_dev[dev];
-    if (!ds.tuned) {
-        int cu = 0;
-        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) { (void)hipGetLastError(); cu = 256; }
-        ds.tune.num_cu = cu;
-        ds.tune.hist_blocks_per_cu = env_int("LC_TUNE_HIST_BLOCKS_PER_CU", ds.tune.hist_blocks_per_cu, 1, 64);
-        ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
-        ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
-        ds.tune.spec_waves_per_cu = env_int("LC_TUNE_SPEC_WAVES_PER_CU", ds.tune.spec_waves_per_cu, 1, 64);
-        ds.tune.batch_waves_per_cu = env_int("LC_TUNE_BATCH_WAVES_PER_CU", ds.tune.batch_waves_per_cu, 1, 64);
-        ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
-        ds.tune.fused_waves_per_cu = env_int("LC_TUNE_FUSED_WAVES_PER_CU", ds.tune.fused_waves_per_cu, 1, 32);
-        ds.tune.fused_min_waves_per_cu = env_int("LC_TUNE_FUSED_MIN_WAVES_PER_CU", ds.tune.fused_min_waves_per_cu, 1, 32);
-        ds.tuned = true;
-    }
+    read_tuning(ds, dev);
     if (!g_pinned) {
         if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(HostResult), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess ||
             hipHostGetDevicePointer(reinterpret_cast<void**>(&g_pinned_dev), g_pinned, 0) != hipSuccess) {
@@ -133,6 +137,29 @@ Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
 
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
+// Bytes of scratch an encode of nc chunks at nbits takes (what lc_workspace_bytes reports), and where its parts lie.
+constexpr size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+constexpr size_t encode_scratch_bytes(uint64_t nc, int nbits) {
+    return kWorkspaceHead + up256(4 * nc) + (size_t)(nc * (kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u)) * 4) +
+           256 + up256(16 * nc);                                  // + the per-batch maxima of sweep 1
+}
+struct Scratch {
+    Workspace* ws;
+    uint32_t *group_words, *chunk_maxexp, *chunk_list, *chunk_bits, *prov;
+    uint8_t* batch_max;                                           // one byte per 4 KiB batch of sweep 1 (16 per chunk at most), behind the slots
+    uint32_t slot_words;
+    Scratch(void* base, uint64_t nc, int nbits) {
+        ws = static_cast<Workspace*>(base);
+        group_words = reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(base) + kWorkspaceFixed);
+        chunk_maxexp = group_words + kMaxGroups;
+        chunk_list = chunk_maxexp + kMaxChunks;
+        chunk_bits = chunk_list + kMaxChunks;
+        prov = chunk_bits + (nc + 63) / 64 * 64;
+        slot_words = slot_words_of(nbits);
+        batch_max = reinterpret_cast<uint8_t*>((reinterpret_cast<uintptr_t>(prov + nc * slot_words) + 255) & ~(uintptr_t)255);
+    }
+};
+
 // Every call uses the device's one scratch area: work enqueued on `s` must not start before the
 // latest asynchronous call has finished with it.
 bool order_after_async(DeviceState* ds, hipStream_t s) {
@@ -153,9 +180,7 @@ size_t lc_encode_bound(uint64_t n, int nbits) {
 
 size_t lc_workspace_bytes(uint64_t n, int nbits) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N) return 0;
-    const uint64_t nc = num_chunks_of(n);
-    return kWorkspaceHead + (size_t)((4 * nc + 255) / 256 * 256) + (size_t)(nc * slot_words_of(nbits) * 4) +
-           256 + (size_t)((16 * nc + 255) / 256 * 256);      // + the per-batch maxima of sweep 1
+    return encode_scratch_bytes(num_chunks_of(n), nbits);
 }
 
 int lc_set_workspace(void* dev_ws, size_t bytes) {
@@ -188,15 +213,11 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
     if (!ws) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint32_t* group_words = reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(ws) + kWorkspaceFixed);
-    uint32_t* chunk_maxexp = group_words + kMaxGroups;
-    uint32_t* chunk_list = chunk_maxexp + kMaxChunks;
-    uint32_t* chunk_bits = chunk_list + kMaxChunks;
-    const uint64_t nc = num_chunks_of(n);
-    uint32_t* prov = chunk_bits + (nc + 63) / 64 * 64;
-    const uint32_t slot_words = slot_words_of(nbits);
-    // one byte per 4 KiB batch of sweep 1 (16 per chunk at most), behind the slots
-    uint8_t* batch_max = reinterpret_cast<uint8_t*>((reinterpret_cast<uintptr_t>(prov + nc * slot_words) + 255) & ~(uintptr_t)255);
+    const Scratch sc(ws, num_chunks_of(n), nbits);
+    uint32_t *group_words = sc.group_words, *chunk_maxexp = sc.chunk_maxexp, *chunk_list = sc.chunk_list, *chunk_bits = sc.chunk_bits,
+             *prov = sc.prov;
+    const uint32_t slot_words = sc.slot_words;
+    uint8_t* batch_max = sc.batch_max;
     uint8_t* o = static_cast<uint8_t*>(out);
     int ticket = -1;
     if (async) {

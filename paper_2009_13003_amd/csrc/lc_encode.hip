@@ -265,7 +265,7 @@ struct TableLds {
 
 // When the sweep before it coded speculatively with a cached table (ws->spec), the kernel also decides
 // whether that stands: this checkpoint's kept set must be the cached one and exactly the symbols with a
-// cached code must occur.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
+// cached code must occur, in a coding of at most n * nbits payload bits.  If so the cached lengths are kept and the sweep's output is final (spec_ok);
 // if not, the traces of the speculative coding are cleared and the table is this checkpoint's own.
 // With chunk_list (and a workgroup of more than one wavefront) the other wavefronts meanwhile list the chunks
 // that sweep 2 has to read: all but the full chunks whose largest exponent lies below every kept bucket.
@@ -371,7 +371,10 @@ __device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int
             u32 cached_len = 0;
             if (lane < K) differs = T.kept[lane] != S.kept[lane];
             if (lane < msym) { cached_len = T.codelen[lane] & 31; differs = differs || ((cached_len != 0) != (c != 0)); }
-            reuse = !nonfinite && T.K == K && !__any(differs);
+            // ... and the cached lengths must not need more than the n * nbits payload bits every blob is promised to
+            // fit (a stale table on shifted populations can; this checkpoint's own Huffman code never does)
+            const u64 payload_bits = wave_sum64(lane < msym ? c * cached_len : 0ull);
+            reuse = !nonfinite && T.K == K && !__any(differs) && payload_bits <= n * (u64)nbits;
             if (reuse) len = cached_len;
         }
         if (!reuse && nl == 1) len = have ? 1u : 0u;

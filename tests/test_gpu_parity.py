@@ -599,6 +599,42 @@ def test_cached_encode_edge_cases(lc):
     assert e.value.status == lc.ERR_BADARG
 
 
+def test_cached_encode_stale_table_never_outgrows_the_bound(lc):
+    """A table cached on skewed populations, then the same buckets with the populations reversed: under the cached
+    lengths the blob would need about 7 bits per element where lc_encode_bound promises 3, so the reuse is refused
+    (blob = lc_encode's, used = 0), as in the oracle; nothing is written behind the stated bound."""
+    n, nbits = 4 * 16384, 3
+    mags = [2.0 ** -e for e in range(1, 8)]
+    skew = [n >> (j + 1) for j in range(7)]
+    skew.append(n - sum(skew))
+
+    def delta(counts, seed):
+        d = torch.cat([torch.full((c,), m) for c, m in zip(counts[:-1], mags)] + [torch.zeros(counts[-1])])
+        g = torch.Generator(); g.manual_seed(seed)
+        return d[torch.randperm(n, generator=g)].to(DEV)
+
+    zero = torch.zeros(n, device=DEV)
+    bound = lc.lc_encode_bound(n, nbits)
+    buf = torch.full((bound + 65536,), 0x5A, dtype=torch.uint8, device=DEV)     # guard bytes behind the bound
+    out = buf[:bound]
+    cache_gpu, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    _, used = cached_step(lc, delta(skew, 0), zero, nbits, out, cache_gpu, cache_cpu)
+    assert not used and [int(x) for x in cache_cpu[20:28]] == [1, 2, 3, 4, 5, 6, 7, 7]
+    d2 = delta(skew[::-1], 1)
+    blob, used = cached_step(lc, d2, zero, nbits, out, cache_gpu, cache_cpu)
+    assert not used and blob.numel() <= bound
+    assert bool((buf[bound:] == 0x5A).all())
+    size = lc.lc_encode(d2, zero, nbits, out)
+    assert size == blob.numel() and torch.equal(out[:size], blob)
+    # the asynchronous form takes the same decision
+    cache_async = lc.new_cache(DEV)
+    for counts, seed in ((skew, 0), (skew[::-1], 1)):
+        ticket = lc.lc_encode_async(delta(counts, seed), zero, nbits, out, cache_async)
+        size2, used2 = lc.lc_encode_wait(ticket)
+        assert not used2
+    assert size2 == size and torch.equal(out[:size], blob) and bool((buf[bound:] == 0x5A).all())
+
+
 # ---------------------------------------------------------------- asynchronous encode (Section 3.2)
 def test_async_encode_equals_sync_and_releases_inputs(lc):
     """lc_encode_async + lc_encode_wait give lc_encode's blob; after lc_encode_release_inputs the caller may

@@ -582,6 +582,64 @@ def test_cached_encode_misses():
     assert u and np.array_equal(b, orc.encode((w0 + d1).astype(np.float32), w0, 2))
 
 
+def _by_symbol(counts, mags, seed=0):
+    """A delta on a zero state whose symbol j (priority order: larger magnitude first) occurs counts[j] times;
+    the last count is the number of zeros (the merged bucket)."""
+    parts = [np.full(c, m, np.float32) for c, m in zip(counts[:-1], mags)] + [np.zeros(counts[-1], np.float32)]
+    d = np.concatenate(parts)
+    np.random.RandomState(seed).shuffle(d)
+    return d
+
+
+def test_cached_encode_never_outgrows_the_bound():
+    """A table cached on skewed populations, then the populations reversed: the cached lengths would need about
+    7 bits per element where lc_encode_bound promises nbits = 3, so the cache must not be used and the blob is the
+    plain one (Section 3.2 re-sorts the buckets by population before a table is reused; this reading does not, so
+    it must at least refuse a reuse that outgrows the buffer)."""
+    n, nbits = 65536, 3
+    mags = np.float32([2.0 ** -e for e in range(1, 8)])                  # 7 kept buckets, all positive
+    skew = [n >> (j + 1) for j in range(7)]                               # 32768, 16384, ... 512
+    skew.append(n - sum(skew))                                            # merged bucket: 512
+    zero = np.zeros(n, np.float32)
+    cache = orc.new_cache()
+    d1 = _by_symbol(skew, mags)
+    b1, u1 = orc.encode_cached(d1, zero, nbits, cache)
+    assert not u1 and [int(x) for x in cache[20:28]] == [1, 2, 3, 4, 5, 6, 7, 7]
+    d2 = _by_symbol(skew[::-1], mags, seed=1)                             # same buckets, populations reversed
+    stale = cache.copy()
+    b2, u2 = orc.encode_cached(d2, zero, nbits, cache)
+    plain = orc.encode(d2, zero, nbits)
+    assert not u2 and np.array_equal(b2, plain) and b2.size <= orc.encode_bound(n, nbits)
+    assert not np.array_equal(cache, stale)                               # the cache now describes this blob
+    assert [int(x) for x in cache[20:28]] == [s["len"] for s in lcb1_reader.parse_header(plain)["slots"][:8]]
+    # the same populations as the cached ones again: a hit
+    cache = stale.copy()
+    b3, u3 = orc.encode_cached(_by_symbol(skew, mags, seed=2), zero, nbits, cache)
+    assert u3
+
+
+def test_cached_encode_reuse_limit_is_n_times_nbits_bits():
+    """The limit itself: a reuse whose payload is exactly n * nbits bits is taken, one bit more is not."""
+    nbits, n = 2, 1000
+    mags = np.float32([0.5, 0.25, 0.125])
+    zero = np.zeros(n, np.float32)
+    hand = orc.new_cache()
+    hand[0], hand[1], hand[2] = 1, nbits, 3
+    hand[4:7] = [126, 125, 124]                                           # buckets of 0.5, 0.25, 0.125
+    hand[20:24] = [1, 2, 3, 3]
+    at = [300, 400, 200, 100]                                             # 300 + 800 + 600 + 300 = 2000 = n * nbits
+    c = hand.copy()
+    blob, used = orc.encode_cached(_by_symbol(at, mags), zero, nbits, c)
+    assert used and [s["len"] for s in lcb1_reader.parse_header(blob)["slots"][:4]] == [1, 2, 3, 3]
+    _, _, lane_bits, _ = lcb1_reader.read(blob)
+    assert int(sum(lb.sum() for lb in lane_bits)) == n * nbits
+    over = [299, 400, 201, 100]                                           # 2002 bits
+    c = hand.copy()
+    d = _by_symbol(over, mags)
+    blob, used = orc.encode_cached(d, zero, nbits, c)
+    assert not used and np.array_equal(blob, orc.encode(d, zero, nbits))
+
+
 def test_cached_encode_rejects_a_damaged_cache():
     """A cache whose lengths are not a complete prefix code is not used, whatever else matches."""
     n, nbits = lcb1_reader.C + 9, 3
