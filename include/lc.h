@@ -81,7 +81,7 @@ enum lc_status {
     LC_OK = 0,
     LC_ERR_BADARG = 1,           /* null/misaligned pointer, nbits outside [1,4], n too large, n mismatch */
     LC_ERR_NONFINITE = 2,        /* some delta is Inf or NaN */
-    LC_ERR_OUT_TOO_SMALL = 3,    /* reserved (the encoder cannot exceed lc_encode_bound) */
+    LC_ERR_OUT_TOO_SMALL = 3,    /* lc_encode_sized: out_bytes below lc_encode_bound (no blob ever exceeds that bound) */
     LC_ERR_BAD_BLOB = 4,         /* blob fails validation */
     LC_ERR_HIP = 5,              /* a HIP runtime call failed */
     LC_ERR_WORKSPACE = 6         /* caller-supplied workspace too small or misaligned */
@@ -133,6 +133,17 @@ int lc_set_workspace(void* dev_ws, size_t bytes);
  */
 lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
                    void* out, void* stream);
+
+/*
+ * The two calls with the sizes of the caller's buffers stated (any dtype of lc_encode_t / lc_decode_t):
+ * lc_encode_sized returns -LC_ERR_OUT_TOO_SMALL without touching anything if out_bytes < lc_encode_bound(n, nbits),
+ * and is lc_encode_t otherwise; lc_decode_sized is lc_decode_t that also refuses, before any read past the header
+ * and with w_ref untouched, a blob whose header claims more than blob_bytes bytes (LC_ERR_BAD_BLOB; blob_bytes
+ * below 512 likewise), so a forged size field cannot make the kernels read past a tightly allocated buffer.
+ */
+lc_ssize lc_encode_sized(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, size_t out_bytes, int dtype,
+                         void* stream);
+lc_ssize lc_decode_sized(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream);
 
 /*
  * Parameters stored as bf16 or fp16.  The method works on the fp32 delta (Algorithm 1 line 4), so the
@@ -211,8 +222,9 @@ lc_ssize lc_encode_wait(int ticket, int* used);
  * on the device before w_ref is touched (LC_ERR_BAD_BLOB leaves w_ref unchanged); a
  * lane stream that does not decode to exactly its stated length is only found
  * during the sweep and then also returns LC_ERR_BAD_BLOB, with w_ref partly updated.
- * Reads never leave [blob, blob + header.total_bytes).  Waits for `stream`; returns
- * the bytes consumed or -(lc_status).
+ * Reads never leave [blob, blob + header.total_bytes) (lc_decode_sized also holds that size
+ * against the caller's buffer).  A caller that must survive a damaged payload keeps a copy of
+ * w_ref, or restores into a copy.  Waits for `stream`; returns the bytes consumed or -(lc_status).
  */
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
 
@@ -290,17 +302,6 @@ void lc_shutdown(void);
 
 /* Static string for an lc_status (positive or negated). */
 const char* lc_strerror(int status);
-
-/*
- * Per-kernel timing with HIP events on the caller's stream (for benchmarks).
- * lc_profile(1) switches it on and clears the totals, lc_profile(0) switches it off.
- * lc_profile_read copies up to `cap` accumulated kernel times (milliseconds) and
- * launch counts; returns the number of kernel slots.  lc_profile_name(i) names slot i
- * (NULL past the end).
- */
-int lc_profile(int enable);
-int lc_profile_read(double* ms_total, uint64_t* launches, int cap);
-const char* lc_profile_name(int slot);
 
 #ifdef __cplusplus
 }

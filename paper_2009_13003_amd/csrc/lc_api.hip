@@ -2,6 +2,7 @@
 // launch order, the small size/status read-back, optional per-kernel event timing.
 // No step of the method runs here.
 #include "../../include/lc.h"
+#include "../../include/lc_bench.h"
 #include "lc_internal.h"
 
 #include <mutex>
@@ -323,8 +324,13 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
     return lc_encode_cached_t(w, w_ref, n, nbits, out, LC_F32, cache, used, stream);
 }
 
-lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream) {
+}  // extern "C"
+
+namespace {
+// blob_bytes: what the caller says its buffer holds (SIZE_MAX: not stated); the header's total may not pass it
+lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream) {
     if (!blob || misaligned(blob, 16) || n > LC_MAX_N) return -LC_ERR_BADARG;
+    if (blob_bytes < kHeaderBytes) return -LC_ERR_BAD_BLOB;
     if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
     if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -337,7 +343,8 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
     if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = b;
-    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, lc_encode_bound(n, 4), ws, epoch, g_pinned_dev, s); }
+    const uint64_t bound = lc_encode_bound(n, 4), max_total = blob_bytes < bound ? blob_bytes : bound;
+    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, max_total, ws, epoch, g_pinned_dev, s); }
     { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, dtype, ws, epoch, g_pinned_dev, ds->tune, s); }
     LC_HIP(hipGetLastError());
     LC_HIP(hipStreamSynchronize(s));
@@ -346,6 +353,25 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
     collect(slots, 2);
     if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
     return (lc_ssize)g_pinned->bytes[0];
+}
+}  // namespace
+
+extern "C" {
+
+lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void* stream) {
+    return decode_impl(blob, SIZE_MAX, w_ref, n, dtype, stream);
+}
+
+lc_ssize lc_decode_sized(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream) {
+    return decode_impl(blob, blob_bytes, w_ref, n, dtype, stream);
+}
+
+lc_ssize lc_encode_sized(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, size_t out_bytes, int dtype,
+                         void* stream) {
+    const size_t bound = lc_encode_bound(n, nbits);
+    if (bound == 0) return -LC_ERR_BADARG;
+    if (out_bytes < bound) return -LC_ERR_OUT_TOO_SMALL;
+    return encode_impl(w, w_ref, n, nbits, out, dtype, nullptr, nullptr, stream, false);
 }
 
 lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream) {

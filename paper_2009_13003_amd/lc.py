@@ -29,6 +29,10 @@ _lib.lc_set_workspace.restype = _int
 _lib.lc_set_workspace.argtypes = [_vp, _sz]
 _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
+_lib.lc_encode_sized.restype = _i64
+_lib.lc_encode_sized.argtypes = [_vp, _vp, _u64, _int, _vp, _sz, _int, _vp]
+_lib.lc_decode_sized.restype = _i64
+_lib.lc_decode_sized.argtypes = [_vp, _sz, _vp, _u64, _int, _vp]
 _lib.lc_encode_t.restype = _i64
 _lib.lc_encode_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp]
 _lib.lc_decode_t.restype = _i64
@@ -166,6 +170,28 @@ def lc_decode_t(blob, w_ref, stream=None, n=None):
     return r
 
 
+def lc_encode_sized(w, w_ref, nbits, out, stream=None, n=None):
+    """lc_encode_t with the size of `out` stated: ERR_OUT_TOO_SMALL if it is below lc_encode_bound."""
+    n = w.numel() if n is None else n
+    assert w.dtype == w_ref.dtype and out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    r = int(_lib.lc_encode_sized(_dev_any(w), _dev_any(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), out.numel(),
+                                 DTYPES[w.dtype], _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
+def lc_decode_sized(blob, w_ref, stream=None, n=None):
+    """lc_decode_t with the size of `blob` stated: a header that claims more bytes is refused."""
+    n = w_ref.numel() if n is None else n
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    r = int(_lib.lc_decode_sized(ctypes.c_void_p(blob.data_ptr()), blob.numel(), _dev_any(w_ref), n, DTYPES[w_ref.dtype],
+                                 _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
+
+
 class EncodeBatch:
     """The marshalled arguments of one lc_encode_batch call, kept for the next call on the same tensors: a
     training loop checkpoints the same parameter tensors every time, and checking and converting a few hundred
@@ -205,9 +231,7 @@ def lc_encode_batch(ws, w_refs, nbits, outs, stream=None):
     return EncodeBatch(ws, w_refs, nbits, outs).run(stream)
 
 
-def lc_encode_batch_t(ws, w_refs, nbits, outs, stream=None):
-    """lc_encode_batch for float32, bfloat16 or float16 tensors (all of one dtype)."""
-    return EncodeBatch(ws, w_refs, nbits, outs).run(stream)
+lc_encode_batch_t = lc_encode_batch      # (EncodeBatch picks the entry point by the tensors' dtype)
 
 
 def lc_blob_sizes(header_bytes):
@@ -253,9 +277,7 @@ def lc_decode_batch(blobs, w_refs, stream=None):
     return DecodeBatch(blobs, w_refs).run(stream)
 
 
-def lc_decode_batch_t(blobs, w_refs, stream=None):
-    """lc_decode_batch for float32, bfloat16 or float16 tensors (all of one dtype)."""
-    return DecodeBatch(blobs, w_refs).run(stream)
+lc_decode_batch_t = lc_decode_batch      # (DecodeBatch picks the entry point by the tensors' dtype)
 
 
 CACHE_BYTES = 256

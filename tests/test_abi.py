@@ -7,7 +7,7 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "lc.h")
+HEADERS = sorted(os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
 LIB = os.path.join(ROOT, "paper_2009_13003_amd", "liblc.so")
 
 
@@ -20,15 +20,18 @@ def lib():
 
 
 def declared_functions():
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
-    return sorted(set(re.findall(r"\b(lc_[a-z_0-9]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(lc_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"lc_encode", "lc_blob_sizes", "lc_encode_batch", "lc_decode_batch", "lc_batch_workspace_bytes", "lc_encode_t", "lc_decode_t", "lc_encode_cached", "lc_encode_async", "lc_encode_release_inputs", "lc_encode_wait", "lc_decode", "lc_decode_many", "lc_encode_bound", "lc_workspace_bytes", "lc_set_workspace",
             "lc_blob_info", "lc_shutdown", "lc_strerror", "lc_profile", "lc_profile_read",
-            "lc_profile_name"} <= set(names)
+            "lc_profile_name", "lc_encode_sized", "lc_decode_sized"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 

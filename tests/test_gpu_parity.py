@@ -227,6 +227,45 @@ def test_decode_rejects_damaged_blobs(lc):
     assert lc.lc_decode(good, rec) == size
 
 
+def test_calls_with_stated_buffer_sizes(lc):
+    """lc_encode_sized refuses an `out` below lc_encode_bound without touching it; lc_decode_sized restores from a
+    buffer of exactly the blob's size and refuses, with w_ref untouched, a blob whose header claims more bytes than
+    the caller's buffer holds (truncated buffer; forged size field with a matching last offset)."""
+    n, nbits = 3 * 16384 + 500, 3
+    w, w_ref = laplace_case(n, seed=77)
+    bound = lc.lc_encode_bound(n, nbits)
+    small = torch.full((bound - 1,), 0x77, dtype=torch.uint8, device=DEV)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode_sized(w, w_ref, nbits, small)
+    assert e.value.status == lc.ERR_OUT_TOO_SMALL and bool((small == 0x77).all())
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode_sized(w, w_ref, nbits, out)
+    blob_cpu = orc.encode(w.cpu().numpy(), w_ref.cpu().numpy(), nbits)
+    assert size == blob_cpu.size and np.array_equal(out[:size].cpu().numpy(), blob_cpu)
+    exact = out[:size].clone()
+    rec = w_ref.clone()
+    assert lc.lc_decode_sized(exact, rec) == size
+    ref_h = w_ref.cpu().numpy(); orc.decode(blob_cpu, ref_h)
+    assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h))
+    for cut in (4, size - 600, size - 100):                     # the buffer ends inside the payload / the header
+        rec = w_ref.clone()
+        with pytest.raises(lc.LcError) as e:
+            lc.lc_decode_sized(exact[:size - cut], rec)
+        assert e.value.status == lc.ERR_BAD_BLOB and torch.equal(rec, w_ref)
+    # a forged blob that claims 64 more bytes (size field and last offset agree): lc_decode's own checks pass the
+    # header, the stated buffer size does not
+    nchunks = (n + 16383) // 16384
+    forged = exact.clone()
+    forged[40:48] = torch.tensor(np.frombuffer(np.uint64(size + 64).tobytes(), np.uint8).copy(), device=DEV)
+    last = 512 + 4 * nchunks
+    words = int(exact[last:last + 4].cpu().numpy().view(np.uint32)[0]) + 16
+    forged[last:last + 4] = torch.tensor(np.frombuffer(np.uint32(words).tobytes(), np.uint8).copy(), device=DEV)
+    rec = w_ref.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_sized(forged, rec)
+    assert e.value.status == lc.ERR_BAD_BLOB and torch.equal(rec, w_ref)
+
+
 def test_caller_workspace(lc):
     n = 4 * 16384
     w, w_ref = laplace_case(n, seed=12)
