@@ -146,6 +146,22 @@ lc_ssize lc_encode_sized(const void* w, const void* w_ref, uint64_t n, int nbits
 lc_ssize lc_decode_sized(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream);
 
 /*
+ * lc_encode for callers that cannot allocate device or pinned memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same kernels as lc_encode, with their scratch (bucket counts, code
+ * table, per-chunk notes, the slots that hold the code words before they are placed) in an array that is part of
+ * the library's device image, LC_STATIC_MAX_N elements' worth: about 19 MB, which every GPU the library runs on
+ * holds until the process ends.  The call allocates and frees nothing and does not wait: it enqueues on `stream`
+ * and returns an lc_status (LC_OK, LC_ERR_BADARG as for lc_encode, LC_ERR_WORKSPACE if n > LC_STATIC_MAX_N,
+ * LC_ERR_HIP).  Once the stream has reached the end of the call, `out` holds exactly what lc_encode would have
+ * written: the blob, whose header carries its size (u64 at byte 40) and status (u32 at byte 48; 2 = non-finite
+ * delta, header only).  w, w_ref: fp32, as for lc_encode.  All calls on one GPU share that GPU's array: calls that
+ * overlap there (different streams, or replays of captured graphs in flight together) race; calls on one stream,
+ * and calls of the other entry points, which have their own scratch, do not.
+ */
+#define LC_STATIC_MAX_N (1ull << 23)
+int lc_encode_static(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream);
+
+/*
  * Parameters stored as bf16 or fp16.  The method works on the fp32 delta (Algorithm 1 line 4), so the
  * 16-bit values are widened exactly to fp32, delta, buckets, representatives and codes are those of
  * lc_encode on the widened vectors, and the restore computes fl32(float(w_ref[i]) + representative) and

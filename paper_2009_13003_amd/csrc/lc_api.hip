@@ -274,6 +274,56 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits, vo
     return encode_impl(w, w_ref, n, nbits, out, LC_F32, nullptr, nullptr, stream, false);
 }
 
+}  // extern "C"
+
+// ---- lc_encode_static: the scratch area lives in the library's own device image
+namespace {
+constexpr uint64_t kStaticChunks = LC_STATIC_MAX_N / kChunk;
+static_assert(LC_STATIC_MAX_N % kChunk == 0, "whole chunks");
+// the scratch of the largest call it accepts (nbits 4), then the call's outcome as the kernels report it
+constexpr size_t kStaticResultAt = up256(encode_scratch_bytes(kStaticChunks, 4));
+constexpr size_t kStaticBytes = kStaticResultAt + 256;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+namespace {
+void* g_static[kMaxDevices];      // each device's copy of `scratch`, as hipGetSymbolAddress reports it there
+}  // namespace
+
+extern "C" {
+
+int lc_encode_static(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* stream) {
+    if (nbits < 1 || nbits > 4 || !out || misaligned(out, 16)) return LC_ERR_BADARG;
+    if (n > LC_STATIC_MAX_N) return LC_ERR_WORKSPACE;                 // more than the built-in scratch area holds
+    if (n && (!w || !w_ref || misaligned(w, 4) || misaligned(w_ref, 4))) return LC_ERR_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    if (!g_static[dev]) {
+        // `scratch` itself is no device address on the host side; every device holds its own copy at its own address
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return LC_ERR_HIP; }
+        g_static[dev] = ptr;
+    }
+    DeviceState& ds = g_dev[dev];
+    read_tuning(ds, dev);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t* base = static_cast<uint8_t*>(g_static[dev]);
+    const Scratch sc(base, num_chunks_of(n), nbits);
+    Result* result = reinterpret_cast<Result*>(base + kStaticResultAt);
+    uint8_t* o = static_cast<uint8_t*>(out);
+    // The area keeps what the last call on this device left (a call that ran to its end leaves the state cleared,
+    // one that was captured and never replayed to its end does not): cleared by a kernel before every call.
+    launch_reset_chunks(sc.ws, sc.group_words, sc.chunk_maxexp, (uint32_t)kStaticChunks, s);
+    launch_hist(w, w_ref, n, LC_F32, sc.ws, sc.chunk_maxexp, sc.batch_max, ds.tune, s);
+    launch_table(sc.ws, n, nbits, LC_F32, sc.group_words, sc.chunk_maxexp, sc.chunk_list, s);
+    launch_pack(w, w_ref, n, LC_F32, sc.ws, sc.chunk_bits, sc.group_words, sc.chunk_maxexp, sc.chunk_list, sc.batch_max, sc.prov,
+                sc.slot_words, ds.tune, s);
+    launch_place(o, sc.ws, sc.chunk_bits, sc.group_words, sc.prov, sc.slot_words, n, sc.chunk_maxexp, s);
+    launch_finalize(o, sc.ws, result, sc.group_words, nullptr, n, nbits, LC_F32, s);
+    if (hipGetLastError() != hipSuccess) return LC_ERR_HIP;
+    return LC_OK;
+}
+
 lc_ssize lc_encode_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* stream) {
     return encode_impl(w, w_ref, n, nbits, out, dtype, nullptr, nullptr, stream, false);
 }

@@ -37,6 +37,13 @@ __global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups, u32* chunk
     for (u32 i = threadIdx.x; i < nchunks; i += blockDim.x) chunk_maxexp[i] = 0;
 }
 
+// The same for a scratch area that only ever serves calls of at most `nchunks` chunks (their entries of the
+// transposed maxima, their groups of 64 chunks): what such an area needs cleared before every call of its own.
+__global__ void k_reset_chunks(EncState* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
+    clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
+    for (u32 c = threadIdx.x; c < nchunks; c += blockDim.x) chunk_maxexp[maxexp_slot(c)] = 0;
+}
+
 // ----------------------------------------------------------------------------- k_hist
 // Sweep 1 (Section 3.1.1, exponent-based quantization): population of each of the 2^9
 // (sign, exponent) buckets.  LDS histogram replicated 8 times (copy = lane & 7, copies
@@ -1417,6 +1424,10 @@ __global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
 // ----------------------------------------------------------------------------- launchers
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s) {
     hipLaunchKernelGGL(k_reset, dim3(1), dim3(1024), 0, s, ws, group_words, (u32)kMaxGroups, chunk_maxexp, (u32)kMaxChunks);
+}
+
+void launch_reset_chunks(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, uint32_t nchunks, hipStream_t s) {
+    hipLaunchKernelGGL(k_reset_chunks, dim3(1), dim3(1024), 0, s, ws, group_words, (nchunks + 63) / 64, chunk_maxexp, nchunks);
 }
 
 template <int DT>

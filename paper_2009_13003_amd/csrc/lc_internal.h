@@ -143,6 +143,7 @@ struct Tuning {
 
 // Launchers (lc_encode.hip, lc_decode.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s);
+void launch_reset_chunks(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, uint32_t nchunks, hipStream_t s);
 void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, uint8_t* batch_max,
                  const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,

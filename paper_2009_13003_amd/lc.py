@@ -33,6 +33,8 @@ _lib.lc_encode_sized.restype = _i64
 _lib.lc_encode_sized.argtypes = [_vp, _vp, _u64, _int, _vp, _sz, _int, _vp]
 _lib.lc_decode_sized.restype = _i64
 _lib.lc_decode_sized.argtypes = [_vp, _sz, _vp, _u64, _int, _vp]
+_lib.lc_encode_static.restype = _int
+_lib.lc_encode_static.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
 _lib.lc_encode_t.restype = _i64
 _lib.lc_encode_t.argtypes = [_vp, _vp, _u64, _int, _vp, _int, _vp]
 _lib.lc_decode_t.restype = _i64
@@ -138,6 +140,20 @@ def lc_encode(w, w_ref, nbits, out, stream=None, n=None):
     if r < 0:
         raise LcError(-r)
     return r
+
+
+STATIC_MAX_N = 1 << 23
+
+
+def lc_encode_static(w, w_ref, nbits, out, stream=None, n=None):
+    """lc_encode without any allocation and without waiting: enqueues only; the blob's size and status are in its
+    header once the stream has run the call.  Raises LcError on a status other than LC_OK."""
+    n = w.numel() if n is None else n
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous()
+    assert out.numel() >= lc_encode_bound(n, nbits) > 0 or not (1 <= nbits <= 4), "out is smaller than lc_encode_bound"
+    st = int(_lib.lc_encode_static(_dev_f32(w), _dev_f32(w_ref), n, nbits, ctypes.c_void_p(out.data_ptr()), _stream(stream)))
+    if st != OK:
+        raise LcError(st)
 
 
 DTYPES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2, torch.float64: 3}
