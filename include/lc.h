@@ -135,6 +135,24 @@ lc_ssize lc_encode(const float* w, const float* w_ref, uint64_t n, int nbits,
                    void* out, void* stream);
 
 /*
+ * How lc_encode (fp32, 16-byte aligned w and w_ref, no cache) feeds its second sweep.  With staged keys the first
+ * sweep also writes the 9 bits of every element's bucket id (sign, exponent: Section 3.1.1) to scratch and gathers
+ * the buckets' extremes, and the second sweep codes from those keys instead of reading w and w_ref again: 10.25 + c/8
+ * bytes per element moved instead of 16 + c/8, but the keys of chunks that hold the merged bucket only are written for
+ * nothing, so on sparse updates (where the plain second sweep passes over most chunks) it loses.
+ *   LC_STAGING_AUTO    (default) stage keys for a vector of at least 2^26 elements (told by address and length) iff
+ *                      its last encode on this device had to read more than 30 % of its chunks in the second sweep;
+ *                      a vector's first encode: plain
+ *   LC_STAGING_ALWAYS  whenever it applies;  LC_STAGING_NEVER  never
+ * The blob is byte for byte the same either way.  Staging needs 1.125 bytes of scratch per element on top of
+ * lc_workspace_bytes (a caller-supplied workspace without that room keeps the plain path).  Process-wide; the
+ * environment variable LC_TUNE_KEY_STAGING=0|1|2 sets the initial value.  Returns LC_OK or LC_ERR_BADARG.
+ */
+enum lc_option { LC_OPT_KEY_STAGING = 1 };
+enum { LC_STAGING_AUTO = 0, LC_STAGING_ALWAYS = 1, LC_STAGING_NEVER = 2 };
+int lc_set_option(int option, int value);
+
+/*
  * The two calls with the sizes of the caller's buffers stated (any dtype of lc_encode_t / lc_decode_t):
  * lc_encode_sized returns -LC_ERR_OUT_TOO_SMALL without touching anything if out_bytes < lc_encode_bound(n, nbits),
  * and is lc_encode_t otherwise; lc_decode_sized is lc_decode_t that also refuses, before any read past the header

@@ -15,6 +15,7 @@ using namespace lc;
 
 constexpr int kMaxDevices = 16;
 
+constexpr int kHintBits = 10, kHints = 1 << kHintBits;
 struct DeviceState {
     void* owned = nullptr;       // library-owned scratch
     size_t owned_bytes = 0;
@@ -25,12 +26,17 @@ struct DeviceState {
     const void* clean = nullptr;  // scratch area whose encode state is known to be cleared
     hipEvent_t last = nullptr;    // end of the latest asynchronous call on this device
     bool pending = false;         // ... which later calls must order themselves after (they share the scratch)
+    // What the last encode of a vector (told apart by address and length) found: the share of its chunks that sweep 2
+    // had to read.  Decides whether the next encode of that vector stages keys (see stage_keys()).
+    struct Hint { const void* w = nullptr; uint64_t n = 0; float listed = 0; };
+    Hint hint[kHints];
 };
 
 // lc_encode_async: a call in flight.
 constexpr int kMaxTickets = 16;
 struct Ticket {
     bool busy = false;
+    int dev = 0; const void* w = nullptr; uint64_t n = 0;   // whose hint its outcome updates
     hipEvent_t inputs = nullptr;  // after the last kernel that reads w / w_ref
     hipEvent_t done = nullptr;    // after the last kernel
 };
@@ -54,13 +60,14 @@ HostResult* g_pinned = nullptr;  // mapped pinned host memory the kernels write 
 HostResult* g_pinned_dev = nullptr;   // the same memory as the device sees it
 uint64_t g_epoch = 0;            // tags the decode status word of each call
 
+int g_key_staging = -1;          // LC_OPT_KEY_STAGING (-1: not yet read from the environment)
 bool g_prof = false;
 double g_prof_ms[kNumSlots];
 uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
 const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize", "k_spec_table", "k_spec_sweep",
-                                           "k_dec_check", "k_decode", "k_decode_fused"};
+                                           "k_dec_check", "k_decode", "k_decode_fused", "k_hist_keys", "k_pack_keys"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
     const char* v = getenv(name);
@@ -97,6 +104,8 @@ void read_tuning(DeviceState& ds, int dev) {
     ds.tune.hist_threads = env_int("LC_TUNE_HIST_THREADS", ds.tune.hist_threads, 64, 1024) / 64 * 64;
     ds.tune.pack_waves_per_cu = env_int("LC_TUNE_PACK_WAVES_PER_CU", ds.tune.pack_waves_per_cu, 1, 64);
     ds.tune.spec_waves_per_cu = env_int("LC_TUNE_SPEC_WAVES_PER_CU", ds.tune.spec_waves_per_cu, 1, 64);
+    ds.tune.keys_waves_per_cu = env_int("LC_TUNE_KEYS_WAVES_PER_CU", ds.tune.keys_waves_per_cu, 1, 64);
+    if (g_key_staging < 0) g_key_staging = env_int("LC_TUNE_KEY_STAGING", 0, 0, 2);
     ds.tune.batch_waves_per_cu = env_int("LC_TUNE_BATCH_WAVES_PER_CU", ds.tune.batch_waves_per_cu, 1, 64);
     ds.tune.decode_blocks_per_cu = env_int("LC_TUNE_DECODE_BLOCKS_PER_CU", ds.tune.decode_blocks_per_cu, 1, 64);
     ds.tune.fused_waves_per_cu = env_int("LC_TUNE_FUSED_WAVES_PER_CU", ds.tune.fused_waves_per_cu, 1, 32);
@@ -144,6 +153,10 @@ constexpr size_t encode_scratch_bytes(uint64_t nc, int nbits) {
     return kWorkspaceHead + up256(4 * nc) + (size_t)(nc * (kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u)) * 4) +
            256 + up256(16 * nc);                                  // + the per-batch maxima of sweep 1
 }
+// ... and with staged keys behind that: a byte and a bit per element of every whole batch
+size_t staged_scratch_bytes(uint64_t n, int nbits) {
+    return encode_scratch_bytes(num_chunks_of(n), nbits) + up256(key_exp_bytes(n)) + up256(key_sign_bytes(n));
+}
 struct Scratch {
     Workspace* ws;
     uint32_t *group_words, *chunk_maxexp, *chunk_list, *chunk_bits, *prov;
@@ -158,6 +171,11 @@ struct Scratch {
         prov = chunk_bits + (nc + 63) / 64 * 64;
         slot_words = slot_words_of(nbits);
         batch_max = reinterpret_cast<uint8_t*>((reinterpret_cast<uintptr_t>(prov + nc * slot_words) + 255) & ~(uintptr_t)255);
+    }
+    KeyPlanes keys(uint64_t n) const {                            // (only an area of staged_scratch_bytes has them)
+        const uint64_t nc = num_chunks_of(n);
+        uint8_t* e = batch_max + up256(16 * nc);
+        return KeyPlanes{e, reinterpret_cast<uint16_t*>(e + up256(key_exp_bytes(n)))};
     }
 };
 
@@ -199,6 +217,33 @@ int lc_set_workspace(void* dev_ws, size_t bytes) {
 }  // extern "C"
 
 namespace {
+// Whether this encode stages keys: sweep 1 then also writes 9 bits per element and sweep 2 reads those instead of w
+// and w_ref again (10.25 + c/8 bytes per element moved instead of 16 + c/8).  That pays when sweep 2 has to read most
+// of the vector; when it passes over most chunks (sparse updates) the plain second sweep is cheaper, since the keys
+// of chunks nobody reads are written for nothing.  How much sweep 2 reads is known only after sweep 1, so the choice
+// follows what the last encode of the same vector found (a training loop checkpoints the same tensors again and
+// again); a vector seen for the first time takes the plain path.  The blob is the same either way.
+DeviceState::Hint* hint_of(DeviceState* ds, const void* w, uint64_t n) {
+    const uint64_t key = ((uint64_t)reinterpret_cast<uintptr_t>(w) + n) * 0x9E3779B97F4A7C15ull;   // (slices lie 2^30 bytes apart)
+    return &ds->hint[key >> (64 - kHintBits)];
+}
+// Measured on 2^28-element calls: staging costs sweep 1 0.06 to 0.11 ms (the key writes) and saves sweep 2 0.27 ms
+// times the share of chunks it has to read; below some 2^26 elements the sweeps are too short for either to show.
+constexpr float kStageAbove = 0.30f;
+constexpr uint64_t kStageFromN = 1ull << 26;
+bool stage_keys(DeviceState* ds, const void* w, const void* w_ref, uint64_t n, int dtype, bool cached) {
+    if (dtype != LC_F32 || cached || n < kChunk || misaligned(w, 16) || misaligned(w_ref, 16)) return false;
+    if (g_key_staging == 1) return true;
+    if (g_key_staging == 2 || n < kStageFromN) return false;
+    const DeviceState::Hint* h = hint_of(ds, w, n);
+    return h->w == w && h->n == n && h->listed > kStageAbove;
+}
+void note_outcome(DeviceState* ds, const void* w, uint64_t n, const Result& r) {
+    if (r.status != LC_OK || n < kChunk) return;
+    DeviceState::Hint* h = hint_of(ds, w, n);
+    h->w = w; h->n = n; h->listed = (float)r.listed / (float)num_chunks_of(n);
+}
+
 // lc_encode (cache == nullptr: two sweeps) and lc_encode_cached (one sweep that counts and, when the
 // cache holds a usable table, codes with it; k_table confirms or voids that, and only then does the
 // second sweep have anything to do).
@@ -213,8 +258,15 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     int err = 0; DeviceState* ds = nullptr;
     Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
     if (!ws) return -(lc_ssize)err;
+    bool staged = stage_keys(ds, w, w_ref, n, dtype, cache != nullptr);
+    if (staged) {
+        // the key planes lie behind the usual scratch; a caller's area that has no room for them keeps the plain path
+        Workspace* bigger = get_workspace(staged_scratch_bytes(n, nbits), &err, &ds);
+        if (bigger) ws = bigger; else staged = false;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Scratch sc(ws, num_chunks_of(n), nbits);
+    const KeyPlanes keys = staged ? sc.keys(n) : KeyPlanes{nullptr, nullptr};
     uint32_t *group_words = sc.group_words, *chunk_maxexp = sc.chunk_maxexp, *chunk_list = sc.chunk_list, *chunk_bits = sc.chunk_bits,
              *prov = sc.prov;
     const uint32_t slot_words = sc.slot_words;
@@ -241,27 +293,32 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
         { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
         { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
     } else {
-        Timed t(kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, batch_max, ds->tune, s);
+        Timed t(staged ? kSlotHistKeys : kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, batch_max, keys, ds->tune, s);
     }
     { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, dtype, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
-    { Timed t(kSlotPack, s);     launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, batch_max, prov, slot_words, ds->tune, s); }
+    if (staged) { Timed t(kSlotPackKeys, s); launch_pack_keys(w, w_ref, n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, keys, prov, slot_words, ds->tune, s); }
+    else { Timed t(kSlotPack, s); launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, batch_max, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, s); }
+    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, staged, s); }
     LC_HIP(hipGetLastError());
     if (async) {
         LC_HIP(hipEventRecord(g_ticket[ticket].done, s));
         LC_HIP(hipEventRecord(ds->last, s));
         ds->pending = true;
         ds->clean = ws;              // later calls are ordered after this one
-        g_ticket[ticket].busy = true;
+        Ticket& tk = g_ticket[ticket];
+        tk.busy = true;
+        tk.dev = (int)(ds - g_dev); tk.w = cache ? nullptr : w; tk.n = n;
         return ticket;
     }
     LC_HIP(hipStreamSynchronize(s));
     ds->pending = false;             // this call was ordered after every asynchronous one
     ds->clean = ws;
-    const int slots[] = {cache ? kSlotSpecTable : kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecSweep};
+    const int slots[] = {cache ? kSlotSpecTable : staged ? kSlotHistKeys : kSlotHist, kSlotTable, staged ? kSlotPackKeys : kSlotPack,
+                         kSlotPlace, kSlotFinalize, kSlotSpecSweep};
     collect(slots, cache ? 6 : 5);
+    if (!cache && dtype == LC_F32) note_outcome(ds, w, n, g_pinned->enc);
     if (used) *used = (int)g_pinned->enc.used_cache;
     if (g_pinned->enc.status != LC_OK) return -(lc_ssize)g_pinned->enc.status;
     return (lc_ssize)g_pinned->enc.bytes;
@@ -314,12 +371,12 @@ int lc_encode_static(const float* w, const float* w_ref, uint64_t n, int nbits, 
     // The area keeps what the last call on this device left (a call that ran to its end leaves the state cleared,
     // one that was captured and never replayed to its end does not): cleared by a kernel before every call.
     launch_reset_chunks(sc.ws, sc.group_words, sc.chunk_maxexp, (uint32_t)kStaticChunks, s);
-    launch_hist(w, w_ref, n, LC_F32, sc.ws, sc.chunk_maxexp, sc.batch_max, ds.tune, s);
+    launch_hist(w, w_ref, n, LC_F32, sc.ws, sc.chunk_maxexp, sc.batch_max, KeyPlanes{nullptr, nullptr}, ds.tune, s);
     launch_table(sc.ws, n, nbits, LC_F32, sc.group_words, sc.chunk_maxexp, sc.chunk_list, s);
     launch_pack(w, w_ref, n, LC_F32, sc.ws, sc.chunk_bits, sc.group_words, sc.chunk_maxexp, sc.chunk_list, sc.batch_max, sc.prov,
                 sc.slot_words, ds.tune, s);
     launch_place(o, sc.ws, sc.chunk_bits, sc.group_words, sc.prov, sc.slot_words, n, sc.chunk_maxexp, s);
-    launch_finalize(o, sc.ws, result, sc.group_words, nullptr, n, nbits, LC_F32, s);
+    launch_finalize(o, sc.ws, result, sc.group_words, nullptr, n, nbits, LC_F32, false, s);
     if (hipGetLastError() != hipSuccess) return LC_ERR_HIP;
     return LC_OK;
 }
@@ -357,6 +414,7 @@ lc_ssize lc_encode_wait(int ticket, int* used) {
     g_ticket[ticket].busy = false;
     if (e != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
     const Result r = g_pinned->enc_async[ticket];
+    if (g_ticket[ticket].w) note_outcome(&g_dev[g_ticket[ticket].dev], g_ticket[ticket].w, g_ticket[ticket].n, r);
     if (used) *used = (int)r.used_cache;
     if (r.status != LC_OK) return -(lc_ssize)r.status;
     return (lc_ssize)r.bytes;
@@ -675,6 +733,12 @@ int lc_blob_sizes(const void* host_header, uint64_t bits[3]) {
     bits[1] = n * x + b * (1u << x);            // x bits per element + 2^x representatives
     bits[2] = 8 * total;                        // the blob as stored
     return LC_OK;
+}
+
+int lc_set_option(int option, int value) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (option == LC_OPT_KEY_STAGING && value >= LC_STAGING_AUTO && value <= LC_STAGING_NEVER) { g_key_staging = value; return LC_OK; }
+    return LC_ERR_BADARG;
 }
 
 void lc_shutdown(void) {

@@ -31,9 +31,14 @@ __device__ __forceinline__ void clear_ext64(Ext64* ext, u32 tid, u32 nthr) {
     if (tid < kMaxSym) { ext->mmin[tid] = 0xFFFFFFFFFFFFFull; ext->mmax[tid] = 0; }
 }
 
+__device__ __forceinline__ void clear_bucket_extremes(Workspace* ws, u32 tid, u32 nthr) {
+    for (u32 i = tid; i < 512; i += nthr) { ws->bucket_min[i] = 0xFFFFFFFFu; ws->bucket_max[i] = 0; }
+}
+
 __global__ void k_reset(Workspace* ws, u32* group_words, u32 ngroups, u32* chunk_maxexp, u32 nchunks) {
     clear_encode_state(ws, group_words, ngroups, threadIdx.x, blockDim.x);
     clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
+    clear_bucket_extremes(ws, threadIdx.x, blockDim.x);
     for (u32 i = threadIdx.x; i < nchunks; i += blockDim.x) chunk_maxexp[i] = 0;
 }
 
@@ -91,13 +96,20 @@ __device__ __forceinline__ float max_magnitude(const u32 (&u)[EPU], float m) {
 // one chunk of the coding sweep and its largest exponent goes to chunk_maxexp with one atomic per batch.
 // batch_max (or null) receives every whole batch's largest exponent as a byte of its own: the coding sweep then
 // knows which parts of a chunk it has to read.
-template <bool ALIGNED, int DT>
+// KEYS (binary32, aligned arrays): the sweep also stages a 9-bit key per element of every whole batch -- the 16
+// exponent bytes and the 16 sign bits of the 16 elements a lane holds of a batch, which are the lane's own elements of
+// 4 rows of the coding sweep's chunk -- and, being then the only sweep that sees the mantissas, tracks the smallest and
+// largest delta bit pattern of every bucket (Section 3.1.1: the representative is the mean of these two).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+template <bool ALIGNED, int DT, bool KEYS = false>
 __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const void* __restrict__ w_ref,
-                                               u64 n, EncState* ws, u32* chunk_maxexp, uint8_t* batch_max) {
+                                               u64 n, Workspace* ws, u32* chunk_maxexp, uint8_t* batch_max, KeyPlanes keys) {
     __shared__ u32 h[512 * kHistCopies];
+    __shared__ u32 mn[KEYS ? 512 * kHistCopies : 1], mx[KEYS ? 512 * kHistCopies : 1];
+    static_assert(!KEYS || (ALIGNED && DT == kF32), "keys are staged for aligned binary32 arrays only");
     constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
-    for (u32 i = tid; i < 512 * kHistCopies; i += nthr) h[i] = 0;
+    for (u32 i = tid; i < 512 * kHistCopies; i += nthr) { h[i] = 0; if (KEYS) { mn[i] = 0xFFFFFFFFu; mx[i] = 0; } }
     __syncthreads();
     const u32 copy = tid & (kHistCopies - 1);
     const u64 nu = n / EPU;
@@ -114,18 +126,38 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
 #pragma unroll
         for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * kW); bb[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * kW); }
     };
+    u32 key_word = 0, key_signs = 0;                 // KEYS: exponent bytes of the unit just counted; sign bits of the batch so far
+    auto count_one = [&](u32 u) {
+        const u32 at = (u >> 23) * kHistCopies + copy;
+        atomicAdd(&h[at], 1u);
+        if (KEYS) { atomicMin(&mn[at], u); atomicMax(&mx[at], u); }
+    };
     auto count_unit = [&](const float4& a, const float4& bb, float m) {
         float x[EPU], y[EPU];
         u32 u[EPU];
         unpack_unit<DT, EPU>(a, x); unpack_unit<DT, EPU>(bb, y);
+        key_word = 0;
 #pragma unroll
-        for (int v = 0; v < EPU; ++v) { u[v] = delta_bits(x[v], y[v]); atomicAdd(&h[(u[v] >> 23) * kHistCopies + copy], 1u); }
+        for (int v = 0; v < EPU; ++v) {
+            u[v] = delta_bits(x[v], y[v]);
+            count_one(u[v]);
+            if (KEYS) { key_word |= ((u[v] >> 23) & 255u) << (8 * v); key_signs = (key_signs >> 1) | ((u[v] >> 31) << 15); }
+        }
         return max_magnitude<EPU>(u, m);
     };
     auto count = [&](float4 (&a)[PF], float4 (&bb)[PF], u64 batch) {
         float mf = 0.f;
+        u32 kw[PF];
 #pragma unroll
-        for (int k = 0; k < PF; ++k) mf = count_unit(a[k], bb[k], mf);
+        for (int k = 0; k < PF; ++k) { mf = count_unit(a[k], bb[k], mf); kw[k] = key_word; }
+        if constexpr (KEYS) {
+            // (after 16 elements the sign bit of element 4 k + v has arrived at bit 4 k + v)
+            static_assert(PF == 4 && EPU == 4, "a batch is 4 rows of 4 elements per lane");
+            const u32x4 kv = {kw[0], kw[1], kw[2], kw[3]};
+            const u64 at = batch * kW + (tid & (kW - 1));
+            __builtin_nontemporal_store(kv, reinterpret_cast<u32x4*>(keys.exp) + at);
+            __builtin_nontemporal_store((uint16_t)key_signs, keys.sign + at);
+        }
         const u32 m = wave_max_u32(__float_as_uint(mf));     // whole wavefronts only: b < nbatch is the same for all lanes
         if ((tid & (kW - 1)) == 0) {
             atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m >> 23);
@@ -158,16 +190,22 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
         if (tid < (u32)(n - EPU * nu)) {
             const u64 i = EPU * nu + tid;
             const u32 u = delta_bits(load_one<DT>(w, i), load_one<DT>(w_ref, i));
-            atomicAdd(&h[(u >> 23) * kHistCopies + copy], 1u);
+            count_one(u);
             atomicMax(&chunk_maxexp[maxexp_slot((u32)(i / kChunk))], (u >> 23) & 255u);
         }
     }
     __syncthreads();
     for (u32 bk = tid; bk < 512; bk += nthr) {
-        u32 sum = 0;
+        u32 sum = 0, lo = 0xFFFFFFFFu, hi = 0;
 #pragma unroll
-        for (int k = 0; k < kHistCopies; ++k) sum += h[bk * kHistCopies + k];
-        if (sum) atomicAdd(&ws->hist[bk], (u64)sum);
+        for (int k = 0; k < kHistCopies; ++k) {
+            sum += h[bk * kHistCopies + k];
+            if (KEYS) { lo = min(lo, mn[bk * kHistCopies + k]); hi = max(hi, mx[bk * kHistCopies + k]); }
+        }
+        if (sum) {
+            atomicAdd(&ws->hist[bk], (u64)sum);
+            if (KEYS) { atomicMin(&ws->bucket_min[bk], lo); atomicMax(&ws->bucket_max[bk], hi); }
+        }
     }
 }
 
@@ -998,6 +1036,117 @@ __global__ __launch_bounds__(64) void k_pack(const void* __restrict__ w, const v
     pack_merge_extremes(L, ws, K, lane);
 }
 
+// ----------------------------------------------------------------------------- k_pack_keys
+// Sweep 2 of an encode with staged keys: the same chunks, slots and lane strings as k_pack, coded from the 9-bit keys
+// sweep 1 left (16 exponent bytes + 16 sign bits per lane and batch of 4 rows) instead of from w and w_ref: 1.125
+// bytes per element read instead of 8.  The extremes of the kept buckets are sweep 1's business then.  A full chunk
+// takes 16 key loads per lane, all in flight together, and the next chunk's are issued before this one is coded; the
+// vector's ragged last chunk (whose tail has no keys) is coded from w and w_ref like any ragged chunk.
+constexpr u32 kKeyBatches = kR / 4;             // batches of 4 rows per chunk
+constexpr u32 kHalfBatches = kKeyBatches / 2;
+
+// The keys of half a chunk as one lane holds them: 8 batches of 16 exponent bytes and 16 sign bits.
+struct HalfKeys { u32x4 exp[kHalfBatches]; u32 sign[kHalfBatches]; };
+
+__device__ __forceinline__ void fetch_half(const KeyPlanes& keys, u32 c, u32 half, HalfKeys& k) {
+    const u64 at = ((u64)c * kKeyBatches + half * kHalfBatches) * kW + lane_id();
+#pragma unroll
+    for (u32 b = 0; b < kHalfBatches; ++b) {
+        k.exp[b] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(keys.exp) + at + b * kW);
+        k.sign[b] = __builtin_nontemporal_load(keys.sign + at + b * kW);
+    }
+}
+
+// A lane's growing code string of one chunk.
+struct LaneString {
+    u64 acc; u32 nb, nw;                // bits waiting in acc (nb of them), words written
+    u32* lane_words;
+    __device__ __forceinline__ void start(const ChunkRef& ch) { acc = 0; nb = 0; nw = 0; lane_words = ch.slot + kLaneBitsWords + lane_id(); }
+    __device__ __forceinline__ void put(u32 word, PackLds<false>& L) {
+        if (nw < kStageRows) L.stage[nw * kW + lane_id()] = word;
+        else lane_words[nw * kW] = word;
+    }
+    __device__ __forceinline__ void flush(PackLds<false>& L) {
+        if (nb >= 32) { put((u32)(acc >> (nb - 32)), L); ++nw; nb -= 32; }
+    }
+};
+
+template <bool ROWCHK>
+__device__ __forceinline__ void code_half(const HalfKeys& k, LaneString& S, PackLds<false>& L) {
+#pragma unroll
+    for (u32 b = 0; b < kHalfBatches; ++b) {
+        const u32 wv[4] = {k.exp[b].x, k.exp[b].y, k.exp[b].z, k.exp[b].w};
+        u32 t[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)        // bucket id = sign << 8 | exponent, as the top 9 bits of the delta
+            t[i] = L.sym8[((wv[i >> 2] >> (8 * (i & 3))) & 255u) | (((k.sign[b] >> i) & 1u) << 8)];
+        uint2 p[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            p[i] = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint8_t*>(L.pair) + ((t[2 * i] << 4) | t[2 * i + 1]));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            S.acc = (S.acc << p[i].y) | p[i].x; S.nb += p[i].y;
+            if (!ROWCHK || (i & 1)) S.flush(L);
+        }
+    }
+}
+
+// the last, partly filled word, then the staged rows to the slot (as pack_chunk_fast), then the sizes
+__device__ __forceinline__ void finish_chunk_keys(const ChunkRef& cur, LaneString& S, PackLds<false>& L) {
+    const u32 lane = lane_id();
+    if (S.nb > 0) S.put((u32)(S.acc << (32 - S.nb)), L);
+    u32 rows = min(S.nw + (S.nb > 0 ? 1u : 0u), kStageRows);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) rows = max(rows, (u32)__shfl_xor(rows, d, 64));
+    const uint4* src = reinterpret_cast<const uint4*>(L.stage);
+    uint4* dst = reinterpret_cast<uint4*>(cur.slot + kLaneBitsWords);
+    for (u32 i = lane; i < rows * (kW / 4); i += kW) dst[i] = src[i];
+    finish_lane_sizes(cur, S.nb, S.nw);
+}
+
+// Half a chunk's keys are always on their way while the half before is coded, across chunk borders too.
+template <bool ROWCHK>
+__device__ __forceinline__ void pack_keys_loop(VectorChunks& src, const KeyPlanes& keys, PackLds<false>& L) {
+    HalfKeys A, B;
+    ChunkRef cur = src.take();
+    if (cur.valid && cur.fast) fetch_half(keys, cur.c, 0, A);
+    while (cur.valid) {
+        const ChunkRef next = src.take();
+        if (cur.fast) {
+            LaneString S;
+            S.start(cur);
+            fetch_half(keys, cur.c, 1, B);
+            code_half<ROWCHK>(A, S, L);
+            if (next.valid && next.fast) fetch_half(keys, next.c, 0, A);
+            code_half<ROWCHK>(B, S, L);
+            finish_chunk_keys(cur, S, L);
+        } else {
+            pack_chunk_plain<false, true, kF32>(cur, L);
+            if (next.valid && next.fast) fetch_half(keys, next.c, 0, A);
+        }
+        cur = next;
+    }
+}
+
+__global__ __launch_bounds__(64) void k_pack_keys(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
+                                                  EncState* ws, u32* chunk_bits, u32* group_words, const u32* chunk_maxexp,
+                                                  const u32* chunk_list, KeyPlanes keys, u32* prov, u32 slot_words, u32 nchunks) {
+    __shared__ PackLds<false> L;
+    const u32 lane = threadIdx.x;
+    const Table& T = ws->table;
+    if (T.status != 0) return;
+    pack_setup(L, T, lane);
+    const u32 K = T.K;
+    __syncthreads();
+    // (aligned arrays by construction; no part-by-part coding: a listed chunk's keys are 18 KB, read whole)
+    VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, true, K << 3, T.max_len <= 8,
+                        chunk_list, ws->list_count, 0, nullptr, 16u, T.min_kept_exp, T.codelen[K]};
+    note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
+    if (src.row) pack_keys_loop<true>(src, keys, L);
+    else pack_keys_loop<false>(src, keys, L);
+}
+
 // ----------------------------------------------------------------------------- k_pack64
 // Sweep 2 for binary64 parameters: the same chunks, slots and lane strings; the symbol of an element comes from the
 // top 12 bits of its binary64 delta, the extremes are 64-bit patterns.  One symbol per look-up, rows fetched four
@@ -1126,7 +1275,8 @@ constexpr u32 kPlaceWords = 1024, kPlaceWordsFew = 2048;
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
 __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
-                                              u64 n, int nbits, u32 nchunks, u32 dtype, const Ext64* ext = nullptr) {
+                                              u64 n, int nbits, u32 nchunks, u32 dtype, const Ext64* ext = nullptr,
+                                              const u32* bucket_min = nullptr, const u32* bucket_max = nullptr) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
@@ -1148,6 +1298,7 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
         hdr[15] = dtype;
         if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
         host_result->bytes = total; host_result->status = status; host_result->used_cache = ws->spec_ok;
+        host_result->listed = ws->list_count; host_result->pad_r = 0;
         if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = T.K; cache->pad = 0; }
     }
     if (cache && ok && t < kMaxSym) {              // what this blob was coded with, for the next call
@@ -1161,7 +1312,8 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
         u32 bucket = 0xFFFFu, rep = 0;
         if (t < T.K && dtype != kF64) {
             bucket = T.kept[t];
-            const u32 sum = ws->mmin[t] + ws->mmax[t];
+            // (an encode with staged keys: the extremes of every bucket were gathered by sweep 1)
+            const u32 sum = bucket_min ? (bucket_min[bucket] & 0x7FFFFFu) + (bucket_max[bucket] & 0x7FFFFFu) : ws->mmin[t] + ws->mmax[t];
             u32 mm = sum >> 1;
             if ((sum & 1) && (mm & 1)) ++mm;
             rep = (bucket << 23) | mm;
@@ -1192,10 +1344,12 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
 }
 
 __global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
-                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype) {
-    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, &ws->ext64);
+                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype, int staged) {
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, &ws->ext64, staged ? ws->bucket_min : nullptr,
+                  staged ? ws->bucket_max : nullptr);
     clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
     if (dtype == kF64) clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
+    if (staged) clear_bucket_extremes(ws, threadIdx.x, blockDim.x);
     __threadfence_system();
 }
 
@@ -1433,12 +1587,14 @@ void launch_reset_chunks(Workspace* ws, uint32_t* group_words, uint32_t* chunk_m
 template <int DT>
 static void launch_hist_t(const void* w, const void* w_ref, uint64_t n, Workspace* ws, u32* chunk_maxexp, uint8_t* batch_max,
                           u32 blocks, u32 threads, hipStream_t s) {
-    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max);
-    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max);
+    const KeyPlanes none = {nullptr, nullptr};
+    if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL((k_hist<true, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max, none);
+    else hipLaunchKernelGGL((k_hist<false, DT>), dim3(blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max, none);
 }
 
+// keys.exp != null: stage keys (binary32, both arrays 16-byte aligned: the caller has checked)
 void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, uint8_t* batch_max,
-                 const Tuning& tune, hipStream_t s) {
+                 KeyPlanes keys, const Tuning& tune, hipStream_t s) {
     if (n == 0) return;
     const u32 threads = tune.hist_threads;
     const u64 units = n / (dtype == kF32 ? 4 : dtype == kF64 ? 2 : 8);   // 16-byte units
@@ -1453,7 +1609,20 @@ void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     }
     if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
     else if (dtype == kF16) launch_hist_t<kF16>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
+    else if (keys.exp) hipLaunchKernelGGL((k_hist<true, kF32, true>), dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, ws, chunk_maxexp, batch_max, keys);
     else launch_hist_t<kF32>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
+}
+
+static u32 even_waves(u64 nchunks, u64 cap);
+
+void launch_pack_keys(const void* w, const void* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits, uint32_t* group_words,
+                      const uint32_t* chunk_maxexp, const uint32_t* chunk_list, KeyPlanes keys, uint32_t* prov, uint32_t slot_words,
+                      const Tuning& tune, hipStream_t s) {
+    const u64 nchunks = num_chunks_of(n);
+    if (nchunks == 0) return;
+    const u32 blocks = even_waves(nchunks, (u64)tune.num_cu * tune.keys_waves_per_cu);
+    hipLaunchKernelGGL(k_pack_keys, dim3(blocks), dim3(64), 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list,
+                       keys, prov, slot_words, (u32)nchunks);
 }
 
 // chunk_list: where to list the chunks sweep 2 has to read (chunk_maxexp then holds what k_hist recorded), or null
@@ -1517,9 +1686,9 @@ void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const
 }
 
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, hipStream_t s) {
+                     uint64_t n, int nbits, int dtype, bool staged, hipStream_t s) {
     hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
-                       (u32)num_chunks_of(n), (u32)dtype);
+                       (u32)num_chunks_of(n), (u32)dtype, staged ? 1 : 0);
 }
 
 void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s) {

@@ -56,6 +56,8 @@ struct Result {
     uint64_t bytes;
     uint32_t status;
     uint32_t used_cache;     // lc_encode_cached: 1 if the blob carries the cached code table
+    uint32_t listed;         // chunks sweep 2 had to read (the others hold the merged symbol only)
+    uint32_t pad_r;
 };
 
 // Caller-owned device memory of lc_encode_cached (LC_CACHE_BYTES, all-zero = empty): the kept set and
@@ -108,6 +110,9 @@ struct Workspace : EncState {
     unsigned long long dec_status;   // (epoch << 8) | lc_status, raised with atomicMax
     DecSet dec_set[kMaxSets];        // one per blob of the call
     Ext64 ext64;
+    // An encode with staged keys: smallest / largest delta bit pattern of every (sign, exponent) bucket, gathered by
+    // sweep 1 (which is then the only sweep that sees the mantissas).  Left cleared (all ones / zero) like the rest.
+    uint32_t bucket_min[512], bucket_max[512];
 };
 
 constexpr size_t kWorkspaceFixed = (sizeof(Workspace) + 255) / 256 * 256;
@@ -125,7 +130,7 @@ __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsW
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
 enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecTable, kSlotSpecSweep,
-            kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kNumSlots };
+            kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kSlotHistKeys, kSlotPackKeys, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
 // variables (read once) for sweeps.
@@ -134,6 +139,8 @@ struct Tuning {
     int hist_blocks_per_cu = 1;
     int hist_threads = 256;
     int pack_waves_per_cu = 8;         // single-wave workgroups of k_pack per compute unit
+    int keys_waves_per_cu = 10;        // ... of the sweep that codes from staged keys (3 fit a SIMD; 10 measured best)
+    int key_staging = 0;               // 0: by the vector's last call, 1: whenever it applies, 2: never
     int spec_waves_per_cu = 6;         // of the single sweep of the cached encode
     int batch_waves_per_cu = 8;        // of the batch kernels
     int decode_blocks_per_cu = 9;     // (LDS lets 4 run at once; more, smaller shares even out chunks that decode to nothing)
@@ -144,8 +151,21 @@ struct Tuning {
 // Launchers (lc_encode.hip, lc_decode.hip).
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s);
 void launch_reset_chunks(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, uint32_t nchunks, hipStream_t s);
+// The keys of an encode with staged keys (fp32, 16-byte aligned arrays): sweep 1 leaves, for every whole batch of 4 rows
+// (1024 elements) and lane, the 16 exponent bytes of the lane's elements (row-major: byte 4 k + v = row k, element v) and
+// their 16 sign bits, and sweep 2 codes from those 9 bits per element instead of reading w and w_ref again.
+struct KeyPlanes {
+    uint8_t* exp;            // 16 bytes per lane and batch: [batch][lane][16]   (null: no staging)
+    uint16_t* sign;          // 16 bits per lane and batch:  [batch][lane]
+};
+constexpr uint32_t kKeyBatch = 4 * kRowElems;          // elements per batch
+__host__ __device__ inline uint64_t key_exp_bytes(uint64_t n) { return (n / kKeyBatch) * kKeyBatch; }
+__host__ __device__ inline uint64_t key_sign_bytes(uint64_t n) { return (n / kKeyBatch) * (kKeyBatch / 8); }
 void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_maxexp, uint8_t* batch_max,
-                 const Tuning& tune, hipStream_t s);
+                 KeyPlanes keys, const Tuning& tune, hipStream_t s);
+void launch_pack_keys(const void* w, const void* w_ref, uint64_t n, Workspace* ws, uint32_t* chunk_bits, uint32_t* group_words,
+                      const uint32_t* chunk_maxexp, const uint32_t* chunk_list, KeyPlanes keys, uint32_t* prov, uint32_t slot_words,
+                      const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
                   uint32_t* chunk_list, hipStream_t s);
 void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
@@ -156,8 +176,9 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
                  uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
                   const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s);
+// staged: the extremes of the kept buckets are in ws->bucket_min / bucket_max (an encode with staged keys)
 void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, hipStream_t s);
+                     uint64_t n, int nbits, int dtype, bool staged, hipStream_t s);
 // One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
 // chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
 struct Seg {

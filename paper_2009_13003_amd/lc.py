@@ -29,6 +29,8 @@ _lib.lc_set_workspace.restype = _int
 _lib.lc_set_workspace.argtypes = [_vp, _sz]
 _lib.lc_encode.restype = _i64
 _lib.lc_encode.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
+_lib.lc_set_option.restype = _int
+_lib.lc_set_option.argtypes = [_int, _int]
 _lib.lc_encode_sized.restype = _i64
 _lib.lc_encode_sized.argtypes = [_vp, _vp, _u64, _int, _vp, _sz, _int, _vp]
 _lib.lc_decode_sized.restype = _i64
@@ -184,6 +186,15 @@ def lc_decode_t(blob, w_ref, stream=None, n=None):
     if r < 0:
         raise LcError(-r)
     return r
+
+
+OPT_KEY_STAGING, STAGING_AUTO, STAGING_ALWAYS, STAGING_NEVER = 1, 0, 1, 2
+
+
+def lc_set_option(option, value):
+    st = int(_lib.lc_set_option(option, value))
+    if st != OK:
+        raise LcError(st)
 
 
 def lc_encode_sized(w, w_ref, nbits, out, stream=None, n=None):

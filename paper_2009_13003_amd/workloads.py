@@ -144,8 +144,10 @@ def llama7b(seed=0, device="cpu", shrink_by=1):
     return per_tensor_laplace(shrink(llama7b_shapes(), shrink_by), -6, -3, 4, seed, device)
 
 
-def llama7b_head(nel=1 << 28, seed=0, device="cpu"):
-    """The first `nel` elements of config 5 (same values as llama7b()[:nel]): enough leading tensors, then cut."""
+def llama7b_head(nel=1 << 28, seed=0, device="cpu", noise_seed=None):
+    """The first `nel` elements of config 5 (same values as llama7b()[:nel]): enough leading tensors, then cut.
+    noise_seed: draw the deltas from a generator seeded with it instead (same reference weights, same per-tensor
+    scales): the delta of another iteration of the same model."""
     shapes, total = [], 0
     for s in llama7b_shapes():
         shapes.append(s)
@@ -155,7 +157,7 @@ def llama7b_head(nel=1 << 28, seed=0, device="cpu"):
     nfull = len(llama7b_shapes())
     scales = 10.0 ** np.random.RandomState(seed + 2).uniform(-6, -3, size=nfull)[:len(shapes)]
     w_ref = reference_weights(total, seed, device)
-    g = _gen(seed + 1, device)
+    g = _gen(seed + 1 if noise_seed is None else noise_seed, device)
     w = torch.empty_like(w_ref)
     off = 0
     for s, b in zip(shapes, scales):

@@ -172,6 +172,23 @@ def test_config5_llama7b_all_slices(lc):
         jobs.drain()
 
 
+def test_staged_keys_at_full_size(lc):
+    """The encode with staged keys (what a dense vector's second and later encodes take) on config 3 and on the first and
+    the ragged last slice of config 5, in full against the oracle."""
+    from paper_2009_13003_amd import workloads
+    lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_ALWAYS)
+    try:
+        w, w_ref, nbits = workloads.vgg16(device=DEV)
+        full_check(lc, w, w_ref, nbits, "config 3, staged keys")
+        del w, w_ref
+        w, w_ref, nbits = workloads.llama7b_head(device=DEV)
+        full_check(lc, w, w_ref, nbits, "config 5 slice 0, staged keys")
+        n_last = 27_529_216
+        full_check(lc, w[:n_last], w_ref[:n_last], nbits, "a slice of config 5's last length, staged keys")
+    finally:
+        lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_AUTO)
+
+
 def test_single_call_past_4gib_offsets(lc):
     """One call whose arrays are larger than 4 GiB (byte offsets and chunk indices beyond 32-bit
     element arithmetic), ragged tail included, in full against the oracle."""

@@ -1568,3 +1568,127 @@ def test_many_chunks_with_long_payloads(lc):
     d = torch.exp2(-4 - e) * (1 + torch.rand(n, generator=g, device=DEV))
     w_ref = torch.zeros(n, device=DEV)
     check_case(lc, w_ref + d, w_ref, nbits, "many chunks, long payloads")
+
+
+# ---------------------------------------------------------------- encode with staged keys
+@pytest.fixture
+def staged(lc):
+    """lc_encode stages keys wherever that applies (fp32, aligned arrays, at least one chunk) for the test's duration."""
+    lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_ALWAYS)
+    yield
+    lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_AUTO)
+
+
+def staged_launches(lc, fn):
+    """Runs fn with the library's kernel timing on; returns how often the key-staging sweep ran."""
+    lc.lc_profile(True)
+    try:
+        fn()
+        return lc.lc_profile_read()["k_hist_keys"][1]
+    finally:
+        lc.lc_profile(False)
+
+
+@pytest.mark.parametrize("nbits", [1, 2, 3, 4])
+def test_staged_keys_sizes_and_bit_budgets(lc, staged, nbits):
+    """The second sweep coding from the 9-bit keys of the first: blobs and restored weights as the oracle's, for
+    vectors of whole chunks, with ragged tails shorter and longer than a batch of keys, and below one chunk (where
+    nothing is staged)."""
+    for n in (16384, 16385, 2 * 16384 + 1023, 2 * 16384 + 1024, 5 * 16384 + 77, 37 * 16384, 64 * 16384 + 4097, (1 << 20) + 13, 1000):
+        w, w_ref = laplace_case(n, seed=n * 4 + nbits, zero_frac=0.05)
+        ran = staged_launches(lc, lambda: check_case(lc, w, w_ref, nbits, "staged keys"))
+        assert ran == (1 if n >= 16384 else 0), n
+
+
+def test_staged_keys_degenerate_and_long_codes(lc, staged):
+    n = 2 * 16384 + 500
+    w_ref = 0.05 * torch.randn(n, device=DEV)
+    check_case(lc, w_ref.clone(), w_ref, 3, "all zero delta")
+    check_case(lc, w_ref * 0 + 1.0, w_ref * 0, 2, "one bucket, one value")
+    d = torch.zeros(n, device=DEV); d[12345] = 0.5
+    check_case(lc, d, torch.zeros(n, device=DEV), 3, "single non-zero")
+    w = w_ref.clone(); w[::3] = 0.0; ref = w_ref.clone(); ref[::3] = -0.0
+    w[1::3] = w_ref[1::3] + 0.01
+    ref[2::9] = 1e-39; w[2::9] = 3e-39
+    check_case(lc, w, ref, 3, "zeros / subnormals")
+    # both signs of many exponents, flat and geometric populations (codes of 12 and more bits)
+    n = 20 * 16384 + 9
+    g = torch.Generator(device=DEV); g.manual_seed(5)
+    e = torch.randint(-8, 0, (n,), generator=g, device=DEV).float()
+    sgn = torch.randint(0, 2, (n,), generator=g, device=DEV).float() * 2 - 1
+    d = sgn * torch.exp2(e) * (1 + torch.rand(n, generator=g, device=DEV))
+    check_case(lc, d, torch.zeros(n, device=DEV), 4, "16 flat symbols")
+    e = torch.floor(torch.log2(torch.rand(n, generator=g, device=DEV).clamp_(min=2.0 ** -20)))
+    d = torch.exp2(-20 - e) * (1 + 0.5 * torch.rand(n, generator=g, device=DEV))
+    blob = check_case(lc, d, torch.zeros(n, device=DEV), 4, "geometric populations")
+    assert lcb1_reader.parse_header(blob)["max_len"] >= 12
+    # extremes of a bucket that sit in the ragged tail behind the last whole batch of keys, and in the last element
+    n = 3 * 16384 + 1024 + 37
+    w, w_ref = laplace_case(n, seed=808)
+    w[-1] = w_ref[-1] + 0.0312; w[-20] = w_ref[-20] - 0.0623; w[3 * 16384 + 1024 + 3] = w_ref[3 * 16384 + 1024 + 3] + 0.03126
+    check_case(lc, w, w_ref, 3, "extremes in the tail")
+    # non-finite delta: rejected as ever, and the call after it is sound
+    bad = w.clone(); bad[777] = float("nan")
+    out = lc.alloc_out(n, 3, DEV)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_encode(bad, w_ref, 3, out)
+    assert e.value.status == lc.ERR_NONFINITE
+    check_case(lc, w, w_ref, 3, "after a rejected call")
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_staged_keys_quiet_chunks_and_other_paths(lc, staged, nbits):
+    """Chunks below every kept bucket are passed over by the key sweep too; unaligned arrays, 16-bit parameters and the
+    cached encode do not stage and still give their blobs; a plain call after staged ones finds the scratch state clean."""
+    nchunks = 150
+    n = nchunks * 16384 + 1234
+    quiet = [0, 5, 63, 64] + list(range(100, 111)) + [149, 150]
+    w, w_ref = quiet_chunk_case(n, 300 + nbits, quiet)
+    assert staged_launches(lc, lambda: check_case(lc, w, w_ref, nbits, "quiet chunks, staged")) == 1
+    assert staged_launches(lc, lambda: check_case(lc, w[3:], w_ref[3:], nbits, "unaligned: not staged")) == 0
+    w2, ref2 = quiet_chunk_case(n, 310 + nbits, list(range(nchunks + 1)))
+    check_case(lc, w2, ref2, nbits, "all quiet")
+    w2[-5] = ref2[-5] + 0.25
+    check_case(lc, w2, ref2, nbits, "all quiet but one")
+    cache_gpu, cache_cpu = lc.new_cache(DEV), orc.new_cache()
+    out = lc.alloc_out(n, nbits, DEV)
+    cached_step(lc, w, w_ref, nbits, out, cache_gpu, cache_cpu)
+    _, used = cached_step(lc, w, w_ref, nbits, out, cache_gpu, cache_cpu)
+    assert used
+    ticket = lc.lc_encode_async(w, w_ref, nbits, out)
+    size, _ = lc.lc_encode_wait(ticket)
+    assert np.array_equal(out[:size].cpu().numpy(), orc.encode(w.cpu().numpy(), w_ref.cpu().numpy(), nbits))
+    lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_NEVER)
+    assert staged_launches(lc, lambda: check_case(lc, w, w_ref, nbits, "plain after staged")) == 0
+
+
+def test_staged_keys_follow_the_vectors_last_encode(lc):
+    """The default: a vector's first encode takes the plain second sweep; the next stages keys iff the one before had
+    to read more than 30 % of the chunks (vectors of 2^26 elements and more); the blob never depends on it."""
+    lc.lc_set_option(lc.OPT_KEY_STAGING, lc.STAGING_AUTO)
+    small_w, small_r = laplace_case(40 * 16384 + 5, seed=900)                 # below 2^26 elements: never staged by default
+    out = lc.alloc_out(small_w.numel(), 3, DEV)
+    for _ in range(2):
+        assert staged_launches(lc, lambda: lc.lc_encode(small_w, small_r, 3, out)) == 0
+    n = (1 << 26) + 5
+    dense_w, dense_r = laplace_case(n, seed=901)
+    sparse_w, sparse_r = quiet_chunk_case(n, 902, list(range(1000, 4096)))    # 1001 loud chunks of 4097
+    out = lc.alloc_out(n, 3, DEV)
+    for w, r, expect in ((dense_w, dense_r, [0, 1, 1]), (sparse_w, sparse_r, [0, 0, 0])):
+        blob_cpu = orc.encode(w.cpu().numpy(), r.cpu().numpy(), 3)
+        got = []
+        for _ in range(3):
+            sizes = []
+            got.append(staged_launches(lc, lambda: sizes.append(lc.lc_encode(w, r, 3, out))))
+            assert np.array_equal(out[:sizes[0]].cpu().numpy(), blob_cpu)
+        assert got == expect, got
+    # the same buffers with new content: the hint is a guess about performance only
+    dense_w.copy_(sparse_w); dense_r.copy_(sparse_r)
+    for expect in (1, 0):
+        sizes = []
+        assert staged_launches(lc, lambda: sizes.append(lc.lc_encode(dense_w, dense_r, 3, out))) == expect
+        assert np.array_equal(out[:sizes[0]].cpu().numpy(), orc.encode(sparse_w.cpu().numpy(), sparse_r.cpu().numpy(), 3))
+    with pytest.raises(lc.LcError):
+        lc.lc_set_option(lc.OPT_KEY_STAGING, 3)
+    with pytest.raises(lc.LcError):
+        lc.lc_set_option(7, 0)
