@@ -16,9 +16,9 @@
  *
  * Every step runs in HIP kernels; nothing is computed on the host except argument
  * checks.  All pointers are DEVICE pointers unless a parameter says "host".
- * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls are
- * serialised inside the library (one scratch area per device): they may be issued
- * from several threads but do not overlap.
+ * `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls may be
+ * issued from several threads; the library keeps a scratch area per stream in use
+ * (see lc_encode_async), so calls on different streams overlap on the device.
  *
  * ---------------------------------------------------------------------------
  * LCB1 blob layout (little-endian).  The paper says only "save to disk"; this
@@ -221,8 +221,9 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
 #define LC_CACHE_BYTES 256
 lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nbits,
                           void* out, void* cache, int* used, void* stream);
-/* The same for parameters stored as bf16 or fp16 (dtype as for lc_encode_t; a cache serves any of LC_F32, LC_BF16,
- * LC_F16, since all three code the fp32 delta; LC_F64: LC_ERR_BADARG). */
+/* The same for parameters of another type (dtype as for lc_encode_t).  A cache serves any of LC_F32, LC_BF16, LC_F16,
+ * since all three code the fp32 delta.  LC_F64: the same rule on the binary64 delta's 12-bit bucket ids (a cache made
+ * by the other types never matches), but coded in two sweeps like lc_encode_t: the reuse saves the Huffman build only. */
 lc_ssize lc_encode_cached_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype,
                             void* cache, int* used, void* stream);
 
@@ -236,13 +237,16 @@ lc_ssize lc_encode_cached_t(const void* w, const void* w_ref, uint64_t n, int nb
  * (say the optimizer step that overwrites w) wait for exactly that point, without blocking the host;
  * it returns an lc_status.  out, and cache, belong to the call until lc_encode_wait(ticket, used)
  * returns: it blocks until the call has finished, returns what lc_encode / lc_encode_cached would
- * have returned (`used` may be NULL) and frees the ticket.  All calls of this library on one device
- * share one scratch area, so the library orders each call after the asynchronous calls issued
- * before it, whatever their streams.
+ * have returned (`used` may be NULL) and frees the ticket.
+ * Calls on one stream run in order and share a scratch area; calls on different streams get different
+ * areas (up to 8 per device, each of lc_workspace_bytes of the largest call it has served; with a
+ * caller-supplied workspace there is one, and calls on other streams wait for each other) and run
+ * side by side on the device.  So the slices of a large vector can be enqueued on one stream one
+ * after the other and waited for once, and the tensors of a model can be spread over a few streams.
  */
-#define LC_MAX_TICKETS 16
+#define LC_MAX_TICKETS 32
 int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, void* out, void* cache, void* stream);
-/* lc_encode_async for parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: -LC_ERR_BADARG). */
+/* lc_encode_async for parameters of type dtype (as for lc_encode_t / lc_encode_cached_t). */
 int lc_encode_async_t(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, int dtype, void* cache,
                       void* stream);
 int lc_encode_release_inputs(int ticket, void* other_stream);
@@ -275,9 +279,10 @@ lc_ssize lc_decode(const void* blob, float* w_ref, uint64_t n, void* stream);
  * returns the sum of the bytes consumed or -(lc_status).
  */
 lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint64_t n, void* stream);
-/* The same for parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: LC_ERR_BADARG), every blob of that
- * type: bit for bit what `count` successive lc_decode_t calls give, i.e. the running value is rounded to the
- * storage type after every blob's addition. */
+/* The same for parameters of type dtype, every blob of that type: bit for bit what `count` successive lc_decode_t
+ * calls give, i.e. the running value is rounded to the storage type after every blob's addition.  LC_F64: every
+ * blob is validated first as for the other types, then the blobs are applied one sweep each (one read and one write
+ * of w_ref per blob). */
 lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint64_t n, int dtype, void* stream);
 
 /*
@@ -296,8 +301,8 @@ lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint
 size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits);
 lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const uint64_t* n, int count, int nbits,
                          void* const* out, int64_t* sizes, void* stream);
-/* The same for tensors that all hold parameters of type dtype (LC_F32, LC_BF16 or LC_F16; LC_F64: LC_ERR_BADARG):
- * tensor t is coded as lc_encode_t(w[t], w_ref[t], n[t], nbits, out[t], dtype) would. */
+/* The same for tensors that all hold parameters of type dtype: tensor t is coded as lc_encode_t(w[t], w_ref[t], n[t],
+ * nbits, out[t], dtype) would.  LC_F64: by one such encode after the other inside the call. */
 lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const uint64_t* n, int count, int nbits,
                            void* const* out, int64_t* sizes, int dtype, void* stream);
 
@@ -310,8 +315,8 @@ lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const
  */
 lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
                          void* stream);
-/* The same for tensors and blobs of element type dtype (LC_F32, LC_BF16 or LC_F16): tensor t as
- * lc_decode_t(blobs[t], w_ref[t], n[t], dtype); a blob of another element type fails with LC_ERR_BADARG. */
+/* The same for tensors and blobs of element type dtype: tensor t as lc_decode_t(blobs[t], w_ref[t], n[t], dtype); a
+ * blob of another element type fails with LC_ERR_BADARG.  LC_F64: by one such restore after the other inside the call. */
 lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
                            int dtype, void* stream);
 

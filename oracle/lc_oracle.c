@@ -669,13 +669,9 @@ static void write_header64(uint8_t* out, uint64_t n, int nbits, const lco_model6
     put32(out + 56, maxlen);
 }
 
-/* Algorithm 1 lines 4-6 for binary64 parameters; element order and records as in write_blob. */
-int64_t lco_encode64(const double* w, const double* wref, uint64_t n, int nbits,
-                     uint8_t* out, uint64_t cap) {
-    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || (n && (!w || !wref))) return -LCO_BADARG;
-    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
-    lco_model64 M; int st = build_model64(w, wref, n, nbits, &M);
-    if (st == LCO_NONFINITE) { write_header64(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+/* The blob of one binary64 checkpoint for a finished model; element order and records as in write_blob. */
+static int64_t write_blob64(const double* w, const double* wref, uint64_t n, int nbits, const lco_model64* M,
+                            uint8_t* out, uint64_t cap) {
     uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
     memset(out + LCO_HEADER, 0, lco_encode_bound(n, nbits) - LCO_HEADER);
     uint64_t word_off = 0;
@@ -690,9 +686,9 @@ int64_t lco_encode64(const double* w, const double* wref, uint64_t n, int nbits,
                 uint64_t i = c * LCO_C + (uint64_t)r * (LCO_W * LCO_V) + l * LCO_V + v;
                 if (i >= n) continue;
                 uint32_t b = (uint32_t)(d2u(delta_of64(w[i], wref[i])) >> 52);
-                uint32_t s = M.sym_of_bucket[b];
-                if ((uint64_t)(payload - out) + 4 * ((p + M.len[s] + 31) / 32) > cap) return -LCO_OUT_TOO_SMALL;
-                for (int k = M.len[s] - 1; k >= 0; --k) put_bit(payload, p++, (M.code[s] >> k) & 1u);
+                uint32_t s = M->sym_of_bucket[b];
+                if ((uint64_t)(payload - out) + 4 * ((p + M->len[s] + 31) / 32) > cap) return -LCO_OUT_TOO_SMALL;
+                for (int k = M->len[s] - 1; k >= 0; --k) put_bit(payload, p++, (M->code[s] >> k) & 1u);
             }
             put16(rec + 2 * l, (uint32_t)(p - start));
         }
@@ -700,8 +696,59 @@ int64_t lco_encode64(const double* w, const double* wref, uint64_t n, int nbits,
     }
     put32(out + LCO_HEADER + 4 * nchunks, (uint32_t)word_off);
     uint64_t total = area + 4 * word_off;
-    write_header64(out, n, nbits, &M, nchunks, total, LCO_OK);
+    write_header64(out, n, nbits, M, nchunks, total, LCO_OK);
     return (int64_t)total;
+}
+
+/* Algorithm 1 lines 4-6 for binary64 parameters. */
+int64_t lco_encode64(const double* w, const double* wref, uint64_t n, int nbits,
+                     uint8_t* out, uint64_t cap) {
+    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || (n && (!w || !wref))) return -LCO_BADARG;
+    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
+    lco_model64 M; int st = build_model64(w, wref, n, nbits, &M);
+    if (st == LCO_NONFINITE) { write_header64(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+    return write_blob64(w, wref, n, nbits, &M, out, cap);
+}
+
+/*
+ * Section 3.2 table caching for binary64 parameters: the rule of lco_encode_cached word for word, on the 12-bit
+ * bucket ids (a cache made by a binary32 encode names other buckets and simply does not match).
+ */
+int64_t lco_encode_cached64(const double* w, const double* wref, uint64_t n, int nbits,
+                            uint8_t* out, uint64_t cap, lco_cache* cache, int* used) {
+    if (nbits < 1 || nbits > 4 || n > LCO_MAX_N || !out || !cache || (n && (!w || !wref))) return -LCO_BADARG;
+    if (cap < lco_encode_bound(n, nbits)) return -LCO_OUT_TOO_SMALL;
+    if (used) *used = 0;
+    lco_model64 M; int st = build_model64(w, wref, n, nbits, &M);
+    if (st == LCO_NONFINITE) { write_header64(out, n, nbits, NULL, 0, LCO_HEADER, LCO_NONFINITE); return -LCO_NONFINITE; }
+    int ok = cache->valid == 1 && cache->nbits == (uint32_t)nbits && cache->K == (uint32_t)M.K;
+    if (ok) {
+        uint32_t kraft = 0; int active = 0;
+        uint64_t payload_bits = 0;
+        for (int j = 0; j <= M.K; ++j) {
+            uint32_t l = cache->len[j];
+            if (l > 15) { ok = 0; break; }
+            if (l) { kraft += 1u << (15 - l); ++active; }
+            if (j < M.K && cache->kept[j] != M.kept[j]) ok = 0;
+            if ((l > 0) != (M.cnt[j] > 0)) ok = 0;
+            payload_bits += M.cnt[j] * (uint64_t)l;
+        }
+        if (active >= 2 && kraft != (1u << 15)) ok = 0;
+        if (active == 1 && kraft != (1u << 14)) ok = 0;
+        if (payload_bits > n * (uint64_t)nbits) ok = 0;
+    }
+    if (ok) {
+        for (int j = 0; j <= M.K; ++j) M.len[j] = (uint8_t)cache->len[j];
+        lco_canonical_codes(M.len, M.K + 1, M.code);
+        if (used) *used = 1;
+    }
+    int64_t r = write_blob64(w, wref, n, nbits, &M, out, cap);
+    if (r < 0) return r;
+    memset(cache, 0, sizeof *cache);
+    cache->valid = 1; cache->nbits = (uint32_t)nbits; cache->K = (uint32_t)M.K;
+    for (int j = 0; j < M.K; ++j) cache->kept[j] = M.kept[j];
+    for (int j = 0; j <= M.K; ++j) cache->len[j] = M.len[j];
+    return r;
 }
 
 /* Algorithm 1 line 7 for binary64 parameters; checks as in lco_decode. */

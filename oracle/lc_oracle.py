@@ -67,6 +67,8 @@ def lib():
         L.lco_quantize64.argtypes = [vp, vp, u64, i32, vp, vp, vp]
         L.lco_encode64.restype = i64
         L.lco_encode64.argtypes = [vp, vp, u64, i32, vp, u64]
+        L.lco_encode_cached64.restype = i64
+        L.lco_encode_cached64.argtypes = [vp, vp, u64, i32, vp, u64, vp, vp]
         L.lco_decode64.restype = i64
         L.lco_decode64.argtypes = [vp, u64, vp, u64]
         _lib = L
@@ -228,6 +230,21 @@ def encode64(w, w_ref, nbits):
     return out[:r].copy()
 
 
+def encode_cached64(w, w_ref, nbits, cache):
+    """Section 3.2 table caching for binary64 parameters: returns (blob, used_cache); `cache` is updated in place."""
+    w, w_ref = _f64(w), _f64(w_ref)
+    assert w.size == w_ref.size and cache.dtype == np.uint32 and cache.size == CACHE_WORDS
+    cap = encode_bound(w.size, min(max(nbits, 1), 4))
+    out = np.zeros(max(cap, 1), np.uint8)
+    used = ctypes.c_int(0)
+    r = lib().lco_encode_cached64(_p(w), _p(w_ref), w.size, nbits, _p(out), cap, _p(cache), ctypes.byref(used))
+    if r < 0:
+        err = OracleError(-r)
+        err.header = out[:512].copy()
+        raise err
+    return out[:r].copy(), bool(used.value)
+
+
 def decode64(blob, w_ref):
     """Updates w_ref (float64 contiguous numpy array) in place; returns bytes consumed."""
     assert w_ref.dtype == np.float64 and w_ref.flags.c_contiguous
@@ -277,6 +294,8 @@ def encode_t(w, w_ref, nbits, dtype):
 def encode_cached_t(w, w_ref, nbits, dtype, cache):
     """encode_cached on the exactly widened vectors (16-bit storage types code the fp32 delta, as in encode_t);
     the blob names the storage type.  Returns (blob, used_cache)."""
+    if dtype == DT_F64:
+        return encode_cached64(w, w_ref, nbits, cache)
     assert dtype in (DT_F32, DT_BF16, DT_F16)
     blob, used = encode_cached(widen(w, dtype), widen(w_ref, dtype), nbits, cache)
     blob[60:64] = np.frombuffer(np.uint32(dtype).tobytes(), np.uint8)

@@ -16,31 +16,48 @@ using namespace lc;
 constexpr int kMaxDevices = 16;
 
 constexpr int kHintBits = 10, kHints = 1 << kHintBits;
+
+// One scratch area (lc_workspace_bytes and more) of a device.  A call takes the area its stream used last (calls on one
+// stream are ordered, so they share an area without waiting), else an idle one, else a new one (at most kMaxAreas per
+// device), else the least recently used one, which its stream then waits for.  Calls on different streams thus
+// get different areas and overlap on the device.
+constexpr int kMaxAreas = 8;
+struct Area {
+    void* mem = nullptr;
+    size_t bytes = 0;
+    bool user = false;            // caller-supplied (lc_set_workspace): never freed, never grown
+    hipStream_t stream = nullptr; // the stream of the last call that used it
+    bool used = false;
+    hipEvent_t idle = nullptr;    // recorded behind the last call that used it
+    bool clean = false;           // its encode state is known to be cleared
+    uint64_t stamp = 0;           // when it was last taken
+};
+
 struct DeviceState {
-    void* owned = nullptr;       // library-owned scratch
-    size_t owned_bytes = 0;
-    void* user = nullptr;        // caller-supplied scratch (lc_set_workspace)
+    Area area[kMaxAreas];
+    void* user = nullptr;        // caller-supplied scratch (lc_set_workspace): then the only area
     size_t user_bytes = 0;
+    uint64_t clock = 0;
     Tuning tune;
     bool tuned = false;
-    const void* clean = nullptr;  // scratch area whose encode state is known to be cleared
-    hipEvent_t last = nullptr;    // end of the latest asynchronous call on this device
-    bool pending = false;         // ... which later calls must order themselves after (they share the scratch)
     // What the last encode of a vector (told apart by address and length) found: the share of its chunks that sweep 2
     // had to read.  Decides whether the next encode of that vector stages keys (see stage_keys()).
     struct Hint { const void* w = nullptr; uint64_t n = 0; float listed = 0; };
     Hint hint[kHints];
 };
 
-// lc_encode_async: a call in flight.
-constexpr int kMaxTickets = 16;
-struct Ticket {
-    bool busy = false;
+// A call in progress: where its kernels report (g_pinned[slot]) and, for lc_encode_async, its events.  Asynchronous
+// calls hand their slot out as the ticket; at most LC_MAX_TICKETS of them are in flight, the other slots serve
+// calls that wait themselves (several host threads may be inside such calls at once).
+constexpr int kMaxTickets = LC_MAX_TICKETS, kCallSlots = 2 * LC_MAX_TICKETS;
+struct CallSlot {
+    bool busy = false, async = false;
     int dev = 0; const void* w = nullptr; uint64_t n = 0;   // whose hint its outcome updates
     hipEvent_t inputs = nullptr;  // after the last kernel that reads w / w_ref
     hipEvent_t done = nullptr;    // after the last kernel
 };
-Ticket g_ticket[kMaxTickets];
+CallSlot g_slot[kCallSlots];
+int g_async_in_flight = 0;
 
 // lc_encode_batch: pinned host memory for the tensor list on its way to the device and for the
 // per-tensor outcomes the kernels write (mapped).
@@ -50,13 +67,12 @@ struct BatchHost {
 };
 BatchHost* g_batch = nullptr;
 BatchHost* g_batch_dev = nullptr;
-static_assert(sizeof(((HostResult*)0)->enc_async) / sizeof(Result) == kMaxTickets, "one result per ticket");
 
 std::mutex g_mu;
 DeviceState g_dev[kMaxDevices];
 static_assert(sizeof(TableCache) <= LC_CACHE_BYTES, "LC_CACHE_BYTES too small");
 static_assert(sizeof(((HostResult*)0)->bytes) / sizeof(unsigned long long) >= LC_MAX_MANY, "HostResult too small");
-HostResult* g_pinned = nullptr;  // mapped pinned host memory the kernels write their outcome to
+HostResult* g_pinned = nullptr;  // mapped pinned host memory, kCallSlots records: the kernels write their outcome there
 HostResult* g_pinned_dev = nullptr;   // the same memory as the device sees it
 uint64_t g_epoch = 0;            // tags the decode status word of each call
 
@@ -113,36 +129,96 @@ void read_tuning(DeviceState& ds, int dev) {
     ds.tuned = true;
 }
 
-// Scratch for the current device, at least `need` bytes.  Returns nullptr with *err set.
-Workspace* get_workspace(size_t need, int* err, DeviceState** ds_out) {
+// The current device's state, with the pinned result records in place.  Returns nullptr with *err set.
+DeviceState* device_state(int* err) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); *err = LC_ERR_HIP; return nullptr; }
     DeviceState& ds = g_dev[dev];
     read_tuning(ds, dev);
     if (!g_pinned) {
-        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), sizeof(HostResult), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess ||
+        if (hipHostMalloc(reinterpret_cast<void**>(&g_pinned), kCallSlots * sizeof(HostResult), hipHostMallocMapped | hipHostMallocPortable) != hipSuccess ||
             hipHostGetDevicePointer(reinterpret_cast<void**>(&g_pinned_dev), g_pinned, 0) != hipSuccess) {
             (void)hipGetLastError();
             if (g_pinned) (void)hipHostFree(g_pinned);
             g_pinned = nullptr; *err = LC_ERR_HIP; return nullptr;
         }
-        memset(g_pinned, 0, sizeof(HostResult));
+        memset(g_pinned, 0, kCallSlots * sizeof(HostResult));
     }
-    *ds_out = &ds;
-    if (ds.user) {
-        if (ds.user_bytes < need) { *err = LC_ERR_WORKSPACE; return nullptr; }
-        return static_cast<Workspace*>(ds.user);
+    return &ds;
+}
+
+// A scratch area of at least `need` bytes for a call on stream s (see Area).  Returns nullptr with *err set.
+Area* acquire(DeviceState* ds, hipStream_t s, size_t need, int* err) {
+    Area* a = nullptr;
+    if (ds->user) {
+        // the caller's area is the only one: calls on other streams are ordered behind its last user
+        a = &ds->area[0];
+        if (ds->user_bytes < need) { *err = LC_ERR_WORKSPACE; return nullptr; }
+    } else {
+        Area *same = nullptr, *idle = nullptr, *empty = nullptr, *lru = nullptr;
+        for (int i = 0; i < kMaxAreas; ++i) {
+            Area* c = &ds->area[i];
+            if (!c->mem) { if (!empty) empty = c; continue; }
+            if (c->used && c->stream == s) { if (!same || c->stamp > same->stamp) same = c; continue; }
+            bool is_idle = !c->used;
+            if (!is_idle) {
+                const hipError_t q = hipEventQuery(c->idle);
+                if (q == hipSuccess) is_idle = true; else (void)hipGetLastError();
+            }
+            if (is_idle && (!idle || (idle->bytes < need && c->bytes > idle->bytes))) idle = c;
+            if (!lru || c->stamp < lru->stamp) lru = c;
+        }
+        a = same ? same : idle ? idle : empty ? empty : lru;
     }
-    if (ds.owned_bytes < need) {
-        if (ds.owned) { (void)hipDeviceSynchronize(); (void)hipFree(ds.owned); ds.owned = nullptr; ds.owned_bytes = 0; }
+    if (!a->idle && hipEventCreateWithFlags(&a->idle, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); a->idle = nullptr; *err = LC_ERR_HIP; return nullptr; }
+    if (a->used && a->stream != s) {
+        // another stream's work may still be using it (the caller's single area, or every area busy): wait for that on s
+        if (hipStreamWaitEvent(s, a->idle, 0) != hipSuccess) { (void)hipGetLastError(); *err = LC_ERR_HIP; return nullptr; }
+    }
+    if (ds->user) {
+        if (a->mem != ds->user) { a->mem = ds->user; a->bytes = ds->user_bytes; a->user = true; a->clean = false; a->used = false; }
+    } else if (a->bytes < need) {
+        if (a->mem) {
+            if (a->used) (void)hipEventSynchronize(a->idle);         // its last call must be through with the old memory
+            (void)hipFree(a->mem); a->mem = nullptr; a->bytes = 0;
+        }
         size_t want = need < (4u << 20) ? (4u << 20) : need;     // never smaller than the head that is cleared below
         static_assert(kWorkspaceHead <= (4u << 20), "the smallest scratch area must hold the fixed head");
-        if (hipMalloc(&ds.owned, want) != hipSuccess) { (void)hipGetLastError(); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
-        if (hipMemset(ds.owned, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(ds.owned); ds.owned = nullptr; *err = LC_ERR_HIP; return nullptr; }
-        ds.owned_bytes = want;
-        ds.clean = nullptr;      // new memory (possibly at the old address): its encode state is not set up yet
+        if (hipMalloc(&a->mem, want) != hipSuccess) { (void)hipGetLastError(); a->mem = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        if (hipMemset(a->mem, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(a->mem); a->mem = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        a->bytes = want; a->user = false; a->used = false;
+        a->clean = false;        // new memory (possibly at the old address): its encode state is not set up yet
     }
-    return static_cast<Workspace*>(ds.owned);
+    a->stream = s; a->stamp = ++ds->clock;
+    return a;
+}
+
+// Behind the last kernel of a call that used the area.
+bool release(Area* a, hipStream_t s) {
+    a->used = true;
+    if (hipEventRecord(a->idle, s) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return true;
+}
+
+// A free call slot (asynchronous calls: at most kMaxTickets in flight), or -1.
+int take_slot(bool async) {
+    if (async && g_async_in_flight >= kMaxTickets) return -1;
+    for (int i = 0; i < kCallSlots; ++i) {
+        if (g_slot[i].busy) continue;
+        CallSlot& c = g_slot[i];
+        if (async && !c.done) {
+            if (hipEventCreateWithFlags(&c.inputs, hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&c.done, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); c.inputs = c.done = nullptr; return -1; }
+        }
+        c.busy = true; c.async = async; c.w = nullptr; c.n = 0;
+        if (async) ++g_async_in_flight;
+        return i;
+    }
+    return -1;
+}
+void free_slot(int i) {
+    if (g_slot[i].async) --g_async_in_flight;
+    g_slot[i].busy = false; g_slot[i].async = false;
 }
 
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -179,14 +255,6 @@ struct Scratch {
     }
 };
 
-// Every call uses the device's one scratch area: work enqueued on `s` must not start before the
-// latest asynchronous call has finished with it.
-bool order_after_async(DeviceState* ds, hipStream_t s) {
-    if (!ds->pending) return true;
-    if (hipStreamWaitEvent(s, ds->last, 0) != hipSuccess) { (void)hipGetLastError(); return false; }
-    return true;
-}
-
 }  // namespace
 
 extern "C" {
@@ -207,10 +275,20 @@ int lc_set_workspace(void* dev_ws, size_t bytes) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
     if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceHead)) return LC_ERR_WORKSPACE;
+    (void)hipDeviceSynchronize();                 // no call may still be using the areas that change hands here
     if (dev_ws && hipMemset(dev_ws, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
-    g_dev[dev].user = dev_ws;
-    g_dev[dev].user_bytes = dev_ws ? bytes : 0;
-    g_dev[dev].clean = nullptr;
+    DeviceState& ds = g_dev[dev];
+    if (ds.user && ds.area[0].mem == ds.user) { ds.area[0].mem = nullptr; ds.area[0].bytes = 0; ds.area[0].user = false; ds.area[0].used = false; }
+    if (dev_ws) {
+        // the caller's area becomes the only one: the library's own go
+        for (int i = 0; i < kMaxAreas; ++i) {
+            Area& a = ds.area[i];
+            if (a.mem && !a.user) (void)hipFree(a.mem);
+            a.mem = nullptr; a.bytes = 0; a.user = false; a.used = false; a.clean = false;
+        }
+    }
+    ds.user = dev_ws;
+    ds.user_bytes = dev_ws ? bytes : 0;
     return LC_OK;
 }
 
@@ -251,20 +329,23 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
                      int* used, void* stream, bool async) {
     if (nbits < 1 || nbits > 4 || n > LC_MAX_N || !out || misaligned(out, 16)) return -LC_ERR_BADARG;
     if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
-    if (dtype == LC_F64 && (cache || async)) return -LC_ERR_BADARG;          // those forms code the fp32 delta only
     const uintptr_t esize = dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2;
     if (n && (!w || !w_ref || misaligned(w, esize) || misaligned(w_ref, esize))) return -LC_ERR_BADARG;
-    std::lock_guard<std::mutex> lock(g_mu);
-    int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(lc_workspace_bytes(n, nbits), &err, &ds);
-    if (!ws) return -(lc_ssize)err;
+    std::unique_lock<std::mutex> lock(g_mu);
+    int err = 0;
+    DeviceState* ds = device_state(&err);
+    if (!ds) return -(lc_ssize)err;
+    hipStream_t s = static_cast<hipStream_t>(stream);
     bool staged = stage_keys(ds, w, w_ref, n, dtype, cache != nullptr);
+    Area* area = nullptr;
     if (staged) {
         // the key planes lie behind the usual scratch; a caller's area that has no room for them keeps the plain path
-        Workspace* bigger = get_workspace(staged_scratch_bytes(n, nbits), &err, &ds);
-        if (bigger) ws = bigger; else staged = false;
+        area = acquire(ds, s, staged_scratch_bytes(n, nbits), &err);
+        if (!area) staged = false;
     }
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!area) area = acquire(ds, s, lc_workspace_bytes(n, nbits), &err);
+    if (!area) return -(lc_ssize)err;
+    Workspace* ws = static_cast<Workspace*>(area->mem);
     const Scratch sc(ws, num_chunks_of(n), nbits);
     const KeyPlanes keys = staged ? sc.keys(n) : KeyPlanes{nullptr, nullptr};
     uint32_t *group_words = sc.group_words, *chunk_maxexp = sc.chunk_maxexp, *chunk_list = sc.chunk_list, *chunk_bits = sc.chunk_bits,
@@ -272,56 +353,54 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     const uint32_t slot_words = sc.slot_words;
     uint8_t* batch_max = sc.batch_max;
     uint8_t* o = static_cast<uint8_t*>(out);
-    int ticket = -1;
-    if (async) {
-        for (int i = 0; i < kMaxTickets && ticket < 0; ++i) if (!g_ticket[i].busy) ticket = i;
-        if (ticket < 0) return -LC_ERR_BADARG;                       // too many calls in flight
-        Ticket& tk = g_ticket[ticket];
-        if (!tk.done) {
-            if (hipEventCreateWithFlags(&tk.inputs, hipEventDisableTiming) != hipSuccess ||
-                hipEventCreateWithFlags(&tk.done, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); tk.inputs = tk.done = nullptr; return -LC_ERR_HIP; }
-        }
-        if (!ds->last && hipEventCreateWithFlags(&ds->last, hipEventDisableTiming) != hipSuccess) { (void)hipGetLastError(); ds->last = nullptr; return -LC_ERR_HIP; }
-    }
-    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
-    Result* result = async ? &g_pinned_dev->enc_async[ticket] : &g_pinned_dev->enc;
+    const int slot = take_slot(async);
+    if (slot < 0) return async ? -LC_ERR_BADARG : -LC_ERR_HIP;      // too many calls in flight
+    CallSlot& call = g_slot[slot];
+    struct Undo { int slot; bool armed; ~Undo() { if (armed) free_slot(slot); } } undo{slot, true};   // (the lock is still held on every early return)
+    Result* result = &g_pinned_dev[slot].enc;
     // Every call leaves the encode state cleared behind it; a fresh scratch area, or one whose last
     // call did not run to its end, is cleared first.
-    if (ds->clean != ws) { Timed t(kSlotReset, s); launch_reset(ws, group_words, chunk_maxexp, s); }
-    ds->clean = nullptr;
-    if (cache) {
-        { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, s); }
-        { Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s); }
+    if (!area->clean) { Timed t(kSlotReset, s); launch_reset(ws, group_words, chunk_maxexp, s); }
+    area->clean = false;
+    // (binary64 with a cache: two sweeps, the second one coding with the cached lengths when k_table confirms them)
+    const bool spec_sweep = cache && dtype != LC_F64;
+    if (cache) { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, dtype, s); }
+    if (spec_sweep) {
+        Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s);
     } else {
         Timed t(staged ? kSlotHistKeys : kSlotHist, s); launch_hist(w, w_ref, n, dtype, ws, chunk_maxexp, batch_max, keys, ds->tune, s);
     }
-    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, dtype, group_words, chunk_maxexp, cache ? nullptr : chunk_list, s); }
+    const bool listed = !spec_sweep;            // sweep 1 recorded the chunk maxima, so k_table can list the chunks to read
+    { Timed t(kSlotTable, s);    launch_table(ws, n, nbits, dtype, group_words, chunk_maxexp, listed ? chunk_list : nullptr, s); }
     if (staged) { Timed t(kSlotPackKeys, s); launch_pack_keys(w, w_ref, n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, keys, prov, slot_words, ds->tune, s); }
-    else { Timed t(kSlotPack, s); launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, cache ? nullptr : chunk_list, batch_max, prov, slot_words, ds->tune, s); }
-    if (async) LC_HIP(hipEventRecord(g_ticket[ticket].inputs, s));   // w and w_ref are not read past this point
+    else { Timed t(kSlotPack, s); launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, listed ? chunk_list : nullptr, batch_max, prov, slot_words, ds->tune, s); }
+    if (async) LC_HIP(hipEventRecord(call.inputs, s));   // w and w_ref are not read past this point
     { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
     { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, staged, s); }
     LC_HIP(hipGetLastError());
+    if (!release(area, s)) return -LC_ERR_HIP;
+    area->clean = true;              // whoever takes the area next is ordered behind this call
+    call.dev = (int)(ds - g_dev); call.w = (!cache && dtype == LC_F32) ? w : nullptr; call.n = n;
     if (async) {
-        LC_HIP(hipEventRecord(g_ticket[ticket].done, s));
-        LC_HIP(hipEventRecord(ds->last, s));
-        ds->pending = true;
-        ds->clean = ws;              // later calls are ordered after this one
-        Ticket& tk = g_ticket[ticket];
-        tk.busy = true;
-        tk.dev = (int)(ds - g_dev); tk.w = cache ? nullptr : w; tk.n = n;
-        return ticket;
+        LC_HIP(hipEventRecord(call.done, s));
+        undo.armed = false;
+        return slot;
     }
-    LC_HIP(hipStreamSynchronize(s));
-    ds->pending = false;             // this call was ordered after every asynchronous one
-    ds->clean = ws;
+    // Waiting happens outside the lock, so that calls of other host threads on other streams go on meanwhile; with the
+    // per-kernel timing switched on the calls stay one at a time (its events are shared).
+    const bool serial = g_prof;
+    if (!serial) lock.unlock();
+    const hipError_t waited = hipStreamSynchronize(s);
+    if (!serial) lock.lock();
+    if (waited != hipSuccess) { (void)hipGetLastError(); area->clean = false; return -LC_ERR_HIP; }
     const int slots[] = {cache ? kSlotSpecTable : staged ? kSlotHistKeys : kSlotHist, kSlotTable, staged ? kSlotPackKeys : kSlotPack,
-                         kSlotPlace, kSlotFinalize, kSlotSpecSweep};
+                         kSlotPlace, kSlotFinalize, spec_sweep ? kSlotSpecSweep : kSlotHist};
     collect(slots, cache ? 6 : 5);
-    if (!cache && dtype == LC_F32) note_outcome(ds, w, n, g_pinned->enc);
-    if (used) *used = (int)g_pinned->enc.used_cache;
-    if (g_pinned->enc.status != LC_OK) return -(lc_ssize)g_pinned->enc.status;
-    return (lc_ssize)g_pinned->enc.bytes;
+    const Result r = g_pinned[slot].enc;
+    if (call.w) note_outcome(ds, call.w, call.n, r);
+    if (used) *used = (int)r.used_cache;
+    if (r.status != LC_OK) return -(lc_ssize)r.status;
+    return (lc_ssize)r.bytes;
 }
 }  // namespace
 
@@ -397,8 +476,8 @@ int lc_encode_async(const float* w, const float* w_ref, uint64_t n, int nbits, v
 
 int lc_encode_release_inputs(int ticket, void* other_stream) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (ticket < 0 || ticket >= kMaxTickets || !g_ticket[ticket].busy) return LC_ERR_BADARG;
-    if (hipStreamWaitEvent(static_cast<hipStream_t>(other_stream), g_ticket[ticket].inputs, 0) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    if (ticket < 0 || ticket >= kCallSlots || !g_slot[ticket].busy || !g_slot[ticket].async) return LC_ERR_BADARG;
+    if (hipStreamWaitEvent(static_cast<hipStream_t>(other_stream), g_slot[ticket].inputs, 0) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
     return LC_OK;
 }
 
@@ -406,15 +485,16 @@ lc_ssize lc_encode_wait(int ticket, int* used) {
     hipEvent_t done;
     {
         std::lock_guard<std::mutex> lock(g_mu);
-        if (ticket < 0 || ticket >= kMaxTickets || !g_ticket[ticket].busy) return -LC_ERR_BADARG;
-        done = g_ticket[ticket].done;
+        if (ticket < 0 || ticket >= kCallSlots || !g_slot[ticket].busy || !g_slot[ticket].async) return -LC_ERR_BADARG;
+        done = g_slot[ticket].done;
     }
     const hipError_t e = hipEventSynchronize(done);          // not under the lock: other threads may keep calling
     std::lock_guard<std::mutex> lock(g_mu);
-    g_ticket[ticket].busy = false;
+    const CallSlot call = g_slot[ticket];
+    free_slot(ticket);
     if (e != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
-    const Result r = g_pinned->enc_async[ticket];
-    if (g_ticket[ticket].w) note_outcome(&g_dev[g_ticket[ticket].dev], g_ticket[ticket].w, g_ticket[ticket].n, r);
+    const Result r = g_pinned[ticket].enc;
+    if (call.w) note_outcome(&g_dev[call.dev], call.w, call.n, r);
     if (used) *used = (int)r.used_cache;
     if (r.status != LC_OK) return -(lc_ssize)r.status;
     return (lc_ssize)r.bytes;
@@ -441,26 +521,36 @@ lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t 
     if (blob_bytes < kHeaderBytes) return -LC_ERR_BAD_BLOB;
     if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
     if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
-    std::lock_guard<std::mutex> lock(g_mu);
-    int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
-    if (!ws) return -(lc_ssize)err;
+    std::unique_lock<std::mutex> lock(g_mu);
+    int err = 0;
+    DeviceState* ds = device_state(&err);
+    if (!ds) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    Area* area = acquire(ds, s, kWorkspaceFixed, &err);
+    if (!area) return -(lc_ssize)err;
+    Workspace* ws = static_cast<Workspace*>(area->mem);
+    const int slot = take_slot(false);
+    if (slot < 0) return -LC_ERR_HIP;
+    struct Undo { int slot; ~Undo() { free_slot(slot); } } undo{slot};     // (the lock is held on every return)
+    HostResult* host = &g_pinned_dev[slot];
     const uint8_t* b = static_cast<const uint8_t*>(blob);
     const uint64_t epoch = ++g_epoch;
-    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = b;
     const uint64_t bound = lc_encode_bound(n, 4), max_total = blob_bytes < bound ? blob_bytes : bound;
-    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, max_total, ws, epoch, g_pinned_dev, s); }
-    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, dtype, ws, epoch, g_pinned_dev, ds->tune, s); }
+    { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, max_total, ws, epoch, host, s); }
+    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, dtype, ws, 0, epoch, host, ds->tune, s); }
     LC_HIP(hipGetLastError());
-    LC_HIP(hipStreamSynchronize(s));
-    ds->pending = false;
+    if (!release(area, s)) return -LC_ERR_HIP;
+    const bool serial = g_prof;              // (see encode_impl)
+    if (!serial) lock.unlock();
+    const hipError_t waited = hipStreamSynchronize(s);
+    if (!serial) lock.lock();
+    if (waited != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
     const int slots[] = {kSlotDecCheck, kSlotDecode};
     collect(slots, 2);
-    if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
-    return (lc_ssize)g_pinned->bytes[0];
+    if ((g_pinned[slot].dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned[slot].dec_status & 0xFF);
+    return (lc_ssize)g_pinned[slot].bytes[0];
 }
 }  // namespace
 
@@ -492,43 +582,64 @@ lc_ssize lc_decode_many(const void* const* blobs, int count, float* w_ref, uint6
 
 lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint64_t n, int dtype, void* stream) {
     if (!blobs || count < 1 || count > LC_MAX_MANY || n > LC_MAX_N) return -LC_ERR_BADARG;
-    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
-    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : 2))) return -LC_ERR_BADARG;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
+    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
     for (int i = 0; i < count; ++i) if (!blobs[i] || misaligned(blobs[i], 16)) return -LC_ERR_BADARG;
+    // (a call of several phases: it keeps the lock, so that no other call's check moves into its area between them)
     std::lock_guard<std::mutex> lock(g_mu);
-    int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(kWorkspaceFixed, &err, &ds);
-    if (!ws) return -(lc_ssize)err;
+    int err = 0;
+    DeviceState* ds = device_state(&err);
+    if (!ds) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    Area* area = acquire(ds, s, kWorkspaceFixed, &err);
+    if (!area) return -(lc_ssize)err;
+    Workspace* ws = static_cast<Workspace*>(area->mem);
+    const int slot = take_slot(false);
+    if (slot < 0) return -LC_ERR_HIP;
+    struct Undo { int slot; ~Undo() { free_slot(slot); } } undo{slot};
+    HostResult* host = &g_pinned_dev[slot];
+    const HostResult& got = g_pinned[slot];
     const uint64_t epoch = ++g_epoch, bound = lc_encode_bound(n, 4);
-    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
     BlobList list;
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[t < count ? t : 0]);
     // every blob is validated (one launch, one grid row per blob) before w_ref is touched
-    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, dtype, bound, ws, epoch, g_pinned_dev, s); }
+    { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, dtype, bound, ws, epoch, host, s); }
     LC_HIP(hipGetLastError());
+    if (!release(area, s)) return -LC_ERR_HIP;
     LC_HIP(hipStreamSynchronize(s));
-    ds->pending = false;
-    if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
+    if ((got.dec_status >> 8) == epoch) return -(lc_ssize)(got.dec_status & 0xFF);
     uint64_t total = 0;
-    for (int i = 0; i < count; ++i) total += g_pinned->bytes[i];
+    for (int i = 0; i < count; ++i) total += got.bytes[i];
+    if (dtype == LC_F64) {
+        // binary64 parameters: the blobs one after the other (one read and one write of w_ref per blob), each sweep
+        // with the tables the check left for its blob
+        for (int i = 0; i < count; ++i) {
+            Timed tm(kSlotDecode, s);
+            launch_decode(list.p[i], w_ref, n, dtype, ws, i, epoch, host, ds->tune, s);
+        }
+        LC_HIP(hipGetLastError());
+        if (!release(area, s)) return -LC_ERR_HIP;
+        LC_HIP(hipStreamSynchronize(s));
+        if ((got.dec_status >> 8) == epoch) return -(lc_ssize)(got.dec_status & 0xFF);
+        return (lc_ssize)total;
+    }
     // Sweeps of up to kMaxMany blobs through the fused kernel.  Its LDS payload area is sized to 1.1 x the blobs'
     // average chunk payloads (a chunk above that still decodes, from memory), and a sweep takes only as many
     // blobs as leave room for fused_min_waves_per_cu wavefronts per compute unit.  Blobs with codes longer than
     // the first decode table (7 bits) are grouped apart from those without: they take the kernel's LONG form.
-    const uint64_t nchunks = num_chunks_of(n), area = chunk_area_of(nchunks);
+    const uint64_t nchunks = num_chunks_of(n), area_at = chunk_area_of(nchunks);
     const size_t lds_budget = kLdsPerCu / (size_t)ds->tune.fused_min_waves_per_cu;
     auto pay_words_of = [](double words) {
         uint32_t w = ((uint32_t)(words * 1.1) + 63u) & ~63u;
         return w < kFusedMinWords ? kFusedMinWords : w;
     };
     for (int g0 = 0; g0 < count;) {
-        const bool short_codes = g_pinned->max_len[g0] <= kDecLut1Bits;
+        const bool short_codes = got.max_len[g0] <= kDecLut1Bits;
         int T = 0;
         double words = 0;
-        while (g0 + T < count && T < kMaxMany && (g_pinned->max_len[g0 + T] <= kDecLut1Bits) == short_codes) {
+        while (g0 + T < count && T < kMaxMany && (got.max_len[g0 + T] <= kDecLut1Bits) == short_codes) {
             if (nchunks) {
-                const double avg = (double)(g_pinned->bytes[g0 + T] - area) / 4.0 / (double)nchunks - kLaneBitsWords + 6.0;
+                const double avg = (double)(got.bytes[g0 + T] - area_at) / 4.0 / (double)nchunks - kLaneBitsWords + 6.0;
                 if (T > 0 && fused_lds_bytes(T + 1, pay_words_of(words + avg)) > lds_budget) break;
                 words += avg;
             }
@@ -537,15 +648,16 @@ lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint
         {
             const uint32_t pay_words = pay_words_of(words);
             Timed tm(kSlotDecodeFused, s);
-            launch_decode_fused(list, g0, T, w_ref, n, dtype, ws, epoch, g_pinned_dev, pay_words, !short_codes, ds->tune, s);
+            launch_decode_fused(list, g0, T, w_ref, n, dtype, ws, epoch, host, pay_words, !short_codes, ds->tune, s);
         }
         LC_HIP(hipGetLastError());
         g0 += T;
     }
+    if (!release(area, s)) return -LC_ERR_HIP;
     LC_HIP(hipStreamSynchronize(s));
     int slots[2] = {kSlotDecCheck, kSlotDecodeFused};
     collect(slots, 2);
-    if ((g_pinned->dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned->dec_status & 0xFF);
+    if ((got.dec_status >> 8) == epoch) return -(lc_ssize)(got.dec_status & 0xFF);
     return (lc_ssize)total;
 }
 
@@ -583,22 +695,35 @@ lc_ssize lc_decode_batch(const void* const* blobs, float* const* w_ref, const ui
 lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const uint64_t* n, int count, int64_t* sizes,
                            int dtype, void* stream) {
     if (!blobs || !w_ref || !n || count < 1 || count > kMaxBatch) return -LC_ERR_BADARG;
-    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
-    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
+    const uintptr_t esize = dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2;
     for (int t = 0; t < count; ++t) {
         if (n[t] > LC_MAX_N || !blobs[t] || misaligned(blobs[t], 16)) return -LC_ERR_BADARG;
         if (n[t] && (!w_ref[t] || misaligned(w_ref[t], esize))) return -LC_ERR_BADARG;
+    }
+    if (dtype == LC_F64) {
+        // binary64 tensors: one lc_decode_t after the other (its kernels are not among the batched ones); a tensor
+        // whose blob fails is left untouched and reported, the others are restored
+        lc_ssize total = 0; int first_err = 0;
+        for (int t = 0; t < count; ++t) {
+            const lc_ssize r = decode_impl(blobs[t], SIZE_MAX, w_ref[t], n[t], dtype, stream);
+            if (sizes) sizes[t] = r;
+            if (r < 0) { if (!first_err) first_err = (int)-r; } else total += r;
+        }
+        return first_err ? -(lc_ssize)first_err : total;
     }
     uint64_t chunks64 = 0;
     const size_t need = batch_decode_bytes(n, count, &chunks64);
     if (chunks64 > 0xFFFFFFFFull) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(need, &err, &ds);
-    if (!ws) return -(lc_ssize)err;
-    if (!batch_host()) return -LC_ERR_HIP;
+    int err = 0;
+    DeviceState* ds = device_state(&err);
+    if (!ds) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
+    Area* area = acquire(ds, s, need, &err);
+    if (!area) return -(lc_ssize)err;
+    Workspace* ws = static_cast<Workspace*>(area->mem);
+    if (!batch_host()) return -LC_ERR_HIP;
     auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
     uint8_t* base = reinterpret_cast<uint8_t*>(ws) + kWorkspaceHead;
     BatchDecArgs a;
@@ -619,8 +744,8 @@ lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const u
     LC_HIP(hipMemcpyAsync(a.segs, g_batch->dsegs, (size_t)count * sizeof(SegD), hipMemcpyHostToDevice, s));
     launch_batch_decode(a, ds->tune, s);
     LC_HIP(hipGetLastError());
+    if (!release(area, s)) return -LC_ERR_HIP;
     LC_HIP(hipStreamSynchronize(s));
-    ds->pending = false;
     lc_ssize total = 0; int first_err = 0;
     for (int t = 0; t < count; ++t) {
         const Result& r = g_batch->results[t];
@@ -655,21 +780,33 @@ lc_ssize lc_encode_batch(const float* const* w, const float* const* w_ref, const
 lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const uint64_t* n, int count, int nbits,
                            void* const* out, int64_t* sizes, int dtype, void* stream) {
     if (!w || !w_ref || !n || !out || count < 1 || count > kMaxBatch || nbits < 1 || nbits > 4) return -LC_ERR_BADARG;
-    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16) return -LC_ERR_BADARG;
-    const uintptr_t esize = dtype == LC_F32 ? 4 : 2;
+    if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
+    const uintptr_t esize = dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2;
     for (int t = 0; t < count; ++t) {
         if (n[t] > LC_MAX_N || !out[t] || misaligned(out[t], 16)) return -LC_ERR_BADARG;
         if (n[t] && (!w[t] || !w_ref[t] || misaligned(w[t], esize) || misaligned(w_ref[t], esize))) return -LC_ERR_BADARG;
     }
+    if (dtype == LC_F64) {
+        // binary64 tensors: one lc_encode_t after the other (its kernels are not among the batched ones)
+        lc_ssize total = 0; int first_err = 0;
+        for (int t = 0; t < count; ++t) {
+            const lc_ssize r = encode_impl(w[t], w_ref[t], n[t], nbits, out[t], dtype, nullptr, nullptr, stream, false);
+            if (sizes) sizes[t] = r;
+            if (r < 0) { if (!first_err) first_err = (int)-r; } else total += r;
+        }
+        return first_err ? -(lc_ssize)first_err : total;
+    }
     const size_t need = lc_batch_workspace_bytes(n, count, nbits);
     if (!need) return -LC_ERR_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    int err = 0; DeviceState* ds = nullptr;
-    Workspace* ws = get_workspace(need, &err, &ds);
-    if (!ws) return -(lc_ssize)err;
-    if (!batch_host()) return -LC_ERR_HIP;
+    int err = 0;
+    DeviceState* ds = device_state(&err);
+    if (!ds) return -(lc_ssize)err;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (!order_after_async(ds, s)) return -LC_ERR_HIP;
+    Area* area = acquire(ds, s, need, &err);
+    if (!area) return -(lc_ssize)err;
+    Workspace* ws = static_cast<Workspace*>(area->mem);
+    if (!batch_host()) return -LC_ERR_HIP;
     // carve the scratch behind the single-vector head (which this call leaves alone)
     auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
     uint8_t* base = reinterpret_cast<uint8_t*>(ws) + kWorkspaceHead;
@@ -695,8 +832,8 @@ lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const
     LC_HIP(hipMemcpyAsync(a.segs, g_batch->segs, (size_t)count * sizeof(Seg), hipMemcpyHostToDevice, s));
     launch_batch_encode(a, ds->tune, s);
     LC_HIP(hipGetLastError());
+    if (!release(area, s)) return -LC_ERR_HIP;
     LC_HIP(hipStreamSynchronize(s));
-    ds->pending = false;
     lc_ssize total = 0; int first_err = 0;
     for (int t = 0; t < count; ++t) {
         const Result& r = g_batch->results[t];
@@ -746,24 +883,27 @@ void lc_shutdown(void) {
     int cur = 0;
     const bool have_cur = hipGetDevice(&cur) == hipSuccess;
     for (int d = 0; d < kMaxDevices; ++d) {
-        if (g_dev[d].owned) {
-            if (hipSetDevice(d) == hipSuccess) { (void)hipDeviceSynchronize(); (void)hipFree(g_dev[d].owned); }
-            g_dev[d].owned = nullptr; g_dev[d].owned_bytes = 0;
+        bool any = false;
+        for (int i = 0; i < kMaxAreas; ++i) any = any || g_dev[d].area[i].mem || g_dev[d].area[i].idle;
+        if (any && hipSetDevice(d) == hipSuccess) {
+            (void)hipDeviceSynchronize();
+            for (int i = 0; i < kMaxAreas; ++i) {
+                Area& a = g_dev[d].area[i];
+                if (a.mem && !a.user) (void)hipFree(a.mem);
+                if (a.idle) (void)hipEventDestroy(a.idle);
+            }
         }
+        for (int i = 0; i < kMaxAreas; ++i) g_dev[d].area[i] = Area();
         g_dev[d].user = nullptr; g_dev[d].user_bytes = 0;
     }
     if (have_cur) (void)hipSetDevice(cur);
-    for (int i = 0; i < kMaxTickets; ++i) {
-        if (g_ticket[i].done) { (void)hipEventDestroy(g_ticket[i].inputs); (void)hipEventDestroy(g_ticket[i].done); }
-        g_ticket[i] = Ticket();
+    for (int i = 0; i < kCallSlots; ++i) {
+        if (g_slot[i].done) { (void)hipEventDestroy(g_slot[i].inputs); (void)hipEventDestroy(g_slot[i].done); }
+        g_slot[i] = CallSlot();
     }
-    for (int d = 0; d < kMaxDevices; ++d) {
-        if (g_dev[d].last) { (void)hipEventDestroy(g_dev[d].last); g_dev[d].last = nullptr; }
-        g_dev[d].pending = false;
-    }
+    g_async_in_flight = 0;
     if (g_pinned) { (void)hipHostFree(g_pinned); g_pinned = nullptr; g_pinned_dev = nullptr; }
     if (g_batch) { (void)hipHostFree(g_batch); g_batch = nullptr; g_batch_dev = nullptr; }
-    for (int d = 0; d < kMaxDevices; ++d) g_dev[d].clean = nullptr;
     if (g_ev_made) {
         for (int i = 0; i < kNumSlots; ++i) { (void)hipEventDestroy(g_ev[i][0]); (void)hipEventDestroy(g_ev[i][1]); }
         g_ev_made = false; g_prof = false;

@@ -474,13 +474,13 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
 template <int DT>
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                                 Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host,
-                                                u32 pay_words) {
+                                                u32 pay_words, u32 set) {
     __shared__ DecLds L;
     extern __shared__ uint4 dec_pay[];                   // 4 areas of pay_words + 4 payload words, one per wavefront
     // What the check kernel left (the verdict and the blob's tables) is fetched in one go: a failed check leaves
     // tables that mean nothing, but reading them is harmless.  If it found something, nothing else is touched.
     const u32 t = threadIdx.x;
-    const DecSet& D = ws->dec_set[0];
+    const DecSet& D = ws->dec_set[set];
     const u64 verdict = __hip_atomic_load(&ws->dec_status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     u32 M = D.info.max_len, K = D.info.K;
     u64 area = D.info.area;
@@ -1052,7 +1052,7 @@ void launch_decode_fused(const BlobList& blobs, int first, int count, void* w_re
     }
 }
 
-void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch, HostResult* host,
+void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, int set, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
@@ -1072,10 +1072,10 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
         if (pay_words < kPayWords) pay_words = kPayWords;
     }
     const size_t lds = 4 * (size_t)(pay_words / 4 + 1) * sizeof(uint4);
-    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
-    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
-    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
-    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words);
+    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
+    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
+    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
+    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
 }
 
 }  // namespace lc

@@ -507,11 +507,14 @@ __global__ __launch_bounds__(1024) void k_table(EncState* ws, Ext64* ext, u64 n,
 // ----------------------------------------------------------------------------- k_spec_table
 // lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
 // priority order, lengths forming a complete prefix code) into the table the sweep codes with.
-__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCache* cache, int nbits) {
-    __shared__ u32 s_ok, s_len[kMaxSym + 1], s_sym[512];
+template <int EB>                         // EB: exponent bits of the parameters' delta (8, or 11 for binary64)
+__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, Ext64* ext, const TableCache* cache, int nbits) {
+    constexpr u32 kBuckets = 2u << EB, kEmax = (1u << EB) - 1;
+    __shared__ u32 s_ok, s_len[kMaxSym + 1];
+    __shared__ uint8_t s_sym[kBuckets];
     const u32 lane = threadIdx.x;
     Table& T = ws->table;
-    for (u32 b = lane; b < 512; b += kW) s_sym[b] = 0xFF;
+    for (u32 b = lane; b < kBuckets; b += kW) s_sym[b] = 0xFF;
     __syncthreads();
     if (lane == 0) {
         const u32 kmax = (1u << nbits) - 1, K = cache->K;
@@ -522,9 +525,9 @@ __global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCach
         if (ok) {
             u32 prev_key = 0xFFFFFFFFu;
             for (u32 j = 0; j < K; ++j) {
-                const u32 b = cache->kept[j], e = b & 255;
-                const u32 key = (e << 1) | (1u - ((b >> 8) & 1u));     // larger exponent first, + before -
-                if (b >= 512 || e == 0 || e == 255 || key >= prev_key) { ok = false; break; }
+                const u32 b = cache->kept[j], e = b & kEmax;
+                const u32 key = (e << 1) | (1u - ((b >> EB) & 1u));    // larger exponent first, + before -
+                if (b >= kBuckets || e == 0 || e == kEmax || key >= prev_key) { ok = false; break; }
                 prev_key = key;
             }
             for (u32 j = 0; j <= K && ok; ++j) {
@@ -547,7 +550,7 @@ __global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCach
                 if (j < K) s_sym[cache->kept[j]] = j;
             }
             T.K = K; T.max_len = max_len; T.k_E = 0; T.status = 0;
-            T.min_kept_exp = K ? (cache->kept[K - 1] & 255u) : 256u;
+            T.min_kept_exp = K ? (cache->kept[K - 1] & kEmax) : kEmax + 1;
         }
         s_ok = ok;
         ws->spec = ok; ws->spec_ok = 0;
@@ -555,9 +558,10 @@ __global__ __launch_bounds__(64) void k_spec_table(EncState* ws, const TableCach
     __syncthreads();
     if (s_ok) {
         const u32 K = cache->K;
-        for (u32 b = lane; b < 512; b += kW) {
+        uint8_t* symlen_of_bucket = EB == 8 ? T.symlen_of_bucket : ext->symlen_of_bucket;
+        for (u32 b = lane; b < kBuckets; b += kW) {
             const u32 sy = s_sym[b] == 0xFF ? K : s_sym[b];
-            T.symlen_of_bucket[b] = (uint8_t)(sy | (s_len[sy] << 4));
+            symlen_of_bucket[b] = (uint8_t)(sy | (s_len[sy] << 4));
         }
     }
 }
@@ -1642,8 +1646,9 @@ static u32 even_waves(u64 nchunks, u64 cap) {
     return (u32)((nchunks + turns - 1) / turns);
 }
 
-void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s) {
-    hipLaunchKernelGGL(k_spec_table, dim3(1), dim3(64), 0, s, ws, cache, nbits);
+void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, int dtype, hipStream_t s) {
+    if (dtype == kF64) hipLaunchKernelGGL(k_spec_table<11>, dim3(1), dim3(64), 0, s, ws, &ws->ext64, cache, nbits);
+    else hipLaunchKernelGGL(k_spec_table<8>, dim3(1), dim3(64), 0, s, ws, (Ext64*)nullptr, cache, nbits);
 }
 
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,

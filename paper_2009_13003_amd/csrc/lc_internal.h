@@ -68,11 +68,10 @@ struct TableCache {
     uint32_t len[kMaxSym];
 };
 
-// Lives in mapped, pinned host memory: kernels write the outcome of a call here with plain
-// stores, and the host reads it after waiting for the stream.
+// Lives in mapped, pinned host memory, one per call in progress: kernels write the outcome of the call here with
+// plain stores, and the host reads it after waiting for the stream.
 struct HostResult {
-    Result enc;                                  // lc_encode: blob bytes, lc_status
-    Result enc_async[16];                        // lc_encode_async: one per ticket
+    Result enc;                                  // encode calls: blob bytes, lc_status, ...
     unsigned long long dec_status;               // lc_decode*: (epoch << 8) | lc_status of the worst finding
     unsigned long long bytes[kMaxSets];          // lc_decode*: total_bytes of each blob
     uint32_t max_len[kMaxSets];                  // lc_decode*: longest code of each blob
@@ -168,7 +167,7 @@ void launch_pack_keys(const void* w, const void* w_ref, uint64_t n, Workspace* w
                       const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
                   uint32_t* chunk_list, hipStream_t s);
-void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, hipStream_t s);
+void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, int dtype, hipStream_t s);
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
@@ -213,7 +212,8 @@ struct BlobList { const uint8_t* p[kMaxSets]; };
 // Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
                       uint64_t epoch, HostResult* host, hipStream_t s);
-void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, uint64_t epoch, HostResult* host,
+// (set: which of the workspace's decode sets the check kernel filled for this blob)
+void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, int set, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s);
 // Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused
 // kernel requires every code of these blobs to be at most kDecLut1Bits long.

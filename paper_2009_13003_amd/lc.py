@@ -17,6 +17,7 @@ _lib = ctypes.CDLL(_PATH)
 
 OK, ERR_BADARG, ERR_NONFINITE, ERR_OUT_TOO_SMALL, ERR_BAD_BLOB, ERR_HIP, ERR_WORKSPACE = range(7)
 MAX_N = 1 << 32
+MAX_TICKETS = 32
 MAX_MANY = 64
 CHUNK = 16384
 

@@ -550,7 +550,7 @@ def test_cached_encode_chain_matches_oracle(lc, nbits, n):
 @pytest.mark.parametrize("tdt", [torch.bfloat16, torch.float16])
 def test_cached_and_async_encode_of_16_bit_parameters(lc, tdt):
     """lc_encode_cached_t / lc_encode_async_t: a chain of bf16 / fp16 checkpoints, blob, verdict and cache as the
-    oracle's at every step, hits and a miss both occur; the asynchronous form gives the same blobs; fp64 is refused."""
+    oracle's at every step, hits and a miss both occur; the asynchronous form gives the same blobs."""
     code = orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16
     nbits, n = 3, 7 * 16384 + 321
     g = torch.Generator(device=DEV); g.manual_seed(321)
@@ -583,13 +583,6 @@ def test_cached_and_async_encode_of_16_bit_parameters(lc, tdt):
     ticket = lc.lc_encode_async_t(w, tracked, nbits, out2)                    # without a cache: lc_encode_t's blob
     size2, used2 = lc.lc_encode_wait(ticket)
     assert not used2 and size2 == lc.lc_encode_t(w, tracked, nbits, out) and torch.equal(out2[:size2], out[:size2])
-    w64 = w.double()
-    with pytest.raises(lc.LcError) as e:
-        lc.lc_encode_cached_t(w64, w64.clone(), nbits, out, cache_gpu)
-    assert e.value.status == lc.ERR_BADARG
-    with pytest.raises(lc.LcError) as e:
-        lc.lc_encode_async_t(w64, w64.clone(), nbits, out)
-    assert e.value.status == lc.ERR_BADARG
 
 
 def test_cached_encode_edge_cases(lc):
@@ -729,7 +722,7 @@ def test_async_encode_many_in_flight_and_mixed_with_other_calls(lc):
     with pytest.raises(lc.LcError) as e:
         lc.lc_encode_release_inputs(99)
     assert e.value.status == lc.ERR_BADARG
-    held = [lc.lc_encode_async(w, r, nbits, outs[3]) for _ in range(16)]
+    held = [lc.lc_encode_async(w, r, nbits, outs[3]) for _ in range(lc.MAX_TICKETS)]
     with pytest.raises(lc.LcError) as e:
         lc.lc_encode_async(w, r, nbits, outs[3])
     assert e.value.status == lc.ERR_BADARG
@@ -1417,11 +1410,6 @@ def test_batched_encode_and_restore_of_16_bit_tensors(lc, tdt):
     assert torch.equal(recs[0].view(torch.int16), refs[0].view(torch.int16))
     ref_h = raw16(refs[4]); orc.decode_t(outs[4][:sizes[4]].cpu().numpy(), ref_h, code)
     assert np.array_equal(raw16(recs[1]).view(np.uint16), ref_h.view(np.uint16))
-    # binary64 tensors are refused
-    w64 = ws[0].double()
-    with pytest.raises(lc.LcError) as e:
-        lc.lc_encode_batch_t([w64], [w64.clone()], nbits, [outs[0]])
-    assert e.value.status == lc.ERR_BADARG
 
 
 def test_seeded_mixtures_of_loud_and_quiet_chunks_all_types(lc):
@@ -1692,3 +1680,116 @@ def test_staged_keys_follow_the_vectors_last_encode(lc):
         lc.lc_set_option(lc.OPT_KEY_STAGING, 3)
     with pytest.raises(lc.LcError):
         lc.lc_set_option(7, 0)
+
+
+# ---------------------------------------------------------------- binary64 parameters through the other entry points
+def test_fp64_cached_async_many_and_batch(lc):
+    """The cached, asynchronous, several-blob and batched calls on binary64 parameters (Section 3.1.1, footnote on the
+    bucket count): a chain of checkpoints through lc_encode_cached_t with blob, verdict and cache as the oracle's (hits
+    and a miss), the asynchronous form with and without a cache, the restore from all blobs in one lc_decode_many_t call
+    against the oracle's successive restores, and lists of tensors through lc_encode_batch_t / lc_decode_batch_t."""
+    nbits, n = 3, 6 * 16384 + 321
+    g = torch.Generator(device=DEV); g.manual_seed(640)
+    w = 0.05 * torch.randn(n, generator=g, device=DEV, dtype=torch.float64)
+    w0 = w.clone()
+    tracked = w.clone()
+    out, out2 = lc.alloc_out(n, nbits, DEV), lc.alloc_out(n, nbits, DEV)
+    cache_gpu, cache_cpu, cache_async = lc.new_cache(DEV), orc.new_cache(), lc.new_cache(DEV)
+    verdicts, blobs = [], []
+    tracked_h = tracked.cpu().numpy()
+    for t in range(6):
+        d = 2e-3 * torch.randn(n, generator=g, device=DEV, dtype=torch.float64)
+        d[:4] = torch.tensor([0.02, -0.02, 0.011, -0.011], device=DEV, dtype=torch.float64)
+        if t == 4:
+            d[9] = 0.4                                                        # a new largest exponent: miss
+        w = w + d
+        size, used = lc.lc_encode_cached_t(w, tracked, nbits, out, cache_gpu)
+        blob_cpu, used_cpu = orc.encode_cached64(w.cpu().numpy(), tracked_h, nbits, cache_cpu)
+        blob_gpu = out[:size].cpu().numpy()
+        assert used == used_cpu, t
+        assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+        assert np.array_equal(cache_gpu.cpu().numpy()[:4 * orc.CACHE_WORDS].view(np.uint32), cache_cpu)
+        verdicts.append(used)
+        ticket = lc.lc_encode_async_t(w, tracked, nbits, out2, cache_async)
+        size2, used2 = lc.lc_encode_wait(ticket)
+        assert size2 == size and used2 == used and torch.equal(out2[:size2], out[:size])
+        ticket = lc.lc_encode_async_t(w, tracked, nbits, out2)              # without a cache: lc_encode_t's blob
+        size2, used2 = lc.lc_encode_wait(ticket)
+        assert not used2 and np.array_equal(out2[:size2].cpu().numpy(), orc.encode64(w.cpu().numpy(), tracked_h, nbits))
+        blobs.append(out[:size].clone())
+        orc.decode64(blob_cpu, tracked_h)
+        assert lc.lc_decode_t(out, tracked) == size
+        assert np.array_equal(bits64(tracked.cpu().numpy()), bits64(tracked_h))
+    assert verdicts[0] is False and verdicts[4] is False and any(verdicts[1:4]), verdicts
+    # restore from u_0 and all blobs in one call
+    rec = w0.clone()
+    assert lc.lc_decode_many_t(blobs, rec) == sum(b.numel() for b in blobs)
+    assert np.array_equal(bits64(rec.cpu().numpy()), bits64(tracked_h))
+    # a damaged blob anywhere in the list leaves the parameters alone
+    bad = [b.clone() for b in blobs]
+    bad[3][66] ^= 0x01                                                         # a code length: the lengths stop being a prefix code
+    rec = w0.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many_t(bad, rec)
+    assert e.value.status == lc.ERR_BAD_BLOB and torch.equal(rec, w0)
+    # lists of tensors
+    sizes_n = [5 * 16384 + 3, 100, 0, 16384, 2 * 16384 + 999]
+    ws, refs = [], []
+    for k, m in enumerate(sizes_n):
+        r = 0.05 * torch.randn(m, generator=g, device=DEV, dtype=torch.float64)
+        ws.append(r + 10.0 ** -(2 + k) * torch.randn(m, generator=g, device=DEV, dtype=torch.float64)); refs.append(r)
+    outs = [lc.alloc_out(m, 4, DEV) for m in sizes_n]
+    got = lc.lc_encode_batch_t(ws, refs, 4, outs)
+    expect = [orc.encode64(a.cpu().numpy(), b.cpu().numpy(), 4) for a, b in zip(ws, refs)]
+    assert got == [e.size for e in expect]
+    for o, e in zip(outs, expect):
+        assert np.array_equal(o[:e.size].cpu().numpy(), e)
+    recs = [r.clone() for r in refs]
+    outs[1][80] ^= 0x01                                                       # tensor 1's blob is damaged: reported, left alone
+    used = lc.lc_decode_batch_t(outs, recs)
+    assert used == [e.size if k != 1 else -lc.ERR_BAD_BLOB for k, e in enumerate(expect)]
+    for k, (rec, r, e) in enumerate(zip(recs, refs, expect)):
+        ref_h = r.cpu().numpy()
+        if k != 1:
+            orc.decode64(e, ref_h)
+        assert np.array_equal(bits64(rec.cpu().numpy()), bits64(ref_h)), k
+
+
+# ---------------------------------------------------------------- calls on different streams run side by side
+def test_encodes_on_different_streams_have_their_own_scratch(lc):
+    """Section 3.2, asynchronous execution in a trainer with many tensors: asynchronous encodes issued on several
+    streams at once (more streams than the library keeps scratch areas, so some share), slices of one vector enqueued
+    on one stream and waited for once, with restores and synchronous encodes on yet other streams between them: every
+    blob is the oracle's."""
+    nbits = 4
+    cases = [laplace_case(16384 * (3 + 5 * k) + 11 * k, seed=700 + k, scale=10.0 ** -(2 + k % 3)) for k in range(12)]
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w, _ in cases]
+    streams = [torch.cuda.Stream() for _ in range(10)]
+    expect = [orc.encode(w.cpu().numpy(), r.cpu().numpy(), nbits) for w, r in cases]
+    torch.cuda.synchronize()
+    for rnd in range(3):
+        for o in outs:
+            o.zero_()
+        torch.cuda.synchronize()
+        tickets = [lc.lc_encode_async(w, r, nbits, o, stream=streams[(i + rnd) % len(streams)])
+                   for i, ((w, r), o) in enumerate(zip(cases, outs))]
+        # a restore and a synchronous encode on the default stream while those are in flight
+        w0, r0 = cases[0]
+        rec = r0.clone()
+        tmp = lc.alloc_out(w0.numel(), nbits, DEV)
+        size0 = lc.lc_encode(w0, r0, nbits, tmp)
+        assert lc.lc_decode(tmp, rec) == size0 == expect[0].size
+        for t, o, e in zip(tickets, outs, expect):
+            size, _ = lc.lc_encode_wait(t)
+            assert size == e.size and np.array_equal(o[:size].cpu().numpy(), e)
+    # the slices of one vector on one stream, one wait at the end (the tickets are collected afterwards)
+    w, r = laplace_case(8 * 65536 + 777, seed=720)
+    cuts = list(range(0, w.numel(), 65536)) + [w.numel()]
+    souts = [lc.alloc_out(b - a, nbits, DEV) for a, b in zip(cuts[:-1], cuts[1:])]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    tickets = [lc.lc_encode_async(w[a:b], r[a:b], nbits, o, stream=s) for (a, b), o in zip(zip(cuts[:-1], cuts[1:]), souts)]
+    s.synchronize()
+    for t, (a, b), o in zip(tickets, zip(cuts[:-1], cuts[1:]), souts):
+        size, _ = lc.lc_encode_wait(t)
+        assert np.array_equal(o[:size].cpu().numpy(), orc.encode(w[a:b].cpu().numpy(), r[a:b].cpu().numpy(), nbits))

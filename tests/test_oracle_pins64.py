@@ -216,3 +216,76 @@ def test_accounting64_uses_64_bit_bucket_values():
     k = h["k_E"]
     assert k == 6 and a["bits_E"] == n * 3 + 64 * k == orc.size_exponent_only(n, k, 64)
     assert a["bits_EP"] == n * 2 + 64 * 4
+
+
+# ---------------------------------------------------------------- code table caching (Section 3.2), binary64
+def test_cached_encode64_follows_the_binary32_rule():
+    """lco_encode_cached64 against what pins lco_encode_cached: the first call is the plain blob and fills the cache
+    with its 12-bit bucket ids and lengths; a second checkpoint with the same buckets carries the cached lengths (the
+    plain blob's symbols, counts and representatives; payload = sum of count x cached length); a new largest
+    exponent, another nbits, a payload above n * nbits bits and a cache made by a binary32 encode are misses."""
+    from tests import lcb1_reader
+    rng = np.random.RandomState(64)
+    n, nbits = 3 * lcb1_reader.C + 77, 3
+    w0 = 0.05 * rng.randn(n)
+    d1 = 1e-3 * rng.laplace(size=n); d2 = 0.8e-3 * rng.laplace(size=n)
+    for d in (d1, d2):
+        d[:4] = [0.02, -0.02, 0.011, -0.011]
+    cache = orc.new_cache()
+    w1 = w0 + d1
+    b1, u1 = orc.encode_cached64(w1, w0, nbits, cache)
+    assert not u1 and np.array_equal(b1, orc.encode64(w1, w0, nbits))
+    h1 = lcb1_reader.parse_header(b1)
+    assert cache[0] == 1 and cache[1] == nbits and cache[2] == h1["K"]
+    assert [int(x) for x in cache[4:4 + h1["K"]]] == [s["bucket"] for s in h1["slots"][:h1["K"]]]
+    assert all(int(x) >= 512 or (int(x) >> 11) == 0 for x in cache[4:4 + h1["K"]])       # 12-bit ids: sign << 11 | exponent
+    ref = w0.copy(); orc.decode64(b1, ref)
+    w2 = w1 + d2
+    stale = cache.copy()
+    c2, u2 = orc.encode_cached64(w2, ref, nbits, cache)
+    p2 = orc.encode64(w2, ref, nbits)
+    assert u2 and c2.size >= p2.size
+    hp, hc = lcb1_reader.parse_header(p2), lcb1_reader.parse_header(c2)
+    K = hp["K"]
+    for j in range(K + 1):
+        assert hc["slots"][j]["bucket"] == hp["slots"][j]["bucket"] and hc["slots"][j]["cnt"] == hp["slots"][j]["cnt"]
+        assert hc["slots"][j]["rep_bits"] == hp["slots"][j]["rep_bits"]
+        assert hc["slots"][j]["len"] == int(stale[20 + j])
+    assert c2[320:384].tobytes() == p2[320:384].tobytes()                                 # high halves of the representatives
+    bits_expected = sum(hc["slots"][j]["cnt"] * int(stale[20 + j]) for j in range(K + 1))
+    area = 512 + (4 * (hc["num_chunks"] + 1) + 15) // 16 * 16
+    lane_bits = 0
+    off = np.frombuffer(c2[512:512 + 4 * (hc["num_chunks"] + 1)].tobytes(), "<u4")
+    for c in range(hc["num_chunks"]):
+        lane_bits += int(np.frombuffer(c2[area + 4 * int(off[c]):area + 4 * int(off[c]) + 128].tobytes(), "<u2").sum())
+    assert lane_bits == bits_expected
+    a, b = ref.copy(), ref.copy()
+    orc.decode64(p2, a); orc.decode64(c2, b)
+    assert np.array_equal(a.view(np.uint64), b.view(np.uint64))
+    # misses
+    d3 = d2.copy(); d3[9] = 0.3
+    c = stale.copy()
+    blob, used = orc.encode_cached64(w1 + d3, ref, nbits, c)
+    assert not used and np.array_equal(blob, orc.encode64(w1 + d3, ref, nbits))
+    c = stale.copy()
+    blob, used = orc.encode_cached64(w2, ref, 2, c)
+    assert not used and np.array_equal(blob, orc.encode64(w2, ref, 2))
+    c32 = orc.new_cache()
+    orc.encode_cached(w2.astype(np.float32), ref.astype(np.float32), nbits, c32)
+    blob, used = orc.encode_cached64(w2, ref, nbits, c32)
+    assert not used and np.array_equal(blob, p2)
+    # a stale table that would outgrow the bound: reversed populations
+    m = 65536
+    mags = [2.0 ** -e for e in range(1, 8)]
+    skew = [m >> (j + 1) for j in range(7)]; skew.append(m - sum(skew))
+    def by_symbol(counts, seed):
+        d = np.concatenate([np.full(c_, v) for c_, v in zip(counts[:-1], mags)] + [np.zeros(counts[-1])])
+        np.random.RandomState(seed).shuffle(d)
+        return d
+    zero = np.zeros(m)
+    c = orc.new_cache()
+    orc.encode_cached64(by_symbol(skew, 0), zero, 3, c)
+    assert [int(x) for x in c[20:28]] == [1, 2, 3, 4, 5, 6, 7, 7]
+    d_rev = by_symbol(skew[::-1], 1)
+    blob, used = orc.encode_cached64(d_rev, zero, 3, c)
+    assert not used and np.array_equal(blob, orc.encode64(d_rev, zero, 3)) and blob.size <= orc.encode_bound(m, 3)
