@@ -85,6 +85,15 @@ class Job:
         t2 = time.perf_counter()
         return t1 - t0, t2 - t1
 
+    def encode_one_wait(self):
+        """The same encodes enqueued behind each other through lc_encode_async, then one wait for the stream (the
+        tickets are collected afterwards): no host round trip between the slices."""
+        lc = self.lc
+        tickets = [lc.lc_encode_async(self.w[lo:hi], self.w_ref[lo:hi], self.nbits, self.outs[k]) for k, (lo, hi) in enumerate(self.sl)]
+        self.torch.cuda.current_stream().synchronize()
+        for k, t in enumerate(tickets):
+            self.sizes[k] = lc.lc_encode_wait(t)[0]
+
     def blob_bytes(self):
         return sum(self.sizes)
 
@@ -133,6 +142,14 @@ def run(job, steps, warmup, with_cached=True):
         enc += e; dec += d
     torch.cuda.synchronize()
     total = time.perf_counter() - t0
+    one_wait_ms = None
+    if 1 < len(job.sl) <= lc.MAX_TICKETS:
+        job.encode_one_wait()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(steps):
+            job.encode_one_wait()
+        one_wait_ms = 1e3 * (time.perf_counter() - t1) / steps
     lc.lc_profile(True)
     for _ in range(steps):
         job.step()
@@ -186,7 +203,7 @@ def run(job, steps, warmup, with_cached=True):
     dec_moved, dec_frac = call_frac(DECODE_KERNELS, dec / steps)
     return dict(ms_per_step=1e3 * total / steps, value=gb / (total / steps),
                 encode_GBps=gb / (enc / steps), decode_GBps=gb / (dec / steps),
-                encode_ms=1e3 * enc / steps, decode_ms=1e3 * dec / steps,
+                encode_ms=1e3 * enc / steps, decode_ms=1e3 * dec / steps, encode_ms_slices_enqueued_one_wait=one_wait_ms,
                 encode_alg_GBps=(16.0 + bits / 8.0) * job.n / 1e9 / (enc / steps),
                 decode_alg_GBps=(8.0 + bits / 8.0) * job.n / 1e9 / (dec / steps),
                 encode_hbm_bytes=enc_moved, encode_hbm_frac=enc_frac, decode_hbm_bytes=dec_moved, decode_hbm_frac=dec_frac,
@@ -228,6 +245,11 @@ def cached_leg(job, steps, bits):
                   k_spec_sweep_ms=round(sweep_ms, 4), k_spec_sweep_GBps=round(sweep_alg / 1e9 / (sweep_ms / 1e3), 1),
                   k_spec_sweep_frac=round(sweep_alg / 1e9 / (sweep_ms / 1e3) / HBM_PEAK_GBPS, 4),
                   frac_basis="formula (reads every element)", ranking=rank_report)
+    traffic, source = traffic_from_profiles(job.name)
+    if "k_spec_sweep" in traffic:
+        cached.update(k_spec_sweep_traffic_bytes=traffic["k_spec_sweep"],
+                      k_spec_sweep_traffic_frac=round(traffic["k_spec_sweep"] / 1e9 / (sweep_ms / 1e3) / HBM_PEAK_GBPS, 4),
+                      traffic_source=source.replace("_hbm_", "_cached_hbm_"))
     return cached
 
 
@@ -375,6 +397,13 @@ def traffic_from_profiles(workload):
                 out[f[1]] = float(f[2])
     except OSError:
         return {}, None
+    try:                                         # the kernels of the cached encode: counted in a run of their own
+        for line in open(os.path.join(ROOT, "profiles", "%s_cached_hbm_traffic_pmc.txt" % workload)):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch":
+                out.setdefault(f[1], float(f[2]))
+    except OSError:
+        pass
     return out, "profiles/" + name
 
 
@@ -501,6 +530,30 @@ PAPER_CONTEXT = {
 }
 
 
+def two_streams_leg(device, steps):
+    """Section 3.2, asynchronous execution: two lc_encode_async calls (the two halves of config 3's vector) issued on two
+    streams, where they work in scratch areas of their own and overlap on the device, against the same two calls on one
+    stream, where the second runs behind the first."""
+    import torch
+    from paper_2009_13003_amd import lc, workloads
+    w, r, nbits = workloads.vgg16(device=device)
+    n = w.numel() // 2
+    a = (w[:n].clone(), r[:n].clone()); b = (w[n:2 * n].clone(), r[n:2 * n].clone())
+    oa, ob = lc.alloc_out(n, nbits, device), lc.alloc_out(n, nbits, device)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    out = {"n_each": n, "nbits": nbits, "pairs": steps}
+    for rnd in range(2):                                   # (the first round pays for the second scratch area)
+        for mode, sb in (("two_streams", s2), ("one_stream", s1)):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                t1 = lc.lc_encode_async(a[0], a[1], nbits, oa, stream=s1)
+                t2 = lc.lc_encode_async(b[0], b[1], nbits, ob, stream=sb)
+                lc.lc_encode_wait(t1); lc.lc_encode_wait(t2)
+            out["ms_per_pair_" + mode] = round(1e3 * (time.perf_counter() - t0) / steps, 4)
+    return out
+
+
 def rounded(r, job):
     out = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
     out["n"], out["nbits"] = job.n, job.nbits
@@ -565,6 +618,8 @@ def main():
     ap.add_argument("--chain-steps", type=int, default=32, help="checkpoints in the config-4 chain leg (0 = skip)")
     ap.add_argument("--no-cached", action="store_true", help="skip the lc_encode_cached leg")
     ap.add_argument("--chain-only", action="store_true", help="run only the config-4 chain leg and print its result")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="run only the pair of asynchronous encodes (the two halves of config 3) on two streams and on one")
     ap.add_argument("--calibrate", action="store_true",
                     help="run only a plain elementwise copy kernel of known size (553,430,176 bytes read and "
                          "written per launch): the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -589,6 +644,10 @@ def main():
 
     if args.chain_only:
         print(json.dumps(chain_leg(dev, args.chain_steps)))
+        return
+
+    if args.two_streams:
+        print(json.dumps(two_streams_leg(dev, args.steps)))
         return
 
     job = Job(args.workload, dev)
