@@ -1650,6 +1650,30 @@ def test_staged_keys_quiet_chunks_and_other_paths(lc, staged, nbits):
     assert staged_launches(lc, lambda: check_case(lc, w, w_ref, nbits, "plain after staged")) == 0
 
 
+@pytest.mark.parametrize("nbits", [3, 4])
+def test_staged_keys_kept_buckets_spread_over_many_binades(lc, staged, nbits):
+    """Kept buckets far apart: the keys carry the whole exponent byte, so a kept set that reaches 28 and more binades
+    below the largest delta is coded from the keys like any other; chunks of a narrow range far below sit beside
+    chunks of the wide one; and exponents 13 to 16 binades under the largest, around where a four-bit distance
+    would run out, each land in their own bucket."""
+    n = 24 * 16384 + 777
+    g = torch.Generator(device=DEV); g.manual_seed(77 + nbits)
+    k = torch.randint(0, 8, (n,), generator=g, device=DEV).float()
+    sgn = torch.randint(0, 2, (n,), generator=g, device=DEV).float() * 2 - 1
+    wide = sgn * torch.exp2(-4 * k) * (1 + 0.5 * torch.rand(n, generator=g, device=DEV))
+    zero = torch.zeros(n, device=DEV)
+    assert staged_launches(lc, lambda: check_case(lc, wide, zero, nbits, "kept buckets 4 binades apart")) == 1
+    # the upper half of the vector in a narrow range far below the lower half's
+    mixed = wide.clone()
+    mixed[12 * 16384:] = sgn[12 * 16384:] * 2.0 ** -30 * (1 + torch.rand(n - 12 * 16384, generator=g, device=DEV))
+    check_case(lc, mixed, zero, nbits, "wide and narrow chunks")
+    # exponents 0, -1 .. -3 and -13 .. -16 in every batch, seven or fifteen buckets kept from the top
+    e = torch.tensor([0.0, -14.0, -15.0, -1.0, -2.0, -3.0, -13.0, -16.0], device=DEV)[torch.randint(0, 8, (n,), generator=g, device=DEV)]
+    edge = sgn * torch.exp2(e) * (1 + 0.25 * torch.rand(n, generator=g, device=DEV))
+    check_case(lc, edge, zero, nbits, "far exponents")
+    check_case(lc, edge.abs(), zero, nbits, "far exponents, one sign")
+
+
 def test_staged_keys_follow_the_vectors_last_encode(lc):
     """The default: a vector's first encode takes the plain second sweep; the next stages keys iff the one before had
     to read more than 30 % of the chunks (vectors of 2^26 elements and more); the blob never depends on it."""
