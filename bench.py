@@ -286,14 +286,20 @@ def typed_leg(device, steps, workload, tdt_name):
                 decode_hbm_frac=round((2.0 * esize + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
 
 
-def per_tensor_leg(device, steps):
-    """Config 2's tensors (ResNet-50: 161 tensors, 25.6 M parameters) with one table per tensor: lc_encode_batch /
-    lc_decode_batch against one lc_encode / lc_decode call per tensor."""
+def per_tensor_leg(device, steps, workload="resnet50"):
+    """One table per tensor (lc_encode_batch / lc_decode_batch) against one lc_encode / lc_decode call per tensor, and
+    against the flat vector with one table: config 2's tensors (ResNet-50: 161 tensors, 25.6 M parameters, every tensor
+    dense in its own kept buckets) or config 3's (VGG-16: 32 tensors, 138 M, heavy-tailed: most chunks of a tensor lie
+    below its kept buckets and the coding sweep passes over them)."""
     import math
     import torch
     from paper_2009_13003_amd import lc, workloads
-    shapes = workloads.resnet50_shapes()
-    w, r, nbits = workloads.resnet50(device=device)
+    if workload == "vgg16":
+        shapes = workloads.vgg16_shapes()
+        w, r, nbits = workloads.vgg16(device=device)
+    else:
+        shapes = workloads.resnet50_shapes()
+        w, r, nbits = workloads.resnet50(device=device)
     offs = [0]
     for sh in shapes:
         offs.append(offs[-1] + math.prod(sh))
@@ -321,10 +327,24 @@ def per_tensor_leg(device, steps):
     for a, o in zip(recs, outs):
         lc.lc_decode(o, a)
     t4 = time.perf_counter()
+    # the flat vector with one table, for scale
+    out_flat = lc.alloc_out(n, nbits, device)
+    rec_flat = r.clone()
+    for _ in range(2):
+        flat = lc.lc_encode(w, r, nbits, out_flat); lc.lc_decode(out_flat, rec_flat)
+    t5 = time.perf_counter()
+    for _ in range(steps):
+        lc.lc_encode(w, r, nbits, out_flat)
+    t6 = time.perf_counter()
+    for _ in range(steps):
+        lc.lc_decode(out_flat, rec_flat)
+    t7 = time.perf_counter()
     enc, dec, gb = (t1 - t0) / steps, (t2 - t1) / steps, 4.0 * n / 1e9
     return dict(n=n, tensors=len(ws), nbits=nbits, encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
                 encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(4.0 * n / sum(sizes), 3),
-                encode_ms_one_call_per_tensor=round(1e3 * (t3 - t2), 3), decode_ms_one_call_per_tensor=round(1e3 * (t4 - t3), 3))
+                encode_ms_one_call_per_tensor=round(1e3 * (t3 - t2), 3), decode_ms_one_call_per_tensor=round(1e3 * (t4 - t3), 3),
+                flat_vector=dict(encode_ms=round(1e3 * (t6 - t5) / steps, 4), decode_ms=round(1e3 * (t7 - t6) / steps, 4),
+                                 ratio=round(4.0 * n / flat, 3)))
 
 
 def chain_leg(device, steps):
@@ -690,6 +710,7 @@ def main():
         also["llama7b_slice0_fp64"] = typed_leg(dev, max(2, args.steps // 2), "llama7b_slice0", "fp64")
         torch.cuda.empty_cache()
         also["resnet50_per_tensor"] = per_tensor_leg(dev, args.steps)
+        also["vgg16_per_tensor"] = per_tensor_leg(dev, args.steps, "vgg16")
         torch.cuda.empty_cache()
         if args.chain_steps > 0:
             also["gpt2_medium_chain"] = chain_leg(dev, args.chain_steps)

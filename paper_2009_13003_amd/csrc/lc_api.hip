@@ -681,7 +681,7 @@ size_t batch_decode_bytes(const uint64_t* n, int count, uint64_t* chunks_out) {
     for (int t = 0; t < count; ++t) chunks += num_chunks_of(n[t]);
     if (chunks_out) *chunks_out = chunks;
     auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
-    return (size_t)(kWorkspaceHead + up((uint64_t)count * sizeof(DecSet)) + up((uint64_t)count * sizeof(SegD)) + up(4 * chunks) + up(4ull * count));
+    return (size_t)(kWorkspaceHead + up((uint64_t)count * sizeof(DecSet)) + up((uint64_t)count * sizeof(SegD)) + up(4 * chunks) + up(4ull * count) + up(16 * chunks));
 }
 }  // namespace
 
@@ -738,7 +738,8 @@ lc_ssize lc_decode_batch_t(const void* const* blobs, void* const* w_ref, const u
     a.sets = reinterpret_cast<DecSet*>(base);                base += up((uint64_t)count * sizeof(DecSet));
     a.segs = reinterpret_cast<SegD*>(base);                  base += up((uint64_t)count * sizeof(SegD));
     a.seg_of_chunk = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
-    a.seg_status = reinterpret_cast<uint32_t*>(base);
+    a.seg_status = reinterpret_cast<uint32_t*>(base);        base += up(4ull * count);
+    a.chunk_info = reinterpret_cast<uint32_t*>(base);
     a.results = g_batch_dev->results;
     a.count = (uint32_t)count; a.total_chunks = chunks; a.dtype = dtype; a.pad = 0;
     LC_HIP(hipMemcpyAsync(a.segs, g_batch->dsegs, (size_t)count * sizeof(SegD), hipMemcpyHostToDevice, s));
@@ -766,7 +767,8 @@ size_t lc_batch_workspace_bytes(const uint64_t* n, int count, int nbits) {
     if (chunks > 0xFFFFFFFFull) return 0;
     auto up = [](uint64_t x) { return (x + 255) / 256 * 256; };
     const size_t enc = (size_t)(kWorkspaceHead + up((uint64_t)count * sizeof(EncState)) + up((uint64_t)count * sizeof(Seg)) +
-                                up(4 * chunks) + up(4 * groups) + up(4 * chunks) + chunks * slot_words_of(nbits) * 4);
+                                up(4 * chunks) + up(4 * groups) + 3 * up(4 * chunks) + up(kPartBytes * chunks) + 256 +
+                                chunks * slot_words_of(nbits) * 4);
     const size_t dec = batch_decode_bytes(n, count, nullptr);
     return enc > dec ? enc : dec;
 }
@@ -825,6 +827,10 @@ lc_ssize lc_encode_batch_t(const void* const* w, const void* const* w_ref, const
     a.seg_of_chunk = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
     a.group_words = reinterpret_cast<uint32_t*>(base);       base += up(4ull * groups);
     a.chunk_bits = reinterpret_cast<uint32_t*>(base);        base += up(4ull * chunks);
+    a.chunk_maxexp = reinterpret_cast<uint32_t*>(base);      base += up(4ull * chunks);
+    a.chunk_list = reinterpret_cast<uint32_t*>(base);        base += up(4ull * chunks);
+    a.part_max = base;                                       base += up((uint64_t)kPartBytes * chunks);
+    a.list_count = reinterpret_cast<uint32_t*>(base);        base += 256;
     a.prov = reinterpret_cast<uint32_t*>(base);
     a.results = g_batch_dev->results;
     a.count = (uint32_t)count; a.total_chunks = chunks; a.total_groups = groups;

@@ -585,14 +585,22 @@ __global__ __launch_bounds__(256) void kb_dec_tables(BatchDecArgs a) {
     if (s_ok) dec_build_luts(D, s_len, s_code, t, 256);
 }
 
+// Also leaves, per chunk, what the sweep needs to find it: {tensor, chunk index there, the chunk's two offset-table
+// entries}, so that the sweep's wavefronts get each chunk's place with one load that they can issue a chunk ahead.
 __global__ __launch_bounds__(256) void kb_dec_chunks(BatchDecArgs a) {
     const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (g >= a.total_chunks) return;
     const u32 sidx = a.seg_of_chunk[g];
     const SegD& sg = a.segs[sidx];
     const DecInfo& I = a.sets[sidx].info;
-    if (!I.pad[0]) return;
-    if (!dec_chunk_ok(sg.blob, I.area, I.total_words, sg.nchunks, g - sg.chunk0) && lane_id() == 0) atomicMax(&a.seg_status[sidx], 4u);
+    const u32 c = g - sg.chunk0;
+    uint4 info = make_uint4(sidx, c, 0u, 0u);
+    if (I.pad[0]) {                                   // (a blob whose header failed: its tensor's status says so, the sweep skips it)
+        const u32* off_tab = reinterpret_cast<const u32*>(sg.blob + kHeaderBytes);
+        info.z = off_tab[c]; info.w = off_tab[c + 1];
+        if (!dec_chunk_ok(sg.blob, I.area, I.total_words, sg.nchunks, c) && lane_id() == 0) atomicMax(&a.seg_status[sidx], 4u);
+    }
+    if (lane_id() == 0) reinterpret_cast<uint4*>(a.chunk_info)[g] = info;
 }
 
 template <int DT>
@@ -602,8 +610,18 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
     const u32 lane = threadIdx.x;
     u32 active = 0xFFFFFFFFu, M = 0, K = 0, P1 = 0, P2 = 0;
     u64 area = 0;
+    const uint4* chunk_info = reinterpret_cast<const uint4*>(a.chunk_info);
+    auto info_of = [&](u32 g) {                      // (the same in every lane: back to scalar registers)
+        uint4 q = g < a.total_chunks ? chunk_info[g] : make_uint4(0u, 0u, 0u, 0u);
+        q.x = __builtin_amdgcn_readfirstlane(q.x); q.y = __builtin_amdgcn_readfirstlane(q.y);
+        q.z = __builtin_amdgcn_readfirstlane(q.z); q.w = __builtin_amdgcn_readfirstlane(q.w);
+        return q;
+    };
+    uint4 next = info_of(blockIdx.x);
     for (u32 g = blockIdx.x; g < a.total_chunks; g += gridDim.x) {
-        const u32 sidx = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
+        const uint4 info = next;
+        next = info_of(g + gridDim.x);               // on its way while this chunk is decoded
+        const u32 sidx = info.x;
         // a tensor whose blob failed a check is not touched
         if (__hip_atomic_load(&a.seg_status[sidx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) continue;
         const SegD& sg = a.segs[sidx];
@@ -626,9 +644,7 @@ __global__ __launch_bounds__(64) void kb_decode(BatchDecArgs a) {
             __syncthreads();
         }
         auto raise = [&](u32 code) { atomicMax(&a.seg_status[sidx], code); };
-        const u32 c = g - sg.chunk0;
-        const u32* off_tab = reinterpret_cast<const u32*>(sg.blob + kHeaderBytes);
-        const u32 o0 = off_tab[c], o1 = off_tab[c + 1];
+        const u32 c = info.y, o0 = info.z, o1 = info.w;
         const bool full = (u64)(c + 1) * kChunk <= sg.n;
         const u32 zero_bits = full ? zero_chunk_bits(L.len[K], L.code[K]) : 0u;
         if (full && sg.aligned) {
@@ -979,6 +995,10 @@ void launch_batch_decode(const BatchDecArgs& a, const Tuning& tune, hipStream_t 
     hipLaunchKernelGGL(kb_dec_tables, dim3(a.count), dim3(256), 0, s, a);
     if (a.total_chunks) {
         hipLaunchKernelGGL(kb_dec_chunks, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
+        // single-wavefront workgroups, three times as many as the compute units hold at once (12 each, by their LDS)
+        // as long as there are chunks for them: workgroups that draw cheap chunks (nothing but merged symbols) make
+        // room for the next, which evens out the load better than a fixed deal of chunks to resident wavefronts
+        // (VGG-16's 32 tensors: 60 us against 80)
         u32 waves = (u32)tune.num_cu * (u32)tune.decode_blocks_per_cu * 4u;
         if (waves > a.total_chunks) waves = a.total_chunks;
         if (a.dtype == kBF16) hipLaunchKernelGGL(kb_decode<kBF16>, dim3(waves), dim3(64), 0, s, a);

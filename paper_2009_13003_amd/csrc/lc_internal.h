@@ -14,6 +14,7 @@ constexpr uint32_t kChunk = kRowElems * kR; // 16384 elements
 constexpr uint32_t kHeaderBytes = 512;
 constexpr uint32_t kLaneBitsWords = (2 * kW) / 4;   // 32 words of u16 lane lengths per chunk record
 constexpr uint32_t kMaxSym = 16;
+constexpr uint32_t kExtCopies = 16;
 enum ElemType { kF32 = 0, kBF16 = 1, kF16 = 2, kF64 = 3 };   // element type of the parameter arrays (= LC_F32 ...)
 constexpr uint32_t kDecLut1Bits = 7;        // first decode table: conflict-free in LDS
 constexpr uint32_t kDecLut2Bits = 12;       // second decode table, for codes of 8..12 bits
@@ -81,8 +82,8 @@ struct HostResult {
 // code table.  One per call; a batched call (one table per tensor) has one per tensor.
 struct EncState {
     unsigned long long hist[512];
-    uint32_t mmin[kMaxSym];
-    uint32_t mmax[kMaxSym];
+    uint32_t mmin[kExtCopies][kMaxSym];      // smallest / largest mantissa seen of every kept bucket: a workgroup of the coding
+    uint32_t mmax[kExtCopies][kMaxSym];      // sweep updates copy (its index mod kExtCopies), the finalize kernel joins them
     uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
     uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
     unsigned long long total_words;
@@ -186,11 +187,17 @@ struct Seg {
     uint32_t nchunks, chunk0, group0, aligned;
 };
 constexpr int kMaxBatch = 1024;
+constexpr uint32_t kPartBytes = 16;
 struct BatchArgs {
     Seg* segs; EncState* states; Result* results;     // device (results: mapped host memory)
     uint32_t* seg_of_chunk; uint32_t* group_words; uint32_t* chunk_bits; uint32_t* prov;
+    uint32_t* chunk_maxexp;      // largest |delta| exponent of every chunk (chunks of all tensors numbered through), from the counting sweep
+    uint8_t* part_max;           // ... and of each of its 4 KiB parts: kPartBytes per chunk (16 parts of 4-byte elements, 8 of 2-byte)
+    uint32_t* chunk_list;        // the chunks the coding sweep has to read, and
+    uint32_t* list_count;        // how many those are
     uint32_t count, total_chunks, total_groups, slot_words;
     int nbits, dtype;                                  // dtype: element type of every tensor of the call
+    uint32_t waves_long, pad_b;                        // wavefronts of the coding sweep when more chunks are listed than its grid has
 };
 void launch_batch_encode(const BatchArgs& a, const Tuning& tune, hipStream_t s);
 
@@ -203,6 +210,7 @@ struct SegD {
 struct BatchDecArgs {
     SegD* segs; DecSet* sets; Result* results;         // device (results: mapped host memory)
     uint32_t* seg_of_chunk; uint32_t* seg_status;      // seg_status: lc_status per tensor, raised with atomicMax
+    uint32_t* chunk_info;                              // per chunk {tensor, chunk index there, its two offset-table entries}, 16 bytes
     uint32_t count, total_chunks;
     int dtype, pad;
 };

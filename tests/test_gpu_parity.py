@@ -1032,6 +1032,54 @@ def quiet_chunk_case(n, seed, quiet, tiny=2.0 ** -30):
 
 
 @pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_batched_encode_of_chunks_below_their_tensors_kept_buckets(lc, nbits):
+    """A batched call passes over full chunks whose largest delta lies below every kept bucket of *their own* tensor
+    (the counting sweep notes every chunk's maximum, a list kernel tells them apart once the tables exist): quiet
+    chunks at the start and the end of tensors, at group borders, whole quiet tensors (all deltas zero; all tiny but
+    one), a tensor whose quiet level is another tensor's kept range, a ragged last chunk that is quiet (read anyway),
+    an unaligned tensor, 16-bit tensors, and a non-finite tensor in between."""
+    C = 16384
+    specs = [  # (chunks, extra elements, quiet chunks, tiny level, offset)
+        (70, 123, [0, 1, 2, 63, 64, 65, 69, 70], 2.0 ** -30, 0),
+        (3, 0, [0, 1, 2], 2.0 ** -30, 0),                     # all tiny: the tiny values are this tensor's own kept buckets
+        (5, 17, [4, 5], 2.0 ** -30, 0),                       # last full chunk and the ragged tail quiet
+        (9, 0, [1, 2, 3, 4, 5, 6, 7], 2.0 ** -13, 0),         # quiet level inside the first tensors' kept range
+        (6, 999, [0, 2, 4], 2.0 ** -30, 3),                   # unaligned
+        (130, 1, list(range(3, 128)), 2.0 ** -28, 0),
+    ]
+    ws, refs = [], []
+    for i, (nc, extra, quiet, tiny, off) in enumerate(specs):
+        w, r = quiet_chunk_case(nc * C + extra + off, 900 + 10 * nbits + i, quiet, tiny=tiny)
+        ws.append(w[off:]); refs.append(r[off:])
+    # a tensor that does not change at all, and one with a single changed element in its last chunk
+    z = 0.05 * torch.randn(4 * C + 5, device=DEV)
+    ws.append(z.clone()); refs.append(z)
+    one = z.clone(); one[3 * C + 77] += 0.25
+    ws.append(one); refs.append(z)
+    check_batch(lc, ws, refs, nbits)
+    # the coding sweep really passed over chunks: tensor 5's blob holds 125 chunks of the merged code only
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    sizes = lc.lc_encode_batch(ws, refs, nbits, outs)
+    hdr = lcb1_reader.parse_header(outs[5][:sizes[5]].cpu().numpy())
+    K = hdr["K"]
+    rec_words = 32 + C * hdr["slots"][K]["len"] // 32
+    offs = outs[5][512:512 + 4 * 132].cpu().numpy().view(np.uint32)
+    assert all(int(offs[c + 1]) - int(offs[c]) == rec_words for c in range(3, 128))
+    # with a non-finite tensor between them the others still come out the same
+    bad = ws[2].clone(); bad[C + 5] = float("inf")
+    check_batch(lc, [ws[0], bad, ws[3]], [refs[0], refs[2], refs[3]], nbits, expect_status={1: 2})
+    # 16-bit tensors
+    for tdt in (torch.bfloat16, torch.float16):
+        w16 = [w.to(tdt) for w in ws[:4]]
+        r16 = [r.to(tdt) for r in refs[:4]]
+        outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in w16]
+        sizes = lc.lc_encode_batch(w16, r16, nbits, outs)
+        for t, (w, r, o, size) in enumerate(zip(w16, r16, outs, sizes)):
+            blob_cpu = orc.encode_t(raw16(w), raw16(r), nbits, orc.DT_BF16 if tdt == torch.bfloat16 else orc.DT_F16)
+            assert size == blob_cpu.size and np.array_equal(o[:size].cpu().numpy(), blob_cpu), (tdt, t)
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
 def test_encode_of_chunks_below_every_kept_bucket(lc, nbits):
     """Whole chunks whose deltas all fall into the merged bucket are coded without being read again, from the
     per-chunk exponent maxima of the first sweep: at the start, at group borders (63, 64), in a run, as the
