@@ -612,8 +612,13 @@ struct ChunkRef {
     bool vec;                    // the arrays are aligned for 4-element accesses (whole rows of a ragged chunk too)
     bool by_parts;               // a chunk of aligned arrays that is mostly merged: coded part by part, and
     u32 parts;                   // which of its whole parts have to be read
-    u32* maxexp_at;              // counting sweep of a batched call: where the chunk's largest exponent goes (or null),
-    uint8_t* parts_at;           // ... and those of its 4 KiB parts (one byte each)
+};
+
+// Where the counting sweep of a batched call notes a chunk's largest exponent and those of its 4 KiB parts (one byte
+// each); both null where nobody wants them.  (Not part of ChunkRef: the coding kernels carry that in registers.)
+struct MaximaAt {
+    u32* chunk;
+    uint8_t* parts;
 };
 
 // The counting sweep of a batched call also notes the largest |delta| exponent of every chunk and of each of its 4 KiB
@@ -630,11 +635,10 @@ struct ChunkMaxima {
         const u32 pm = wave_max_u32(gm) >> 23;
         if (lane_id() == r0 / kRowsPerPart) part_max = max(part_max, pm);
     }
-    __device__ __forceinline__ void note(const ChunkRef& ch) {
+    __device__ __forceinline__ void note(const MaximaAt& at) {
         const u32 m = wave_max_u32(umax);
-        if (!ch.maxexp_at) return;
-        if (lane_id() == 0) *ch.maxexp_at = m >> 23;
-        if (lane_id() < kParts) ch.parts_at[lane_id()] = (uint8_t)part_max;
+        if (lane_id() == 0) *at.chunk = m >> 23;
+        if (lane_id() < kParts) at.parts[lane_id()] = (uint8_t)part_max;
     }
 };
 
@@ -655,7 +659,7 @@ __device__ __forceinline__ void finish_lane_sizes(const ChunkRef& ch, u32 nb, u3
 constexpr int kPlainRows = 4;
 
 template <bool HIST, bool PACK, int DT>
-__device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& L) {
+__device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& L, const MaximaAt at = MaximaAt{nullptr, nullptr}) {
     const u32 lane = lane_id();
     const void* __restrict__ w = ch.w; const void* __restrict__ w_ref = ch.w_ref;
     const u64 n = ch.n, base = (u64)ch.c * kChunk;
@@ -703,7 +707,7 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
         auto code = [&](const float (&a)[kPlainRows][4], const float (&b)[kPlainRows][4], u32 r0) {
 #pragma unroll
             for (int k = 0; k < kPlainRows; ++k) code_row(yes(), row_at_(r0 + k), a[k], b[k]);
-            if (HIST && !PACK) { cm.group(gmax, r0); gmax = 0; }
+            if (HIST && !PACK && at.chunk) { cm.group(gmax, r0); gmax = 0; }
         };
         fetch(xa, xb, 0);
         for (; r < whole_rows; r += 2 * kPlainRows) {
@@ -722,7 +726,7 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
 #pragma unroll
         for (int k = 0; k < kPlainRows; ++k) code_row(no(), row_at_(r + k), xa[k], xb[k]);
     }
-    if (HIST && !PACK) { cm.umax = max(cm.umax, gmax); cm.note(ch); }     // (rows behind the last whole part: the chunk's maximum only)
+    if (HIST && !PACK && at.chunk) { cm.umax = max(cm.umax, gmax); cm.note(at); }     // (rows behind the last whole part: the chunk's maximum only)
     if (!PACK) return;
     if (nb > 0) slot[kLaneBitsWords + nw * kW + lane] = (u32)(acc << (32 - nb));
     finish_lane_sizes(ch, nb, nw);
@@ -834,7 +838,7 @@ __device__ __forceinline__ void fetch_first_batch(const ChunkRef& ch, typename R
 template <bool ROWCHK, bool HIST, bool PACK, int DT>
 __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const ChunkRef& next,
                                                 typename Raw<DT>::type (&A0)[kPackPF], typename Raw<DT>::type (&B0)[kPackPF],
-                                                u32 K8, PackLds<HIST>& L) {
+                                                u32 K8, PackLds<HIST>& L, const MaximaAt at = MaximaAt{nullptr, nullptr}) {
     constexpr int PF = kPackPF;
     typedef typename Raw<DT>::type raw_t;
     const u32 lane = lane_id();
@@ -873,7 +877,7 @@ __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const Chunk
 #pragma unroll
             for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
         }
-        if (HIST && !PACK) {
+        if (HIST && !PACK && at.chunk) {
             u32 gm = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i) gm = max(gm, u[i] & 0x7FFFFFFFu);
@@ -916,7 +920,7 @@ __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const Chunk
         }
         group(A1, B1, r0 + 8); group(A1 + 4, B1 + 4, r0 + 12);
     }
-    if (HIST && !PACK) cm.note(cur);
+    if (HIST && !PACK && at.chunk) cm.note(at);
     if (!PACK) return;
     // the last, partly filled word, then rows 0 .. (most words of any lane) - 1, four rows per store
     if (nb > 0) {
@@ -951,7 +955,16 @@ __device__ __forceinline__ void pack_loop(Src& src, PackLds<HIST>& L) {
     while (cur.valid) {
         const ChunkRef next = src.take();
         src.enter(cur, L);
-        if (!cur.fast) {
+        if constexpr (HIST && !PACK) {
+            // counting only
+            const MaximaAt at = src.maxima_at(cur);
+            if (!cur.fast) {
+                pack_chunk_plain<HIST, PACK, DT>(cur, L, at);
+                if (next.valid && next.fast) fetch_first_batch<DT>(next, A0, B0);
+            } else {
+                pack_chunk_fast<true, HIST, PACK, DT>(cur, next, A0, B0, src.K8(), L, at);
+            }
+        } else if (!cur.fast) {
             if constexpr (!HIST && PACK) {
                 if (cur.by_parts) pack_chunk_parts<DT>(cur, src.merged_codelen(), L);
                 else pack_chunk_plain<HIST, PACK, DT>(cur, L);
@@ -1008,7 +1021,6 @@ struct VectorChunks {
         ch.group_at = group_words + (c >> 6);
         ch.seg = 0;
         ch.parts = 0; ch.by_parts = false;
-        ch.maxexp_at = nullptr; ch.parts_at = nullptr;
         if (valid && aligned && batch_max) {
             const u64 inside = n - (u64)c * kChunk, part_elems = kChunk / parts_per_chunk;
             const u32 whole = inside >= kChunk ? parts_per_chunk : (u32)(inside / part_elems);
@@ -1024,6 +1036,7 @@ struct VectorChunks {
         return i < listed ? ref(load_uniform(chunk_list + i), true) : ref(nchunks, false);
     }
     template <bool HIST> __device__ __forceinline__ void enter(const ChunkRef&, PackLds<HIST>&) const {}
+    __device__ __forceinline__ MaximaAt maxima_at(const ChunkRef&) const { return MaximaAt{nullptr, nullptr}; }
     __device__ __forceinline__ u32 K8() const { return k8; }
     __device__ __forceinline__ bool rowchk() const { return row; }
 };
@@ -1554,8 +1567,6 @@ struct BatchChunks {
         const u32 g = (PACK && ch.valid) ? load_uniform(a.chunk_list + i) : i;
         ch.seg = 0; ch.c = 0; ch.w = nullptr; ch.w_ref = nullptr; ch.n = 0; ch.fast = false; ch.vec = false; ch.by_parts = false; ch.parts = 0;
         ch.slot = nullptr; ch.bits_at = nullptr; ch.group_at = nullptr;
-        ch.maxexp_at = (!PACK && ch.valid) ? a.chunk_maxexp + g : nullptr;
-        ch.parts_at = (!PACK && ch.valid) ? a.part_max + (u64)g * kPartBytes : nullptr;
         if (ch.valid) {
             ch.seg = __builtin_amdgcn_readfirstlane(a.seg_of_chunk[g]);
             const Seg& sg = a.segs[ch.seg];
@@ -1605,6 +1616,10 @@ struct BatchChunks {
             k8 = T.K << 3; row = T.max_len <= 8; cl_merged = T.codelen[T.K];
             __syncthreads();
         }
+    }
+    __device__ __forceinline__ MaximaAt maxima_at(const ChunkRef& ch) const {
+        const u32 g = load_uniform(&a.segs[ch.seg].chunk0) + ch.c;
+        return MaximaAt{a.chunk_maxexp + g, a.part_max + (u64)g * kPartBytes};
     }
     __device__ __forceinline__ u32 K8() const { return k8; }
     __device__ __forceinline__ bool rowchk() const { return row; }
