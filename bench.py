@@ -660,6 +660,8 @@ def main():
     ap.add_argument("--chain-steps", type=int, default=32, help="checkpoints in the config-4 chain leg (0 = skip)")
     ap.add_argument("--no-cached", action="store_true", help="skip the lc_encode_cached leg")
     ap.add_argument("--chain-only", action="store_true", help="run only the config-4 chain leg and print its result")
+    ap.add_argument("--per-tensor", choices=("resnet50", "vgg16"),
+                    help="run only the batched per-tensor leg on that model's tensors and print its result")
     ap.add_argument("--two-streams", action="store_true",
                     help="run only the pair of asynchronous encodes (the two halves of config 3) on two streams and on one")
     ap.add_argument("--calibrate", action="store_true",
@@ -688,6 +690,9 @@ def main():
         print(json.dumps(chain_leg(dev, args.chain_steps)))
         return
 
+    if args.per_tensor:
+        print(json.dumps(per_tensor_leg(dev, args.steps, args.per_tensor)))
+        return
     if args.two_streams:
         print(json.dumps(two_streams_leg(dev, args.steps)))
         return

@@ -242,7 +242,9 @@ struct BitReader {
 };
 
 // `raise(code)` reports a lane string that does not decode to its stated length.
-template <bool FAST, bool LV2, bool STAGED, int DT, typename LDS, typename Raise>
+// DEEP: the launch has so few wavefronts that nothing hides a wavefront's waits on memory: rows are then fetched 8 at
+// a time (2-byte elements: 16), two such batches in flight, instead of 4.
+template <bool FAST, bool LV2, bool STAGED, int DT, bool DEEP, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
                                             void* __restrict__ w_ref, u64 n, u32 c,
                                             const LDS& L, u32 P1, u32 P2, u32 K, u32 row_zero_bits, bool sparse, Raise& raise) {
@@ -354,7 +356,7 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
             load_row_v<false, DT>(w_ref, idx, n, x);
             row(no(), idx, x);
         }
-    } else if (FAST && DT == kF32) {
+    } else if (FAST && DT == kF32 && !DEEP) {
 #pragma unroll 4
         for (u32 r = 0; r < kR; ++r) {
             const u64 idx = base + (u64)r * kRowElems + lane * kV;
@@ -366,7 +368,7 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
         // 2-byte and 8-byte elements: rows in batches of 4, the next batch fetched before this one is decoded and stored
         // (in program order: the compiler does not move a load above an earlier store of the same kind).  13 % faster
         // than the loop above for bf16, 1 % for fp64; 3 % slower for fp32, which keeps the loop.
-        constexpr u32 PF = 4;
+        constexpr u32 PF = DEEP ? ((DT == kF64 || DT == kF32) ? 8 : 16) : 4;        // (two workgroups must still fit a compute unit)
         typedef typename Raw<DT>::type raw_t;
         auto fetch = [&](raw_t (&X)[PF], u32 r0) {
 #pragma unroll
@@ -422,7 +424,7 @@ __device__ __forceinline__ u32 zero_chunk_bits(u32 len_merged, u32 code_merged) 
 }
 
 // pay: this wavefront's LDS area of pay_words + 4 words for the chunk's payload
-template <bool FAST, bool LV2, int DT, typename LDS, typename Raise>
+template <bool FAST, bool LV2, int DT, bool DEEP = false, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                              u32 c, u32 o0, u32 o1, LDS& L, uint4* pay, u32 pay_words, u32 P1, u32 P2, u32 K,
                                              u64 area, u32 zero_bits, Raise& raise) {
@@ -464,14 +466,14 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
             nonzero |= (i == 0) ? ((k0 < 1 ? q.x : 0u) | (k0 < 2 ? q.y : 0u) | (k0 < 3 ? q.z : 0u) | q.w) : (q.x | q.y | q.z | q.w);
         }
         if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
-        decode_rows<FAST, LV2, true, DT>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
+        decode_rows<FAST, LV2, true, DT, DEEP>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
                                          w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     } else {
-        decode_rows<FAST, LV2, false, DT>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
+        decode_rows<FAST, LV2, false, DT, DEEP>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     }
 }
 
-template <int DT>
+template <int DT, bool DEEP>
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                                 Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host,
                                                 u32 pay_words, u32 set) {
@@ -524,8 +526,8 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
             if (cn < nchunks) { n0 = off_tab[cn]; n1 = off_tab[cn + 1]; }
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
-                else decode_chunk<true, false, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT, DEEP>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                else decode_chunk<true, false, DT, DEEP>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
             } else {
                 decode_chunk<false, true, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
             }
@@ -1092,10 +1094,18 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
         if (pay_words < kPayWords) pay_words = kPayWords;
     }
     const size_t lds = 4 * (size_t)(pay_words / 4 + 1) * sizeof(uint4);
-    if (dtype == kF64) hipLaunchKernelGGL(k_decode<kF64>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
-    else if (dtype == kBF16) hipLaunchKernelGGL(k_decode<kBF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
-    else if (dtype == kF16) hipLaunchKernelGGL(k_decode<kF16>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
-    else hipLaunchKernelGGL(k_decode<kF32>, grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
+    // At most two workgroups per compute unit: a wavefront has its SIMD almost to itself and nothing hides its waits
+    // on memory, so the kernel's form with rows fetched far ahead runs (it needs more registers than would let more
+    // workgroups share a unit).
+    const bool deep = per_cu <= 2;
+#define LC_DECODE(DT) \
+    if (deep) hipLaunchKernelGGL((k_decode<DT, true>), grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set); \
+    else hipLaunchKernelGGL((k_decode<DT, false>), grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set)
+    if (dtype == kF64) { LC_DECODE(kF64); }
+    else if (dtype == kBF16) { LC_DECODE(kBF16); }
+    else if (dtype == kF16) { LC_DECODE(kF16); }
+    else { LC_DECODE(kF32); }
+#undef LC_DECODE
 }
 
 }  // namespace lc
