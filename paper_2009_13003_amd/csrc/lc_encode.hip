@@ -586,7 +586,8 @@ constexpr int kMmCopies = 32;       // LDS copies of the per-symbol extremes, on
 
 constexpr u32 kStageRows = 32;      // code words per lane that a chunk gathers in LDS before they go to its slot
 
-constexpr int kSpecCopies = 4;      // LDS copies of the bucket histogram in the speculative sweep
+constexpr int kSpecCopies = 2;      // LDS copies of the bucket histogram in the speculative sweep (4 copies leave room for 6
+                                    // wavefronts per compute unit instead of 8: 0.443 against 0.428 ms per 2^28 elements)
 
 template <bool HIST>
 struct PackLds {
@@ -1838,9 +1839,9 @@ void launch_batch_encode(const BatchArgs& args, const Tuning& tune, hipStream_t 
     if (setup_blocks < 1) setup_blocks = 1;
     hipLaunchKernelGGL(kb_setup, dim3(setup_blocks), dim3(256), 0, s, a);
     if (a.total_chunks) {
-        // (with its histogram copies a counting workgroup needs 23 KB of LDS: 6 fit a compute unit, and a grid of more
-        // leaves the last ones a round of their own: 0.20 ms instead of 0.18 on VGG-16's 32 tensors)
-        const int per_cu = tune.batch_waves_per_cu < 6 ? tune.batch_waves_per_cu : 6;
+        // (a counting workgroup needs 19 KB of LDS: 8 fit a compute unit, and a grid of more leaves the last ones a
+        // round of their own: 0.20 ms instead of 0.18 on VGG-16's 32 tensors)
+        const int per_cu = tune.batch_waves_per_cu < 8 ? tune.batch_waves_per_cu : 8;
         const u32 waves = even_waves(a.total_chunks, (u64)tune.num_cu * per_cu);
         if (a.dtype == kBF16) hipLaunchKernelGGL(kb_hist<kBF16>, dim3(waves), dim3(64), 0, s, a);
         else if (a.dtype == kF16) hipLaunchKernelGGL(kb_hist<kF16>, dim3(waves), dim3(64), 0, s, a);

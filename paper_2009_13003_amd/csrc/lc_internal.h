@@ -141,7 +141,7 @@ struct Tuning {
     int pack_waves_per_cu = 8;         // single-wave workgroups of k_pack per compute unit
     int keys_waves_per_cu = 10;        // ... of the sweep that codes from staged keys (3 fit a SIMD; 10 measured best)
     int key_staging = 0;               // 0: by the vector's last call, 1: whenever it applies, 2: never
-    int spec_waves_per_cu = 6;         // of the single sweep of the cached encode
+    int spec_waves_per_cu = 8;         // of the single sweep of the cached encode (what its LDS and registers allow)
     int batch_waves_per_cu = 8;        // of the batch kernels
     int decode_blocks_per_cu = 9;     // (LDS lets 4 run at once; more, smaller shares even out chunks that decode to nothing)
     int fused_waves_per_cu = 16;       // most wavefronts per compute unit
