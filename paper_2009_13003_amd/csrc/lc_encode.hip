@@ -1518,7 +1518,7 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const
 }
 
 // ----------------------------------------------------------------------------- batched encode
-// lc_encode_batch: many vectors, one table each, in six launches.  The chunks of all tensors are numbered
+// lc_encode_batch: many vectors, one table each, in seven launches.  The chunks of all tensors are numbered
 // through; the sweeps deal those dense chunks round-robin to their wavefronts exactly as for one vector,
 // and a wavefront that moves on to a chunk of another tensor first hands in what it gathered for the last
 // one (bucket counts, extremes) and loads the new tensor's table.
