@@ -79,6 +79,11 @@ class Job:
         for k, (lo, hi) in enumerate(self.sl):
             self.lc.lc_decode(self.outs[k], self.rec[lo:hi])
 
+    def verify(self):
+        """lc_verify on every blob of the workload: the end-to-end check that reads the blobs only."""
+        for k, (lo, hi) in enumerate(self.sl):
+            self.lc.lc_verify(self.outs[k][:self.sizes[k]], hi - lo)
+
     def step(self):
         t0 = time.perf_counter(); self.encode()
         t1 = time.perf_counter(); self.decode()
@@ -172,6 +177,12 @@ def run(job, steps, warmup, with_cached=True):
         for _ in range(steps):
             job.encode_two_streams(streams)
         two_streams_ms = 1e3 * (time.perf_counter() - t1) / steps
+    job.verify()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        job.verify()
+    verify_ms = 1e3 * (time.perf_counter() - t1) / steps
     lc.lc_profile(True)
     for _ in range(steps):
         job.step()
@@ -225,7 +236,7 @@ def run(job, steps, warmup, with_cached=True):
     dec_moved, dec_frac = call_frac(DECODE_KERNELS, dec / steps)
     return dict(ms_per_step=1e3 * total / steps, value=gb / (total / steps),
                 encode_GBps=gb / (enc / steps), decode_GBps=gb / (dec / steps),
-                encode_ms=1e3 * enc / steps, decode_ms=1e3 * dec / steps, encode_ms_slices_enqueued_one_wait=one_wait_ms, encode_ms_slices_on_two_streams=two_streams_ms,
+                encode_ms=1e3 * enc / steps, decode_ms=1e3 * dec / steps, encode_ms_slices_enqueued_one_wait=one_wait_ms, encode_ms_slices_on_two_streams=two_streams_ms, verify_ms=verify_ms,
                 encode_alg_GBps=(16.0 + bits / 8.0) * job.n / 1e9 / (enc / steps),
                 decode_alg_GBps=(8.0 + bits / 8.0) * job.n / 1e9 / (dec / steps),
                 encode_hbm_bytes=enc_moved, encode_hbm_frac=enc_frac, decode_hbm_bytes=dec_moved, decode_hbm_frac=dec_frac,
@@ -760,7 +771,7 @@ def main():
         "roofline": roofline, "kernels": res["kernels"], "encode_cached": res["encode_cached"], "cpu_baseline": cpu,
         "paper_context": PAPER_CONTEXT, "also": also,
     }
-    for key in ("encode_ms_slices_enqueued_one_wait", "encode_ms_slices_on_two_streams"):
+    for key in ("encode_ms_slices_enqueued_one_wait", "encode_ms_slices_on_two_streams", "verify_ms"):
         if res.get(key) is not None:
             line[key] = round(res[key], 4)
     print(json.dumps(line))

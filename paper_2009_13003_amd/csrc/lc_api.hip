@@ -77,13 +77,14 @@ HostResult* g_pinned_dev = nullptr;   // the same memory as the device sees it
 uint64_t g_epoch = 0;            // tags the decode status word of each call
 
 int g_key_staging = -1;          // LC_OPT_KEY_STAGING (-1: not yet read from the environment)
+bool g_verify_first = false;     // LC_OPT_VERIFY_FIRST
 bool g_prof = false;
 double g_prof_ms[kNumSlots];
 uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
 const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize", "k_spec_table", "k_spec_sweep",
-                                           "k_dec_check", "k_decode", "k_decode_fused", "k_hist_keys", "k_pack_keys"};
+                                           "k_dec_check", "k_decode", "k_decode_fused", "k_hist_keys", "k_pack_keys", "k_verify"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
     const char* v = getenv(name);
@@ -516,11 +517,13 @@ lc_ssize lc_encode_cached(const float* w, const float* w_ref, uint64_t n, int nb
 
 namespace {
 // blob_bytes: what the caller says its buffer holds (SIZE_MAX: not stated); the header's total may not pass it
-lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream) {
+// verify_only: nothing but the blob is read (lc_verify); else the restore, after the same lane-string check if the
+// option asks for it
+lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream, bool verify_only = false) {
     if (!blob || misaligned(blob, 16) || n > LC_MAX_N) return -LC_ERR_BADARG;
     if (blob_bytes < kHeaderBytes) return -LC_ERR_BAD_BLOB;
     if (dtype != LC_F32 && dtype != LC_BF16 && dtype != LC_F16 && dtype != LC_F64) return -LC_ERR_BADARG;
-    if (n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
+    if (!verify_only && n && (!w_ref || misaligned(w_ref, dtype == LC_F32 ? 4 : dtype == LC_F64 ? 8 : 2))) return -LC_ERR_BADARG;
     std::unique_lock<std::mutex> lock(g_mu);
     int err = 0;
     DeviceState* ds = device_state(&err);
@@ -539,7 +542,9 @@ lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t 
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = b;
     const uint64_t bound = lc_encode_bound(n, 4), max_total = blob_bytes < bound ? blob_bytes : bound;
     { Timed t(kSlotDecCheck, s); launch_dec_check(list, 0, 1, n, dtype, max_total, ws, epoch, host, s); }
-    { Timed t(kSlotDecode, s);   launch_decode(b, w_ref, n, dtype, ws, 0, epoch, host, ds->tune, s); }
+    // (a finding of the verifying sweep gates the restoring one on the device, like a finding of the check)
+    if (verify_only || g_verify_first) { Timed t(kSlotVerify, s); launch_decode(b, nullptr, n, dtype, ws, 0, epoch, host, ds->tune, s); }
+    if (!verify_only) { Timed t(kSlotDecode, s); launch_decode(b, w_ref, n, dtype, ws, 0, epoch, host, ds->tune, s); }
     LC_HIP(hipGetLastError());
     if (!release(area, s)) return -LC_ERR_HIP;
     const bool serial = g_prof;              // (see encode_impl)
@@ -547,8 +552,8 @@ lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t 
     const hipError_t waited = hipStreamSynchronize(s);
     if (!serial) lock.lock();
     if (waited != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
-    const int slots[] = {kSlotDecCheck, kSlotDecode};
-    collect(slots, 2);
+    const int slots[] = {kSlotDecCheck, kSlotDecode, kSlotVerify};
+    collect(slots, 3);
     if ((g_pinned[slot].dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned[slot].dec_status & 0xFF);
     return (lc_ssize)g_pinned[slot].bytes[0];
 }
@@ -562,6 +567,10 @@ lc_ssize lc_decode_t(const void* blob, void* w_ref, uint64_t n, int dtype, void*
 
 lc_ssize lc_decode_sized(const void* blob, size_t blob_bytes, void* w_ref, uint64_t n, int dtype, void* stream) {
     return decode_impl(blob, blob_bytes, w_ref, n, dtype, stream);
+}
+
+lc_ssize lc_verify(const void* blob, size_t blob_bytes, uint64_t n, int dtype, void* stream) {
+    return decode_impl(blob, blob_bytes, nullptr, n, dtype, stream, true);
 }
 
 lc_ssize lc_encode_sized(const void* w, const void* w_ref, uint64_t n, int nbits, void* out, size_t out_bytes, int dtype,
@@ -604,6 +613,9 @@ lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint
     for (int t = 0; t < kMaxSets; ++t) list.p[t] = static_cast<const uint8_t*>(blobs[t < count ? t : 0]);
     // every blob is validated (one launch, one grid row per blob) before w_ref is touched
     { Timed tm(kSlotDecCheck, s); launch_dec_check(list, 0, count, n, dtype, bound, ws, epoch, host, s); }
+    if (g_verify_first) {
+        for (int i = 0; i < count; ++i) { Timed tm(kSlotVerify, s); launch_decode(list.p[i], nullptr, n, dtype, ws, i, epoch, host, ds->tune, s); }
+    }
     LC_HIP(hipGetLastError());
     if (!release(area, s)) return -LC_ERR_HIP;
     LC_HIP(hipStreamSynchronize(s));
@@ -881,6 +893,7 @@ int lc_blob_sizes(const void* host_header, uint64_t bits[3]) {
 int lc_set_option(int option, int value) {
     std::lock_guard<std::mutex> lock(g_mu);
     if (option == LC_OPT_KEY_STAGING && value >= LC_STAGING_AUTO && value <= LC_STAGING_NEVER) { g_key_staging = value; return LC_OK; }
+    if (option == LC_OPT_VERIFY_FIRST && (value == 0 || value == 1)) { g_verify_first = value != 0; return LC_OK; }
     return LC_ERR_BADARG;
 }
 

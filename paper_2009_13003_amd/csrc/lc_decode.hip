@@ -244,7 +244,8 @@ struct BitReader {
 // `raise(code)` reports a lane string that does not decode to its stated length.
 // DEEP: the launch has so few wavefronts that nothing hides a wavefront's waits on memory: rows are then fetched 8 at
 // a time (2-byte elements: 16), two such batches in flight, instead of 4.
-template <bool FAST, bool LV2, bool STAGED, int DT, bool DEEP, typename LDS, typename Raise>
+// VERIFY: the lane strings are only decoded and measured against their stated lengths; w_ref is not touched (nor read).
+template <bool FAST, bool LV2, bool STAGED, int DT, bool DEEP, bool VERIFY, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 first_bit, u32 lane_bits,
                                             void* __restrict__ w_ref, u64 n, u32 c,
                                             const LDS& L, u32 P1, u32 P2, u32 K, u32 row_zero_bits, bool sparse, Raise& raise) {
@@ -254,6 +255,27 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     const u32 wi0 = br.wi, avail0 = br.avail;
     const u32 shr1 = 64 - P1, shr2 = 64 - P2;
     const u64 base = (u64)c * kChunk;
+    if constexpr (VERIFY) {
+        for (u32 r = 0; r < kR && (FAST || base + (u64)r * kRowElems < n); ++r) {
+            const u64 idx = base + (u64)r * kRowElems + lane * kV;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (FAST || idx + v < n) {
+                    u32 e = L.lut1[(u32)(br.win >> shr1)];
+                    if (LV2 && e == 0xFF) {
+                        e = L.lut2[(u32)(br.win >> shr2)];
+                        if (e == 0xFF) e = decode_long(L, br.win, K);
+                    }
+                    const u32 len = e >> 4;
+                    br.win <<= len; br.avail -= len;
+                }
+                if ((v & 1) && br.avail <= 32) br.refill();
+            }
+        }
+        const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
+        if (__any(used != lane_bits) && lane == 0) raise(4u);
+        return;
+    }
     // one row of the chunk; WHOLE: all 4 elements of every lane exist and the row can be stored as vectors
     typedef typename Val<DT>::type val_t;
     auto row = [&](auto whole, u64 idx, val_t (&x)[4]) {
@@ -424,7 +446,7 @@ __device__ __forceinline__ u32 zero_chunk_bits(u32 len_merged, u32 code_merged) 
 }
 
 // pay: this wavefront's LDS area of pay_words + 4 words for the chunk's payload
-template <bool FAST, bool LV2, int DT, bool DEEP = false, typename LDS, typename Raise>
+template <bool FAST, bool LV2, int DT, bool DEEP = false, bool VERIFY = false, typename LDS, typename Raise>
 __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                              u32 c, u32 o0, u32 o1, LDS& L, uint4* pay, u32 pay_words, u32 P1, u32 P2, u32 K,
                                              u64 area, u32 zero_bits, Raise& raise) {
@@ -466,14 +488,16 @@ __device__ __forceinline__ void decode_chunk(const uint8_t* __restrict__ blob, v
             nonzero |= (i == 0) ? ((k0 < 1 ? q.x : 0u) | (k0 < 2 ? q.y : 0u) | (k0 < 3 ? q.z : 0u) | q.w) : (q.x | q.y | q.z | q.w);
         }
         if (zero_bits != 0 && !__any(lane_bits != zero_bits || nonzero != 0)) return;
-        decode_rows<FAST, LV2, true, DT, DEEP>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
+        decode_rows<FAST, LV2, true, DT, DEEP, VERIFY>(reinterpret_cast<const u32*>(pay) + k0, nwords, o, lane_bits,
                                          w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     } else {
-        decode_rows<FAST, LV2, false, DT, DEEP>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
+        decode_rows<FAST, LV2, false, DT, DEEP, VERIFY>(gw, nwords, o, lane_bits, w_ref, n, c, L, P1, P2, K, row_zero_bits, sparse, raise);
     }
 }
 
-template <int DT, bool DEEP>
+// VERIFY: lc_verify's sweep (and the one lc_decode runs first when asked to): the same walk over the blob, decoding
+// only; `w_ref` is not used.
+template <int DT, bool DEEP, bool VERIFY = false>
 __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob, void* __restrict__ w_ref, u64 n,
                                                 Workspace* ws, u32 nchunks, int aligned, u64 epoch, HostResult* host,
                                                 u32 pay_words, u32 set) {
@@ -526,10 +550,10 @@ __global__ __launch_bounds__(256) void k_decode(const uint8_t* __restrict__ blob
             if (cn < nchunks) { n0 = off_tab[cn]; n1 = off_tab[cn + 1]; }
             const bool full = (u64)(c + 1) * kChunk <= n;
             if (full && aligned) {
-                if (M > kDecLut1Bits) decode_chunk<true, true, DT, DEEP>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
-                else decode_chunk<true, false, DT, DEEP>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                if (M > kDecLut1Bits) decode_chunk<true, true, DT, DEEP, VERIFY>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
+                else decode_chunk<true, false, DT, DEEP, VERIFY>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, zero_bits, raise);
             } else {
-                decode_chunk<false, true, DT>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
+                decode_chunk<false, true, DT, false, VERIFY>(blob, w_ref, n, c, o0, o1, L, pay, pay_words, P1, P2, K, area, full ? zero_bits : 0u, raise);
             }
             c = cn; o0 = n0; o1 = n1;
         }
@@ -1074,13 +1098,15 @@ void launch_decode_fused(const BlobList& blobs, int first, int count, void* w_re
     }
 }
 
+// w_ref null: the verifying sweep (nothing but the blob is read)
 void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, int set, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
     if (nchunks == 0) return;
+    const bool verify = w_ref == nullptr;
     const u64 blocks = balanced_workers((nchunks + 3) / 4, (u64)tune.num_cu * tune.decode_blocks_per_cu);
     const dim3 grid((u32)blocks), wg(256);
-    const int al = aligned_rows(w_ref, dtype);
+    const int al = verify ? 1 : aligned_rows(w_ref, dtype);
     // LDS payload areas: the usual size when every compute unit gets as many workgroups as fit beside each other
     // (4); with fewer workgroups than that, what the unit's LDS leaves each, so that chunks with long payloads
     // (codes of 5 and more bits on average) need not read their lane strings from memory
@@ -1098,6 +1124,10 @@ void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Work
     // on memory, so the kernel's form with rows fetched far ahead runs (it needs more registers than would let more
     // workgroups share a unit).
     const bool deep = per_cu <= 2;
+    if (verify) {
+        hipLaunchKernelGGL((k_decode<kF32, false, true>), grid, wg, lds, s, blob, (void*)nullptr, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set);
+        return;
+    }
 #define LC_DECODE(DT) \
     if (deep) hipLaunchKernelGGL((k_decode<DT, true>), grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set); \
     else hipLaunchKernelGGL((k_decode<DT, false>), grid, wg, lds, s, blob, w_ref, (u64)n, ws, (u32)nchunks, al, (u64)epoch, host, pay_words, (u32)set)

@@ -130,7 +130,7 @@ __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsW
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
 enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecTable, kSlotSpecSweep,
-            kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kSlotHistKeys, kSlotPackKeys, kNumSlots };
+            kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kSlotHistKeys, kSlotPackKeys, kSlotVerify, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
 // variables (read once) for sweeps.
@@ -220,7 +220,7 @@ struct BlobList { const uint8_t* p[kMaxSets]; };
 // Checks blobs.p[first .. first+count) into dec_set[first ..] and host->bytes / max_len[first ..].
 void launch_dec_check(const BlobList& blobs, int first, int count, uint64_t n, int dtype, uint64_t max_total, Workspace* ws,
                       uint64_t epoch, HostResult* host, hipStream_t s);
-// (set: which of the workspace's decode sets the check kernel filled for this blob)
+// (set: which of the workspace's decode sets the check kernel filled for this blob; w_ref null: only verify the lane strings)
 void launch_decode(const uint8_t* blob, void* w_ref, uint64_t n, int dtype, Workspace* ws, int set, uint64_t epoch, HostResult* host,
                    const Tuning& tune, hipStream_t s);
 // Both apply blobs.p[first .. first+count), count <= kMaxMany, using dec_set[first ..]; the fused

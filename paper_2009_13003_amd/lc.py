@@ -36,6 +36,8 @@ _lib.lc_encode_sized.restype = _i64
 _lib.lc_encode_sized.argtypes = [_vp, _vp, _u64, _int, _vp, _sz, _int, _vp]
 _lib.lc_decode_sized.restype = _i64
 _lib.lc_decode_sized.argtypes = [_vp, _sz, _vp, _u64, _int, _vp]
+_lib.lc_verify.restype = _i64
+_lib.lc_verify.argtypes = [_vp, _sz, _u64, _int, _vp]
 _lib.lc_encode_static.restype = _int
 _lib.lc_encode_static.argtypes = [_vp, _vp, _u64, _int, _vp, _vp]
 _lib.lc_encode_t.restype = _i64
@@ -190,6 +192,7 @@ def lc_decode_t(blob, w_ref, stream=None, n=None):
 
 
 OPT_KEY_STAGING, STAGING_AUTO, STAGING_ALWAYS, STAGING_NEVER = 1, 0, 1, 2
+OPT_VERIFY_FIRST = 2
 
 
 def lc_set_option(option, value):
@@ -391,6 +394,17 @@ def lc_encode_wait(ticket):
     if r < 0:
         raise LcError(-r)
     return r, bool(used.value)
+
+
+def lc_verify(blob, n, dtype=torch.float32, stream=None, blob_bytes=None):
+    """Checks a blob from end to end (header, tables, offsets, every lane string) without touching any parameters;
+    returns the blob's size in bytes; raises LcError on a negative status."""
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    size = blob.numel() if blob_bytes is None else blob_bytes
+    r = int(_lib.lc_verify(ctypes.c_void_p(blob.data_ptr()), size, n, DTYPES[dtype], _stream(stream)))
+    if r < 0:
+        raise LcError(-r)
+    return r
 
 
 def lc_decode(blob, w_ref, stream=None, n=None):

@@ -43,6 +43,7 @@ def check_case(lc, w, w_ref, nbits, label=""):
     blob_cpu = orc.encode(w_h, ref_h, nbits)
     blob_gpu = out[:size].cpu().numpy()
     assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    assert lc.lc_verify(out[:size], n) == size            # (the check that reads the blob only accepts it, too)
     rec = w_ref.clone()
     assert lc.lc_decode(out, rec) == size
     orc.decode(blob_cpu, ref_h)
@@ -225,6 +226,125 @@ def test_decode_rejects_damaged_blobs(lc):
     assert not all(outcomes)
     rec = w_ref.clone()
     assert lc.lc_decode(good, rec) == size
+
+
+@pytest.fixture
+def verify_first(lc):
+    lc.lc_set_option(lc.OPT_VERIFY_FIRST, 1)
+    yield
+    lc.lc_set_option(lc.OPT_VERIFY_FIRST, 0)
+
+
+def payload_damage_cases(blob_t, nchunks, count, seed):
+    """`count` copies of the blob with one bit flipped somewhere in the chunk area (lane lengths or lane strings)."""
+    area = 512 + (4 * (nchunks + 1) + 15) // 16 * 16
+    rng = np.random.RandomState(seed)
+    out = []
+    for _ in range(count):
+        b = blob_t.clone()
+        at = int(rng.randint(area, b.numel()))
+        b[at] ^= 1 << int(rng.randint(0, 8))
+        out.append((at, b))
+    return out
+
+
+@pytest.mark.parametrize("nbits,scale", [(3, 1e-3), (4, 1e-3), (2, 1e-5)])
+def test_verify_gives_the_oracles_verdict_on_damaged_payloads(lc, nbits, scale):
+    """lc_verify reads the blob only: on 60 blobs with one bit flipped in the chunk area (a lane length, a lane string,
+    the padding) it says what the oracle's decoder says; a truncated buffer and a blob for another vector are refused."""
+    n = 7 * 16384 + 4321
+    w, w_ref = laplace_case(n, seed=700 + nbits, scale=scale)
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode(w, w_ref, nbits, out)
+    good = out[:size].clone()
+    assert lc.lc_verify(good, n) == size
+    verdicts = []
+    for k, (at, b) in enumerate(payload_damage_cases(good, 8, 60, 40 + nbits)):
+        print("verify: damaged byte", at, flush=True)
+        try:
+            orc.decode(b.cpu().numpy(), w_ref.cpu().numpy()); cpu_ok = True
+        except orc.OracleError as e:
+            assert e.status == 4; cpu_ok = False
+        try:
+            assert lc.lc_verify(b, n) == size; gpu_ok = True
+        except lc.LcError as e:
+            assert e.status == lc.ERR_BAD_BLOB; gpu_ok = False
+        assert gpu_ok == cpu_ok, (k, at)
+        verdicts.append(gpu_ok)
+    assert not all(verdicts) and any(verdicts)            # (a flip inside a code can give another valid code; one in the padding is refused)
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_verify(good, n, blob_bytes=size - 4)
+    assert e.value.status == lc.ERR_BAD_BLOB
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_verify(good, n + 1)
+    assert e.value.status == lc.ERR_BADARG
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_verify(good, n, torch.bfloat16)
+    assert e.value.status == lc.ERR_BADARG
+    z = torch.empty(0, device=DEV)
+    oz = lc.alloc_out(0, nbits, DEV)
+    empty = lc.lc_encode(z, z, nbits, oz)
+    assert lc.lc_verify(oz[:empty], 0) == empty
+
+
+def test_restore_that_verifies_first_leaves_w_ref_alone(lc, verify_first):
+    """With LC_OPT_VERIFY_FIRST a blob whose payload is damaged leaves w_ref untouched (without the option the sweep
+    finds the damage half way); good blobs restore as always; in lc_decode_many one damaged blob among good ones stops
+    the whole restore before the first sweep.  16-bit and binary64 parameters too."""
+    n = 9 * 16384 + 100
+    w, w_ref = laplace_case(n, seed=750)
+    blob = torch.from_numpy(check_case(lc, w, w_ref, 3, "verify first, good blob")).to(DEV)
+    refused = 0
+    for at, b in payload_damage_cases(blob, 10, 30, 51):
+        try:
+            orc.decode(b.cpu().numpy(), w_ref.cpu().numpy()); cpu_ok = True
+        except orc.OracleError:
+            cpu_ok = False
+        rec = w_ref.clone()
+        if cpu_ok:
+            assert lc.lc_decode(b, rec) == blob.numel()
+            ref_h = w_ref.cpu().numpy(); orc.decode(b.cpu().numpy(), ref_h)
+            assert np.array_equal(bits(rec.cpu().numpy()), bits(ref_h))
+        else:
+            refused += 1
+            with pytest.raises(lc.LcError) as e:
+                lc.lc_decode(b, rec)
+            assert e.value.status == lc.ERR_BAD_BLOB
+            assert torch.equal(rec.view(torch.int32), w_ref.view(torch.int32)), "w_ref touched (damage at byte %d)" % at
+    assert refused >= 5
+    # several checkpoints: the third blob's payload damaged
+    g = torch.Generator(device=DEV); g.manual_seed(751)
+    deltas = [1e-3 * torch.randn(n, generator=g, device=DEV) for _ in range(5)]
+    tracked, blobs = encode_chain(lc, w_ref, deltas, [3] * 5)
+    rec = w_ref.clone()
+    lc.lc_decode_many(blobs, rec)
+    assert np.array_equal(bits(rec.cpu().numpy()), bits(oracle_restore(w_ref, blobs)))
+    area = 512 + (4 * 11 + 15) // 16 * 16
+    bad = [b.clone() for b in blobs]
+    bad[2][area + 60] ^= 0x7F                           # lane 30's length in chunk 0: its string no longer ends where it says
+    with pytest.raises(orc.OracleError):
+        orc.decode(bad[2].cpu().numpy(), w_ref.cpu().numpy())
+    rec = w_ref.clone()
+    with pytest.raises(lc.LcError) as e:
+        lc.lc_decode_many(bad, rec)
+    assert e.value.status == lc.ERR_BAD_BLOB and torch.equal(rec.view(torch.int32), w_ref.view(torch.int32))
+    # other element types
+    for tdt in (torch.bfloat16, torch.float64):
+        wt, rt = w.to(tdt), w_ref.to(tdt)
+        out = lc.alloc_out(n, 3, DEV)
+        size = lc.lc_encode_t(wt, rt, 3, out)
+        rec = rt.clone()
+        assert lc.lc_decode_t(out, rec) == size
+        plain = rt.clone()
+        lc.lc_set_option(lc.OPT_VERIFY_FIRST, 0)
+        assert lc.lc_decode_t(out, plain) == size
+        lc.lc_set_option(lc.OPT_VERIFY_FIRST, 1)
+        assert torch.equal(rec.view(torch.int16 if tdt == torch.bfloat16 else torch.int64), plain.view(torch.int16 if tdt == torch.bfloat16 else torch.int64))
+        b = out[:size].clone(); b[area + 60] ^= 0x7F
+        rec = rt.clone()
+        with pytest.raises(lc.LcError):
+            lc.lc_decode_t(b, rec)
+        assert torch.equal(rec.view(torch.int16 if tdt == torch.bfloat16 else torch.int64), rt.view(torch.int16 if tdt == torch.bfloat16 else torch.int64))
 
 
 def test_calls_with_stated_buffer_sizes(lc):
@@ -1183,6 +1303,7 @@ def check_case64(lc, w, w_ref, nbits, label=""):
     blob_cpu = orc.encode64(w_h, ref_h, nbits)
     blob_gpu = out[:size].cpu().numpy()
     assert blob_gpu.size == blob_cpu.size and np.array_equal(blob_gpu, blob_cpu), first_diff(blob_gpu, blob_cpu)
+    assert lc.lc_verify(out[:size], n, torch.float64) == size
     rec = w_ref.clone()
     assert lc.lc_decode_t(out, rec) == size
     orc.decode64(blob_cpu, ref_h)
