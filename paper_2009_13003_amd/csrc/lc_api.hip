@@ -228,7 +228,7 @@ bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t
 constexpr size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 constexpr size_t encode_scratch_bytes(uint64_t nc, int nbits) {
     return kWorkspaceHead + up256(4 * nc) + (size_t)(nc * (kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u)) * 4) +
-           256 + up256(16 * nc);                                  // + the per-batch maxima of sweep 1
+           256 + up256(kPartMaxBytes * nc);                       // + the per-batch maxima of sweep 1
 }
 // ... and with staged keys behind that: a byte and a bit per element of every whole batch
 size_t staged_scratch_bytes(uint64_t n, int nbits) {
@@ -237,7 +237,7 @@ size_t staged_scratch_bytes(uint64_t n, int nbits) {
 struct Scratch {
     Workspace* ws;
     uint32_t *group_words, *chunk_maxexp, *chunk_list, *chunk_bits, *prov;
-    uint8_t* batch_max;                                           // one byte per 4 KiB batch of sweep 1 (16 per chunk at most), behind the slots
+    uint8_t* batch_max;                                           // the largest exponent of every 4 KiB batch of sweep 1, kPartMaxBytes per chunk, behind the slots
     uint32_t slot_words;
     Scratch(void* base, uint64_t nc, int nbits) {
         ws = static_cast<Workspace*>(base);
@@ -251,7 +251,7 @@ struct Scratch {
     }
     KeyPlanes keys(uint64_t n) const {                            // (only an area of staged_scratch_bytes has them)
         const uint64_t nc = num_chunks_of(n);
-        uint8_t* e = batch_max + up256(16 * nc);
+        uint8_t* e = batch_max + up256(kPartMaxBytes * nc);
         return KeyPlanes{e, reinterpret_cast<uint16_t*>(e + up256(key_exp_bytes(n)))};
     }
 };

@@ -231,7 +231,7 @@ __device__ __forceinline__ float4 load_unit64(const void* __restrict__ p, u64 un
 
 template <bool ALIGNED>
 __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, const void* __restrict__ w_ref,
-                                                 u64 n, Ext64* ext, u32* chunk_maxexp) {
+                                                 u64 n, Ext64* ext, u32* chunk_maxexp, uint16_t* part_max) {
     __shared__ u32 h[kBuckets64 * kHistCopies64];
     constexpr int EPU = 2;
     const u32 tid = threadIdx.x, nthr = blockDim.x;
@@ -266,7 +266,12 @@ __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, con
 #pragma unroll
         for (int k = 0; k < PF; ++k) m = count_unit(a[k], bb[k], m);
         m = wave_max_u32(m);
-        if ((tid & (kW - 1)) == 0) atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
+        // (a batch is 4 KiB of each array: the largest exponent of every such part lets sweep 2 read a mostly merged
+        // chunk part by part, as for the other element types; 11 exponent bits: two bytes each)
+        if ((tid & (kW - 1)) == 0) {
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
+            if (part_max) part_max[batch] = (uint16_t)m;
+        }
     };
     if (b < nbatch) {
         fetch(a0, b0, b);
@@ -332,16 +337,19 @@ __device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int
     if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
     u32 total = 0;
     bool nonfinite = false, zero_class = false;
-    // binary32: all eight counts of this lane first, the four ranking steps below then run without waiting on memory
-    u64 cnt0[4], cnt1[4];
-    if (EB == 8) {
+    // all counts of this lane first (8, or 64 for binary64), the ranking steps below then run without waiting on memory
+    // (binary64, 32 steps with the loads inside the loop: 28 us for the kernel instead of 24)
+    u64 cnt0[kSteps], cnt1[kSteps];
 #pragma unroll
-        for (u32 step = 0; active && step < 4; ++step) { cnt0[step] = hist[kEmax - (step * kW + lane)]; cnt1[step] = hist[kNeg + kEmax - (step * kW + lane)]; }
+    for (u32 step = 0; step < kSteps; ++step) {
+        cnt0[step] = active ? hist[kEmax - (step * kW + lane)] : 0;
+        cnt1[step] = active ? hist[kNeg + kEmax - (step * kW + lane)] : 0;
     }
-#pragma unroll 4
-    for (u32 step = 0; active && step < kSteps; ++step) {
+#pragma unroll
+    for (u32 step = 0; step < kSteps; ++step) {
+        if (!active) break;
         const u32 E = kEmax - (step * kW + lane);
-        const u64 c0 = EB == 8 ? cnt0[step & 3] : hist[E], c1 = EB == 8 ? cnt1[step & 3] : hist[kNeg + E];
+        const u64 c0 = cnt0[step], c1 = cnt1[step];
         const bool normal = E >= 1 && E <= kEmax - 1;
         const bool cand0 = normal && c0 > 0, cand1 = normal && c1 > 0;
         const u64 m0 = __ballot(cand0), m1 = __ballot(cand1), lt = (1ull << lane) - 1;
@@ -998,6 +1006,20 @@ __device__ __forceinline__ bool parts_to_read(const uint8_t* maxima, u32 parts_p
     return (u32)__popc(mask) <= parts_per_chunk / 4;
 }
 
+// The same for binary64 parameters: 32 parts of 512 elements per chunk, two bytes per maximum (11 exponent bits).
+__device__ __forceinline__ bool parts_to_read64(const uint16_t* maxima, u32 min_kept_exp, u32 whole, u32* parts) {
+    const u32* p = reinterpret_cast<const u32*>(maxima);
+    u32 mask = 0;
+    for (u32 i = 0; i < 16; ++i) {
+        const u32 word = load_uniform(p + i);
+        mask |= ((word & 0xFFFFu) >= min_kept_exp ? 1u : 0u) << (2 * i);
+        mask |= ((word >> 16) >= min_kept_exp ? 1u : 0u) << (2 * i + 1);
+    }
+    if (whole < 32) mask &= (1u << whole) - 1u;
+    *parts = mask;
+    return (u32)__popc(mask) <= 8u;
+}
+
 // The chunks of one vector that have to be read, dealt round-robin to the wavefronts of the grid: all of
 // them, or with chunk_list the `listed` ones named there.
 struct VectorChunks {
@@ -1009,6 +1031,7 @@ struct VectorChunks {
     const u32* chunk_list; u32 listed;
     u32 pos;
     const uint8_t* batch_max; u32 parts_per_chunk, min_kept_exp, cl_merged;     // what sweep 1 recorded per 4 KiB batch, or null
+    bool wide;                   // binary64: two bytes per recorded maximum
     __device__ __forceinline__ u32 merged_codelen() const { return cl_merged; }
     __device__ __forceinline__ ChunkRef ref(u32 c, bool valid) const {
         ChunkRef ch;
@@ -1026,7 +1049,8 @@ struct VectorChunks {
             const u64 inside = n - (u64)c * kChunk, part_elems = kChunk / parts_per_chunk;
             const u32 whole = inside >= kChunk ? parts_per_chunk : (u32)(inside / part_elems);
             // (less than one whole part: the guarded path)
-            ch.by_parts = whole != 0 && parts_to_read(batch_max + (u64)c * parts_per_chunk, parts_per_chunk, min_kept_exp, whole, &ch.parts);
+            ch.by_parts = whole != 0 && (wide ? parts_to_read64(reinterpret_cast<const uint16_t*>(batch_max) + (u64)c * parts_per_chunk, min_kept_exp, whole, &ch.parts)
+                                              : parts_to_read(batch_max + (u64)c * parts_per_chunk, parts_per_chunk, min_kept_exp, whole, &ch.parts));
             if (ch.by_parts) ch.fast = false;        // off the pipelined path: see pack_chunk_parts
         }
         return ch;
@@ -1267,9 +1291,83 @@ __device__ __forceinline__ void pack_chunk64(const ChunkRef& ch, PackLds64& L, u
     finish_lane_sizes(ch, nb, nw);
 }
 
+// A chunk of which at most a quarter of the 4 KiB parts (2 rows of doubles each) hold anything but merged elements:
+// see pack_chunk_parts.
+__device__ __noinline__ void pack_chunk64_parts(const ChunkRef ch, u32 cl_merged, PackLds64& L, u32 K) {
+    constexpr u32 kRowsPerPart = 2, kParts = kR / kRowsPerPart;
+    const u32 lane = lane_id();
+    u32* lane_words = ch.slot + kLaneBitsWords + lane;
+    const u32 mm = lane & (kMmCopies64 - 1);
+    u64 acc = 0;
+    u32 nb = 0, nw = 0;
+    auto flush = [&]() {
+        if (nb >= 32) { lane_words[nw * kW] = (u32)(acc >> (nb - 32)); ++nw; nb -= 32; }
+    };
+    const u32 len_merged = cl_merged & 31, per_step = len_merged ? 32 / len_merged : 1;
+    u32 run = 0;                                                             // per_step copies of the merged code
+    for (u32 i = 0; i < per_step; ++i) run = (run << len_merged) | (cl_merged >> 5);
+    auto code_element = [&](double a, double b) {
+        const u64 u = delta_bits(a, b);
+        const u32 sy = L.sym[bucket_of(u)];
+        const u32 cl = L.codelen[sy];
+        if (sy < K) { atomicMin(&L.mn[sy * kMmCopies64 + mm], u); atomicMax(&L.mx[sy * kMmCopies64 + mm], u); }
+        acc = (acc << (cl & 31)) | (cl >> 5);
+        nb += cl & 31;
+    };
+    const u64 n = ch.n, base = (u64)ch.c * kChunk, inside = n - base;
+    const u32 whole = inside >= kChunk ? kParts : (u32)(inside / (kRowsPerPart * kRowElems));
+    auto row_idx = [&](u32 r) { return base + (u64)r * kRowElems + lane * kV; };
+    for (u32 p = 0; p < whole; ++p) {
+        if ((ch.parts >> p) & 1u) {
+            double xa[kRowsPerPart][4], xb[kRowsPerPart][4];
+#pragma unroll
+            for (u32 k = 0; k < kRowsPerPart; ++k) {
+                load_row64<true>(ch.w, row_idx(p * kRowsPerPart + k), n, xa[k]);
+                load_row64<true>(ch.w_ref, row_idx(p * kRowsPerPart + k), n, xb[k]);
+            }
+#pragma unroll
+            for (u32 k = 0; k < kRowsPerPart; ++k) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    code_element(xa[k][v], xb[k][v]);
+                    if (v & 1) flush();
+                }
+            }
+        } else {
+            for (u32 left = kRowsPerPart * kV; left != 0;) {
+                const u32 k = left < per_step ? left : per_step;
+                acc = (acc << (k * len_merged)) | (u64)(run >> ((per_step - k) * len_merged));
+                nb += k * len_merged;
+                flush();
+                left -= k;
+            }
+        }
+    }
+    if (whole < kParts) {
+        // a ragged chunk's last rows (fewer than one part), elements past the end left out
+        double xa[kRowsPerPart][4], xb[kRowsPerPart][4];
+#pragma unroll
+        for (u32 k = 0; k < kRowsPerPart; ++k) {
+            load_row64<false>(ch.w, row_idx(whole * kRowsPerPart + k), n, xa[k]);
+            load_row64<false>(ch.w_ref, row_idx(whole * kRowsPerPart + k), n, xb[k]);
+        }
+#pragma unroll
+        for (u32 k = 0; k < kRowsPerPart; ++k) {
+            const u64 idx = row_idx(whole * kRowsPerPart + k);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                if (idx + v < n) code_element(xa[k][v], xb[k][v]);
+                if (v & 1) flush();
+            }
+        }
+    }
+    if (nb > 0) lane_words[nw * kW] = (u32)(acc << (32 - nb));
+    finish_lane_sizes(ch, nb, nw);
+}
+
 __global__ __launch_bounds__(64) void k_pack64(const void* __restrict__ w, const void* __restrict__ w_ref, u64 n,
                                                EncState* ws, Ext64* ext, u32* chunk_bits, u32* group_words,
-                                               const u32* chunk_maxexp, const u32* chunk_list, u32* prov,
+                                               const u32* chunk_maxexp, const u32* chunk_list, const uint8_t* part_max, u32* prov,
                                                u32 slot_words, u32 nchunks, int aligned) {
     __shared__ PackLds64 L;
     const u32 lane = threadIdx.x;
@@ -1281,10 +1379,12 @@ __global__ __launch_bounds__(64) void k_pack64(const void* __restrict__ w, const
     for (u32 i = lane; i < kMaxSym * kMmCopies64; i += kW) { L.mn[i] = ~0ull; L.mx[i] = 0; }
     __syncthreads();
     VectorChunks src = {w, w_ref, n, prov, slot_words, chunk_bits, group_words, nchunks, aligned != 0, K << 3, true,
-                        chunk_list, chunk_list ? ws->list_count : 0, 0, nullptr, 16u, 0u, 0u};
+                        chunk_list, chunk_list ? ws->list_count : 0, 0, chunk_list ? part_max : nullptr, 32u, T.min_kept_exp,
+                        T.codelen[K], true};
     if (chunk_list) note_merged_chunks(T, n, chunk_bits, group_words, chunk_maxexp);
     for (ChunkRef ch = src.take(); ch.valid; ch = src.take()) {
-        if (ch.fast) pack_chunk64<true>(ch, L, K);
+        if (ch.by_parts) pack_chunk64_parts(ch, src.merged_codelen(), L, K);
+        else if (ch.fast) pack_chunk64<true>(ch, L, K);
         else pack_chunk64<false>(ch, L, K);
     }
     __syncthreads();
@@ -1740,8 +1840,9 @@ void launch_hist(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     if (dtype == kF64) {
-        if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist64<true>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp);
-        else hipLaunchKernelGGL(k_hist64<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp);
+        uint16_t* part_max = reinterpret_cast<uint16_t*>(batch_max);
+        if (aligned16(w) && aligned16(w_ref)) hipLaunchKernelGGL(k_hist64<true>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp, part_max);
+        else hipLaunchKernelGGL(k_hist64<false>, dim3((u32)blocks), dim3(threads), 0, s, w, w_ref, (u64)n, &ws->ext64, chunk_maxexp, part_max);
         return;
     }
     if (dtype == kBF16) launch_hist_t<kBF16>(w, w_ref, n, ws, chunk_maxexp, batch_max, (u32)blocks, threads, s);
@@ -1805,7 +1906,7 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     const u32 blocks = even_waves(nchunks, (u64)tune.num_cu * tune.pack_waves_per_cu);
     const int al = aligned_rows(w, dtype) && aligned_rows(w_ref, dtype);
     const dim3 grid(blocks), wg(64);
-    if (dtype == kF64) hipLaunchKernelGGL(k_pack64, grid, wg, 0, s, w, w_ref, (u64)n, ws, &ws->ext64, chunk_bits, group_words, chunk_maxexp, chunk_list, prov, slot_words, (u32)nchunks, al);
+    if (dtype == kF64) hipLaunchKernelGGL(k_pack64, grid, wg, 0, s, w, w_ref, (u64)n, ws, &ws->ext64, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kBF16) hipLaunchKernelGGL(k_pack<kBF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
     else if (dtype == kF16) hipLaunchKernelGGL(k_pack<kF16>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
     else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);

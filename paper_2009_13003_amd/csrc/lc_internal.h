@@ -95,7 +95,7 @@ struct EncState {
 // Fixed part of the per-device scratch.  It is followed by group_words[kMaxGroups] and
 // chunk_maxexp[kMaxChunks] (u32, at fixed places so that they can be left cleared from one call to the
 // next), chunk_list[kMaxChunks] (u32), chunk_bits[num_chunks] (u32, padded to 256 bytes), one slot of
-// slot_words_of(nbits) 32-bit words per chunk and, 256-byte aligned behind the slots, 16 bytes per chunk for the
+// slot_words_of(nbits) 32-bit words per chunk and, 256-byte aligned behind the slots, kPartMaxBytes per chunk for the
 // largest exponent of every 4 KiB batch of sweep 1.
 // What an encode of binary64 parameters keeps instead of EncState's counts, extremes and bucket map: 2^12
 // (sign, exponent) buckets, 52-bit mantissas (Section 3.1.1, footnote on the bucket count).  Left cleared like them.
@@ -188,6 +188,9 @@ struct Seg {
 };
 constexpr int kMaxBatch = 1024;
 constexpr uint32_t kPartBytes = 16;
+// ... of a single-vector call: one byte per 4 KiB part (16 parts of 4-byte elements, 8 of 2-byte), two bytes each for the
+// 32 parts of 8-byte elements
+constexpr uint32_t kPartMaxBytes = 64;
 struct BatchArgs {
     Seg* segs; EncState* states; Result* results;     // device (results: mapped host memory)
     uint32_t* seg_of_chunk; uint32_t* group_words; uint32_t* chunk_bits; uint32_t* prov;

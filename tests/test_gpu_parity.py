@@ -1152,6 +1152,27 @@ def quiet_chunk_case(n, seed, quiet, tiny=2.0 ** -30):
 
 
 @pytest.mark.parametrize("nbits", [2, 3, 4])
+def test_fp64_encode_of_quiet_chunks_and_parts(lc, nbits):
+    """binary64 parameters: whole chunks below every kept bucket are passed over, and a chunk of which only a few
+    4 KiB parts (512 doubles) hold a kept element is coded part by part: loud elements in the first, the last and a
+    middle part of otherwise quiet chunks, more loud parts than the quarter that still goes by parts, a quiet ragged
+    tail with one loud element, an unaligned vector.  Blob and restore as the oracle's."""
+    nchunks = 70
+    n = nchunks * 16384 + 1500
+    quiet = [0, 1, 5, 63, 64, 65] + list(range(20, 40)) + [69, 70]
+    w, w_ref = quiet_chunk_case(n, 500 + nbits, quiet)
+    w, w_ref = w.double(), w_ref.double()
+    loud = lambda i: float(w_ref[i]) + 2.0 ** -11
+    for c, offs in ((1, [3]), (5, [0, 16383]), (22, [512 * 7 + 5, 512 * 8 - 1]), (25, [512 * k + 17 for k in range(8)]),
+                    (26, [512 * k + 17 for k in range(9)]), (30, [512 * k for k in range(32)]), (70, [1499]), (69, [16384 - 512, 100])):
+        for o in offs:
+            w[c * 16384 + o] = loud(c * 16384 + o)
+    check_case64(lc, w, w_ref, nbits, "fp64 quiet chunks and parts")
+    check_case64(lc, w[1:], w_ref[1:], nbits, "fp64 quiet chunks, unaligned")
+    check_case64(lc, w[:3 * 16384 + 700], w_ref[:3 * 16384 + 700], nbits, "fp64 quiet, short ragged tail")
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4])
 def test_batched_encode_of_chunks_below_their_tensors_kept_buckets(lc, nbits):
     """A batched call passes over full chunks whose largest delta lies below every kept bucket of *their own* tensor
     (the counting sweep notes every chunk's maximum, a list kernel tells them apart once the tables exist): quiet
