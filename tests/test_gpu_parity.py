@@ -1460,6 +1460,99 @@ def test_seeded_cases_all_types(lc, seed):
         assert np.array_equal(raw16(rec).view(np.uint16), ref_h.view(np.uint16))
 
 
+def seeded_quiet_tensor(rng, g, tdt):
+    """A tensor of 0..8 chunks and a ragged end, deltas over 1..6 binades at a random scale; whole chunks made quiet
+    (zero, or scaled down by 2^8..2^29) with none, a few or many loud elements left in them."""
+    C = 16384
+    nchunks = int(rng.randint(0, 9))
+    n = nchunks * C + int(rng.choice([0, 0, 1, 77, 1023, 4096, 4097, 16383]))
+    off = int(rng.choice([0, 0, 0, 1, 2]))
+    scale_exp, binades = int(rng.randint(5, 20)), int(rng.randint(1, 7))
+    r = 0.05 * torch.randn(n + off, generator=g, device=DEV)
+    e = torch.randint(scale_exp, scale_exp + binades, (n + off,), generator=g, device=DEV).float()
+    d = torch.exp2(-e) * (1 + torch.rand(n + off, generator=g, device=DEV))
+    d = d * (2 * torch.randint(0, 2, (n + off,), generator=g, device=DEV).float() - 1)
+    for c in rng.choice(nchunks + 1, size=int(rng.randint(0, nchunks + 2)), replace=False):
+        lo, hi = off + int(c) * C, min(n + off, off + (int(c) + 1) * C)
+        if lo >= hi:
+            continue
+        keep = d[lo:hi].clone()
+        d[lo:hi] = 0 if int(rng.randint(0, 3)) == 0 else keep * 2.0 ** -int(rng.randint(8, 30))
+        k = int(rng.choice([0, 0, 1, 3, 40]))
+        if k:
+            idx = torch.from_numpy(rng.randint(0, hi - lo, size=k)).to(DEV)
+            d[lo:hi][idx] = keep[idx]
+    r = torch.where(d.abs() < 1e-7, torch.zeros_like(r), r)      # tiny deltas survive the subtraction only next to a zero
+    if tdt == torch.float32:
+        return (r + d)[off:], r[off:]
+    r = r.to(tdt)
+    return (r.float() + d).to(tdt)[off:], r[off:]
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_seeded_batches_single_calls_and_verdicts(lc, seed):
+    """Seeded lists of 1..8 tensors with quiet stretches: every blob of the batched call is the oracle's and the
+    single call's; lc_verify accepts it; restores agree with the oracle; one flipped bit in the chunk area gets the
+    oracle's verdict from lc_verify and lc_decode, and with LC_OPT_VERIFY_FIRST (odd seeds) a refused blob leaves
+    the parameters alone; the batched restore equals the single ones."""
+    C = 16384
+    rng = np.random.RandomState(9000 + seed)
+    g = torch.Generator(device=DEV); g.manual_seed(9000 + seed)
+    tdt = [torch.float32, torch.float32, torch.bfloat16, torch.float16][seed % 4]
+    code = {torch.float32: orc.DT_F32, torch.bfloat16: orc.DT_BF16, torch.float16: orc.DT_F16}[tdt]
+    view = torch.int32 if tdt == torch.float32 else torch.int16
+    host = (lambda t: t.cpu().numpy()) if tdt == torch.float32 else raw16
+    oracle_encode = (lambda a, b, x: orc.encode(a, b, x)) if tdt == torch.float32 else (lambda a, b, x: orc.encode_t(a, b, x, code))
+    oracle_decode = (lambda blob, a: orc.decode(blob, a)) if tdt == torch.float32 else (lambda blob, a: orc.decode_t(blob, a, code))
+    count, nbits = int(rng.randint(1, 9)), int(rng.randint(1, 5))
+    print("seeded batch", seed, tdt, "tensors=%d nbits=%d" % (count, nbits), flush=True)
+    ws, rs = zip(*[seeded_quiet_tensor(rng, g, tdt) for _ in range(count)])
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w in ws]
+    sizes = lc.lc_encode_batch(list(ws), list(rs), nbits, outs)
+    lc.lc_set_option(lc.OPT_VERIFY_FIRST, seed & 1)
+    try:
+        for t, (w, r, o, size) in enumerate(zip(ws, rs, outs, sizes)):
+            n = w.numel()
+            rh = host(r)
+            blob_cpu = oracle_encode(host(w), rh, nbits)
+            assert size == blob_cpu.size and np.array_equal(o[:size].cpu().numpy(), blob_cpu), (t, "batched blob")
+            assert lc.lc_verify(o[:size], n, tdt) == size
+            o2 = lc.alloc_out(n, nbits, DEV)
+            assert lc.lc_encode_t(w, r, nbits, o2) == size and torch.equal(o2[:size], o[:size]), (t, "single blob")
+            rec = r.clone()
+            assert lc.lc_decode_t(o[:size], rec) == size
+            oracle_decode(blob_cpu, rh)
+            assert np.array_equal(host(rec).view(np.uint8), rh.view(np.uint8)), (t, "restore")
+            if size > 700:
+                area = 512 + (4 * ((n + C - 1) // C + 1) + 15) // 16 * 16
+                b = o[:size].clone()
+                at = int(rng.randint(area, size)); b[at] ^= 1 << int(rng.randint(0, 8))
+                try:
+                    oracle_decode(b.cpu().numpy(), host(r)); ok = True
+                except orc.OracleError:
+                    ok = False
+                try:
+                    lc.lc_verify(b, n, tdt); verified = True
+                except lc.LcError:
+                    verified = False
+                rec = r.clone()
+                try:
+                    lc.lc_decode_t(b, rec); decoded = True
+                except lc.LcError:
+                    decoded = False
+                assert verified == ok and decoded == ok, (t, at)
+                if not ok and (seed & 1):
+                    assert torch.equal(rec.view(view), r.view(view)), (t, at, "parameters touched")
+    finally:
+        lc.lc_set_option(lc.OPT_VERIFY_FIRST, 0)
+    recs = [r.clone() for r in rs]
+    assert lc.lc_decode_batch(outs, recs) == sizes
+    for t, (rec, r, o, size) in enumerate(zip(recs, rs, outs, sizes)):
+        single = r.clone()
+        lc.lc_decode_t(o[:size], single)
+        assert torch.equal(rec.view(view), single.view(view)), (t, "batched restore")
+
+
 @pytest.mark.parametrize("steps,offset", [(2, 0), (5, 0), (8, 0), (3, 1)])
 def test_fused_restore_long_codes(lc, steps, offset):
     """Every blob has codes of up to 15 bits (nbits = 4, magnitudes spread geometrically over many binades, so the
