@@ -256,8 +256,7 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
     const u32 shr1 = 64 - P1, shr2 = 64 - P2;
     const u64 base = (u64)c * kChunk;
     if constexpr (VERIFY) {
-        for (u32 r = 0; r < kR && (FAST || base + (u64)r * kRowElems < n); ++r) {
-            const u64 idx = base + (u64)r * kRowElems + lane * kV;
+        auto symbols_of_row = [&](u64 idx) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 if (FAST || idx + v < n) {
@@ -271,6 +270,20 @@ __device__ __forceinline__ void decode_rows(const u32* words, u32 nwords, u32 fi
                 }
                 if ((v & 1) && br.avail <= 32) br.refill();
             }
+        };
+        if (sparse && row_zero_bits != 0) {
+            // a chunk with few kept symbols: a whole row of merged symbols whose code is zeros is passed over as in
+            // the restoring sweep (in a loop of its own: elsewhere the test costs more than it saves)
+            for (u32 r = 0; r < kR && (FAST || base + (u64)r * kRowElems < n); ++r) {
+                if ((FAST || base + (u64)(r + 1) * kRowElems <= n) && !__any((u32)(br.win >> (64 - row_zero_bits)) != 0)) {
+                    br.win <<= row_zero_bits; br.avail -= row_zero_bits;
+                    if (br.avail <= 32) br.refill();
+                    continue;
+                }
+                symbols_of_row(base + (u64)r * kRowElems + lane * kV);
+            }
+        } else {
+            for (u32 r = 0; r < kR && (FAST || base + (u64)r * kRowElems < n); ++r) symbols_of_row(base + (u64)r * kRowElems + lane * kV);
         }
         const u32 used = avail0 + 32 * (br.wi - wi0) - br.avail;
         if (__any(used != lane_bits) && lane == 0) raise(4u);
