@@ -142,7 +142,7 @@ class Job:
 # bytes per element these kernels move whatever the data (k_spec_sweep: see cached_leg); the key-staging sweep reads w and
 # w_ref and writes a byte and a bit per element
 READS_EVERYTHING = {"k_hist": 8.0, "k_hist_keys": 9.125}
-ENCODE_KERNELS = ("k_hist", "k_hist_keys", "k_table", "k_pack", "k_pack_keys", "k_place", "k_finalize")
+ENCODE_KERNELS = ("k_hist", "k_hist_keys", "k_table", "k_pack", "k_pack_keys", "k_place")
 DECODE_KERNELS = ("k_dec_check", "k_decode")
 
 

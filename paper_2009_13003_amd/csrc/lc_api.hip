@@ -83,7 +83,7 @@ double g_prof_ms[kNumSlots];
 uint64_t g_prof_n[kNumSlots];
 hipEvent_t g_ev[kNumSlots][2];
 bool g_ev_made = false;
-const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_finalize", "k_spec_table", "k_spec_sweep",
+const char* const kSlotNames[kNumSlots] = {"k_reset", "k_hist", "k_table", "k_pack", "k_place", "k_spec_table", "k_spec_sweep",
                                            "k_dec_check", "k_decode", "k_decode_fused", "k_hist_keys", "k_pack_keys", "k_verify"};
 
 int env_int(const char* name, int dflt, int lo, int hi) {
@@ -365,7 +365,7 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     area->clean = false;
     // (binary64 with a cache: two sweeps, the second one coding with the cached lengths when k_table confirms them)
     const bool spec_sweep = cache && dtype != LC_F64;
-    if (cache) { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, nbits, dtype, s); }
+    if (cache) { Timed t(kSlotSpecTable, s); launch_spec_table(ws, cache, n, nbits, dtype, group_words, s); }
     if (spec_sweep) {
         Timed t(kSlotSpecSweep, s); launch_spec_sweep(w, w_ref, n, dtype, ws, chunk_bits, group_words, prov, slot_words, ds->tune, s);
     } else {
@@ -376,8 +376,7 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     if (staged) { Timed t(kSlotPackKeys, s); launch_pack_keys(w, w_ref, n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, keys, prov, slot_words, ds->tune, s); }
     else { Timed t(kSlotPack, s); launch_pack(w, w_ref, n, dtype, ws, chunk_bits, group_words, chunk_maxexp, listed ? chunk_list : nullptr, batch_max, prov, slot_words, ds->tune, s); }
     if (async) LC_HIP(hipEventRecord(call.inputs, s));   // w and w_ref are not read past this point
-    { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, s); }
-    { Timed t(kSlotFinalize, s); launch_finalize(o, ws, result, group_words, cache, n, nbits, dtype, staged, s); }
+    { Timed t(kSlotPlace, s);    launch_place(o, ws, chunk_bits, group_words, prov, slot_words, n, chunk_maxexp, result, cache, nbits, dtype, staged, s); }
     LC_HIP(hipGetLastError());
     if (!release(area, s)) return -LC_ERR_HIP;
     area->clean = true;              // whoever takes the area next is ordered behind this call
@@ -395,8 +394,8 @@ lc_ssize encode_impl(const void* w, const void* w_ref, uint64_t n, int nbits, vo
     if (!serial) lock.lock();
     if (waited != hipSuccess) { (void)hipGetLastError(); area->clean = false; return -LC_ERR_HIP; }
     const int slots[] = {cache ? kSlotSpecTable : staged ? kSlotHistKeys : kSlotHist, kSlotTable, staged ? kSlotPackKeys : kSlotPack,
-                         kSlotPlace, kSlotFinalize, spec_sweep ? kSlotSpecSweep : kSlotHist};
-    collect(slots, cache ? 6 : 5);
+                         kSlotPlace, spec_sweep ? kSlotSpecSweep : kSlotHist};
+    collect(slots, cache ? 5 : 4);
     const Result r = g_pinned[slot].enc;
     if (call.w) note_outcome(ds, call.w, call.n, r);
     if (used) *used = (int)r.used_cache;
@@ -455,8 +454,7 @@ int lc_encode_static(const float* w, const float* w_ref, uint64_t n, int nbits, 
     launch_table(sc.ws, n, nbits, LC_F32, sc.group_words, sc.chunk_maxexp, sc.chunk_list, s);
     launch_pack(w, w_ref, n, LC_F32, sc.ws, sc.chunk_bits, sc.group_words, sc.chunk_maxexp, sc.chunk_list, sc.batch_max, sc.prov,
                 sc.slot_words, ds.tune, s);
-    launch_place(o, sc.ws, sc.chunk_bits, sc.group_words, sc.prov, sc.slot_words, n, sc.chunk_maxexp, s);
-    launch_finalize(o, sc.ws, result, sc.group_words, nullptr, n, nbits, LC_F32, false, s);
+    launch_place(o, sc.ws, sc.chunk_bits, sc.group_words, sc.prov, sc.slot_words, n, sc.chunk_maxexp, result, nullptr, nbits, LC_F32, false, s);
     if (hipGetLastError() != hipSuccess) return LC_ERR_HIP;
     return LC_OK;
 }
@@ -552,8 +550,10 @@ lc_ssize decode_impl(const void* blob, size_t blob_bytes, void* w_ref, uint64_t 
     const hipError_t waited = hipStreamSynchronize(s);
     if (!serial) lock.lock();
     if (waited != hipSuccess) { (void)hipGetLastError(); return -LC_ERR_HIP; }
-    const int slots[] = {kSlotDecCheck, kSlotDecode, kSlotVerify};
-    collect(slots, 3);
+    int slots[3] = {kSlotDecCheck, 0, 0}, launched = 1;          // (only what this call launched has fresh events)
+    if (verify_only || g_verify_first) slots[launched++] = kSlotVerify;
+    if (!verify_only) slots[launched++] = kSlotDecode;
+    collect(slots, launched);
     if ((g_pinned[slot].dec_status >> 8) == epoch) return -(lc_ssize)(g_pinned[slot].dec_status & 0xFF);
     return (lc_ssize)g_pinned[slot].bytes[0];
 }

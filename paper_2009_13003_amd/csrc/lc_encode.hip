@@ -1,9 +1,9 @@
 // Encode kernels of the LC-Checkpoint compress / restore path for gfx950 (wave64).
 //
-// lc_encode:         k_hist -> k_table -> k_pack -> k_place -> k_finalize (which also clears the scratch
+// lc_encode:         k_hist -> k_table -> k_pack -> k_place (whose first workgroup writes the header) (which also clears the scratch
 //                    state for the next call, k_place the per-chunk maxima); k_reset only for a fresh scratch area
-//                    (fp64 parameters: k_hist64 -> k_table<11> -> k_pack64 -> k_place -> k_finalize)
-// lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place -> k_finalize
+//                    (fp64 parameters: k_hist64 -> k_table<11> -> k_pack64 -> k_place)
+// lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place
 // lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_list -> kb_pack -> kb_place -> kb_finalize
 //
 // The paper (arXiv 2009.13003) defines what is computed: delta against the last
@@ -334,6 +334,10 @@ __device__ __forceinline__ void table_build(EncState* ws, Ext64* ext, u64 n, int
     const u32 lane = lane_id();
     const bool active = threadIdx.x < kW;
     const u32 kmax = (1u << nbits) - 1;
+    // The groups' record sizes start from zero in every call: the last call's placement read them to its end, so they
+    // are cleared here, ahead of the coding sweep that adds to them (a cached table's speculative coding has already
+    // added to them: then k_spec_table has cleared them).
+    if (group_words && !ws->spec) for (u32 i = threadIdx.x; i < ngroups; i += blockDim.x) group_words[i] = 0;
     if (active) for (u32 i = lane; i <= kMaxSym; i += kW) { S.cnt[i] = 0; S.len[i] = 0; if (i < kMaxSym) S.kept[i] = 0; }
     u32 total = 0;
     bool nonfinite = false, zero_class = false;
@@ -521,12 +525,14 @@ __global__ __launch_bounds__(1024) void k_table(EncState* ws, Ext64* ext, u64 n,
 // lc_encode_cached, before the sweep: turns a usable cache (valid, same nbits, kept buckets in strict
 // priority order, lengths forming a complete prefix code) into the table the sweep codes with.
 template <int EB>                         // EB: exponent bits of the parameters' delta (8, or 11 for binary64)
-__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, Ext64* ext, const TableCache* cache, int nbits) {
+__global__ __launch_bounds__(64) void k_spec_table(EncState* ws, Ext64* ext, const TableCache* cache, int nbits,
+                                                   u32* group_words, u32 ngroups) {
     constexpr u32 kBuckets = 2u << EB, kEmax = (1u << EB) - 1;
     __shared__ u32 s_ok, s_len[kMaxSym + 1];
     __shared__ uint8_t s_sym[kBuckets];
     const u32 lane = threadIdx.x;
     Table& T = ws->table;
+    for (u32 i = lane; i < ngroups; i += kW) group_words[i] = 0;      // (the sweep that follows may add to them: see k_table)
     for (u32 b = lane; b < kBuckets; b += kW) s_sym[b] = 0xFF;
     __syncthreads();
     if (lane == 0) {
@@ -1442,18 +1448,44 @@ constexpr u32 kPlaceWords = 1024, kPlaceWordsFew = 2048;
 // Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
+// total_words: 32-bit words of all chunk records together.  Everything a thread needs from memory is asked for before the
+// first use of any of it (the workgroup runs beside a whole placement sweep: every dependent round trip costs microseconds there).
 __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
-                                              u64 n, int nbits, u32 nchunks, u32 dtype, const Ext64* ext = nullptr,
-                                              const u32* bucket_min = nullptr, const u32* bucket_max = nullptr) {
+                                              u64 n, int nbits, u32 nchunks, u32 dtype, u64 total_words, const Ext64* ext = nullptr,
+                                              const u32* bucket_min = nullptr, const u32* bucket_max = nullptr,
+                                              const u32* group_words = nullptr) {
     __shared__ u32 hdr[kHeaderBytes / 4];
+    __shared__ unsigned long long s_total;
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
+    // (group_words given: the total is the sum of the groups' record sizes, not total_words)
+    u64 part = 0;
+    if (group_words) for (u32 g = t; g < (nchunks + 63) / 64; g += blockDim.x) part += group_words[g];
+    if (t == 0) s_total = total_words;
+    // this thread's symbol (threads 0 .. 15): code, bucket, population, extremes
+    const u32 sym = t < kMaxSym ? t : 0;
+    const u32 my_codelen = T.codelen[sym], my_kept = T.kept[sym];
+    const u64 my_cnt = T.cnt[sym];
+    u32 mn = 0x7FFFFFu, mx = 0;
+    u64 mn64 = 0, mx64 = 0;
+    if (dtype != kF64) {
+#pragma unroll
+        for (u32 k = 0; k < kExtCopies; ++k) { mn = min(mn, ws->mmin[k][sym]); mx = max(mx, ws->mmax[k][sym]); }
+        // (an encode with staged keys: the extremes of every bucket were gathered by sweep 1)
+        if (bucket_min) { mn = bucket_min[my_kept & 511u] & 0x7FFFFFu; mx = bucket_max[my_kept & 511u] & 0x7FFFFFu; }
+    } else {
+        mn64 = ext->mmin[sym]; mx64 = ext->mmax[sym];
+    }
+    const u32 status = T.status, K = T.K, k_E = T.k_E, max_len = T.max_len;
+    const u32 spec_ok = ws->spec_ok, listed = ws->list_count;
     if (t < kHeaderBytes / 4) hdr[t] = 0;
     __syncthreads();
-    const u32 status = T.status;
+    part = wave_sum64(part);
+    if (lane_id() == 0 && part) atomicAdd(&s_total, (unsigned long long)part);
+    __syncthreads();
+    total_words = s_total;
     const bool ok = status == 0;
     const u64 area = chunk_area_of(nchunks);
-    const u64 total_words = ws->total_words;
     const u64 total = ok ? area + 4 * total_words : kHeaderBytes;
     if (t == 0) {
         hdr[0] = 0x3142434Cu;                     // "LCB1"
@@ -1464,32 +1496,29 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
         hdr[10] = (u32)total; hdr[11] = (u32)(total >> 32);
         hdr[12] = status;
         hdr[15] = dtype;
-        if (ok) { hdr[5] = T.K; hdr[9] = nchunks; hdr[13] = T.k_E; hdr[14] = T.max_len; }
-        host_result->bytes = total; host_result->status = status; host_result->used_cache = ws->spec_ok;
-        host_result->listed = ws->list_count; host_result->pad_r = 0;
-        if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = T.K; cache->pad = 0; }
+        if (ok) { hdr[5] = K; hdr[9] = nchunks; hdr[13] = k_E; hdr[14] = max_len; }
+        host_result->bytes = total; host_result->status = status; host_result->used_cache = spec_ok;
+        host_result->listed = listed; host_result->pad_r = 0;
+        if (cache && ok) { cache->valid = 1; cache->nbits = (u32)nbits; cache->K = K; cache->pad = 0; }
     }
     if (cache && ok && t < kMaxSym) {              // what this blob was coded with, for the next call
-        cache->kept[t] = t < T.K ? T.kept[t] : 0;
-        cache->len[t] = t <= T.K ? (T.codelen[t] & 31) : 0;
+        cache->kept[t] = t < K ? my_kept : 0;
+        cache->len[t] = t <= K ? (my_codelen & 31) : 0;
     }
-    if (ok && t <= T.K) {
-        const u32 len = T.codelen[t] & 31;
+    if (ok && t <= K) {
+        const u32 len = my_codelen & 31;
         // representative = midrange of the bucket's extremes, rounded once to nearest even (Section 3.1.1):
         // halve the mantissa sum; an odd sum lies halfway between two mantissas and goes to the even one
         u32 bucket = 0xFFFFu, rep = 0;
-        if (t < T.K && dtype != kF64) {
-            bucket = T.kept[t];
-            // (an encode with staged keys: the extremes of every bucket were gathered by sweep 1)
-            u32 mn = 0x7FFFFFu, mx = 0;
-            for (u32 k = 0; k < kExtCopies; ++k) { mn = min(mn, ws->mmin[k][t]); mx = max(mx, ws->mmax[k][t]); }
-            const u32 sum = bucket_min ? (bucket_min[bucket] & 0x7FFFFFu) + (bucket_max[bucket] & 0x7FFFFFu) : mn + mx;
+        if (t < K && dtype != kF64) {
+            bucket = my_kept;
+            const u32 sum = mn + mx;
             u32 mm = sum >> 1;
             if ((sum & 1) && (mm & 1)) ++mm;
             rep = (bucket << 23) | mm;
-        } else if (t < T.K) {                          // binary64: 52-bit mantissas, high half at header offset 320 + 4 t
-            bucket = T.kept[t];
-            const u64 sum = ext->mmin[t] + ext->mmax[t];
+        } else if (t < K) {                            // binary64: 52-bit mantissas, high half at header offset 320 + 4 t
+            bucket = my_kept;
+            const u64 sum = mn64 + mx64;
             u64 mm = sum >> 1;
             if ((sum & 1) && (mm & 1)) ++mm;
             const u64 rep64 = ((u64)bucket << 52) | mm;
@@ -1498,8 +1527,8 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
         }
         hdr[16 + 4 * t + 0] = bucket | (len << 16);
         hdr[16 + 4 * t + 1] = rep;
-        hdr[16 + 4 * t + 2] = (u32)T.cnt[t];
-        hdr[16 + 4 * t + 3] = (u32)(T.cnt[t] >> 32);
+        hdr[16 + 4 * t + 2] = (u32)my_cnt;
+        hdr[16 + 4 * t + 3] = (u32)(my_cnt >> 32);
     }
     __syncthreads();
     if (t < kHeaderBytes / 4) reinterpret_cast<u32*>(out)[t] = hdr[t];
@@ -1513,21 +1542,27 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
     __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_finalize(uint8_t* out, Workspace* ws, Result* host_result, u32* group_words,
-                                                  TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype, int staged) {
-    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, &ws->ext64, staged ? ws->bucket_min : nullptr,
-                  staged ? ws->bucket_max : nullptr);
-    clear_encode_state(ws, group_words, (nchunks + 63) / 64, threadIdx.x, blockDim.x);
+// The header of a single vector's blob, the call's outcome for the host, and the scratch state left as the next call
+// expects it; by one workgroup of 256 threads.  It runs as the first workgroup of k_place, beside the workgroups that
+// place the chunks: everything it needs is final before that kernel starts (table, extremes, and the size of the blob,
+// which is the sum of the groups' record sizes), and what it clears none of them reads.  The groups' sums, which they
+// do read, are cleared by the next call's first kernel that precedes their use (k_table, or k_spec_table).
+__device__ __forceinline__ void finalize_vector(uint8_t* out, Workspace* ws, Result* host_result, const u32* group_words,
+                                                TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype, int staged) {
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, 0, &ws->ext64, staged ? ws->bucket_min : nullptr,
+                  staged ? ws->bucket_max : nullptr, group_words);
+    clear_encode_state(ws, nullptr, 0, threadIdx.x, blockDim.x);
     if (dtype == kF64) clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
     if (staged) clear_bucket_extremes(ws, threadIdx.x, blockDim.x);
-    __threadfence_system();
+    // (no fence: the host reads its result after waiting for the stream, and the end of the kernel makes every store
+    // visible; a system-scope fence here would have to write back what the other workgroups have just placed)
 }
 
 // Chunk c of one vector, by one wavefront of a workgroup of four; `valid` false: an idle wavefront.
 template <u32 PW>
 __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                             const u32* __restrict__ group_words, const u32* __restrict__ prov,
-                                            u32 slot_words, u32 nchunks, u32 c, bool valid) {
+                                            u32 slot_words, u32 nchunks, u32 c, bool valid, bool note_total = false) {
     __shared__ u32 s_buf_all[4][PW];
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     u32* s_buf = s_buf_all[wv];
@@ -1552,7 +1587,8 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
         reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
         if (lane == 0) {
             reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
-            if (c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
+            // (a batched call's header kernel takes the tensor's total from here; a single vector's sums the groups itself)
+            if (note_total && c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
         }
     }
     if (merged) {
@@ -1606,11 +1642,18 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
     }
 }
 
+// Workgroup 0 writes the header and reports the outcome (finalize_vector); the others place four chunks each.
+struct FinalizeArgs { Result* host_result; TableCache* cache; u64 n; int nbits; u32 dtype; int staged; };
+
 template <u32 PW>
-__global__ __launch_bounds__(256) void k_place(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
+__global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, const u32* __restrict__ chunk_bits,
                                                const u32* __restrict__ group_words, const u32* __restrict__ prov,
-                                               u32 slot_words, u32 nchunks, u32* chunk_maxexp) {
-    const u32 c = blockIdx.x * 4 + (threadIdx.x >> 6);
+                                               u32 slot_words, u32 nchunks, u32* chunk_maxexp, FinalizeArgs fin) {
+    if (blockIdx.x == 0) {
+        finalize_vector(out, ws, fin.host_result, group_words, fin.cache, fin.n, fin.nbits, nchunks, fin.dtype, fin.staged);
+        return;
+    }
+    const u32 c = (blockIdx.x - 1) * 4 + (threadIdx.x >> 6);
     // sweep 2 was the last to look at the chunk maxima: leave them cleared for the next call, whatever this one's outcome
     if (c < nchunks && lane_id() == 0) chunk_maxexp[maxexp_slot(c)] = 0;
     // the last workgroup may hold idle wavefronts
@@ -1804,12 +1847,13 @@ __global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
     const Seg& sg = a.segs[sidx];
     EncState* st = &a.states[sidx];
     place_chunk<kPlaceWords>(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
-                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0);
+                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0, true);
 }
 
 __global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
     const Seg& sg = a.segs[blockIdx.x];
-    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)a.dtype);
+    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)a.dtype,
+                  a.states[blockIdx.x].total_words);
     if (blockIdx.x == gridDim.x - 1) __threadfence_system();
 }
 // ----------------------------------------------------------------------------- launchers
@@ -1880,9 +1924,10 @@ static u32 even_waves(u64 nchunks, u64 cap) {
     return (u32)((nchunks + turns - 1) / turns);
 }
 
-void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, int dtype, hipStream_t s) {
-    if (dtype == kF64) hipLaunchKernelGGL(k_spec_table<11>, dim3(1), dim3(64), 0, s, ws, &ws->ext64, cache, nbits);
-    else hipLaunchKernelGGL(k_spec_table<8>, dim3(1), dim3(64), 0, s, ws, (Ext64*)nullptr, cache, nbits);
+void launch_spec_table(Workspace* ws, const TableCache* cache, uint64_t n, int nbits, int dtype, uint32_t* group_words, hipStream_t s) {
+    const u32 ngroups = (u32)((num_chunks_of(n) + 63) / 64);
+    if (dtype == kF64) hipLaunchKernelGGL(k_spec_table<11>, dim3(1), dim3(64), 0, s, ws, &ws->ext64, cache, nbits, group_words, ngroups);
+    else hipLaunchKernelGGL(k_spec_table<8>, dim3(1), dim3(64), 0, s, ws, (Ext64*)nullptr, cache, nbits, group_words, ngroups);
 }
 
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
@@ -1912,22 +1957,19 @@ void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Worksp
     else hipLaunchKernelGGL(k_pack<kF32>, grid, wg, 0, s, w, w_ref, (u64)n, ws, chunk_bits, group_words, chunk_maxexp, chunk_list, batch_max, prov, slot_words, (u32)nchunks, al);
 }
 
+// The placement of all chunks and, in the same launch, the header and the call's outcome (result: mapped host memory;
+// cache: lc_encode_cached's, or null; staged: the extremes come from sweep 1's per-bucket record).
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
-                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s) {
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, Result* host_result,
+                  TableCache* cache, int nbits, int dtype, bool staged, hipStream_t s) {
     const u64 nchunks = num_chunks_of(n);
-    if (nchunks == 0) return;
-    const u32 blocks = (u32)((nchunks + 3) / 4);
+    const u32 blocks = (u32)((nchunks + 3) / 4) + 1;             // + the workgroup that writes the header
+    const FinalizeArgs fin = {host_result, cache, (u64)n, nbits, (u32)dtype, staged ? 1 : 0};
     // (up to 1024 workgroups are resident together on this chip even with the larger windows)
     if (blocks <= 1024u) hipLaunchKernelGGL(k_place<kPlaceWordsFew>, dim3(blocks), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
-                                                slot_words, (u32)nchunks, chunk_maxexp);
+                                                slot_words, (u32)nchunks, chunk_maxexp, fin);
     else hipLaunchKernelGGL(k_place<kPlaceWords>, dim3(blocks), dim3(256), 0, s, out, ws, chunk_bits, group_words, prov,
-                            slot_words, (u32)nchunks, chunk_maxexp);
-}
-
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, bool staged, hipStream_t s) {
-    hipLaunchKernelGGL(k_finalize, dim3(1), dim3(256), 0, s, out, ws, host_result, group_words, cache, (u64)n, nbits,
-                       (u32)num_chunks_of(n), (u32)dtype, staged ? 1 : 0);
+                            slot_words, (u32)nchunks, chunk_maxexp, fin);
 }
 
 void launch_batch_encode(const BatchArgs& args, const Tuning& tune, hipStream_t s) {

@@ -129,7 +129,7 @@ __host__ __device__ inline uint64_t num_chunks_of(uint64_t n) { return (n + kChu
 __host__ __device__ inline uint32_t slot_words_of(int nbits) { return kLaneBitsWords + kW * 8u * ((1u << nbits) - 1u); }
 __host__ __device__ inline uint64_t chunk_area_of(uint64_t nchunks) { return kHeaderBytes + (4 * (nchunks + 1) + 15) / 16 * 16; }
 
-enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotFinalize, kSlotSpecTable, kSlotSpecSweep,
+enum Slot { kSlotReset = 0, kSlotHist, kSlotTable, kSlotPack, kSlotPlace, kSlotSpecTable, kSlotSpecSweep,
             kSlotDecCheck, kSlotDecode, kSlotDecodeFused, kSlotHistKeys, kSlotPackKeys, kSlotVerify, kNumSlots };
 
 // Launch shapes; defaults chosen by measurement, overridable through LC_TUNE_* environment
@@ -168,17 +168,15 @@ void launch_pack_keys(const void* w, const void* w_ref, uint64_t n, Workspace* w
                       const Tuning& tune, hipStream_t s);
 void launch_table(Workspace* ws, uint64_t n, int nbits, int dtype, uint32_t* group_words, const uint32_t* chunk_maxexp,
                   uint32_t* chunk_list, hipStream_t s);
-void launch_spec_table(Workspace* ws, const TableCache* cache, int nbits, int dtype, hipStream_t s);
+void launch_spec_table(Workspace* ws, const TableCache* cache, uint64_t n, int nbits, int dtype, uint32_t* group_words, hipStream_t s);
 void launch_spec_sweep(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                        uint32_t* group_words, uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_pack(const void* w, const void* w_ref, uint64_t n, int dtype, Workspace* ws, uint32_t* chunk_bits,
                  uint32_t* group_words, const uint32_t* chunk_maxexp, const uint32_t* chunk_list, const uint8_t* batch_max,
                  uint32_t* prov, uint32_t slot_words, const Tuning& tune, hipStream_t s);
 void launch_place(uint8_t* out, Workspace* ws, const uint32_t* chunk_bits, const uint32_t* group_words,
-                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, hipStream_t s);
-// staged: the extremes of the kept buckets are in ws->bucket_min / bucket_max (an encode with staged keys)
-void launch_finalize(uint8_t* out, Workspace* ws, Result* host_result, uint32_t* group_words, TableCache* cache,
-                     uint64_t n, int nbits, int dtype, bool staged, hipStream_t s);
+                  const uint32_t* prov, uint32_t slot_words, uint64_t n, uint32_t* chunk_maxexp, Result* host_result,
+                  TableCache* cache, int nbits, int dtype, bool staged, hipStream_t s);
 // One tensor of a batched call (lc_encode_batch): every tensor has its own EncState, blob and run of
 // chunks; chunks, groups of 64 chunks and slots of all tensors are numbered through ("dense" indices).
 struct Seg {
