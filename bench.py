@@ -315,8 +315,10 @@ def typed_leg(device, steps, workload, tdt_name):
     bits = 8.0 * (size - 512) / n
     return dict(n=n, nbits=nbits, dtype=tdt_name, encode_ms=round(1e3 * enc, 4), decode_ms=round(1e3 * dec, 4),
                 encode_GBps=round(gb / enc, 1), decode_GBps=round(gb / dec, 1), ratio=round(esize * n / size, 3),
-                encode_hbm_frac=round((4.0 * esize + bits / 8.0) * n / 1e9 / enc / HBM_PEAK_GBPS, 4),
-                decode_hbm_frac=round((2.0 * esize + bits / 8.0) * n / 1e9 / dec / HBM_PEAK_GBPS, 4))
+                # bytes by the two-sweep formulas over time: a rate "of parameters", above what moves (and above the HBM
+                # peak) where the second sweep and the restore pass over chunks; no fraction of peak is claimed from it
+                encode_alg_GBps=round((4.0 * esize + bits / 8.0) * n / 1e9 / enc, 1),
+                decode_alg_GBps=round((2.0 * esize + bits / 8.0) * n / 1e9 / dec, 1))
 
 
 def per_tensor_leg(device, steps, workload="resnet50"):
@@ -719,7 +721,9 @@ def main():
     if not args.no_also and args.workload != "llama7b_slice0":
         # config 5's first 2^28-element slice, where every chunk holds kept elements: the sweeps' dense rate
         dense = Job("llama7b_slice0", dev)
-        r = run(dense, max(2, args.steps // 2), 1, not args.no_cached)
+        # (three warm-up calls: the first encode of a vector takes the plain second sweep, the second allocates the larger
+        # scratch area of the staged one)
+        r = run(dense, max(2, args.steps // 2), 3, not args.no_cached)
         also["llama7b_slice0"] = rounded(r, dense)
         roofline["dense"] = roofline_of(r, dense)
         if not args.no_cached:
@@ -735,7 +739,7 @@ def main():
             if name == args.workload:
                 continue
             j = Job(name, dev)
-            r = run(j, max(2, args.steps // 4) if name == "llama7b" else args.steps, 1, not args.no_cached)
+            r = run(j, max(2, args.steps // 4) if name == "llama7b" else args.steps, 2, not args.no_cached)
             also[name] = rounded(r, j)
             del j
             torch.cuda.empty_cache()

@@ -1091,7 +1091,7 @@ __device__ __forceinline__ void pack_merge_extremes(PackLds<HIST>& L, EncState* 
         for (int k = 0; k < kMmCopies; ++k) { mn = min(mn, L.mn[lane * kMmCopies + k]); mx = max(mx, L.mx[lane * kMmCopies + k]); }
         // Wavefronts that code chunks of one vector finish at about the same time, and atomics on one cache line are
         // served one after the other (a 1000-chunk tensor's queued up for 30 us): each workgroup hands its extremes to
-        // one of kExtCopies copies, which the finalize kernel joins.
+        // one of kExtCopies copies, which the workgroup that writes the header joins.
         const u32 copy = blockIdx.x % kExtCopies;
         if (mn <= mx) { atomicMin(&ws->mmin[copy][lane], mn & 0x7FFFFFu); atomicMax(&ws->mmax[copy][lane], mx & 0x7FFFFFu); }
     }

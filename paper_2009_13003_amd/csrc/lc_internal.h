@@ -83,7 +83,7 @@ struct HostResult {
 struct EncState {
     unsigned long long hist[512];
     uint32_t mmin[kExtCopies][kMaxSym];      // smallest / largest mantissa seen of every kept bucket: a workgroup of the coding
-    uint32_t mmax[kExtCopies][kMaxSym];      // sweep updates copy (its index mod kExtCopies), the finalize kernel joins them
+    uint32_t mmax[kExtCopies][kMaxSym];      // sweep updates copy (its index mod kExtCopies), the workgroup that writes the header joins them
     uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
     uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
     unsigned long long total_words;
