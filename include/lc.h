@@ -306,7 +306,7 @@ lc_ssize lc_decode_many_t(const void* const* blobs, int count, void* w_ref, uint
  * Many vectors in one call, each with a table of its own: tensor t is coded exactly as
  * lc_encode(w[t], w_ref[t], n[t], nbits, out[t]) would (the paper quantizes layer by layer: Figure 2,
  * Section 4.3; per-tensor tables keep small-scale tensors from being merged away by large-scale ones),
- * but the whole list takes seven kernel launches instead of four per tensor.
+ * but the whole list takes six kernel launches instead of four per tensor.
  *   w, w_ref, out  HOST arrays of `count` DEVICE pointers (out[t]: 16-byte aligned, at least
  *                  lc_encode_bound(n[t], nbits) bytes); n: HOST array of lengths; 1 <= count <= LC_MAX_BATCH
  *   sizes          HOST array or NULL: blob size of each tensor, or -(lc_status) for a tensor whose delta

@@ -4,7 +4,7 @@
 //                    state for the next call, k_place the per-chunk maxima); k_reset only for a fresh scratch area
 //                    (fp64 parameters: k_hist64 -> k_table<11> -> k_pack64 -> k_place)
 // lc_encode_cached:  k_spec_table -> k_spec_sweep -> k_table -> k_pack (nothing to do on a hit) -> k_place
-// lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_list -> kb_pack -> kb_place -> kb_finalize
+// lc_encode_batch:   kb_setup -> kb_hist -> kb_table -> kb_list -> kb_pack -> kb_place (whose first workgroups write the headers)
 //
 // The paper (arXiv 2009.13003) defines what is computed: delta against the last
 // recovered state (Algorithm 1 line 4), (sign, exponent) buckets represented by the
@@ -28,7 +28,7 @@ __device__ __forceinline__ void clear_encode_state(EncState* ws, u32* group_word
     for (u32 i = tid; i < ngroups; i += nthr) group_words[i] = 0;
     for (u32 i = tid; i < 512; i += nthr) ws->hist[i] = 0;
     clear_extremes(ws, tid, nthr);
-    if (tid == 0) { ws->total_words = 0; ws->spec = 0; ws->spec_ok = 0; ws->list_count = 0; }
+    if (tid == 0) { ws->spec = 0; ws->spec_ok = 0; ws->list_count = 0; }
 }
 
 __device__ __forceinline__ void clear_ext64(Ext64* ext, u32 tid, u32 nthr) {
@@ -1448,20 +1448,21 @@ constexpr u32 kPlaceWords = 1024, kPlaceWordsFew = 2048;
 // Representatives (Section 3.1.1: mean of the bucket's largest and smallest member, rounded once
 // to fp32, ties to even, done on the mantissas since both share a binade), the header, the last
 // offset entry, the result for the host; then the scratch state is cleared for the next call.
-// total_words: 32-bit words of all chunk records together.  Everything a thread needs from memory is asked for before the
-// first use of any of it (the workgroup runs beside a whole placement sweep: every dependent round trip costs microseconds there).
+// The header of one vector's blob and the call's outcome for the host, by a workgroup of 256 threads.  group_words: the
+// record sizes of the vector's groups of 64 chunks; their sum is the size of the chunk area.  Everything a thread needs
+// from memory is asked for before the first use of any of it (the workgroup runs beside a whole placement sweep: every
+// dependent round trip costs microseconds there).
 __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result* host_result, TableCache* cache,
-                                              u64 n, int nbits, u32 nchunks, u32 dtype, u64 total_words, const Ext64* ext = nullptr,
-                                              const u32* bucket_min = nullptr, const u32* bucket_max = nullptr,
-                                              const u32* group_words = nullptr) {
+                                              u64 n, int nbits, u32 nchunks, u32 dtype, const u32* group_words,
+                                              const Ext64* ext = nullptr, const u32* bucket_min = nullptr,
+                                              const u32* bucket_max = nullptr) {
     __shared__ u32 hdr[kHeaderBytes / 4];
     __shared__ unsigned long long s_total;
     const u32 t = threadIdx.x;
     const Table& T = ws->table;
-    // (group_words given: the total is the sum of the groups' record sizes, not total_words)
     u64 part = 0;
-    if (group_words) for (u32 g = t; g < (nchunks + 63) / 64; g += blockDim.x) part += group_words[g];
-    if (t == 0) s_total = total_words;
+    for (u32 g = t; g < (nchunks + 63) / 64; g += blockDim.x) part += group_words[g];
+    if (t == 0) s_total = 0;
     // this thread's symbol (threads 0 .. 15): code, bucket, population, extremes
     const u32 sym = t < kMaxSym ? t : 0;
     const u32 my_codelen = T.codelen[sym], my_kept = T.kept[sym];
@@ -1483,7 +1484,7 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
     part = wave_sum64(part);
     if (lane_id() == 0 && part) atomicAdd(&s_total, (unsigned long long)part);
     __syncthreads();
-    total_words = s_total;
+    const u64 total_words = s_total;
     const bool ok = status == 0;
     const u64 area = chunk_area_of(nchunks);
     const u64 total = ok ? area + 4 * total_words : kHeaderBytes;
@@ -1549,8 +1550,8 @@ __device__ __forceinline__ void finalize_blob(uint8_t* out, EncState* ws, Result
 // do read, are cleared by the next call's first kernel that precedes their use (k_table, or k_spec_table).
 __device__ __forceinline__ void finalize_vector(uint8_t* out, Workspace* ws, Result* host_result, const u32* group_words,
                                                 TableCache* cache, u64 n, int nbits, u32 nchunks, u32 dtype, int staged) {
-    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, 0, &ws->ext64, staged ? ws->bucket_min : nullptr,
-                  staged ? ws->bucket_max : nullptr, group_words);
+    finalize_blob(out, ws, host_result, cache, n, nbits, nchunks, dtype, group_words, &ws->ext64, staged ? ws->bucket_min : nullptr,
+                  staged ? ws->bucket_max : nullptr);
     clear_encode_state(ws, nullptr, 0, threadIdx.x, blockDim.x);
     if (dtype == kF64) clear_ext64(&ws->ext64, threadIdx.x, blockDim.x);
     if (staged) clear_bucket_extremes(ws, threadIdx.x, blockDim.x);
@@ -1562,7 +1563,7 @@ __device__ __forceinline__ void finalize_vector(uint8_t* out, Workspace* ws, Res
 template <u32 PW>
 __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u32* __restrict__ chunk_bits,
                                             const u32* __restrict__ group_words, const u32* __restrict__ prov,
-                                            u32 slot_words, u32 nchunks, u32 c, bool valid, bool note_total = false) {
+                                            u32 slot_words, u32 nchunks, u32 c, bool valid) {
     __shared__ u32 s_buf_all[4][PW];
     const u32 lane = lane_id(), wv = threadIdx.x >> 6;
     u32* s_buf = s_buf_all[wv];
@@ -1587,8 +1588,6 @@ __device__ __forceinline__ void place_chunk(uint8_t* out, EncState* ws, const u3
         reinterpret_cast<uint16_t*>(rec)[lane] = (uint16_t)bits;
         if (lane == 0) {
             reinterpret_cast<u32*>(out + kHeaderBytes)[c] = (u32)word_off;
-            // (a batched call's header kernel takes the tensor's total from here; a single vector's sums the groups itself)
-            if (note_total && c + 1 == nchunks) ws->total_words = word_off + kLaneBitsWords + nwords;
         }
     }
     if (merged) {
@@ -1661,7 +1660,7 @@ __global__ __launch_bounds__(256) void k_place(uint8_t* out, Workspace* ws, cons
 }
 
 // ----------------------------------------------------------------------------- batched encode
-// lc_encode_batch: many vectors, one table each, in seven launches.  The chunks of all tensors are numbered
+// lc_encode_batch: many vectors, one table each, in six launches.  The chunks of all tensors are numbered
 // through; the sweeps deal those dense chunks round-robin to their wavefronts exactly as for one vector,
 // and a wavefront that moves on to a chunk of another tensor first hands in what it gathered for the last
 // one (bucket counts, extremes) and loads the new tensor's table.
@@ -1680,7 +1679,7 @@ __global__ __launch_bounds__(256) void kb_setup(BatchArgs a) {
     for (u32 g = i; g < a.total_groups; g += nthr) a.group_words[g] = 0;
     if (i == 0) *a.list_count = 0;
     constexpr u32 kExt = kExtCopies * kMaxSym;
-    constexpr u32 per = 512 + 2 * kExt + 4;                   // words of state to set per tensor
+    constexpr u32 per = 512 + 2 * kExt + 3;                   // words of state to set per tensor
     for (u64 k = i; k < (u64)a.count * per; k += nthr) {
         EncState& st = a.states[k / per];
         const u32 j = (u32)(k % per);
@@ -1689,7 +1688,6 @@ __global__ __launch_bounds__(256) void kb_setup(BatchArgs a) {
         else if (j < 512 + 2 * kExt) (&st.mmax[0][0])[j - 512 - kExt] = 0;
         else if (j == 512 + 2 * kExt) st.spec = 0;
         else if (j == 512 + 2 * kExt + 1) st.spec_ok = 0;
-        else if (j == 512 + 2 * kExt + 2) st.total_words = 0;
         else st.table.status = 0;
     }
 }
@@ -1840,22 +1838,24 @@ __global__ __launch_bounds__(64) void kb_pack(BatchArgs a) {
     src.hand_in(L);
 }
 
+// The first `count` workgroups write the tensors' headers and report their outcomes (everything that takes is final
+// before the placement starts, as for a single vector: see finalize_vector); the others place four chunks each.
 __global__ __launch_bounds__(256) void kb_place(BatchArgs a) {
-    const u32 g = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blockIdx.x < a.count) {
+        const Seg& sg = a.segs[blockIdx.x];
+        finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)a.dtype,
+                      a.group_words + sg.group0);
+        return;
+    }
+    const u32 g = (blockIdx.x - a.count) * 4 + (threadIdx.x >> 6);
     const bool in_range = g < a.total_chunks;
     const u32 sidx = in_range ? a.seg_of_chunk[g] : 0;
     const Seg& sg = a.segs[sidx];
     EncState* st = &a.states[sidx];
     place_chunk<kPlaceWords>(sg.out, st, a.chunk_bits + sg.chunk0, a.group_words + sg.group0, a.prov + (u64)sg.chunk0 * a.slot_words,
-                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0, true);
+                a.slot_words, sg.nchunks, in_range ? g - sg.chunk0 : 0, in_range && st->table.status == 0);
 }
 
-__global__ __launch_bounds__(256) void kb_finalize(BatchArgs a) {
-    const Seg& sg = a.segs[blockIdx.x];
-    finalize_blob(sg.out, &a.states[blockIdx.x], &a.results[blockIdx.x], nullptr, sg.n, a.nbits, sg.nchunks, (u32)a.dtype,
-                  a.states[blockIdx.x].total_words);
-    if (blockIdx.x == gridDim.x - 1) __threadfence_system();
-}
 // ----------------------------------------------------------------------------- launchers
 void launch_reset(Workspace* ws, uint32_t* group_words, uint32_t* chunk_maxexp, hipStream_t s) {
     hipLaunchKernelGGL(k_reset, dim3(1), dim3(1024), 0, s, ws, group_words, (u32)kMaxGroups, chunk_maxexp, (u32)kMaxChunks);
@@ -1998,9 +1998,8 @@ void launch_batch_encode(const BatchArgs& args, const Tuning& tune, hipStream_t 
         if (a.dtype == kBF16) hipLaunchKernelGGL(kb_pack<kBF16>, dim3(waves), dim3(64), 0, s, a);
         else if (a.dtype == kF16) hipLaunchKernelGGL(kb_pack<kF16>, dim3(waves), dim3(64), 0, s, a);
         else hipLaunchKernelGGL(kb_pack<kF32>, dim3(waves), dim3(64), 0, s, a);
-        hipLaunchKernelGGL(kb_place, dim3((a.total_chunks + 3) / 4), dim3(256), 0, s, a);
     }
-    hipLaunchKernelGGL(kb_finalize, dim3(a.count), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(kb_place, dim3(a.count + (a.total_chunks + 3) / 4), dim3(256), 0, s, a);
 }
 
 }  // namespace lc

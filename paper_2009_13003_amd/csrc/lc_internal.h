@@ -86,7 +86,6 @@ struct EncState {
     uint32_t mmax[kExtCopies][kMaxSym];      // sweep updates copy (its index mod kExtCopies), the workgroup that writes the header joins them
     uint32_t spec;                   // lc_encode_cached: the table in `table` comes from the cache and the sweep coded with it
     uint32_t spec_ok;                // ... and this checkpoint's statistics confirmed it: the blob is already in the slots
-    unsigned long long total_words;
     uint32_t list_count;             // entries of chunk_list (the chunks sweep 2 has to read), written by k_table
     uint32_t pad_e;
     Table table;
