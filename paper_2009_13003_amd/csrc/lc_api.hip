@@ -186,7 +186,9 @@ Area* acquire(DeviceState* ds, hipStream_t s, size_t need, int* err) {
         size_t want = need < (4u << 20) ? (4u << 20) : need;     // never smaller than the head that is cleared below
         static_assert(kWorkspaceHead <= (4u << 20), "the smallest scratch area must hold the fixed head");
         if (hipMalloc(&a->mem, want) != hipSuccess) { (void)hipGetLastError(); a->mem = nullptr; *err = LC_ERR_HIP; return nullptr; }
-        if (hipMemset(a->mem, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(a->mem); a->mem = nullptr; *err = LC_ERR_HIP; return nullptr; }
+        // (on the call's own stream: a fill on the null stream is not ordered with a non-blocking stream's kernels and
+        // has been seen to land behind the reset kernel that follows, which left the smallest mantissas at zero)
+        if (hipMemsetAsync(a->mem, 0, kWorkspaceHead, s) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(a->mem); a->mem = nullptr; *err = LC_ERR_HIP; return nullptr; }
         a->bytes = want; a->user = false; a->used = false;
         a->clean = false;        // new memory (possibly at the old address): its encode state is not set up yet
     }
@@ -277,7 +279,7 @@ int lc_set_workspace(void* dev_ws, size_t bytes) {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LC_ERR_HIP; }
     if (dev_ws && (misaligned(dev_ws, 256) || bytes < kWorkspaceHead)) return LC_ERR_WORKSPACE;
     (void)hipDeviceSynchronize();                 // no call may still be using the areas that change hands here
-    if (dev_ws && hipMemset(dev_ws, 0, kWorkspaceHead) != hipSuccess) { (void)hipGetLastError(); return LC_ERR_HIP; }
+    if (dev_ws && (hipMemset(dev_ws, 0, kWorkspaceHead) != hipSuccess || hipDeviceSynchronize() != hipSuccess)) { (void)hipGetLastError(); return LC_ERR_HIP; }
     DeviceState& ds = g_dev[dev];
     if (ds.user && ds.area[0].mem == ds.user) { ds.area[0].mem = nullptr; ds.area[0].bytes = 0; ds.area[0].user = false; ds.area[0].used = false; }
     if (dev_ws) {

@@ -101,6 +101,9 @@ __device__ __forceinline__ float max_magnitude(const u32 (&u)[EPU], float m) {
 // one chunk of the coding sweep and its largest exponent goes to chunk_maxexp with one atomic per batch.
 // batch_max (or null) receives every whole batch's largest exponent as a byte of its own: the coding sweep then
 // knows which parts of a chunk it has to read.
+// A wavefront keeps the maxima of its last 64 batches in LDS and writes them out 64 at a time, one per lane: a
+// global write after every batch, however small, holds back the loads issued behind it (both are counted, in
+// order, by the one vector-memory counter) and cost the sweep 4 % of its rate.
 // KEYS (binary32, aligned arrays): the sweep also stages a 9-bit key per element of every whole batch -- the 16
 // exponent bytes and the 16 sign bits of the 16 elements a lane holds of a batch, which are the lane's own elements of
 // 4 rows of the coding sweep's chunk -- and, being then the only sweep that sees the mantissas, tracks the smallest and
@@ -111,6 +114,7 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
                                                u64 n, Workspace* ws, u32* chunk_maxexp, uint8_t* batch_max, KeyPlanes keys) {
     __shared__ u32 h[512 * kHistCopies];
     __shared__ u32 mn[KEYS ? 512 * kHistCopies : 1], mx[KEYS ? 512 * kHistCopies : 1];
+    __shared__ uint16_t pend[1024 / kW][kW];         // per wavefront: the maxima of its batches not yet written out
     static_assert(!KEYS || (ALIGNED && DT == kF32), "keys are staged for aligned binary32 arrays only");
     constexpr int EPU = 16 / (int)elem_bytes<DT>();
     const u32 tid = threadIdx.x, nthr = blockDim.x;
@@ -130,6 +134,19 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
         const u64 at = batch * kBatchUnits + (tid & (kW - 1));
 #pragma unroll
         for (int k = 0; k < PF; ++k) { a[k] = load_unit<ALIGNED, DT, EPU>(w, at + k * kW); bb[k] = load_unit<ALIGNED, DT, EPU>(w_ref, at + k * kW); }
+    };
+    u32 pending = 0;                                 // maxima waiting in pend, those of batches pend_first, + stride, ...
+    u64 pend_first = b;
+    auto write_maxima = [&]() {
+        __builtin_amdgcn_wave_barrier();
+        const u32 lane = tid & (kW - 1);
+        if (lane < pending) {
+            const u64 batch = pend_first + (u64)lane * stride;
+            const u32 m = pend[tid / kW][lane];
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
+            if (batch_max) batch_max[batch] = (uint8_t)m;
+        }
+        __builtin_amdgcn_wave_barrier();
     };
     u32 key_word = 0, key_signs = 0;                 // KEYS: exponent bytes of the unit just counted; sign bits of the batch so far
     auto count_one = [&](u32 u) {
@@ -164,10 +181,8 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
             __builtin_nontemporal_store((uint16_t)key_signs, keys.sign + at);
         }
         const u32 m = wave_max_u32(__float_as_uint(mf));     // whole wavefronts only: b < nbatch is the same for all lanes
-        if ((tid & (kW - 1)) == 0) {
-            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m >> 23);
-            if (batch_max) batch_max[batch] = (uint8_t)(m >> 23);
-        }
+        if ((tid & (kW - 1)) == 0) pend[tid / kW][pending] = (uint16_t)(m >> 23);
+        if (++pending == kW) { write_maxima(); pending = 0; pend_first = batch + stride; }
     };
     if (b < nbatch) {
         // The loads of the batch after next are issued without a branch around them (at the end the current
@@ -185,6 +200,7 @@ __global__ __launch_bounds__(1024) void k_hist(const void* __restrict__ w, const
             if (!more0) break;
             b += stride;
         }
+        write_maxima();
     }
     // what is left of the vector: fewer than one batch of units, then fewer than one unit of elements
     if (blockIdx.x == 0) {
@@ -233,6 +249,7 @@ template <bool ALIGNED>
 __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, const void* __restrict__ w_ref,
                                                  u64 n, Ext64* ext, u32* chunk_maxexp, uint16_t* part_max) {
     __shared__ u32 h[kBuckets64 * kHistCopies64];
+    __shared__ uint16_t pend[1024 / kW][kW];         // as in k_hist: maxima written out 64 batches at a time
     constexpr int EPU = 2;
     const u32 tid = threadIdx.x, nthr = blockDim.x;
     for (u32 i = tid; i < kBuckets64 * kHistCopies64; i += nthr) h[i] = 0;
@@ -251,6 +268,21 @@ __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, con
 #pragma unroll
         for (int k = 0; k < PF; ++k) { a[k] = load_unit64<ALIGNED>(w, at + k * kW); bb[k] = load_unit64<ALIGNED>(w_ref, at + k * kW); }
     };
+    u32 pending = 0;
+    u64 pend_first = b;
+    // (a batch is 4 KiB of each array: the largest exponent of every such part lets sweep 2 read a mostly merged
+    // chunk part by part, as for the other element types; 11 exponent bits: two bytes each)
+    auto write_maxima = [&]() {
+        __builtin_amdgcn_wave_barrier();
+        const u32 lane = tid & (kW - 1);
+        if (lane < pending) {
+            const u64 batch = pend_first + (u64)lane * stride;
+            const u32 m = pend[tid / kW][lane];
+            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
+            if (part_max) part_max[batch] = (uint16_t)m;
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
     auto as_double = [](float lo, float hi) { return __hiloint2double(__float_as_int(hi), __float_as_int(lo)); };
     auto count_one = [&](double x, double y, u32 m) {       // returns the larger of m and the delta's biased exponent
         const u64 u = delta_bits(x, y);
@@ -266,12 +298,8 @@ __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, con
 #pragma unroll
         for (int k = 0; k < PF; ++k) m = count_unit(a[k], bb[k], m);
         m = wave_max_u32(m);
-        // (a batch is 4 KiB of each array: the largest exponent of every such part lets sweep 2 read a mostly merged
-        // chunk part by part, as for the other element types; 11 exponent bits: two bytes each)
-        if ((tid & (kW - 1)) == 0) {
-            atomicMax(&chunk_maxexp[maxexp_slot((u32)((batch * kBatchUnits * EPU) / kChunk))], m);
-            if (part_max) part_max[batch] = (uint16_t)m;
-        }
+        if ((tid & (kW - 1)) == 0) pend[tid / kW][pending] = (uint16_t)m;
+        if (++pending == kW) { write_maxima(); pending = 0; pend_first = batch + stride; }
     };
     if (b < nbatch) {
         fetch(a0, b0, b);
@@ -287,6 +315,7 @@ __global__ __launch_bounds__(1024) void k_hist64(const void* __restrict__ w, con
             if (!more0) break;
             b += stride;
         }
+        write_maxima();
     }
     if (blockIdx.x == 0) {
         for (u64 u = nbatch * kBatchUnits + tid; u < nu; u += nthr) {

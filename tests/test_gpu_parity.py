@@ -2063,6 +2063,24 @@ def test_fp64_cached_async_many_and_batch(lc):
 
 
 # ---------------------------------------------------------------- calls on different streams run side by side
+def test_scratch_areas_that_grow_under_calls_on_side_streams(lc):
+    """Every call here needs more scratch than the one before it, so the library allocates and sets up a new area each
+    time, on a side stream that does not wait for the null stream: the set-up must be ordered with the call's own
+    kernels (a fill that landed behind them once left every bucket's smallest mantissa at zero: blobs of the right
+    size with wrong representatives).  Checked against the oracle, representatives included."""
+    nbits = 4
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    cases = [laplace_case(16384 * (40 + 48 * k) + 7 * k, seed=760 + k, scale=10.0 ** -(2 + k % 3)) for k in range(10)]
+    expect = [orc.encode(w.cpu().numpy(), r.cpu().numpy(), nbits) for w, r in cases]
+    outs = [lc.alloc_out(w.numel(), nbits, DEV) for w, _ in cases]
+    torch.cuda.synchronize()
+    tickets = [lc.lc_encode_async(w, r, nbits, o, stream=streams[i % len(streams)]) for i, ((w, r), o) in enumerate(zip(cases, outs))]
+    for t, o, e in zip(tickets, outs, expect):
+        size, _ = lc.lc_encode_wait(t)
+        g = o[:size].cpu().numpy()
+        assert size == e.size and np.array_equal(g, e), first_diff(g, e)
+
+
 def test_encodes_on_different_streams_have_their_own_scratch(lc):
     """Section 3.2, asynchronous execution in a trainer with many tensors: asynchronous encodes issued on several
     streams at once (more streams than the library keeps scratch areas, so some share), slices of one vector enqueued
