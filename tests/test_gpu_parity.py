@@ -626,6 +626,53 @@ def test_fused_restore_eight_blobs_per_sweep():
     assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
 
 
+OTHER_SHAPES = """
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+from oracle import lc_oracle as orc
+from paper_2009_13003_amd import lc
+DEV = "cuda:0"
+g = torch.Generator(device=DEV); g.manual_seed(77)
+def pair(n, dtype):
+    ref = 0.05 * torch.randn(n, generator=g, device=DEV, dtype=torch.float64 if dtype == torch.float64 else torch.float32)
+    d = 1e-3 * torch.randn(n, generator=g, device=DEV, dtype=ref.dtype) * (torch.rand(n, generator=g, device=DEV) < 0.4)
+    d[n // 3] = 0.3; d[n // 2 + 5] = -0.2                  # a few large deltas: most chunks lie below the kept buckets
+    return (ref + d).to(dtype), ref.to(dtype)
+# sweep 1 with one wavefront per compute unit: 150 batches per wavefront, so its per-batch maxima are written out in
+# several rounds; the other sweeps with launch shapes of their own as well
+for dtype, n, nbits in ((torch.float32, 256 * 1024 * 150 + 4321, 3), (torch.bfloat16, 256 * 2048 * 70 + 77, 4), (torch.float64, 256 * 512 * 150 + 3, 2)):
+    w, ref = pair(n, dtype)
+    out = lc.alloc_out(n, nbits, DEV)
+    size = lc.lc_encode_t(w, ref, nbits, out)
+    if dtype == torch.float64:
+        e = orc.encode64(w.cpu().numpy(), ref.cpu().numpy(), nbits)
+    elif dtype == torch.float32:
+        e = orc.encode(w.cpu().numpy(), ref.cpu().numpy(), nbits)
+    else:
+        e = orc.encode_t(w.view(torch.int16).cpu().numpy().view(np.uint16), ref.view(torch.int16).cpu().numpy().view(np.uint16), nbits, orc.DT_BF16)
+    got = out[:size].cpu().numpy()
+    assert got.size == e.size and np.array_equal(got, e), (str(dtype), got.size, e.size)
+    rec = ref.clone()
+    assert lc.lc_decode_t(out[:size], rec) == size
+    again = lc.alloc_out(n, nbits, DEV)
+    assert lc.lc_encode_t(w, rec, nbits, again) > 0        # (the restored state is a valid reference for the next checkpoint)
+    print("ok", dtype, flush=True)
+print("ok")
+"""
+
+
+def test_sweeps_under_other_launch_shapes():
+    """The launch-shape knobs are read once per process, hence the child process: sweep 1 with a single wavefront per
+    compute unit (every wavefront then walks 150 batches and hands in its per-batch maxima in several rounds), the
+    coding and restoring sweeps with fewer wavefronts than they take by themselves; fp32, bf16 and fp64 blobs against the oracle."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, LC_TUNE_HIST_THREADS="64", LC_TUNE_HIST_BLOCKS_PER_CU="1", LC_TUNE_PACK_WAVES_PER_CU="3",
+               LC_TUNE_DECODE_BLOCKS_PER_CU="2")
+    r = subprocess.run([sys.executable, "-c", OTHER_SHAPES % root], env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+
+
 # ---------------------------------------------------------------- code table caching (Section 3.2)
 def cached_step(lc, w, ref, nbits, out, cache_gpu, cache_cpu):
     """One lc_encode_cached on both sides with their own caches; compares blob, verdict and cache."""
