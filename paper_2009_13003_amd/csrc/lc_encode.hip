@@ -632,6 +632,10 @@ constexpr u32 kStageRows = 32;      // code words per lane that a chunk gathers 
 constexpr int kSpecCopies = 2;      // LDS copies of the bucket histogram in the speculative sweep (4 copies leave room for 6
                                     // wavefronts per compute unit instead of 8: 0.443 against 0.428 ms per 2^28 elements)
 
+// Where copy `copy` of bucket b's count lies in PackLds::hist.  The two signs of an exponent would otherwise share an LDS
+// bank (512 words apart), and a delta's sign is a coin toss: bit 4 of the index is flipped for the negative half.
+__device__ __forceinline__ u32 hist_slot(u32 b, u32 copy) { return (b * kSpecCopies + copy) ^ ((b >> 8) << 4); }
+
 template <bool HIST>
 struct PackLds {
     uint8_t sym8[512];               // bucket -> symbol << 3
@@ -719,7 +723,7 @@ __device__ __noinline__ void pack_chunk_plain(const ChunkRef ch, PackLds<HIST>& 
         for (int v = 0; v < 4; ++v) {
             if (WHOLE || idx + v < n) {
                 const u32 u = delta_bits(xa[v], xb[v]);
-                if (HIST) atomicAdd(&L.hist[(u >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+                if (HIST) atomicAdd(&L.hist[hist_slot(u >> 23, lane & (kSpecCopies - 1))], 1u);
                 if (HIST && !PACK) gmax = max(gmax, u & 0x7FFFFFFFu);
                 if (!PACK) continue;
                 const u32 sy = L.sym8[u >> 23] >> 3;
@@ -925,7 +929,7 @@ __device__ __forceinline__ void pack_chunk_fast(const ChunkRef& cur, const Chunk
         }
         if (HIST) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[(u[i] >> 23) * kSpecCopies + (lane & (kSpecCopies - 1))], 1u);
+            for (int i = 0; i < 16; ++i) atomicAdd(&L.hist[hist_slot(u[i] >> 23, lane & (kSpecCopies - 1))], 1u);
         }
         if (HIST && !PACK && at.chunk) {
             u32 gm = 0;
@@ -1466,7 +1470,7 @@ __global__ __launch_bounds__(64) void k_spec_sweep(const void* __restrict__ w, c
     for (u32 b = lane; b < 512; b += 64) {
         u32 sum = 0;
 #pragma unroll
-        for (int k = 0; k < kSpecCopies; ++k) sum += L.hist[b * kSpecCopies + k];
+        for (int k = 0; k < kSpecCopies; ++k) sum += L.hist[hist_slot(b, k)];
         if (sum) atomicAdd(&ws->hist[b], (u64)sum);
     }
     if (spec) pack_merge_extremes(L, ws, K, lane);
@@ -1780,7 +1784,7 @@ struct BatchChunks {
             for (u32 b = lane; b < 512; b += kW) {
                 u32 sum = 0;
 #pragma unroll
-                for (int k = 0; k < kSpecCopies; ++k) { sum += L.hist[b * kSpecCopies + k]; L.hist[b * kSpecCopies + k] = 0; }
+                for (int k = 0; k < kSpecCopies; ++k) { sum += L.hist[hist_slot(b, k)]; L.hist[hist_slot(b, k)] = 0; }
                 if (sum) atomicAdd(&st->hist[b], (u64)sum);
             }
         }
